@@ -1,0 +1,472 @@
+// C-ABI entry points for the shift-fused convolutions and the residual blocks,
+// and the internal block driver the TSM-ResNet-50 step reuses.
+#include "internal.h"
+#include "block.h"
+
+namespace tsm {
+
+#define RUN(expr)                          \
+    do {                                   \
+        if (!dry) TSM_TRY(expr);           \
+    } while (0)
+
+// ---- descriptor checks -----------------------------------------------------------
+static int check_common(int dtype, int layout, const char* who) {
+    if (dtype != TSM_F32 && dtype != TSM_BF16) return fail(TSM_ERR_DTYPE, "%s: unknown dtype %d", who, dtype);
+    if (layout != TSM_NTCHW && layout != TSM_NTHWC) return fail(TSM_ERR_LAYOUT, "%s: unknown layout %d", who, layout);
+    return TSM_OK;
+}
+
+static int make_convp(const tsm_conv_desc* d, ConvP* p, const char* who) {
+    if (!d) return fail(TSM_ERR_NULLPTR, "%s: null descriptor", who);
+    TSM_TRY(check_common(d->dtype, d->layout, who));
+    if (d->N <= 0 || d->T <= 0 || d->Cin <= 0 || d->H <= 0 || d->W <= 0 || d->Cout <= 0 || d->kh <= 0 || d->kw <= 0 ||
+        d->stride <= 0 || d->pad < 0)
+        return fail(TSM_ERR_SHAPE, "%s: non-positive dimension", who);
+    if (d->H + 2 * d->pad < d->kh || d->W + 2 * d->pad < d->kw) return fail(TSM_ERR_SHAPE, "%s: filter larger than padded frame", who);
+    if ((long)d->N * d->T > 0x7fffffffL / 4) return fail(TSM_ERR_SHAPE, "%s: too many frames", who);
+    int fold = 0;
+    if (fold_of(d->Cin, d->fold_div, &fold) != TSM_OK) return fail(TSM_ERR_FOLD, "%s: invalid fold_div %d for Cin=%d", who, d->fold_div, d->Cin);
+    p->F = d->N * d->T; p->T = d->T; p->H = d->H; p->W = d->W; p->Cin = d->Cin;
+    p->Ho = (d->H + 2 * d->pad - d->kh) / d->stride + 1;
+    p->Wo = (d->W + 2 * d->pad - d->kw) / d->stride + 1;
+    p->Cout = d->Cout; p->KT = 1; p->KH = d->kh; p->KW = d->kw; p->stride = d->stride; p->pad = d->pad;
+    p->fold = fold;
+    return TSM_OK;
+}
+
+static inline bool use_mfma(const ConvP& p, int dtype) { return dtype == TSM_BF16 && mfma_conv_supported(p); }
+
+// ---- internal conv runners (channels-innermost) -----------------------------------------
+// stats_acc: zeroed fp64 [2*Cout] or null.
+int run_conv_fwd(const ConvP& p, int dtype, const void* x, const void* w, const bf16_t* wp, void* y,
+                 double* stats_acc, Arena& ws, bool dry, hipStream_t s) {
+    if (use_mfma(p, dtype)) {
+        if (!wp) {
+            bf16_t* pk = ws.take_n<bf16_t>((size_t)p.Cout * p.K());
+            RUN(pack_weights_fwd(dtype, w, pk, p.Cout, p.Cin, p.taps(), s));
+            wp = pk;
+        }
+        RUN(conv_mfma_fwd(p, (const bf16_t*)x, wp, (bf16_t*)y, stats_acc, s));
+    } else {
+        RUN(conv_direct_fwd(p, dtype, x, w, y, s));
+        if (stats_acc) RUN(channel_stats(dtype, y, p.rows_out(), p.Cout, stats_acc, s));
+    }
+    return TSM_OK;
+}
+
+int run_conv_dgrad(const ConvP& p, int dtype, const void* dy, const void* w, const bf16_t* wd, void* dx,
+                   const void* addend, Arena& ws, bool dry, hipStream_t s) {
+    if (use_mfma(p, dtype)) {
+        if (!wd) {
+            bf16_t* pk = ws.take_n<bf16_t>((size_t)p.Cout * p.K());
+            RUN(pack_weights_dgrad(dtype, w, pk, p.Cout, p.Cin, p.KT, p.KH, p.KW, s));
+            wd = pk;
+        }
+        RUN(conv_mfma_dgrad(p, (const bf16_t*)dy, wd, (bf16_t*)dx, (const bf16_t*)addend, s));
+    } else {
+        RUN(conv_direct_dgrad(p, dtype, dy, w, dx, addend, s));
+    }
+    return TSM_OK;
+}
+
+int run_conv_wgrad(const ConvP& p, int dtype, const void* x, const void* dy, float* dw, int accumulate, Arena& ws,
+                   bool dry, hipStream_t s) {
+    const size_t n = (size_t)p.Cout * p.K();
+    if (use_mfma(p, dtype)) {
+        float* dwp = ws.take_n<float>(n);
+        RUN(fill_zero(dwp, n * sizeof(float), s));
+        RUN(conv_mfma_wgrad(p, (const bf16_t*)x, (const bf16_t*)dy, dwp, s));
+        RUN(unpack_wgrad(dwp, dw, p.Cout, p.Cin, p.taps(), accumulate, s));
+    } else {
+        if (!accumulate) RUN(fill_zero(dw, n * sizeof(float), s));
+        RUN(conv_direct_wgrad(p, dtype, x, dy, dw, s));
+    }
+    return TSM_OK;
+}
+
+// ---- conv entry points -------------------------------------------------------------------
+enum { CONV_FWD = 0, CONV_DGRAD = 1, CONV_WGRAD = 2 };
+
+static int conv_entry(int which, const tsm_conv_desc* d, const void* a0, const void* a1, void* out, float* ch_sum,
+                      float* ch_sumsq, int accumulate, void* wsp, size_t ws_bytes, bool dry, hipStream_t s,
+                      size_t* need) {
+    const char* who = which == CONV_FWD ? "tsm_conv_fwd" : which == CONV_DGRAD ? "tsm_conv_dgrad" : "tsm_conv_wgrad";
+    ConvP p;
+    TSM_TRY(make_convp(d, &p, who));
+    if (!dry) {
+        if (!a0 || !a1 || !out) return fail(TSM_ERR_NULLPTR, "%s: null tensor pointer", who);
+        if ((ch_sum == nullptr) != (ch_sumsq == nullptr)) return fail(TSM_ERR_NULLPTR, "%s: ch_sum and ch_sumsq must both be set or both be NULL", who);
+        if (!aligned16(a0) || !aligned16(a1) || !aligned16(out) || !aligned16(wsp))
+            return fail(TSM_ERR_ALIGN, "%s: pointers must be 16-byte aligned", who);
+        if (ws_bytes > 0 && !wsp) return fail(TSM_ERR_NULLPTR, "%s: null workspace", who);
+    }
+    Arena ws(dry ? nullptr : wsp, dry ? (size_t)-1 : ws_bytes);
+    if (!dry) {  // size check first, with a dry pass of the same plan
+        size_t req = 0;
+        TSM_TRY(conv_entry(which, d, a0, a1, out, ch_sum, ch_sumsq, accumulate, nullptr, 0, true, s, &req));
+        if (req > ws_bytes) return fail(TSM_ERR_WORKSPACE, "%s: workspace %zu bytes, need %zu", who, ws_bytes, req);
+    }
+    const int es = (int)dtype_size(d->dtype);
+    const size_t xin = (size_t)p.rows_in() * p.Cin * es, yout = (size_t)p.rows_out() * p.Cout * es;
+    const bool tr = d->layout == TSM_NTCHW;
+    if (which == CONV_FWD) {
+        const void* x = a0;
+        void* y = out;
+        if (tr) {
+            void* xt = ws.take(xin);
+            y = ws.take(yout);
+            RUN(transpose_frames(a0, xt, p.F, p.Cin, p.H * p.W, es, s));
+            x = xt;
+        }
+        double* acc = nullptr;
+        if (ch_sum || dry) {
+            acc = ws.take_n<double>(2 * (size_t)p.Cout);
+            if (ch_sum) RUN(fill_zero(acc, 2 * (size_t)p.Cout * sizeof(double), s));
+        }
+        TSM_TRY(run_conv_fwd(p, d->dtype, x, a1, nullptr, y, ch_sum ? acc : nullptr, ws, dry, s));
+        if (ch_sum) RUN(stats_to_float(acc, p.Cout, ch_sum, ch_sumsq, s));
+        if (tr) RUN(transpose_frames(y, out, p.F, p.Ho * p.Wo, p.Cout, es, s));
+    } else if (which == CONV_DGRAD) {
+        const void* dy = a0;
+        void* dx = out;
+        if (tr) {
+            void* dyt = ws.take(yout);
+            dx = ws.take(xin);
+            RUN(transpose_frames(a0, dyt, p.F, p.Cout, p.Ho * p.Wo, es, s));
+            dy = dyt;
+        }
+        TSM_TRY(run_conv_dgrad(p, d->dtype, dy, a1, nullptr, dx, nullptr, ws, dry, s));
+        if (tr) RUN(transpose_frames(dx, out, p.F, p.H * p.W, p.Cin, es, s));
+    } else {
+        const void *x = a0, *dy = a1;
+        if (tr) {
+            void* xt = ws.take(xin);
+            void* dyt = ws.take(yout);
+            RUN(transpose_frames(a0, xt, p.F, p.Cin, p.H * p.W, es, s));
+            RUN(transpose_frames(a1, dyt, p.F, p.Cout, p.Ho * p.Wo, es, s));
+            x = xt;
+            dy = dyt;
+        }
+        TSM_TRY(run_conv_wgrad(p, d->dtype, x, dy, (float*)out, accumulate, ws, dry, s));
+    }
+    if (need) *need = ws.used;
+    return TSM_OK;
+}
+
+// ---- residual blocks ---------------------------------------------------------------------
+static size_t bnvec_take(Arena& a, int C, BnVec* v) {
+    v->mean = a.take_n<float>(C);
+    v->rstd = a.take_n<float>(C);
+    v->scale = a.take_n<float>(C);
+    v->shift = a.take_n<float>(C);
+    return 0;
+}
+
+// Lays the saved buffer out (same order in fwd and bwd).
+void block_saved_layout(BlockPlan& b, Arena& sv, bool keep_x_copy) {
+    const int es = (int)dtype_size(b.dtype);
+    if (keep_x_copy) {
+        b.x_copy = sv.take((size_t)b.st[0].p.rows_in() * b.st[0].p.Cin * es);
+        b.out_copy = sv.take((size_t)b.st[b.nst - 1].p.rows_out() * b.st[b.nst - 1].p.Cout * es);
+    }
+    for (int i = 0; i < b.nst; ++i) {
+        const ConvP& p = b.st[i].p;
+        b.y[i] = sv.take((size_t)p.rows_out() * p.Cout * es);
+        if (i + 1 < b.nst) b.z[i] = sv.take((size_t)p.rows_out() * p.Cout * es);
+        bnvec_take(sv, p.Cout, &b.bn[i]);
+    }
+    if (b.proj) {
+        const ConvP& p = b.ds.p;
+        b.yd = sv.take((size_t)p.rows_out() * p.Cout * es);
+        bnvec_take(sv, p.Cout, &b.bnd);
+    }
+}
+
+int block_fwd_impl(BlockPlan& b, const void* x, void* out, Arena& ws, bool dry, hipStream_t s) {
+    const void* cur = x;
+    for (int i = 0; i < b.nst; ++i) {
+        StageDef& st = b.st[i];
+        double* acc = ws.take_n<double>(2 * (size_t)st.p.Cout);
+        RUN(fill_zero(acc, 2 * (size_t)st.p.Cout * sizeof(double), s));
+        TSM_TRY(run_conv_fwd(st.p, b.dtype, cur, st.w, st.wp, b.y[i], acc, ws, dry, s));
+        RUN(bn_finalize(acc, st.p.rows_out(), st.p.Cout, st.g, st.b, b.eps, b.bn[i], st.run_mean, st.run_var,
+                        b.bn_momentum, s));
+        if (i + 1 < b.nst) {
+            RUN(bn_relu_apply(b.dtype, b.y[i], st.p.rows_out(), st.p.Cout, b.bn[i].scale, b.bn[i].shift, b.z[i], s));
+            cur = b.z[i];
+        }
+    }
+    if (b.proj) {
+        StageDef& st = b.ds;
+        double* acc = ws.take_n<double>(2 * (size_t)st.p.Cout);
+        RUN(fill_zero(acc, 2 * (size_t)st.p.Cout * sizeof(double), s));
+        TSM_TRY(run_conv_fwd(st.p, b.dtype, x, st.w, st.wp, b.yd, acc, ws, dry, s));
+        RUN(bn_finalize(acc, st.p.rows_out(), st.p.Cout, st.g, st.b, b.eps, b.bnd, st.run_mean, st.run_var,
+                        b.bn_momentum, s));
+    }
+    const int L = b.nst - 1;
+    const ConvP& pl = b.st[L].p;
+    RUN(block_tail_fwd(b.dtype, b.y[L], pl.rows_out(), pl.Cout, b.bn[L].scale, b.bn[L].shift, b.proj ? b.yd : x,
+                       b.proj ? b.bnd.scale : nullptr, b.proj ? b.bnd.shift : nullptr, out, s));
+    return TSM_OK;
+}
+
+int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dout, void* dx, Arena& ws, bool dry,
+                   hipStream_t s) {
+    const int es = (int)dtype_size(b.dtype);
+    const int L = b.nst - 1;
+    const ConvP& pl = b.st[L].p;
+    const size_t out_bytes = (size_t)pl.rows_out() * pl.Cout * es;
+    void* dzL = ws.take(out_bytes);
+    void* dyL = ws.take(out_bytes);
+    double* accL = ws.take_n<double>(2 * (size_t)pl.Cout);
+    double* accd = ws.take_n<double>(2 * (size_t)pl.Cout);
+    RUN(fill_zero(accL, 2 * (size_t)pl.Cout * sizeof(double), s));
+    if (b.proj) RUN(fill_zero(accd, 2 * (size_t)pl.Cout * sizeof(double), s));
+    RUN(relu_bn_bwd_reduce(b.dtype, dout, out, b.y[L], pl.rows_out(), pl.Cout, b.bn[L].mean, b.bn[L].rstd, dzL, accL,
+                           b.proj ? b.yd : nullptr, b.proj ? b.bnd.mean : nullptr, b.proj ? b.bnd.rstd : nullptr,
+                           b.proj ? accd : nullptr, s));
+    RUN(bn_bwd_apply(b.dtype, dzL, b.y[L], pl.rows_out(), pl.Cout, b.bn[L].mean, b.bn[L].rstd, b.st[L].g, accL, dyL,
+                     b.st[L].dg, b.st[L].db, s));
+    void* g = dyL;
+    for (int i = L; i >= 1; --i) {
+        StageDef& st = b.st[i];
+        const ConvP& pp = b.st[i - 1].p;  // producer of this stage's input
+        TSM_TRY(run_conv_wgrad(st.p, b.dtype, b.z[i - 1], g, st.dw, 0, ws, dry, s));
+        void* dzin = ws.take((size_t)pp.rows_out() * pp.Cout * es);
+        TSM_TRY(run_conv_dgrad(st.p, b.dtype, g, st.w, st.wd, dzin, nullptr, ws, dry, s));
+        double* acc = ws.take_n<double>(2 * (size_t)pp.Cout);
+        RUN(fill_zero(acc, 2 * (size_t)pp.Cout * sizeof(double), s));
+        RUN(relu_bn_bwd_reduce(b.dtype, dzin, b.z[i - 1], b.y[i - 1], pp.rows_out(), pp.Cout, b.bn[i - 1].mean,
+                               b.bn[i - 1].rstd, dzin, acc, nullptr, nullptr, nullptr, nullptr, s));
+        RUN(bn_bwd_apply(b.dtype, dzin, b.y[i - 1], pp.rows_out(), pp.Cout, b.bn[i - 1].mean, b.bn[i - 1].rstd,
+                         b.st[i - 1].g, acc, dzin, b.st[i - 1].dg, b.st[i - 1].db, s));
+        g = dzin;
+    }
+    TSM_TRY(run_conv_wgrad(b.st[0].p, b.dtype, x, g, b.st[0].dw, 0, ws, dry, s));
+    const void* addend = dzL;
+    if (b.proj) {
+        StageDef& st = b.ds;
+        void* dyd = ws.take(out_bytes);
+        RUN(bn_bwd_apply(b.dtype, dzL, b.yd, pl.rows_out(), pl.Cout, b.bnd.mean, b.bnd.rstd, st.g, accd, dyd, st.dg,
+                         st.db, s));
+        TSM_TRY(run_conv_wgrad(st.p, b.dtype, x, dyd, st.dw, 0, ws, dry, s));
+        void* dsc = ws.take((size_t)st.p.rows_in() * st.p.Cin * es);
+        TSM_TRY(run_conv_dgrad(st.p, b.dtype, dyd, st.w, st.wd, dsc, nullptr, ws, dry, s));
+        addend = dsc;
+    }
+    if (dx || dry) TSM_TRY(run_conv_dgrad(b.st[0].p, b.dtype, g, b.st[0].w, b.st[0].wd, dx, addend, ws, dry, s));
+    return TSM_OK;
+}
+
+static void set_stage(StageDef& st, int F, int T, int H, int W, int Cin, int Cout, int KT, int k, int stride, int pad,
+                      int fold) {
+    st = StageDef{};
+    ConvP& p = st.p;
+    p.F = F; p.T = T; p.H = H; p.W = W; p.Cin = Cin; p.Cout = Cout; p.KT = KT; p.KH = k; p.KW = k;
+    p.stride = stride; p.pad = pad; p.fold = fold;
+    p.Ho = (H + 2 * pad - k) / stride + 1;
+    p.Wo = (W + 2 * pad - k) / stride + 1;
+}
+
+int make_block_plan(const tsm_block_desc* d, BlockPlan* b, const char* who) {
+    if (!d) return fail(TSM_ERR_NULLPTR, "%s: null descriptor", who);
+    TSM_TRY(check_common(d->dtype, d->layout, who));
+    if (d->N <= 0 || d->T <= 0 || d->Cin <= 0 || d->H <= 0 || d->W <= 0 || d->Cmid <= 0 || d->Cout <= 0 || d->stride <= 0)
+        return fail(TSM_ERR_SHAPE, "%s: non-positive dimension", who);
+    if (d->kind != TSM_BLOCK_BASIC && d->kind != TSM_BLOCK_BOTTLENECK && d->kind != TSM_BLOCK_BOTTLENECK_T3)
+        return fail(TSM_ERR_UNSUPPORTED, "%s: unknown block kind %d", who, d->kind);
+    if (!(d->bn_eps >= 0.f)) return fail(TSM_ERR_SHAPE, "%s: bn_eps must be >= 0", who);
+    int fold = 0;
+    const int fd = d->kind == TSM_BLOCK_BOTTLENECK_T3 ? 0 : d->fold_div;
+    if (fold_of(d->Cin, fd, &fold) != TSM_OK) return fail(TSM_ERR_FOLD, "%s: invalid fold_div %d for Cin=%d", who, d->fold_div, d->Cin);
+    *b = BlockPlan{};
+    b->dtype = d->dtype;
+    b->eps = d->bn_eps;
+    b->bn_momentum = 0.f;
+    const int F = d->N * d->T;
+    if (d->kind == TSM_BLOCK_BASIC) {
+        if (d->Cmid != d->Cin || d->Cout != d->Cin || d->stride != 1 || d->has_projection)
+            return fail(TSM_ERR_SHAPE, "%s: the basic block needs Cmid == Cout == Cin, stride 1, no projection", who);
+        b->nst = 2;
+        set_stage(b->st[0], F, d->T, d->H, d->W, d->Cin, d->Cin, 1, 3, 1, 1, fold);
+        set_stage(b->st[1], F, d->T, d->H, d->W, d->Cin, d->Cin, 1, 3, 1, 1, 0);
+    } else {
+        if (!d->has_projection && (d->Cout != d->Cin || d->stride != 1))
+            return fail(TSM_ERR_SHAPE, "%s: an identity shortcut needs Cout == Cin and stride 1", who);
+        if (d->H + 2 < 3 || d->W + 2 < 3) return fail(TSM_ERR_SHAPE, "%s: frame too small", who);
+        b->nst = 3;
+        const int KT = d->kind == TSM_BLOCK_BOTTLENECK_T3 ? 3 : 1;
+        set_stage(b->st[0], F, d->T, d->H, d->W, d->Cin, d->Cmid, KT, 1, 1, 0, fold);
+        set_stage(b->st[1], F, d->T, d->H, d->W, d->Cmid, d->Cmid, 1, 3, d->stride, 1, 0);
+        set_stage(b->st[2], F, d->T, b->st[1].p.Ho, b->st[1].p.Wo, d->Cmid, d->Cout, 1, 1, 1, 0, 0);
+        b->proj = d->has_projection != 0;
+        if (b->proj) set_stage(b->ds, F, d->T, d->H, d->W, d->Cin, d->Cout, 1, 1, d->stride, 0, 0);
+    }
+    return TSM_OK;
+}
+
+static void bind_params(BlockPlan& b, const tsm_block_params* p, const tsm_block_grads* g) {
+    const void* w[3] = {p->w1, p->w2, p->w3};
+    const float* gm[3] = {p->g1, p->g2, p->g3};
+    const float* bt[3] = {p->b1, p->b2, p->b3};
+    for (int i = 0; i < b.nst; ++i) {
+        b.st[i].w = w[i];
+        b.st[i].g = gm[i];
+        b.st[i].b = bt[i];
+    }
+    if (b.proj) {
+        b.ds.w = p->wd;
+        b.ds.g = p->gd;
+        b.ds.b = p->bd;
+    }
+    if (g) {
+        float* dw[3] = {g->dw1, g->dw2, g->dw3};
+        float* dg[3] = {g->dg1, g->dg2, g->dg3};
+        float* db[3] = {g->db1, g->db2, g->db3};
+        for (int i = 0; i < b.nst; ++i) {
+            b.st[i].dw = dw[i];
+            b.st[i].dg = dg[i];
+            b.st[i].db = db[i];
+        }
+        if (b.proj) {
+            b.ds.dw = g->dwd;
+            b.ds.dg = g->dgd;
+            b.ds.db = g->dbd;
+        }
+    }
+}
+
+static int check_block_ptrs(const BlockPlan& b, bool bwd, const char* who) {
+    for (int i = 0; i < b.nst; ++i) {
+        if (!b.st[i].w || !b.st[i].g || !b.st[i].b) return fail(TSM_ERR_NULLPTR, "%s: null parameter pointer (stage %d)", who, i + 1);
+        if (!aligned16(b.st[i].w)) return fail(TSM_ERR_ALIGN, "%s: weight pointers must be 16-byte aligned", who);
+        if (bwd && (!b.st[i].dw || !b.st[i].dg || !b.st[i].db)) return fail(TSM_ERR_NULLPTR, "%s: null gradient pointer (stage %d)", who, i + 1);
+    }
+    if (b.proj) {
+        if (!b.ds.w || !b.ds.g || !b.ds.b) return fail(TSM_ERR_NULLPTR, "%s: null projection parameter pointer", who);
+        if (bwd && (!b.ds.dw || !b.ds.dg || !b.ds.db)) return fail(TSM_ERR_NULLPTR, "%s: null projection gradient pointer", who);
+    }
+    return TSM_OK;
+}
+
+static int block_entry(bool bwd, const tsm_block_desc* d, const void* x, const void* out_in, const void* dout,
+                       const tsm_block_params* prm, void* out, void* saved, void* dx, const tsm_block_grads* grads,
+                       void* wsp, size_t ws_bytes, bool dry, hipStream_t s, size_t* need_ws, size_t* need_saved) {
+    const char* who = bwd ? "tsm_block_bwd" : "tsm_block_fwd";
+    BlockPlan b;
+    TSM_TRY(make_block_plan(d, &b, who));
+    const bool tr = d->layout == TSM_NTCHW;
+    if (!dry) {
+        if (!prm) return fail(TSM_ERR_NULLPTR, "%s: null params", who);
+        if (bwd && !grads) return fail(TSM_ERR_NULLPTR, "%s: null grads", who);
+        bind_params(b, prm, grads);
+        TSM_TRY(check_block_ptrs(b, bwd, who));
+        if (!x || !saved || (!bwd && !out) || (bwd && (!out_in || !dout || !dx))) return fail(TSM_ERR_NULLPTR, "%s: null tensor pointer", who);
+        if (!aligned16(x) || !aligned16(saved) || !aligned16(out) || !aligned16(out_in) || !aligned16(dout) || !aligned16(dx) || !aligned16(wsp))
+            return fail(TSM_ERR_ALIGN, "%s: pointers must be 16-byte aligned", who);
+        size_t req = 0;
+        TSM_TRY(block_entry(bwd, d, x, out_in, dout, prm, out, saved, dx, grads, nullptr, 0, true, s, &req, nullptr));
+        if (req > ws_bytes) return fail(TSM_ERR_WORKSPACE, "%s: workspace %zu bytes, need %zu", who, ws_bytes, req);
+        if (req > 0 && !wsp) return fail(TSM_ERR_NULLPTR, "%s: null workspace", who);
+    }
+    Arena sv(dry ? nullptr : saved, (size_t)-1);
+    block_saved_layout(b, sv, tr);
+    if (need_saved) *need_saved = sv.used;
+    Arena ws(dry ? nullptr : wsp, dry ? (size_t)-1 : ws_bytes);
+    const int es = (int)dtype_size(d->dtype);
+    const ConvP& p0 = b.st[0].p;
+    const ConvP& pl = b.st[b.nst - 1].p;
+    if (!bwd) {
+        const void* xi = x;
+        void* oi = out;
+        if (tr) {
+            RUN(transpose_frames(x, b.x_copy, p0.F, p0.Cin, p0.H * p0.W, es, s));
+            xi = b.x_copy;
+            oi = b.out_copy;
+        }
+        TSM_TRY(block_fwd_impl(b, xi, oi, ws, dry, s));
+        if (tr) RUN(transpose_frames(oi, out, pl.F, pl.Ho * pl.Wo, pl.Cout, es, s));
+    } else {
+        const void *xi = x, *oi = out_in, *di = dout;
+        void* dxi = dx;
+        if (tr) {
+            xi = b.x_copy;
+            oi = b.out_copy;
+            void* dt = ws.take((size_t)pl.rows_out() * pl.Cout * es);
+            RUN(transpose_frames(dout, dt, pl.F, pl.Cout, pl.Ho * pl.Wo, es, s));
+            di = dt;
+            dxi = ws.take((size_t)p0.rows_in() * p0.Cin * es);
+        }
+        TSM_TRY(block_bwd_impl(b, xi, oi, di, dxi, ws, dry, s));
+        if (tr) RUN(transpose_frames(dxi, dx, p0.F, p0.H * p0.W, p0.Cin, es, s));
+    }
+    if (need_ws) *need_ws = ws.used;
+    return TSM_OK;
+}
+
+}  // namespace tsm
+
+using namespace tsm;
+
+extern "C" {
+
+size_t tsm_conv_workspace_bytes(const tsm_conv_desc* d) {
+    size_t best = 0;
+    for (int which = 0; which < 3; ++which) {
+        size_t need = 0;
+        if (conv_entry(which, d, nullptr, nullptr, nullptr, nullptr, nullptr, 0, nullptr, 0, true, nullptr, &need) != TSM_OK) return 0;
+        if (need > best) best = need;
+    }
+    return best;
+}
+
+int tsm_conv_fwd(const tsm_conv_desc* d, const void* x, const void* w, void* y, float* ch_sum, float* ch_sumsq,
+                 void* ws, size_t ws_bytes, void* stream) {
+    return conv_entry(CONV_FWD, d, x, w, y, ch_sum, ch_sumsq, 0, ws, ws_bytes, false, (hipStream_t)stream, nullptr);
+}
+
+int tsm_conv_dgrad(const tsm_conv_desc* d, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes,
+                   void* stream) {
+    return conv_entry(CONV_DGRAD, d, dy, w, dx, nullptr, nullptr, 0, ws, ws_bytes, false, (hipStream_t)stream, nullptr);
+}
+
+int tsm_conv_wgrad(const tsm_conv_desc* d, const void* x, const void* dy, float* dw, int accumulate, void* ws,
+                   size_t ws_bytes, void* stream) {
+    return conv_entry(CONV_WGRAD, d, x, dy, dw, nullptr, nullptr, accumulate, ws, ws_bytes, false, (hipStream_t)stream, nullptr);
+}
+
+size_t tsm_block_saved_bytes(const tsm_block_desc* d) {
+    size_t sv = 0;
+    if (block_entry(false, d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, true,
+                    nullptr, nullptr, &sv) != TSM_OK)
+        return 0;
+    return sv;
+}
+
+size_t tsm_block_workspace_bytes(const tsm_block_desc* d) {
+    size_t a = 0, b = 0;
+    if (block_entry(false, d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, true,
+                    nullptr, &a, nullptr) != TSM_OK)
+        return 0;
+    if (block_entry(true, d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, true,
+                    nullptr, &b, nullptr) != TSM_OK)
+        return 0;
+    return a > b ? a : b;
+}
+
+int tsm_block_fwd(const tsm_block_desc* d, const void* x, const tsm_block_params* p, void* out, void* saved, void* ws,
+                  size_t ws_bytes, void* stream) {
+    return block_entry(false, d, x, nullptr, nullptr, p, out, saved, nullptr, nullptr, ws, ws_bytes, false,
+                       (hipStream_t)stream, nullptr, nullptr);
+}
+
+int tsm_block_bwd(const tsm_block_desc* d, const void* x, const void* out, const void* dout, const void* saved,
+                  const tsm_block_params* p, void* dx, const tsm_block_grads* g, void* ws, size_t ws_bytes,
+                  void* stream) {
+    return block_entry(true, d, x, out, dout, p, nullptr, const_cast<void*>(saved), dx, g, ws, ws_bytes, false,
+                       (hipStream_t)stream, nullptr, nullptr);
+}
+
+}  // extern "C"

@@ -1,0 +1,47 @@
+// Internal description of one residual block (channels-innermost frames) shared
+// by the block entry points and the TSM-ResNet-50 step.
+#pragma once
+#include "internal.h"
+
+namespace tsm {
+
+struct StageDef {
+    ConvP p;
+    const void* w;        // weights, ABI order [Cout][Cin][taps], block dtype
+    const bf16_t* wp;     // optional pre-packed forward weights  [Cout][taps][Cin]
+    const bf16_t* wd;     // optional pre-packed dgrad weights    [Cin][flipped taps][Cout]
+    const float *g, *b;   // BatchNorm scale / offset
+    float *dw, *dg, *db;  // gradients (fp32)
+    float *run_mean, *run_var;  // optional running statistics
+};
+
+struct BlockPlan {
+    int nst;              // 2 (basic) or 3 (bottleneck) convolution stages
+    StageDef st[3];
+    bool proj;
+    StageDef ds;          // projection shortcut
+    int dtype;
+    float eps, bn_momentum;
+    // saved-for-backward buffers (caller-owned memory)
+    void* y[3];           // convolution outputs
+    void* z[2];           // ReLU(BN(y)) of all but the last stage
+    void* yd;             // projection output
+    BnVec bn[3], bnd;
+    void *x_copy, *out_copy;  // channels-innermost copies when the caller's order is NTCHW
+};
+
+int run_conv_fwd(const ConvP& p, int dtype, const void* x, const void* w, const bf16_t* wp, void* y,
+                 double* stats_acc, Arena& ws, bool dry, hipStream_t s);
+int run_conv_dgrad(const ConvP& p, int dtype, const void* dy, const void* w, const bf16_t* wd, void* dx,
+                   const void* addend, Arena& ws, bool dry, hipStream_t s);
+int run_conv_wgrad(const ConvP& p, int dtype, const void* x, const void* dy, float* dw, int accumulate, Arena& ws,
+                   bool dry, hipStream_t s);
+
+int make_block_plan(const tsm_block_desc* d, BlockPlan* b, const char* who);
+void block_saved_layout(BlockPlan& b, Arena& sv, bool keep_x_copy);
+int block_fwd_impl(BlockPlan& b, const void* x, void* out, Arena& ws, bool dry, hipStream_t s);
+// dx may be null (no input gradient wanted).
+int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dout, void* dx, Arena& ws, bool dry,
+                   hipStream_t s);
+
+}  // namespace tsm

@@ -1,0 +1,84 @@
+// Internal launch interface between the translation units of the library.
+// All activations here are channels-innermost frames: [F][H][W][C].
+#pragma once
+#include "common.h"
+
+namespace tsm {
+
+// Geometry of one (shift-fused) convolution over F = N*T frames.
+struct ConvP {
+    int F, T;            // frames in the batch, frames per clip
+    int H, W, Cin;       // input frame
+    int Ho, Wo, Cout;    // output frame
+    int KT, KH, KW;      // temporal (1 or 3) and spatial taps
+    int stride, pad;     // spatial; the temporal taps use stride 1, padding KT/2
+    int fold;            // channels shifted each way on the input (0: none)
+    long rows_in() const { return (long)F * H * W; }
+    long rows_out() const { return (long)F * Ho * Wo; }
+    int taps() const { return KT * KH * KW; }
+    long K() const { return (long)taps() * Cin; }
+};
+
+// ---- shift.hip ----------------------------------------------------------------
+int shift_launch(const void* x, void* y, int N, int T, int C, int H, int W, int fold, int es, int layout,
+                 int dir, hipStream_t s);
+int transpose_frames(const void* in, void* out, int F, int rows, int cols, int es, hipStream_t s);
+
+// ---- direct.hip: plain kernels for any shape, fp32 or bf16 storage ---------------
+// Weights in the ABI order [Cout][Cin][KT*KH*KW], element type T (dtype).
+int conv_direct_fwd(const ConvP& p, int dtype, const void* x, const void* w, void* y, hipStream_t s);
+// dx = S^T(conv^T(dy, w)) (+ addend if not null, same shape as dx).
+int conv_direct_dgrad(const ConvP& p, int dtype, const void* dy, const void* w, void* dx, const void* addend,
+                      hipStream_t s);
+// dw fp32 [Cout][Cin][taps]; must be zeroed by the caller unless accumulating.
+int conv_direct_wgrad(const ConvP& p, int dtype, const void* x, const void* dy, float* dw, hipStream_t s);
+
+// ---- elementwise.hip -----------------------------------------------------------------
+// Per-channel batch statistics live in a double buffer `acc` of 2*C entries:
+// acc[c] = sum, acc[C + c] = sum of squares (or the two BatchNorm-backward sums).
+int fill_zero(void* p, size_t bytes, hipStream_t s);
+int channel_stats(int dtype, const void* y, long rows, int C, double* acc, hipStream_t s);
+struct BnVec {           // per-channel fp32 vectors of one BatchNorm, each [C]
+    float *mean, *rstd, *scale, *shift;
+};
+// mean/rstd/scale=gamma*rstd/shift=beta-mean*scale from acc; optional running stats update.
+int bn_finalize(const double* acc, long rows, int C, const float* gamma, const float* beta, float eps,
+                BnVec out, float* run_mean, float* run_var, float momentum, hipStream_t s);
+int stats_to_float(const double* acc, int C, float* sum, float* sumsq, hipStream_t s);
+// z = relu(scale*y + shift)
+int bn_relu_apply(int dtype, const void* y, long rows, int C, const float* scale, const float* shift, void* z,
+                  hipStream_t s);
+// out = relu(scale*y + shift + sc), sc = shortcut (scale_d == null) or scale_d*shortcut + shift_d
+int block_tail_fwd(int dtype, const void* y, long rows, int C, const float* scale, const float* shift,
+                   const void* shortcut, const float* scale_d, const float* shift_d, void* out, hipStream_t s);
+// dz = dout * [act > 0] written to dz_out (may alias dout); acc[c] += sum dz, acc[C+c] += sum dz*yhat with
+// yhat = (y - mean)*rstd.  If y2 != null a second BatchNorm (projection shortcut) is reduced into acc2.
+int relu_bn_bwd_reduce(int dtype, const void* dout, const void* act, const void* y, long rows, int C,
+                       const float* mean, const float* rstd, void* dz_out, double* acc, const void* y2,
+                       const float* mean2, const float* rstd2, double* acc2, hipStream_t s);
+// dy = gamma*rstd*(dz - sum_dz/m - yhat*sum_dzyhat/m); also writes dgamma, dbeta (fp32 [C]).
+int bn_bwd_apply(int dtype, const void* dz, const void* y, long rows, int C, const float* mean, const float* rstd,
+                 const float* gamma, const double* acc, void* dy, float* dgamma, float* dbeta, hipStream_t s);
+// out = a + b
+int add_tensors(int dtype, const void* a, const void* b, void* out, size_t n, hipStream_t s);
+// dtype conversion / repacking of weights
+// ABI [Cout][Cin][taps] (dtype) -> bf16 [Cout][taps][Cin]
+int pack_weights_fwd(int dtype, const void* w, bf16_t* out, int Cout, int Cin, int taps, hipStream_t s);
+// ABI [Cout][Cin][KT][KH][KW] -> bf16 [Cin][flipped taps][Cout]
+int pack_weights_dgrad(int dtype, const void* w, bf16_t* out, int Cout, int Cin, int KT, int KH, int KW,
+                       hipStream_t s);
+// fp32 [Cout][taps][Cin] -> fp32 [Cout][Cin][taps] (+= if accumulate)
+int unpack_wgrad(const float* packed, float* dw, int Cout, int Cin, int taps, int accumulate, hipStream_t s);
+
+// ---- conv_mfma.hip: bf16 MFMA implicit GEMM, channels-innermost -------------------------
+bool mfma_conv_supported(const ConvP& p);
+// y = conv(S(x)); wp = bf16 [Cout][taps][Cin]; stats (nullable) receives per-channel sum / sum of squares
+// of the stored (rounded) output, accumulated with atomics: zero it first.
+int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, double* stats, hipStream_t s);
+// dx = S^T(conv^T(dy)) + addend; wd = bf16 [Cin][flipped taps][Cout]
+int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* dx, const bf16_t* addend,
+                    hipStream_t s);
+// dwp fp32 [Cout][taps][Cin], accumulated with atomics: zero it first.
+int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dwp, hipStream_t s);
+
+}  // namespace tsm

