@@ -185,6 +185,7 @@ typedef struct {
     int fold_div;
     float lr, momentum, weight_decay;
     float bn_eps, bn_momentum;
+    int dtype;                /* storage type of clips and activations: TSM_BF16 (MFMA path) or TSM_F32 */
 } tsm_r50_desc;
 
 /* Number of parameters (24,327,632 for 400 classes) and of parameter tensors. */
@@ -201,7 +202,7 @@ int tsm_resnet50_param_info(int num_classes, int index, char* name, int name_cap
 int64_t tsm_resnet50_bn_state_count(void);
 size_t tsm_resnet50_workspace_bytes(const tsm_r50_desc* d);
 
-/* clips   bf16 [N,T,3,size,size] in the paper's order (TSM_NTCHW);
+/* clips   [N,T,3,size,size] of desc.dtype in the paper's order (TSM_NTCHW);
  * labels  int32 [N];
  * params, momentum   fp32 [param_count], updated in place;
  * bn_state  fp32 [bn_state_count] running mean/variance, updated in place, may be NULL;

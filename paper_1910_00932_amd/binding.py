@@ -57,7 +57,8 @@ class BlockGrads(ctypes.Structure):
 class R50Desc(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int), ("T", ctypes.c_int), ("size", ctypes.c_int), ("num_classes", ctypes.c_int),
                 ("fold_div", ctypes.c_int), ("lr", ctypes.c_float), ("momentum", ctypes.c_float),
-                ("weight_decay", ctypes.c_float), ("bn_eps", ctypes.c_float), ("bn_momentum", ctypes.c_float)]
+                ("weight_decay", ctypes.c_float), ("bn_eps", ctypes.c_float), ("bn_momentum", ctypes.c_float),
+                ("dtype", ctypes.c_int)]
 
 
 _LIB = None

@@ -44,7 +44,7 @@ int run_conv_fwd(const ConvP& p, int dtype, const void* x, const void* w, const 
     if (use_mfma(p, dtype)) {
         if (!wp) {
             bf16_t* pk = ws.take_n<bf16_t>((size_t)p.Cout * p.K());
-            RUN(pack_weights_fwd(dtype, w, pk, p.Cout, p.Cin, p.taps(), s));
+            RUN(pack_weights_fwd(dtype, w, pk, p.Cout, p.Cin, p.taps(), p.Cin, s));
             wp = pk;
         }
         RUN(conv_mfma_fwd(p, (const bf16_t*)x, wp, (bf16_t*)y, stats_acc, s));
@@ -77,7 +77,7 @@ int run_conv_wgrad(const ConvP& p, int dtype, const void* x, const void* dy, flo
         float* dwp = ws.take_n<float>(n);
         RUN(fill_zero(dwp, n * sizeof(float), s));
         RUN(conv_mfma_wgrad(p, (const bf16_t*)x, (const bf16_t*)dy, dwp, s));
-        RUN(unpack_wgrad(dwp, dw, p.Cout, p.Cin, p.taps(), accumulate, s));
+        RUN(unpack_wgrad(dwp, dw, p.Cout, p.Cin, p.taps(), p.Cin, accumulate, s));
     } else {
         if (!accumulate) RUN(fill_zero(dw, n * sizeof(float), s));
         RUN(conv_direct_wgrad(p, dtype, x, dy, dw, s));

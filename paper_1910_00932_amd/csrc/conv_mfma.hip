@@ -345,11 +345,13 @@ int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* 
 }
 
 // ---------------------------------------------------------------------------------
-// Weight gradient.  Per block: a [BCO x BCI] tile of one tap, reduced over a
-// chunk of output pixels.  Both operands are needed with the pixel index
-// contiguous, so the 16-byte global rows ([pixel][channel]) are transposed on
-// their way into LDS: each thread pairs two consecutive pixels of eight
-// channels into eight 32-bit LDS writes.
+// Weight gradient, D[Cout x K] = dy^T [Cout x pixels] * gathered x [pixels x K] with
+// K = taps * Cin enumerated tap-major (the packed-weight order).  Per block: a
+// [BCO x BCI] tile of D reduced over a chunk of output pixels, added to dwp with
+// fp32 atomics.  Both operands are needed with the pixel index contiguous, so the
+// 16-byte global rows ([pixel][channel]) are transposed on their way into LDS:
+// each thread pairs two consecutive pixels of eight channels into eight 32-bit
+// LDS writes.
 struct WgradArgs {
     const bf16_t* x;
     const bf16_t* dy;
@@ -361,7 +363,8 @@ struct WgradArgs {
     int fold;
     long M;                // output pixels
     long chunk;            // pixels per block (multiple of 64)
-    int taps;
+    int K;                 // taps * Cin
+    int col_tiles;
 };
 
 static constexpr int WMK = 64;        // pixels per main-loop step
@@ -380,25 +383,40 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs a) {
     constexpr int TM = BCO / 2, TN = BCI / 2;
     constexpr int MI = TM / 32, NJ = TN / 32;
     __shared__ __attribute__((aligned(16))) bf16_t At[2][BCO][LDT];   // dy^T  [co][pixel]
-    __shared__ __attribute__((aligned(16))) bf16_t Bt[2][BCI][LDT];   // xs^T  [ci][pixel]
+    __shared__ __attribute__((aligned(16))) bf16_t Bt[2][BCI][LDT];   // xs^T  [column][pixel]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int tap = blockIdx.z;
-    const int kw = tap % a.KW, kh = (tap / a.KW) % a.KH, kt = tap / (a.KW * a.KH);
-    const int ci_tiles = (a.Cin + BCI - 1) / BCI;
-    const int co0 = (blockIdx.y / ci_tiles) * BCO;
-    const int ci0 = (blockIdx.y % ci_tiles) * BCI;
+    const int co0 = (blockIdx.y / a.col_tiles) * BCO;
+    const int j0 = (blockIdx.y % a.col_tiles) * BCI;
     const long mbeg = (long)blockIdx.x * a.chunk;
     long mend = mbeg + a.chunk;
     if (mend > a.M) mend = a.M;
     const int hw = a.Ho * a.Wo;
 
-    // loader mapping: 8 consecutive lanes read one 128-byte row segment; every
-    // thread owns pixel pairs (2*pp, 2*pp+1) of channel vector `vec`.
+    // loader mapping: consecutive lanes read consecutive 16-byte pieces of one row;
+    // every thread owns pixel pairs (2*pp, 2*pp+1) of channel vector `vec`.
     constexpr int AV = BCO / 8, BV = BCI / 8;         // vectors per row
     constexpr int AP = (32 * AV + 255) / 256;         // (pair, vec) items per thread
     constexpr int BP = (32 * BV + 255) / 256;
+
+    // this thread's B columns: 8 consecutive K indices = 8 channels of one tap
+    int b_ci[BP], b_kh[BP], b_kw[BP], b_df[BP];
+#pragma unroll
+    for (int q = 0; q < BP; ++q) {
+        const int vec = (q * 256 + tid) % BV;
+        const int j = j0 + vec * 8;
+        if (j < a.K) {
+            const int tap = j / a.Cin;
+            b_ci[q] = j - tap * a.Cin;
+            b_kw[q] = tap % a.KW;
+            b_kh[q] = (tap / a.KW) % a.KH;
+            b_df[q] = tap / (a.KW * a.KH) - a.KT / 2 + group_dt(b_ci[q], a.fold);
+        } else {
+            b_ci[q] = -1;
+            b_kh[q] = b_kw[q] = b_df[q] = 0;
+        }
+    }
 
     f32x16 acc[MI][NJ];
 #pragma unroll
@@ -426,22 +444,19 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs a) {
         }
 #pragma unroll
         for (int q = 0; q < BP; ++q) {
-            const int item = q * 256 + tid;
-            const int vec = item % BV, pp = item / BV;
-            const int ci = ci0 + vec * 8;
-            const int df = kt - a.KT / 2 + group_dt(ci, a.fold);
+            const int pp = (q * 256 + tid) / BV;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const long m = mstep + 2 * pp + h;
                 u32x4 v = {0u, 0u, 0u, 0u};
-                if (pp < 32 && m < mend && ci < a.Cin) {
+                if (pp < 32 && m < mend && b_ci[q] >= 0) {
                     const int f = (int)(m / hw);
                     const int pix = (int)(m - (long)f * hw);
                     const int oh = pix / a.Wo, ow = pix - oh * a.Wo;
-                    const int ih = oh * a.stride + kh - a.pad, iw = ow * a.stride + kw - a.pad;
-                    const int ts = f % a.T + df;
+                    const int ih = oh * a.stride + b_kh[q] - a.pad, iw = ow * a.stride + b_kw[q] - a.pad;
+                    const int ts = f % a.T + b_df[q];
                     if (ts >= 0 && ts < a.T && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W)
-                        v = *(const u32x4*)(a.x + (((long)(f + df) * a.H + ih) * a.W + iw) * a.Cin + ci);
+                        v = *(const u32x4*)(a.x + (((long)(f + b_df[q]) * a.H + ih) * a.W + iw) * a.Cin + b_ci[q]);
                 }
                 br[q][h] = v;
             }
@@ -510,12 +525,11 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs a) {
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
-                const int ci = ci0 + wn * TN + j * 32 + (lane & 31);
+                const int col = j0 + wn * TN + j * 32 + (lane & 31);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int co = co0 + wm * TM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    if (co < a.Cout && ci < a.Cin)
-                        atomicAdd(a.dwp + ((long)co * a.taps + tap) * a.Cin + ci, acc[i][j][r]);
+                    if (co < a.Cout && col < a.K) atomicAdd(a.dwp + (long)co * a.K + col, acc[i][j][r]);
                 }
             }
     }
@@ -529,19 +543,20 @@ int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw
     a.KT = p.KT; a.KH = p.KH; a.KW = p.KW; a.stride = p.stride; a.pad = p.pad;
     a.fold = p.fold;
     a.M = p.rows_out();
-    a.taps = p.taps();
+    a.K = (int)p.K();
     if (a.M == 0) return TSM_OK;
-    const bool big = p.Cout > 64 && p.Cin > 64;
+    const bool big = p.Cout > 64 && a.K > 64;
     const int bco = big ? 128 : 64, bci = big ? 128 : 64;
-    const int tiles = cdiv(p.Cout, bco) * cdiv(p.Cin, bci);
-    long want = (long)4 * num_cu() / ((long)tiles * a.taps);
+    a.col_tiles = cdiv(a.K, bci);
+    const int tiles = cdiv(p.Cout, bco) * a.col_tiles;
+    long want = (long)4 * num_cu() / tiles;
     if (want < 1) want = 1;
     long chunk = (a.M + want - 1) / want;
     chunk = (chunk + WMK - 1) / WMK * WMK;
     if (chunk < 4 * WMK) chunk = 4 * WMK;
     a.chunk = chunk;
     const unsigned gx = (unsigned)((a.M + chunk - 1) / chunk);
-    dim3 grid(gx, (unsigned)tiles, (unsigned)a.taps);
+    dim3 grid(gx, (unsigned)tiles);
     if (big)
         wgrad_kernel<128, 128><<<grid, dim3(256), 0, s>>>(a);
     else

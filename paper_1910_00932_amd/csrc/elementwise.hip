@@ -258,12 +258,12 @@ __global__ void __launch_bounds__(256) relu_bn_bwd_reduce_kernel(
         }
         for (long r = (long)blockIdx.x * blockDim.y + threadIdx.y; r < rows; r += (long)gridDim.x * blockDim.y) {
             const long off = r * C + (long)cvi * V;
-            Pack<T, V> d = *(const Pack<T, V>*)(dout + off), a = *(const Pack<T, V>*)(act + off),
-                       yy = *(const Pack<T, V>*)(y + off), o, yy2;
+            Pack<T, V> d = *(const Pack<T, V>*)(dout + off), a, yy = *(const Pack<T, V>*)(y + off), o, yy2;
+            if (act) a = *(const Pack<T, V>*)(act + off);
             if (y2) yy2 = *(const Pack<T, V>*)(y2 + off);
 #pragma unroll
             for (int j = 0; j < V; ++j) {
-                const float dz = Elem<T>::ld(a.v[j]) > 0.f ? Elem<T>::ld(d.v[j]) : 0.f;
+                const float dz = (!act || Elem<T>::ld(a.v[j]) > 0.f) ? Elem<T>::ld(d.v[j]) : 0.f;
                 o.v[j] = Elem<T>::st(dz);
                 s1[j] += dz;
                 s2[j] = fmaf(dz, (Elem<T>::ld(yy.v[j]) - mu[j]) * rs[j], s2[j]);
@@ -383,21 +383,21 @@ int add_tensors(int dtype, const void* a, const void* b, void* out, size_t n, hi
 // ---- weight repacking ----------------------------------------------------------------------------
 template <typename T>
 __global__ void __launch_bounds__(256) pack_fwd_kernel(const T* __restrict__ w, bf16_t* __restrict__ out, int Cout,
-                                                       int Cin, int taps) {
-    long i = (long)blockIdx.x * 256 + threadIdx.x;  // out index: [co][tap][ci]
-    if (i >= (long)Cout * Cin * taps) return;
-    const int ci = (int)(i % Cin);
-    const int tap = (int)((i / Cin) % taps);
-    const int co = (int)(i / ((long)Cin * taps));
-    out[i] = f32_to_bf16(Elem<T>::ld(w[((long)co * Cin + ci) * taps + tap]));
+                                                       int Cin, int taps, int CinP) {
+    long i = (long)blockIdx.x * 256 + threadIdx.x;  // out index: [co][tap][ci padded to CinP]
+    if (i >= (long)Cout * CinP * taps) return;
+    const int ci = (int)(i % CinP);
+    const int tap = (int)((i / CinP) % taps);
+    const int co = (int)(i / ((long)CinP * taps));
+    out[i] = ci < Cin ? f32_to_bf16(Elem<T>::ld(w[((long)co * Cin + ci) * taps + tap])) : (bf16_t)0;
 }
 
-int pack_weights_fwd(int dtype, const void* w, bf16_t* out, int Cout, int Cin, int taps, hipStream_t s) {
-    long n = (long)Cout * Cin * taps;
+int pack_weights_fwd(int dtype, const void* w, bf16_t* out, int Cout, int Cin, int taps, int CinP, hipStream_t s) {
+    long n = (long)Cout * CinP * taps;
     if (dtype == TSM_F32)
-        pack_fwd_kernel<float><<<dim3(cdiv(n, 256)), dim3(256), 0, s>>>((const float*)w, out, Cout, Cin, taps);
+        pack_fwd_kernel<float><<<dim3(cdiv(n, 256)), dim3(256), 0, s>>>((const float*)w, out, Cout, Cin, taps, CinP);
     else
-        pack_fwd_kernel<bf16_t><<<dim3(cdiv(n, 256)), dim3(256), 0, s>>>((const bf16_t*)w, out, Cout, Cin, taps);
+        pack_fwd_kernel<bf16_t><<<dim3(cdiv(n, 256)), dim3(256), 0, s>>>((const bf16_t*)w, out, Cout, Cin, taps, CinP);
     return check_launch("pack_weights_fwd");
 }
 
@@ -426,19 +426,20 @@ int pack_weights_dgrad(int dtype, const void* w, bf16_t* out, int Cout, int Cin,
 }
 
 __global__ void __launch_bounds__(256) unpack_wgrad_kernel(const float* __restrict__ packed, float* __restrict__ dw,
-                                                           int Cout, int Cin, int taps, int accumulate) {
+                                                           int Cout, int Cin, int taps, int CinP, int accumulate) {
     long i = (long)blockIdx.x * 256 + threadIdx.x;  // dw index: [co][ci][tap]
     if (i >= (long)Cout * Cin * taps) return;
     const int tap = (int)(i % taps);
     const int ci = (int)((i / taps) % Cin);
     const int co = (int)(i / ((long)Cin * taps));
-    const float v = packed[((long)co * taps + tap) * Cin + ci];
+    const float v = packed[((long)co * taps + tap) * CinP + ci];
     dw[i] = accumulate ? dw[i] + v : v;
 }
 
-int unpack_wgrad(const float* packed, float* dw, int Cout, int Cin, int taps, int accumulate, hipStream_t s) {
+int unpack_wgrad(const float* packed, float* dw, int Cout, int Cin, int taps, int CinP, int accumulate,
+                 hipStream_t s) {
     long n = (long)Cout * Cin * taps;
-    unpack_wgrad_kernel<<<dim3(cdiv(n, 256)), dim3(256), 0, s>>>(packed, dw, Cout, Cin, taps, accumulate);
+    unpack_wgrad_kernel<<<dim3(cdiv(n, 256)), dim3(256), 0, s>>>(packed, dw, Cout, Cin, taps, CinP, accumulate);
     return check_launch("unpack_wgrad");
 }
 

@@ -51,7 +51,7 @@ int bn_relu_apply(int dtype, const void* y, long rows, int C, const float* scale
 // out = relu(scale*y + shift + sc), sc = shortcut (scale_d == null) or scale_d*shortcut + shift_d
 int block_tail_fwd(int dtype, const void* y, long rows, int C, const float* scale, const float* shift,
                    const void* shortcut, const float* scale_d, const float* shift_d, void* out, hipStream_t s);
-// dz = dout * [act > 0] written to dz_out (may alias dout); acc[c] += sum dz, acc[C+c] += sum dz*yhat with
+// dz = dout * [act > 0] (act == null: no mask) written to dz_out (may alias dout); acc[c] += sum dz, acc[C+c] += sum dz*yhat with
 // yhat = (y - mean)*rstd.  If y2 != null a second BatchNorm (projection shortcut) is reduced into acc2.
 int relu_bn_bwd_reduce(int dtype, const void* dout, const void* act, const void* y, long rows, int C,
                        const float* mean, const float* rstd, void* dz_out, double* acc, const void* y2,
@@ -62,13 +62,14 @@ int bn_bwd_apply(int dtype, const void* dz, const void* y, long rows, int C, con
 // out = a + b
 int add_tensors(int dtype, const void* a, const void* b, void* out, size_t n, hipStream_t s);
 // dtype conversion / repacking of weights
-// ABI [Cout][Cin][taps] (dtype) -> bf16 [Cout][taps][Cin]
-int pack_weights_fwd(int dtype, const void* w, bf16_t* out, int Cout, int Cin, int taps, hipStream_t s);
+// ABI [Cout][Cin][taps] (dtype) -> bf16 [Cout][taps][CinP], channels ci >= Cin zero
+int pack_weights_fwd(int dtype, const void* w, bf16_t* out, int Cout, int Cin, int taps, int CinP, hipStream_t s);
 // ABI [Cout][Cin][KT][KH][KW] -> bf16 [Cin][flipped taps][Cout]
 int pack_weights_dgrad(int dtype, const void* w, bf16_t* out, int Cout, int Cin, int KT, int KH, int KW,
                        hipStream_t s);
-// fp32 [Cout][taps][Cin] -> fp32 [Cout][Cin][taps] (+= if accumulate)
-int unpack_wgrad(const float* packed, float* dw, int Cout, int Cin, int taps, int accumulate, hipStream_t s);
+// fp32 [Cout][taps][CinP] -> fp32 [Cout][Cin][taps] (+= if accumulate)
+int unpack_wgrad(const float* packed, float* dw, int Cout, int Cin, int taps, int CinP, int accumulate,
+                 hipStream_t s);
 
 // ---- conv_mfma.hip: bf16 MFMA implicit GEMM, channels-innermost -------------------------
 bool mfma_conv_supported(const ConvP& p);

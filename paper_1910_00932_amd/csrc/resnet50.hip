@@ -1,0 +1,650 @@
+// One training iteration of TSM-ResNet-50 (paper section 3, model (3): ResNet-50
+// backbone, the shift inserted into every residual block, 8 frames, no temporal
+// pooling -- Table 2; Table 1: 24.3M parameters, 33G multiply-accumulates per
+// clip, which fixes the stride on the 3x3 convolution; section 4.1: SGD with
+// weight decay that skips BatchNorm and bias parameters).
+//
+// Everything between the clip tensor and the updated parameters runs here as a
+// stream of kernel launches on the caller's stream, with no host synchronisation.
+#include <string.h>
+#include <string>
+#include <vector>
+#include "block.h"
+#include "internal.h"
+
+namespace tsm {
+
+// ---- parameter table -------------------------------------------------------------------
+struct TensorInfo {
+    std::string name;
+    int64_t offset;
+    int ndim;
+    int shape[4];
+    bool decays;
+    int64_t count() const {
+        int64_t n = 1;
+        for (int i = 0; i < ndim; ++i) n *= shape[i];
+        return n;
+    }
+};
+
+struct StageSpec { const char* name; int blocks, mid, stride; };
+static const StageSpec kStages[4] = {{"res2", 3, 64, 1}, {"res3", 4, 128, 2}, {"res4", 6, 256, 2}, {"res5", 3, 512, 2}};
+
+static std::vector<TensorInfo> build_table(int num_classes) {
+    std::vector<TensorInfo> t;
+    int64_t off = 0;
+    auto add = [&](const std::string& name, std::initializer_list<int> shp, bool decays) {
+        TensorInfo ti;
+        ti.name = name;
+        ti.offset = off;
+        ti.ndim = (int)shp.size();
+        int i = 0;
+        for (int v : shp) ti.shape[i++] = v;
+        for (; i < 4; ++i) ti.shape[i] = 1;
+        ti.decays = decays;
+        off += ti.count();
+        t.push_back(ti);
+    };
+    auto add_bn = [&](const std::string& pre, int c) {
+        add(pre + ".g", {c}, false);
+        add(pre + ".b", {c}, false);
+    };
+    add("conv1.w", {64, 3, 7, 7}, true);
+    add_bn("bn1", 64);
+    int cin = 64;
+    for (const StageSpec& st : kStages) {
+        for (int b = 0; b < st.blocks; ++b) {
+            const std::string pre = std::string(st.name) + "." + std::to_string(b) + ".";
+            add(pre + "c1.w", {st.mid, cin, 1, 1}, true);
+            add_bn(pre + "bn1", st.mid);
+            add(pre + "c2.w", {st.mid, st.mid, 3, 3}, true);
+            add_bn(pre + "bn2", st.mid);
+            add(pre + "c3.w", {4 * st.mid, st.mid, 1, 1}, true);
+            add_bn(pre + "bn3", 4 * st.mid);
+            if (b == 0) {
+                add(pre + "ds.w", {4 * st.mid, cin, 1, 1}, true);
+                add_bn(pre + "dsbn", 4 * st.mid);
+            }
+            cin = 4 * st.mid;
+        }
+    }
+    add("fc.w", {num_classes, 2048}, true);
+    add("fc.b", {num_classes}, false);
+    return t;
+}
+
+static int find_tensor(const std::vector<TensorInfo>& t, const std::string& name) {
+    for (size_t i = 0; i < t.size(); ++i)
+        if (t[i].name == name) return (int)i;
+    return -1;
+}
+
+// ---- stem input: [F][3][S][S] planes -> [F][S][S][8] (channels 3..7 zero) ---------------------
+__global__ void __launch_bounds__(256) clips_to_nhwc8_kernel(const bf16_t* __restrict__ in, uint4* __restrict__ out,
+                                                             long pixels_per_frame, long total) {
+    long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const long f = i / pixels_per_frame, p = i - f * pixels_per_frame;
+    const bf16_t* base = in + f * 3 * pixels_per_frame + p;
+    const uint32_t c0 = base[0], c1 = base[pixels_per_frame], c2 = base[2 * pixels_per_frame];
+    out[i] = make_uint4(c0 | (c1 << 16), c2, 0u, 0u);
+}
+
+// ---- BN + ReLU + 3x3/2 max-pool (padding 1; padding never wins) ---------------------------------
+// Values are rounded to bf16 before they are compared, so the first-maximum rule is
+// applied to the tensor a separate BN/ReLU pass would have stored.
+template <typename T>
+__global__ void __launch_bounds__(256) stem_pool_fwd_kernel(const T* __restrict__ y, const float* __restrict__ scale,
+                                                            const float* __restrict__ shift, T* __restrict__ out,
+                                                            uint8_t* __restrict__ arg, int H, int W, int Ho, int Wo,
+                                                            int cv, long total) {
+    constexpr int V = Elem<T>::VEC;
+    long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int v = (int)(i % cv);
+    long r = i / cv;
+    const int ow = (int)(r % Wo);
+    r /= Wo;
+    const int oh = (int)(r % Ho);
+    const long f = r / Ho;
+    float best[V], sc[V], sh[V];
+    int barg[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        best[j] = -1.f;   // post-ReLU values are >= 0, so any valid tap beats this
+        barg[j] = 0;
+        sc[j] = scale[v * V + j];
+        sh[j] = shift[v * V + j];
+    }
+    for (int kh = 0; kh < 3; ++kh) {
+        const int ih = 2 * oh + kh - 1;
+        if (ih < 0 || ih >= H) continue;
+        for (int kw = 0; kw < 3; ++kw) {
+            const int iw = 2 * ow + kw - 1;
+            if (iw < 0 || iw >= W) continue;
+            const Vec16<T> pk = *(const Vec16<T>*)(y + ((f * H + ih) * W + iw) * (long)cv * V + v * V);
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                float z = fmaf(Elem<T>::ld(pk.v[j]), sc[j], sh[j]);
+                z = Elem<T>::ld(Elem<T>::st(z > 0.f ? z : 0.f));
+                if (z > best[j]) {
+                    best[j] = z;
+                    barg[j] = kh * 3 + kw;
+                }
+            }
+        }
+    }
+    Vec16<T> o;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        o.v[j] = Elem<T>::st(best[j]);
+        arg[i * V + j] = (uint8_t)barg[j];
+    }
+    *(Vec16<T>*)(out + i * V) = o;
+}
+
+// Gradient of the pooled tensor routed back to the window position that won, times the
+// ReLU mask of the (recomputed) stem activation.  Gather form: no atomics.
+template <typename T>
+__global__ void __launch_bounds__(256) stem_pool_bwd_kernel(const T* __restrict__ dp, const uint8_t* __restrict__ arg,
+                                                            const T* __restrict__ y, const float* __restrict__ scale,
+                                                            const float* __restrict__ shift, T* __restrict__ da,
+                                                            int H, int W, int Ho, int Wo, int cv, long total) {
+    constexpr int V = Elem<T>::VEC;
+    long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int v = (int)(i % cv);
+    long r = i / cv;
+    const int iw = (int)(r % W);
+    r /= W;
+    const int ih = (int)(r % H);
+    const long f = r / H;
+    float g[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) g[j] = 0.f;
+    const int oh_lo = ih / 2, oh_hi = (ih + 1) / 2;   // windows [2*oh-1, 2*oh+1] containing ih
+    const int ow_lo = iw / 2, ow_hi = (iw + 1) / 2;
+    for (int oh = oh_lo; oh <= oh_hi; ++oh) {
+        if (oh >= Ho) continue;
+        const int kh = ih - (2 * oh - 1);
+        for (int ow = ow_lo; ow <= ow_hi; ++ow) {
+            if (ow >= Wo) continue;
+            const int code = kh * 3 + (iw - (2 * ow - 1));
+            const long o = ((f * Ho + oh) * Wo + ow) * (long)cv + v;
+            const Vec16<T> d = *(const Vec16<T>*)(dp + o * V);
+#pragma unroll
+            for (int j = 0; j < V; ++j)
+                if ((int)arg[o * V + j] == code) g[j] += Elem<T>::ld(d.v[j]);
+        }
+    }
+    const Vec16<T> pk = *(const Vec16<T>*)(y + i * V);
+    Vec16<T> o;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        const float z = fmaf(Elem<T>::ld(pk.v[j]), scale[v * V + j], shift[v * V + j]);
+        const bool live = Elem<T>::ld(Elem<T>::st(z > 0.f ? z : 0.f)) > 0.f;
+        o.v[j] = Elem<T>::st(live ? g[j] : 0.f);
+    }
+    *(Vec16<T>*)(da + i * V) = o;
+}
+
+// ---- head: global average pool + temporal consensus + linear + softmax cross-entropy ---------
+// The consensus (mean over T of the per-frame linear outputs) is an affine map, so the
+// mean over frames and pixels is taken first: pm[n][c] = mean_{t,h,w} feat[n,t,h,w,c].
+template <typename T>
+__global__ void __launch_bounds__(256) pool_mean_kernel(const T* __restrict__ feat, float* __restrict__ pm,
+                                                        int rows_per_clip, int C) {
+    const int n = blockIdx.y;
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C) return;
+    const T* p = feat + (long)n * rows_per_clip * C + c;
+    float s = 0.f;
+    for (int r = 0; r < rows_per_clip; ++r) s += Elem<T>::ld(p[(long)r * C]);
+    pm[(long)n * C + c] = s / (float)rows_per_clip;
+}
+
+// logits[n][k] = b[k] + sum_c W[k][c] * pm[n][c]; one block per class k.
+__global__ void __launch_bounds__(256) fc_fwd_kernel(const float* __restrict__ pm, const float* __restrict__ W,
+                                                     const float* __restrict__ b, float* __restrict__ logits, int N,
+                                                     int C, int K) {
+    __shared__ float red[4];
+    const int k = blockIdx.x;
+    for (int n = 0; n < N; ++n) {
+        float s = 0.f;
+        for (int c = threadIdx.x; c < C; c += 256) s = fmaf(W[(long)k * C + c], pm[(long)n * C + c], s);
+        for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o, 64);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+        __syncthreads();
+        if (threadIdx.x == 0) logits[(long)n * K + k] = red[0] + red[1] + red[2] + red[3] + b[k];
+        __syncthreads();
+    }
+}
+
+// One block; loss = -mean_n log softmax(logits[n])[label[n]]; dlogits = (softmax - onehot)/N.
+__global__ void __launch_bounds__(256) softmax_ce_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
+                                                         float* __restrict__ dlogits, float* __restrict__ loss, int N,
+                                                         int K) {
+    __shared__ float red[4];
+    __shared__ float bcast;
+    float total = 0.f;
+    for (int n = 0; n < N; ++n) {
+        const float* z = logits + (long)n * K;
+        float mx = -3.0e38f;
+        for (int k = threadIdx.x; k < K; k += 256) mx = fmaxf(mx, z[k]);
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_down(mx, o, 64));
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+        __syncthreads();
+        if (threadIdx.x == 0) bcast = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        __syncthreads();
+        mx = bcast;
+        float s = 0.f;
+        for (int k = threadIdx.x; k < K; k += 256) s += expf(z[k] - mx);
+        for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o, 64);
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+        __syncthreads();
+        if (threadIdx.x == 0) bcast = red[0] + red[1] + red[2] + red[3];
+        __syncthreads();
+        const float lse = mx + logf(bcast);
+        int lab = labels[n];
+        if (lab < 0 || lab >= K) lab = 0;   // out-of-range labels are treated as class 0
+        for (int k = threadIdx.x; k < K; k += 256)
+            dlogits[(long)n * K + k] = (expf(z[k] - lse) - (k == lab ? 1.f : 0.f)) / (float)N;
+        total += lse - z[lab];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss = total / (float)N;
+}
+
+// dW[k][c] = sum_n dlogits[n][k]*pm[n][c]; db[k] = sum_n dlogits[n][k]
+__global__ void __launch_bounds__(256) fc_bwd_w_kernel(const float* __restrict__ dlogits, const float* __restrict__ pm,
+                                                       float* __restrict__ dW, float* __restrict__ db, int N, int C,
+                                                       int K) {
+    const int k = blockIdx.y;
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c < C) {
+        float s = 0.f;
+        for (int n = 0; n < N; ++n) s = fmaf(dlogits[(long)n * K + k], pm[(long)n * C + c], s);
+        dW[(long)k * C + c] = s;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        float s = 0.f;
+        for (int n = 0; n < N; ++n) s += dlogits[(long)n * K + k];
+        db[k] = s;
+    }
+}
+
+// dpm[n][c] = sum_k dlogits[n][k]*W[k][c]
+__global__ void __launch_bounds__(256) fc_bwd_x_kernel(const float* __restrict__ dlogits, const float* __restrict__ W,
+                                                       float* __restrict__ dpm, int C, int K) {
+    const int n = blockIdx.y;
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C) return;
+    float s = 0.f;
+    for (int k = 0; k < K; ++k) s = fmaf(dlogits[(long)n * K + k], W[(long)k * C + c], s);
+    dpm[(long)n * C + c] = s;
+}
+
+// dfeat[n][r][c] = dpm[n][c] / rows_per_clip
+template <typename T>
+__global__ void __launch_bounds__(256) pool_mean_bwd_kernel(const float* __restrict__ dpm, T* __restrict__ dfeat,
+                                                            int rows_per_clip, int C, long total) {
+    long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int c = (int)(i % C);
+    const long n = i / ((long)rows_per_clip * C);
+    dfeat[i] = Elem<T>::st(dpm[n * C + c] / (float)rows_per_clip);
+}
+
+// ---- SGD with momentum; weight decay only inside "decay" segments -----------------------------
+struct SgdSegments {
+    int n;
+    unsigned start[120];     // ascending element offsets; segment s covers [start[s], start[s+1])
+    unsigned char decays[120];
+};
+
+__global__ void __launch_bounds__(256) sgd_kernel(float* __restrict__ w, float* __restrict__ v,
+                                                  const float* __restrict__ g, long total, SgdSegments seg, float lr,
+                                                  float momentum, float wd) {
+    long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    int lo = 0, hi = seg.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((long)seg.start[mid] <= i) lo = mid; else hi = mid - 1;
+    }
+    const float wi = w[i];
+    const float gi = g[i] + (seg.decays[lo] ? wd * wi : 0.f);
+    const float vi = fmaf(momentum, v[i], gi);
+    v[i] = vi;
+    w[i] = wi - lr * vi;
+}
+
+// ---- the step ---------------------------------------------------------------------------------
+#define RUN(expr)                          \
+    do {                                   \
+        if (!dry) TSM_TRY(expr);           \
+    } while (0)
+#define LAUNCH_CHECK(what) RUN(check_launch(what))
+
+static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* labels, float* params, float* momentum,
+                    float* bn_state, float* grads_out, float* loss_out, float* logits_out, int update, void* wsp,
+                    size_t ws_bytes, bool dry, hipStream_t s, size_t* need) {
+    const char* who = "tsm_resnet50_step";
+    if (!d) return fail(TSM_ERR_NULLPTR, "%s: null descriptor", who);
+    if (d->N <= 0 || d->T <= 0 || d->size < 32 || d->num_classes <= 0)
+        return fail(TSM_ERR_SHAPE, "%s: N, T, num_classes must be positive and size >= 32", who);
+    if (d->size % 32) return fail(TSM_ERR_SHAPE, "%s: size must be a multiple of 32", who);
+    if ((long)d->N * d->T > 65535) return fail(TSM_ERR_SHAPE, "%s: too many frames", who);
+    if (d->dtype != TSM_F32 && d->dtype != TSM_BF16) return fail(TSM_ERR_DTYPE, "%s: unknown dtype %d", who, d->dtype);
+    int fold_chk = 0;
+    if (fold_of(64, d->fold_div, &fold_chk) != TSM_OK) return fail(TSM_ERR_FOLD, "%s: invalid fold_div %d", who, d->fold_div);
+    if (!dry) {
+        if (!clips || !labels || !params || !momentum || !loss_out) return fail(TSM_ERR_NULLPTR, "%s: null pointer", who);
+        if (!aligned16(clips) || !aligned16(params) || !aligned16(momentum) || !aligned16(wsp) || !aligned16(grads_out))
+            return fail(TSM_ERR_ALIGN, "%s: pointers must be 16-byte aligned", who);
+        size_t req = 0;
+        TSM_TRY(r50_step(d, clips, labels, params, momentum, bn_state, grads_out, loss_out, logits_out, update, nullptr,
+                         0, true, s, &req));
+        if (req > ws_bytes) return fail(TSM_ERR_WORKSPACE, "%s: workspace %zu bytes, need %zu", who, ws_bytes, req);
+        if (!wsp) return fail(TSM_ERR_NULLPTR, "%s: null workspace", who);
+    }
+    static thread_local std::vector<TensorInfo> table;
+    static thread_local int table_classes = -1;
+    if (table_classes != d->num_classes) {
+        table = build_table(d->num_classes);
+        table_classes = d->num_classes;
+    }
+    const int64_t nparams = table.back().offset + table.back().count();
+    const int F = d->N * d->T, T = d->T, S = d->size, K = d->num_classes;
+    const int dtype = d->dtype;
+    const bool bf = dtype == TSM_BF16;
+    const size_t es = dtype_size(dtype);
+    const int VEC = bf ? 8 : 4;
+    Arena A(dry ? nullptr : wsp, (size_t)-1);
+
+    // running-statistics slots follow the BatchNorm order of the table
+    int64_t bn_off = 0;
+    auto run_slot = [&](int C, float** rm, float** rv) {
+        if (bn_state) {
+            *rm = bn_state + bn_off;
+            *rv = bn_state + bn_off + C;
+        } else {
+            *rm = *rv = nullptr;
+        }
+        bn_off += 2 * C;
+    };
+
+    float* grads = grads_out ? grads_out : A.take_n<float>((size_t)nparams);
+
+    auto P = [&](const std::string& name) { return params + table[find_tensor(table, name)].offset; };
+    auto G = [&](const std::string& name) { return grads + table[find_tensor(table, name)].offset; };
+    // bf16: working copies of the convolution weights in both packings; fp32: the master weights are used directly
+    auto pack_conv = [&](const std::string& name, int Cout, int Cin, int k, int CinP, const bf16_t** wp,
+                         const bf16_t** wd) -> int {
+        *wp = nullptr;
+        if (wd) *wd = nullptr;
+        if (!bf) return TSM_OK;
+        bf16_t* a = A.take_n<bf16_t>((size_t)Cout * CinP * k * k);
+        RUN(pack_weights_fwd(TSM_F32, P(name), a, Cout, Cin, k * k, CinP, s));
+        *wp = a;
+        if (wd) {
+            bf16_t* b2 = A.take_n<bf16_t>((size_t)Cout * Cin * k * k);
+            RUN(pack_weights_dgrad(TSM_F32, P(name), b2, Cout, Cin, 1, k, k, s));
+            *wd = b2;
+        }
+        return TSM_OK;
+    };
+
+    size_t scratch_need = 0;
+
+    // ---- stem: bf16 pads the three input channels to eight for the MFMA kernel; fp32 keeps three
+    const int H1 = S / 2, Hp = S / 4;     // conv1 output, pooled output
+    const int C0 = bf ? 8 : 3;
+    const bf16_t* wp0 = nullptr;
+    TSM_TRY(pack_conv("conv1.w", 64, 3, 7, 8, &wp0, nullptr));
+    void* x0 = A.take((size_t)F * S * S * C0 * es);
+    void* y0 = A.take((size_t)F * H1 * H1 * 64 * es);
+    BnVec bn0;
+    bn0.mean = A.take_n<float>(64); bn0.rstd = A.take_n<float>(64); bn0.scale = A.take_n<float>(64); bn0.shift = A.take_n<float>(64);
+    double* acc0 = A.take_n<double>(128);
+    uint8_t* arg0 = A.take_n<uint8_t>((size_t)F * Hp * Hp * 64);
+    void* p0 = A.take((size_t)F * Hp * Hp * 64 * es);
+    ConvP stem{};
+    stem.F = F; stem.T = T; stem.H = S; stem.W = S; stem.Cin = C0; stem.Ho = H1; stem.Wo = H1; stem.Cout = 64;
+    stem.KT = 1; stem.KH = 7; stem.KW = 7; stem.stride = 2; stem.pad = 3; stem.fold = 0;
+    float *rm0, *rv0;
+    run_slot(64, &rm0, &rv0);
+
+    // ---- blocks: plans, saved buffers, outputs
+    struct Blk {
+        BlockPlan plan;
+        void* out;
+        const void* in;
+    };
+    std::vector<Blk> blks;
+    {
+        int cin = 64, h = Hp;
+        const void* cur = p0;
+        for (const StageSpec& st : kStages) {
+            for (int b = 0; b < st.blocks; ++b) {
+                const std::string pre = std::string(st.name) + "." + std::to_string(b) + ".";
+                tsm_block_desc bd{};
+                bd.kind = TSM_BLOCK_BOTTLENECK; bd.N = d->N; bd.T = T; bd.Cin = cin; bd.H = h; bd.W = h;
+                bd.Cmid = st.mid; bd.Cout = 4 * st.mid; bd.stride = b == 0 ? st.stride : 1; bd.has_projection = b == 0;
+                bd.fold_div = d->fold_div; bd.dtype = dtype; bd.layout = TSM_NTHWC; bd.bn_eps = d->bn_eps;
+                Blk blk;
+                TSM_TRY(make_block_plan(&bd, &blk.plan, who));
+                BlockPlan& pl = blk.plan;
+                pl.bn_momentum = d->bn_momentum;
+                const char* cn[3] = {"c1.w", "c2.w", "c3.w"};
+                const char* bnn[3] = {"bn1", "bn2", "bn3"};
+                for (int i = 0; i < 3; ++i) {
+                    StageDef& sd = pl.st[i];
+                    TSM_TRY(pack_conv(pre + cn[i], sd.p.Cout, sd.p.Cin, sd.p.KH, sd.p.Cin, &sd.wp, &sd.wd));
+                    sd.w = P(pre + cn[i]);   // fp32 master weights: read by the fp32 kernels only
+                    sd.g = P(pre + bnn[i] + ".g"); sd.b = P(pre + bnn[i] + ".b");
+                    sd.dw = G(pre + cn[i]); sd.dg = G(pre + bnn[i] + ".g"); sd.db = G(pre + bnn[i] + ".b");
+                    run_slot(sd.p.Cout, &sd.run_mean, &sd.run_var);
+                }
+                if (pl.proj) {
+                    StageDef& sd = pl.ds;
+                    TSM_TRY(pack_conv(pre + "ds.w", sd.p.Cout, sd.p.Cin, 1, sd.p.Cin, &sd.wp, &sd.wd));
+                    sd.w = P(pre + "ds.w");
+                    sd.g = P(pre + "dsbn.g"); sd.b = P(pre + "dsbn.b");
+                    sd.dw = G(pre + "ds.w"); sd.dg = G(pre + "dsbn.g"); sd.db = G(pre + "dsbn.b");
+                    run_slot(sd.p.Cout, &sd.run_mean, &sd.run_var);
+                }
+                block_saved_layout(pl, A, false);
+                const ConvP& last = pl.st[2].p;
+                blk.out = A.take((size_t)last.rows_out() * last.Cout * es);
+                blk.in = cur;
+                cur = blk.out;
+                blks.push_back(blk);
+                cin = 4 * st.mid;
+                h = last.Ho;
+            }
+        }
+    }
+    const ConvP& lastp = blks.back().plan.st[2].p;
+    const int Cf = lastp.Cout, rows_clip = T * lastp.Ho * lastp.Wo;
+    float* pm = A.take_n<float>((size_t)d->N * Cf);
+    float* dpm = A.take_n<float>((size_t)d->N * Cf);
+    float* logits = logits_out ? logits_out : A.take_n<float>((size_t)d->N * K);
+    float* dlogits = A.take_n<float>((size_t)d->N * K);
+    // gradient ping-pong buffers: the largest activation between blocks
+    size_t act_max = (size_t)F * Hp * Hp * 64 * es;
+    for (const Blk& b : blks) {
+        const ConvP& l = b.plan.st[2].p;
+        const size_t by = (size_t)l.rows_out() * l.Cout * es;
+        if (by > act_max) act_max = by;
+    }
+    void* dbuf[2] = {A.take(act_max), A.take(act_max)};
+    void* da0 = A.take((size_t)F * H1 * H1 * 64 * es);
+    float* dwp0 = A.take_n<float>((size_t)64 * 49 * 8);
+    char* scratch_base = dry ? nullptr : (char*)wsp + A.used;
+    const size_t scratch_cap = dry ? (size_t)-1 : (ws_bytes > A.used ? ws_bytes - A.used : 0);
+    auto note = [&](const Arena& sc) { if (sc.used > scratch_need) scratch_need = sc.used; };
+
+    // ================= forward =================
+    {
+        const long px = (long)S * S, total = (long)F * px;
+        if (bf) {
+            if (!dry) {
+                clips_to_nhwc8_kernel<<<dim3(cdiv(total, 256)), dim3(256), 0, s>>>((const bf16_t*)clips, (uint4*)x0, px, total);
+                LAUNCH_CHECK("clips_to_nhwc8");
+            }
+        } else {
+            RUN(transpose_frames(clips, x0, F, 3, S * S, 4, s));
+        }
+        RUN(fill_zero(acc0, 128 * sizeof(double), s));
+        if (bf) {
+            RUN(conv_mfma_fwd(stem, (const bf16_t*)x0, wp0, (bf16_t*)y0, acc0, s));
+        } else {
+            RUN(conv_direct_fwd(stem, dtype, x0, P("conv1.w"), y0, s));
+            RUN(channel_stats(dtype, y0, stem.rows_out(), 64, acc0, s));
+        }
+        RUN(bn_finalize(acc0, stem.rows_out(), 64, P("bn1.g"), P("bn1.b"), d->bn_eps, bn0, rm0, rv0, d->bn_momentum, s));
+        const int cv = 64 / VEC;
+        const long ptotal = (long)F * Hp * Hp * cv;
+        if (!dry) {
+            if (bf)
+                stem_pool_fwd_kernel<bf16_t><<<dim3(cdiv(ptotal, 256)), dim3(256), 0, s>>>((const bf16_t*)y0, bn0.scale, bn0.shift, (bf16_t*)p0, arg0, H1, H1, Hp, Hp, cv, ptotal);
+            else
+                stem_pool_fwd_kernel<float><<<dim3(cdiv(ptotal, 256)), dim3(256), 0, s>>>((const float*)y0, bn0.scale, bn0.shift, (float*)p0, arg0, H1, H1, Hp, Hp, cv, ptotal);
+            LAUNCH_CHECK("stem_pool_fwd");
+        }
+    }
+    for (Blk& b : blks) {
+        Arena sc(scratch_base, scratch_cap);
+        TSM_TRY(block_fwd_impl(b.plan, b.in, b.out, sc, dry, s));
+        note(sc);
+    }
+    if (!dry) {
+        if (bf)
+            pool_mean_kernel<bf16_t><<<dim3(cdiv(Cf, 256), d->N), dim3(256), 0, s>>>((const bf16_t*)blks.back().out, pm, rows_clip, Cf);
+        else
+            pool_mean_kernel<float><<<dim3(cdiv(Cf, 256), d->N), dim3(256), 0, s>>>((const float*)blks.back().out, pm, rows_clip, Cf);
+        LAUNCH_CHECK("pool_mean");
+        fc_fwd_kernel<<<dim3(K), dim3(256), 0, s>>>(pm, P("fc.w"), P("fc.b"), logits, d->N, Cf, K);
+        LAUNCH_CHECK("fc_fwd");
+        softmax_ce_kernel<<<dim3(1), dim3(256), 0, s>>>(logits, labels, dlogits, loss_out, d->N, K);
+        LAUNCH_CHECK("softmax_ce");
+        // ================= backward =================
+        fc_bwd_w_kernel<<<dim3(cdiv(Cf, 256), K), dim3(256), 0, s>>>(dlogits, pm, G("fc.w"), G("fc.b"), d->N, Cf, K);
+        LAUNCH_CHECK("fc_bwd_w");
+        fc_bwd_x_kernel<<<dim3(cdiv(Cf, 256), d->N), dim3(256), 0, s>>>(dlogits, P("fc.w"), dpm, Cf, K);
+        LAUNCH_CHECK("fc_bwd_x");
+        const long ftotal = (long)d->N * rows_clip * Cf;
+        if (bf)
+            pool_mean_bwd_kernel<bf16_t><<<dim3(cdiv(ftotal, 256)), dim3(256), 0, s>>>(dpm, (bf16_t*)dbuf[0], rows_clip, Cf, ftotal);
+        else
+            pool_mean_bwd_kernel<float><<<dim3(cdiv(ftotal, 256)), dim3(256), 0, s>>>(dpm, (float*)dbuf[0], rows_clip, Cf, ftotal);
+        LAUNCH_CHECK("pool_mean_bwd");
+    }
+    int cur = 0;
+    for (int i = (int)blks.size() - 1; i >= 0; --i) {
+        Blk& b = blks[i];
+        Arena sc(scratch_base, scratch_cap);
+        TSM_TRY(block_bwd_impl(b.plan, b.in, b.out, dbuf[cur], dbuf[cur ^ 1], sc, dry, s));
+        note(sc);
+        cur ^= 1;
+    }
+    {   // stem backward: max-pool routing + ReLU mask, BatchNorm backward, weight gradient (no input gradient)
+        const int cv = 64 / VEC;
+        const long total = (long)F * H1 * H1 * cv;
+        if (!dry) {
+            if (bf)
+                stem_pool_bwd_kernel<bf16_t><<<dim3(cdiv(total, 256)), dim3(256), 0, s>>>((const bf16_t*)dbuf[cur], arg0, (const bf16_t*)y0, bn0.scale, bn0.shift, (bf16_t*)da0, H1, H1, Hp, Hp, cv, total);
+            else
+                stem_pool_bwd_kernel<float><<<dim3(cdiv(total, 256)), dim3(256), 0, s>>>((const float*)dbuf[cur], arg0, (const float*)y0, bn0.scale, bn0.shift, (float*)da0, H1, H1, Hp, Hp, cv, total);
+            LAUNCH_CHECK("stem_pool_bwd");
+        }
+        RUN(fill_zero(acc0, 128 * sizeof(double), s));
+        RUN(relu_bn_bwd_reduce(dtype, da0, nullptr, y0, stem.rows_out(), 64, bn0.mean, bn0.rstd, da0, acc0, nullptr,
+                               nullptr, nullptr, nullptr, s));
+        RUN(bn_bwd_apply(dtype, da0, y0, stem.rows_out(), 64, bn0.mean, bn0.rstd, P("bn1.g"), acc0, da0, G("bn1.g"),
+                         G("bn1.b"), s));
+        if (bf) {
+            RUN(fill_zero(dwp0, (size_t)64 * 49 * 8 * sizeof(float), s));
+            RUN(conv_mfma_wgrad(stem, (const bf16_t*)x0, (const bf16_t*)da0, dwp0, s));
+            RUN(unpack_wgrad(dwp0, G("conv1.w"), 64, 3, 49, 8, 0, s));
+        } else {
+            RUN(fill_zero(G("conv1.w"), (size_t)64 * 3 * 49 * sizeof(float), s));
+            RUN(conv_direct_wgrad(stem, dtype, x0, da0, G("conv1.w"), s));
+        }
+    }
+    // ================= update =================
+    if (update && !dry) {
+        SgdSegments seg;
+        seg.n = 0;
+        for (const TensorInfo& ti : table) {
+            if (seg.n == 0 || (bool)seg.decays[seg.n - 1] != ti.decays) {
+                if (seg.n >= 120) return fail(TSM_ERR_UNSUPPORTED, "%s: too many optimiser segments", who);
+                seg.start[seg.n] = (unsigned)ti.offset;
+                seg.decays[seg.n] = ti.decays ? 1 : 0;
+                ++seg.n;
+            }
+        }
+        sgd_kernel<<<dim3(cdiv(nparams, 256)), dim3(256), 0, s>>>(params, momentum, grads, nparams, seg, d->lr, d->momentum, d->weight_decay);
+        LAUNCH_CHECK("sgd");
+    }
+    if (need) *need = A.used + scratch_need;
+    return TSM_OK;
+}
+
+}  // namespace tsm
+
+using namespace tsm;
+
+extern "C" {
+
+int64_t tsm_resnet50_param_count(int num_classes) {
+    if (num_classes <= 0) return 0;
+    std::vector<TensorInfo> t = build_table(num_classes);
+    return t.back().offset + t.back().count();
+}
+
+int tsm_resnet50_num_tensors(void) { return (int)build_table(1).size(); }
+
+int tsm_resnet50_param_info(int num_classes, int index, char* name, int name_cap, int64_t* offset, int* ndim,
+                            int shape[4], int* decays) {
+    if (num_classes <= 0) return fail(TSM_ERR_SHAPE, "tsm_resnet50_param_info: num_classes must be positive");
+    std::vector<TensorInfo> t = build_table(num_classes);
+    if (index < 0 || index >= (int)t.size()) return fail(TSM_ERR_SHAPE, "tsm_resnet50_param_info: index %d out of range", index);
+    const TensorInfo& ti = t[index];
+    if (name && name_cap > 0) {
+        strncpy(name, ti.name.c_str(), (size_t)name_cap - 1);
+        name[name_cap - 1] = 0;
+    }
+    if (offset) *offset = ti.offset;
+    if (ndim) *ndim = ti.ndim;
+    if (shape) for (int i = 0; i < 4; ++i) shape[i] = ti.shape[i];
+    if (decays) *decays = ti.decays ? 1 : 0;
+    return TSM_OK;
+}
+
+int64_t tsm_resnet50_bn_state_count(void) {
+    int64_t n = 0;
+    for (const TensorInfo& ti : build_table(1))
+        if (ti.ndim == 1 && ti.name.size() > 2 && ti.name.compare(ti.name.size() - 2, 2, ".g") == 0) n += 2 * ti.shape[0];
+    return n;
+}
+
+size_t tsm_resnet50_workspace_bytes(const tsm_r50_desc* d) {
+    size_t need = 0;
+    if (r50_step(d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 1, nullptr, 0, true, nullptr,
+                 &need) != TSM_OK)
+        return 0;
+    return need;
+}
+
+int tsm_resnet50_step(const tsm_r50_desc* d, const void* clips, const int32_t* labels, float* params, float* momentum,
+                      float* bn_state, float* grads_out, float* loss_out, float* logits_out, int update, void* ws,
+                      size_t ws_bytes, void* stream) {
+    return r50_step(d, clips, labels, params, momentum, bn_state, grads_out, loss_out, logits_out, update, ws, ws_bytes,
+                    false, (hipStream_t)stream, nullptr);
+}
+
+}  // extern "C"
