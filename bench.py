@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Throughput of the TSM-ResNet-50 train step (forward + backward + SGD update) on one MI355X.
+
+One "step" = one call of tsm_resnet50_step on a batch of synthetic Kinetics-shaped clips
+(8 frames of 3x224x224, 400 classes) that is already resident in HBM.  Prints ONE JSON line with the
+throughput in clips/s, a roofline object for the kernel class that takes the most time (its time
+measured live with HIP events on the launch stream), and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
+STAGES = (("res2", 3, 64, 1), ("res3", 4, 128, 2), ("res4", 6, 256, 2), ("res5", 3, 512, 2))
+
+
+def conv_layers(F, size):
+    """(name, rows_in, Cin, rows_out, Cout, taps, has_dgrad) of the 53 convolutions for F frames."""
+    h = size // 2
+    layers = [("conv1", F * size * size, 3, F * h * h, 64, 49, False)]
+    h //= 2
+    cin = 64
+    for name, blocks, mid, stride in STAGES:
+        for b in range(blocks):
+            s = stride if b == 0 else 1
+            ho = h // s
+            pre = "%s.%d." % (name, b)
+            layers.append((pre + "c1", F * h * h, cin, F * h * h, mid, 1, True))
+            layers.append((pre + "c2", F * h * h, mid, F * ho * ho, mid, 9, True))
+            layers.append((pre + "c3", F * ho * ho, mid, F * ho * ho, 4 * mid, 1, True))
+            if b == 0:
+                layers.append((pre + "ds", F * h * h, cin, F * ho * ho, 4 * mid, 1, True))
+            cin, h = 4 * mid, ho
+    return layers
+
+
+def class_work(F, size):
+    """Algorithmic FLOPs per step of each MFMA kernel class (2 x multiply-accumulates of the layers it
+    runs) -- counted from the layer table, never from padded tiles."""
+    work = {}
+
+    def add(cls, macs):
+        work[cls] = work.get(cls, 0.0) + 2.0 * macs
+
+    for name, rin, cin, rout, cout, taps, has_dgrad in conv_layers(F, size):
+        macs = float(rout) * cout * cin * taps
+        add("igemm_fwd_128x64" if cout <= 64 else "igemm_fwd_128x128", macs)
+        if has_dgrad:
+            add("igemm_dgrad_128x64" if cin <= 64 else "igemm_dgrad_128x128", macs)
+        kk = taps * (8 if name == "conv1" else cin)
+        add("wgrad_128x128" if (cout > 64 and kk > 64) else "wgrad_64x64", macs)
+    return work
+
+
+def total_flops_per_clip(T, size):
+    return sum(class_work(T, size).values())
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--clips", type=int, default=64, help="clips per step: 64 = configs[3] (throughput run), 8 = configs[2]")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); --gpus %d is not supported"
+                 % args.gpus)
+
+    import torch
+    from paper_1910_00932_amd import binding as B
+    from paper_1910_00932_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    N, T, S, K = args.clips, 8, 224, 400
+    lr = 0.00125 * N / 8.0          # linear scaling rule (paper section 4.1)
+    table = B.tsm_resnet50_param_table(K)
+    flat = I.init_params([(n, s) for n, _, s, _ in table], 1)
+    d = B.R50Desc(N=N, T=T, size=S, num_classes=K, fold_div=8, lr=lr, momentum=0.9, weight_decay=1e-4, bn_eps=1e-5,
+                  bn_momentum=0.1, dtype=B.TSM_BF16)
+    ws_bytes = B.tsm_resnet50_workspace_bytes(d)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    # inputs are generated once and live in HBM before the timed region
+    rng = np.random.default_rng(0)
+    clips = torch.from_numpy(I.clips(min(N, 8), T, S, 0, "bf16")).to(torch.bfloat16)
+    clips = clips.repeat((N + clips.shape[0] - 1) // clips.shape[0], 1, 1, 1, 1)[:N].contiguous().cuda()
+    labels = torch.from_numpy(I.labels(N, K)).cuda()
+    params = torch.from_numpy(flat).cuda()
+    mom = torch.zeros_like(params)
+    bn_state = torch.zeros(B.tsm_resnet50_bn_state_count(), dtype=torch.float32, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        B.tsm_resnet50_step(d, clips, labels, params, mom, bn_state, None, loss, None, 1, ws, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    first_loss = None
+    t0 = time.perf_counter()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    final_loss = float(loss.item())
+    if not np.isfinite(final_loss):
+        sys.exit("bench.py: loss is not finite (%r)" % final_loss)
+
+    # per-class time of one more step, HIP events on the launch stream after every launch
+    B.tsm_profile_begin(stream)
+    step()
+    prof = B.tsm_profile_end()
+    work = class_work(N * T, S)
+    dom = max(prof, key=lambda k: prof[k][1])
+    n_launch, dom_ms = prof[dom]
+    if dom in work:
+        achieved = work[dom] / (dom_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "kernel": dom, "launches_per_step": n_launch,
+                "avg_launch_ms": dom_ms / n_launch, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None}
+    else:
+        roof = {"bound": "hbm", "kernel": dom, "launches_per_step": n_launch, "avg_launch_ms": dom_ms / n_launch,
+                "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": None, "traffic": None}
+    prof_total = sum(v[1] for v in prof.values())
+    classes = {k: {"launches": v[0], "ms": round(v[1], 4),
+                   "tflops": round(work[k] / (v[1] * 1e-3) / 1e12, 1) if k in work else None}
+               for k, v in sorted(prof.items(), key=lambda kv: -kv[1][1])}
+
+    flops_step = sum(work.values())
+    out = {
+        "metric": "TSM-ResNet-50 train clips/sec (8x224^2, fwd+bwd) at 1 GPU; % bf16 MFMA peak",
+        "value": N / (ms_per_step * 1e-3), "unit": "clips/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[%d]: full TSM-ResNet-50 train step, %d clips x 8 frames x 3x224x224, 400 classes, "
+                               "fold_div 8, SGD momentum 0.9" % (3 if N == 64 else 2, N),
+                   "clips_per_step": N, "frames": T, "size": S, "num_classes": K},
+        "step_tflops": flops_step / (ms_per_step * 1e-3) / 1e12,
+        "pct_bf16_mfma_peak": 100.0 * flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "loss_after": final_loss, "wall_s": wall,
+        "roofline": roof, "kernel_classes": classes, "profiled_step_ms": prof_total,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import tsm_oracle as O
+        P = O.unflatten_params(flat.astype(np.float64))
+        V = {k: np.zeros_like(v) for k, v in P.items()}
+        c1 = I.clips(1, T, S, 0, "bf16").astype(np.float64)
+        t0 = time.perf_counter()
+        O.resnet50_step(P, V, c1, I.labels(1, K), lr)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 1.0 / dt, "unit": "clips/s", "cores": O.max_threads(), "kind": "oracle",
+                               "sample": "1 clip (8x3x224x224): one full fwd+bwd+update of the fp64 oracle, %.1f s" % dt}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -72,6 +72,15 @@ typedef enum { TSM_NTCHW = 0, TSM_NTHWC = 1 } tsm_layout;
 /* Host string for the last error on this thread (never NULL). */
 const char* tsm_last_error(void);
 
+/* Measurement aid, not part of the method: between tsm_profile_begin(stream) and
+ * tsm_profile_end() a HIP event is recorded on `stream` after every kernel this
+ * thread launches through the library; tsm_profile_end synchronises the stream
+ * and writes one line per kernel class, "name launches total_ms", into the host
+ * buffer `report` (NUL-terminated, truncated to report_cap).  The time booked on
+ * a launch runs from the end of the previous launch to its own end. */
+int tsm_profile_begin(void* stream);
+int tsm_profile_end(char* report, size_t report_cap);
+
 /* ------------------------------------------------------------------------
  * Temporal shift, stand-alone (section 2, Fig. 1: zero FLOPs, zero parameters).
  * y = S(x) / gx = S^T(gy); a pure copy, bit-exact for any 2- or 4-byte type.

@@ -20,7 +20,7 @@ STATUS = {0: "TSM_OK", -1: "TSM_ERR_NULLPTR", -2: "TSM_ERR_SHAPE", -3: "TSM_ERR_
           -5: "TSM_ERR_LAYOUT", -6: "TSM_ERR_WORKSPACE", -7: "TSM_ERR_ALIGN", -8: "TSM_ERR_LAUNCH",
           -9: "TSM_ERR_UNSUPPORTED"}
 
-EXPORTS = ["tsm_last_error", "tsm_shift_fwd", "tsm_shift_bwd", "tsm_conv_workspace_bytes", "tsm_conv_fwd",
+EXPORTS = ["tsm_last_error", "tsm_profile_begin", "tsm_profile_end", "tsm_shift_fwd", "tsm_shift_bwd", "tsm_conv_workspace_bytes", "tsm_conv_fwd",
            "tsm_conv_dgrad", "tsm_conv_wgrad", "tsm_block_saved_bytes", "tsm_block_workspace_bytes",
            "tsm_block_fwd", "tsm_block_bwd", "tsm_resnet50_param_count", "tsm_resnet50_num_tensors",
            "tsm_resnet50_param_info", "tsm_resnet50_bn_state_count", "tsm_resnet50_workspace_bytes",
@@ -81,6 +81,8 @@ def lib():
 
         vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
         sig("tsm_last_error", ctypes.c_char_p, [])
+        sig("tsm_profile_begin", ci, [vp])
+        sig("tsm_profile_end", ci, [ctypes.c_char_p, sz])
         for n in ("tsm_conv_workspace_bytes", "tsm_block_saved_bytes", "tsm_block_workspace_bytes",
                   "tsm_resnet50_workspace_bytes"):
             sig(n, sz, [vp])
@@ -130,6 +132,21 @@ def _ws(ws):
 
 def tsm_last_error():
     return lib().tsm_last_error().decode()
+
+
+def tsm_profile_begin(stream=None):
+    _check(lib().tsm_profile_begin(_stream(stream)))
+
+
+def tsm_profile_end():
+    """Returns {kernel class: (launches, total_ms)}."""
+    buf = ctypes.create_string_buffer(1 << 16)
+    _check(lib().tsm_profile_end(buf, len(buf)))
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, n, ms = line.rsplit(" ", 2)
+        out[name] = (int(n), float(ms))
+    return out
 
 
 def tsm_shift_fwd(x, y, N, T, C, H, W, fold_div, dtype, layout, stream=None):

@@ -38,19 +38,24 @@ static int make_convp(const tsm_conv_desc* d, ConvP* p, const char* who) {
 static inline bool use_mfma(const ConvP& p, int dtype) { return dtype == TSM_BF16 && mfma_conv_supported(p); }
 
 // ---- internal conv runners (channels-innermost) -----------------------------------------
-// stats_acc: zeroed fp64 [2*Cout] or null.
+// Rows of the statistics partial buffer run_conv_fwd fills for this convolution.
+int conv_stats_blocks(const ConvP& p, int dtype) {
+    return use_mfma(p, dtype) ? conv_mfma_fwd_blocks(p) : red_blocks(p.rows_out(), p.Cout, dtype);
+}
+
+// stats_partial: fp32 [conv_stats_blocks(p, dtype)][2*Cout] or null.
 int run_conv_fwd(const ConvP& p, int dtype, const void* x, const void* w, const bf16_t* wp, void* y,
-                 double* stats_acc, Arena& ws, bool dry, hipStream_t s) {
+                 float* stats_partial, Arena& ws, bool dry, hipStream_t s) {
     if (use_mfma(p, dtype)) {
         if (!wp) {
             bf16_t* pk = ws.take_n<bf16_t>((size_t)p.Cout * p.K());
             RUN(pack_weights_fwd(dtype, w, pk, p.Cout, p.Cin, p.taps(), p.Cin, s));
             wp = pk;
         }
-        RUN(conv_mfma_fwd(p, (const bf16_t*)x, wp, (bf16_t*)y, stats_acc, s));
+        RUN(conv_mfma_fwd(p, (const bf16_t*)x, wp, (bf16_t*)y, stats_partial, s));
     } else {
         RUN(conv_direct_fwd(p, dtype, x, w, y, s));
-        if (stats_acc) RUN(channel_stats(dtype, y, p.rows_out(), p.Cout, stats_acc, s));
+        if (stats_partial) RUN(channel_stats(dtype, y, p.rows_out(), p.Cout, stats_partial, s));
     }
     return TSM_OK;
 }
@@ -72,16 +77,21 @@ int run_conv_dgrad(const ConvP& p, int dtype, const void* dy, const void* w, con
 
 int run_conv_wgrad(const ConvP& p, int dtype, const void* x, const void* dy, float* dw, int accumulate, Arena& ws,
                    bool dry, hipStream_t s) {
+    // all kernels add with atomics; "accumulate" skips the zero fill of dw
     const size_t n = (size_t)p.Cout * p.K();
-    if (use_mfma(p, dtype)) {
+    if (use_mfma(p, dtype) && p.taps() > 1) {
+        // several taps: accumulate in the packed order (contiguous atomics), then permute into dw
         float* dwp = ws.take_n<float>(n);
         RUN(fill_zero(dwp, n * sizeof(float), s));
-        RUN(conv_mfma_wgrad(p, (const bf16_t*)x, (const bf16_t*)dy, dwp, s));
+        RUN(conv_mfma_wgrad(p, (const bf16_t*)x, (const bf16_t*)dy, dwp, p.Cin, true, s));
         RUN(unpack_wgrad(dwp, dw, p.Cout, p.Cin, p.taps(), p.Cin, accumulate, s));
-    } else {
-        if (!accumulate) RUN(fill_zero(dw, n * sizeof(float), s));
-        RUN(conv_direct_wgrad(p, dtype, x, dy, dw, s));
+        return TSM_OK;
     }
+    if (!accumulate) RUN(fill_zero(dw, n * sizeof(float), s));
+    if (use_mfma(p, dtype))
+        RUN(conv_mfma_wgrad(p, (const bf16_t*)x, (const bf16_t*)dy, dw, p.Cin, false, s));
+    else
+        RUN(conv_direct_wgrad(p, dtype, x, dy, dw, s));
     return TSM_OK;
 }
 
@@ -119,13 +129,10 @@ static int conv_entry(int which, const tsm_conv_desc* d, const void* a0, const v
             RUN(transpose_frames(a0, xt, p.F, p.Cin, p.H * p.W, es, s));
             x = xt;
         }
-        double* acc = nullptr;
-        if (ch_sum || dry) {
-            acc = ws.take_n<double>(2 * (size_t)p.Cout);
-            if (ch_sum) RUN(fill_zero(acc, 2 * (size_t)p.Cout * sizeof(double), s));
-        }
-        TSM_TRY(run_conv_fwd(p, d->dtype, x, a1, nullptr, y, ch_sum ? acc : nullptr, ws, dry, s));
-        if (ch_sum) RUN(stats_to_float(acc, p.Cout, ch_sum, ch_sumsq, s));
+        const int nb = conv_stats_blocks(p, d->dtype);
+        float* part = (ch_sum || dry) ? ws.take_n<float>((size_t)nb * 2 * p.Cout) : nullptr;
+        TSM_TRY(run_conv_fwd(p, d->dtype, x, a1, nullptr, y, ch_sum ? part : nullptr, ws, dry, s));
+        if (ch_sum) RUN(stats_to_float(part, nb, p.Cout, ch_sum, ch_sumsq, s));
         if (tr) RUN(transpose_frames(y, out, p.F, p.Ho * p.Wo, p.Cout, es, s));
     } else if (which == CONV_DGRAD) {
         const void* dy = a0;
@@ -187,10 +194,10 @@ int block_fwd_impl(BlockPlan& b, const void* x, void* out, Arena& ws, bool dry, 
     const void* cur = x;
     for (int i = 0; i < b.nst; ++i) {
         StageDef& st = b.st[i];
-        double* acc = ws.take_n<double>(2 * (size_t)st.p.Cout);
-        RUN(fill_zero(acc, 2 * (size_t)st.p.Cout * sizeof(double), s));
-        TSM_TRY(run_conv_fwd(st.p, b.dtype, cur, st.w, st.wp, b.y[i], acc, ws, dry, s));
-        RUN(bn_finalize(acc, st.p.rows_out(), st.p.Cout, st.g, st.b, b.eps, b.bn[i], st.run_mean, st.run_var,
+        const int nb = conv_stats_blocks(st.p, b.dtype);
+        float* part = ws.take_n<float>((size_t)nb * 2 * st.p.Cout);
+        TSM_TRY(run_conv_fwd(st.p, b.dtype, cur, st.w, st.wp, b.y[i], part, ws, dry, s));
+        RUN(bn_finalize(part, nb, st.p.rows_out(), st.p.Cout, st.g, st.b, b.eps, b.bn[i], st.run_mean, st.run_var,
                         b.bn_momentum, s));
         if (i + 1 < b.nst) {
             RUN(bn_relu_apply(b.dtype, b.y[i], st.p.rows_out(), st.p.Cout, b.bn[i].scale, b.bn[i].shift, b.z[i], s));
@@ -199,10 +206,10 @@ int block_fwd_impl(BlockPlan& b, const void* x, void* out, Arena& ws, bool dry, 
     }
     if (b.proj) {
         StageDef& st = b.ds;
-        double* acc = ws.take_n<double>(2 * (size_t)st.p.Cout);
-        RUN(fill_zero(acc, 2 * (size_t)st.p.Cout * sizeof(double), s));
-        TSM_TRY(run_conv_fwd(st.p, b.dtype, x, st.w, st.wp, b.yd, acc, ws, dry, s));
-        RUN(bn_finalize(acc, st.p.rows_out(), st.p.Cout, st.g, st.b, b.eps, b.bnd, st.run_mean, st.run_var,
+        const int nb = conv_stats_blocks(st.p, b.dtype);
+        float* part = ws.take_n<float>((size_t)nb * 2 * st.p.Cout);
+        TSM_TRY(run_conv_fwd(st.p, b.dtype, x, st.w, st.wp, b.yd, part, ws, dry, s));
+        RUN(bn_finalize(part, nb, st.p.rows_out(), st.p.Cout, st.g, st.b, b.eps, b.bnd, st.run_mean, st.run_var,
                         b.bn_momentum, s));
     }
     const int L = b.nst - 1;
@@ -220,38 +227,43 @@ int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dou
     const size_t out_bytes = (size_t)pl.rows_out() * pl.Cout * es;
     void* dzL = ws.take(out_bytes);
     void* dyL = ws.take(out_bytes);
-    double* accL = ws.take_n<double>(2 * (size_t)pl.Cout);
-    double* accd = ws.take_n<double>(2 * (size_t)pl.Cout);
-    RUN(fill_zero(accL, 2 * (size_t)pl.Cout * sizeof(double), s));
-    if (b.proj) RUN(fill_zero(accd, 2 * (size_t)pl.Cout * sizeof(double), s));
-    RUN(relu_bn_bwd_reduce(b.dtype, dout, out, b.y[L], pl.rows_out(), pl.Cout, b.bn[L].mean, b.bn[L].rstd, dzL, accL,
+    const int nbL = red_blocks(pl.rows_out(), pl.Cout, b.dtype);
+    float* partL = ws.take_n<float>((size_t)nbL * 2 * pl.Cout);
+    float* partd = ws.take_n<float>((size_t)nbL * 2 * pl.Cout);
+    float* coefL = ws.take_n<float>(3 * (size_t)pl.Cout);
+    const int acc_flag = b.grads_prezeroed ? 1 : 0;
+    RUN(relu_bn_bwd_reduce(b.dtype, dout, out, b.y[L], pl.rows_out(), pl.Cout, b.bn[L].mean, b.bn[L].rstd, dzL, partL,
                            b.proj ? b.yd : nullptr, b.proj ? b.bnd.mean : nullptr, b.proj ? b.bnd.rstd : nullptr,
-                           b.proj ? accd : nullptr, s));
-    RUN(bn_bwd_apply(b.dtype, dzL, b.y[L], pl.rows_out(), pl.Cout, b.bn[L].mean, b.bn[L].rstd, b.st[L].g, accL, dyL,
-                     b.st[L].dg, b.st[L].db, s));
+                           b.proj ? partd : nullptr, s));
+    RUN(bn_bwd_coeffs(partL, nbL, pl.rows_out(), pl.Cout, b.bn[L].mean, b.bn[L].rstd, b.st[L].g, coefL, b.st[L].dg,
+                      b.st[L].db, s));
+    RUN(bn_bwd_apply(b.dtype, dzL, b.y[L], pl.rows_out(), pl.Cout, coefL, dyL, s));
     void* g = dyL;
     for (int i = L; i >= 1; --i) {
         StageDef& st = b.st[i];
         const ConvP& pp = b.st[i - 1].p;  // producer of this stage's input
-        TSM_TRY(run_conv_wgrad(st.p, b.dtype, b.z[i - 1], g, st.dw, 0, ws, dry, s));
+        TSM_TRY(run_conv_wgrad(st.p, b.dtype, b.z[i - 1], g, st.dw, acc_flag, ws, dry, s));
         void* dzin = ws.take((size_t)pp.rows_out() * pp.Cout * es);
         TSM_TRY(run_conv_dgrad(st.p, b.dtype, g, st.w, st.wd, dzin, nullptr, ws, dry, s));
-        double* acc = ws.take_n<double>(2 * (size_t)pp.Cout);
-        RUN(fill_zero(acc, 2 * (size_t)pp.Cout * sizeof(double), s));
+        const int nb = red_blocks(pp.rows_out(), pp.Cout, b.dtype);
+        float* part = ws.take_n<float>((size_t)nb * 2 * pp.Cout);
+        float* coef = ws.take_n<float>(3 * (size_t)pp.Cout);
         RUN(relu_bn_bwd_reduce(b.dtype, dzin, b.z[i - 1], b.y[i - 1], pp.rows_out(), pp.Cout, b.bn[i - 1].mean,
-                               b.bn[i - 1].rstd, dzin, acc, nullptr, nullptr, nullptr, nullptr, s));
-        RUN(bn_bwd_apply(b.dtype, dzin, b.y[i - 1], pp.rows_out(), pp.Cout, b.bn[i - 1].mean, b.bn[i - 1].rstd,
-                         b.st[i - 1].g, acc, dzin, b.st[i - 1].dg, b.st[i - 1].db, s));
+                               b.bn[i - 1].rstd, dzin, part, nullptr, nullptr, nullptr, nullptr, s));
+        RUN(bn_bwd_coeffs(part, nb, pp.rows_out(), pp.Cout, b.bn[i - 1].mean, b.bn[i - 1].rstd, b.st[i - 1].g, coef,
+                          b.st[i - 1].dg, b.st[i - 1].db, s));
+        RUN(bn_bwd_apply(b.dtype, dzin, b.y[i - 1], pp.rows_out(), pp.Cout, coef, dzin, s));
         g = dzin;
     }
-    TSM_TRY(run_conv_wgrad(b.st[0].p, b.dtype, x, g, b.st[0].dw, 0, ws, dry, s));
+    TSM_TRY(run_conv_wgrad(b.st[0].p, b.dtype, x, g, b.st[0].dw, acc_flag, ws, dry, s));
     const void* addend = dzL;
     if (b.proj) {
         StageDef& st = b.ds;
         void* dyd = ws.take(out_bytes);
-        RUN(bn_bwd_apply(b.dtype, dzL, b.yd, pl.rows_out(), pl.Cout, b.bnd.mean, b.bnd.rstd, st.g, accd, dyd, st.dg,
-                         st.db, s));
-        TSM_TRY(run_conv_wgrad(st.p, b.dtype, x, dyd, st.dw, 0, ws, dry, s));
+        float* coefd = ws.take_n<float>(3 * (size_t)pl.Cout);
+        RUN(bn_bwd_coeffs(partd, nbL, pl.rows_out(), pl.Cout, b.bnd.mean, b.bnd.rstd, st.g, coefd, st.dg, st.db, s));
+        RUN(bn_bwd_apply(b.dtype, dzL, b.yd, pl.rows_out(), pl.Cout, coefd, dyd, s));
+        TSM_TRY(run_conv_wgrad(st.p, b.dtype, x, dyd, st.dw, acc_flag, ws, dry, s));
         void* dsc = ws.take((size_t)st.p.rows_in() * st.p.Cin * es);
         TSM_TRY(run_conv_dgrad(st.p, b.dtype, dyd, st.w, st.wd, dsc, nullptr, ws, dry, s));
         addend = dsc;

@@ -22,6 +22,7 @@ struct BlockPlan {
     StageDef ds;          // projection shortcut
     int dtype;
     float eps, bn_momentum;
+    bool grads_prezeroed;  // the caller zeroed every dw: weight gradients are added without a fill
     // saved-for-backward buffers (caller-owned memory)
     void* y[3];           // convolution outputs
     void* z[2];           // ReLU(BN(y)) of all but the last stage
@@ -30,8 +31,9 @@ struct BlockPlan {
     void *x_copy, *out_copy;  // channels-innermost copies when the caller's order is NTCHW
 };
 
+int conv_stats_blocks(const ConvP& p, int dtype);
 int run_conv_fwd(const ConvP& p, int dtype, const void* x, const void* w, const bf16_t* wp, void* y,
-                 double* stats_acc, Arena& ws, bool dry, hipStream_t s);
+                 float* stats_partial, Arena& ws, bool dry, hipStream_t s);
 int run_conv_dgrad(const ConvP& p, int dtype, const void* dy, const void* w, const bf16_t* wd, void* dx,
                    const void* addend, Arena& ws, bool dry, hipStream_t s);
 int run_conv_wgrad(const ConvP& p, int dtype, const void* x, const void* dy, float* dw, int accumulate, Arena& ws,

@@ -30,7 +30,7 @@ struct IgemmArgs {
     const bf16_t* wp;      // packed weights [N][K]
     bf16_t* dst;           // y (fwd) or dx (dgrad)
     const bf16_t* addend;  // dgrad only: added to dx (nullable)
-    double* stats;         // fwd only: per-channel sum / sum of squares (nullable)
+    float* stats;          // fwd only: per-block partial sums, [gridDim.x][2*Cd] (nullable)
     int F, T;
     int Hs, Ws, Cs;        // source frame
     int Hd, Wd, Cd;        // destination frame; Cd = GEMM N
@@ -255,12 +255,10 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
         __syncthreads();
     }
 
-    if (do_stats) {
+    if (do_stats) {   // every block publishes its row, zeros included: the consumer adds all rows up
         __syncthreads();
-        for (int c = tid; c < 2 * a.Cd; c += 256) {
-            const float v = s_sum[c];
-            if (v != 0.f) atomicAdd(a.stats + c, (double)v);
-        }
+        float* prow = a.stats + (size_t)blockIdx.x * 2 * a.Cd;
+        for (int c = tid; c < 2 * a.Cd; c += 256) prow[c] = s_sum[c];
     }
 }
 
@@ -285,13 +283,22 @@ bool mfma_conv_supported(const ConvP& p) {
     return true;
 }
 
+// Persistent grid: two blocks per CU (a multiple of 8 so that a block stays on one XCD), capped by
+// the number of tile ids, which enumerate (group of 8 M tiles) x N tiles x (xcd).
+static int igemm_grid(long M, int Cd, int BM, int BN) {
+    const int mtiles = (int)((M + BM - 1) / BM), ntiles = (Cd + BN - 1) / BN;
+    const int total = ((mtiles + 7) / 8) * 8 * ntiles;
+    int grid = 2 * num_cu();
+    grid = (grid / 8) * 8;
+    if (grid > total) grid = total;
+    if (grid < 1) grid = 1;
+    return grid;
+}
+
 template <int BM, int BN, int WM, int WN, bool DGRAD>
 static int launch_igemm(IgemmArgs& a, hipStream_t s) {
     a.mtiles = (int)((a.M + BM - 1) / BM);
     a.ntiles = (a.Cd + BN - 1) / BN;
-    // tile ids enumerate (group of 8 M tiles) x N tiles x (xcd): pad M tiles to a multiple of 8
-    const int mgroups = (a.mtiles + 7) / 8;
-    const int total = mgroups * 8 * a.ntiles;
     size_t smem = (size_t)2 * (BM + BN) * LDK * sizeof(bf16_t) + (size_t)2 * a.Cd * sizeof(float);
     auto kern = igemm_kernel<BM, BN, WM, WN, DGRAD>;
     static bool configured = false;
@@ -300,12 +307,11 @@ static int launch_igemm(IgemmArgs& a, hipStream_t s) {
             return fail(TSM_ERR_LAUNCH, "igemm: cannot raise dynamic LDS limit");
         configured = true;
     }
-    int grid = 2 * num_cu();
-    grid = (grid / 8) * 8;
-    if (grid > total) grid = total;
-    if (grid < 1) grid = 1;
+    const int grid = igemm_grid(a.M, a.Cd, BM, BN);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, a);
-    return check_launch(DGRAD ? "conv_mfma_dgrad" : "conv_mfma_fwd");
+    // class names carry the tile shape so that they map one-to-one onto kernel symbols
+    return check_launch(DGRAD ? (BN == 64 ? "igemm_dgrad_128x64" : "igemm_dgrad_128x128")
+                              : (BN == 64 ? "igemm_fwd_128x64" : "igemm_fwd_128x128"));
 }
 
 template <bool DGRAD>
@@ -315,7 +321,9 @@ static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     return launch_igemm<128, 128, 2, 2, DGRAD>(a, s);
 }
 
-int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, double* stats, hipStream_t s) {
+int conv_mfma_fwd_blocks(const ConvP& p) { return igemm_grid(p.rows_out(), p.Cout, 128, p.Cout <= 64 ? 64 : 128); }
+
+int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, float* stats, hipStream_t s) {
     IgemmArgs a;
     a.src = x; a.wp = wp; a.dst = y; a.addend = nullptr; a.stats = stats;
     a.F = p.F; a.T = p.T;
@@ -347,15 +355,17 @@ int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* 
 // ---------------------------------------------------------------------------------
 // Weight gradient, D[Cout x K] = dy^T [Cout x pixels] * gathered x [pixels x K] with
 // K = taps * Cin enumerated tap-major (the packed-weight order).  Per block: a
-// [BCO x BCI] tile of D reduced over a chunk of output pixels, added to dwp with
-// fp32 atomics.  Both operands are needed with the pixel index contiguous, so the
+// [BCO x BCI] tile of D reduced over a chunk of output pixels, added with fp32
+// atomics to dw in the ABI order [Cout][Cin][taps].  Both operands are needed with the pixel index contiguous, so the
 // 16-byte global rows ([pixel][channel]) are transposed on their way into LDS:
 // each thread pairs two consecutive pixels of eight channels into eight 32-bit
 // LDS writes.
 struct WgradArgs {
     const bf16_t* x;
     const bf16_t* dy;
-    float* dwp;            // [Cout][taps][Cin]
+    float* dw;             // element (co, ci, tap) at co*so + ci*si + tap*st
+    long so;
+    int si, st, cin_real;
     int F, T;
     int H, W, Cin;
     int Ho, Wo, Cout;
@@ -526,18 +536,26 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs a) {
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
                 const int col = j0 + wn * TN + j * 32 + (lane & 31);
+                const int tap = col / a.Cin, ci = col - tap * a.Cin;
+                if (col >= a.K || ci >= a.cin_real) continue;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int co = co0 + wm * TM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    if (co < a.Cout && col < a.K) atomicAdd(a.dwp + (long)co * a.K + col, acc[i][j][r]);
+                    if (co < a.Cout) atomicAdd(a.dw + (long)co * a.so + (long)ci * a.si + (long)tap * a.st, acc[i][j][r]);
                 }
             }
     }
 }
 
-int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dwp, hipStream_t s) {
+int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, bool packed,
+                    hipStream_t s) {
     WgradArgs a;
-    a.x = x; a.dy = dy; a.dwp = dwp;
+    a.x = x; a.dy = dy; a.dw = dw; a.cin_real = cin_real;
+    if (packed) {   // [Cout][taps][p.Cin]: consecutive lanes (channels) hit consecutive addresses
+        a.so = (long)p.taps() * p.Cin; a.si = 1; a.st = p.Cin;
+    } else {        // ABI order [Cout][cin_real][taps]
+        a.so = (long)cin_real * p.taps(); a.si = p.taps(); a.st = 1;
+    }
     a.F = p.F; a.T = p.T; a.H = p.H; a.W = p.W; a.Cin = p.Cin;
     a.Ho = p.Ho; a.Wo = p.Wo; a.Cout = p.Cout;
     a.KT = p.KT; a.KH = p.KH; a.KW = p.KW; a.stride = p.stride; a.pad = p.pad;
@@ -561,7 +579,7 @@ int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw
         wgrad_kernel<128, 128><<<grid, dim3(256), 0, s>>>(a);
     else
         wgrad_kernel<64, 64><<<grid, dim3(256), 0, s>>>(a);
-    return check_launch("conv_mfma_wgrad");
+    return check_launch(big ? "wgrad_128x128" : "wgrad_64x64");
 }
 
 }  // namespace tsm

@@ -25,31 +25,46 @@ int fill_zero(void* p, size_t bytes, hipStream_t s) {
     return check_launch("fill_zero");
 }
 
-// ---- row-reduction launch shape ------------------------------------------------------
-// Threads (tx, ty): tx walks channel vectors, ty walks rows; every thread keeps
-// one channel vector for its whole life, so partial sums stay in registers.
-struct RedShape {
+// ---- launch shape shared by every per-channel kernel ---------------------------------------
+// Threads (tx, ty): tx walks channel vectors, ty walks rows; every thread keeps one
+// channel vector for its whole life, so per-channel coefficients and partial sums
+// stay in registers and consecutive lanes touch consecutive 16-byte pieces of a row.
+struct RowShape {
     dim3 grid, block;
     int cv;
 };
 
-static RedShape red_shape(long rows, int C, int V) {
-    RedShape r;
+static RowShape row_shape(long rows, int C, int V, int rows_per_thread, int max_gx) {
+    RowShape r;
     r.cv = C / V;
     int bx = r.cv < 256 ? r.cv : 256;
     int by = 256 / bx;
     if (by < 1) by = 1;
-    long gx = (rows + (long)by * 8 - 1) / ((long)by * 8);  // >= 8 rows per thread
+    long gx = (rows + (long)by * rows_per_thread - 1) / ((long)by * rows_per_thread);
     if (gx < 1) gx = 1;
-    if (gx > 2048) gx = 2048;
+    if (gx > max_gx) gx = max_gx;
     r.block = dim3(bx, by);
     r.grid = dim3((unsigned)gx, (unsigned)((r.cv + bx - 1) / bx));
     return r;
 }
 
-// Sums the per-thread partials a[V], b[V] over ty and adds them into acc[c], acc[C+c].
+static inline int vec_of(int dtype, int C) {
+    const int v = dtype == TSM_F32 ? 4 : 8;
+    return C % v == 0 ? v : 1;
+}
+
+static constexpr int RED_ROWS_PER_THREAD = 8, RED_MAX_GX = 512;
+static constexpr int EW_ROWS_PER_THREAD = 2, EW_MAX_GX = 8192;
+
+// Number of per-block partial rows the reduction kernels write for this tensor.
+int red_blocks(long rows, int C, int dtype) {
+    return (int)row_shape(rows, C, vec_of(dtype, C), RED_ROWS_PER_THREAD, RED_MAX_GX).grid.x;
+}
+
+// Sums the per-thread partials a[V], b[V] over ty and stores them into this block's
+// row of the partial buffer: prow[c] and prow[C + c].  No atomics: deterministic.
 template <int V>
-__device__ __forceinline__ void block_reduce_2(float* a, float* b, int cvi, int cv, int C, double* acc) {
+__device__ __forceinline__ void block_partial_2(const float* a, const float* b, int cvi, int cv, int C, float* prow) {
     __shared__ float red[2][256 * V];
     const int tx = threadIdx.x, ty = threadIdx.y, bx = blockDim.x, by = blockDim.y;
 #pragma unroll
@@ -66,8 +81,8 @@ __device__ __forceinline__ void block_reduce_2(float* a, float* b, int cvi, int 
                 sa += red[0][(r * bx + tx) * V + j];
                 sb += red[1][(r * bx + tx) * V + j];
             }
-            atomicAdd(acc + cvi * V + j, (double)sa);
-            atomicAdd(acc + C + cvi * V + j, (double)sb);
+            prow[cvi * V + j] = sa;
+            prow[C + cvi * V + j] = sb;
         }
     }
 }
@@ -75,7 +90,7 @@ __device__ __forceinline__ void block_reduce_2(float* a, float* b, int cvi, int 
 // ---- per-channel sum and sum of squares -------------------------------------------------
 template <typename T, int V>
 __global__ void __launch_bounds__(256) channel_stats_kernel(const T* __restrict__ y, long rows, int C, int cv,
-                                                            double* __restrict__ acc) {
+                                                            float* __restrict__ partial) {
     const int cvi = blockIdx.y * blockDim.x + threadIdx.x;
     float s1[V], s2[V];
 #pragma unroll
@@ -91,36 +106,65 @@ __global__ void __launch_bounds__(256) channel_stats_kernel(const T* __restrict_
             }
         }
     }
-    block_reduce_2<V>(s1, s2, cvi, cv, C, acc);
+    block_partial_2<V>(s1, s2, cvi, cv, C, partial + (size_t)blockIdx.x * 2 * C);
 }
 
-template <typename T>
-static int channel_stats_t(const T* y, long rows, int C, double* acc, hipStream_t s) {
-    constexpr int VEC = Elem<T>::VEC;
-    if (C % VEC == 0) {
-        RedShape r = red_shape(rows, C, VEC);
-        channel_stats_kernel<T, VEC><<<r.grid, r.block, 0, s>>>(y, rows, C, r.cv, acc);
-    } else {
-        RedShape r = red_shape(rows, C, 1);
-        channel_stats_kernel<T, 1><<<r.grid, r.block, 0, s>>>(y, rows, C, r.cv, acc);
-    }
+template <typename T, int V>
+static int channel_stats_tv(const T* y, long rows, int C, float* partial, hipStream_t s) {
+    RowShape r = row_shape(rows, C, V, RED_ROWS_PER_THREAD, RED_MAX_GX);
+    channel_stats_kernel<T, V><<<r.grid, r.block, 0, s>>>(y, rows, C, r.cv, partial);
     return check_launch("channel_stats");
 }
 
-int channel_stats(int dtype, const void* y, long rows, int C, double* acc, hipStream_t s) {
-    if (rows == 0) return TSM_OK;
-    return dtype == TSM_F32 ? channel_stats_t<float>((const float*)y, rows, C, acc, s)
-                            : channel_stats_t<bf16_t>((const bf16_t*)y, rows, C, acc, s);
+// partial: fp32 [red_blocks(rows, C, dtype)][2*C]
+int channel_stats(int dtype, const void* y, long rows, int C, float* partial, hipStream_t s) {
+    const int v = vec_of(dtype, C);
+    if (dtype == TSM_F32)
+        return v == 4 ? channel_stats_tv<float, 4>((const float*)y, rows, C, partial, s)
+                      : channel_stats_tv<float, 1>((const float*)y, rows, C, partial, s);
+    return v == 8 ? channel_stats_tv<bf16_t, 8>((const bf16_t*)y, rows, C, partial, s)
+                  : channel_stats_tv<bf16_t, 1>((const bf16_t*)y, rows, C, partial, s);
 }
 
-// ---- statistics -> per-channel vectors ------------------------------------------------------
-__global__ void bn_finalize_kernel(const double* __restrict__ acc, double inv_m, double unbias, int C,
+// Adds up the rows of a partial buffer for channel c: the four ty lanes of a (64 x 4) block split the
+// rows and keep independent accumulators, then meet in LDS.  Returns the totals on ty == 0.
+__device__ __forceinline__ void sum_partials(const float* __restrict__ partial, int nblocks, int C, int c,
+                                             double* out1, double* out2) {
+    __shared__ double red[2][4][64];
+    double s1 = 0.0, s2 = 0.0;
+    if (c < C) {
+        float a0 = 0.f, a1 = 0.f, b0 = 0.f, b1 = 0.f;
+        int b = threadIdx.y;
+        for (; b + 4 < nblocks; b += 8) {
+            a0 += partial[(size_t)b * 2 * C + c];
+            b0 += partial[(size_t)b * 2 * C + C + c];
+            a1 += partial[(size_t)(b + 4) * 2 * C + c];
+            b1 += partial[(size_t)(b + 4) * 2 * C + C + c];
+        }
+        if (b < nblocks) {
+            a0 += partial[(size_t)b * 2 * C + c];
+            b0 += partial[(size_t)b * 2 * C + C + c];
+        }
+        s1 = (double)a0 + (double)a1;
+        s2 = (double)b0 + (double)b1;
+    }
+    red[0][threadIdx.y][threadIdx.x] = s1;
+    red[1][threadIdx.y][threadIdx.x] = s2;
+    __syncthreads();
+    *out1 = red[0][0][threadIdx.x] + red[0][1][threadIdx.x] + red[0][2][threadIdx.x] + red[0][3][threadIdx.x];
+    *out2 = red[1][0][threadIdx.x] + red[1][1][threadIdx.x] + red[1][2][threadIdx.x] + red[1][3][threadIdx.x];
+}
+
+// ---- partial statistics -> per-channel vectors ------------------------------------------------------
+__global__ void bn_finalize_kernel(const float* __restrict__ partial, int nblocks, double inv_m, double unbias, int C,
                                    const float* __restrict__ gamma, const float* __restrict__ beta, float eps,
                                    BnVec o, float* run_mean, float* run_var, float momentum) {
-    int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= C) return;
-    const double mean = acc[c] * inv_m;
-    double var = acc[C + c] * inv_m - mean * mean;
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    double s1, s2;
+    sum_partials(partial, nblocks, C, c, &s1, &s2);
+    if (c >= C || threadIdx.y != 0) return;
+    const double mean = s1 * inv_m;
+    double var = s2 * inv_m - mean * mean;
     if (var < 0) var = 0;
     const float rstd = (float)(1.0 / sqrt(var + (double)eps));
     const float g = gamma ? gamma[c] : 1.f;
@@ -135,113 +179,131 @@ __global__ void bn_finalize_kernel(const double* __restrict__ acc, double inv_m,
     }
 }
 
-int bn_finalize(const double* acc, long rows, int C, const float* gamma, const float* beta, float eps, BnVec out,
-                float* run_mean, float* run_var, float momentum, hipStream_t s) {
+int bn_finalize(const float* partial, int nblocks, long rows, int C, const float* gamma, const float* beta, float eps,
+                BnVec out, float* run_mean, float* run_var, float momentum, hipStream_t s) {
     const double inv_m = rows > 0 ? 1.0 / (double)rows : 0.0;
     const double unbias = rows > 1 ? (double)rows / (double)(rows - 1) : 1.0;
-    bn_finalize_kernel<<<dim3(cdiv(C, 256)), dim3(256), 0, s>>>(acc, inv_m, unbias, C, gamma, beta, eps, out,
-                                                               run_mean, run_var, momentum);
+    bn_finalize_kernel<<<dim3(cdiv(C, 64)), dim3(64, 4), 0, s>>>(partial, nblocks, inv_m, unbias, C, gamma, beta, eps,
+                                                                out, run_mean, run_var, momentum);
     return check_launch("bn_finalize");
 }
 
-__global__ void stats_to_float_kernel(const double* __restrict__ acc, int C, float* sum, float* sumsq) {
-    int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= C) return;
-    sum[c] = (float)acc[c];
-    sumsq[c] = (float)acc[C + c];
+__global__ void stats_to_float_kernel(const float* __restrict__ partial, int nblocks, int C, float* sum, float* sumsq) {
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    double s1, s2;
+    sum_partials(partial, nblocks, C, c, &s1, &s2);
+    if (c >= C || threadIdx.y != 0) return;
+    sum[c] = (float)s1;
+    sumsq[c] = (float)s2;
 }
 
-int stats_to_float(const double* acc, int C, float* sum, float* sumsq, hipStream_t s) {
-    stats_to_float_kernel<<<dim3(cdiv(C, 256)), dim3(256), 0, s>>>(acc, C, sum, sumsq);
+int stats_to_float(const float* partial, int nblocks, int C, float* sum, float* sumsq, hipStream_t s) {
+    stats_to_float_kernel<<<dim3(cdiv(C, 64)), dim3(64, 4), 0, s>>>(partial, nblocks, C, sum, sumsq);
     return check_launch("stats_to_float");
 }
 
 // ---- z = relu(scale*y + shift) ------------------------------------------------------------------
 template <typename T, int V>
-__global__ void __launch_bounds__(256) bn_relu_kernel(const T* __restrict__ y, size_t nvec, int cv,
+__global__ void __launch_bounds__(256) bn_relu_kernel(const T* __restrict__ y, long rows, int C, int cv,
                                                       const float* __restrict__ scale,
                                                       const float* __restrict__ shift, T* __restrict__ z) {
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= nvec) return;
-    const int c0 = (int)(i % cv) * V;
-    Pack<T, V> in = *(const Pack<T, V>*)(y + i * V), out;
+    const int cvi = blockIdx.y * blockDim.x + threadIdx.x;
+    if (cvi >= cv) return;
+    float sc[V], sh[V];
 #pragma unroll
     for (int j = 0; j < V; ++j) {
-        float v = fmaf(Elem<T>::ld(in.v[j]), scale[c0 + j], shift[c0 + j]);
-        out.v[j] = Elem<T>::st(v > 0.f ? v : 0.f);
+        sc[j] = scale[cvi * V + j];
+        sh[j] = shift[cvi * V + j];
     }
-    *(Pack<T, V>*)(z + i * V) = out;
+    for (long r = (long)blockIdx.x * blockDim.y + threadIdx.y; r < rows; r += (long)gridDim.x * blockDim.y) {
+        const long off = r * C + (long)cvi * V;
+        Pack<T, V> in = *(const Pack<T, V>*)(y + off), out;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            float v = fmaf(Elem<T>::ld(in.v[j]), sc[j], sh[j]);
+            out.v[j] = Elem<T>::st(v > 0.f ? v : 0.f);
+        }
+        *(Pack<T, V>*)(z + off) = out;
+    }
 }
 
-template <typename T>
-static int bn_relu_t(const T* y, long rows, int C, const float* scale, const float* shift, T* z, hipStream_t s) {
-    constexpr int VEC = Elem<T>::VEC;
-    if (C % VEC == 0) {
-        size_t nvec = (size_t)rows * C / VEC;
-        bn_relu_kernel<T, VEC><<<dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, s>>>(y, nvec, C / VEC, scale, shift, z);
-    } else {
-        size_t nvec = (size_t)rows * C;
-        bn_relu_kernel<T, 1><<<dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, s>>>(y, nvec, C, scale, shift, z);
-    }
+template <typename T, int V>
+static int bn_relu_tv(const T* y, long rows, int C, const float* scale, const float* shift, T* z, hipStream_t s) {
+    RowShape r = row_shape(rows, C, V, EW_ROWS_PER_THREAD, EW_MAX_GX);
+    bn_relu_kernel<T, V><<<r.grid, r.block, 0, s>>>(y, rows, C, r.cv, scale, shift, z);
     return check_launch("bn_relu_apply");
 }
 
 int bn_relu_apply(int dtype, const void* y, long rows, int C, const float* scale, const float* shift, void* z,
                   hipStream_t s) {
     if (rows == 0) return TSM_OK;
-    return dtype == TSM_F32 ? bn_relu_t<float>((const float*)y, rows, C, scale, shift, (float*)z, s)
-                            : bn_relu_t<bf16_t>((const bf16_t*)y, rows, C, scale, shift, (bf16_t*)z, s);
+    const int v = vec_of(dtype, C);
+    if (dtype == TSM_F32)
+        return v == 4 ? bn_relu_tv<float, 4>((const float*)y, rows, C, scale, shift, (float*)z, s)
+                      : bn_relu_tv<float, 1>((const float*)y, rows, C, scale, shift, (float*)z, s);
+    return v == 8 ? bn_relu_tv<bf16_t, 8>((const bf16_t*)y, rows, C, scale, shift, (bf16_t*)z, s)
+                  : bn_relu_tv<bf16_t, 1>((const bf16_t*)y, rows, C, scale, shift, (bf16_t*)z, s);
 }
 
 // ---- out = relu(scale*y + shift + shortcut') -------------------------------------------------------
-template <typename T, int V>
-__global__ void __launch_bounds__(256) tail_kernel(const T* __restrict__ y, size_t nvec, int cv,
+template <typename T, int V, bool PROJ>
+__global__ void __launch_bounds__(256) tail_kernel(const T* __restrict__ y, long rows, int C, int cv,
                                                    const float* __restrict__ scale, const float* __restrict__ shift,
                                                    const T* __restrict__ sc, const float* __restrict__ scale_d,
                                                    const float* __restrict__ shift_d, T* __restrict__ out) {
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= nvec) return;
-    const int c0 = (int)(i % cv) * V;
-    Pack<T, V> a = *(const Pack<T, V>*)(y + i * V), b = *(const Pack<T, V>*)(sc + i * V), o;
+    const int cvi = blockIdx.y * blockDim.x + threadIdx.x;
+    if (cvi >= cv) return;
+    float s0[V], h0[V], s1[V], h1[V];
 #pragma unroll
     for (int j = 0; j < V; ++j) {
-        float r = Elem<T>::ld(b.v[j]);
-        if (scale_d) r = fmaf(r, scale_d[c0 + j], shift_d[c0 + j]);
-        float v = fmaf(Elem<T>::ld(a.v[j]), scale[c0 + j], shift[c0 + j]) + r;
-        o.v[j] = Elem<T>::st(v > 0.f ? v : 0.f);
+        s0[j] = scale[cvi * V + j];
+        h0[j] = shift[cvi * V + j];
+        s1[j] = PROJ ? scale_d[cvi * V + j] : 1.f;
+        h1[j] = PROJ ? shift_d[cvi * V + j] : 0.f;
     }
-    *(Pack<T, V>*)(out + i * V) = o;
+    for (long r = (long)blockIdx.x * blockDim.y + threadIdx.y; r < rows; r += (long)gridDim.x * blockDim.y) {
+        const long off = r * C + (long)cvi * V;
+        Pack<T, V> a = *(const Pack<T, V>*)(y + off), b = *(const Pack<T, V>*)(sc + off), o;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            float rr = Elem<T>::ld(b.v[j]);
+            if (PROJ) rr = fmaf(rr, s1[j], h1[j]);
+            const float v = fmaf(Elem<T>::ld(a.v[j]), s0[j], h0[j]) + rr;
+            o.v[j] = Elem<T>::st(v > 0.f ? v : 0.f);
+        }
+        *(Pack<T, V>*)(out + off) = o;
+    }
 }
 
-template <typename T>
-static int tail_t(const T* y, long rows, int C, const float* scale, const float* shift, const T* sc,
-                  const float* scale_d, const float* shift_d, T* out, hipStream_t s) {
-    constexpr int VEC = Elem<T>::VEC;
-    if (C % VEC == 0) {
-        size_t nvec = (size_t)rows * C / VEC;
-        tail_kernel<T, VEC><<<dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, s>>>(y, nvec, C / VEC, scale, shift, sc, scale_d, shift_d, out);
-    } else {
-        size_t nvec = (size_t)rows * C;
-        tail_kernel<T, 1><<<dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, s>>>(y, nvec, C, scale, shift, sc, scale_d, shift_d, out);
-    }
+template <typename T, int V>
+static int tail_tv(const T* y, long rows, int C, const float* scale, const float* shift, const T* sc,
+                   const float* scale_d, const float* shift_d, T* out, hipStream_t s) {
+    RowShape r = row_shape(rows, C, V, EW_ROWS_PER_THREAD, EW_MAX_GX);
+    if (scale_d)
+        tail_kernel<T, V, true><<<r.grid, r.block, 0, s>>>(y, rows, C, r.cv, scale, shift, sc, scale_d, shift_d, out);
+    else
+        tail_kernel<T, V, false><<<r.grid, r.block, 0, s>>>(y, rows, C, r.cv, scale, shift, sc, scale_d, shift_d, out);
     return check_launch("block_tail_fwd");
 }
 
 int block_tail_fwd(int dtype, const void* y, long rows, int C, const float* scale, const float* shift,
                    const void* shortcut, const float* scale_d, const float* shift_d, void* out, hipStream_t s) {
     if (rows == 0) return TSM_OK;
-    return dtype == TSM_F32
-               ? tail_t<float>((const float*)y, rows, C, scale, shift, (const float*)shortcut, scale_d, shift_d, (float*)out, s)
-               : tail_t<bf16_t>((const bf16_t*)y, rows, C, scale, shift, (const bf16_t*)shortcut, scale_d, shift_d, (bf16_t*)out, s);
+    const int v = vec_of(dtype, C);
+    if (dtype == TSM_F32)
+        return v == 4 ? tail_tv<float, 4>((const float*)y, rows, C, scale, shift, (const float*)shortcut, scale_d, shift_d, (float*)out, s)
+                      : tail_tv<float, 1>((const float*)y, rows, C, scale, shift, (const float*)shortcut, scale_d, shift_d, (float*)out, s);
+    return v == 8 ? tail_tv<bf16_t, 8>((const bf16_t*)y, rows, C, scale, shift, (const bf16_t*)shortcut, scale_d, shift_d, (bf16_t*)out, s)
+                  : tail_tv<bf16_t, 1>((const bf16_t*)y, rows, C, scale, shift, (const bf16_t*)shortcut, scale_d, shift_d, (bf16_t*)out, s);
 }
 
 // ---- backward, pass A: ReLU mask + the two BatchNorm reductions -------------------------------------
 template <typename T, int V>
 __global__ void __launch_bounds__(256) relu_bn_bwd_reduce_kernel(
     const T* __restrict__ dout, const T* __restrict__ act, const T* __restrict__ y, long rows, int C, int cv,
-    const float* __restrict__ mean, const float* __restrict__ rstd, T* __restrict__ dz_out, double* __restrict__ acc,
-    const T* __restrict__ y2, const float* __restrict__ mean2, const float* __restrict__ rstd2,
-    double* __restrict__ acc2) {
+    const float* __restrict__ mean, const float* __restrict__ rstd, T* __restrict__ dz_out,
+    float* __restrict__ partial, const T* __restrict__ y2, const float* __restrict__ mean2,
+    const float* __restrict__ rstd2, float* __restrict__ partial2) {
     const int cvi = blockIdx.y * blockDim.x + threadIdx.x;
     float s1[V], s2[V], s3[V], mu[V], rs[V], mu2[V], rs2[V];
 #pragma unroll
@@ -272,94 +334,108 @@ __global__ void __launch_bounds__(256) relu_bn_bwd_reduce_kernel(
             *(Pack<T, V>*)(dz_out + off) = o;
         }
     }
-    block_reduce_2<V>(s1, s2, cvi, cv, C, acc);
+    block_partial_2<V>(s1, s2, cvi, cv, C, partial + (size_t)blockIdx.x * 2 * C);
     if (y2) {
         __syncthreads();
-        block_reduce_2<V>(s1, s3, cvi, cv, C, acc2);
+        block_partial_2<V>(s1, s3, cvi, cv, C, partial2 + (size_t)blockIdx.x * 2 * C);
     }
 }
 
-template <typename T>
-static int relu_bn_bwd_reduce_t(const T* dout, const T* act, const T* y, long rows, int C, const float* mean,
-                                const float* rstd, T* dz_out, double* acc, const T* y2, const float* mean2,
-                                const float* rstd2, double* acc2, hipStream_t s) {
-    constexpr int VEC = Elem<T>::VEC;
-    if (C % VEC == 0) {
-        RedShape r = red_shape(rows, C, VEC);
-        relu_bn_bwd_reduce_kernel<T, VEC><<<r.grid, r.block, 0, s>>>(dout, act, y, rows, C, r.cv, mean, rstd, dz_out, acc, y2, mean2, rstd2, acc2);
-    } else {
-        RedShape r = red_shape(rows, C, 1);
-        relu_bn_bwd_reduce_kernel<T, 1><<<r.grid, r.block, 0, s>>>(dout, act, y, rows, C, r.cv, mean, rstd, dz_out, acc, y2, mean2, rstd2, acc2);
-    }
+template <typename T, int V>
+static int relu_bn_bwd_reduce_tv(const T* dout, const T* act, const T* y, long rows, int C, const float* mean,
+                                 const float* rstd, T* dz_out, float* partial, const T* y2, const float* mean2,
+                                 const float* rstd2, float* partial2, hipStream_t s) {
+    RowShape r = row_shape(rows, C, V, RED_ROWS_PER_THREAD, RED_MAX_GX);
+    relu_bn_bwd_reduce_kernel<T, V><<<r.grid, r.block, 0, s>>>(dout, act, y, rows, C, r.cv, mean, rstd, dz_out, partial,
+                                                                y2, mean2, rstd2, partial2);
     return check_launch("relu_bn_bwd_reduce");
 }
 
+// partial / partial2: fp32 [red_blocks(rows, C, dtype)][2*C]
 int relu_bn_bwd_reduce(int dtype, const void* dout, const void* act, const void* y, long rows, int C,
-                       const float* mean, const float* rstd, void* dz_out, double* acc, const void* y2,
-                       const float* mean2, const float* rstd2, double* acc2, hipStream_t s) {
+                       const float* mean, const float* rstd, void* dz_out, float* partial, const void* y2,
+                       const float* mean2, const float* rstd2, float* partial2, hipStream_t s) {
     if (rows == 0) return TSM_OK;
-    return dtype == TSM_F32
-               ? relu_bn_bwd_reduce_t<float>((const float*)dout, (const float*)act, (const float*)y, rows, C, mean, rstd,
-                                             (float*)dz_out, acc, (const float*)y2, mean2, rstd2, acc2, s)
-               : relu_bn_bwd_reduce_t<bf16_t>((const bf16_t*)dout, (const bf16_t*)act, (const bf16_t*)y, rows, C, mean,
-                                              rstd, (bf16_t*)dz_out, acc, (const bf16_t*)y2, mean2, rstd2, acc2, s);
+    const int v = vec_of(dtype, C);
+#define TSM_RBR(T, V)                                                                                                \
+    relu_bn_bwd_reduce_tv<T, V>((const T*)dout, (const T*)act, (const T*)y, rows, C, mean, rstd, (T*)dz_out, partial, \
+                                (const T*)y2, mean2, rstd2, partial2, s)
+    if (dtype == TSM_F32) return v == 4 ? TSM_RBR(float, 4) : TSM_RBR(float, 1);
+    return v == 8 ? TSM_RBR(bf16_t, 8) : TSM_RBR(bf16_t, 1);
+#undef TSM_RBR
 }
 
-// ---- backward, pass B: dy = gamma*rstd*(dz - sum_dz/m - yhat*sum_dzyhat/m) -------------------------------
+// ---- backward, between the passes: sums -> per-channel coefficients ---------------------------------------
+// dy = gamma*rstd*(dz - S1/m - yhat*S2/m), yhat = (y-mean)*rstd, rewritten as dy = a*dz + b*y + c with
+//   a = gamma*rstd,  b = -gamma*rstd^2*S2/m,  c = gamma*rstd*(mean*rstd*S2/m - S1/m);
+// dbeta = S1, dgamma = S2.
+__global__ void bn_bwd_coeffs_kernel(const float* __restrict__ partial, int nblocks, double inv_m, int C,
+                                     const float* __restrict__ mean, const float* __restrict__ rstd,
+                                     const float* __restrict__ gamma, float* __restrict__ coef,
+                                     float* __restrict__ dgamma, float* __restrict__ dbeta) {
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    double s1, s2;
+    sum_partials(partial, nblocks, C, c, &s1, &s2);
+    if (c >= C || threadIdx.y != 0) return;
+    const float g = gamma ? gamma[c] : 1.f;
+    const float rs = rstd[c], mu = mean[c];
+    const float m1 = (float)(s1 * inv_m), m2 = (float)(s2 * inv_m);
+    coef[c] = g * rs;
+    coef[C + c] = -g * rs * rs * m2;
+    coef[2 * C + c] = g * rs * (mu * rs * m2 - m1);
+    if (dbeta) dbeta[c] = (float)s1;
+    if (dgamma) dgamma[c] = (float)s2;
+}
+
+int bn_bwd_coeffs(const float* partial, int nblocks, long rows, int C, const float* mean, const float* rstd,
+                  const float* gamma, float* coef, float* dgamma, float* dbeta, hipStream_t s) {
+    const double inv_m = rows > 0 ? 1.0 / (double)rows : 0.0;
+    bn_bwd_coeffs_kernel<<<dim3(cdiv(C, 64)), dim3(64, 4), 0, s>>>(partial, nblocks, inv_m, C, mean, rstd, gamma, coef,
+                                                                  dgamma, dbeta);
+    return check_launch("bn_bwd_coeffs");
+}
+
+// ---- backward, pass B: dy = a*dz + b*y + c ------------------------------------------------------------------
 template <typename T, int V>
 __global__ void __launch_bounds__(256) bn_bwd_apply_kernel(const T* __restrict__ dz, const T* __restrict__ y,
-                                                           size_t nvec, int cv, int C, float inv_m,
-                                                           const float* __restrict__ mean,
-                                                           const float* __restrict__ rstd,
-                                                           const float* __restrict__ gamma,
-                                                           const double* __restrict__ acc, T* __restrict__ dy,
-                                                           float* __restrict__ dgamma, float* __restrict__ dbeta) {
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < (size_t)cv) {  // the first row's threads also publish dgamma / dbeta
-#pragma unroll
-        for (int j = 0; j < V; ++j) {
-            const int c = (int)i * V + j;
-            if (dbeta) dbeta[c] = (float)acc[c];
-            if (dgamma) dgamma[c] = (float)acc[C + c];
-        }
-    }
-    if (i >= nvec) return;
-    const int c0 = (int)(i % cv) * V;
-    Pack<T, V> a = *(const Pack<T, V>*)(dz + i * V), b = *(const Pack<T, V>*)(y + i * V), o;
+                                                           long rows, int C, int cv, const float* __restrict__ coef,
+                                                           T* __restrict__ dy) {
+    const int cvi = blockIdx.y * blockDim.x + threadIdx.x;
+    if (cvi >= cv) return;
+    float ka[V], kb[V], kc[V];
 #pragma unroll
     for (int j = 0; j < V; ++j) {
-        const int c = c0 + j;
-        const float rs = rstd[c];
-        const float yhat = (Elem<T>::ld(b.v[j]) - mean[c]) * rs;
-        const float sdz = (float)acc[c] * inv_m, sdzy = (float)acc[C + c] * inv_m;
-        const float g = gamma ? gamma[c] : 1.f;
-        o.v[j] = Elem<T>::st(g * rs * (Elem<T>::ld(a.v[j]) - sdz - yhat * sdzy));
+        ka[j] = coef[cvi * V + j];
+        kb[j] = coef[C + cvi * V + j];
+        kc[j] = coef[2 * C + cvi * V + j];
     }
-    *(Pack<T, V>*)(dy + i * V) = o;
+    for (long r = (long)blockIdx.x * blockDim.y + threadIdx.y; r < rows; r += (long)gridDim.x * blockDim.y) {
+        const long off = r * C + (long)cvi * V;
+        Pack<T, V> a = *(const Pack<T, V>*)(dz + off), b = *(const Pack<T, V>*)(y + off), o;
+#pragma unroll
+        for (int j = 0; j < V; ++j)
+            o.v[j] = Elem<T>::st(fmaf(ka[j], Elem<T>::ld(a.v[j]), fmaf(kb[j], Elem<T>::ld(b.v[j]), kc[j])));
+        *(Pack<T, V>*)(dy + off) = o;
+    }
 }
 
-template <typename T>
-static int bn_bwd_apply_t(const T* dz, const T* y, long rows, int C, const float* mean, const float* rstd,
-                          const float* gamma, const double* acc, T* dy, float* dgamma, float* dbeta, hipStream_t s) {
-    constexpr int VEC = Elem<T>::VEC;
-    const float inv_m = 1.f / (float)rows;
-    if (C % VEC == 0) {
-        size_t nvec = (size_t)rows * C / VEC;
-        bn_bwd_apply_kernel<T, VEC><<<dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, s>>>(dz, y, nvec, C / VEC, C, inv_m, mean, rstd, gamma, acc, dy, dgamma, dbeta);
-    } else {
-        size_t nvec = (size_t)rows * C;
-        bn_bwd_apply_kernel<T, 1><<<dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, s>>>(dz, y, nvec, C, C, inv_m, mean, rstd, gamma, acc, dy, dgamma, dbeta);
-    }
+template <typename T, int V>
+static int bn_bwd_apply_tv(const T* dz, const T* y, long rows, int C, const float* coef, T* dy, hipStream_t s) {
+    RowShape r = row_shape(rows, C, V, EW_ROWS_PER_THREAD, EW_MAX_GX);
+    bn_bwd_apply_kernel<T, V><<<r.grid, r.block, 0, s>>>(dz, y, rows, C, r.cv, coef, dy);
     return check_launch("bn_bwd_apply");
 }
 
-int bn_bwd_apply(int dtype, const void* dz, const void* y, long rows, int C, const float* mean, const float* rstd,
-                 const float* gamma, const double* acc, void* dy, float* dgamma, float* dbeta, hipStream_t s) {
+// coef: fp32 [3*C] from bn_bwd_coeffs
+int bn_bwd_apply(int dtype, const void* dz, const void* y, long rows, int C, const float* coef, void* dy,
+                 hipStream_t s) {
     if (rows == 0) return TSM_OK;
-    return dtype == TSM_F32 ? bn_bwd_apply_t<float>((const float*)dz, (const float*)y, rows, C, mean, rstd, gamma, acc,
-                                                    (float*)dy, dgamma, dbeta, s)
-                            : bn_bwd_apply_t<bf16_t>((const bf16_t*)dz, (const bf16_t*)y, rows, C, mean, rstd, gamma,
-                                                     acc, (bf16_t*)dy, dgamma, dbeta, s);
+    const int v = vec_of(dtype, C);
+    if (dtype == TSM_F32)
+        return v == 4 ? bn_bwd_apply_tv<float, 4>((const float*)dz, (const float*)y, rows, C, coef, (float*)dy, s)
+                      : bn_bwd_apply_tv<float, 1>((const float*)dz, (const float*)y, rows, C, coef, (float*)dy, s);
+    return v == 8 ? bn_bwd_apply_tv<bf16_t, 8>((const bf16_t*)dz, (const bf16_t*)y, rows, C, coef, (bf16_t*)dy, s)
+                  : bn_bwd_apply_tv<bf16_t, 1>((const bf16_t*)dz, (const bf16_t*)y, rows, C, coef, (bf16_t*)dy, s);
 }
 
 // ---- out = a + b ------------------------------------------------------------------------------

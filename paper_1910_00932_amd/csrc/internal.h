@@ -34,31 +34,38 @@ int conv_direct_dgrad(const ConvP& p, int dtype, const void* dy, const void* w, 
 int conv_direct_wgrad(const ConvP& p, int dtype, const void* x, const void* dy, float* dw, hipStream_t s);
 
 // ---- elementwise.hip -----------------------------------------------------------------
-// Per-channel batch statistics live in a double buffer `acc` of 2*C entries:
-// acc[c] = sum, acc[C + c] = sum of squares (or the two BatchNorm-backward sums).
+// Per-channel reductions are deterministic and atomic-free: every block of a
+// reduction kernel writes one row of a `partial` buffer, fp32 [blocks][2*C]
+// (first C: sum / sum dz, next C: sum of squares / sum dz*yhat); the small kernel that
+// consumes the statistics adds the rows up in fp64.
 int fill_zero(void* p, size_t bytes, hipStream_t s);
-int channel_stats(int dtype, const void* y, long rows, int C, double* acc, hipStream_t s);
+// Rows of `partial` written by channel_stats / relu_bn_bwd_reduce for this tensor.
+int red_blocks(long rows, int C, int dtype);
+int channel_stats(int dtype, const void* y, long rows, int C, float* partial, hipStream_t s);
 struct BnVec {           // per-channel fp32 vectors of one BatchNorm, each [C]
     float *mean, *rstd, *scale, *shift;
 };
-// mean/rstd/scale=gamma*rstd/shift=beta-mean*scale from acc; optional running stats update.
-int bn_finalize(const double* acc, long rows, int C, const float* gamma, const float* beta, float eps,
-                BnVec out, float* run_mean, float* run_var, float momentum, hipStream_t s);
-int stats_to_float(const double* acc, int C, float* sum, float* sumsq, hipStream_t s);
+// mean/rstd/scale=gamma*rstd/shift=beta-mean*scale from the partial rows; optional running stats update.
+int bn_finalize(const float* partial, int nblocks, long rows, int C, const float* gamma, const float* beta,
+                float eps, BnVec out, float* run_mean, float* run_var, float momentum, hipStream_t s);
+int stats_to_float(const float* partial, int nblocks, int C, float* sum, float* sumsq, hipStream_t s);
 // z = relu(scale*y + shift)
 int bn_relu_apply(int dtype, const void* y, long rows, int C, const float* scale, const float* shift, void* z,
                   hipStream_t s);
 // out = relu(scale*y + shift + sc), sc = shortcut (scale_d == null) or scale_d*shortcut + shift_d
 int block_tail_fwd(int dtype, const void* y, long rows, int C, const float* scale, const float* shift,
                    const void* shortcut, const float* scale_d, const float* shift_d, void* out, hipStream_t s);
-// dz = dout * [act > 0] (act == null: no mask) written to dz_out (may alias dout); acc[c] += sum dz, acc[C+c] += sum dz*yhat with
-// yhat = (y - mean)*rstd.  If y2 != null a second BatchNorm (projection shortcut) is reduced into acc2.
+// dz = dout * [act > 0] (act == null: no mask) written to dz_out (may alias dout); partial rows receive
+// sum dz and sum dz*yhat with yhat = (y - mean)*rstd.  If y2 != null a second BatchNorm (projection
+// shortcut) is reduced into partial2.
 int relu_bn_bwd_reduce(int dtype, const void* dout, const void* act, const void* y, long rows, int C,
-                       const float* mean, const float* rstd, void* dz_out, double* acc, const void* y2,
-                       const float* mean2, const float* rstd2, double* acc2, hipStream_t s);
-// dy = gamma*rstd*(dz - sum_dz/m - yhat*sum_dzyhat/m); also writes dgamma, dbeta (fp32 [C]).
-int bn_bwd_apply(int dtype, const void* dz, const void* y, long rows, int C, const float* mean, const float* rstd,
-                 const float* gamma, const double* acc, void* dy, float* dgamma, float* dbeta, hipStream_t s);
+                       const float* mean, const float* rstd, void* dz_out, float* partial, const void* y2,
+                       const float* mean2, const float* rstd2, float* partial2, hipStream_t s);
+// coef fp32 [3*C] such that dy = coef[c]*dz + coef[C+c]*y + coef[2C+c]; also dgamma, dbeta (nullable).
+int bn_bwd_coeffs(const float* partial, int nblocks, long rows, int C, const float* mean, const float* rstd,
+                  const float* gamma, float* coef, float* dgamma, float* dbeta, hipStream_t s);
+int bn_bwd_apply(int dtype, const void* dz, const void* y, long rows, int C, const float* coef, void* dy,
+                 hipStream_t s);
 // out = a + b
 int add_tensors(int dtype, const void* a, const void* b, void* out, size_t n, hipStream_t s);
 // dtype conversion / repacking of weights
@@ -73,13 +80,18 @@ int unpack_wgrad(const float* packed, float* dw, int Cout, int Cin, int taps, in
 
 // ---- conv_mfma.hip: bf16 MFMA implicit GEMM, channels-innermost -------------------------
 bool mfma_conv_supported(const ConvP& p);
-// y = conv(S(x)); wp = bf16 [Cout][taps][Cin]; stats (nullable) receives per-channel sum / sum of squares
-// of the stored (rounded) output, accumulated with atomics: zero it first.
-int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, double* stats, hipStream_t s);
+// Blocks the forward kernel launches for p (= rows of its statistics partial buffer).
+int conv_mfma_fwd_blocks(const ConvP& p);
+// y = conv(S(x)); wp = bf16 [Cout][taps][Cin]; stats_partial (nullable), fp32 [conv_mfma_fwd_blocks(p)][2*Cout],
+// receives per block the per-channel sum / sum of squares of the stored (rounded) output.
+int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, float* stats_partial, hipStream_t s);
 // dx = S^T(conv^T(dy)) + addend; wd = bf16 [Cin][flipped taps][Cout]
 int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* dx, const bf16_t* addend,
                     hipStream_t s);
-// dwp fp32 [Cout][taps][Cin], accumulated with atomics: zero it first.
-int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dwp, hipStream_t s);
+// dw fp32, accumulated with atomics: zero it first (or keep what is there to accumulate).
+// packed: [Cout][taps][p.Cin] (contiguous atomics, the fast order when taps > 1);
+// otherwise the ABI order [Cout][cin_real][taps].  Channels >= cin_real are padding and are not written.
+int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, bool packed,
+                    hipStream_t s);
 
 }  // namespace tsm

@@ -408,7 +408,6 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
     void* y0 = A.take((size_t)F * H1 * H1 * 64 * es);
     BnVec bn0;
     bn0.mean = A.take_n<float>(64); bn0.rstd = A.take_n<float>(64); bn0.scale = A.take_n<float>(64); bn0.shift = A.take_n<float>(64);
-    double* acc0 = A.take_n<double>(128);
     uint8_t* arg0 = A.take_n<uint8_t>((size_t)F * Hp * Hp * 64);
     void* p0 = A.take((size_t)F * Hp * Hp * 64 * es);
     ConvP stem{};
@@ -416,6 +415,11 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
     stem.KT = 1; stem.KH = 7; stem.KW = 7; stem.stride = 2; stem.pad = 3; stem.fold = 0;
     float *rm0, *rv0;
     run_slot(64, &rm0, &rv0);
+    const int nb0f = bf ? conv_mfma_fwd_blocks(stem) : red_blocks(stem.rows_out(), 64, dtype);
+    const int nb0b = red_blocks(stem.rows_out(), 64, dtype);
+    float* part0 = A.take_n<float>((size_t)(nb0f > nb0b ? nb0f : nb0b) * 128);
+    float* coef0 = A.take_n<float>(3 * 64);
+    float* dwp0 = A.take_n<float>((size_t)64 * 49 * 8);
 
     // ---- blocks: plans, saved buffers, outputs
     struct Blk {
@@ -438,6 +442,7 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
                 TSM_TRY(make_block_plan(&bd, &blk.plan, who));
                 BlockPlan& pl = blk.plan;
                 pl.bn_momentum = d->bn_momentum;
+                pl.grads_prezeroed = true;
                 const char* cn[3] = {"c1.w", "c2.w", "c3.w"};
                 const char* bnn[3] = {"bn1", "bn2", "bn3"};
                 for (int i = 0; i < 3; ++i) {
@@ -482,10 +487,12 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
     }
     void* dbuf[2] = {A.take(act_max), A.take(act_max)};
     void* da0 = A.take((size_t)F * H1 * H1 * 64 * es);
-    float* dwp0 = A.take_n<float>((size_t)64 * 49 * 8);
     char* scratch_base = dry ? nullptr : (char*)wsp + A.used;
     const size_t scratch_cap = dry ? (size_t)-1 : (ws_bytes > A.used ? ws_bytes - A.used : 0);
     auto note = [&](const Arena& sc) { if (sc.used > scratch_need) scratch_need = sc.used; };
+
+    // every weight gradient is accumulated with atomics: one fill for the whole gradient vector
+    RUN(fill_zero(grads, (size_t)nparams * sizeof(float), s));
 
     // ================= forward =================
     {
@@ -498,14 +505,14 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
         } else {
             RUN(transpose_frames(clips, x0, F, 3, S * S, 4, s));
         }
-        RUN(fill_zero(acc0, 128 * sizeof(double), s));
         if (bf) {
-            RUN(conv_mfma_fwd(stem, (const bf16_t*)x0, wp0, (bf16_t*)y0, acc0, s));
+            RUN(conv_mfma_fwd(stem, (const bf16_t*)x0, wp0, (bf16_t*)y0, part0, s));
         } else {
             RUN(conv_direct_fwd(stem, dtype, x0, P("conv1.w"), y0, s));
-            RUN(channel_stats(dtype, y0, stem.rows_out(), 64, acc0, s));
+            RUN(channel_stats(dtype, y0, stem.rows_out(), 64, part0, s));
         }
-        RUN(bn_finalize(acc0, stem.rows_out(), 64, P("bn1.g"), P("bn1.b"), d->bn_eps, bn0, rm0, rv0, d->bn_momentum, s));
+        RUN(bn_finalize(part0, nb0f, stem.rows_out(), 64, P("bn1.g"), P("bn1.b"), d->bn_eps, bn0, rm0, rv0,
+                        d->bn_momentum, s));
         const int cv = 64 / VEC;
         const long ptotal = (long)F * Hp * Hp * cv;
         if (!dry) {
@@ -561,19 +568,18 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
                 stem_pool_bwd_kernel<float><<<dim3(cdiv(total, 256)), dim3(256), 0, s>>>((const float*)dbuf[cur], arg0, (const float*)y0, bn0.scale, bn0.shift, (float*)da0, H1, H1, Hp, Hp, cv, total);
             LAUNCH_CHECK("stem_pool_bwd");
         }
-        RUN(fill_zero(acc0, 128 * sizeof(double), s));
-        RUN(relu_bn_bwd_reduce(dtype, da0, nullptr, y0, stem.rows_out(), 64, bn0.mean, bn0.rstd, da0, acc0, nullptr,
+        RUN(relu_bn_bwd_reduce(dtype, da0, nullptr, y0, stem.rows_out(), 64, bn0.mean, bn0.rstd, da0, part0, nullptr,
                                nullptr, nullptr, nullptr, s));
-        RUN(bn_bwd_apply(dtype, da0, y0, stem.rows_out(), 64, bn0.mean, bn0.rstd, P("bn1.g"), acc0, da0, G("bn1.g"),
-                         G("bn1.b"), s));
+        RUN(bn_bwd_coeffs(part0, nb0b, stem.rows_out(), 64, bn0.mean, bn0.rstd, P("bn1.g"), coef0, G("bn1.g"),
+                          G("bn1.b"), s));
+        RUN(bn_bwd_apply(dtype, da0, y0, stem.rows_out(), 64, coef0, da0, s));
+        // the gradient buffer was zeroed at the start of the step; both kernels add into it
         if (bf) {
             RUN(fill_zero(dwp0, (size_t)64 * 49 * 8 * sizeof(float), s));
-            RUN(conv_mfma_wgrad(stem, (const bf16_t*)x0, (const bf16_t*)da0, dwp0, s));
-            RUN(unpack_wgrad(dwp0, G("conv1.w"), 64, 3, 49, 8, 0, s));
-        } else {
-            RUN(fill_zero(G("conv1.w"), (size_t)64 * 3 * 49 * sizeof(float), s));
+            RUN(conv_mfma_wgrad(stem, (const bf16_t*)x0, (const bf16_t*)da0, dwp0, 3, true, s));
+            RUN(unpack_wgrad(dwp0, G("conv1.w"), 64, 3, 49, 8, 1, s));
+        } else
             RUN(conv_direct_wgrad(stem, dtype, x0, da0, G("conv1.w"), s));
-        }
     }
     // ================= update =================
     if (update && !dry) {

@@ -5,6 +5,10 @@
 // cost is one read and one write of the tensor, so the design goal is plain
 // 16-byte coalesced traffic at HBM rate.
 #include <stdarg.h>
+#include <string.h>
+#include <map>
+#include <string>
+#include <vector>
 #include "common.h"
 #include "internal.h"
 
@@ -28,9 +32,35 @@ int fail(int code, const char* fmt, ...) {
     return code;
 }
 
+// ---- optional per-launch timing (measurement aid) ----------------------------------
+// While enabled, a HIP event is recorded on the profiled stream after every kernel
+// launch that goes through check_launch(); the time between consecutive events is
+// booked on the kernel class named by `what`.
+struct ProfState {
+    bool on = false;
+    hipStream_t stream = nullptr;
+    std::vector<hipEvent_t> pool;
+    std::vector<const char*> names;   // names[i] belongs to event i+1 (event 0 is the start mark)
+    size_t used = 0;
+};
+static thread_local ProfState g_prof;
+
+static hipEvent_t prof_next_event() {
+    if (g_prof.used == g_prof.pool.size()) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        g_prof.pool.push_back(e);
+    }
+    return g_prof.pool[g_prof.used++];
+}
+
 int check_launch(const char* what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(TSM_ERR_LAUNCH, "%s: %s", what, hipGetErrorString(e));
+    if (g_prof.on) {
+        hipEvent_t ev = prof_next_event();
+        if (ev && hipEventRecord(ev, g_prof.stream) == hipSuccess) g_prof.names.push_back(what);
+    }
     return TSM_OK;
 }
 
@@ -186,6 +216,41 @@ static int shift_entry(const void* x, void* y, int N, int T, int C, int H, int W
 extern "C" {
 
 const char* tsm_last_error(void) { return tsm::g_err; }
+
+int tsm_profile_begin(void* stream) {
+    using namespace tsm;
+    g_prof.used = 0;
+    g_prof.names.clear();
+    g_prof.stream = (hipStream_t)stream;
+    hipEvent_t ev = prof_next_event();
+    if (!ev || hipEventRecord(ev, g_prof.stream) != hipSuccess) return fail(TSM_ERR_LAUNCH, "tsm_profile_begin: cannot record event");
+    g_prof.on = true;
+    return TSM_OK;
+}
+
+int tsm_profile_end(char* report, size_t report_cap) {
+    using namespace tsm;
+    if (!g_prof.on) return fail(TSM_ERR_UNSUPPORTED, "tsm_profile_end: profiling was not started");
+    g_prof.on = false;
+    if (!report || report_cap == 0) return fail(TSM_ERR_NULLPTR, "tsm_profile_end: null report buffer");
+    if (hipStreamSynchronize(g_prof.stream) != hipSuccess) return fail(TSM_ERR_LAUNCH, "tsm_profile_end: synchronise failed");
+    std::map<std::string, std::pair<long, double>> agg;
+    for (size_t i = 0; i < g_prof.names.size(); ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_prof.pool[i], g_prof.pool[i + 1]) != hipSuccess) continue;
+        auto& a = agg[g_prof.names[i]];
+        a.first += 1;
+        a.second += ms;
+    }
+    size_t off = 0;
+    report[0] = 0;
+    for (auto& kv : agg) {
+        int n = snprintf(report + off, report_cap - off, "%s %ld %.6f\n", kv.first.c_str(), kv.second.first, kv.second.second);
+        if (n < 0 || (size_t)n >= report_cap - off) break;
+        off += (size_t)n;
+    }
+    return TSM_OK;
+}
 
 int tsm_shift_fwd(const void* x, void* y, int N, int T, int C, int H, int W, int fold_div, int dtype, int layout,
                   void* stream) {
