@@ -38,12 +38,40 @@ struct IgemmArgs {
     int stride;
     int padh, padw;        // fwd: pad; dgrad: K-1-pad
     int fold;              // fwd: shift of source channels; dgrad: adjoint shift of destination channels
-    long M;
-    int K;
-    int mtiles, ntiles;
+    int K;                 // taps * Cs: row pitch of wp
+    int ntiles;            // tiles along N
+    // Destination pixels are processed in classes.  Forward and stride-1 dgrad have one class (all
+    // pixels, all taps).  A stride-s dgrad has s*s parity classes: pixel (dh, dw) with dh % s == ph,
+    // dw % s == pw receives only the flipped taps a = a0h + th*s, b = a0w + tw*s, so each class is a
+    // dense GEMM over its own tap subset and no multiply is spent on structural zeros.
+    int ncls, cstep;
+    int ph[4], pw[4];      // parity of the class
+    int hc[4], wc[4];      // pixels of that parity per frame
+    int mt0[5];            // prefix sum of M tiles per class
+    int a0h[4], nth[4], a0w[4], ntw[4];
 };
 
 __device__ __forceinline__ int group_dt(int c, int fold) { return c < fold ? 1 : (c < 2 * fold ? -1 : 0); }
+
+// quad_perm [1,0,3,2]: every lane reads its neighbour in the pair (lane ^ 1)
+__device__ __forceinline__ uint32_t pair_swap(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);
+}
+
+// Lanes whose gather falls on padding (spatial border, clip end, K tail, row beyond M) read this instead.
+static __device__ uint4 g_zero_page[1];
+
+// Per tile row, decoded once per tile into LDS:
+//   off   element offset in `src` of the row's tap origin (frame f, source row oh, column ow); may point
+//         before the frame when the origin lies in the padding -- it is only used for taps inside the frame
+//   mask  bits 0..7: tap rows th with 0 <= oh+th < Hs; bits 8..15: tap columns tw with 0 <= ow+tw < Ws;
+//         bit 30: frame t+1 is in the clip; bit 31: frame t-1 is in the clip; 0 for rows beyond M
+//   dst   destination row index, -1 for rows beyond M
+struct RowInfo {
+    long off;
+    uint32_t mask;
+    int dst;
+};
 
 template <int BM, int BN, int WM, int WN, bool DGRAD>
 __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
@@ -56,18 +84,22 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
     constexpr int LDC = BN + 8;                     // staging pitch (elements)
     static_assert(BM % RPP == 0 && BN % RPP == 0, "tile / thread mismatch");
     static_assert(BM * LDC <= 2 * (BM + BN) * LDK, "staging must fit in the operand buffers");
+    static_assert(sizeof(RowInfo) == 16, "one 16-byte LDS read per row");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16_t* As = (bf16_t*)smem;                      // [2][BM][LDK]
     bf16_t* Bs = As + 2 * BM * LDK;                  // [2][BN][LDK]
     bf16_t* Cst = (bf16_t*)smem;                     // [BM][LDC], reuses As/Bs after the main loop
-    float* s_sum = (float*)(Bs + 2 * BN * LDK);      // [Cd] then [Cd]
+    RowInfo* s_row = (RowInfo*)(Bs + 2 * BN * LDK);  // [BM]
+    float* s_sum = (float*)(s_row + BM);             // [Cd] sums then [Cd] sums of squares
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int kvec = tid % KV, lrow = tid / KV;
     const bool do_stats = (!DGRAD) && a.stats != nullptr;
+    const bool uniform_tap = (a.Cs % BK) == 0;      // a K step never straddles two taps
+    const bf16_t* zero_page = (const bf16_t*)g_zero_page;
 
     if (do_stats) {
         for (int c = tid; c < 2 * a.Cd; c += 256) s_sum[c] = 0.f;
@@ -75,36 +107,74 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
     __syncthreads();
 
     const int hw_d = a.Hd * a.Wd;
-    const int nk = (a.K + BK - 1) / BK;
-    const int total_tiles = ((a.mtiles + 7) / 8) * 8 * a.ntiles;  // M tiles padded to whole groups of 8
+    const int hw_s = a.Hs * a.Ws;
+    const int frame_el = hw_s * a.Cs;               // elements per source frame
+    const int total_tiles = ((a.mt0[a.ncls] + 7) / 8) * 8 * a.ntiles;  // M tiles padded to whole groups of 8
 
     for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
         // Tiles that share an M range sit on the same XCD (ids 8 apart) so the
         // gathered rows are served by that XCD's L2.
         const int xcd = tile & 7, slot = tile >> 3;
-        int mt = (slot / a.ntiles) * 8 + xcd;
-        int nt = slot % a.ntiles;
-        if (mt >= a.mtiles) continue;  // the last group of 8 M tiles may be ragged (block-uniform branch)
-        const long m0 = (long)mt * BM;
+        const int mt = (slot / a.ntiles) * 8 + xcd;
+        const int nt = slot % a.ntiles;
+        if (mt >= a.mt0[a.ncls]) continue;  // the last group of 8 M tiles may be ragged (block-uniform branch)
+        int cls = 0;
+        while (cls + 1 < a.ncls && mt >= a.mt0[cls + 1]) ++cls;
+        const int hc = a.hc[cls], wc = a.wc[cls];
+        const long Mc = (long)a.F * hc * wc;
+        const long m0 = (long)(mt - a.mt0[cls]) * BM;
         const int n0 = nt * BN;
+        const int nth = a.nth[cls], ntw = a.ntw[cls], a0h = a.a0h[cls], a0w = a.a0w[cls];
+        const int ntaps = a.KT * nth * ntw;
+        const int Kc = ntaps * a.Cs;
+        const int nk = (Kc + BK - 1) / BK;
 
-        // ---- decode this thread's A rows once per tile
-        int rf[PA], rt[PA], rh[PA], rw[PA];
+        // ---- decode the tile's rows once, one row per thread, into LDS
+        if (tid < BM) {
+            const long m = m0 + tid;
+            RowInfo info;
+            info.off = 0;
+            info.mask = 0;
+            info.dst = -1;
+            if (m < Mc) {
+                const int f = (int)(m / (hc * wc));
+                const int q = (int)(m - (long)f * (hc * wc));
+                const int qh = q / wc, qw = q - qh * wc;
+                const int dh = qh * a.cstep + a.ph[cls], dw = qw * a.cstep + a.pw[cls];
+                // source coordinate of class-local tap (th, tw) is (oh + th, ow + tw); for a strided dgrad
+                // the division by the stride is exact by construction of the class
+                const int oh = DGRAD ? (dh - a.padh + a0h) / a.cstep : dh * a.stride - a.padh;
+                const int ow = DGRAD ? (dw - a.padw + a0w) / a.cstep : dw * a.stride - a.padw;
+                const int t = f % a.T;
+                uint32_t mask = 0;
+                for (int th = 0; th < nth; ++th)
+                    if (oh + th >= 0 && oh + th < a.Hs) mask |= 1u << th;
+                for (int tw = 0; tw < ntw; ++tw)
+                    if (ow + tw >= 0 && ow + tw < a.Ws) mask |= 1u << (8 + tw);
+                if (t + 1 < a.T) mask |= 1u << 30;
+                if (t >= 1) mask |= 1u << 31;
+                info.off = ((long)f * hw_s + (long)oh * a.Ws + ow) * a.Cs;
+                info.mask = mask;
+                info.dst = (f * a.Hd + dh) * a.Wd + dw;
+            }
+            s_row[tid] = info;
+        }
+        __syncthreads();
+
+        // this thread's gather rows and weight rows
+        const bf16_t* aptr[PA];
+        uint32_t amask[PA];
 #pragma unroll
         for (int i = 0; i < PA; ++i) {
-            const long m = m0 + i * RPP + lrow;
-            if (m < a.M) {
-                const int f = (int)(m / hw_d);
-                const int pix = (int)(m - (long)f * hw_d);
-                const int dh = pix / a.Wd, dw = pix - dh * a.Wd;
-                rf[i] = f;
-                rt[i] = f % a.T;
-                rh[i] = (DGRAD ? dh : dh * a.stride) - a.padh;
-                rw[i] = (DGRAD ? dw : dw * a.stride) - a.padw;
-            } else {
-                rf[i] = -1;
-                rt[i] = rh[i] = rw[i] = 0;
-            }
+            const RowInfo ri = s_row[i * RPP + lrow];
+            aptr[i] = a.src + ri.off;
+            amask[i] = ri.mask;
+        }
+        const bf16_t* bptr[PB];
+#pragma unroll
+        for (int j = 0; j < PB; ++j) {
+            const int n = n0 + j * RPP + lrow;
+            bptr[j] = n < a.Cd ? a.wp + (long)n * a.K : nullptr;
         }
 
         f32x16 acc[MI][NJ];
@@ -118,38 +188,36 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
         u32x4 areg[PA], breg[PB];
 
         auto load_tiles = [&](int kc) {
-            const int kk = kc * BK + kvec * 8;
-            const bool kvalid = kk < a.K;
-            const int tap = kk / a.Cs;
-            const int c = kk - tap * a.Cs;
-            const int kw = tap % a.KW;
-            const int kh = (tap / a.KW) % a.KH;
-            const int kt = tap / (a.KW * a.KH);
-            const int df = kt - a.KT / 2 + (DGRAD ? 0 : group_dt(c, a.fold));
+            int ltap, c;
+            if (uniform_tap) {
+                const int kk0 = kc * BK;
+                ltap = kk0 / a.Cs;                    // uniform over the block: scalar arithmetic
+                c = kk0 - ltap * a.Cs + kvec * 8;
+            } else {
+                const int kk = kc * BK + kvec * 8;
+                ltap = kk / a.Cs;
+                c = kk - ltap * a.Cs;
+            }
+            const bool kvalid = ltap < ntaps;
+            const int tw_ = ltap % ntw;
+            const int th_ = (ltap / ntw) % nth;
+            const int kt = ltap / (ntw * nth);
+            const int d = kt - a.KT / 2 + (DGRAD ? 0 : group_dt(c, a.fold));   // frame offset, in {-1, 0, 1}
+            // bits a row's mask must have for this tap
+            const uint32_t need = (1u << th_) | (1u << (8 + tw_)) | (d > 0 ? 1u << 30 : 0u) | (d < 0 ? 1u << 31 : 0u);
+            const int aoff = d * frame_el + (th_ * a.Ws + tw_) * a.Cs + c;
 #pragma unroll
             for (int i = 0; i < PA; ++i) {
-                int sh = rh[i] + kh, sw = rw[i] + kw;
-                bool ok = kvalid && rf[i] >= 0;
-                if (DGRAD && a.stride > 1) {
-                    ok = ok && sh >= 0 && sw >= 0 && (sh % a.stride == 0) && (sw % a.stride == 0);
-                    sh /= a.stride;
-                    sw /= a.stride;
-                }
-                const int ts = rt[i] + df;
-                ok = ok && ts >= 0 && ts < a.T && sh >= 0 && sh < a.Hs && sw >= 0 && sw < a.Ws;
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (ok) {
-                    const long off = (((long)(rf[i] + df) * a.Hs + sh) * a.Ws + sw) * a.Cs + c;
-                    v = *(const u32x4*)(a.src + off);
-                }
-                areg[i] = v;
+                const bool ok = kvalid && (amask[i] & need) == need;
+                const bf16_t* p = ok ? aptr[i] + aoff : zero_page;
+                areg[i] = *(const u32x4*)p;
             }
+            const int ta = a0h + th_ * a.cstep, tb = a0w + tw_ * a.cstep;   // (flipped) tap coordinates
+            const int woff = ((kt * a.KH + ta) * a.KW + tb) * a.Cs + c;
 #pragma unroll
             for (int j = 0; j < PB; ++j) {
-                const int n = n0 + j * RPP + lrow;
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (kvalid && n < a.Cd) v = *(const u32x4*)(a.wp + (long)n * a.K + kk);
-                breg[j] = v;
+                const bf16_t* p = (kvalid && bptr[j]) ? bptr[j] + woff : zero_page;
+                breg[j] = *(const u32x4*)p;
             }
         };
         auto store_tiles = [&](int buf) {
@@ -160,13 +228,7 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
 #pragma unroll
             for (int j = 0; j < PB; ++j) *(u32x4*)(Bb + (j * RPP + lrow) * LDK + kvec * 8) = breg[j];
         };
-
-        load_tiles(0);
-        store_tiles(0);
-        __syncthreads();
-        for (int kc = 0; kc < nk; ++kc) {
-            const int buf = kc & 1;
-            if (kc + 1 < nk) load_tiles(kc + 1);
+        auto compute = [&](int buf) {
             const bf16_t* Ab = As + buf * BM * LDK + (wm * TM + (lane & 31)) * LDK + 8 * (lane >> 5);
             const bf16_t* Bb = Bs + buf * BN * LDK + (wn * TN + (lane & 31)) * LDK + 8 * (lane >> 5);
 #pragma unroll
@@ -182,29 +244,47 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
                     for (int j = 0; j < NJ; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
             }
+        };
+
+        // Main loop: global loads for step k+1 are in flight (in registers) while the MFMAs of step k
+        // run out of LDS; LDS is double-buffered, one barrier per step.
+        if (nk > 0) {
+            load_tiles(0);
+            store_tiles(0);
+        }
+        __syncthreads();
+        for (int kc = 0; kc < nk; ++kc) {
+            const int buf = kc & 1;
+            if (kc + 1 < nk) load_tiles(kc + 1);
+            compute(buf);
             if (kc + 1 < nk) store_tiles(buf ^ 1);
             __syncthreads();
         }
 
         // ---- epilogue: round to bf16, per-channel statistics, stage through LDS, 16-byte stores.
         // D layout of the 32x32 MFMA: lane holds column (lane % 32); register r holds
-        // row 8*(r/4) + 4*(lane/32) + r%4.
+        // row 8*(r/4) + 4*(lane/32) + r%4.  Neighbouring lanes swap one value of each row pair so
+        // that every lane writes two adjacent columns of one row as a single 32-bit LDS store.
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
             float s1 = 0.f, s2 = 0.f;
             const int col = wn * TN + j * 32 + (lane & 31);
+            const bool odd = lane & 1;
 #pragma unroll
             for (int i = 0; i < MI; ++i) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const bf16_t b = f32_to_bf16(acc[i][j][r]);
-                    const int row = wm * TM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    Cst[row * LDC + col] = b;
-                    if (do_stats) {
-                        const float v = bf16_to_f32(b);
-                        s1 += v;
-                        s2 = fmaf(v, v, s2);
+                for (int r = 0; r < 16; r += 2) {
+                    const float v0 = acc[i][j][r], v1 = acc[i][j][r + 1];
+                    if (do_stats) {   // statistics of the values as stored (rows beyond M are exact zeros)
+                        const uint32_t own = pack_bf16x2(v0, v1);
+                        const float q0 = __uint_as_float(own << 16), q1 = __uint_as_float(own & 0xffff0000u);
+                        s1 += q0 + q1;
+                        s2 = fmaf(q0, q0, fmaf(q1, q1, s2));
                     }
+                    const float got = __uint_as_float(pair_swap(__float_as_uint(odd ? v0 : v1)));
+                    const uint32_t word = pack_bf16x2(odd ? got : v0, odd ? v1 : got);
+                    const int row = wm * TM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3) + (odd ? 1 : 0);
+                    *(uint32_t*)(Cst + row * LDC + (col & ~1)) = word;
                 }
             }
             if (do_stats && n0 + col < a.Cd) {
@@ -221,18 +301,18 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
 #pragma unroll
             for (int pss = 0; pss < BM / RPS; ++pss) {
                 const int row = pss * RPS + r0;
-                const long m = m0 + row;
-                if (m >= a.M || col >= a.Cd) continue;
+                const int mrow = s_row[row].dst;
+                if (mrow < 0 || col >= a.Cd) continue;
+                const long m = mrow;
                 u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
                 if (!DGRAD) {
                     *(u32x4*)(a.dst + m * a.Cd + col) = v;
                 } else {
                     const int dt = group_dt(col, a.fold);
-                    const int t = (int)((m / hw_d) % a.T);
-                    auto emit = [&](long mrow, bool with_value) {
+                    auto emit = [&](long mr, bool with_value) {
                         u32x4 o = with_value ? v : u32x4{0u, 0u, 0u, 0u};
                         if (a.addend) {
-                            const u32x4 ad = *(const u32x4*)(a.addend + mrow * a.Cd + col);
+                            const u32x4 ad = *(const u32x4*)(a.addend + mr * a.Cd + col);
 #pragma unroll
                             for (int q = 0; q < 4; ++q) {
                                 const float lo = bf16_to_f32((bf16_t)(o[q] & 0xffffu)) + bf16_to_f32((bf16_t)(ad[q] & 0xffffu));
@@ -240,11 +320,12 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
                                 o[q] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
                             }
                         }
-                        *(u32x4*)(a.dst + mrow * a.Cd + col) = o;
+                        *(u32x4*)(a.dst + mr * a.Cd + col) = o;
                     };
                     if (dt == 0) {
                         emit(m, true);
                     } else {
+                        const int t = (mrow / hw_d) % a.T;
                         if (t + dt >= 0 && t + dt < a.T) emit(m + (long)dt * hw_d, true);
                         // the frame that receives nothing from inside the clip
                         if ((dt == 1 && t == 0) || (dt == -1 && t == a.T - 1)) emit(m, false);
@@ -279,14 +360,54 @@ bool mfma_conv_supported(const ConvP& p) {
     if (p.Cin % 8 || p.Cout % 8) return false;
     if (p.fold % 8) return false;
     if (p.Cin > 8192 || p.Cout > 8192) return false;
-    if (p.K() > 0x3fffffffL || p.rows_in() * p.Cin > 0x7fffffffffffL) return false;
+    if (p.stride > 2) return false;   // the dgrad kernel enumerates at most four parity classes
+    if (p.KH > 8 || p.KW > 8) return false;        // tap-validity bit masks hold eight rows / columns
+    if (p.KT > 1 && p.fold > 0) return false;      // frame offsets stay within one frame either way
+    if (p.K() > 0x3fffffffL) return false;
+    if (p.rows_in() * (long)p.Cin > 0x7fffffffL * 64 || p.rows_in() > 0x7fffffffL || p.rows_out() > 0x7fffffffL) return false;
+    if ((long)p.H * p.W * p.Cin * (p.T + 2) > 0x7fffffffL || (long)p.Ho * p.Wo * p.Cout * (p.T + 2) > 0x7fffffffL) return false;
     return true;
+}
+
+// Fills the class table; returns the total number of M tiles.
+static int setup_classes(IgemmArgs& a, bool dgrad, int BM) {
+    if (!dgrad || a.stride == 1) {
+        a.ncls = 1; a.cstep = 1;
+        a.ph[0] = a.pw[0] = 0; a.hc[0] = a.Hd; a.wc[0] = a.Wd;
+        a.a0h[0] = a.a0w[0] = 0; a.nth[0] = a.KH; a.ntw[0] = a.KW;
+    } else {
+        const int s = a.stride;
+        a.ncls = s * s; a.cstep = s;
+        for (int ph = 0; ph < s; ++ph)
+            for (int pw = 0; pw < s; ++pw) {
+                const int c = ph * s + pw;
+                a.ph[c] = ph; a.pw[c] = pw;
+                a.hc[c] = (a.Hd - ph + s - 1) / s;
+                a.wc[c] = (a.Wd - pw + s - 1) / s;
+                // destination row dh = ph (mod s) meets flipped tap a when (dh - padh + a) % s == 0
+                a.a0h[c] = (((a.padh - ph) % s) + s) % s;
+                a.a0w[c] = (((a.padw - pw) % s) + s) % s;
+                a.nth[c] = a.a0h[c] < a.KH ? (a.KH - a.a0h[c] + s - 1) / s : 0;
+                a.ntw[c] = a.a0w[c] < a.KW ? (a.KW - a.a0w[c] + s - 1) / s : 0;
+                if (a.nth[c] == 0 || a.ntw[c] == 0) { a.nth[c] = a.ntw[c] = 0; }
+            }
+    }
+    a.mt0[0] = 0;
+    for (int c = 0; c < a.ncls; ++c) {
+        const long Mc = (long)a.F * a.hc[c] * a.wc[c];
+        a.mt0[c + 1] = a.mt0[c] + (int)((Mc + BM - 1) / BM);
+    }
+    for (int c = a.ncls; c < 4; ++c) {
+        a.ph[c] = a.pw[c] = a.hc[c] = a.wc[c] = a.a0h[c] = a.a0w[c] = a.nth[c] = a.ntw[c] = 0;
+        a.mt0[c + 1] = a.mt0[a.ncls];
+    }
+    return a.mt0[a.ncls];
 }
 
 // Persistent grid: two blocks per CU (a multiple of 8 so that a block stays on one XCD), capped by
 // the number of tile ids, which enumerate (group of 8 M tiles) x N tiles x (xcd).
-static int igemm_grid(long M, int Cd, int BM, int BN) {
-    const int mtiles = (int)((M + BM - 1) / BM), ntiles = (Cd + BN - 1) / BN;
+static int igemm_grid(int mtiles, int Cd, int BN) {
+    const int ntiles = (Cd + BN - 1) / BN;
     const int total = ((mtiles + 7) / 8) * 8 * ntiles;
     int grid = 2 * num_cu();
     grid = (grid / 8) * 8;
@@ -297,9 +418,9 @@ static int igemm_grid(long M, int Cd, int BM, int BN) {
 
 template <int BM, int BN, int WM, int WN, bool DGRAD>
 static int launch_igemm(IgemmArgs& a, hipStream_t s) {
-    a.mtiles = (int)((a.M + BM - 1) / BM);
+    const int mtiles = setup_classes(a, DGRAD, BM);
     a.ntiles = (a.Cd + BN - 1) / BN;
-    size_t smem = (size_t)2 * (BM + BN) * LDK * sizeof(bf16_t) + (size_t)2 * a.Cd * sizeof(float);
+    size_t smem = (size_t)2 * (BM + BN) * LDK * sizeof(bf16_t) + (size_t)BM * sizeof(RowInfo) + (size_t)2 * a.Cd * sizeof(float);
     auto kern = igemm_kernel<BM, BN, WM, WN, DGRAD>;
     static bool configured = false;
     if (!configured) {
@@ -307,7 +428,7 @@ static int launch_igemm(IgemmArgs& a, hipStream_t s) {
             return fail(TSM_ERR_LAUNCH, "igemm: cannot raise dynamic LDS limit");
         configured = true;
     }
-    const int grid = igemm_grid(a.M, a.Cd, BM, BN);
+    const int grid = igemm_grid(mtiles, a.Cd, BN);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, a);
     // class names carry the tile shape so that they map one-to-one onto kernel symbols
     return check_launch(DGRAD ? (BN == 64 ? "igemm_dgrad_128x64" : "igemm_dgrad_128x128")
@@ -316,12 +437,14 @@ static int launch_igemm(IgemmArgs& a, hipStream_t s) {
 
 template <bool DGRAD>
 static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
-    if (a.M == 0) return TSM_OK;
+    if ((long)a.F * a.Hd * a.Wd == 0) return TSM_OK;
     if (a.Cd <= 64) return launch_igemm<128, 64, 4, 1, DGRAD>(a, s);
     return launch_igemm<128, 128, 2, 2, DGRAD>(a, s);
 }
 
-int conv_mfma_fwd_blocks(const ConvP& p) { return igemm_grid(p.rows_out(), p.Cout, 128, p.Cout <= 64 ? 64 : 128); }
+int conv_mfma_fwd_blocks(const ConvP& p) {
+    return igemm_grid((int)((p.rows_out() + 127) / 128), p.Cout, p.Cout <= 64 ? 64 : 128);
+}
 
 int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, float* stats, hipStream_t s) {
     IgemmArgs a;
@@ -332,7 +455,6 @@ int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, 
     a.KT = p.KT; a.KH = p.KH; a.KW = p.KW;
     a.stride = p.stride; a.padh = p.pad; a.padw = p.pad;
     a.fold = p.fold;
-    a.M = p.rows_out();
     a.K = (int)p.K();
     return dispatch_igemm<false>(a, s);
 }
@@ -347,7 +469,6 @@ int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* 
     a.KT = p.KT; a.KH = p.KH; a.KW = p.KW;
     a.stride = p.stride; a.padh = p.KH - 1 - p.pad; a.padw = p.KW - 1 - p.pad;
     a.fold = p.fold;
-    a.M = p.rows_in();
     a.K = p.taps() * p.Cout;
     return dispatch_igemm<true>(a, s);
 }
@@ -356,10 +477,10 @@ int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* 
 // Weight gradient, D[Cout x K] = dy^T [Cout x pixels] * gathered x [pixels x K] with
 // K = taps * Cin enumerated tap-major (the packed-weight order).  Per block: a
 // [BCO x BCI] tile of D reduced over a chunk of output pixels, added with fp32
-// atomics to dw in the ABI order [Cout][Cin][taps].  Both operands are needed with the pixel index contiguous, so the
-// 16-byte global rows ([pixel][channel]) are transposed on their way into LDS:
-// each thread pairs two consecutive pixels of eight channels into eight 32-bit
-// LDS writes.
+// atomics to dw.  Both MFMA operands are needed with the pixel index contiguous, so
+// the 16-byte global rows ([pixel][channel]) are transposed on their way into LDS:
+// each thread takes four consecutive pixels of eight channels and writes, per
+// channel, the four pixels as one 64-bit LDS store.
 struct WgradArgs {
     const bf16_t* x;
     const bf16_t* dy;
@@ -380,11 +501,10 @@ struct WgradArgs {
 static constexpr int WMK = 64;        // pixels per main-loop step
 static constexpr int LDT = WMK + 8;   // pitch of the transposed tiles
 
-// Element offset of pixel pair `pp` (two pixels = one 32-bit word) in the transposed
-// tile row `row`: groups of four words (one 16-byte fragment) are XOR-swizzled with
-// the row's channel-vector index so that the eight lanes writing eight channel vectors
-// of the same pixels fall into different LDS banks.
-__device__ __forceinline__ int swz_pair(int pp, int row) { return ((((pp >> 2) ^ ((row >> 3) & 7)) << 2) | (pp & 3)) * 2; }
+// Element offset of pixel quad `pq` (four pixels = 8 bytes) in the transposed tile row `row`: the
+// 16-byte groups of eight pixels are XOR-swizzled with the row's channel-vector index so that lanes
+// writing different channel vectors of the same pixels fall into different LDS banks.
+__device__ __forceinline__ int swz_quad(int pq, int row) { return (((pq >> 1) ^ ((row >> 3) & 7)) << 3) | ((pq & 1) << 2); }
 // Element offset of the 8-pixel fragment `g` (0..7) of row `row`.
 __device__ __forceinline__ int swz_frag(int g, int row) { return (g ^ ((row >> 3) & 7)) * 8; }
 
@@ -392,8 +512,12 @@ template <int BCO, int BCI>
 __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs a) {
     constexpr int TM = BCO / 2, TN = BCI / 2;
     constexpr int MI = TM / 32, NJ = TN / 32;
+    constexpr int AV = BCO / 8, BV = BCI / 8;         // 16-byte vectors per tile row
+    constexpr int AITEMS = AV * (WMK / 4), BITEMS = BV * (WMK / 4);   // (vector, pixel quad) work items
+    static_assert(AITEMS <= 256 && BITEMS <= 256, "one item per thread");
     __shared__ __attribute__((aligned(16))) bf16_t At[2][BCO][LDT];   // dy^T  [co][pixel]
     __shared__ __attribute__((aligned(16))) bf16_t Bt[2][BCI][LDT];   // xs^T  [column][pixel]
+    __shared__ RowInfo s_info[3][WMK];                                // per-pixel gather origin, three steps deep
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -402,31 +526,56 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs a) {
     const long mbeg = (long)blockIdx.x * a.chunk;
     long mend = mbeg + a.chunk;
     if (mend > a.M) mend = a.M;
+    if (mbeg >= mend) return;
     const int hw = a.Ho * a.Wo;
+    const bf16_t* zero_page = (const bf16_t*)g_zero_page;
 
-    // loader mapping: consecutive lanes read consecutive 16-byte pieces of one row;
-    // every thread owns pixel pairs (2*pp, 2*pp+1) of channel vector `vec`.
-    constexpr int AV = BCO / 8, BV = BCI / 8;         // vectors per row
-    constexpr int AP = (32 * AV + 255) / 256;         // (pair, vec) items per thread
-    constexpr int BP = (32 * BV + 255) / 256;
-
-    // this thread's B columns: 8 consecutive K indices = 8 channels of one tap
-    int b_ci[BP], b_kh[BP], b_kw[BP], b_df[BP];
-#pragma unroll
-    for (int q = 0; q < BP; ++q) {
-        const int vec = (q * 256 + tid) % BV;
-        const int j = j0 + vec * 8;
+    // ---- this thread's work items: consecutive lanes take consecutive 16-byte pieces of a pixel row
+    const int avec = tid % AV, apq = tid / AV;        // dy: channels co0 + 8*avec.., pixels 4*apq..4*apq+3
+    const int bvec = tid % BV, bpq = tid / BV;        // x : columns  j0 + 8*bvec..
+    const bool a_item = tid < AITEMS, b_item = tid < BITEMS;
+    const bool a_chan_ok = co0 + avec * 8 < a.Cout;
+    // B column -> (tap, channel): constant for the thread's whole life
+    uint32_t need = 0xffffffffu;   // unsatisfiable: column beyond K
+    int boff = 0;
+    {
+        const int j = j0 + bvec * 8;
         if (j < a.K) {
-            const int tap = j / a.Cin;
-            b_ci[q] = j - tap * a.Cin;
-            b_kw[q] = tap % a.KW;
-            b_kh[q] = (tap / a.KW) % a.KH;
-            b_df[q] = tap / (a.KW * a.KH) - a.KT / 2 + group_dt(b_ci[q], a.fold);
-        } else {
-            b_ci[q] = -1;
-            b_kh[q] = b_kw[q] = b_df[q] = 0;
+            const int tap = j / a.Cin, ci = j - tap * a.Cin;
+            const int kw = tap % a.KW, kh = (tap / a.KW) % a.KH, kt = tap / (a.KW * a.KH);
+            const int d = kt - a.KT / 2 + group_dt(ci, a.fold);
+            need = (1u << kh) | (1u << (8 + kw)) | (d > 0 ? 1u << 30 : 0u) | (d < 0 ? 1u << 31 : 0u);
+            boff = d * a.H * a.W * a.Cin + (kh * a.W + kw) * a.Cin + ci;
         }
     }
+
+    // ---- per-step decode of the 64 pixels' gather origins (one pixel per thread of the first wavefront)
+    auto decode = [&](int st) {
+        if (tid < WMK) {
+            const long m = mbeg + (long)st * WMK + tid;
+            RowInfo info;
+            info.off = 0;
+            info.mask = 0;
+            info.dst = 0;
+            if (m < mend) {
+                const int f = (int)(m / hw);
+                const int pix = (int)(m - (long)f * hw);
+                const int oh = pix / a.Wo, ow = pix - oh * a.Wo;
+                const int ih = oh * a.stride - a.pad, iw = ow * a.stride - a.pad;
+                const int t = f % a.T;
+                uint32_t mask = 0;
+                for (int kh = 0; kh < a.KH; ++kh)
+                    if (ih + kh >= 0 && ih + kh < a.H) mask |= 1u << kh;
+                for (int kw = 0; kw < a.KW; ++kw)
+                    if (iw + kw >= 0 && iw + kw < a.W) mask |= 1u << (8 + kw);
+                if (t + 1 < a.T) mask |= 1u << 30;
+                if (t >= 1) mask |= 1u << 31;
+                info.off = ((long)f * a.H * a.W + (long)ih * a.W + iw) * a.Cin;
+                info.mask = mask;
+            }
+            s_info[st % 3][tid] = info;
+        }
+    };
 
     f32x16 acc[MI][NJ];
 #pragma unroll
@@ -436,115 +585,91 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    u32x4 ar[AP][2], br[BP][2];
+    u32x4 ar[4], br[4];
 
-    auto load = [&](long mstep) {
+    auto load = [&](int st) {
+        const long mstep = mbeg + (long)st * WMK;
+        if (a_item) {
 #pragma unroll
-        for (int q = 0; q < AP; ++q) {
-            const int item = q * 256 + tid;
-            const int vec = item % AV, pp = item / AV;
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const long m = mstep + 2 * pp + h;
-                const int co = co0 + vec * 8;
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (pp < 32 && m < mend && co < a.Cout) v = *(const u32x4*)(a.dy + m * a.Cout + co);
-                ar[q][h] = v;
+            for (int h = 0; h < 4; ++h) {
+                const long m = mstep + 4 * apq + h;
+                const bf16_t* p = (a_chan_ok && m < mend) ? a.dy + m * a.Cout + co0 + avec * 8 : zero_page;
+                ar[h] = *(const u32x4*)p;
             }
         }
+        if (b_item) {
 #pragma unroll
-        for (int q = 0; q < BP; ++q) {
-            const int pp = (q * 256 + tid) / BV;
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const long m = mstep + 2 * pp + h;
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (pp < 32 && m < mend && b_ci[q] >= 0) {
-                    const int f = (int)(m / hw);
-                    const int pix = (int)(m - (long)f * hw);
-                    const int oh = pix / a.Wo, ow = pix - oh * a.Wo;
-                    const int ih = oh * a.stride + b_kh[q] - a.pad, iw = ow * a.stride + b_kw[q] - a.pad;
-                    const int ts = f % a.T + b_df[q];
-                    if (ts >= 0 && ts < a.T && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W)
-                        v = *(const u32x4*)(a.x + (((long)(f + b_df[q]) * a.H + ih) * a.W + iw) * a.Cin + b_ci[q]);
-                }
-                br[q][h] = v;
+            for (int h = 0; h < 4; ++h) {
+                const RowInfo ri = s_info[st % 3][4 * bpq + h];
+                const bf16_t* p = ((ri.mask & need) == need) ? a.x + ri.off + boff : zero_page;
+                br[h] = *(const u32x4*)p;
             }
+        }
+    };
+    // four pixels x eight channels -> per channel one 8-byte store of four pixels
+    auto scatter = [&](bf16_t (*Tt)[LDT], int vec, int pq, const u32x4* v) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint2 even, odd;
+            even.x = __builtin_amdgcn_perm(v[1][e], v[0][e], 0x05040100u);
+            even.y = __builtin_amdgcn_perm(v[3][e], v[2][e], 0x05040100u);
+            odd.x = __builtin_amdgcn_perm(v[1][e], v[0][e], 0x07060302u);
+            odd.y = __builtin_amdgcn_perm(v[3][e], v[2][e], 0x07060302u);
+            *(uint2*)&Tt[vec * 8 + 2 * e][swz_quad(pq, vec * 8)] = even;
+            *(uint2*)&Tt[vec * 8 + 2 * e + 1][swz_quad(pq, vec * 8)] = odd;
         }
     };
     auto store = [&](int buf) {
-#pragma unroll
-        for (int q = 0; q < AP; ++q) {
-            const int item = q * 256 + tid;
-            const int vec = item % AV, pp = item / AV;
-            if (pp < 32) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t lo = ar[q][0][e], hi = ar[q][1][e];
-                    *(uint32_t*)&At[buf][vec * 8 + 2 * e][swz_pair(pp, vec * 8)] = (lo & 0xffffu) | (hi << 16);
-                    *(uint32_t*)&At[buf][vec * 8 + 2 * e + 1][swz_pair(pp, vec * 8)] = (lo >> 16) | (hi & 0xffff0000u);
-                }
-            }
-        }
-#pragma unroll
-        for (int q = 0; q < BP; ++q) {
-            const int item = q * 256 + tid;
-            const int vec = item % BV, pp = item / BV;
-            if (pp < 32) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t lo = br[q][0][e], hi = br[q][1][e];
-                    *(uint32_t*)&Bt[buf][vec * 8 + 2 * e][swz_pair(pp, vec * 8)] = (lo & 0xffffu) | (hi << 16);
-                    *(uint32_t*)&Bt[buf][vec * 8 + 2 * e + 1][swz_pair(pp, vec * 8)] = (lo >> 16) | (hi & 0xffff0000u);
-                }
-            }
-        }
+        if (a_item) scatter(At[buf], avec, apq, ar);
+        if (b_item) scatter(Bt[buf], bvec, bpq, br);
     };
 
-    if (mbeg < mend) {
-        const int nsteps = (int)((mend - mbeg + WMK - 1) / WMK);
-        load(mbeg);
-        store(0);
-        __syncthreads();
-        for (int st = 0; st < nsteps; ++st) {
-            const int buf = st & 1;
-            if (st + 1 < nsteps) load(mbeg + (long)(st + 1) * WMK);
+    const int nsteps = (int)((mend - mbeg + WMK - 1) / WMK);
+    decode(0);
+    if (nsteps > 1) decode(1);
+    __syncthreads();
+    load(0);
+    store(0);
+    __syncthreads();
+    for (int st = 0; st < nsteps; ++st) {
+        const int buf = st & 1;
+        if (st + 2 < nsteps) decode(st + 2);
+        if (st + 1 < nsteps) load(st + 1);
 #pragma unroll
-            for (int ks = 0; ks < WMK / 16; ++ks) {
-                bf16x8 af[MI], bfr[NJ];
+        for (int ks = 0; ks < WMK / 16; ++ks) {
+            bf16x8 af[MI], bfr[NJ];
 #pragma unroll
-                for (int i = 0; i < MI; ++i) {
-                    const int row = wm * TM + i * 32 + (lane & 31);
-                    af[i] = *(const bf16x8*)&At[buf][row][swz_frag(2 * ks + (lane >> 5), row)];
-                }
-#pragma unroll
-                for (int j = 0; j < NJ; ++j) {
-                    const int row = wn * TN + j * 32 + (lane & 31);
-                    bfr[j] = *(const bf16x8*)&Bt[buf][row][swz_frag(2 * ks + (lane >> 5), row)];
-                }
-#pragma unroll
-                for (int i = 0; i < MI; ++i)
-#pragma unroll
-                    for (int j = 0; j < NJ; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            for (int i = 0; i < MI; ++i) {
+                const int row = wm * TM + i * 32 + (lane & 31);
+                af[i] = *(const bf16x8*)&At[buf][row][swz_frag(2 * ks + (lane >> 5), row)];
             }
-            if (st + 1 < nsteps) store(buf ^ 1);
-            __syncthreads();
-        }
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
-                const int col = j0 + wn * TN + j * 32 + (lane & 31);
-                const int tap = col / a.Cin, ci = col - tap * a.Cin;
-                if (col >= a.K || ci >= a.cin_real) continue;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int co = co0 + wm * TM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    if (co < a.Cout) atomicAdd(a.dw + (long)co * a.so + (long)ci * a.si + (long)tap * a.st, acc[i][j][r]);
-                }
+                const int row = wn * TN + j * 32 + (lane & 31);
+                bfr[j] = *(const bf16x8*)&Bt[buf][row][swz_frag(2 * ks + (lane >> 5), row)];
             }
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        if (st + 1 < nsteps) store(buf ^ 1);
+        __syncthreads();
     }
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const int col = j0 + wn * TN + j * 32 + (lane & 31);
+            const int tap = col / a.Cin, ci = col - tap * a.Cin;
+            if (col >= a.K || ci >= a.cin_real) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int co = co0 + wm * TM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (co < a.Cout) atomicAdd(a.dw + (long)co * a.so + (long)ci * a.si + (long)tap * a.st, acc[i][j][r]);
+            }
+        }
 }
 
 int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, bool packed,
