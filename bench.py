@@ -156,6 +156,27 @@ def main():
         "roofline": roof, "kernel_classes": classes, "profiled_step_ms": prof_total,
     }
 
+    # the stand-alone shift (a pure gather copy) at the configs[1] activation shape x 64 clips: HBM GB/s
+    sh_shape = (64, 8, 256, 56, 56)
+    nbytes = int(np.prod(sh_shape)) * 2
+    xs = torch.empty(nbytes // 2, dtype=torch.bfloat16, device="cuda").normal_()
+    ys = torch.empty_like(xs)
+    for fn in (B.tsm_shift_fwd, B.tsm_shift_bwd):
+        fn(xs, ys, *sh_shape, 8, B.TSM_BF16, B.TSM_NTHWC, stream)
+    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 20
+    s0.record(stream)
+    for _ in range(reps):
+        B.tsm_shift_fwd(xs, ys, *sh_shape, 8, B.TSM_BF16, B.TSM_NTHWC, stream)
+    s1.record(stream)
+    torch.cuda.synchronize()
+    sh_ms = s0.elapsed_time(s1) / reps
+    sh_gbs = 2.0 * nbytes / (sh_ms * 1e-3) / 1e9
+    out["shift"] = {"shape": list(sh_shape), "dtype": "bf16", "layout": "NTHWC", "ms": sh_ms, "achieved": sh_gbs,
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": sh_gbs / PEAK_HBM_GBS,
+                    "bytes": "one read + one write of the tensor"}
+    del xs, ys
+
     if not args.no_cpu_baseline:
         from oracle import tsm_oracle as O
         P = O.unflatten_params(flat.astype(np.float64))
