@@ -14,6 +14,7 @@
 //
 // 256 threads = 4 wavefronts of 64; v_mfma_f32_32x32x16_bf16; operands staged
 // through LDS with 16-byte loads; fp32 accumulation.
+#include <stdlib.h>
 #include "internal.h"
 
 namespace tsm {
@@ -90,8 +91,8 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
     bf16_t* As = (bf16_t*)smem;                      // [2][BM][LDK]
     bf16_t* Bs = As + 2 * BM * LDK;                  // [2][BN][LDK]
     bf16_t* Cst = (bf16_t*)smem;                     // [BM][LDC], reuses As/Bs after the main loop
-    RowInfo* s_row = (RowInfo*)(Bs + 2 * BN * LDK);  // [BM]
-    float* s_sum = (float*)(s_row + BM);             // [Cd] sums then [Cd] sums of squares
+    RowInfo* s_row = (RowInfo*)(Bs + 2 * BN * LDK);  // [2][BM]: rows of the current and of the next tile
+    float* s_sum = (float*)(s_row + 2 * BM);         // [Cd] sums then [Cd] sums of squares
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -104,34 +105,41 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
     if (do_stats) {
         for (int c = tid; c < 2 * a.Cd; c += 256) s_sum[c] = 0.f;
     }
-    __syncthreads();
 
     const int hw_d = a.Hd * a.Wd;
     const int hw_s = a.Hs * a.Ws;
     const int frame_el = hw_s * a.Cs;               // elements per source frame
-    const int total_tiles = ((a.mt0[a.ncls] + 7) / 8) * 8 * a.ntiles;  // M tiles padded to whole groups of 8
+    const int mtiles = a.mt0[a.ncls];
+    const int total_tiles = ((mtiles + 7) / 8) * 8 * a.ntiles;  // M tiles padded to whole groups of 8
 
-    for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
-        // Tiles that share an M range sit on the same XCD (ids 8 apart) so the
-        // gathered rows are served by that XCD's L2.
-        const int xcd = tile & 7, slot = tile >> 3;
-        const int mt = (slot / a.ntiles) * 8 + xcd;
-        const int nt = slot % a.ntiles;
-        if (mt >= a.mt0[a.ncls]) continue;  // the last group of 8 M tiles may be ragged (block-uniform branch)
-        int cls = 0;
-        while (cls + 1 < a.ncls && mt >= a.mt0[cls + 1]) ++cls;
-        const int hc = a.hc[cls], wc = a.wc[cls];
-        const long Mc = (long)a.F * hc * wc;
-        const long m0 = (long)(mt - a.mt0[cls]) * BM;
-        const int n0 = nt * BN;
-        const int nth = a.nth[cls], ntw = a.ntw[cls], a0h = a.a0h[cls], a0w = a.a0w[cls];
-        const int ntaps = a.KT * nth * ntw;
-        const int Kc = ntaps * a.Cs;
-        const int nk = (Kc + BK - 1) / BK;
+    // Tile ids: tiles that share an M range sit on the same XCD (ids 8 apart) so the gathered rows are
+    // served by that XCD's L2.  The last group of 8 M tiles may be ragged: such ids are skipped.
+    auto tile_mt = [&](int tile) { return ((tile >> 3) / a.ntiles) * 8 + (tile & 7); };
+    auto next_tile = [&](int tile) {
+        while (tile < total_tiles && tile_mt(tile) >= mtiles) tile += gridDim.x;
+        return tile < total_tiles ? tile : -1;
+    };
 
-        // ---- decode the tile's rows once, one row per thread, into LDS
+    // Everything the main loop needs to know about one tile.
+    struct Ctx {
+        int n0, nth, ntw, a0h, a0w, ntaps, nk;
+        const bf16_t* aptr[PA];
+        uint32_t amask[PA];
+        const bf16_t* bptr[PB];
+        // position of the next K step to fetch: class-local tap (kt, th, tw), first channel of this
+        // thread's 16-byte vector, flat tap index; advanced by load_tiles without any division
+        int kt, th, tw, ch, ltap;
+    };
+
+    // ---- decode a tile's rows, one row per thread, into LDS row buffer rb
+    auto decode_rows = [&](int tile, int rb) {
         if (tid < BM) {
-            const long m = m0 + tid;
+            const int mt = tile_mt(tile);
+            int cls = 0;
+            while (cls + 1 < a.ncls && mt >= a.mt0[cls + 1]) ++cls;
+            const int hc = a.hc[cls], wc = a.wc[cls];
+            const long Mc = (long)a.F * hc * wc;
+            const long m = (long)(mt - a.mt0[cls]) * BM + tid;
             RowInfo info;
             info.off = 0;
             info.mask = 0;
@@ -143,13 +151,13 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
                 const int dh = qh * a.cstep + a.ph[cls], dw = qw * a.cstep + a.pw[cls];
                 // source coordinate of class-local tap (th, tw) is (oh + th, ow + tw); for a strided dgrad
                 // the division by the stride is exact by construction of the class
-                const int oh = DGRAD ? (dh - a.padh + a0h) / a.cstep : dh * a.stride - a.padh;
-                const int ow = DGRAD ? (dw - a.padw + a0w) / a.cstep : dw * a.stride - a.padw;
+                const int oh = DGRAD ? (dh - a.padh + a.a0h[cls]) / a.cstep : dh * a.stride - a.padh;
+                const int ow = DGRAD ? (dw - a.padw + a.a0w[cls]) / a.cstep : dw * a.stride - a.padw;
                 const int t = f % a.T;
                 uint32_t mask = 0;
-                for (int th = 0; th < nth; ++th)
+                for (int th = 0; th < a.nth[cls]; ++th)
                     if (oh + th >= 0 && oh + th < a.Hs) mask |= 1u << th;
-                for (int tw = 0; tw < ntw; ++tw)
+                for (int tw = 0; tw < a.ntw[cls]; ++tw)
                     if (ow + tw >= 0 && ow + tw < a.Ws) mask |= 1u << (8 + tw);
                 if (t + 1 < a.T) mask |= 1u << 30;
                 if (t >= 1) mask |= 1u << 31;
@@ -157,25 +165,104 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
                 info.mask = mask;
                 info.dst = (f * a.Hd + dh) * a.Wd + dw;
             }
-            s_row[tid] = info;
+            s_row[rb * BM + tid] = info;
         }
-        __syncthreads();
-
-        // this thread's gather rows and weight rows
-        const bf16_t* aptr[PA];
-        uint32_t amask[PA];
+    };
+    // ---- per-thread view of a decoded tile (call after the barrier that follows decode_rows)
+    auto make_ctx = [&](int tile, int rb) {
+        Ctx c;
+        const int mt = tile_mt(tile);
+        int cls = 0;
+        while (cls + 1 < a.ncls && mt >= a.mt0[cls + 1]) ++cls;
+        c.n0 = ((tile >> 3) % a.ntiles) * BN;
+        c.nth = a.nth[cls]; c.ntw = a.ntw[cls]; c.a0h = a.a0h[cls]; c.a0w = a.a0w[cls];
+        c.ntaps = a.KT * c.nth * c.ntw;
+        c.nk = (c.ntaps * a.Cs + BK - 1) / BK;
 #pragma unroll
         for (int i = 0; i < PA; ++i) {
-            const RowInfo ri = s_row[i * RPP + lrow];
-            aptr[i] = a.src + ri.off;
-            amask[i] = ri.mask;
+            const RowInfo ri = s_row[rb * BM + i * RPP + lrow];
+            c.aptr[i] = a.src + ri.off;
+            c.amask[i] = ri.mask;
         }
-        const bf16_t* bptr[PB];
 #pragma unroll
         for (int j = 0; j < PB; ++j) {
-            const int n = n0 + j * RPP + lrow;
-            bptr[j] = n < a.Cd ? a.wp + (long)n * a.K : nullptr;
+            const int n = c.n0 + j * RPP + lrow;
+            c.bptr[j] = n < a.Cd ? a.wp + (long)n * a.K : nullptr;
         }
+        c.kt = c.th = c.tw = c.ltap = 0;
+        c.ch = kvec * 8;
+        while (c.ch >= a.Cs) {   // fewer than 64 channels: this thread's vector starts in a later tap
+            c.ch -= a.Cs;
+            ++c.ltap;
+            if (++c.tw >= c.ntw) { c.tw = 0; if (++c.th >= c.nth) { c.th = 0; ++c.kt; } }
+        }
+        return c;
+    };
+
+    u32x4 areg[PA], breg[PB];   // one K step of gathered data in flight
+
+    // Fetches the next K step of tile `c` (steps are fetched strictly in order) and advances c's position.
+    auto load_tiles = [&](Ctx& c, u32x4* areg, u32x4* breg) {
+        // steps beyond the tile's K range (harmless filler loads) read the zero page
+        const bool kvalid = c.ltap < c.ntaps;
+        const int ch = c.ch, th_ = c.th, tw_ = c.tw, kt = c.kt;
+        const int d = kt - a.KT / 2 + (DGRAD ? 0 : group_dt(ch, a.fold));   // frame offset, in {-1, 0, 1}
+        // bits a row's mask must have for this tap
+        const uint32_t need = (1u << th_) | (1u << (8 + tw_)) | (d > 0 ? 1u << 30 : 0u) | (d < 0 ? 1u << 31 : 0u);
+        const int aoff = d * frame_el + (th_ * a.Ws + tw_) * a.Cs + ch;
+#pragma unroll
+        for (int i = 0; i < PA; ++i) {
+            const bool ok = kvalid && (c.amask[i] & need) == need;
+            const bf16_t* p = ok ? c.aptr[i] + aoff : zero_page;
+            areg[i] = *(const u32x4*)p;
+        }
+        const int ta = c.a0h + th_ * a.cstep, tb = c.a0w + tw_ * a.cstep;   // (flipped) tap coordinates
+        const int woff = ((kt * a.KH + ta) * a.KW + tb) * a.Cs + ch;
+#pragma unroll
+        for (int j = 0; j < PB; ++j) {
+            const bf16_t* p = (kvalid && c.bptr[j]) ? c.bptr[j] + woff : zero_page;
+            breg[j] = *(const u32x4*)p;
+        }
+        // advance by BK channels; when channels are a multiple of 64 this is uniform over the block
+        c.ch += BK;
+        if (uniform_tap) {
+            if (c.ch >= a.Cs) {
+                c.ch -= a.Cs;
+                ++c.ltap;
+                if (++c.tw >= c.ntw) { c.tw = 0; if (++c.th >= c.nth) { c.th = 0; ++c.kt; } }
+            }
+        } else {
+            while (c.ch >= a.Cs) {
+                c.ch -= a.Cs;
+                ++c.ltap;
+                if (++c.tw >= c.ntw) { c.tw = 0; if (++c.th >= c.nth) { c.th = 0; ++c.kt; } }
+            }
+        }
+    };
+    auto store_tiles = [&](int buf) {
+        bf16_t* Ab = As + buf * BM * LDK;
+        bf16_t* Bb = Bs + buf * BN * LDK;
+#pragma unroll
+        for (int i = 0; i < PA; ++i) *(u32x4*)(Ab + (i * RPP + lrow) * LDK + kvec * 8) = areg[i];
+#pragma unroll
+        for (int j = 0; j < PB; ++j) *(u32x4*)(Bb + (j * RPP + lrow) * LDK + kvec * 8) = breg[j];
+    };
+
+    int tile = next_tile(blockIdx.x);
+    int rb = 0;
+    Ctx ctx;
+    if (tile >= 0) decode_rows(tile, 0);
+    __syncthreads();   // also orders the s_sum initialisation
+    if (tile >= 0) {
+        ctx = make_ctx(tile, 0);
+        load_tiles(ctx, areg, breg);
+    }
+
+    while (tile >= 0) {
+        // The next tile's rows are decoded now and its first K step is fetched before this tile's
+        // epilogue, so that the memory latency of a tile's first loads hides behind the previous epilogue.
+        const int ntile = next_tile(tile + gridDim.x);
+        if (ntile >= 0) decode_rows(ntile, rb ^ 1);
 
         f32x16 acc[MI][NJ];
 #pragma unroll
@@ -185,49 +272,6 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-        u32x4 areg[PA], breg[PB];
-
-        auto load_tiles = [&](int kc) {
-            int ltap, c;
-            if (uniform_tap) {
-                const int kk0 = kc * BK;
-                ltap = kk0 / a.Cs;                    // uniform over the block: scalar arithmetic
-                c = kk0 - ltap * a.Cs + kvec * 8;
-            } else {
-                const int kk = kc * BK + kvec * 8;
-                ltap = kk / a.Cs;
-                c = kk - ltap * a.Cs;
-            }
-            const bool kvalid = ltap < ntaps;
-            const int tw_ = ltap % ntw;
-            const int th_ = (ltap / ntw) % nth;
-            const int kt = ltap / (ntw * nth);
-            const int d = kt - a.KT / 2 + (DGRAD ? 0 : group_dt(c, a.fold));   // frame offset, in {-1, 0, 1}
-            // bits a row's mask must have for this tap
-            const uint32_t need = (1u << th_) | (1u << (8 + tw_)) | (d > 0 ? 1u << 30 : 0u) | (d < 0 ? 1u << 31 : 0u);
-            const int aoff = d * frame_el + (th_ * a.Ws + tw_) * a.Cs + c;
-#pragma unroll
-            for (int i = 0; i < PA; ++i) {
-                const bool ok = kvalid && (amask[i] & need) == need;
-                const bf16_t* p = ok ? aptr[i] + aoff : zero_page;
-                areg[i] = *(const u32x4*)p;
-            }
-            const int ta = a0h + th_ * a.cstep, tb = a0w + tw_ * a.cstep;   // (flipped) tap coordinates
-            const int woff = ((kt * a.KH + ta) * a.KW + tb) * a.Cs + c;
-#pragma unroll
-            for (int j = 0; j < PB; ++j) {
-                const bf16_t* p = (kvalid && bptr[j]) ? bptr[j] + woff : zero_page;
-                breg[j] = *(const u32x4*)p;
-            }
-        };
-        auto store_tiles = [&](int buf) {
-            bf16_t* Ab = As + buf * BM * LDK;
-            bf16_t* Bb = Bs + buf * BN * LDK;
-#pragma unroll
-            for (int i = 0; i < PA; ++i) *(u32x4*)(Ab + (i * RPP + lrow) * LDK + kvec * 8) = areg[i];
-#pragma unroll
-            for (int j = 0; j < PB; ++j) *(u32x4*)(Bb + (j * RPP + lrow) * LDK + kvec * 8) = breg[j];
-        };
         auto compute = [&](int buf) {
             const bf16_t* Ab = As + buf * BM * LDK + (wm * TM + (lane & 31)) * LDK + 8 * (lane >> 5);
             const bf16_t* Bb = Bs + buf * BN * LDK + (wn * TN + (lane & 31)) * LDK + 8 * (lane >> 5);
@@ -246,19 +290,24 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
             }
         };
 
-        // Main loop: global loads for step k+1 are in flight (in registers) while the MFMAs of step k
-        // run out of LDS; LDS is double-buffered, one barrier per step.
-        if (nk > 0) {
-            load_tiles(0);
-            store_tiles(0);
-        }
+        // Main loop: the gather of step k+1 is in flight (in registers) while the MFMAs of step k run out
+        // of LDS; LDS is double-buffered, one barrier per step.  On entry the registers hold step 0 of this
+        // tile.  Loads and LDS stores are issued unconditionally (steps past the end read the zero page and
+        // land in a buffer nobody reads), which keeps the loop body free of branches.
+        const int nk = ctx.nk;
+        store_tiles(0);
         __syncthreads();
         for (int kc = 0; kc < nk; ++kc) {
             const int buf = kc & 1;
-            if (kc + 1 < nk) load_tiles(kc + 1);
+            load_tiles(ctx, areg, breg);
             compute(buf);
-            if (kc + 1 < nk) store_tiles(buf ^ 1);
+            store_tiles(buf ^ 1);
             __syncthreads();
+        }
+        const int n0 = ctx.n0;
+        if (ntile >= 0) {
+            ctx = make_ctx(ntile, rb ^ 1);
+            load_tiles(ctx, areg, breg);
         }
 
         // ---- epilogue: round to bf16, per-channel statistics, stage through LDS, 16-byte stores.
@@ -301,7 +350,7 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
 #pragma unroll
             for (int pss = 0; pss < BM / RPS; ++pss) {
                 const int row = pss * RPS + r0;
-                const int mrow = s_row[row].dst;
+                const int mrow = s_row[rb * BM + row].dst;
                 if (mrow < 0 || col >= a.Cd) continue;
                 const long m = mrow;
                 u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
@@ -315,9 +364,9 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
                             const u32x4 ad = *(const u32x4*)(a.addend + mr * a.Cd + col);
 #pragma unroll
                             for (int q = 0; q < 4; ++q) {
-                                const float lo = bf16_to_f32((bf16_t)(o[q] & 0xffffu)) + bf16_to_f32((bf16_t)(ad[q] & 0xffffu));
-                                const float hi = bf16_to_f32((bf16_t)(o[q] >> 16)) + bf16_to_f32((bf16_t)(ad[q] >> 16));
-                                o[q] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+                                const float lo = __uint_as_float(o[q] << 16) + __uint_as_float(ad[q] << 16);
+                                const float hi = __uint_as_float(o[q] & 0xffff0000u) + __uint_as_float(ad[q] & 0xffff0000u);
+                                o[q] = pack_bf16x2(lo, hi);
                             }
                         }
                         *(u32x4*)(a.dst + mr * a.Cd + col) = o;
@@ -334,6 +383,8 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
             }
         }
         __syncthreads();
+        tile = ntile;
+        rb ^= 1;
     }
 
     if (do_stats) {   // every block publishes its row, zeros included: the consumer adds all rows up
@@ -420,7 +471,7 @@ template <int BM, int BN, int WM, int WN, bool DGRAD>
 static int launch_igemm(IgemmArgs& a, hipStream_t s) {
     const int mtiles = setup_classes(a, DGRAD, BM);
     a.ntiles = (a.Cd + BN - 1) / BN;
-    size_t smem = (size_t)2 * (BM + BN) * LDK * sizeof(bf16_t) + (size_t)BM * sizeof(RowInfo) + (size_t)2 * a.Cd * sizeof(float);
+    size_t smem = (size_t)2 * (BM + BN) * LDK * sizeof(bf16_t) + (size_t)2 * BM * sizeof(RowInfo) + (size_t)2 * a.Cd * sizeof(float);
     auto kern = igemm_kernel<BM, BN, WM, WN, DGRAD>;
     static bool configured = false;
     if (!configured) {
@@ -429,6 +480,11 @@ static int launch_igemm(IgemmArgs& a, hipStream_t s) {
         configured = true;
     }
     const int grid = igemm_grid(mtiles, a.Cd, BN);
+    if (getenv("TSM_DEBUG")) {
+        int nb = -1;
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)kern, 256, smem);
+        fprintf(stderr, "igemm<%d,%d,%d> grid %d smem %zu occupancy %d (err %d) cus %d\n", BM, BN, (int)DGRAD, grid, smem, nb, (int)e, num_cu());
+    }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, a);
     // class names carry the tile shape so that they map one-to-one onto kernel symbols
     return check_launch(DGRAD ? (BN == 64 ? "igemm_dgrad_128x64" : "igemm_dgrad_128x128")
@@ -501,12 +557,15 @@ struct WgradArgs {
 static constexpr int WMK = 64;        // pixels per main-loop step
 static constexpr int LDT = WMK + 8;   // pitch of the transposed tiles
 
-// Element offset of pixel quad `pq` (four pixels = 8 bytes) in the transposed tile row `row`: the
-// 16-byte groups of eight pixels are XOR-swizzled with the row's channel-vector index so that lanes
-// writing different channel vectors of the same pixels fall into different LDS banks.
-__device__ __forceinline__ int swz_quad(int pq, int row) { return (((pq >> 1) ^ ((row >> 3) & 7)) << 3) | ((pq & 1) << 2); }
+// Transposed-tile rows are [channel][pixel] with a 144-byte pitch.  The transposing 8-byte stores come
+// from lanes whose rows are 8 apart, which would all fall into the same banks; the 16-byte pixel groups of
+// a row are therefore XOR-ed with the row's channel-vector index (measured faster than leaving the groups
+// in place or XOR-ing with a coarser row index).
+__device__ __forceinline__ int swz_x(int row) { return (row >> 3) & 7; }
+// Element offset of pixel quad `pq` (four pixels = 8 bytes) in row `row`.
+__device__ __forceinline__ int swz_quad(int pq, int row) { return (((pq >> 1) ^ swz_x(row)) << 3) | ((pq & 1) << 2); }
 // Element offset of the 8-pixel fragment `g` (0..7) of row `row`.
-__device__ __forceinline__ int swz_frag(int g, int row) { return (g ^ ((row >> 3) & 7)) * 8; }
+__device__ __forceinline__ int swz_frag(int g, int row) { return (g ^ swz_x(row)) * 8; }
 
 template <int BCO, int BCI>
 __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs a) {
