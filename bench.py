@@ -60,8 +60,37 @@ def class_work(F, size):
     return work
 
 
-def total_flops_per_clip(T, size):
-    return sum(class_work(T, size).values())
+def class_bytes(F, size):
+    """Algorithmic HBM bytes per step of each MFMA kernel class: every layer reads its two operands once
+    and writes its result once (bf16 activations; weight-sized tensors are negligible and left out)."""
+    byt = {}
+
+    def add(cls, b):
+        byt[cls] = byt.get(cls, 0.0) + b
+
+    for name, rin, cin, rout, cout, taps, has_dgrad in conv_layers(F, size):
+        cin_s = 8 if name == "conv1" else cin
+        x_b, y_b = 2.0 * rin * cin_s, 2.0 * rout * cout
+        add("igemm_fwd_128x64" if cout <= 64 else "igemm_fwd_128x128", x_b + y_b)
+        if has_dgrad:
+            extra = x_b if name.endswith(".c1") else 0.0       # the shortcut gradient added in the epilogue
+            add("igemm_dgrad_128x64" if cin <= 64 else "igemm_dgrad_128x128", x_b + y_b + extra)
+        kk = taps * cin_s
+        add("wgrad_128x128" if (cout > 64 and kk > 64) else "wgrad_64x64", x_b + y_b)
+    return byt
+
+
+def measured_traffic(clips):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, scaled by
+    the copy-kernel calibration stated there); None when no summary for this workload is committed."""
+    path = os.path.join(ROOT, "profiles", "tsm_resnet50_step_%dclips_hbm_traffic.txt" % clips)
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch":
+                out[parts[1]] = float(parts[2])
+    return out
 
 
 def main():
@@ -128,11 +157,17 @@ def main():
     work = class_work(N * T, S)
     dom = max(prof, key=lambda k: prof[k][1])
     n_launch, dom_ms = prof[dom]
+    traffic = measured_traffic(N)
     if dom in work:
         achieved = work[dom] / (dom_ms * 1e-3) / 1e12
+        alg_bytes = class_bytes(N * T, S)[dom]
         roof = {"bound": "mfma", "kernel": dom, "launches_per_step": n_launch,
                 "avg_launch_ms": dom_ms / n_launch, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None}
+                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic.get(dom),
+                "flops_per_launch": work[dom] / n_launch, "algorithmic_bytes_per_launch": alg_bytes / n_launch,
+                "algorithmic_gbs": alg_bytes / (dom_ms * 1e-3) / 1e9,
+                "roofline_frac_of_min_mfma_hbm": (dom_ms * 1e-3) and
+                max(work[dom] / (PEAK_BF16_TFLOPS * 1e12), alg_bytes / (PEAK_HBM_GBS * 1e9)) / (dom_ms * 1e-3)}
     else:
         roof = {"bound": "hbm", "kernel": dom, "launches_per_step": n_launch, "avg_launch_ms": dom_ms / n_launch,
                 "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": None, "traffic": None}
@@ -172,9 +207,17 @@ def main():
     torch.cuda.synchronize()
     sh_ms = s0.elapsed_time(s1) / reps
     sh_gbs = 2.0 * nbytes / (sh_ms * 1e-3) / 1e9
+    # reference: the framework's own device-to-device copy of the same buffer (what a plain copy reaches here)
+    ys.copy_(xs)
+    s0.record(stream)
+    for _ in range(reps):
+        ys.copy_(xs)
+    s1.record(stream)
+    torch.cuda.synchronize()
+    cp_gbs = 2.0 * nbytes / (s0.elapsed_time(s1) / reps * 1e-3) / 1e9
     out["shift"] = {"shape": list(sh_shape), "dtype": "bf16", "layout": "NTHWC", "ms": sh_ms, "achieved": sh_gbs,
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": sh_gbs / PEAK_HBM_GBS,
-                    "bytes": "one read + one write of the tensor"}
+                    "bytes": "one read + one write of the tensor", "plain_copy_gbs": cp_gbs}
     del xs, ys
 
     if not args.no_cpu_baseline:
