@@ -42,6 +42,13 @@ def conv_layers(F, size):
     return layers
 
 
+def wgrad_class(cout, kk):
+    """Tile the library picks for a weight gradient with `cout` output channels and K = taps * Cin."""
+    if cout > 64 and kk > 64:
+        return "wgrad_128x128"
+    return "wgrad_64x192" if (cout <= 64 and kk >= 192 and kk % 192 == 0) else "wgrad_64x64"
+
+
 def class_work(F, size):
     """Algorithmic FLOPs per step of each MFMA kernel class (2 x multiply-accumulates of the layers it
     runs) -- counted from the layer table, never from padded tiles."""
@@ -56,7 +63,7 @@ def class_work(F, size):
         if has_dgrad:
             add("igemm_dgrad_128x64" if cin <= 64 else "igemm_dgrad_128x128", macs)
         kk = taps * (8 if name == "conv1" else cin)
-        add("wgrad_128x128" if (cout > 64 and kk > 64) else "wgrad_64x64", macs)
+        add(wgrad_class(cout, kk), macs)
     return work
 
 
@@ -76,7 +83,7 @@ def class_bytes(F, size):
             extra = x_b if name.endswith(".c1") else 0.0       # the shortcut gradient added in the epilogue
             add("igemm_dgrad_128x64" if cin <= 64 else "igemm_dgrad_128x128", x_b + y_b + extra)
         kk = taps * cin_s
-        add("wgrad_128x128" if (cout > 64 and kk > 64) else "wgrad_64x64", x_b + y_b)
+        add(wgrad_class(cout, kk), x_b + y_b)
     return byt
 
 

@@ -74,8 +74,10 @@ struct RowInfo {
     int dst;
 };
 
-template <int BM, int BN, int WM, int WN, bool DGRAD>
-__global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
+// PF: K steps of gathered data kept in flight in registers (1 or 2); MINB: blocks per CU the register
+// budget is sized for (2: 256 registers per lane, 1: 512).
+template <int BM, int BN, int WM, int WN, bool DGRAD, int PF, int MINB>
+__global__ void __launch_bounds__(256, MINB) igemm_kernel(IgemmArgs a) {
     static_assert(WM * WN == 4, "four wavefronts");
     constexpr int TM = BM / WM, TN = BN / WN;       // wavefront tile
     constexpr int MI = TM / 32, NJ = TN / 32;       // 32x32 MFMA tiles per wavefront
@@ -199,7 +201,9 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
         return c;
     };
 
-    u32x4 areg[PA], breg[PB];   // one K step of gathered data in flight
+    // gathered data in flight: one K step, or two (PF2: steps k+1 and k+2) when the registers allow it
+    constexpr bool PF2 = (PF == 2);
+    u32x4 areg[PA], breg[PB], areg1[PF2 ? PA : 1], breg1[PF2 ? PB : 1];
 
     // Fetches the next K step of tile `c` (steps are fetched strictly in order) and advances c's position.
     auto load_tiles = [&](Ctx& c, u32x4* areg, u32x4* breg) {
@@ -239,7 +243,7 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
             }
         }
     };
-    auto store_tiles = [&](int buf) {
+    auto store_tiles = [&](int buf, const u32x4* areg, const u32x4* breg) {
         bf16_t* Ab = As + buf * BM * LDK;
         bf16_t* Bb = Bs + buf * BN * LDK;
 #pragma unroll
@@ -256,6 +260,7 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
     if (tile >= 0) {
         ctx = make_ctx(tile, 0);
         load_tiles(ctx, areg, breg);
+        if (PF2) load_tiles(ctx, areg1, breg1);
     }
 
     while (tile >= 0) {
@@ -290,24 +295,40 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs a) {
             }
         };
 
-        // Main loop: the gather of step k+1 is in flight (in registers) while the MFMAs of step k run out
-        // of LDS; LDS is double-buffered, one barrier per step.  On entry the registers hold step 0 of this
-        // tile.  Loads and LDS stores are issued unconditionally (steps past the end read the zero page and
-        // land in a buffer nobody reads), which keeps the loop body free of branches.
+        // Main loop.  The gathers of the next step (or next two steps, PF2) are in flight in registers while
+        // the MFMAs of step k run out of LDS; LDS is double-buffered, one barrier per step.  On entry the
+        // registers hold step 0 (and 1) of this tile.  Loads and LDS stores are issued unconditionally (steps
+        // past the end read the zero page and land in a buffer nobody reads): with no branch around them the
+        // compiler waits for exactly the older register set.
         const int nk = ctx.nk;
-        store_tiles(0);
+        store_tiles(0, areg, breg);
         __syncthreads();
-        for (int kc = 0; kc < nk; ++kc) {
-            const int buf = kc & 1;
-            load_tiles(ctx, areg, breg);
-            compute(buf);
-            store_tiles(buf ^ 1);
-            __syncthreads();
+        if (PF2) {
+            for (int kc = 0; kc < nk; kc += 2) {
+                load_tiles(ctx, areg, breg);
+                compute(0);
+                store_tiles(1, areg1, breg1);
+                __syncthreads();
+                if (kc + 1 >= nk) break;
+                load_tiles(ctx, areg1, breg1);
+                compute(1);
+                store_tiles(0, areg, breg);
+                __syncthreads();
+            }
+        } else {
+            for (int kc = 0; kc < nk; ++kc) {
+                const int buf = kc & 1;
+                load_tiles(ctx, areg, breg);
+                compute(buf);
+                store_tiles(buf ^ 1, areg, breg);
+                __syncthreads();
+            }
         }
         const int n0 = ctx.n0;
         if (ntile >= 0) {
             ctx = make_ctx(ntile, rb ^ 1);
             load_tiles(ctx, areg, breg);
+            if (PF2) load_tiles(ctx, areg1, breg1);
         }
 
         // ---- epilogue: round to bf16, per-channel statistics, stage through LDS, 16-byte stores.
@@ -455,51 +476,48 @@ static int setup_classes(IgemmArgs& a, bool dgrad, int BM) {
     return a.mt0[a.ncls];
 }
 
-// Persistent grid: two blocks per CU (a multiple of 8 so that a block stays on one XCD), capped by
-// the number of tile ids, which enumerate (group of 8 M tiles) x N tiles x (xcd).
-static int igemm_grid(int mtiles, int Cd, int BN) {
+// Persistent grid: `per_cu` blocks per CU (a multiple of 8 blocks so that a block stays on one XCD), capped
+// by the number of tile ids, which enumerate (group of 8 M tiles) x N tiles x (xcd).
+static int igemm_grid(int mtiles, int Cd, int BN, int per_cu) {
     const int ntiles = (Cd + BN - 1) / BN;
     const int total = ((mtiles + 7) / 8) * 8 * ntiles;
-    int grid = 2 * num_cu();
+    int grid = per_cu * num_cu();
     grid = (grid / 8) * 8;
     if (grid > total) grid = total;
     if (grid < 1) grid = 1;
     return grid;
 }
 
-template <int BM, int BN, int WM, int WN, bool DGRAD>
-static int launch_igemm(IgemmArgs& a, hipStream_t s) {
+template <int BM, int BN, int WM, int WN, bool DGRAD, int PF, int MINB>
+static int launch_igemm(IgemmArgs& a, const char* name, hipStream_t s) {
     const int mtiles = setup_classes(a, DGRAD, BM);
     a.ntiles = (a.Cd + BN - 1) / BN;
     size_t smem = (size_t)2 * (BM + BN) * LDK * sizeof(bf16_t) + (size_t)2 * BM * sizeof(RowInfo) + (size_t)2 * a.Cd * sizeof(float);
-    auto kern = igemm_kernel<BM, BN, WM, WN, DGRAD>;
+    auto kern = igemm_kernel<BM, BN, WM, WN, DGRAD, PF, MINB>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return fail(TSM_ERR_LAUNCH, "igemm: cannot raise dynamic LDS limit");
         configured = true;
     }
-    const int grid = igemm_grid(mtiles, a.Cd, BN);
-    if (getenv("TSM_DEBUG")) {
-        int nb = -1;
-        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)kern, 256, smem);
-        fprintf(stderr, "igemm<%d,%d,%d> grid %d smem %zu occupancy %d (err %d) cus %d\n", BM, BN, (int)DGRAD, grid, smem, nb, (int)e, num_cu());
-    }
+    const int grid = igemm_grid(mtiles, a.Cd, BN, MINB);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, a);
-    // class names carry the tile shape so that they map one-to-one onto kernel symbols
-    return check_launch(DGRAD ? (BN == 64 ? "igemm_dgrad_128x64" : "igemm_dgrad_128x128")
-                              : (BN == 64 ? "igemm_fwd_128x64" : "igemm_fwd_128x128"));
+    return check_launch(name);   // class names carry the tile shape so that they map one-to-one onto kernel symbols
 }
 
+// Tile choice: narrow outputs (<= 64 channels) take the 128x64 tile, everything else 128x128; both keep two
+// blocks per CU and one K step in flight.  (A 256x128 tile with two K steps in flight was tried: the compiler
+// spills in its main loop and it runs three times slower.)
 template <bool DGRAD>
 static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
-    if ((long)a.F * a.Hd * a.Wd == 0) return TSM_OK;
-    if (a.Cd <= 64) return launch_igemm<128, 64, 4, 1, DGRAD>(a, s);
-    return launch_igemm<128, 128, 2, 2, DGRAD>(a, s);
+    const long rows = (long)a.F * a.Hd * a.Wd;
+    if (rows == 0) return TSM_OK;
+    if (a.Cd <= 64) return launch_igemm<128, 64, 4, 1, DGRAD, 1, 2>(a, DGRAD ? "igemm_dgrad_128x64" : "igemm_fwd_128x64", s);
+    return launch_igemm<128, 128, 2, 2, DGRAD, 1, 2>(a, DGRAD ? "igemm_dgrad_128x128" : "igemm_fwd_128x128", s);
 }
 
 int conv_mfma_fwd_blocks(const ConvP& p) {
-    return igemm_grid((int)((p.rows_out() + 127) / 128), p.Cout, p.Cout <= 64 ? 64 : 128);
+    return igemm_grid((int)((p.rows_out() + 127) / 128), p.Cout, p.Cout <= 64 ? 64 : 128, 2);
 }
 
 int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, float* stats, hipStream_t s) {
@@ -573,7 +591,8 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs a) {
     constexpr int MI = TM / 32, NJ = TN / 32;
     constexpr int AV = BCO / 8, BV = BCI / 8;         // 16-byte vectors per tile row
     constexpr int AITEMS = AV * (WMK / 4), BITEMS = BV * (WMK / 4);   // (vector, pixel quad) work items
-    static_assert(AITEMS <= 256 && BITEMS <= 256, "one item per thread");
+    static_assert(AITEMS <= 256, "one dy item per thread");
+    constexpr int BQ = (BITEMS + 255) / 256;                          // x items per thread
     __shared__ __attribute__((aligned(16))) bf16_t At[2][BCO][LDT];   // dy^T  [co][pixel]
     __shared__ __attribute__((aligned(16))) bf16_t Bt[2][BCI][LDT];   // xs^T  [column][pixel]
     __shared__ RowInfo s_info[3][WMK];                                // per-pixel gather origin, three steps deep
@@ -591,20 +610,27 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs a) {
 
     // ---- this thread's work items: consecutive lanes take consecutive 16-byte pieces of a pixel row
     const int avec = tid % AV, apq = tid / AV;        // dy: channels co0 + 8*avec.., pixels 4*apq..4*apq+3
-    const int bvec = tid % BV, bpq = tid / BV;        // x : columns  j0 + 8*bvec..
-    const bool a_item = tid < AITEMS, b_item = tid < BITEMS;
+    const bool a_item = tid < AITEMS;
     const bool a_chan_ok = co0 + avec * 8 < a.Cout;
-    // B column -> (tap, channel): constant for the thread's whole life
-    uint32_t need = 0xffffffffu;   // unsatisfiable: column beyond K
-    int boff = 0;
-    {
-        const int j = j0 + bvec * 8;
+    // x items: columns j0 + 8*bvec.., pixel quad bpq; column -> (tap, channel) is constant for the thread's life
+    int bvec[BQ], bpq[BQ], boff[BQ];
+    uint32_t need[BQ];
+    bool b_item[BQ];
+#pragma unroll
+    for (int q = 0; q < BQ; ++q) {
+        const int item = q * 256 + tid;
+        bvec[q] = item % BV;
+        bpq[q] = item / BV;
+        b_item[q] = item < BITEMS;
+        need[q] = 0xffffffffu;   // unsatisfiable: column beyond K
+        boff[q] = 0;
+        const int j = j0 + bvec[q] * 8;
         if (j < a.K) {
             const int tap = j / a.Cin, ci = j - tap * a.Cin;
             const int kw = tap % a.KW, kh = (tap / a.KW) % a.KH, kt = tap / (a.KW * a.KH);
             const int d = kt - a.KT / 2 + group_dt(ci, a.fold);
-            need = (1u << kh) | (1u << (8 + kw)) | (d > 0 ? 1u << 30 : 0u) | (d < 0 ? 1u << 31 : 0u);
-            boff = d * a.H * a.W * a.Cin + (kh * a.W + kw) * a.Cin + ci;
+            need[q] = (1u << kh) | (1u << (8 + kw)) | (d > 0 ? 1u << 30 : 0u) | (d < 0 ? 1u << 31 : 0u);
+            boff[q] = d * a.H * a.W * a.Cin + (kh * a.W + kw) * a.Cin + ci;
         }
     }
 
@@ -644,7 +670,7 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    u32x4 ar[4], br[4];
+    u32x4 ar[4], br[BQ][4];
 
     auto load = [&](int st) {
         const long mstep = mbeg + (long)st * WMK;
@@ -656,12 +682,15 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs a) {
                 ar[h] = *(const u32x4*)p;
             }
         }
-        if (b_item) {
 #pragma unroll
-            for (int h = 0; h < 4; ++h) {
-                const RowInfo ri = s_info[st % 3][4 * bpq + h];
-                const bf16_t* p = ((ri.mask & need) == need) ? a.x + ri.off + boff : zero_page;
-                br[h] = *(const u32x4*)p;
+        for (int q = 0; q < BQ; ++q) {
+            if (b_item[q]) {
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    const RowInfo ri = s_info[st % 3][4 * bpq[q] + h];
+                    const bf16_t* p = ((ri.mask & need[q]) == need[q]) ? a.x + ri.off + boff[q] : zero_page;
+                    br[q][h] = *(const u32x4*)p;
+                }
             }
         }
     };
@@ -680,7 +709,9 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs a) {
     };
     auto store = [&](int buf) {
         if (a_item) scatter(At[buf], avec, apq, ar);
-        if (b_item) scatter(Bt[buf], bvec, bpq, br);
+#pragma unroll
+        for (int q = 0; q < BQ; ++q)
+            if (b_item[q]) scatter(Bt[buf], bvec[q], bpq[q], br[q]);
     };
 
     const int nsteps = (int)((mend - mbeg + WMK - 1) / WMK);
@@ -747,8 +778,11 @@ int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw
     a.M = p.rows_out();
     a.K = (int)p.K();
     if (a.M == 0) return TSM_OK;
+    // tiles: 128x128 for wide outputs; for <= 64 output channels a 64x192 tile when K is long enough (the
+    // transposed dy tile is then shared by three times as many columns); 64x64 otherwise
     const bool big = p.Cout > 64 && a.K > 64;
-    const int bco = big ? 128 : 64, bci = big ? 128 : 64;
+    const bool wide = !big && p.Cout <= 64 && a.K >= 192 && a.K % 192 == 0;
+    const int bco = big ? 128 : 64, bci = big ? 128 : (wide ? 192 : 64);
     a.col_tiles = cdiv(a.K, bci);
     const int tiles = cdiv(p.Cout, bco) * a.col_tiles;
     long want = (long)4 * num_cu() / tiles;
@@ -761,9 +795,11 @@ int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw
     dim3 grid(gx, (unsigned)tiles);
     if (big)
         wgrad_kernel<128, 128><<<grid, dim3(256), 0, s>>>(a);
+    else if (wide)
+        wgrad_kernel<64, 192><<<grid, dim3(256), 0, s>>>(a);
     else
         wgrad_kernel<64, 64><<<grid, dim3(256), 0, s>>>(a);
-    return check_launch(big ? "wgrad_128x128" : "wgrad_64x64");
+    return check_launch(big ? "wgrad_128x128" : (wide ? "wgrad_64x192" : "wgrad_64x64"));
 }
 
 }  // namespace tsm
