@@ -94,7 +94,9 @@ __global__ void __launch_bounds__(256, MINB) igemm_kernel(IgemmArgs a) {
     bf16_t* Bs = As + 2 * BM * LDK;                  // [2][BN][LDK]
     bf16_t* Cst = (bf16_t*)smem;                     // [BM][LDC], reuses As/Bs after the main loop
     RowInfo* s_row = (RowInfo*)(Bs + 2 * BN * LDK);  // [2][BM]: rows of the current and of the next tile
-    float* s_sum = (float*)(s_row + 2 * BM);         // [Cd] sums then [Cd] sums of squares
+    // per-tile statistics slots [2 stats][WM*2 slots][BN], placed behind the staging tile in the operand buffers
+    float* s_part = (float*)(Cst + BM * LDC);
+    static_assert((size_t)BM * LDC * 2 + (size_t)2 * WM * 2 * BN * 4 <= (size_t)2 * (BM + BN) * LDK * 2, "slots must fit");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -104,8 +106,14 @@ __global__ void __launch_bounds__(256, MINB) igemm_kernel(IgemmArgs a) {
     const bool uniform_tap = (a.Cs % BK) == 0;      // a K step never straddles two taps
     const bf16_t* zero_page = (const bf16_t*)g_zero_page;
 
+    // Statistics: this block owns one row of the partial buffer.  It is zeroed here; after every tile one
+    // fixed thread per column adds that tile's column sums to it (device-scope atomics used as plain
+    // coherent read-modify-writes: no other block touches the row), in tile order -- so the result is
+    // bit-reproducible.
+    float* prow = do_stats ? a.stats + (size_t)blockIdx.x * 2 * a.Cd : nullptr;
     if (do_stats) {
-        for (int c = tid; c < 2 * a.Cd; c += 256) s_sum[c] = 0.f;
+        // the barrier below waits for these stores to be acknowledged by L2, where the later atomics execute
+        for (int c = tid; c < 2 * a.Cd; c += 256) prow[c] = 0.f;
     }
 
     const int hw_d = a.Hd * a.Wd;
@@ -256,7 +264,7 @@ __global__ void __launch_bounds__(256, MINB) igemm_kernel(IgemmArgs a) {
     int rb = 0;
     Ctx ctx;
     if (tile >= 0) decode_rows(tile, 0);
-    __syncthreads();   // also orders the s_sum initialisation
+    __syncthreads();   // also orders the zeroing of the statistics row
     if (tile >= 0) {
         ctx = make_ctx(tile, 0);
         load_tiles(ctx, areg, breg);
@@ -357,12 +365,20 @@ __global__ void __launch_bounds__(256, MINB) igemm_kernel(IgemmArgs a) {
                     *(uint32_t*)(Cst + row * LDC + (col & ~1)) = word;
                 }
             }
-            if (do_stats && n0 + col < a.Cd) {
-                atomicAdd(&s_sum[n0 + col], s1);
-                atomicAdd(&s_sum[a.Cd + n0 + col], s2);
+            if (do_stats) {   // own slot: (wavefront row, lane half) x column
+                const int slot = wm * 2 + (lane >> 5);
+                s_part[slot * BN + col] = s1;
+                s_part[(WM * 2 + slot) * BN + col] = s2;
             }
         }
         __syncthreads();
+        if (do_stats && tid < 2 * BN) {   // fixed summation order over the slots, one thread per (statistic, column)
+            const int stat = tid / BN, col = tid % BN;
+            float v = 0.f;
+#pragma unroll
+            for (int sl = 0; sl < WM * 2; ++sl) v += s_part[(stat * WM * 2 + sl) * BN + col];
+            if (n0 + col < a.Cd) atomicAdd(prow + stat * a.Cd + n0 + col, v);
+        }
         {
             constexpr int CV = BN / 8;          // vectors per staged row
             constexpr int RPS = 256 / CV;       // rows per pass
@@ -408,11 +424,6 @@ __global__ void __launch_bounds__(256, MINB) igemm_kernel(IgemmArgs a) {
         rb ^= 1;
     }
 
-    if (do_stats) {   // every block publishes its row, zeros included: the consumer adds all rows up
-        __syncthreads();
-        float* prow = a.stats + (size_t)blockIdx.x * 2 * a.Cd;
-        for (int c = tid; c < 2 * a.Cd; c += 256) prow[c] = s_sum[c];
-    }
 }
 
 // ---------------------------------------------------------------------------------
@@ -492,7 +503,7 @@ template <int BM, int BN, int WM, int WN, bool DGRAD, int PF, int MINB>
 static int launch_igemm(IgemmArgs& a, const char* name, hipStream_t s) {
     const int mtiles = setup_classes(a, DGRAD, BM);
     a.ntiles = (a.Cd + BN - 1) / BN;
-    size_t smem = (size_t)2 * (BM + BN) * LDK * sizeof(bf16_t) + (size_t)2 * BM * sizeof(RowInfo) + (size_t)2 * a.Cd * sizeof(float);
+    size_t smem = (size_t)2 * (BM + BN) * LDK * sizeof(bf16_t) + (size_t)2 * BM * sizeof(RowInfo);
     auto kern = igemm_kernel<BM, BN, WM, WN, DGRAD, PF, MINB>;
     static bool configured = false;
     if (!configured) {

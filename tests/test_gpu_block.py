@@ -132,3 +132,36 @@ def test_config4_blocks_reduced():
 
 def test_t3_block_fp32():
     run_block("t3", 2, 3, 16, 5, 5, 8, 16, 1, False, 0, "f32", "nthwc")
+
+
+def test_config1_full_size_bottleneck():
+    """One bottleneck of configs[1] at its full size: x[8,8,256,56,56] bf16, 256 -> 64 -> 64 -> 256, fold_div 8,
+    in the launch configuration bench.py times (channels innermost); every output and gradient against the oracle."""
+    run_block("bottleneck", 8, 8, 256, 56, 56, 64, 256, 1, False, 8, "bf16", "nthwc")
+
+
+def test_config4_full_size_tsm_block():
+    """The TSM block of configs[4] at its full size: x[8,8,1024,14,14] bf16, 1024 -> 256 -> 256 -> 1024."""
+    run_block("bottleneck", 8, 8, 1024, 14, 14, 256, 1024, 1, False, 8, "bf16", "nthwc")
+
+
+def test_forward_is_bit_reproducible():
+    """The forward pass uses no atomics: two runs give identical bits (the BatchNorm statistics are reduced
+    in a fixed order)."""
+    kinds = B.TSM_BLOCK_BOTTLENECK
+    N, T, Cin, H, W, Cmid, Cout = 2, 4, 256, 28, 28, 64, 256
+    p = make_params("bottleneck", Cin, Cmid, Cout, False, "bf16")
+    x = I.normal((N, T, Cin, H, W), 0, "bf16")
+    d = B.BlockDesc(kind=kinds, N=N, T=T, Cin=Cin, H=H, W=W, Cmid=Cmid, Cout=Cout, stride=1, has_projection=0,
+                    fold_div=8, dtype=B.TSM_BF16, layout=B.TSM_NTHWC, bn_eps=1e-5)
+    saved = workspace(B.tsm_block_saved_bytes(d))
+    ws = workspace(B.tsm_block_workspace_bytes(d))
+    dp = {k: dev_vec(v, "bf16" if k.startswith("w") else "f32") for k, v in p.items()}
+    xd = to_dev(x, "bf16", "nthwc")
+    outs = []
+    for _ in range(2):
+        out = empty_act((N, T, Cout, H, W), "bf16", "nthwc")
+        B.tsm_block_fwd(d, xd, dp, out, saved, ws)
+        torch.cuda.synchronize()
+        outs.append(out.view(torch.int16).cpu().numpy().copy())
+    assert np.array_equal(outs[0], outs[1])

@@ -94,3 +94,13 @@ def test_fold_zero_equals_unshifted_and_shift_matters():
         outs.append(from_dev(y, "nthwc"))
     assert rel_l2(outs[1], O.conv_fwd(x.astype(np.float64), w.astype(np.float64), s, p, 0)) < 2e-2
     assert rel_l2(outs[0], outs[1]) > 0.1
+
+
+@pytest.mark.parametrize("case", [
+    (8, 8, 256, 56, 56, 64, 1, 1, 0, 8),     # configs[1] first conv (shifted 1x1) at full size
+    (8, 8, 64, 56, 56, 64, 3, 1, 1, 0),      # configs[1] 3x3 at full size
+    (8, 8, 512, 14, 14, 512, 3, 2, 1, 0),    # strided 3x3 of the last stage's first block (parity-class dgrad)
+])
+def test_conv_full_size_layers(case):
+    """Full-size layers in the launch configuration of the benchmark, every element against the oracle."""
+    _run(case, "bf16", "nthwc")
