@@ -126,20 +126,22 @@ int channel_stats(int dtype, const void* y, long rows, int C, float* partial, hi
                   : channel_stats_tv<bf16_t, 1>((const bf16_t*)y, rows, C, partial, s);
 }
 
-// Adds up the rows of a partial buffer for channel c: the four ty lanes of a (64 x 4) block split the
-// rows and keep independent accumulators, then meet in LDS.  Returns the totals on ty == 0.
+// Adds up the rows of a partial buffer for channel c = blockIdx.x*16 + threadIdx.x: the 16 ty lanes of a
+// (16 x 16) block split the rows (short dependent chains: this kernel is pure latency), keep two
+// independent accumulators each, then meet in LDS in a fixed order.  Totals are valid on every thread.
+static constexpr int SP_C = 16, SP_R = 16;
 __device__ __forceinline__ void sum_partials(const float* __restrict__ partial, int nblocks, int C, int c,
                                              double* out1, double* out2) {
-    __shared__ double red[2][4][64];
+    __shared__ double red[2][SP_R][SP_C];
     double s1 = 0.0, s2 = 0.0;
     if (c < C) {
         float a0 = 0.f, a1 = 0.f, b0 = 0.f, b1 = 0.f;
         int b = threadIdx.y;
-        for (; b + 4 < nblocks; b += 8) {
+        for (; b + SP_R < nblocks; b += 2 * SP_R) {
             a0 += partial[(size_t)b * 2 * C + c];
             b0 += partial[(size_t)b * 2 * C + C + c];
-            a1 += partial[(size_t)(b + 4) * 2 * C + c];
-            b1 += partial[(size_t)(b + 4) * 2 * C + C + c];
+            a1 += partial[(size_t)(b + SP_R) * 2 * C + c];
+            b1 += partial[(size_t)(b + SP_R) * 2 * C + C + c];
         }
         if (b < nblocks) {
             a0 += partial[(size_t)b * 2 * C + c];
@@ -151,15 +153,21 @@ __device__ __forceinline__ void sum_partials(const float* __restrict__ partial, 
     red[0][threadIdx.y][threadIdx.x] = s1;
     red[1][threadIdx.y][threadIdx.x] = s2;
     __syncthreads();
-    *out1 = red[0][0][threadIdx.x] + red[0][1][threadIdx.x] + red[0][2][threadIdx.x] + red[0][3][threadIdx.x];
-    *out2 = red[1][0][threadIdx.x] + red[1][1][threadIdx.x] + red[1][2][threadIdx.x] + red[1][3][threadIdx.x];
+    double t1 = 0.0, t2 = 0.0;
+#pragma unroll
+    for (int r = 0; r < SP_R; ++r) {
+        t1 += red[0][r][threadIdx.x];
+        t2 += red[1][r][threadIdx.x];
+    }
+    *out1 = t1;
+    *out2 = t2;
 }
 
 // ---- partial statistics -> per-channel vectors ------------------------------------------------------
 __global__ void bn_finalize_kernel(const float* __restrict__ partial, int nblocks, double inv_m, double unbias, int C,
                                    const float* __restrict__ gamma, const float* __restrict__ beta, float eps,
                                    BnVec o, float* run_mean, float* run_var, float momentum) {
-    const int c = blockIdx.x * 64 + threadIdx.x;
+    const int c = blockIdx.x * SP_C + threadIdx.x;
     double s1, s2;
     sum_partials(partial, nblocks, C, c, &s1, &s2);
     if (c >= C || threadIdx.y != 0) return;
@@ -183,13 +191,13 @@ int bn_finalize(const float* partial, int nblocks, long rows, int C, const float
                 BnVec out, float* run_mean, float* run_var, float momentum, hipStream_t s) {
     const double inv_m = rows > 0 ? 1.0 / (double)rows : 0.0;
     const double unbias = rows > 1 ? (double)rows / (double)(rows - 1) : 1.0;
-    bn_finalize_kernel<<<dim3(cdiv(C, 64)), dim3(64, 4), 0, s>>>(partial, nblocks, inv_m, unbias, C, gamma, beta, eps,
+    bn_finalize_kernel<<<dim3(cdiv(C, SP_C)), dim3(SP_C, SP_R), 0, s>>>(partial, nblocks, inv_m, unbias, C, gamma, beta, eps,
                                                                 out, run_mean, run_var, momentum);
     return check_launch("bn_finalize");
 }
 
 __global__ void stats_to_float_kernel(const float* __restrict__ partial, int nblocks, int C, float* sum, float* sumsq) {
-    const int c = blockIdx.x * 64 + threadIdx.x;
+    const int c = blockIdx.x * SP_C + threadIdx.x;
     double s1, s2;
     sum_partials(partial, nblocks, C, c, &s1, &s2);
     if (c >= C || threadIdx.y != 0) return;
@@ -198,7 +206,7 @@ __global__ void stats_to_float_kernel(const float* __restrict__ partial, int nbl
 }
 
 int stats_to_float(const float* partial, int nblocks, int C, float* sum, float* sumsq, hipStream_t s) {
-    stats_to_float_kernel<<<dim3(cdiv(C, 64)), dim3(64, 4), 0, s>>>(partial, nblocks, C, sum, sumsq);
+    stats_to_float_kernel<<<dim3(cdiv(C, SP_C)), dim3(SP_C, SP_R), 0, s>>>(partial, nblocks, C, sum, sumsq);
     return check_launch("stats_to_float");
 }
 
@@ -373,7 +381,7 @@ __global__ void bn_bwd_coeffs_kernel(const float* __restrict__ partial, int nblo
                                      const float* __restrict__ mean, const float* __restrict__ rstd,
                                      const float* __restrict__ gamma, float* __restrict__ coef,
                                      float* __restrict__ dgamma, float* __restrict__ dbeta) {
-    const int c = blockIdx.x * 64 + threadIdx.x;
+    const int c = blockIdx.x * SP_C + threadIdx.x;
     double s1, s2;
     sum_partials(partial, nblocks, C, c, &s1, &s2);
     if (c >= C || threadIdx.y != 0) return;
@@ -390,7 +398,7 @@ __global__ void bn_bwd_coeffs_kernel(const float* __restrict__ partial, int nblo
 int bn_bwd_coeffs(const float* partial, int nblocks, long rows, int C, const float* mean, const float* rstd,
                   const float* gamma, float* coef, float* dgamma, float* dbeta, hipStream_t s) {
     const double inv_m = rows > 0 ? 1.0 / (double)rows : 0.0;
-    bn_bwd_coeffs_kernel<<<dim3(cdiv(C, 64)), dim3(64, 4), 0, s>>>(partial, nblocks, inv_m, C, mean, rstd, gamma, coef,
+    bn_bwd_coeffs_kernel<<<dim3(cdiv(C, SP_C)), dim3(SP_C, SP_R), 0, s>>>(partial, nblocks, inv_m, C, mean, rstd, gamma, coef,
                                                                   dgamma, dbeta);
     return check_launch("bn_bwd_coeffs");
 }

@@ -297,6 +297,41 @@ __global__ void __launch_bounds__(256) pool_mean_bwd_kernel(const float* __restr
     dfeat[i] = Elem<T>::st(dpm[n * C + c] / (float)rows_per_clip);
 }
 
+// ---- bf16 working copies of all convolution weights, one launch per packing ---------------------
+// Entry l packs params[in_off ..] = fp32 [Cout][Cin][taps] into out + out_off: forward order
+// [Cout][taps][CinP] (channels >= Cin zero) or, with `flip`, the data-gradient order [Cin][flipped taps][Cout].
+struct PackTable {
+    int n;
+    unsigned start[56];       // first output element of entry l in the launch's flat index space (start[n] = total)
+    unsigned in_off[55];      // element offset into the fp32 parameter vector
+    unsigned out_off[55];     // bf16 element offset from the output base
+    unsigned short cout[55], cin[55], cinp[55], k[55];
+};
+
+__global__ void __launch_bounds__(256) pack_all_kernel(PackTable t, const float* __restrict__ params,
+                                                       bf16_t* __restrict__ out, int flip) {
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= t.start[t.n]) return;
+    int lo = 0, hi = t.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (t.start[mid] <= i) lo = mid; else hi = mid - 1;
+    }
+    const unsigned e = i - t.start[lo];
+    const int Cout = t.cout[lo], Cin = t.cin[lo], CinP = t.cinp[lo], K = t.k[lo], taps = K * K;
+    const float* w = params + t.in_off[lo];
+    float v = 0.f;
+    if (!flip) {          // e = (co * taps + tap) * CinP + ci
+        const int ci = e % CinP, tap = (e / CinP) % taps, co = e / (CinP * taps);
+        if (ci < Cin) v = w[((size_t)co * Cin + ci) * taps + tap];
+    } else {              // e = (ci * taps + ftap) * Cout + co
+        const int co = e % Cout, ftap = (e / Cout) % taps, ci = e / (Cout * taps);
+        const int kw = K - 1 - ftap % K, kh = K - 1 - ftap / K;
+        v = w[((size_t)co * Cin + ci) * taps + kh * K + kw];
+    }
+    out[(size_t)t.out_off[lo] + e] = f32_to_bf16(v);
+}
+
 // ---- SGD with momentum; weight decay only inside "decay" segments -----------------------------
 struct SgdSegments {
     int n;
@@ -381,17 +416,33 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
     auto P = [&](const std::string& name) { return params + table[find_tensor(table, name)].offset; };
     auto G = [&](const std::string& name) { return grads + table[find_tensor(table, name)].offset; };
     // bf16: working copies of the convolution weights in both packings; fp32: the master weights are used directly
+    PackTable pk_fwd, pk_dg;
+    pk_fwd.n = pk_dg.n = 0;
+    pk_fwd.start[0] = pk_dg.start[0] = 0;
+    bf16_t* const pack_base = (bf16_t*)(dry ? nullptr : wsp);   // packed buffers are addressed relative to the workspace
+    auto pack_entry = [&](PackTable& t, const std::string& name, int Cout, int Cin, int k, int CinP, size_t count,
+                          const bf16_t* dst) {
+        const int l = t.n++;
+        t.in_off[l] = (unsigned)table[find_tensor(table, name)].offset;
+        t.out_off[l] = (unsigned)(dst - pack_base);
+        t.cout[l] = (unsigned short)Cout; t.cin[l] = (unsigned short)Cin; t.cinp[l] = (unsigned short)CinP;
+        t.k[l] = (unsigned short)k;
+        t.start[l + 1] = t.start[l] + (unsigned)count;
+    };
     auto pack_conv = [&](const std::string& name, int Cout, int Cin, int k, int CinP, const bf16_t** wp,
                          const bf16_t** wd) -> int {
         *wp = nullptr;
         if (wd) *wd = nullptr;
         if (!bf) return TSM_OK;
-        bf16_t* a = A.take_n<bf16_t>((size_t)Cout * CinP * k * k);
-        RUN(pack_weights_fwd(TSM_F32, P(name), a, Cout, Cin, k * k, CinP, s));
+        if (pk_fwd.n >= 55 || pk_dg.n >= 55) return fail(TSM_ERR_UNSUPPORTED, "%s: too many convolutions", who);
+        const size_t nf = (size_t)Cout * CinP * k * k;
+        bf16_t* a = A.take_n<bf16_t>(nf);
+        pack_entry(pk_fwd, name, Cout, Cin, k, CinP, nf, a);
         *wp = a;
         if (wd) {
-            bf16_t* b2 = A.take_n<bf16_t>((size_t)Cout * Cin * k * k);
-            RUN(pack_weights_dgrad(TSM_F32, P(name), b2, Cout, Cin, 1, k, k, s));
+            const size_t nd = (size_t)Cout * Cin * k * k;
+            bf16_t* b2 = A.take_n<bf16_t>(nd);
+            pack_entry(pk_dg, name, Cout, Cin, k, Cin, nd, b2);
             *wd = b2;
         }
         return TSM_OK;
@@ -493,6 +544,12 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
 
     // every weight gradient is accumulated with atomics: one fill for the whole gradient vector
     RUN(fill_zero(grads, (size_t)nparams * sizeof(float), s));
+    if (bf && !dry) {   // bf16 working copies of all convolution weights: two launches
+        pack_all_kernel<<<dim3(cdiv(pk_fwd.start[pk_fwd.n], 256)), dim3(256), 0, s>>>(pk_fwd, params, pack_base, 0);
+        LAUNCH_CHECK("pack_weights_fwd");
+        pack_all_kernel<<<dim3(cdiv(pk_dg.start[pk_dg.n], 256)), dim3(256), 0, s>>>(pk_dg, params, pack_base, 1);
+        LAUNCH_CHECK("pack_weights_dgrad");
+    }
 
     // ================= forward =================
     {
