@@ -42,6 +42,14 @@ def conv_layers(F, size):
     return layers
 
 
+def igemm_class(kind, cd, cs):
+    """Tile the library picks for a forward ("fwd") or data-gradient ("dgrad") convolution that produces
+    `cd` channels from `cs` source channels (tensors below 2 GiB, which holds for every workload here)."""
+    if cd > 64 and cs % 64 == 0:
+        return "igemm_%s_256x128" % kind
+    return "igemm_%s_%s" % (kind, "128x64" if cd <= 64 else "128x128")
+
+
 def wgrad_class(cout, kk):
     """Tile the library picks for a weight gradient with `cout` output channels and K = taps * Cin."""
     if cout > 64 and kk > 64:
@@ -59,9 +67,9 @@ def class_work(F, size):
 
     for name, rin, cin, rout, cout, taps, has_dgrad in conv_layers(F, size):
         macs = float(rout) * cout * cin * taps
-        add("igemm_fwd_128x64" if cout <= 64 else "igemm_fwd_128x128", macs)
+        add(igemm_class("fwd", cout, 8 if name == "conv1" else cin), macs)
         if has_dgrad:
-            add("igemm_dgrad_128x64" if cin <= 64 else "igemm_dgrad_128x128", macs)
+            add(igemm_class("dgrad", cin, cout), macs)
         kk = taps * (8 if name == "conv1" else cin)
         add(wgrad_class(cout, kk), macs)
     return work
@@ -78,10 +86,10 @@ def class_bytes(F, size):
     for name, rin, cin, rout, cout, taps, has_dgrad in conv_layers(F, size):
         cin_s = 8 if name == "conv1" else cin
         x_b, y_b = 2.0 * rin * cin_s, 2.0 * rout * cout
-        add("igemm_fwd_128x64" if cout <= 64 else "igemm_fwd_128x128", x_b + y_b)
+        add(igemm_class("fwd", cout, cin_s), x_b + y_b)
         if has_dgrad:
             extra = x_b if name.endswith(".c1") else 0.0       # the shortcut gradient added in the epilogue
-            add("igemm_dgrad_128x64" if cin <= 64 else "igemm_dgrad_128x128", x_b + y_b + extra)
+            add(igemm_class("dgrad", cin, cout), x_b + y_b + extra)
         kk = taps * cin_s
         add(wgrad_class(cout, kk), x_b + y_b)
     return byt

@@ -427,6 +427,397 @@ __global__ void __launch_bounds__(256, MINB) igemm_kernel(IgemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
+// The same GEMM for source channel counts that are a multiple of 64 (every K step lies inside one tap), one
+// block of WM*WN wavefronts per CU, a BM x BN tile.  What differs from igemm_kernel:
+//
+//  * Gathers are buffer loads: per tile every thread keeps one 32-bit byte offset per row it fetches; the part
+//    of the address that changes from K step to K step (tap position, channel block) is the same for the whole
+//    block and travels in the instruction's scalar offset, so a K step costs a mask test and a select per load
+//    instead of 64-bit pointer arithmetic.  Lanes that fall on padding pass an offset beyond the buffer and
+//    receive zeros from the bounds check.  The buffer starts `bias` bytes before the tensor so that the offset
+//    of a row's tap origin, which may lie in the padding in front of the first frame, is never negative.
+//  * LDS holds two stages.  A stage is the A rows [BM][64] followed by the B rows [BN][64], 128 bytes per row
+//    without padding; position p (16 bytes) of row r holds the row's K vector p ^ ((r >> 1) & 7), which spreads
+//    the 16-byte fragment reads of 16 consecutive rows over 16 different bank groups.  While step g is
+//    multiplied out of one stage, step g+1 moves from registers into the other and step g+2 is loaded into the
+//    registers, a few loads and stores after every group of MFMAs.  The stream of K steps runs across tile
+//    boundaries, so a tile's first two steps are on the chip before the previous tile's epilogue starts.
+static constexpr uint32_t OOB_OFFSET = 0x80000000u;   // buffers are smaller than 2 GiB
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
+}
+
+template <int BM, int BN, int WM, int WN, bool DGRAD>
+__global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
+    constexpr int NT = WM * WN * 64;                // threads
+    constexpr int NS = 2;                           // LDS stages
+    constexpr int MI = BM / (WM * 32), NJ = BN / (WN * 32);   // 32x32 MFMA tiles per wavefront
+    constexpr int HM = BM / MI;                     // rows per epilogue pass; wavefront rows: i*HM + wm*32
+    constexpr int TN = BN / WN;
+    constexpr int KV = BK / 8;                      // 16-byte vectors per tile row
+    constexpr int RPP = NT / KV;                    // tile rows loaded per pass
+    constexpr int PA = BM / RPP, PB = BN / RPP;
+    constexpr int ROWB = BK * 2;                    // bytes per LDS row
+    constexpr int STAGE = (BM + BN) * ROWB;         // bytes per ring stage
+    constexpr int LDC = BN + 8;                     // staging pitch (elements)
+    static_assert(BK == 64 && KV == 8, "rows of eight 16-byte vectors");
+    static_assert(BM % RPP == 0 && BN % RPP == 0 && HM == WM * 32, "tile / thread mismatch");
+    static_assert((HM * LDC * 2) % 16 == 0, "alignment of the regions behind the staging tile");
+    static_assert(sizeof(RowInfo) == 16, "one 16-byte LDS read per row");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t* Cst = (bf16_t*)(smem + NS * STAGE);      // [HM][LDC] staging tile of the epilogue
+    float* s_part = (float*)(Cst + HM * LDC);        // [2 stats][WM*2 slots][BN] statistics slots
+    RowInfo* s_row = (RowInfo*)(s_part + 2 * WM * 2 * BN);   // [2][BM]: rows of the current and of the next tile
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int lrow = tid / KV;                                   // row within a load pass
+    const int kvec = (tid % KV) ^ ((lrow >> 1) & 7);             // K vector this thread fetches (see layout above)
+    const bool do_stats = (!DGRAD) && a.stats != nullptr;
+
+    const int hw_d = a.Hd * a.Wd;
+    const int hw_s = a.Hs * a.Ws;
+    const int frame_bytes = hw_s * a.Cs * 2;
+    const int bias_el = (a.padh * a.Ws + a.padw) * a.Cs;         // the most negative tap origin, in elements
+    const __amdgpu_buffer_rsrc_t rsrc_a =
+        make_rsrc(a.src - bias_el, (uint32_t)(((long)a.F * hw_s * a.Cs + bias_el) * 2));
+    const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.wp, (uint32_t)((long)a.Cd * a.K * 2));
+
+    float* prow = do_stats ? a.stats + (size_t)blockIdx.x * 2 * a.Cd : nullptr;
+    if (do_stats) {
+        for (int c = tid; c < 2 * a.Cd; c += NT) prow[c] = 0.f;
+    }
+
+    const int mtiles = a.mt0[a.ncls];
+    const int total_tiles = ((mtiles + 7) / 8) * 8 * a.ntiles;
+    auto tile_mt = [&](int tile) { return ((tile >> 3) / a.ntiles) * 8 + (tile & 7); };
+    auto next_tile = [&](int tile) {
+        while (tile < total_tiles && tile_mt(tile) >= mtiles) tile += gridDim.x;
+        return tile < total_tiles ? tile : -1;
+    };
+
+    // Producer view of one tile.  Everything but the per-row offsets and masks is the same for all threads.
+    struct Ctx {
+        int n0, nth, ntw, a0h, a0w, ntaps;
+        int nk;               // K steps of the tile, at least two (steps beyond the data multiply zeros)
+        uint32_t aoff[PA];    // byte offset of (row's tap origin, this thread's K vector) in the biased buffer
+        uint32_t amask[PA];
+        uint32_t boff[PB];    // byte offset of (output channel row, this thread's K vector) in the weights
+        int kt, th, tw, chb, ltap;   // next K step to fetch: class-local tap, first channel of the step, flat tap
+    };
+
+    auto decode_rows = [&](int tile, int rb) {
+        if (tid < BM) {
+            const int mt = tile_mt(tile);
+            int cls = 0;
+            while (cls + 1 < a.ncls && mt >= a.mt0[cls + 1]) ++cls;
+            const int hc = a.hc[cls], wc = a.wc[cls];
+            const long Mc = (long)a.F * hc * wc;
+            const long m = (long)(mt - a.mt0[cls]) * BM + tid;
+            RowInfo info;
+            info.off = 0;
+            info.mask = 0;
+            info.dst = -1;
+            if (m < Mc) {
+                const int f = (int)(m / (hc * wc));
+                const int q = (int)(m - (long)f * (hc * wc));
+                const int qh = q / wc, qw = q - qh * wc;
+                const int dh = qh * a.cstep + a.ph[cls], dw = qw * a.cstep + a.pw[cls];
+                const int oh = DGRAD ? (dh - a.padh + a.a0h[cls]) / a.cstep : dh * a.stride - a.padh;
+                const int ow = DGRAD ? (dw - a.padw + a.a0w[cls]) / a.cstep : dw * a.stride - a.padw;
+                const int t = f % a.T;
+                uint32_t mask = 0;
+                for (int th = 0; th < a.nth[cls]; ++th)
+                    if (oh + th >= 0 && oh + th < a.Hs) mask |= 1u << th;
+                for (int tw = 0; tw < a.ntw[cls]; ++tw)
+                    if (ow + tw >= 0 && ow + tw < a.Ws) mask |= 1u << (8 + tw);
+                if (t + 1 < a.T) mask |= 1u << 30;
+                if (t >= 1) mask |= 1u << 31;
+                info.off = ((long)f * hw_s + (long)oh * a.Ws + ow) * a.Cs;
+                info.mask = mask;
+                info.dst = (f * a.Hd + dh) * a.Wd + dw;
+            }
+            s_row[rb * BM + tid] = info;
+        }
+    };
+    auto make_ctx = [&](int tile, int rb) {
+        Ctx c;
+        const int mt = tile_mt(tile);
+        int cls = 0;
+        while (cls + 1 < a.ncls && mt >= a.mt0[cls + 1]) ++cls;
+        c.n0 = ((tile >> 3) % a.ntiles) * BN;
+        c.nth = a.nth[cls]; c.ntw = a.ntw[cls]; c.a0h = a.a0h[cls]; c.a0w = a.a0w[cls];
+        c.ntaps = a.KT * c.nth * c.ntw;
+        c.nk = c.ntaps * (a.Cs / BK);
+        if (c.nk < 2) c.nk = 2;
+#pragma unroll
+        for (int i = 0; i < PA; ++i) {
+            const RowInfo ri = s_row[rb * BM + i * RPP + lrow];
+            c.aoff[i] = (uint32_t)((ri.off + bias_el) * 2) + kvec * 16;
+            c.amask[i] = ri.mask;
+        }
+#pragma unroll
+        for (int j = 0; j < PB; ++j) {
+            const int n = c.n0 + j * RPP + lrow;
+            c.boff[j] = n < a.Cd ? (uint32_t)n * (uint32_t)a.K * 2u + kvec * 16 : OOB_OFFSET;
+        }
+        c.kt = c.th = c.tw = c.ltap = c.chb = 0;
+        return c;
+    };
+
+    // The gathers of one K step: per-thread offsets (OOB_OFFSET for padding), block-wide scalar offsets.
+    constexpr int NP = PA + PB;
+    struct Plan {
+        uint32_t v[NP];
+        int soff_a, soff_b;
+    };
+    // Plans the producer's next K step and advances its position.  `live` false: nothing is left to fetch and
+    // the step is all zeros.
+    auto plan = [&](Ctx& c, bool live) {
+        Plan p;
+        const bool kvalid = live && c.ltap < c.ntaps;
+        const int d0 = c.kt - a.KT / 2;                              // frame offset of a temporal tap
+        const bool lane_dt = !DGRAD && a.fold > 0 && c.chb < 2 * a.fold;   // shifted channels in this step
+        const uint32_t need0 = (1u << c.th) | (1u << (8 + c.tw));
+        p.soff_a = ((c.th * a.Ws + c.tw) * a.Cs + c.chb) * 2;
+        const int ta = c.a0h + c.th * a.cstep, tb = c.a0w + c.tw * a.cstep;   // (flipped) tap coordinates
+        p.soff_b = (((c.kt * a.KH + ta) * a.KW + tb) * a.Cs + c.chb) * 2;
+        if (!kvalid) {
+            p.soff_a = p.soff_b = 0;
+#pragma unroll
+            for (int i = 0; i < NP; ++i) p.v[i] = OOB_OFFSET;
+        } else {
+            if (!lane_dt && d0 == 0) {
+#pragma unroll
+                for (int i = 0; i < PA; ++i) p.v[i] = (c.amask[i] & need0) == need0 ? c.aoff[i] : OOB_OFFSET;
+            } else {
+                const int d = d0 + (lane_dt ? group_dt(c.chb + kvec * 8, a.fold) : 0);   // in {-1, 0, 1}
+                const uint32_t need = need0 | (d > 0 ? 1u << 30 : 0u) | (d < 0 ? 1u << 31 : 0u);
+                const int dl = d * frame_bytes;
+#pragma unroll
+                for (int i = 0; i < PA; ++i) p.v[i] = (c.amask[i] & need) == need ? c.aoff[i] + (uint32_t)dl : OOB_OFFSET;
+            }
+#pragma unroll
+            for (int j = 0; j < PB; ++j) p.v[PA + j] = c.boff[j];
+        }
+        c.chb += BK;
+        if (c.chb >= a.Cs) {
+            c.chb = 0;
+            ++c.ltap;
+            if (++c.tw >= c.ntw) { c.tw = 0; if (++c.th >= c.nth) { c.th = 0; ++c.kt; } }
+        }
+        return p;
+    };
+    // One 16-byte piece of a K step per call: pieces 0..PA-1 are A rows, the rest B rows.  A piece is loaded
+    // into its register during one step and written to the ring during the next one.
+    u32x4 greg[NP];
+    auto load_piece = [&](const Plan& p, int i) {
+        greg[i] = i < PA ? __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, (int)p.v[i], p.soff_a, 0)
+                         : __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, (int)p.v[i], p.soff_b, 0);
+    };
+    auto store_piece = [&](int stage, int i) {   // thread -> row lrow of the piece's pass, position tid % 8
+        const int row0 = i < PA ? i * RPP : BM + (i - PA) * RPP;
+        *(u32x4*)(smem + stage * STAGE + row0 * ROWB + tid * 16) = greg[i];
+    };
+
+    // fragment addresses inside a stage: row (lane % 32) of the wavefront's first row block, K vector
+    // 2*ks + lane/32 at its swizzled position
+    int a_rd[BK / 16], b_rd[BK / 16];
+    {
+        const int r = lane & 31, hi = lane >> 5, sw = (r >> 1) & 7;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            const int pos = ((2 * ks + hi) ^ sw) * 16;
+            a_rd[ks] = (wm * 32 + r) * ROWB + pos;
+            b_rd[ks] = (BM + wn * TN + r) * ROWB + pos;
+        }
+    }
+
+    int tile = next_tile(blockIdx.x);
+    int rb = 0;
+    int cstage = 0;                  // stage being multiplied; the other one is being filled
+    Ctx pc;                          // producer position
+    int p_left = 0;                  // K steps the producer still has to fetch for its tile
+    bool p_on_next = false;          // the producer has moved on to the tile after the current one
+    if (tile >= 0) decode_rows(tile, 0);
+    __syncthreads();                 // also orders the zeroing of the statistics row
+    if (tile >= 0) {
+        pc = make_ctx(tile, 0);
+        p_left = pc.nk - 2;
+        Plan p0 = plan(pc, true);
+#pragma unroll
+        for (int i = 0; i < NP; ++i) load_piece(p0, i);
+#pragma unroll
+        for (int i = 0; i < NP; ++i) store_piece(0, i);
+        Plan p1 = plan(pc, true);
+#pragma unroll
+        for (int i = 0; i < NP; ++i) load_piece(p1, i);
+    }
+    int cur_nk = tile >= 0 ? pc.nk : 0, cur_n0 = tile >= 0 ? pc.n0 : 0;
+
+    while (tile >= 0) {
+        const int ntile = next_tile(tile + gridDim.x);
+        if (ntile >= 0) decode_rows(ntile, rb ^ 1);   // published by the first barrier of the main loop
+
+        f32x16 acc[MI][NJ];
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+        // Main loop.  On entry to step g (stream position of the block, across tiles) stage g % 2 holds step g
+        // and the registers hold step g+1, loaded during step g-1.  While step g is multiplied, the registers
+        // are written to the other stage piece by piece and each freed register is reloaded with its piece of
+        // step g+2.  The pieces are spread over the MFMA groups: issued in one burst, the loads of all eight
+        // wavefronts would fill the address unit's queue and stall the wavefronts in front of their MFMAs.
+        int next_nk = 0, next_n0 = 0;
+        // Plans the step the producer fetches next; the producer crosses into the next tile when it has
+        // fetched all steps of its tile.
+        auto plan_next = [&]() {
+            if (p_left == 0 && !p_on_next) {
+                p_on_next = true;
+                if (ntile >= 0) {
+                    pc = make_ctx(ntile, rb ^ 1);
+                    p_left = pc.nk;
+                    next_nk = pc.nk;
+                    next_n0 = pc.n0;
+                }
+            }
+            const bool live = p_left > 0;
+            if (live) --p_left;
+            return plan(pc, live);
+        };
+        __syncthreads();       // the next tile's rows are decoded
+        Plan pl = plan_next();
+        for (int kc = 0; kc < cur_nk; ++kc) {
+            __syncthreads();   // stage `cstage` is complete, and everybody is done with the other stage
+            const unsigned char* st = smem + cstage * STAGE;
+            constexpr int KS = BK / 16;
+            constexpr int PPK = (NP + KS - 2) / (KS - 1);     // pieces handled after each of the first KS-1 groups
+            bf16x8 af[2][MI], bfr[2][NJ];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) af[0][i] = *(const bf16x8*)(st + a_rd[0] + i * HM * ROWB);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) bfr[0][j] = *(const bf16x8*)(st + b_rd[0] + j * 32 * ROWB);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int cb = ks & 1, nb = cb ^ 1;
+                if (ks + 1 < KS) {
+#pragma unroll
+                    for (int i = 0; i < MI; ++i) af[nb][i] = *(const bf16x8*)(st + a_rd[ks + 1] + i * HM * ROWB);
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) bfr[nb][j] = *(const bf16x8*)(st + b_rd[ks + 1] + j * 32 * ROWB);
+                }
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb][i], bfr[cb][j], acc[i][j], 0, 0, 0);
+#pragma unroll
+                for (int q = ks * PPK; q < (ks + 1) * PPK && q < NP; ++q) {
+                    store_piece(cstage ^ 1, q);
+                    load_piece(pl, q);
+                }
+                __builtin_amdgcn_sched_barrier(0);   // keep the pieces where they are
+            }
+            // the address arithmetic of the next step runs while the last MFMAs of this one are in the pipeline
+            if (kc + 1 < cur_nk) pl = plan_next();
+            cstage ^= 1;
+        }
+
+        // ---- epilogue, one pass per row block through the staging tile; the registers and the other LDS
+        // stage already hold the first two K steps of the next tile.
+        float s1[NJ], s2[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) s1[j] = s2[j] = 0.f;
+#pragma unroll
+        for (int h = 0; h < MI; ++h) {
+            if (h > 0) __syncthreads();   // previous pass stored (the previous tile's last pass: barrier at its end)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const int col = wn * TN + j * 32 + (lane & 31);
+                const bool odd = lane & 1;
+#pragma unroll
+                for (int r = 0; r < 16; r += 2) {
+                    const float v0 = acc[h][j][r], v1 = acc[h][j][r + 1];
+                    if (do_stats) {   // statistics of the values as stored (rows beyond M are exact zeros)
+                        const uint32_t own = pack_bf16x2(v0, v1);
+                        const float q0 = __uint_as_float(own << 16), q1 = __uint_as_float(own & 0xffff0000u);
+                        s1[j] += q0 + q1;
+                        s2[j] = fmaf(q0, q0, fmaf(q1, q1, s2[j]));
+                    }
+                    const float got = __uint_as_float(pair_swap(__float_as_uint(odd ? v0 : v1)));
+                    const uint32_t word = pack_bf16x2(odd ? got : v0, odd ? v1 : got);
+                    const int row = wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3) + (odd ? 1 : 0);
+                    *(uint32_t*)(Cst + row * LDC + (col & ~1)) = word;
+                }
+                if (do_stats && h == MI - 1) {   // own slot: (wavefront row, lane half) x column
+                    const int slot = wm * 2 + (lane >> 5);
+                    s_part[slot * BN + col] = s1[j];
+                    s_part[(WM * 2 + slot) * BN + col] = s2[j];
+                }
+            }
+            __syncthreads();
+            if (do_stats && h == MI - 1 && tid < 2 * BN) {   // fixed summation order over the slots
+                const int stat = tid / BN, col = tid % BN;
+                float v = 0.f;
+#pragma unroll
+                for (int sl = 0; sl < WM * 2; ++sl) v += s_part[(stat * WM * 2 + sl) * BN + col];
+                if (cur_n0 + col < a.Cd) atomicAdd(prow + stat * a.Cd + cur_n0 + col, v);
+            }
+            constexpr int CV = BN / 8;          // vectors per staged row
+            constexpr int RPS = NT / CV;        // rows per pass
+            const int vcol = tid % CV, r0 = tid / CV;
+            const int col = cur_n0 + vcol * 8;
+#pragma unroll
+            for (int pss = 0; pss < HM / RPS; ++pss) {
+                const int row = pss * RPS + r0;
+                const int mrow = s_row[rb * BM + h * HM + row].dst;
+                if (mrow < 0 || col >= a.Cd) continue;
+                const long m = mrow;
+                u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
+                if (!DGRAD) {
+                    *(u32x4*)(a.dst + m * a.Cd + col) = v;
+                } else {
+                    const int dt = group_dt(col, a.fold);
+                    auto emit = [&](long mr, bool with_value) {
+                        u32x4 o = with_value ? v : u32x4{0u, 0u, 0u, 0u};
+                        if (a.addend) {
+                            const u32x4 ad = *(const u32x4*)(a.addend + mr * a.Cd + col);
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                const float lo = __uint_as_float(o[q] << 16) + __uint_as_float(ad[q] << 16);
+                                const float hi = __uint_as_float(o[q] & 0xffff0000u) + __uint_as_float(ad[q] & 0xffff0000u);
+                                o[q] = pack_bf16x2(lo, hi);
+                            }
+                        }
+                        *(u32x4*)(a.dst + mr * a.Cd + col) = o;
+                    };
+                    if (dt == 0) {
+                        emit(m, true);
+                    } else {
+                        const int t = (mrow / hw_d) % a.T;
+                        if (t + dt >= 0 && t + dt < a.T) emit(m + (long)dt * hw_d, true);
+                        if ((dt == 1 && t == 0) || (dt == -1 && t == a.T - 1)) emit(m, false);
+                    }
+                }
+            }
+        }
+        __syncthreads();   // the row buffer of this tile is decoded into again at the top of the next tile
+        tile = ntile;
+        rb ^= 1;
+        cur_nk = next_nk;
+        cur_n0 = next_n0;
+        p_on_next = false;
+    }
+}
+
+// ---------------------------------------------------------------------------------
 static int g_num_cu = 0;
 static int num_cu() {
     if (g_num_cu == 0) {
@@ -516,18 +907,52 @@ static int launch_igemm(IgemmArgs& a, const char* name, hipStream_t s) {
     return check_launch(name);   // class names carry the tile shape so that they map one-to-one onto kernel symbols
 }
 
-// Tile choice: narrow outputs (<= 64 channels) take the 128x64 tile, everything else 128x128; both keep two
-// blocks per CU and one K step in flight.  (A 256x128 tile with two K steps in flight was tried: the compiler
-// spills in its main loop and it runs three times slower.)
+template <int BM, int BN, int WM, int WN, bool DGRAD>
+static int launch_igemm_ring(IgemmArgs& a, const char* name, hipStream_t s) {
+    const int mtiles = setup_classes(a, DGRAD, BM);
+    a.ntiles = (a.Cd + BN - 1) / BN;
+    // two operand stages, staging tile of one epilogue pass, statistics slots, two row buffers
+    const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t) + (size_t)(WM * 32) * (BN + 8) * sizeof(bf16_t) +
+                        (size_t)2 * WM * 2 * BN * sizeof(float) + (size_t)2 * BM * sizeof(RowInfo);
+    auto kern = igemm_ring_kernel<BM, BN, WM, WN, DGRAD>;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return fail(TSM_ERR_LAUNCH, "igemm: cannot raise dynamic LDS limit");
+        configured = true;
+    }
+    const int grid = igemm_grid(mtiles, a.Cd, BN, 1);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, a);
+    return check_launch(name);
+}
+
+// Tile choice.  The 256x128 ring kernel (one block of eight wavefronts per CU) takes every layer whose source
+// channels are a multiple of 64, whose output is wider than 64 channels and whose tensors stay below the 2 GiB
+// that its 32-bit buffer offsets address; the rest goes to the register-prefetch kernels, two blocks per CU:
+// 128x64 tiles for narrow outputs (<= 64 channels), 128x128 otherwise.
+static bool ring_eligible(int Cs, int Cd, long src_elems, long w_elems) {
+    static int enabled = -1;   // TSM_IGEMM_RING=0 keeps the register-prefetch kernels everywhere (for comparisons)
+    if (enabled < 0) {
+        const char* e = getenv("TSM_IGEMM_RING");
+        enabled = (e && e[0] == '0') ? 0 : 1;
+    }
+    const long limit = 0x7ff00000L;   // bytes, leaves room for the padding bias in front of the tensor
+    return enabled && Cd > 64 && Cs % BK == 0 && src_elems * 2 < limit && w_elems * 2 < limit;
+}
+
 template <bool DGRAD>
 static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     const long rows = (long)a.F * a.Hd * a.Wd;
     if (rows == 0) return TSM_OK;
+    if (ring_eligible(a.Cs, a.Cd, (long)a.F * a.Hs * a.Ws * a.Cs + (long)(a.padh * a.Ws + a.padw) * a.Cs, (long)a.Cd * a.K))
+        return launch_igemm_ring<256, 128, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_256x128" : "igemm_fwd_256x128", s);
     if (a.Cd <= 64) return launch_igemm<128, 64, 4, 1, DGRAD, 1, 2>(a, DGRAD ? "igemm_dgrad_128x64" : "igemm_fwd_128x64", s);
     return launch_igemm<128, 128, 2, 2, DGRAD, 1, 2>(a, DGRAD ? "igemm_dgrad_128x128" : "igemm_fwd_128x128", s);
 }
 
 int conv_mfma_fwd_blocks(const ConvP& p) {
+    if (ring_eligible(p.Cin, p.Cout, p.rows_in() * (long)p.Cin + (long)(p.pad * p.W + p.pad) * p.Cin, (long)p.Cout * p.K()))
+        return igemm_grid((int)((p.rows_out() + 255) / 256), p.Cout, 128, 1);
     return igemm_grid((int)((p.rows_out() + 127) / 128), p.Cout, p.Cout <= 64 ? 64 : 128, 2);
 }
 
