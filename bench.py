@@ -50,8 +50,18 @@ def igemm_class(kind, cd, cs):
     return "igemm_%s_%s" % (kind, "128x64" if cd <= 64 else "128x128")
 
 
-def wgrad_class(cout, kk):
-    """Tile the library picks for a weight gradient with `cout` output channels and K = taps * Cin."""
+def wgrad_class(cout, cin, taps):
+    """Tile the library picks for a weight gradient (`cin` as stored: the stem's 3 channels are padded to 8)."""
+    kk = taps * cin
+    if cin % 64 == 0 and cout % 64 == 0:
+        if cout % 256 == 0:
+            return "wgrad_tr_256x128" if cin % 128 == 0 else "wgrad_tr_256x64"
+        if cout % 128 == 0 and cin % 128 == 0:
+            return "wgrad_tr_128x128"
+        if cin % 256 == 0:
+            return "wgrad_tr_64x256"
+        if taps == 1:
+            return "wgrad_tr_64x64"
     if cout > 64 and kk > 64:
         return "wgrad_128x128"
     return "wgrad_64x192" if (cout <= 64 and kk >= 192 and kk % 192 == 0) else "wgrad_64x64"
@@ -70,8 +80,7 @@ def class_work(F, size):
         add(igemm_class("fwd", cout, 8 if name == "conv1" else cin), macs)
         if has_dgrad:
             add(igemm_class("dgrad", cin, cout), macs)
-        kk = taps * (8 if name == "conv1" else cin)
-        add(wgrad_class(cout, kk), macs)
+        add(wgrad_class(cout, 8 if name == "conv1" else cin, taps), macs)
     return work
 
 
@@ -90,8 +99,7 @@ def class_bytes(F, size):
         if has_dgrad:
             extra = x_b if name.endswith(".c1") else 0.0       # the shortcut gradient added in the epilogue
             add(igemm_class("dgrad", cin, cout), x_b + y_b + extra)
-        kk = taps * cin_s
-        add(wgrad_class(cout, kk), x_b + y_b)
+        add(wgrad_class(cout, cin_s, taps), x_b + y_b)
     return byt
 
 

@@ -1198,6 +1198,255 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs a) {
         }
 }
 
+// ---------------------------------------------------------------------------------
+// Weight gradient for input channel counts that are a multiple of BCI (a column tile lies inside one tap) and
+// output channel counts that are a multiple of BCO.  Same product as wgrad_kernel, different data path:
+//
+//  * Pixel rows go to LDS the way they come from memory, [pixel][channel], with 16-byte stores.  The MFMA
+//    operands, which need the pixel index contiguous per channel, are read with the transposing LDS load
+//    (ds_read_b64_tr_b16): within 16 lanes, lane 4e+c supplies the address of four channels 4c..4c+3 of pixel
+//    e, and lane i receives pixels 0..3 of channel i.  Two such loads give the eight pixels per lane of a
+//    32x32x16 operand.  No shuffling in registers, no strided LDS stores.
+//  * A row's 32-byte blocks are XOR-ed with 2*(pixel % 4): the four pixels x two channel blocks that 32 lanes
+//    read together then fall into eight different bank groups.
+//  * Gathers are buffer loads as in igemm_ring_kernel (scalar offset = position of the 64-pixel step, lanes on
+//    padding or beyond the pixel range get zeros from the bounds check), software-pipelined the same way:
+//    step g is multiplied from one LDS stage while step g+1 moves from registers into the other and step g+2
+//    is loaded, a few pieces after each group of MFMAs.
+//  * The gather origin of a pixel (frame, row, column -> offset and tap validity) is decoded one pixel per
+//    thread for NT pixels at a time, a batch ahead of its use.
+struct PixInfo {
+    uint32_t off;    // byte offset of the pixel's gather origin in the biased x buffer
+    uint32_t mask;   // as RowInfo::mask; 0 beyond the block's pixel range
+};
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ bf16x8 lds_read_tr_pair(const unsigned char* p0, const unsigned char* p1) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p0);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p1);
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+template <int BCO, int BCI, int WM, int WN>
+__global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int TM = BCO / WM, TN = BCI / WN;       // wavefront tile
+    constexpr int MI = TM / 32, NJ = TN / 32;
+    constexpr int PXS = WMK;                          // pixels per step
+    constexpr int ROWA = BCO * 2, ROWB = BCI * 2;     // bytes per pixel row of the two operands
+    constexpr int STAGE = PXS * (ROWA + ROWB);
+    constexpr int AVR = BCO / 8, BVR = BCI / 8;       // 16-byte pieces per row
+    constexpr int RA = NT / AVR, RB = NT / BVR;       // rows per load pass
+    constexpr int PA = PXS / RA, PB = PXS / RB;
+    constexpr int NP = PA + PB;
+    constexpr int SPB = NT / PXS;                     // steps per decoded batch of NT pixels
+    constexpr int KS = PXS / 16;
+    static_assert(RA % 4 == 0 && RB % 4 == 0 && PXS % RA == 0 && PXS % RB == 0, "tile / thread mismatch");
+    static_assert(NT % PXS == 0 && SPB >= 4, "whole steps per batch; a batch is decoded at least three steps ahead");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [2][STAGE], then the pixel table
+    PixInfo* s_pix = (PixInfo*)(smem + 2 * STAGE);                           // [2][NT]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int co0 = (blockIdx.y / a.col_tiles) * BCO;
+    const int j0 = (blockIdx.y % a.col_tiles) * BCI;
+    const int tap = j0 / a.Cin, ci0 = j0 - tap * a.Cin;
+    const long mbeg = (long)blockIdx.x * a.chunk;
+    long mend = mbeg + a.chunk;
+    if (mend > a.M) mend = a.M;
+    if (mbeg >= mend) return;
+    const int nsteps = (int)((mend - mbeg + PXS - 1) / PXS);
+    const int hw = a.Ho * a.Wo;
+    const int bias_el = (a.pad * a.W + a.pad) * a.Cin;
+    const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(a.dy, (uint32_t)(a.M * a.Cout * 2));
+    const __amdgpu_buffer_rsrc_t rsrc_b =
+        make_rsrc(a.x - bias_el, (uint32_t)(((long)a.F * a.H * a.W * a.Cin + bias_el) * 2));
+
+    // ---- this thread's pieces: dy rows arow + i*RA, x rows brow + j*RB of every step
+    const int avec = tid % AVR, arow = tid / AVR;
+    const int bvec = tid % BVR, brow = tid / BVR;
+    uint32_t a_off[PA];
+#pragma unroll
+    for (int i = 0; i < PA; ++i) a_off[i] = (uint32_t)(((arow + i * RA) * a.Cout + co0 + avec * 8) * 2);
+    uint32_t b_need, b_const;
+    {
+        const int ci = ci0 + bvec * 8;
+        const int kw = tap % a.KW, kh = (tap / a.KW) % a.KH, kt = tap / (a.KW * a.KH);
+        const int d = kt - a.KT / 2 + group_dt(ci, a.fold);
+        b_need = (1u << kh) | (1u << (8 + kw)) | (d > 0 ? 1u << 30 : 0u) | (d < 0 ? 1u << 31 : 0u);
+        b_const = (uint32_t)((d * a.H * a.W * a.Cin + (kh * a.W + kw) * a.Cin + ci) * 2);
+    }
+    // LDS positions of the pieces (row r, 16-byte vector v): 32-byte block (v/2) ^ 2*(r%4), half v%2
+    // (rows of 128 bytes hold only four blocks and two of them span the banks: there the XOR is 2*((r/2)%2))
+    auto swz_a = [](int r) { return ROWA >= 256 ? 2 * (r & 3) : 2 * ((r >> 1) & 1); };
+    auto swz_b = [](int r) { return ROWB >= 256 ? 2 * (r & 3) : 2 * ((r >> 1) & 1); };
+    const int a_wr = arow * ROWA + ((((avec >> 1) ^ swz_a(arow)) << 5) | ((avec & 1) << 4));
+    const int b_wr = PXS * ROWA + brow * ROWB + ((((bvec >> 1) ^ swz_b(brow)) << 5) | ((bvec & 1) << 4));
+
+    // ---- operand read addresses (see the layout of the transposing load above): lane = 32*kg + 16*mblk + 4*e + c
+    int a_rd[MI], b_rd[NJ];
+    {
+        const int c = lane & 3, e = (lane >> 2) & 3, mblk = (lane >> 4) & 1, kg = lane >> 5;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+            a_rd[i] = (8 * kg + e) * ROWA + ((((wm * (TM / 16) + i * 2 + mblk) ^ swz_a(e)) << 5) | (c << 3));
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+            b_rd[j] = PXS * ROWA + (8 * kg + e) * ROWB + ((((wn * (TN / 16) + j * 2 + mblk) ^ swz_b(e)) << 5) | (c << 3));
+    }
+
+    auto decode = [&](int batch) {   // one pixel per thread
+        const long m = mbeg + (long)batch * NT + tid;
+        PixInfo info;
+        info.off = 0;
+        info.mask = 0;
+        if (m < mend) {
+            const int f = (int)(m / hw);
+            const int pix = (int)(m - (long)f * hw);
+            const int oh = pix / a.Wo, ow = pix - oh * a.Wo;
+            const int ih = oh * a.stride - a.pad, iw = ow * a.stride - a.pad;
+            const int t = f % a.T;
+            uint32_t mask = 0;
+            for (int kh = 0; kh < a.KH; ++kh)
+                if (ih + kh >= 0 && ih + kh < a.H) mask |= 1u << kh;
+            for (int kw = 0; kw < a.KW; ++kw)
+                if (iw + kw >= 0 && iw + kw < a.W) mask |= 1u << (8 + kw);
+            if (t + 1 < a.T) mask |= 1u << 30;
+            if (t >= 1) mask |= 1u << 31;
+            info.off = (uint32_t)((((long)f * a.H * a.W + (long)ih * a.W + iw) * a.Cin + bias_el) * 2);
+            info.mask = mask;
+        }
+        s_pix[(batch & 1) * NT + tid] = info;
+    };
+
+    struct Plan {
+        uint32_t v[NP];
+        int soff_a;
+    };
+    auto plan = [&](int st) {   // step st (may lie beyond the last one: all zeros then)
+        Plan p;
+        const long left = mend - (mbeg + (long)st * PXS);        // pixels from the step's first one to the end
+        p.soff_a = left > 0 ? (int)((mbeg + (long)st * PXS) * a.Cout * 2) : 0;
+#pragma unroll
+        for (int i = 0; i < PA; ++i) p.v[i] = (arow + i * RA) < left ? a_off[i] : OOB_OFFSET;
+        const PixInfo* tab = s_pix + ((st / SPB) & 1) * NT + (st % SPB) * PXS;
+#pragma unroll
+        for (int j = 0; j < PB; ++j) {
+            const PixInfo pi = tab[brow + j * RB];
+            p.v[PA + j] = (left > 0 && (pi.mask & b_need) == b_need) ? pi.off + b_const : OOB_OFFSET;
+        }
+        return p;
+    };
+    u32x4 greg[NP];
+    auto load_piece = [&](const Plan& p, int i) {
+        greg[i] = i < PA ? __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, (int)p.v[i], p.soff_a, 0)
+                         : __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, (int)p.v[i], 0, 0);
+    };
+    auto store_piece = [&](int stage, int i) {
+        const int pos = i < PA ? a_wr + i * RA * ROWA : b_wr + (i - PA) * RB * ROWB;
+        *(u32x4*)(smem + stage * STAGE + pos) = greg[i];
+    };
+
+    f32x16 acc[MI][NJ];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    decode(0);
+    __syncthreads();
+    {
+        const Plan p0 = plan(0);
+#pragma unroll
+        for (int i = 0; i < NP; ++i) load_piece(p0, i);
+#pragma unroll
+        for (int i = 0; i < NP; ++i) store_piece(0, i);
+        const Plan p1 = plan(1);
+#pragma unroll
+        for (int i = 0; i < NP; ++i) load_piece(p1, i);
+    }
+    Plan pl = plan(2);
+
+    for (int st = 0; st < nsteps; ++st) {
+        // batch b+1 is decoded during the first step of batch b; it is first read by the plan of its first
+        // step, two steps before that step is multiplied
+        if (st % SPB == 0 && (st / SPB + 1) * SPB < nsteps) decode(st / SPB + 1);
+        __syncthreads();   // stage st % 2 is complete, and everybody is done with the other stage
+        const unsigned char* cur = smem + (st & 1) * STAGE;
+        constexpr int PPK = (NP + KS - 2) / (KS - 1);
+        bf16x8 af[2][MI], bfr[2][NJ];
+#pragma unroll
+        for (int i = 0; i < MI; ++i) af[0][i] = lds_read_tr_pair(cur + a_rd[i], cur + a_rd[i] + 4 * ROWA);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) bfr[0][j] = lds_read_tr_pair(cur + b_rd[j], cur + b_rd[j] + 4 * ROWB);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int cb = ks & 1, nb = cb ^ 1;
+            if (ks + 1 < KS) {
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+                    af[nb][i] = lds_read_tr_pair(cur + a_rd[i] + (ks + 1) * 16 * ROWA, cur + a_rd[i] + ((ks + 1) * 16 + 4) * ROWA);
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    bfr[nb][j] = lds_read_tr_pair(cur + b_rd[j] + (ks + 1) * 16 * ROWB, cur + b_rd[j] + ((ks + 1) * 16 + 4) * ROWB);
+            }
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb][i], bfr[cb][j], acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int q = ks * PPK; q < (ks + 1) * PPK && q < NP; ++q) {
+                store_piece((st & 1) ^ 1, q);
+                load_piece(pl, q);
+            }
+            __builtin_amdgcn_sched_barrier(0);   // keep the pieces where they are
+        }
+        if (st + 1 < nsteps) pl = plan(st + 3);
+    }
+
+    // ---- fp32 atomics: lane = column (input channel), register = row (output channel)
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const int ci = ci0 + wn * TN + j * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int co = co0 + wm * TM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                atomicAdd(a.dw + (long)co * a.so + (long)ci * a.si + (long)tap * a.st, acc[i][j][r]);
+            }
+        }
+}
+
+template <int BCO, int BCI, int WM, int WN>
+static int launch_wgrad_tr(WgradArgs& a, int Cout, int blocks_per_cu, const char* name, hipStream_t s) {
+    constexpr int NT = WM * WN * 64;
+    a.col_tiles = a.K / BCI;
+    const int tiles = (Cout / BCO) * a.col_tiles;
+    long want = (long)blocks_per_cu * num_cu() / tiles;
+    if (want < 1) want = 1;
+    const long chunk = (a.M + want - 1) / want;
+    a.chunk = (chunk + WMK - 1) / WMK * WMK;
+    const dim3 grid((unsigned)((a.M + a.chunk - 1) / a.chunk), (unsigned)tiles);
+    auto kern = wgrad_tr_kernel<BCO, BCI, WM, WN>;
+    const size_t smem = (size_t)2 * WMK * (BCO + BCI) * 2 + (size_t)2 * NT * sizeof(PixInfo);
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return fail(TSM_ERR_LAUNCH, "wgrad: cannot raise dynamic LDS limit");
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(NT), smem, s, a);
+    return check_launch(name);
+}
+
 int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, bool packed,
                     hipStream_t s) {
     WgradArgs a;
@@ -1214,6 +1463,25 @@ int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw
     a.M = p.rows_out();
     a.K = (int)p.K();
     if (a.M == 0) return TSM_OK;
+    {   // transposing-read kernels: channel counts that fill whole tiles, tensors below 2 GiB
+        static int enabled = -1;   // TSM_WGRAD_TR=0 keeps the register-transposing kernels everywhere (for comparisons)
+        if (enabled < 0) {
+            const char* e = getenv("TSM_WGRAD_TR");
+            enabled = (e && e[0] == '0') ? 0 : 1;
+        }
+        const long limit = 0x7ff00000L;
+        const bool fits = a.M * p.Cout * 2 < limit && (p.rows_in() * (long)p.Cin + (long)(p.pad * p.W + p.pad) * p.Cin) * 2 < limit;
+        if (enabled && fits && cin_real == p.Cin && p.Cin % 64 == 0 && p.Cout % 64 == 0) {
+            // blocks per CU follow from the LDS footprint of two stages
+            if (p.Cout % 256 == 0 && p.Cin % 128 == 0) return launch_wgrad_tr<256, 128, 4, 2>(a, p.Cout, 1, "wgrad_tr_256x128", s);
+            if (p.Cout % 256 == 0) return launch_wgrad_tr<256, 64, 4, 1>(a, p.Cout, 1, "wgrad_tr_256x64", s);
+            if (p.Cout % 128 == 0 && p.Cin % 128 == 0) return launch_wgrad_tr<128, 128, 2, 2>(a, p.Cout, 2, "wgrad_tr_128x128", s);
+            if (p.Cin % 256 == 0) return launch_wgrad_tr<64, 256, 1, 4>(a, p.Cout, 1, "wgrad_tr_64x256", s);
+            // 64 x 64 channels with several taps: the 64x192 register-transposing tile below shares the dy tile
+            // among three taps and is faster
+            if (p.taps() == 1) return launch_wgrad_tr<64, 64, 2, 2>(a, p.Cout, 4, "wgrad_tr_64x64", s);
+        }
+    }
     // tiles: 128x128 for wide outputs; for <= 64 output channels a 64x192 tile when K is long enough (the
     // transposed dy tile is then shared by three times as many columns); 64x64 otherwise
     const bool big = p.Cout > 64 && a.K > 64;
