@@ -45,8 +45,8 @@ def conv_layers(F, size):
 def igemm_class(kind, cd, cs):
     """Tile the library picks for a forward ("fwd") or data-gradient ("dgrad") convolution that produces
     `cd` channels from `cs` source channels (tensors below 2 GiB, which holds for every workload here)."""
-    if cd > 64 and cs % 64 == 0:
-        return "igemm_%s_256x128" % kind
+    if cs % 64 == 0:
+        return "igemm_%s_%s" % (kind, "256x64" if cd <= 64 else "256x128")
     return "igemm_%s_%s" % (kind, "128x64" if cd <= 64 else "128x128")
 
 

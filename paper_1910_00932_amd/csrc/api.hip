@@ -60,15 +60,18 @@ int run_conv_fwd(const ConvP& p, int dtype, const void* x, const void* w, const 
     return TSM_OK;
 }
 
+int conv_dgrad_fuse_blocks(const ConvP& p, int dtype) { return use_mfma(p, dtype) ? conv_mfma_dgrad_blocks(p) : 0; }
+
 int run_conv_dgrad(const ConvP& p, int dtype, const void* dy, const void* w, const bf16_t* wd, void* dx,
-                   const void* addend, Arena& ws, bool dry, hipStream_t s) {
+                   const void* addend, const DgradFuse* fuse, Arena& ws, bool dry, hipStream_t s) {
+    if (fuse && !use_mfma(p, dtype)) return fail(TSM_ERR_UNSUPPORTED, "dgrad: no fused path for this layer");
     if (use_mfma(p, dtype)) {
         if (!wd) {
             bf16_t* pk = ws.take_n<bf16_t>((size_t)p.Cout * p.K());
             RUN(pack_weights_dgrad(dtype, w, pk, p.Cout, p.Cin, p.KT, p.KH, p.KW, s));
             wd = pk;
         }
-        RUN(conv_mfma_dgrad(p, (const bf16_t*)dy, wd, (bf16_t*)dx, (const bf16_t*)addend, s));
+        RUN(conv_mfma_dgrad(p, (const bf16_t*)dy, wd, (bf16_t*)dx, (const bf16_t*)addend, fuse, s));
     } else {
         RUN(conv_direct_dgrad(p, dtype, dy, w, dx, addend, s));
     }
@@ -143,7 +146,7 @@ static int conv_entry(int which, const tsm_conv_desc* d, const void* a0, const v
             RUN(transpose_frames(a0, dyt, p.F, p.Cout, p.Ho * p.Wo, es, s));
             dy = dyt;
         }
-        TSM_TRY(run_conv_dgrad(p, d->dtype, dy, a1, nullptr, dx, nullptr, ws, dry, s));
+        TSM_TRY(run_conv_dgrad(p, d->dtype, dy, a1, nullptr, dx, nullptr, nullptr, ws, dry, s));
         if (tr) RUN(transpose_frames(dx, out, p.F, p.H * p.W, p.Cin, es, s));
     } else {
         const void *x = a0, *dy = a1;
@@ -227,14 +230,21 @@ int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dou
     const size_t out_bytes = (size_t)pl.rows_out() * pl.Cout * es;
     void* dzL = ws.take(out_bytes);
     void* dyL = ws.take(out_bytes);
-    const int nbL = red_blocks(pl.rows_out(), pl.Cout, b.dtype);
+    const bool chained = b.dout_part != nullptr;   // dout is dz already, its sums are in dout_part
+    if (chained && b.proj) return fail(TSM_ERR_UNSUPPORTED, "block backward: a chained gradient needs an identity shortcut");
+    const int nbL = chained ? b.dout_nb : red_blocks(pl.rows_out(), pl.Cout, b.dtype);
     float* partL = ws.take_n<float>((size_t)nbL * 2 * pl.Cout);
     float* partd = ws.take_n<float>((size_t)nbL * 2 * pl.Cout);
     float* coefL = ws.take_n<float>(3 * (size_t)pl.Cout);
     const int acc_flag = b.grads_prezeroed ? 1 : 0;
-    RUN(relu_bn_bwd_reduce(b.dtype, dout, out, b.y[L], pl.rows_out(), pl.Cout, b.bn[L].mean, b.bn[L].rstd, dzL, partL,
-                           b.proj ? b.yd : nullptr, b.proj ? b.bnd.mean : nullptr, b.proj ? b.bnd.rstd : nullptr,
-                           b.proj ? partd : nullptr, s));
+    if (chained) {
+        dzL = const_cast<void*>(dout);
+        partL = const_cast<float*>(b.dout_part);
+    } else {
+        RUN(relu_bn_bwd_reduce(b.dtype, dout, out, b.y[L], pl.rows_out(), pl.Cout, b.bn[L].mean, b.bn[L].rstd, dzL, partL,
+                               b.proj ? b.yd : nullptr, b.proj ? b.bnd.mean : nullptr, b.proj ? b.bnd.rstd : nullptr,
+                               b.proj ? partd : nullptr, s));
+    }
     RUN(bn_bwd_coeffs(partL, nbL, pl.rows_out(), pl.Cout, b.bn[L].mean, b.bn[L].rstd, b.st[L].g, coefL, b.st[L].dg,
                       b.st[L].db, s));
     RUN(bn_bwd_apply(b.dtype, dzL, b.y[L], pl.rows_out(), pl.Cout, coefL, dyL, s));
@@ -244,12 +254,20 @@ int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dou
         const ConvP& pp = b.st[i - 1].p;  // producer of this stage's input
         TSM_TRY(run_conv_wgrad(st.p, b.dtype, b.z[i - 1], g, st.dw, acc_flag, ws, dry, s));
         void* dzin = ws.take((size_t)pp.rows_out() * pp.Cout * es);
-        TSM_TRY(run_conv_dgrad(st.p, b.dtype, g, st.w, st.wd, dzin, nullptr, ws, dry, s));
-        const int nb = red_blocks(pp.rows_out(), pp.Cout, b.dtype);
+        // the ReLU mask and the BatchNorm reductions of the producing stage ride in the data gradient's
+        // epilogue when its kernel can do that; otherwise they are a pass of their own
+        const int nbf = conv_dgrad_fuse_blocks(st.p, b.dtype);
+        const int nb = nbf ? nbf : red_blocks(pp.rows_out(), pp.Cout, b.dtype);
         float* part = ws.take_n<float>((size_t)nb * 2 * pp.Cout);
         float* coef = ws.take_n<float>(3 * (size_t)pp.Cout);
-        RUN(relu_bn_bwd_reduce(b.dtype, dzin, b.z[i - 1], b.y[i - 1], pp.rows_out(), pp.Cout, b.bn[i - 1].mean,
-                               b.bn[i - 1].rstd, dzin, part, nullptr, nullptr, nullptr, nullptr, s));
+        if (nbf) {
+            const DgradFuse fz = {(const bf16_t*)b.z[i - 1], (const bf16_t*)b.y[i - 1], b.bn[i - 1].mean, b.bn[i - 1].rstd, part};
+            TSM_TRY(run_conv_dgrad(st.p, b.dtype, g, st.w, st.wd, dzin, nullptr, &fz, ws, dry, s));
+        } else {
+            TSM_TRY(run_conv_dgrad(st.p, b.dtype, g, st.w, st.wd, dzin, nullptr, nullptr, ws, dry, s));
+            RUN(relu_bn_bwd_reduce(b.dtype, dzin, b.z[i - 1], b.y[i - 1], pp.rows_out(), pp.Cout, b.bn[i - 1].mean,
+                                   b.bn[i - 1].rstd, dzin, part, nullptr, nullptr, nullptr, nullptr, s));
+        }
         RUN(bn_bwd_coeffs(part, nb, pp.rows_out(), pp.Cout, b.bn[i - 1].mean, b.bn[i - 1].rstd, b.st[i - 1].g, coef,
                           b.st[i - 1].dg, b.st[i - 1].db, s));
         RUN(bn_bwd_apply(b.dtype, dzin, b.y[i - 1], pp.rows_out(), pp.Cout, coef, dzin, s));
@@ -265,10 +283,10 @@ int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dou
         RUN(bn_bwd_apply(b.dtype, dzL, b.yd, pl.rows_out(), pl.Cout, coefd, dyd, s));
         TSM_TRY(run_conv_wgrad(st.p, b.dtype, x, dyd, st.dw, acc_flag, ws, dry, s));
         void* dsc = ws.take((size_t)st.p.rows_in() * st.p.Cin * es);
-        TSM_TRY(run_conv_dgrad(st.p, b.dtype, dyd, st.w, st.wd, dsc, nullptr, ws, dry, s));
+        TSM_TRY(run_conv_dgrad(st.p, b.dtype, dyd, st.w, st.wd, dsc, nullptr, nullptr, ws, dry, s));
         addend = dsc;
     }
-    if (dx || dry) TSM_TRY(run_conv_dgrad(b.st[0].p, b.dtype, g, b.st[0].w, b.st[0].wd, dx, addend, ws, dry, s));
+    if (dx || dry) TSM_TRY(run_conv_dgrad(b.st[0].p, b.dtype, g, b.st[0].w, b.st[0].wd, dx, addend, b.dx_fuse, ws, dry, s));
     return TSM_OK;
 }
 

@@ -23,6 +23,12 @@ struct BlockPlan {
     int dtype;
     float eps, bn_momentum;
     bool grads_prezeroed;  // the caller zeroed every dw: weight gradients are added without a fill
+    // Chaining inside a network (both optional).  dout_part: the gradient handed to block_bwd_impl is already
+    // masked with out > 0 and the BatchNorm sums of the last stage are in dout_part, dout_nb rows (the
+    // producer was a fused data gradient).  dx_fuse: applied to the data gradient that produces dx.
+    const float* dout_part;
+    int dout_nb;
+    const DgradFuse* dx_fuse;
     // saved-for-backward buffers (caller-owned memory)
     void* y[3];           // convolution outputs
     void* z[2];           // ReLU(BN(y)) of all but the last stage
@@ -34,8 +40,10 @@ struct BlockPlan {
 int conv_stats_blocks(const ConvP& p, int dtype);
 int run_conv_fwd(const ConvP& p, int dtype, const void* x, const void* w, const bf16_t* wp, void* y,
                  float* stats_partial, Arena& ws, bool dry, hipStream_t s);
+// Rows of the partial buffer a fused data gradient fills (see DgradFuse); 0 when it cannot fuse.
+int conv_dgrad_fuse_blocks(const ConvP& p, int dtype);
 int run_conv_dgrad(const ConvP& p, int dtype, const void* dy, const void* w, const bf16_t* wd, void* dx,
-                   const void* addend, Arena& ws, bool dry, hipStream_t s);
+                   const void* addend, const DgradFuse* fuse, Arena& ws, bool dry, hipStream_t s);
 int run_conv_wgrad(const ConvP& p, int dtype, const void* x, const void* dy, float* dw, int accumulate, Arena& ws,
                    bool dry, hipStream_t s);
 

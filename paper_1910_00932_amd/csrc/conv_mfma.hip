@@ -31,7 +31,14 @@ struct IgemmArgs {
     const bf16_t* wp;      // packed weights [N][K]
     bf16_t* dst;           // y (fwd) or dx (dgrad)
     const bf16_t* addend;  // dgrad only: added to dx (nullable)
-    float* stats;          // fwd only: per-block partial sums, [gridDim.x][2*Cd] (nullable)
+    float* stats;          // per-block partial sums, [gridDim.x][2*Cd] (nullable): fwd: sum and sum of squares of
+                           // y; dgrad with `act`: the two BatchNorm-backward sums of the masked gradient
+    // dgrad, igemm_ring_kernel only (nullable): dst is the gradient w.r.t. act = ReLU(BatchNorm(ybn)).  The
+    // epilogue then zeroes it where act <= 0 and accumulates, per channel, sum(dz) and sum(dz * (ybn - mean) * rstd).
+    const bf16_t* act;
+    const bf16_t* ybn;
+    const float* bn_mean;
+    const float* bn_rstd;
     int F, T;
     int Hs, Ws, Cs;        // source frame
     int Hd, Wd, Cd;        // destination frame; Cd = GEMM N
@@ -477,6 +484,8 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
     const int lrow = tid / KV;                                   // row within a load pass
     const int kvec = (tid % KV) ^ ((lrow >> 1) & 7);             // K vector this thread fetches (see layout above)
     const bool do_stats = (!DGRAD) && a.stats != nullptr;
+    const bool fuse_bn = DGRAD && a.act != nullptr;   // ReLU mask + BatchNorm-backward sums in the epilogue
+    static_assert(WM * WN <= WM * 2, "one statistics slot per wavefront");
 
     const int hw_d = a.Hd * a.Wd;
     const int hw_s = a.Hs * a.Ws;
@@ -486,8 +495,8 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
         make_rsrc(a.src - bias_el, (uint32_t)(((long)a.F * hw_s * a.Cs + bias_el) * 2));
     const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.wp, (uint32_t)((long)a.Cd * a.K * 2));
 
-    float* prow = do_stats ? a.stats + (size_t)blockIdx.x * 2 * a.Cd : nullptr;
-    if (do_stats) {
+    float* prow = (do_stats || fuse_bn) ? a.stats + (size_t)blockIdx.x * 2 * a.Cd : nullptr;
+    if (do_stats || fuse_bn) {
         for (int c = tid; c < 2 * a.Cd; c += NT) prow[c] = 0.f;
     }
 
@@ -735,6 +744,21 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
         float s1[NJ], s2[NJ];
 #pragma unroll
         for (int j = 0; j < NJ; ++j) s1[j] = s2[j] = 0.f;
+        // fused BatchNorm backward: this thread stores the same eight columns of every row it handles
+        constexpr int FV = DGRAD ? 8 : 1;
+        float f1[FV], f2[FV], mu[FV], rs[FV];
+#pragma unroll
+        for (int q = 0; q < FV; ++q) f1[q] = f2[q] = mu[q] = rs[q] = 0.f;
+        if (fuse_bn) {
+            const int c0 = cur_n0 + (tid % (BN / 8)) * 8;
+            if (c0 < a.Cd) {
+#pragma unroll
+                for (int q = 0; q < FV; ++q) {
+                    mu[q] = a.bn_mean[c0 + q];
+                    rs[q] = a.bn_rstd[c0 + q];
+                }
+            }
+        }
 #pragma unroll
         for (int h = 0; h < MI; ++h) {
             if (h > 0) __syncthreads();   // previous pass stored (the previous tile's last pass: barrier at its end)
@@ -774,38 +798,111 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
             constexpr int RPS = NT / CV;        // rows per pass
             const int vcol = tid % CV, r0 = tid / CV;
             const int col = cur_n0 + vcol * 8;
+            if (!DGRAD) {
 #pragma unroll
-            for (int pss = 0; pss < HM / RPS; ++pss) {
-                const int row = pss * RPS + r0;
-                const int mrow = s_row[rb * BM + h * HM + row].dst;
-                if (mrow < 0 || col >= a.Cd) continue;
-                const long m = mrow;
-                u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
-                if (!DGRAD) {
-                    *(u32x4*)(a.dst + m * a.Cd + col) = v;
-                } else {
-                    const int dt = group_dt(col, a.fold);
-                    auto emit = [&](long mr, bool with_value) {
-                        u32x4 o = with_value ? v : u32x4{0u, 0u, 0u, 0u};
-                        if (a.addend) {
-                            const u32x4 ad = *(const u32x4*)(a.addend + mr * a.Cd + col);
+                for (int pss = 0; pss < HM / RPS; ++pss) {
+                    const int row = pss * RPS + r0;
+                    const int mrow = s_row[rb * BM + h * HM + row].dst;
+                    if (mrow < 0 || col >= a.Cd) continue;
+                    *(u32x4*)(a.dst + (long)mrow * a.Cd + col) = *(const u32x4*)(Cst + row * LDC + vcol * 8);
+                }
+            } else {
+                // value (+ addend) -> optional ReLU mask and BatchNorm sums -> store
+                auto finish = [&](long mr, u32x4 o, const u32x4& ad, const u32x4& ac, const u32x4& yy) {
+                    if (a.addend) {
 #pragma unroll
-                            for (int q = 0; q < 4; ++q) {
-                                const float lo = __uint_as_float(o[q] << 16) + __uint_as_float(ad[q] << 16);
-                                const float hi = __uint_as_float(o[q] & 0xffff0000u) + __uint_as_float(ad[q] & 0xffff0000u);
-                                o[q] = pack_bf16x2(lo, hi);
-                            }
+                        for (int q = 0; q < 4; ++q) {
+                            const float lo = __uint_as_float(o[q] << 16) + __uint_as_float(ad[q] << 16);
+                            const float hi = __uint_as_float(o[q] & 0xffff0000u) + __uint_as_float(ad[q] & 0xffff0000u);
+                            o[q] = pack_bf16x2(lo, hi);
                         }
-                        *(u32x4*)(a.dst + mr * a.Cd + col) = o;
-                    };
+                    }
+                    if (fuse_bn) {   // on the values as stored (bf16)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const float alo = __uint_as_float(ac[q] << 16), ahi = __uint_as_float(ac[q] & 0xffff0000u);
+                            const float dlo = alo > 0.f ? __uint_as_float(o[q] << 16) : 0.f;
+                            const float dhi = ahi > 0.f ? __uint_as_float(o[q] & 0xffff0000u) : 0.f;
+                            o[q] = (alo > 0.f ? o[q] & 0xffffu : 0u) | (ahi > 0.f ? o[q] & 0xffff0000u : 0u);
+                            f1[2 * q] += dlo;
+                            f1[2 * q + 1] += dhi;
+                            f2[2 * q] = fmaf(dlo, (__uint_as_float(yy[q] << 16) - mu[2 * q]) * rs[2 * q], f2[2 * q]);
+                            f2[2 * q + 1] = fmaf(dhi, (__uint_as_float(yy[q] & 0xffff0000u) - mu[2 * q + 1]) * rs[2 * q + 1], f2[2 * q + 1]);
+                        }
+                    }
+                    *(u32x4*)(a.dst + mr * a.Cd + col) = o;
+                };
+                // The operands of all rows of the pass are requested first, so that their latencies overlap.
+                // A row's value goes to frame t + dt of its channel group (adjoint shift); the frame of the
+                // group that receives nothing from inside the clip gets a zero value (rare, handled last).
+                constexpr int NPS = HM / RPS;
+                const int dt = group_dt(col, a.fold);
+                long mr[NPS], mz[NPS];
+                u32x4 ad[NPS], ac[NPS], yy[NPS];
+#pragma unroll
+                for (int pss = 0; pss < NPS; ++pss) {
+                    const int mrow = s_row[rb * BM + h * HM + pss * RPS + r0].dst;
+                    mr[pss] = mz[pss] = -1;
+                    ad[pss] = ac[pss] = yy[pss] = u32x4{0u, 0u, 0u, 0u};
+                    if (mrow < 0 || col >= a.Cd) continue;
                     if (dt == 0) {
-                        emit(m, true);
+                        mr[pss] = mrow;
                     } else {
                         const int t = (mrow / hw_d) % a.T;
-                        if (t + dt >= 0 && t + dt < a.T) emit(m + (long)dt * hw_d, true);
-                        if ((dt == 1 && t == 0) || (dt == -1 && t == a.T - 1)) emit(m, false);
+                        if (t + dt >= 0 && t + dt < a.T) mr[pss] = (long)mrow + (long)dt * hw_d;
+                        if ((dt == 1 && t == 0) || (dt == -1 && t == a.T - 1)) mz[pss] = mrow;
+                    }
+                    if (mr[pss] >= 0) {
+                        const long e = mr[pss] * a.Cd + col;
+                        if (a.addend) ad[pss] = *(const u32x4*)(a.addend + e);
+                        if (fuse_bn) {
+                            ac[pss] = *(const u32x4*)(a.act + e);
+                            yy[pss] = *(const u32x4*)(a.ybn + e);
+                        }
                     }
                 }
+#pragma unroll
+                for (int pss = 0; pss < NPS; ++pss)
+                    if (mr[pss] >= 0) finish(mr[pss], *(const u32x4*)(Cst + (pss * RPS + r0) * LDC + vcol * 8), ad[pss], ac[pss], yy[pss]);
+#pragma unroll
+                for (int pss = 0; pss < NPS; ++pss) {
+                    if (mz[pss] < 0) continue;
+                    const long e = mz[pss] * a.Cd + col;
+                    u32x4 zad = u32x4{0u, 0u, 0u, 0u}, zac = zad, zyy = zad;
+                    if (a.addend) zad = *(const u32x4*)(a.addend + e);
+                    if (fuse_bn) {
+                        zac = *(const u32x4*)(a.act + e);
+                        zyy = *(const u32x4*)(a.ybn + e);
+                    }
+                    finish(mz[pss], u32x4{0u, 0u, 0u, 0u}, zad, zac, zyy);
+                }
+            }
+        }
+        if (fuse_bn) {
+            // lanes CV apart hold the same columns: fold them, then one slot per wavefront, fixed order over the slots
+            constexpr int CV = BN / 8;
+#pragma unroll
+            for (int q = 0; q < FV; ++q) {
+#pragma unroll
+                for (int off = CV; off < 64; off <<= 1) {
+                    f1[q] += __shfl_xor(f1[q], off);
+                    f2[q] += __shfl_xor(f2[q], off);
+                }
+            }
+            if (lane < CV) {
+#pragma unroll
+                for (int q = 0; q < FV; ++q) {
+                    s_part[wave * BN + lane * 8 + q] = f1[q];
+                    s_part[(WM * 2 + wave) * BN + lane * 8 + q] = f2[q];
+                }
+            }
+            __syncthreads();
+            if (tid < 2 * BN) {
+                const int stat = tid / BN, col = tid % BN;
+                float v = 0.f;
+#pragma unroll
+                for (int sl = 0; sl < WM * WN; ++sl) v += s_part[(stat * WM * 2 + sl) * BN + col];
+                if (cur_n0 + col < a.Cd) atomicAdd(prow + stat * a.Cd + cur_n0 + col, v);
             }
         }
         __syncthreads();   // the row buffer of this tile is decoded into again at the top of the next tile
@@ -926,39 +1023,43 @@ static int launch_igemm_ring(IgemmArgs& a, const char* name, hipStream_t s) {
     return check_launch(name);
 }
 
-// Tile choice.  The 256x128 ring kernel (one block of eight wavefronts per CU) takes every layer whose source
-// channels are a multiple of 64, whose output is wider than 64 channels and whose tensors stay below the 2 GiB
-// that its 32-bit buffer offsets address; the rest goes to the register-prefetch kernels, two blocks per CU:
-// 128x64 tiles for narrow outputs (<= 64 channels), 128x128 otherwise.
-static bool ring_eligible(int Cs, int Cd, long src_elems, long w_elems) {
+// Tile choice.  The ring kernel (one block of eight wavefronts per CU; 256x128 tiles, 256x64 for outputs of at
+// most 64 channels) takes every layer whose source channels are a multiple of 64 and whose tensors stay below
+// the 2 GiB that its 32-bit buffer offsets address; the rest goes to the register-prefetch kernels, two blocks
+// per CU: 128x64 tiles for narrow outputs (<= 64 channels), 128x128 otherwise.
+static bool ring_eligible(int Cs, long src_elems, long w_elems) {
     static int enabled = -1;   // TSM_IGEMM_RING=0 keeps the register-prefetch kernels everywhere (for comparisons)
     if (enabled < 0) {
         const char* e = getenv("TSM_IGEMM_RING");
         enabled = (e && e[0] == '0') ? 0 : 1;
     }
     const long limit = 0x7ff00000L;   // bytes, leaves room for the padding bias in front of the tensor
-    return enabled && Cd > 64 && Cs % BK == 0 && src_elems * 2 < limit && w_elems * 2 < limit;
+    return enabled && Cs % BK == 0 && src_elems * 2 < limit && w_elems * 2 < limit;
 }
 
 template <bool DGRAD>
 static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     const long rows = (long)a.F * a.Hd * a.Wd;
     if (rows == 0) return TSM_OK;
-    if (ring_eligible(a.Cs, a.Cd, (long)a.F * a.Hs * a.Ws * a.Cs + (long)(a.padh * a.Ws + a.padw) * a.Cs, (long)a.Cd * a.K))
+    if (ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.Cs + (long)(a.padh * a.Ws + a.padw) * a.Cs, (long)a.Cd * a.K)) {
+        if (a.Cd <= 64) return launch_igemm_ring<256, 64, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_256x64" : "igemm_fwd_256x64", s);
         return launch_igemm_ring<256, 128, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_256x128" : "igemm_fwd_256x128", s);
+    }
     if (a.Cd <= 64) return launch_igemm<128, 64, 4, 1, DGRAD, 1, 2>(a, DGRAD ? "igemm_dgrad_128x64" : "igemm_fwd_128x64", s);
     return launch_igemm<128, 128, 2, 2, DGRAD, 1, 2>(a, DGRAD ? "igemm_dgrad_128x128" : "igemm_fwd_128x128", s);
 }
 
 int conv_mfma_fwd_blocks(const ConvP& p) {
-    if (ring_eligible(p.Cin, p.Cout, p.rows_in() * (long)p.Cin + (long)(p.pad * p.W + p.pad) * p.Cin, (long)p.Cout * p.K()))
-        return igemm_grid((int)((p.rows_out() + 255) / 256), p.Cout, 128, 1);
-    return igemm_grid((int)((p.rows_out() + 127) / 128), p.Cout, p.Cout <= 64 ? 64 : 128, 2);
+    const int bn = p.Cout <= 64 ? 64 : 128;
+    if (ring_eligible(p.Cin, p.rows_in() * (long)p.Cin + (long)(p.pad * p.W + p.pad) * p.Cin, (long)p.Cout * p.K()))
+        return igemm_grid((int)((p.rows_out() + 255) / 256), p.Cout, bn, 1);
+    return igemm_grid((int)((p.rows_out() + 127) / 128), p.Cout, bn, 2);
 }
 
 int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, float* stats, hipStream_t s) {
     IgemmArgs a;
     a.src = x; a.wp = wp; a.dst = y; a.addend = nullptr; a.stats = stats;
+    a.act = nullptr; a.ybn = nullptr; a.bn_mean = nullptr; a.bn_rstd = nullptr;
     a.F = p.F; a.T = p.T;
     a.Hs = p.H; a.Ws = p.W; a.Cs = p.Cin;
     a.Hd = p.Ho; a.Wd = p.Wo; a.Cd = p.Cout;
@@ -969,10 +1070,7 @@ int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, 
     return dispatch_igemm<false>(a, s);
 }
 
-int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* dx, const bf16_t* addend,
-                    hipStream_t s) {
-    IgemmArgs a;
-    a.src = dy; a.wp = wd; a.dst = dx; a.addend = addend; a.stats = nullptr;
+static void dgrad_args(const ConvP& p, IgemmArgs& a) {
     a.F = p.F; a.T = p.T;
     a.Hs = p.Ho; a.Ws = p.Wo; a.Cs = p.Cout;
     a.Hd = p.H; a.Wd = p.W; a.Cd = p.Cin;
@@ -980,6 +1078,27 @@ int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* 
     a.stride = p.stride; a.padh = p.KH - 1 - p.pad; a.padw = p.KW - 1 - p.pad;
     a.fold = p.fold;
     a.K = p.taps() * p.Cout;
+}
+
+int conv_mfma_dgrad_blocks(const ConvP& p) {
+    IgemmArgs a;
+    dgrad_args(p, a);
+    if (!ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.Cs + (long)(a.padh * a.Ws + a.padw) * a.Cs, (long)a.Cd * a.K)) return 0;
+    if ((long)a.F * a.Hd * a.Wd == 0) return 0;
+    const int mtiles = setup_classes(a, true, 256);
+    return igemm_grid(mtiles, a.Cd, a.Cd <= 64 ? 64 : 128, 1);
+}
+
+int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* dx, const bf16_t* addend,
+                    const DgradFuse* fuse, hipStream_t s) {
+    IgemmArgs a;
+    a.src = dy; a.wp = wd; a.dst = dx; a.addend = addend; a.stats = nullptr;
+    a.act = nullptr; a.ybn = nullptr; a.bn_mean = nullptr; a.bn_rstd = nullptr;
+    dgrad_args(p, a);
+    if (fuse) {
+        if (conv_mfma_dgrad_blocks(p) == 0) return fail(TSM_ERR_UNSUPPORTED, "dgrad: this layer's kernel cannot fuse the BatchNorm reductions");
+        a.act = fuse->act; a.ybn = fuse->y; a.bn_mean = fuse->mean; a.bn_rstd = fuse->rstd; a.stats = fuse->partial;
+    }
     return dispatch_igemm<true>(a, s);
 }
 

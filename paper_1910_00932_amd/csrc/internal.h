@@ -85,9 +85,22 @@ int conv_mfma_fwd_blocks(const ConvP& p);
 // y = conv(S(x)); wp = bf16 [Cout][taps][Cin]; stats_partial (nullable), fp32 [conv_mfma_fwd_blocks(p)][2*Cout],
 // receives per block the per-channel sum / sum of squares of the stored (rounded) output.
 int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, float* stats_partial, hipStream_t s);
-// dx = S^T(conv^T(dy)) + addend; wd = bf16 [Cin][flipped taps][Cout]
+// Optional fusion into the data-gradient epilogue: dx is the gradient w.r.t. act = ReLU(BatchNorm(y)) (all
+// [rows_in][Cin] bf16); it is stored already masked with act > 0, and `partial`, fp32
+// [conv_mfma_dgrad_blocks(p)][2*Cin], receives per block the per-channel sums of dz and of dz*(y-mean)*rstd.
+struct DgradFuse {
+    const bf16_t* act;
+    const bf16_t* y;
+    const float* mean;
+    const float* rstd;
+    float* partial;
+};
+// Blocks the data-gradient kernel launches for p when it can fuse (rows of DgradFuse::partial); 0 when this
+// layer's kernel cannot.
+int conv_mfma_dgrad_blocks(const ConvP& p);
+// dx = S^T(conv^T(dy)) + addend; wd = bf16 [Cin][flipped taps][Cout]; fuse nullable
 int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* dx, const bf16_t* addend,
-                    hipStream_t s);
+                    const DgradFuse* fuse, hipStream_t s);
 // dw fp32, accumulated with atomics: zero it first (or keep what is there to accumulate).
 // packed: [Cout][taps][p.Cin] (contiguous atomics, the fast order when taps > 1);
 // otherwise the ABI order [Cout][cin_real][taps].  Channels >= cin_real are padding and are not written.

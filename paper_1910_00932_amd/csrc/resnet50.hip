@@ -537,6 +537,18 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
         if (by > act_max) act_max = by;
     }
     void* dbuf[2] = {A.take(act_max), A.take(act_max)};
+    // Chaining: the data gradient that produces block i's input gradient also applies block i-1's output
+    // ReLU mask and accumulates the sums of its last BatchNorm, when block i-1 has an identity shortcut and the
+    // kernel can fuse.
+    std::vector<float*> chain_part(blks.size(), nullptr);
+    std::vector<int> chain_nb(blks.size(), 0);
+    for (size_t i = 1; i < blks.size(); ++i) {
+        if (blks[i - 1].plan.proj) continue;
+        const int nbf = conv_dgrad_fuse_blocks(blks[i].plan.st[0].p, dtype);
+        if (!nbf) continue;
+        chain_nb[i - 1] = nbf;
+        chain_part[i - 1] = A.take_n<float>((size_t)nbf * 2 * blks[i - 1].plan.st[2].p.Cout);
+    }
     void* da0 = A.take((size_t)F * H1 * H1 * 64 * es);
     char* scratch_base = dry ? nullptr : (char*)wsp + A.used;
     const size_t scratch_cap = dry ? (size_t)-1 : (ws_bytes > A.used ? ws_bytes - A.used : 0);
@@ -611,6 +623,15 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
     for (int i = (int)blks.size() - 1; i >= 0; --i) {
         Blk& b = blks[i];
         Arena sc(scratch_base, scratch_cap);
+        DgradFuse fz;
+        b.plan.dx_fuse = nullptr;
+        if (i > 0 && chain_nb[i - 1]) {
+            BlockPlan& pp = blks[i - 1].plan;
+            fz = DgradFuse{(const bf16_t*)blks[i - 1].out, (const bf16_t*)pp.y[2], pp.bn[2].mean, pp.bn[2].rstd, chain_part[i - 1]};
+            b.plan.dx_fuse = &fz;
+            pp.dout_part = dry ? (const float*)1 : chain_part[i - 1];   // (dry run: only the flag matters)
+            pp.dout_nb = chain_nb[i - 1];
+        }
         TSM_TRY(block_bwd_impl(b.plan, b.in, b.out, dbuf[cur], dbuf[cur ^ 1], sc, dry, s));
         note(sc);
         cur ^= 1;
