@@ -77,10 +77,11 @@ def class_work(F, size):
 
     for name, rin, cin, rout, cout, taps, has_dgrad in conv_layers(F, size):
         macs = float(rout) * cout * cin * taps
-        add(igemm_class("fwd", cout, 8 if name == "conv1" else cin), macs)
+        stem = name == "conv1"   # runs in space-to-depth form: 64 "channels" x 4 taps, see the library
+        add(igemm_class("fwd", cout, 64 if stem else cin), macs)
         if has_dgrad:
             add(igemm_class("dgrad", cin, cout), macs)
-        add(wgrad_class(cout, 8 if name == "conv1" else cin, taps), macs)
+        add("wgrad_tr_64x256" if stem else wgrad_class(cout, cin, taps), macs)
     return work
 
 
@@ -93,13 +94,15 @@ def class_bytes(F, size):
         byt[cls] = byt.get(cls, 0.0) + b
 
     for name, rin, cin, rout, cout, taps, has_dgrad in conv_layers(F, size):
-        cin_s = 8 if name == "conv1" else cin
-        x_b, y_b = 2.0 * rin * cin_s, 2.0 * rout * cout
-        add(igemm_class("fwd", cout, cin_s), x_b + y_b)
+        stem = name == "conv1"
+        x_b, y_b = 2.0 * rin * cin, 2.0 * rout * cout
+        if stem:   # the space-to-depth image: (size/2 + 3)^2 pixels of 16 values per frame
+            x_b = 2.0 * F * (size // 2 + 3) ** 2 * 16
+        add(igemm_class("fwd", cout, 64 if stem else cin), x_b + y_b)
         if has_dgrad:
             extra = x_b if name.endswith(".c1") else 0.0       # the shortcut gradient added in the epilogue
             add(igemm_class("dgrad", cin, cout), x_b + y_b + extra)
-        add(wgrad_class(cout, cin_s, taps), x_b + y_b)
+        add("wgrad_tr_64x256" if stem else wgrad_class(cout, cin, taps), x_b + y_b)
     return byt
 
 

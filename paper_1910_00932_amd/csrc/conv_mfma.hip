@@ -41,6 +41,7 @@ struct IgemmArgs {
     const float* bn_rstd;
     int F, T;
     int Hs, Ws, Cs;        // source frame
+    int pitch;             // elements between consecutive source pixels (Cs, or less: see ConvP::pitch)
     int Hd, Wd, Cd;        // destination frame; Cd = GEMM N
     int KT, KH, KW;
     int stride;
@@ -489,10 +490,10 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
 
     const int hw_d = a.Hd * a.Wd;
     const int hw_s = a.Hs * a.Ws;
-    const int frame_bytes = hw_s * a.Cs * 2;
-    const int bias_el = (a.padh * a.Ws + a.padw) * a.Cs;         // the most negative tap origin, in elements
+    const int frame_bytes = hw_s * a.pitch * 2;
+    const int bias_el = (a.padh * a.Ws + a.padw) * a.pitch;      // the most negative tap origin, in elements
     const __amdgpu_buffer_rsrc_t rsrc_a =
-        make_rsrc(a.src - bias_el, (uint32_t)(((long)a.F * hw_s * a.Cs + bias_el) * 2));
+        make_rsrc(a.src - bias_el, (uint32_t)(((long)a.F * hw_s * a.pitch + (a.Cs - a.pitch) + bias_el) * 2));
     const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.wp, (uint32_t)((long)a.Cd * a.K * 2));
 
     float* prow = (do_stats || fuse_bn) ? a.stats + (size_t)blockIdx.x * 2 * a.Cd : nullptr;
@@ -545,7 +546,7 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                     if (ow + tw >= 0 && ow + tw < a.Ws) mask |= 1u << (8 + tw);
                 if (t + 1 < a.T) mask |= 1u << 30;
                 if (t >= 1) mask |= 1u << 31;
-                info.off = ((long)f * hw_s + (long)oh * a.Ws + ow) * a.Cs;
+                info.off = ((long)f * hw_s + (long)oh * a.Ws + ow) * a.pitch;
                 info.mask = mask;
                 info.dst = (f * a.Hd + dh) * a.Wd + dw;
             }
@@ -591,7 +592,7 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
         const int d0 = c.kt - a.KT / 2;                              // frame offset of a temporal tap
         const bool lane_dt = !DGRAD && a.fold > 0 && c.chb < 2 * a.fold;   // shifted channels in this step
         const uint32_t need0 = (1u << c.th) | (1u << (8 + c.tw));
-        p.soff_a = ((c.th * a.Ws + c.tw) * a.Cs + c.chb) * 2;
+        p.soff_a = ((c.th * a.Ws + c.tw) * a.pitch + c.chb) * 2;
         const int ta = c.a0h + c.th * a.cstep, tb = c.a0w + c.tw * a.cstep;   // (flipped) tap coordinates
         p.soff_b = (((c.kt * a.KH + ta) * a.KW + tb) * a.Cs + c.chb) * 2;
         if (!kvalid) {
@@ -1041,17 +1042,18 @@ template <bool DGRAD>
 static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     const long rows = (long)a.F * a.Hd * a.Wd;
     if (rows == 0) return TSM_OK;
-    if (ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.Cs + (long)(a.padh * a.Ws + a.padw) * a.Cs, (long)a.Cd * a.K)) {
+    if (ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K)) {
         if (a.Cd <= 64) return launch_igemm_ring<256, 64, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_256x64" : "igemm_fwd_256x64", s);
         return launch_igemm_ring<256, 128, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_256x128" : "igemm_fwd_256x128", s);
     }
+    if (a.pitch != a.Cs) return fail(TSM_ERR_UNSUPPORTED, "igemm: a pixel pitch other than the channel count needs the 64-channel-step kernel");
     if (a.Cd <= 64) return launch_igemm<128, 64, 4, 1, DGRAD, 1, 2>(a, DGRAD ? "igemm_dgrad_128x64" : "igemm_fwd_128x64", s);
     return launch_igemm<128, 128, 2, 2, DGRAD, 1, 2>(a, DGRAD ? "igemm_dgrad_128x128" : "igemm_fwd_128x128", s);
 }
 
 int conv_mfma_fwd_blocks(const ConvP& p) {
     const int bn = p.Cout <= 64 ? 64 : 128;
-    if (ring_eligible(p.Cin, p.rows_in() * (long)p.Cin + (long)(p.pad * p.W + p.pad) * p.Cin, (long)p.Cout * p.K()))
+    if (ring_eligible(p.Cin, p.rows_in() * (long)p.pix_pitch() + p.Cin + (long)(p.pad * p.W + p.pad) * p.pix_pitch(), (long)p.Cout * p.K()))
         return igemm_grid((int)((p.rows_out() + 255) / 256), p.Cout, bn, 1);
     return igemm_grid((int)((p.rows_out() + 127) / 128), p.Cout, bn, 2);
 }
@@ -1061,7 +1063,7 @@ int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, 
     a.src = x; a.wp = wp; a.dst = y; a.addend = nullptr; a.stats = stats;
     a.act = nullptr; a.ybn = nullptr; a.bn_mean = nullptr; a.bn_rstd = nullptr;
     a.F = p.F; a.T = p.T;
-    a.Hs = p.H; a.Ws = p.W; a.Cs = p.Cin;
+    a.Hs = p.H; a.Ws = p.W; a.Cs = p.Cin; a.pitch = p.pix_pitch();
     a.Hd = p.Ho; a.Wd = p.Wo; a.Cd = p.Cout;
     a.KT = p.KT; a.KH = p.KH; a.KW = p.KW;
     a.stride = p.stride; a.padh = p.pad; a.padw = p.pad;
@@ -1072,7 +1074,7 @@ int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, 
 
 static void dgrad_args(const ConvP& p, IgemmArgs& a) {
     a.F = p.F; a.T = p.T;
-    a.Hs = p.Ho; a.Ws = p.Wo; a.Cs = p.Cout;
+    a.Hs = p.Ho; a.Ws = p.Wo; a.Cs = p.Cout; a.pitch = p.Cout;
     a.Hd = p.H; a.Wd = p.W; a.Cd = p.Cin;
     a.KT = p.KT; a.KH = p.KH; a.KW = p.KW;
     a.stride = p.stride; a.padh = p.KH - 1 - p.pad; a.padw = p.KW - 1 - p.pad;
@@ -1083,7 +1085,7 @@ static void dgrad_args(const ConvP& p, IgemmArgs& a) {
 int conv_mfma_dgrad_blocks(const ConvP& p) {
     IgemmArgs a;
     dgrad_args(p, a);
-    if (!ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.Cs + (long)(a.padh * a.Ws + a.padw) * a.Cs, (long)a.Cd * a.K)) return 0;
+    if (!ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K)) return 0;
     if ((long)a.F * a.Hd * a.Wd == 0) return 0;
     const int mtiles = setup_classes(a, true, 256);
     return igemm_grid(mtiles, a.Cd, a.Cd <= 64 ? 64 : 128, 1);
@@ -1118,6 +1120,7 @@ struct WgradArgs {
     int si, st, cin_real;
     int F, T;
     int H, W, Cin;
+    int pitch;             // elements between consecutive input pixels (Cin, or less: see ConvP::pitch)
     int Ho, Wo, Cout;
     int KT, KH, KW, stride, pad;
     int fold;
@@ -1373,17 +1376,16 @@ __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
     const int wm = wave / WN, wn = wave % WN;
     const int co0 = (blockIdx.y / a.col_tiles) * BCO;
     const int j0 = (blockIdx.y % a.col_tiles) * BCI;
-    const int tap = j0 / a.Cin, ci0 = j0 - tap * a.Cin;
     const long mbeg = (long)blockIdx.x * a.chunk;
     long mend = mbeg + a.chunk;
     if (mend > a.M) mend = a.M;
     if (mbeg >= mend) return;
     const int nsteps = (int)((mend - mbeg + PXS - 1) / PXS);
     const int hw = a.Ho * a.Wo;
-    const int bias_el = (a.pad * a.W + a.pad) * a.Cin;
+    const int bias_el = (a.pad * a.W + a.pad) * a.pitch;
     const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(a.dy, (uint32_t)(a.M * a.Cout * 2));
     const __amdgpu_buffer_rsrc_t rsrc_b =
-        make_rsrc(a.x - bias_el, (uint32_t)(((long)a.F * a.H * a.W * a.Cin + bias_el) * 2));
+        make_rsrc(a.x - bias_el, (uint32_t)(((long)a.F * a.H * a.W * a.pitch + (a.Cin - a.pitch) + bias_el) * 2));
 
     // ---- this thread's pieces: dy rows arow + i*RA, x rows brow + j*RB of every step
     const int avec = tid % AVR, arow = tid / AVR;
@@ -1393,11 +1395,12 @@ __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
     for (int i = 0; i < PA; ++i) a_off[i] = (uint32_t)(((arow + i * RA) * a.Cout + co0 + avec * 8) * 2);
     uint32_t b_need, b_const;
     {
-        const int ci = ci0 + bvec * 8;
+        const int j = j0 + bvec * 8;                 // column of D: (tap, input channel), constant for the thread
+        const int tap = j / a.Cin, ci = j - tap * a.Cin;
         const int kw = tap % a.KW, kh = (tap / a.KW) % a.KH, kt = tap / (a.KW * a.KH);
         const int d = kt - a.KT / 2 + group_dt(ci, a.fold);
         b_need = (1u << kh) | (1u << (8 + kw)) | (d > 0 ? 1u << 30 : 0u) | (d < 0 ? 1u << 31 : 0u);
-        b_const = (uint32_t)((d * a.H * a.W * a.Cin + (kh * a.W + kw) * a.Cin + ci) * 2);
+        b_const = (uint32_t)((d * a.H * a.W * a.pitch + (kh * a.W + kw) * a.pitch + ci) * 2);
     }
     // LDS positions of the pieces (row r, 16-byte vector v): 32-byte block (v/2) ^ 2*(r%4), half v%2
     // (rows of 128 bytes hold only four blocks and two of them span the banks: there the XOR is 2*((r/2)%2))
@@ -1436,7 +1439,7 @@ __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
                 if (iw + kw >= 0 && iw + kw < a.W) mask |= 1u << (8 + kw);
             if (t + 1 < a.T) mask |= 1u << 30;
             if (t >= 1) mask |= 1u << 31;
-            info.off = (uint32_t)((((long)f * a.H * a.W + (long)ih * a.W + iw) * a.Cin + bias_el) * 2);
+            info.off = (uint32_t)((((long)f * a.H * a.W + (long)ih * a.W + iw) * a.pitch + bias_el) * 2);
             info.mask = mask;
         }
         s_pix[(batch & 1) * NT + tid] = info;
@@ -1535,7 +1538,8 @@ __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
     for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
-            const int ci = ci0 + wn * TN + j * 32 + (lane & 31);
+            const int col = j0 + wn * TN + j * 32 + (lane & 31);
+            const int tap = col / a.Cin, ci = col - tap * a.Cin;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int co = co0 + wm * TM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
@@ -1575,7 +1579,7 @@ int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw
     } else {        // ABI order [Cout][cin_real][taps]
         a.so = (long)cin_real * p.taps(); a.si = p.taps(); a.st = 1;
     }
-    a.F = p.F; a.T = p.T; a.H = p.H; a.W = p.W; a.Cin = p.Cin;
+    a.F = p.F; a.T = p.T; a.H = p.H; a.W = p.W; a.Cin = p.Cin; a.pitch = p.pix_pitch();
     a.Ho = p.Ho; a.Wo = p.Wo; a.Cout = p.Cout;
     a.KT = p.KT; a.KH = p.KH; a.KW = p.KW; a.stride = p.stride; a.pad = p.pad;
     a.fold = p.fold;
@@ -1589,18 +1593,21 @@ int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw
             enabled = (e && e[0] == '0') ? 0 : 1;
         }
         const long limit = 0x7ff00000L;
-        const bool fits = a.M * p.Cout * 2 < limit && (p.rows_in() * (long)p.Cin + (long)(p.pad * p.W + p.pad) * p.Cin) * 2 < limit;
+        const bool fits = a.M * p.Cout * 2 < limit &&
+                          (p.rows_in() * (long)a.pitch + p.Cin + (long)(p.pad * p.W + p.pad) * a.pitch) * 2 < limit;
         if (enabled && fits && cin_real == p.Cin && p.Cin % 64 == 0 && p.Cout % 64 == 0) {
             // blocks per CU follow from the LDS footprint of two stages
             if (p.Cout % 256 == 0 && p.Cin % 128 == 0) return launch_wgrad_tr<256, 128, 4, 2>(a, p.Cout, 1, "wgrad_tr_256x128", s);
             if (p.Cout % 256 == 0) return launch_wgrad_tr<256, 64, 4, 1>(a, p.Cout, 1, "wgrad_tr_256x64", s);
             if (p.Cout % 128 == 0 && p.Cin % 128 == 0) return launch_wgrad_tr<128, 128, 2, 2>(a, p.Cout, 2, "wgrad_tr_128x128", s);
-            if (p.Cin % 256 == 0) return launch_wgrad_tr<64, 256, 1, 4>(a, p.Cout, 1, "wgrad_tr_64x256", s);
+            // (a column tile may span several taps: 64 input channels x 4 taps fill the 256 columns too)
+            if (a.K % 256 == 0 && (p.Cin % 256 == 0 || a.pitch != p.Cin)) return launch_wgrad_tr<64, 256, 1, 4>(a, p.Cout, 1, "wgrad_tr_64x256", s);
             // 64 x 64 channels with several taps: the 64x192 register-transposing tile below shares the dy tile
             // among three taps and is faster
             if (p.taps() == 1) return launch_wgrad_tr<64, 64, 2, 2>(a, p.Cout, 4, "wgrad_tr_64x64", s);
         }
     }
+    if (a.pitch != p.Cin) return fail(TSM_ERR_UNSUPPORTED, "wgrad: a pixel pitch other than the channel count needs the transposing-read kernels");
     // tiles: 128x128 for wide outputs; for <= 64 output channels a 64x192 tile when K is long enough (the
     // transposed dy tile is then shared by three times as many columns); 64x64 otherwise
     const bool big = p.Cout > 64 && a.K > 64;

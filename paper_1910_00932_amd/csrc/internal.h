@@ -13,6 +13,11 @@ struct ConvP {
     int KT, KH, KW;      // temporal (1 or 3) and spatial taps
     int stride, pad;     // spatial; the temporal taps use stride 1, padding KT/2
     int fold;            // channels shifted each way on the input (0: none)
+    // Elements between consecutive input pixels; 0 means Cin.  A smaller pitch makes the "channels" of a tap
+    // overlap the following pixels: a convolution whose taps along W are folded into the channel dimension
+    // (MFMA kernels with Cin % 64 == 0 only; the caller guarantees that every read stays inside the tensor).
+    int pitch = 0;
+    int pix_pitch() const { return pitch ? pitch : Cin; }
     long rows_in() const { return (long)F * H * W; }
     long rows_out() const { return (long)F * Ho * Wo; }
     int taps() const { return KT * KH * KW; }

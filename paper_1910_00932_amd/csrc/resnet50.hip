@@ -80,15 +80,54 @@ static int find_tensor(const std::vector<TensorInfo>& t, const std::string& name
     return -1;
 }
 
-// ---- stem input: [F][3][S][S] planes -> [F][S][S][8] (channels 3..7 zero) ---------------------
-__global__ void __launch_bounds__(256) clips_to_nhwc8_kernel(const bf16_t* __restrict__ in, uint4* __restrict__ out,
-                                                             long pixels_per_frame, long total) {
-    long i = (long)blockIdx.x * 256 + threadIdx.x;
+// ---- stem in space-to-depth form ------------------------------------------------------------------
+// The 7x7 stride-2 convolution over 3 channels equals a 4x4 stride-1 convolution over the 2x2
+// space-to-depth image of the zero-padded input: with xs[h][w][(ph, pw, c)] = x[2h+ph-3][2w+pw-3][c],
+//   y[oh][ow] = sum over th, tw < 4, ph, pw < 2, c of w[2th+ph][2tw+pw][c] * xs[oh+th][ow+tw][(ph, pw, c)]
+// (taps with index 7 are zero).  xs keeps 16 values per pixel (channel (ph*2+pw)*4 + c, c = 3 is zero), so the
+// four taps along W of one output pixel are 64 contiguous values: the MFMA kernels see a convolution with
+// KH = 4, KW = 1, 64 channels and a pixel pitch of 16.  Every tap lies inside xs (S/2 + 3 pixels each way).
+__global__ void __launch_bounds__(256) clips_to_s2d_kernel(const bf16_t* __restrict__ in, uint4* __restrict__ out,
+                                                           int S, int Hs, long total) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;   // output pixel
     if (i >= total) return;
-    const long f = i / pixels_per_frame, p = i - f * pixels_per_frame;
-    const bf16_t* base = in + f * 3 * pixels_per_frame + p;
-    const uint32_t c0 = base[0], c1 = base[pixels_per_frame], c2 = base[2 * pixels_per_frame];
-    out[i] = make_uint4(c0 | (c1 << 16), c2, 0u, 0u);
+    const int w = (int)(i % Hs), h = (int)((i / Hs) % Hs);
+    const long f = i / ((long)Hs * Hs);
+    const bf16_t* base = in + f * 3 * (long)S * S;
+    uint32_t v[8];
+#pragma unroll
+    for (int sp = 0; sp < 4; ++sp) {
+        const int r = 2 * h + (sp >> 1) - 3, q = 2 * w + (sp & 1) - 3;
+        uint32_t c0 = 0, c1 = 0, c2 = 0;
+        if (r >= 0 && r < S && q >= 0 && q < S) {
+            const bf16_t* px = base + (long)r * S + q;
+            c0 = px[0]; c1 = px[(long)S * S]; c2 = px[2 * (long)S * S];
+        }
+        v[2 * sp] = c0 | (c1 << 16);
+        v[2 * sp + 1] = c2;
+    }
+    out[2 * i] = make_uint4(v[0], v[1], v[2], v[3]);
+    out[2 * i + 1] = make_uint4(v[4], v[5], v[6], v[7]);
+}
+
+// k index of the space-to-depth weights [64][4 th][4 tw][(ph, pw, c)] for (kh, kw, c)
+__device__ __forceinline__ int s2d_index(int kh, int kw, int c) {
+    return (kh >> 1) * 64 + (kw >> 1) * 16 + (((kh & 1) * 2 + (kw & 1)) * 4) + c;
+}
+__global__ void __launch_bounds__(256) stem_pack_kernel(const float* __restrict__ w, bf16_t* __restrict__ out) {
+    const int co = blockIdx.x, k = threadIdx.x;   // one output channel per block, one packed element per thread
+    const int th = k >> 6, tw = (k >> 4) & 3, sp = (k >> 2) & 3, c = k & 3;
+    const int kh = 2 * th + (sp >> 1), kw = 2 * tw + (sp & 1);
+    float v = 0.f;
+    if (kh < 7 && kw < 7 && c < 3) v = w[((co * 3 + c) * 7 + kh) * 7 + kw];
+    out[co * 256 + k] = f32_to_bf16(v);
+}
+// dw [64][3][7][7] += packed gradient [64][256]
+__global__ void __launch_bounds__(256) stem_unpack_kernel(const float* __restrict__ packed, float* __restrict__ dw) {
+    const int co = blockIdx.x, e = threadIdx.x;
+    if (e >= 147) return;
+    const int c = e / 49, kh = (e / 7) % 7, kw = e % 7;
+    dw[co * 147 + e] += packed[co * 256 + s2d_index(kh, kw, c)];
 }
 
 // ---- BN + ReLU + 3x3/2 max-pool (padding 1; padding never wins) ---------------------------------
@@ -450,27 +489,30 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
 
     size_t scratch_need = 0;
 
-    // ---- stem: bf16 pads the three input channels to eight for the MFMA kernel; fp32 keeps three
+    // ---- stem: bf16 runs it in space-to-depth form (see clips_to_s2d_kernel); fp32 keeps the three channels
     const int H1 = S / 2, Hp = S / 4;     // conv1 output, pooled output
-    const int C0 = bf ? 8 : 3;
-    const bf16_t* wp0 = nullptr;
-    TSM_TRY(pack_conv("conv1.w", 64, 3, 7, 8, &wp0, nullptr));
-    void* x0 = A.take((size_t)F * S * S * C0 * es);
+    const int Hs = H1 + 3;                // space-to-depth image, with halo
+    bf16_t* wp0 = bf ? A.take_n<bf16_t>(64 * 256) : nullptr;
+    void* x0 = bf ? A.take((size_t)F * Hs * Hs * 16 * es) : A.take((size_t)F * S * S * 3 * es);
     void* y0 = A.take((size_t)F * H1 * H1 * 64 * es);
     BnVec bn0;
     bn0.mean = A.take_n<float>(64); bn0.rstd = A.take_n<float>(64); bn0.scale = A.take_n<float>(64); bn0.shift = A.take_n<float>(64);
     uint8_t* arg0 = A.take_n<uint8_t>((size_t)F * Hp * Hp * 64);
     void* p0 = A.take((size_t)F * Hp * Hp * 64 * es);
     ConvP stem{};
-    stem.F = F; stem.T = T; stem.H = S; stem.W = S; stem.Cin = C0; stem.Ho = H1; stem.Wo = H1; stem.Cout = 64;
-    stem.KT = 1; stem.KH = 7; stem.KW = 7; stem.stride = 2; stem.pad = 3; stem.fold = 0;
+    stem.F = F; stem.T = T; stem.Ho = H1; stem.Wo = H1; stem.Cout = 64; stem.KT = 1; stem.fold = 0;
+    if (bf) {
+        stem.H = Hs; stem.W = Hs; stem.Cin = 64; stem.pitch = 16; stem.KH = 4; stem.KW = 1; stem.stride = 1; stem.pad = 0;
+    } else {
+        stem.H = S; stem.W = S; stem.Cin = 3; stem.KH = 7; stem.KW = 7; stem.stride = 2; stem.pad = 3;
+    }
     float *rm0, *rv0;
     run_slot(64, &rm0, &rv0);
     const int nb0f = bf ? conv_mfma_fwd_blocks(stem) : red_blocks(stem.rows_out(), 64, dtype);
     const int nb0b = red_blocks(stem.rows_out(), 64, dtype);
     float* part0 = A.take_n<float>((size_t)(nb0f > nb0b ? nb0f : nb0b) * 128);
     float* coef0 = A.take_n<float>(3 * 64);
-    float* dwp0 = A.take_n<float>((size_t)64 * 49 * 8);
+    float* dwp0 = A.take_n<float>((size_t)64 * 256);
 
     // ---- blocks: plans, saved buffers, outputs
     struct Blk {
@@ -565,11 +607,13 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
 
     // ================= forward =================
     {
-        const long px = (long)S * S, total = (long)F * px;
         if (bf) {
             if (!dry) {
-                clips_to_nhwc8_kernel<<<dim3(cdiv(total, 256)), dim3(256), 0, s>>>((const bf16_t*)clips, (uint4*)x0, px, total);
-                LAUNCH_CHECK("clips_to_nhwc8");
+                const long total = (long)F * Hs * Hs;
+                clips_to_s2d_kernel<<<dim3(cdiv(total, 256)), dim3(256), 0, s>>>((const bf16_t*)clips, (uint4*)x0, S, Hs, total);
+                LAUNCH_CHECK("clips_to_s2d");
+                stem_pack_kernel<<<dim3(64), dim3(256), 0, s>>>(P("conv1.w"), wp0);
+                LAUNCH_CHECK("stem_pack");
             }
         } else {
             RUN(transpose_frames(clips, x0, F, 3, S * S, 4, s));
@@ -653,9 +697,12 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
         RUN(bn_bwd_apply(dtype, da0, y0, stem.rows_out(), 64, coef0, da0, s));
         // the gradient buffer was zeroed at the start of the step; both kernels add into it
         if (bf) {
-            RUN(fill_zero(dwp0, (size_t)64 * 49 * 8 * sizeof(float), s));
-            RUN(conv_mfma_wgrad(stem, (const bf16_t*)x0, (const bf16_t*)da0, dwp0, 3, true, s));
-            RUN(unpack_wgrad(dwp0, G("conv1.w"), 64, 3, 49, 8, 1, s));
+            RUN(fill_zero(dwp0, (size_t)64 * 256 * sizeof(float), s));
+            RUN(conv_mfma_wgrad(stem, (const bf16_t*)x0, (const bf16_t*)da0, dwp0, 64, true, s));
+            if (!dry) {
+                stem_unpack_kernel<<<dim3(64), dim3(256), 0, s>>>(dwp0, G("conv1.w"));
+                LAUNCH_CHECK("stem_unpack");
+            }
         } else
             RUN(conv_direct_wgrad(stem, dtype, x0, da0, G("conv1.w"), s));
     }
