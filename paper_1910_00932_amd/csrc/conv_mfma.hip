@@ -456,7 +456,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
     return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
 }
 
-template <int BM, int BN, int WM, int WN, bool DGRAD>
+template <int BM, int BN, int WM, int WN, bool DGRAD, bool STREAM>
 __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
     constexpr int NT = WM * WN * 64;                // threads
     constexpr int NS = 2;                           // LDS stages
@@ -805,7 +805,10 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                     const int row = pss * RPS + r0;
                     const int mrow = s_row[rb * BM + h * HM + row].dst;
                     if (mrow < 0 || col >= a.Cd) continue;
-                    *(u32x4*)(a.dst + (long)mrow * a.Cd + col) = *(const u32x4*)(Cst + row * LDC + vcol * 8);
+                    const u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
+                    u32x4* q = (u32x4*)(a.dst + (long)mrow * a.Cd + col);
+                    if (STREAM) __builtin_nontemporal_store(v, q);
+                    else *q = v;
                 }
             } else {
                 // value (+ addend) -> optional ReLU mask and BatchNorm sums -> store
@@ -831,7 +834,9 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                             f2[2 * q + 1] = fmaf(dhi, (__uint_as_float(yy[q] & 0xffff0000u) - mu[2 * q + 1]) * rs[2 * q + 1], f2[2 * q + 1]);
                         }
                     }
-                    *(u32x4*)(a.dst + mr * a.Cd + col) = o;
+                    u32x4* q = (u32x4*)(a.dst + mr * a.Cd + col);
+                    if (STREAM) __builtin_nontemporal_store(o, q);
+                    else *q = o;
                 };
                 // The operands of all rows of the pass are requested first, so that their latencies overlap.
                 // A row's value goes to frame t + dt of its channel group (adjoint shift); the frame of the
@@ -1005,14 +1010,14 @@ static int launch_igemm(IgemmArgs& a, const char* name, hipStream_t s) {
     return check_launch(name);   // class names carry the tile shape so that they map one-to-one onto kernel symbols
 }
 
-template <int BM, int BN, int WM, int WN, bool DGRAD>
-static int launch_igemm_ring(IgemmArgs& a, const char* name, hipStream_t s) {
+template <int BM, int BN, int WM, int WN, bool DGRAD, bool STREAM>
+static int launch_igemm_ring_s(IgemmArgs& a, const char* name, hipStream_t s) {
     const int mtiles = setup_classes(a, DGRAD, BM);
     a.ntiles = (a.Cd + BN - 1) / BN;
     // two operand stages, staging tile of one epilogue pass, statistics slots, two row buffers
     const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t) + (size_t)(WM * 32) * (BN + 8) * sizeof(bf16_t) +
                         (size_t)2 * WM * 2 * BN * sizeof(float) + (size_t)2 * BM * sizeof(RowInfo);
-    auto kern = igemm_ring_kernel<BM, BN, WM, WN, DGRAD>;
+    auto kern = igemm_ring_kernel<BM, BN, WM, WN, DGRAD, STREAM>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -1022,6 +1027,14 @@ static int launch_igemm_ring(IgemmArgs& a, const char* name, hipStream_t s) {
     const int grid = igemm_grid(mtiles, a.Cd, BN, 1);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, a);
     return check_launch(name);
+}
+
+// Results far larger than the caches are stored past them (the next reader would not find them there anyway,
+// and what is cached survives); smaller ones take the normal path.
+template <int BM, int BN, int WM, int WN, bool DGRAD>
+static int launch_igemm_ring(IgemmArgs& a, const char* name, hipStream_t s) {
+    if ((long)a.F * a.Hd * a.Wd * a.Cd * 2 > (64L << 20)) return launch_igemm_ring_s<BM, BN, WM, WN, DGRAD, true>(a, name, s);
+    return launch_igemm_ring_s<BM, BN, WM, WN, DGRAD, false>(a, name, s);
 }
 
 // Tile choice.  The ring kernel (one block of eight wavefronts per CU; 256x128 tiles, 256x64 for outputs of at
