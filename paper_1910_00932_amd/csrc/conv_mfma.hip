@@ -760,6 +760,39 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                 }
             }
         }
+        // Data gradient: addend, ReLU mask source and BatchNorm input of a pass are requested before the
+        // barriers and the staging of that pass, so that their latency overlaps them.  A row's value goes to
+        // frame t + dt of its channel group (adjoint shift); the frame of the group that receives nothing from
+        // inside the clip gets a zero value (rare, handled after the regular rows).
+        constexpr int CV = BN / 8;          // vectors per staged row
+        constexpr int RPS = NT / CV;        // rows per pass of the store loop
+        constexpr int NPS = HM / RPS;
+        constexpr int NPD = DGRAD ? NPS : 1;
+        const int vcol = tid % CV, r0 = tid / CV;
+        const int col = cur_n0 + vcol * 8;
+        long mr[NPD], mz[NPD];
+        u32x4 ad[NPD], ac[NPD], yy[NPD];
+        const bf16_t* zero_page_d = (const bf16_t*)g_zero_page;
+        auto request = [&](int h) {
+            const int dt = group_dt(col, a.fold);
+#pragma unroll
+            for (int pss = 0; pss < NPD; ++pss) {
+                const int mrow = s_row[rb * BM + h * HM + pss * RPS + r0].dst;
+                const bool live = mrow >= 0 && col < a.Cd;
+                const int t = live ? (mrow / hw_d) % a.T : 0;
+                const bool in_clip = t + dt >= 0 && t + dt < a.T;
+                mr[pss] = live && in_clip ? (long)mrow + (long)dt * hw_d : -1;
+                mz[pss] = live && ((dt == 1 && t == 0) || (dt == -1 && t == a.T - 1)) ? mrow : -1;
+                // loads without a branch around them (rows that are not stored read the zero page): a load
+                // under a condition would be awaited where the branches join
+                const long e = mr[pss] * a.Cd + col;
+                const bool ok = mr[pss] >= 0;
+                ad[pss] = *(const u32x4*)((ok && a.addend) ? a.addend + e : zero_page_d);
+                ac[pss] = *(const u32x4*)((ok && fuse_bn) ? a.act + e : zero_page_d);
+                yy[pss] = *(const u32x4*)((ok && fuse_bn) ? a.ybn + e : zero_page_d);
+            }
+        };
+        if (DGRAD) request(0);
 #pragma unroll
         for (int h = 0; h < MI; ++h) {
             if (h > 0) __syncthreads();   // previous pass stored (the previous tile's last pass: barrier at its end)
@@ -795,10 +828,6 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                 for (int sl = 0; sl < WM * 2; ++sl) v += s_part[(stat * WM * 2 + sl) * BN + col];
                 if (cur_n0 + col < a.Cd) atomicAdd(prow + stat * a.Cd + cur_n0 + col, v);
             }
-            constexpr int CV = BN / 8;          // vectors per staged row
-            constexpr int RPS = NT / CV;        // rows per pass
-            const int vcol = tid % CV, r0 = tid / CV;
-            const int col = cur_n0 + vcol * 8;
             if (!DGRAD) {
 #pragma unroll
                 for (int pss = 0; pss < HM / RPS; ++pss) {
@@ -838,35 +867,6 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                     if (STREAM) __builtin_nontemporal_store(o, q);
                     else *q = o;
                 };
-                // The operands of all rows of the pass are requested first, so that their latencies overlap.
-                // A row's value goes to frame t + dt of its channel group (adjoint shift); the frame of the
-                // group that receives nothing from inside the clip gets a zero value (rare, handled last).
-                constexpr int NPS = HM / RPS;
-                const int dt = group_dt(col, a.fold);
-                long mr[NPS], mz[NPS];
-                u32x4 ad[NPS], ac[NPS], yy[NPS];
-#pragma unroll
-                for (int pss = 0; pss < NPS; ++pss) {
-                    const int mrow = s_row[rb * BM + h * HM + pss * RPS + r0].dst;
-                    mr[pss] = mz[pss] = -1;
-                    ad[pss] = ac[pss] = yy[pss] = u32x4{0u, 0u, 0u, 0u};
-                    if (mrow < 0 || col >= a.Cd) continue;
-                    if (dt == 0) {
-                        mr[pss] = mrow;
-                    } else {
-                        const int t = (mrow / hw_d) % a.T;
-                        if (t + dt >= 0 && t + dt < a.T) mr[pss] = (long)mrow + (long)dt * hw_d;
-                        if ((dt == 1 && t == 0) || (dt == -1 && t == a.T - 1)) mz[pss] = mrow;
-                    }
-                    if (mr[pss] >= 0) {
-                        const long e = mr[pss] * a.Cd + col;
-                        if (a.addend) ad[pss] = *(const u32x4*)(a.addend + e);
-                        if (fuse_bn) {
-                            ac[pss] = *(const u32x4*)(a.act + e);
-                            yy[pss] = *(const u32x4*)(a.ybn + e);
-                        }
-                    }
-                }
 #pragma unroll
                 for (int pss = 0; pss < NPS; ++pss)
                     if (mr[pss] >= 0) finish(mr[pss], *(const u32x4*)(Cst + (pss * RPS + r0) * LDC + vcol * 8), ad[pss], ac[pss], yy[pss]);
@@ -882,6 +882,7 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                     }
                     finish(mz[pss], u32x4{0u, 0u, 0u, 0u}, zad, zac, zyy);
                 }
+                if (h + 1 < MI) request(h + 1);
             }
         }
         if (fuse_bn) {
