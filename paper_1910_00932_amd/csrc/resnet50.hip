@@ -175,11 +175,14 @@ __global__ void __launch_bounds__(256) stem_pool_fwd_kernel(const T* __restrict_
         }
     }
     Vec16<T> o;
+    uint8_t ab[V];
 #pragma unroll
     for (int j = 0; j < V; ++j) {
         o.v[j] = Elem<T>::st(best[j]);
-        arg[i * V + j] = (uint8_t)barg[j];
+        ab[j] = (uint8_t)barg[j];
     }
+    if (V == 8) *(uint2*)(arg + i * V) = *(const uint2*)ab;
+    else *(uint32_t*)(arg + i * V) = *(const uint32_t*)ab;
     *(Vec16<T>*)(out + i * V) = o;
 }
 
@@ -212,9 +215,12 @@ __global__ void __launch_bounds__(256) stem_pool_bwd_kernel(const T* __restrict_
             const int code = kh * 3 + (iw - (2 * ow - 1));
             const long o = ((f * Ho + oh) * Wo + ow) * (long)cv + v;
             const Vec16<T> d = *(const Vec16<T>*)(dp + o * V);
+            uint8_t ab[V];   // the V winner codes in one load
+            if (V == 8) *(uint2*)ab = *(const uint2*)(arg + o * V);
+            else *(uint32_t*)ab = *(const uint32_t*)(arg + o * V);
 #pragma unroll
             for (int j = 0; j < V; ++j)
-                if ((int)arg[o * V + j] == code) g[j] += Elem<T>::ld(d.v[j]);
+                if ((int)ab[j] == code) g[j] += Elem<T>::ld(d.v[j]);
         }
     }
     const Vec16<T> pk = *(const Vec16<T>*)(y + i * V);
