@@ -7,6 +7,7 @@
 // Everything between the clip tensor and the updated parameters runs here as a
 // stream of kernel launches on the caller's stream, with no host synchronisation.
 #include <string.h>
+#include <algorithm>
 #include <string>
 #include <vector>
 #include "block.h"
@@ -186,52 +187,88 @@ __global__ void __launch_bounds__(256) stem_pool_fwd_kernel(const T* __restrict_
     *(Vec16<T>*)(out + i * V) = o;
 }
 
-// Gradient of the pooled tensor routed back to the window position that won, times the
-// ReLU mask of the (recomputed) stem activation.  Gather form: no atomics.
+// Gradient of the pooled tensor routed back to the window position that won, times the ReLU mask of the
+// (recomputed) stem activation: dz, stored to `da`.  Gather form: no atomics.  The same pass accumulates the
+// two BatchNorm-backward sums of dz (as stored), one row of `partial` per block, in a fixed order.
+// Block (C/V, 256/(C/V)): thread x = channel vector, thread y = row lane; rows are conv-output pixels.
 template <typename T>
 __global__ void __launch_bounds__(256) stem_pool_bwd_kernel(const T* __restrict__ dp, const uint8_t* __restrict__ arg,
                                                             const T* __restrict__ y, const float* __restrict__ scale,
-                                                            const float* __restrict__ shift, T* __restrict__ da,
-                                                            int H, int W, int Ho, int Wo, int cv, long total) {
-    constexpr int V = Elem<T>::VEC;
-    long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= total) return;
-    const int v = (int)(i % cv);
-    long r = i / cv;
-    const int iw = (int)(r % W);
-    r /= W;
-    const int ih = (int)(r % H);
-    const long f = r / H;
-    float g[V];
-#pragma unroll
-    for (int j = 0; j < V; ++j) g[j] = 0.f;
-    const int oh_lo = ih / 2, oh_hi = (ih + 1) / 2;   // windows [2*oh-1, 2*oh+1] containing ih
-    const int ow_lo = iw / 2, ow_hi = (iw + 1) / 2;
-    for (int oh = oh_lo; oh <= oh_hi; ++oh) {
-        if (oh >= Ho) continue;
-        const int kh = ih - (2 * oh - 1);
-        for (int ow = ow_lo; ow <= ow_hi; ++ow) {
-            if (ow >= Wo) continue;
-            const int code = kh * 3 + (iw - (2 * ow - 1));
-            const long o = ((f * Ho + oh) * Wo + ow) * (long)cv + v;
-            const Vec16<T> d = *(const Vec16<T>*)(dp + o * V);
-            uint8_t ab[V];   // the V winner codes in one load
-            if (V == 8) *(uint2*)ab = *(const uint2*)(arg + o * V);
-            else *(uint32_t*)ab = *(const uint32_t*)(arg + o * V);
-#pragma unroll
-            for (int j = 0; j < V; ++j)
-                if ((int)ab[j] == code) g[j] += Elem<T>::ld(d.v[j]);
-        }
-    }
-    const Vec16<T> pk = *(const Vec16<T>*)(y + i * V);
-    Vec16<T> o;
+                                                            const float* __restrict__ shift, const float* __restrict__ mean,
+                                                            const float* __restrict__ rstd, T* __restrict__ da,
+                                                            float* __restrict__ partial, int H, int W, int Ho, int Wo,
+                                                            long rows) {
+    constexpr int V = Elem<T>::VEC, C = 64, cv = C / V;
+    const int v = threadIdx.x;
+    float sc[V], sh[V], mu[V], rs[V], s1[V], s2[V];
 #pragma unroll
     for (int j = 0; j < V; ++j) {
-        const float z = fmaf(Elem<T>::ld(pk.v[j]), scale[v * V + j], shift[v * V + j]);
-        const bool live = Elem<T>::ld(Elem<T>::st(z > 0.f ? z : 0.f)) > 0.f;
-        o.v[j] = Elem<T>::st(live ? g[j] : 0.f);
+        sc[j] = scale[v * V + j];
+        sh[j] = shift[v * V + j];
+        mu[j] = mean[v * V + j];
+        rs[j] = rstd[v * V + j];
+        s1[j] = s2[j] = 0.f;
     }
-    *(Vec16<T>*)(da + i * V) = o;
+    for (long r = (long)blockIdx.x * blockDim.y + threadIdx.y; r < rows; r += (long)gridDim.x * blockDim.y) {
+        const int iw = (int)(r % W), ih = (int)((r / W) % H);
+        const long f = r / ((long)W * H);
+        float g[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) g[j] = 0.f;
+        const int oh_lo = ih / 2, oh_hi = (ih + 1) / 2;   // windows [2*oh-1, 2*oh+1] containing ih
+        const int ow_lo = iw / 2, ow_hi = (iw + 1) / 2;
+        for (int oh = oh_lo; oh <= oh_hi; ++oh) {
+            if (oh >= Ho) continue;
+            const int kh = ih - (2 * oh - 1);
+            for (int ow = ow_lo; ow <= ow_hi; ++ow) {
+                if (ow >= Wo) continue;
+                const int code = kh * 3 + (iw - (2 * ow - 1));
+                const long o = ((f * Ho + oh) * Wo + ow) * (long)cv + v;
+                const Vec16<T> d = *(const Vec16<T>*)(dp + o * V);
+                uint8_t ab[V];   // the V winner codes in one load
+                if (V == 8) *(uint2*)ab = *(const uint2*)(arg + o * V);
+                else *(uint32_t*)ab = *(const uint32_t*)(arg + o * V);
+#pragma unroll
+                for (int j = 0; j < V; ++j)
+                    if ((int)ab[j] == code) g[j] += Elem<T>::ld(d.v[j]);
+            }
+        }
+        const long i = r * cv + v;
+        const Vec16<T> pk = *(const Vec16<T>*)(y + i * V);
+        Vec16<T> o;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const float yv = Elem<T>::ld(pk.v[j]);
+            const float z = fmaf(yv, sc[j], sh[j]);
+            const bool live = Elem<T>::ld(Elem<T>::st(z > 0.f ? z : 0.f)) > 0.f;
+            o.v[j] = Elem<T>::st(live ? g[j] : 0.f);
+            const float dz = Elem<T>::ld(o.v[j]);
+            s1[j] += dz;
+            s2[j] = fmaf(dz, (yv - mu[j]) * rs[j], s2[j]);
+        }
+        *(Vec16<T>*)(da + i * V) = o;
+    }
+    __shared__ float red[2][256 * V];
+    const int t = threadIdx.y * cv + v;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        red[0][t * V + j] = s1[j];
+        red[1][t * V + j] = s2[j];
+    }
+    __syncthreads();
+    if (threadIdx.y == 0) {
+        float* prow = partial + (size_t)blockIdx.x * 2 * C;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            float sa = 0.f, sb = 0.f;
+            for (int q = 0; q < (int)blockDim.y; ++q) {
+                sa += red[0][(q * cv + v) * V + j];
+                sb += red[1][(q * cv + v) * V + j];
+            }
+            prow[v * V + j] = sa;
+            prow[C + v * V + j] = sb;
+        }
+    }
 }
 
 // ---- head: global average pool + temporal consensus + linear + softmax cross-entropy ---------
@@ -515,7 +552,9 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
     float *rm0, *rv0;
     run_slot(64, &rm0, &rv0);
     const int nb0f = bf ? conv_mfma_fwd_blocks(stem) : red_blocks(stem.rows_out(), 64, dtype);
-    const int nb0b = red_blocks(stem.rows_out(), 64, dtype);
+    // blocks of the stem backward kernel (rows of its partial buffer): 32 or 16 pixels per block step, a few
+    // steps per block
+    const int nb0b = (int)std::min<long>(4096, std::max<long>(1, stem.rows_out() / 128));
     float* part0 = A.take_n<float>((size_t)(nb0f > nb0b ? nb0f : nb0b) * 128);
     float* coef0 = A.take_n<float>(3 * 64);
     float* dwp0 = A.take_n<float>((size_t)64 * 256);
@@ -687,19 +726,16 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
         cur ^= 1;
     }
     {   // stem backward: max-pool routing + ReLU mask, BatchNorm backward, weight gradient (no input gradient)
-        const int cv = 64 / VEC;
-        const long total = (long)F * H1 * H1 * cv;
+        const long rows0 = stem.rows_out();
         if (!dry) {
+            const dim3 blk(64 / VEC, 256 / (64 / VEC));
             if (bf)
-                stem_pool_bwd_kernel<bf16_t><<<dim3(cdiv(total, 256)), dim3(256), 0, s>>>((const bf16_t*)dbuf[cur], arg0, (const bf16_t*)y0, bn0.scale, bn0.shift, (bf16_t*)da0, H1, H1, Hp, Hp, cv, total);
+                stem_pool_bwd_kernel<bf16_t><<<dim3(nb0b), blk, 0, s>>>((const bf16_t*)dbuf[cur], arg0, (const bf16_t*)y0, bn0.scale, bn0.shift, bn0.mean, bn0.rstd, (bf16_t*)da0, part0, H1, H1, Hp, Hp, rows0);
             else
-                stem_pool_bwd_kernel<float><<<dim3(cdiv(total, 256)), dim3(256), 0, s>>>((const float*)dbuf[cur], arg0, (const float*)y0, bn0.scale, bn0.shift, (float*)da0, H1, H1, Hp, Hp, cv, total);
+                stem_pool_bwd_kernel<float><<<dim3(nb0b), blk, 0, s>>>((const float*)dbuf[cur], arg0, (const float*)y0, bn0.scale, bn0.shift, bn0.mean, bn0.rstd, (float*)da0, part0, H1, H1, Hp, Hp, rows0);
             LAUNCH_CHECK("stem_pool_bwd");
         }
-        RUN(relu_bn_bwd_reduce(dtype, da0, nullptr, y0, stem.rows_out(), 64, bn0.mean, bn0.rstd, da0, part0, nullptr,
-                               nullptr, nullptr, nullptr, s));
-        RUN(bn_bwd_coeffs(part0, nb0b, stem.rows_out(), 64, bn0.mean, bn0.rstd, P("bn1.g"), coef0, G("bn1.g"),
-                          G("bn1.b"), s));
+        RUN(bn_bwd_coeffs(part0, nb0b, rows0, 64, bn0.mean, bn0.rstd, P("bn1.g"), coef0, G("bn1.g"), G("bn1.b"), s));
         RUN(bn_bwd_apply(dtype, da0, y0, stem.rows_out(), 64, coef0, da0, s));
         // the gradient buffer was zeroed at the start of the step; both kernels add into it
         if (bf) {
