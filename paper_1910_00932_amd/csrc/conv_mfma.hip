@@ -12,8 +12,13 @@
 //              K     = taps * source channels
 //   wgrad      D[Cout x Cin] (per tap) = sum over pixels of dy^T * gathered x
 //
-// 256 threads = 4 wavefronts of 64; v_mfma_f32_32x32x16_bf16; operands staged
-// through LDS with 16-byte loads; fp32 accumulation.
+// v_mfma_f32_32x32x16_bf16, operands staged through LDS, fp32 accumulation.  Kernels:
+//   igemm_ring_kernel  fwd/dgrad, source channels % 64 == 0: 256 x {128,64} tile, eight wavefronts,
+//                      buffer-load gathers, loads and LDS stores spread over the MFMA groups
+//   igemm_kernel       fwd/dgrad, any channel count % 8 == 0: 128 x {128,64} tile, four wavefronts,
+//                      register prefetch (the fallback)
+//   wgrad_tr_kernel    wgrad, channels % 64 == 0: operands read with the transposing LDS load
+//   wgrad_kernel       wgrad, any channel count % 8 == 0: operands transposed in registers (the fallback)
 #include <stdlib.h>
 #include "internal.h"
 
