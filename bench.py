@@ -62,6 +62,8 @@ def wgrad_class(cout, cin, taps):
             return "wgrad_tr_64x256"
         if taps == 1:
             return "wgrad_tr_64x64"
+        if kk % 192 == 0:
+            return "wgrad_tr_64x192"
     if cout > 64 and kk > 64:
         return "wgrad_128x128"
     return "wgrad_64x192" if (cout <= 64 and kk >= 192 and kk % 192 == 0) else "wgrad_64x64"

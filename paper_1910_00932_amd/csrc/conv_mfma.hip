@@ -1377,15 +1377,20 @@ __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
     constexpr int TM = BCO / WM, TN = BCI / WN;       // wavefront tile
     constexpr int MI = TM / 32, NJ = TN / 32;
     constexpr int PXS = WMK;                          // pixels per step
-    constexpr int ROWA = BCO * 2, ROWB = BCI * 2;     // bytes per pixel row of the two operands
+    // bytes per pixel row of the two operands in LDS (a power of two: 192 columns sit in 512-byte rows)
+    constexpr int ROWA = BCO * 2, ROWB = BCI == 192 ? 512 : BCI * 2;
     constexpr int STAGE = PXS * (ROWA + ROWB);
     constexpr int AVR = BCO / 8, BVR = BCI / 8;       // 16-byte pieces per row
-    constexpr int RA = NT / AVR, RB = NT / BVR;       // rows per load pass
-    constexpr int PA = PXS / RA, PB = PXS / RB;
+    constexpr int RA = NT / AVR;                      // dy rows per load pass
+    constexpr int PA = PXS / RA, PB = PXS * BVR / NT; // pieces per thread and step
     constexpr int NP = PA + PB;
+    // x pieces: piece tid + j*NT is vector (tid + j*NT) % BVR of row (tid + j*NT) / BVR.  When NT is a multiple
+    // of BVR the vector is the same for all of a thread's pieces and the rows are NT/BVR apart.
+    constexpr bool BREG = NT % BVR == 0;
     constexpr int SPB = NT / PXS;                     // steps per decoded batch of NT pixels
     constexpr int KS = PXS / 16;
-    static_assert(RA % 4 == 0 && RB % 4 == 0 && PXS % RA == 0 && PXS % RB == 0, "tile / thread mismatch");
+    static_assert(RA % 4 == 0 && PXS % RA == 0 && (PXS * BVR) % NT == 0, "tile / thread mismatch");
+    static_assert(!BREG || (NT / BVR) % 4 == 0, "row swizzle of a thread's pieces must agree");
     static_assert(NT % PXS == 0 && SPB >= 4, "whole steps per batch; a batch is decoded at least three steps ahead");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [2][STAGE], then the pixel table
@@ -1408,25 +1413,32 @@ __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
 
     // ---- this thread's pieces: dy rows arow + i*RA, x rows brow + j*RB of every step
     const int avec = tid % AVR, arow = tid / AVR;
-    const int bvec = tid % BVR, brow = tid / BVR;
     uint32_t a_off[PA];
 #pragma unroll
     for (int i = 0; i < PA; ++i) a_off[i] = (uint32_t)(((arow + i * RA) * a.Cout + co0 + avec * 8) * 2);
-    uint32_t b_need, b_const;
-    {
-        const int j = j0 + bvec * 8;                 // column of D: (tap, input channel), constant for the thread
-        const int tap = j / a.Cin, ci = j - tap * a.Cin;
-        const int kw = tap % a.KW, kh = (tap / a.KW) % a.KH, kt = tap / (a.KW * a.KH);
-        const int d = kt - a.KT / 2 + group_dt(ci, a.fold);
-        b_need = (1u << kh) | (1u << (8 + kw)) | (d > 0 ? 1u << 30 : 0u) | (d < 0 ? 1u << 31 : 0u);
-        b_const = (uint32_t)((d * a.H * a.W * a.pitch + (kh * a.W + kw) * a.pitch + ci) * 2);
+    auto swz_a = [](int r) { return ROWA >= 256 ? 2 * (r & 3) : 2 * ((r >> 1) & 1); };
+    auto swz_b = [](int r) { return ROWB >= 256 ? 2 * (r & 3) : 2 * ((r >> 1) & 1); };
+    constexpr int PBV = BREG ? 1 : PB;               // distinct (need, const) pairs per thread
+    uint32_t b_need[PBV], b_const[PBV];
+    int b_row[PB], b_wr[PB];                          // row within the step, LDS position
+#pragma unroll
+    for (int q = 0; q < PB; ++q) {
+        const int p = tid + q * NT;
+        const int bvec = BREG ? tid % BVR : p % BVR;
+        b_row[q] = BREG ? tid / BVR + q * (NT / BVR) : p / BVR;
+        b_wr[q] = PXS * ROWA + b_row[q] * ROWB + ((((bvec >> 1) ^ swz_b(b_row[q])) << 5) | ((bvec & 1) << 4));
+        if (q < PBV) {
+            const int j = j0 + bvec * 8;             // column of D: (tap, input channel)
+            const int tap = j / a.Cin, ci = j - tap * a.Cin;
+            const int kw = tap % a.KW, kh = (tap / a.KW) % a.KH, kt = tap / (a.KW * a.KH);
+            const int d = kt - a.KT / 2 + group_dt(ci, a.fold);
+            b_need[q] = (1u << kh) | (1u << (8 + kw)) | (d > 0 ? 1u << 30 : 0u) | (d < 0 ? 1u << 31 : 0u);
+            b_const[q] = (uint32_t)((d * a.H * a.W * a.pitch + (kh * a.W + kw) * a.pitch + ci) * 2);
+        }
     }
     // LDS positions of the pieces (row r, 16-byte vector v): 32-byte block (v/2) ^ 2*(r%4), half v%2
     // (rows of 128 bytes hold only four blocks and two of them span the banks: there the XOR is 2*((r/2)%2))
-    auto swz_a = [](int r) { return ROWA >= 256 ? 2 * (r & 3) : 2 * ((r >> 1) & 1); };
-    auto swz_b = [](int r) { return ROWB >= 256 ? 2 * (r & 3) : 2 * ((r >> 1) & 1); };
     const int a_wr = arow * ROWA + ((((avec >> 1) ^ swz_a(arow)) << 5) | ((avec & 1) << 4));
-    const int b_wr = PXS * ROWA + brow * ROWB + ((((bvec >> 1) ^ swz_b(brow)) << 5) | ((bvec & 1) << 4));
 
     // ---- operand read addresses (see the layout of the transposing load above): lane = 32*kg + 16*mblk + 4*e + c
     int a_rd[MI], b_rd[NJ];
@@ -1477,8 +1489,9 @@ __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
         const PixInfo* tab = s_pix + ((st / SPB) & 1) * NT + (st % SPB) * PXS;
 #pragma unroll
         for (int j = 0; j < PB; ++j) {
-            const PixInfo pi = tab[brow + j * RB];
-            p.v[PA + j] = (left > 0 && (pi.mask & b_need) == b_need) ? pi.off + b_const : OOB_OFFSET;
+            const PixInfo pi = tab[b_row[j]];
+            const uint32_t need = b_need[BREG ? 0 : j], cst = b_const[BREG ? 0 : j];
+            p.v[PA + j] = (left > 0 && (pi.mask & need) == need) ? pi.off + cst : OOB_OFFSET;
         }
         return p;
     };
@@ -1488,7 +1501,7 @@ __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
                          : __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, (int)p.v[i], 0, 0);
     };
     auto store_piece = [&](int stage, int i) {
-        const int pos = i < PA ? a_wr + i * RA * ROWA : b_wr + (i - PA) * RB * ROWB;
+        const int pos = i < PA ? a_wr + i * RA * ROWA : b_wr[i < PA ? 0 : i - PA];
         *(u32x4*)(smem + stage * STAGE + pos) = greg[i];
     };
 
@@ -1578,7 +1591,7 @@ static int launch_wgrad_tr(WgradArgs& a, int Cout, int blocks_per_cu, const char
     a.chunk = (chunk + WMK - 1) / WMK * WMK;
     const dim3 grid((unsigned)((a.M + a.chunk - 1) / a.chunk), (unsigned)tiles);
     auto kern = wgrad_tr_kernel<BCO, BCI, WM, WN>;
-    const size_t smem = (size_t)2 * WMK * (BCO + BCI) * 2 + (size_t)2 * NT * sizeof(PixInfo);
+    const size_t smem = (size_t)2 * WMK * (BCO * 2 + (BCI == 192 ? 512 : BCI * 2)) + (size_t)2 * NT * sizeof(PixInfo);
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -1621,9 +1634,9 @@ int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw
             if (p.Cout % 128 == 0 && p.Cin % 128 == 0) return launch_wgrad_tr<128, 128, 2, 2>(a, p.Cout, 2, "wgrad_tr_128x128", s);
             // (a column tile may span several taps: 64 input channels x 4 taps fill the 256 columns too)
             if (a.K % 256 == 0 && (p.Cin % 256 == 0 || a.pitch != p.Cin)) return launch_wgrad_tr<64, 256, 1, 4>(a, p.Cout, 1, "wgrad_tr_64x256", s);
-            // 64 x 64 channels with several taps: the 64x192 register-transposing tile below shares the dy tile
-            // among three taps and is faster
             if (p.taps() == 1) return launch_wgrad_tr<64, 64, 2, 2>(a, p.Cout, 4, "wgrad_tr_64x64", s);
+            // 64 input channels and several taps: a column tile of three taps shares the dy tile among them
+            if (a.K % 192 == 0) return launch_wgrad_tr<64, 192, 2, 2>(a, p.Cout, 1, "wgrad_tr_64x192", s);
         }
     }
     if (a.pitch != p.Cin) return fail(TSM_ERR_UNSUPPORTED, "wgrad: a pixel pitch other than the channel count needs the transposing-read kernels");
