@@ -25,6 +25,10 @@ CASES = [  # N,T,Cin,H,W,Cout,k,stride,pad,fold_div
     (2, 3, 24, 5, 6, 40, 3, 1, 1, 3),       # ragged channels, fold = 8
     (1, 2, 20, 5, 5, 12, 3, 1, 1, 8),       # channels not multiple of 8 -> plain kernels
     (1, 1, 16, 6, 6, 16, 1, 1, 0, 4),       # T = 1: both shifted groups read zeros
+    (1, 1, 64, 6, 6, 64, 3, 1, 1, 0),       # fewer pixels than one 256-row tile (most blocks of the grid idle)
+    (1, 4, 64, 10, 10, 64, 1, 1, 0, 8),     # 64 -> 64 1x1 with shift: 256x64 tile, 64x64 weight-gradient tile
+    (2, 2, 128, 9, 9, 320, 1, 1, 0, 0),     # output channels not a multiple of the 128-column tile
+    (1, 2, 192, 7, 7, 64, 3, 1, 1, 8),      # three 64-channel steps per tap, shift inside the first step only
 ]
 
 
