@@ -10,6 +10,17 @@ namespace tsm {
 
 template <typename T, int V> struct alignas(sizeof(T) * V) Pack { T v[V]; };
 
+// Stores of results that the caches cannot hold until their next use go past them (16-byte packs only).
+template <typename T, int V>
+__device__ __forceinline__ void store_pack(T* p, const Pack<T, V>& v, bool stream) {
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    if (sizeof(T) * V == 16 && stream)
+        __builtin_nontemporal_store(*(const u32x4_t*)&v, (u32x4_t*)p);
+    else
+        *(Pack<T, V>*)p = v;
+}
+static inline bool stream_result(long rows, int C, int dtype) { return rows * C * (long)dtype_size(dtype) > (64L << 20); }
+
 // ---------------------------------------------------------------------------------
 __global__ void fill_zero_kernel(uint32_t* p, size_t n) {
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -258,7 +269,7 @@ template <typename T, int V, bool PROJ>
 __global__ void __launch_bounds__(256) tail_kernel(const T* __restrict__ y, long rows, int C, int cv,
                                                    const float* __restrict__ scale, const float* __restrict__ shift,
                                                    const T* __restrict__ sc, const float* __restrict__ scale_d,
-                                                   const float* __restrict__ shift_d, T* __restrict__ out) {
+                                                   const float* __restrict__ shift_d, T* __restrict__ out, bool stream) {
     const int cvi = blockIdx.y * blockDim.x + threadIdx.x;
     if (cvi >= cv) return;
     float s0[V], h0[V], s1[V], h1[V];
@@ -279,7 +290,7 @@ __global__ void __launch_bounds__(256) tail_kernel(const T* __restrict__ y, long
             const float v = fmaf(Elem<T>::ld(a.v[j]), s0[j], h0[j]) + rr;
             o.v[j] = Elem<T>::st(v > 0.f ? v : 0.f);
         }
-        *(Pack<T, V>*)(out + off) = o;
+        store_pack<T, V>(out + off, o, stream);
     }
 }
 
@@ -287,10 +298,11 @@ template <typename T, int V>
 static int tail_tv(const T* y, long rows, int C, const float* scale, const float* shift, const T* sc,
                    const float* scale_d, const float* shift_d, T* out, hipStream_t s) {
     RowShape r = row_shape(rows, C, V, EW_ROWS_PER_THREAD, EW_MAX_GX);
+    const bool st = stream_result(rows, C, sizeof(T) == 2 ? TSM_BF16 : TSM_F32);
     if (scale_d)
-        tail_kernel<T, V, true><<<r.grid, r.block, 0, s>>>(y, rows, C, r.cv, scale, shift, sc, scale_d, shift_d, out);
+        tail_kernel<T, V, true><<<r.grid, r.block, 0, s>>>(y, rows, C, r.cv, scale, shift, sc, scale_d, shift_d, out, st);
     else
-        tail_kernel<T, V, false><<<r.grid, r.block, 0, s>>>(y, rows, C, r.cv, scale, shift, sc, scale_d, shift_d, out);
+        tail_kernel<T, V, false><<<r.grid, r.block, 0, s>>>(y, rows, C, r.cv, scale, shift, sc, scale_d, shift_d, out, st);
     return check_launch("block_tail_fwd");
 }
 
@@ -423,7 +435,7 @@ __global__ void __launch_bounds__(256) bn_bwd_apply_kernel(const T* __restrict__
 #pragma unroll
         for (int j = 0; j < V; ++j)
             o.v[j] = Elem<T>::st(fmaf(ka[j], Elem<T>::ld(a.v[j]), fmaf(kb[j], Elem<T>::ld(b.v[j]), kc[j])));
-        *(Pack<T, V>*)(dy + off) = o;
+        *(Pack<T, V>*)(dy + off) = o;   // (read again right away by two kernels: a nontemporal store measured slower)
     }
 }
 
