@@ -42,11 +42,14 @@ def conv_layers(F, size):
     return layers
 
 
-def igemm_class(kind, cd, cs):
-    """Tile the library picks for a forward ("fwd") or data-gradient ("dgrad") convolution that produces
-    `cd` channels from `cs` source channels (tensors below 2 GiB, which holds for every workload here)."""
+def igemm_class(kind, cd, cs, rows):
+    """Tile the library picks for a forward ("fwd") or data-gradient ("dgrad") convolution that produces `rows`
+    pixels of `cd` channels from `cs` source channels (tensors below 2 GiB, which holds for every workload here;
+    256 CUs)."""
     if cs % 64 == 0:
-        return "igemm_%s_%s" % (kind, "256x64" if cd <= 64 else "256x128")
+        tiles256 = -(-rows // 256) * (1 if cd <= 64 else -(-cd // 128))
+        r = "r128" if tiles256 * 4 < 256 * 3 else "256"
+        return "igemm_%s_%sx%s" % (kind, r, "64" if cd <= 64 else "128")
     return "igemm_%s_%s" % (kind, "128x64" if cd <= 64 else "128x128")
 
 
@@ -80,9 +83,9 @@ def class_work(F, size):
     for name, rin, cin, rout, cout, taps, has_dgrad in conv_layers(F, size):
         macs = float(rout) * cout * cin * taps
         stem = name == "conv1"   # runs in space-to-depth form: 64 "channels" x 4 taps, see the library
-        add(igemm_class("fwd", cout, 64 if stem else cin), macs)
+        add(igemm_class("fwd", cout, 64 if stem else cin, rout), macs)
         if has_dgrad:
-            add(igemm_class("dgrad", cin, cout), macs)
+            add(igemm_class("dgrad", cin, cout, rin), macs)
         add("wgrad_tr_64x256" if stem else wgrad_class(cout, cin, taps), macs)
     return work
 
@@ -100,7 +103,7 @@ def class_bytes(F, size):
         x_b, y_b = 2.0 * rin * cin, 2.0 * rout * cout
         if stem:   # the space-to-depth image: (size/2 + 3)^2 pixels of 16 values per frame
             x_b = 2.0 * F * (size // 2 + 3) ** 2 * 16
-        add(igemm_class("fwd", cout, 64 if stem else cin), x_b + y_b)
+        add(igemm_class("fwd", cout, 64 if stem else cin, rout), x_b + y_b)
         if has_dgrad:
             extra = x_b if name.endswith(".c1") else 0.0       # the shortcut gradient added in the epilogue
             # ReLU mask and BatchNorm sums of the layer below ride in the epilogue (two more tensors of the
@@ -109,7 +112,7 @@ def class_bytes(F, size):
             chained = name.endswith(".c1") and (blk >= 2 or (blk == 0 and not name.startswith("res2")))
             if name.endswith((".c2", ".c3")) or chained:
                 extra += 2.0 * x_b
-            add(igemm_class("dgrad", cin, cout), x_b + y_b + extra)
+            add(igemm_class("dgrad", cin, cout, rin), x_b + y_b + extra)
         add("wgrad_tr_64x256" if stem else wgrad_class(cout, cin, taps), x_b + y_b)
     return byt
 

@@ -1057,11 +1057,29 @@ static bool ring_eligible(int Cs, long src_elems, long w_elems) {
     return enabled && Cs % BK == 0 && src_elems * 2 < limit && w_elems * 2 < limit;
 }
 
+// Rows per tile of the ring kernel: 256, or 128 when 256-row tiles would leave a good part of the CUs without
+// a tile (small batches in the last stages).
+static int ring_rows(long rows, int Cd) {
+    static int forced = -1;   // TSM_IGEMM_BM=128|256 fixes the choice (for comparisons)
+    if (forced < 0) {
+        const char* e = getenv("TSM_IGEMM_BM");
+        forced = e ? atoi(e) : 0;
+    }
+    if (forced == 128 || forced == 256) return forced;
+    const long ntiles = (Cd + 127) / 128;
+    const long tiles256 = ((rows + 255) / 256) * (Cd <= 64 ? 1 : ntiles);
+    return tiles256 * 4 < (long)num_cu() * 3 ? 128 : 256;
+}
+
 template <bool DGRAD>
 static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     const long rows = (long)a.F * a.Hd * a.Wd;
     if (rows == 0) return TSM_OK;
     if (ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K)) {
+        if (ring_rows(rows, a.Cd) == 128) {
+            if (a.Cd <= 64) return launch_igemm_ring<128, 64, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_r128x64" : "igemm_fwd_r128x64", s);
+            return launch_igemm_ring<128, 128, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_r128x128" : "igemm_fwd_r128x128", s);
+        }
         if (a.Cd <= 64) return launch_igemm_ring<256, 64, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_256x64" : "igemm_fwd_256x64", s);
         return launch_igemm_ring<256, 128, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_256x128" : "igemm_fwd_256x128", s);
     }
@@ -1073,7 +1091,10 @@ static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
 int conv_mfma_fwd_blocks(const ConvP& p) {
     const int bn = p.Cout <= 64 ? 64 : 128;
     if (ring_eligible(p.Cin, p.rows_in() * (long)p.pix_pitch() + p.Cin + (long)(p.pad * p.W + p.pad) * p.pix_pitch(), (long)p.Cout * p.K()))
-        return igemm_grid((int)((p.rows_out() + 255) / 256), p.Cout, bn, 1);
+    {
+        const int bm = ring_rows(p.rows_out(), p.Cout);
+        return igemm_grid((int)((p.rows_out() + bm - 1) / bm), p.Cout, bn, 1);
+    }
     return igemm_grid((int)((p.rows_out() + 127) / 128), p.Cout, bn, 2);
 }
 
@@ -1106,7 +1127,7 @@ int conv_mfma_dgrad_blocks(const ConvP& p) {
     dgrad_args(p, a);
     if (!ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K)) return 0;
     if ((long)a.F * a.Hd * a.Wd == 0) return 0;
-    const int mtiles = setup_classes(a, true, 256);
+    const int mtiles = setup_classes(a, true, ring_rows((long)a.F * a.Hd * a.Wd, a.Cd));
     return igemm_grid(mtiles, a.Cd, a.Cd <= 64 ? 64 : 128, 1);
 }
 
