@@ -130,6 +130,84 @@ def measured_traffic(clips):
     return out
 
 
+def block_workload(args, torch, B, I):
+    """Block-level workloads through tsm_block_fwd / tsm_block_bwd (bf16, channels innermost, inputs resident)."""
+    stream = torch.cuda.current_stream()
+
+    def make(kind, N, T, Cin, H, Cmid, Cout, fd, seed):
+        d = B.BlockDesc(kind=kind, N=N, T=T, Cin=Cin, H=H, W=H, Cmid=Cmid, Cout=Cout, stride=1, has_projection=0,
+                        fold_div=fd, dtype=B.TSM_BF16, layout=B.TSM_NTHWC, bn_eps=1e-5)
+        t3 = kind == B.TSM_BLOCK_BOTTLENECK_T3
+        shapes = {"w1": (Cmid, Cin, 3) if t3 else (Cmid, Cin, 1, 1), "w2": (Cmid, Cmid, 3, 3), "w3": (Cout, Cmid, 1, 1)}
+        p = {k: torch.from_numpy(I.kaiming_conv(v, seed + i, "bf16")).to(torch.bfloat16).cuda()
+             for i, (k, v) in enumerate(shapes.items())}
+        for i, c in (("1", Cmid), ("2", Cmid), ("3", Cout)):
+            p["g" + i] = torch.ones(c, dtype=torch.float32, device="cuda")
+            p["b" + i] = torch.zeros(c, dtype=torch.float32, device="cuda")
+        g = {"d" + k: torch.empty(v.shape, dtype=torch.float32, device="cuda") for k, v in p.items()}
+        saved = torch.empty(B.tsm_block_saved_bytes(d), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(B.tsm_block_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+        macs = float(N * T * H * H) * (Cin * Cmid * (3 if t3 else 1) + 9 * Cmid * Cmid + Cmid * Cout)
+        return {"d": d, "p": p, "g": g, "saved": saved, "ws": ws, "flops": 6.0 * macs}
+
+    def act(N, T, C, H, seed):
+        return torch.from_numpy(I.normal((N, T, H, H, C), seed, "bf16")).to(torch.bfloat16).cuda()
+
+    def time_it(fn):
+        for _ in range(args.warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(args.steps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    base = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic"}
+    if args.workload == "res2":
+        N, T, C, H = 8, 8, 256, 56
+        blocks = [make(B.TSM_BLOCK_BOTTLENECK, N, T, C, H, 64, C, 8, 10 * i) for i in range(3)]
+        xs = [act(N, T, C, H, 0)] + [torch.empty(N, T, H, H, C, dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+        gs = [act(N, T, C, H, 3)] + [torch.empty(N, T, H, H, C, dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+
+        def it():
+            for i, b in enumerate(blocks):
+                B.tsm_block_fwd(b["d"], xs[i], b["p"], xs[i + 1], b["saved"], b["ws"], stream)
+            for i in (2, 1, 0):
+                b = blocks[i]
+                B.tsm_block_bwd(b["d"], xs[i], xs[i + 1], gs[2 - i], b["saved"], b["p"], gs[3 - i], b["g"], b["ws"], stream)
+
+        ms = time_it(it)
+        fl = sum(b["flops"] for b in blocks)
+        out = dict(base, metric="TSM res2 bottleneck stack (3 blocks) fwd+bwd clips/s", value=N / (ms * 1e-3),
+                   unit="clips/s", ms_per_step=ms,
+                   config={"workload": "configs[1]: x[8,8,256,56,56] bf16, 256->64->64->256, fold_div 8, three blocks"},
+                   tflops=fl / (ms * 1e-3) / 1e12, pct_bf16_mfma_peak=100.0 * fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS)
+        return out
+    N, T, C, H = 8, 8, 1024, 14
+    res = {}
+    for name, kind, fd in (("tsm", B.TSM_BLOCK_BOTTLENECK, 8), ("t3", B.TSM_BLOCK_BOTTLENECK_T3, 0)):
+        b = make(kind, N, T, C, H, 256, C, fd, 1)
+        x, dout = act(N, T, C, H, 0), act(N, T, C, H, 3)
+        o, dx = torch.empty_like(x), torch.empty_like(x)
+
+        def it():
+            B.tsm_block_fwd(b["d"], x, b["p"], o, b["saved"], b["ws"], stream)
+            B.tsm_block_bwd(b["d"], x, o, dout, b["saved"], b["p"], dx, b["g"], b["ws"], stream)
+
+        ms = time_it(it)
+        res[name] = {"ms": ms, "tflops": b["flops"] / (ms * 1e-3) / 1e12}
+    out = dict(base, metric="TSM block fwd+bwd clips/s at x[8,8,1024,14,14] (3x1x1 temporal-conv block beside it)",
+               value=N / (res["tsm"]["ms"] * 1e-3), unit="clips/s", ms_per_step=res["tsm"]["ms"],
+               config={"workload": "configs[4]: bottleneck 1024->256->256->1024 at 14x14, 8 clips x 8 frames, bf16"},
+               tsm_block=res["tsm"], temporal_conv_block=res["t3"],
+               t3_over_tsm_time=res["t3"]["ms"] / res["tsm"]["ms"])
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -137,6 +215,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--clips", type=int, default=64, help="clips per step: 64 = configs[3] (throughput run), 8 = configs[2]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", default="step", choices=["step", "res2", "cmp"],
+                    help="step: the full train step (the headline, default); res2: configs[1], the three res2 bottlenecks "
+                         "fwd+bwd at 8 clips; cmp: configs[4], TSM block against the 3x1x1 temporal-conv block")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); --gpus %d is not supported"
@@ -148,6 +229,9 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.workload != "step":
+        print(json.dumps(block_workload(args, torch, B, I)))
+        return
     N, T, S, K = args.clips, 8, 224, 400
     lr = 0.00125 * N / 8.0          # linear scaling rule (paper section 4.1)
     table = B.tsm_resnet50_param_table(K)
