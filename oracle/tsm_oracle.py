@@ -545,6 +545,70 @@ def resnet50_fwd_bwd(P, clips, labels, fold_div=8, eps=1e-5, q=_ident, wq=_ident
     return loss, logits, G
 
 
+# ----------------------------------------------------------------------------
+# Forward-only (inference) path: BatchNorm with given statistics.  The paper measures single-GPU
+# throughput of the models this way (section 3a, Table 1: videos per second, forward only, batch 16).
+# ----------------------------------------------------------------------------
+
+def bn_eval(y, gamma, beta, mean, var, eps=1e-5):
+    """BatchNorm in inference mode: the per-channel affine map gamma*(y-mean)/sqrt(var+eps)+beta with
+    statistics supplied by the caller (running averages) instead of computed from the batch."""
+    return (y - _bc(mean)) / np.sqrt(_bc(var) + eps) * _bc(gamma) + _bc(beta)
+
+
+def bn_state_slots():
+    """Ordered (BatchNorm parameter prefix, channels) of the running-statistics vector: per BatchNorm its
+    mean [C] then its variance [C], BatchNorms in the order of the parameter table."""
+    return [(n[:-2], shp[0]) for n, shp, _ in resnet50_param_table() if n.endswith(".g")]
+
+
+def bn_state_count():
+    return sum(2 * c for _, c in bn_state_slots())
+
+
+def unflatten_bn_state(flat):
+    out, off = {}, 0
+    for name, c in bn_state_slots():
+        out[name] = (np.asarray(flat[off:off + c], dtype=np.float64), np.asarray(flat[off + c:off + 2 * c], dtype=np.float64))
+        off += 2 * c
+    assert off == len(flat)
+    return out
+
+
+def bottleneck_infer(x, p, stats, stride=1, fold_div=8, eps=1e-5, q=_ident):
+    """bottleneck_fwd with every BatchNorm in inference mode.  stats: "1","2","3" (and "d") -> (mean, var)."""
+    z1 = q(relu(bn_eval(q(conv_fwd(x, p["w1"], 1, 0, fold_div)), p["g1"], p["b1"], *stats["1"], eps=eps)))
+    z2 = q(relu(bn_eval(q(conv_fwd(z1, p["w2"], stride, 1, 0)), p["g2"], p["b2"], *stats["2"], eps=eps)))
+    a3 = bn_eval(q(conv_fwd(z2, p["w3"], 1, 0, 0)), p["g3"], p["b3"], *stats["3"], eps=eps)
+    if "wd" in p:
+        sc = q(bn_eval(q(conv_fwd(x, p["wd"], stride, 0, 0)), p["gd"], p["bd"], *stats["d"], eps=eps))
+    else:
+        sc = x
+    return q(relu(a3 + sc))
+
+
+def resnet50_infer(P, bn_state, clips, fold_div=8, eps=1e-5, q=_ident, wq=_ident):
+    """Forward pass of TSM-ResNet-50 in inference mode: logits [N,K] (mean over the T per-frame predictions).
+    bn_state: flat running-statistics vector (see bn_state_slots)."""
+    S = unflatten_bn_state(bn_state)
+    y0 = q(conv_fwd(clips, wq(P["conv1.w"]), 2, 3, 0))
+    z0 = q(relu(bn_eval(y0, P["bn1.g"], P["bn1.b"], *S["bn1"], eps=eps)))
+    x, _ = maxpool_fwd(z0)
+    for name, blocks, mid, stride in STAGES:
+        for b in range(blocks):
+            pre = "%s.%d." % (name, b)
+            p = _block_params(P, pre, b == 0)
+            for k in ("w1", "w2", "w3", "wd"):
+                if k in p:
+                    p[k] = wq(p[k])
+            st = {"1": S[pre + "bn1"], "2": S[pre + "bn2"], "3": S[pre + "bn3"]}
+            if b == 0:
+                st["d"] = S[pre + "dsbn"]
+            x = bottleneck_infer(x, p, st, stride if b == 0 else 1, fold_div, eps, q)
+    pooled = x.mean(axis=(3, 4))
+    return (pooled @ P["fc.w"].T + P["fc.b"]).mean(axis=1)
+
+
 def sgd_update(P, V, G, lr, momentum=0.9, weight_decay=1e-4, num_classes=400):
     """g <- g + wd*w on convolution and fc weights only (no decay on BatchNorm
     and bias, section 4.1); v <- momentum*v + g; w <- w - lr*v."""
