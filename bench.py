@@ -208,14 +208,103 @@ def block_workload(args, torch, B, I):
     return out
 
 
+def infer_workload(args, torch, B, I):
+    """Forward-only throughput, BatchNorm in inference mode, as the paper's efficiency table measures it
+    (section 3a, Table 1: videos per second at batch 16 on one GPU)."""
+    N, T, S, K = args.clips, 8, 224, 400
+    table = B.tsm_resnet50_param_table(K)
+    flat = I.init_params([(n, s) for n, _, s, _ in table], 1)
+    d = B.R50Desc(N=N, T=T, size=S, num_classes=K, fold_div=8, lr=0.0, momentum=0.9, weight_decay=1e-4, bn_eps=1e-5,
+                  bn_momentum=0.1, dtype=B.TSM_BF16)
+    ws = torch.empty(B.tsm_resnet50_infer_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+    clips = torch.from_numpy(I.clips(min(N, 8), T, S, 0, "bf16")).to(torch.bfloat16)
+    clips = clips.repeat((N + clips.shape[0] - 1) // clips.shape[0], 1, 1, 1, 1)[:N].contiguous().cuda()
+    params = torch.from_numpy(flat).cuda()
+    # running statistics: mean 0, variance 1 (their values do not change the work done)
+    state = np.concatenate([np.concatenate([np.zeros(sh[0]), np.ones(sh[0])]) for n, _, sh, _ in table if n.endswith(".g")])
+    bn_state = torch.from_numpy(state.astype(np.float32)).cuda()
+    logits = torch.empty((N, K), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        B.tsm_resnet50_infer(d, clips, params, bn_state, logits, ws, stream)
+
+    for _ in range(args.warmup):
+        step()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    if not bool(torch.isfinite(logits).all()):
+        sys.exit("bench.py: logits are not finite")
+    B.tsm_profile_begin(stream)
+    step()
+    prof = B.tsm_profile_end()
+    F = N * T
+    work, byt = {}, {}
+    for name, rin, cin, rout, cout, taps, _ in conv_layers(F, S):
+        stem = name == "conv1"
+        cls = igemm_class("fwd", cout, 64 if stem else cin, rout)
+        x_b = 2.0 * F * (S // 2 + 3) ** 2 * 16 if stem else 2.0 * rin * cin
+        res_b = 2.0 * rout * cout if name.endswith(".c3") else 0.0     # the shortcut read by the epilogue
+        work[cls] = work.get(cls, 0.0) + 2.0 * rout * cout * cin * taps
+        byt[cls] = byt.get(cls, 0.0) + x_b + 2.0 * rout * cout + res_b
+    dom = max(prof, key=lambda k: prof[k][1])
+    n_launch, dom_ms = prof[dom]
+    roof = {"bound": "hbm", "kernel": dom, "launches_per_step": n_launch, "avg_launch_ms": dom_ms / n_launch,
+            "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": None, "traffic": None}
+    if dom in work:
+        tflops, gbs = work[dom] / (dom_ms * 1e-3) / 1e12, byt[dom] / (dom_ms * 1e-3) / 1e9
+        hbm_bound = byt[dom] / (PEAK_HBM_GBS * 1e9) > work[dom] / (PEAK_BF16_TFLOPS * 1e12)
+        roof.update({"bound": "hbm" if hbm_bound else "mfma", "achieved": gbs if hbm_bound else tflops,
+                     "peak": PEAK_HBM_GBS if hbm_bound else PEAK_BF16_TFLOPS, "unit": "GB/s" if hbm_bound else "TFLOP/s",
+                     "frac": gbs / PEAK_HBM_GBS if hbm_bound else tflops / PEAK_BF16_TFLOPS,
+                     "flops_per_launch": work[dom] / n_launch, "algorithmic_bytes_per_launch": byt[dom] / n_launch,
+                     "tflops": tflops, "algorithmic_gbs": gbs})
+    flops = sum(work.values())
+    out = {"metric": "TSM-ResNet-50 inference videos/s (8x224^2, forward only, batch %d) at 1 GPU" % N,
+           "value": N / (ms * 1e-3), "unit": "videos/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+           # the paper's figure for this workload (84.8 videos/s, batch 16) is one Tesla P100's: context, not a target
+           "vs_baseline": (N / (ms * 1e-3) / 84.8) if N == 16 else None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "Table 1 efficiency row: TSM-ResNet-50 forward only, %d clips x 8 frames x 3x224x224, "
+                                  "400 classes, fold_div 8, BatchNorm with running statistics" % N,
+                      "clips_per_step": N, "frames": T, "size": S, "num_classes": K},
+           "step_tflops": flops / (ms * 1e-3) / 1e12,
+           "pct_bf16_mfma_peak": 100.0 * flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+           "roofline": roof,
+           "kernel_classes": {k: {"launches": v[0], "ms": round(v[1], 4),
+                                  "tflops": round(work[k] / (v[1] * 1e-3) / 1e12, 1) if k in work else None}
+                              for k, v in sorted(prof.items(), key=lambda kv: -kv[1][1])},
+           "profiled_step_ms": sum(v[1] for v in prof.values())}
+    if not args.no_cpu_baseline:
+        from oracle import tsm_oracle as O
+        P = O.unflatten_params(flat.astype(np.float64))
+        nc = 2
+        c1 = I.clips(nc, T, S, 0, "bf16").astype(np.float64)
+        t0 = time.perf_counter()
+        O.resnet50_infer(P, state, c1)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": nc / dt, "unit": "videos/s", "cores": O.max_threads(), "kind": "oracle",
+                               "sample": "%d clips of the same shape through the fp64 oracle's inference forward" % nc}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--clips", type=int, default=64, help="clips per step: 64 = configs[3] (throughput run), 8 = configs[2]")
+    ap.add_argument("--clips", type=int, default=None,
+                    help="clips per step: 64 = configs[3] (throughput run, the default), 8 = configs[2]; "
+                         "--workload infer defaults to the paper's batch of 16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="step", choices=["step", "res2", "cmp"],
+    ap.add_argument("--workload", default="step", choices=["step", "res2", "cmp", "infer"],
                     help="step: the full train step (the headline, default); res2: configs[1], the three res2 bottlenecks "
                          "fwd+bwd at 8 clips; cmp: configs[4], TSM block against the 3x1x1 temporal-conv block")
     args = ap.parse_args()
@@ -229,6 +318,11 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.clips is None:
+        args.clips = 16 if args.workload == "infer" else 64
+    if args.workload == "infer":
+        print(json.dumps(infer_workload(args, torch, B, I)))
+        return
     if args.workload != "step":
         print(json.dumps(block_workload(args, torch, B, I)))
         return

@@ -224,6 +224,21 @@ int tsm_resnet50_step(const tsm_r50_desc* d, const void* clips, const int32_t* l
                       float* grads_out, float* loss_out, float* logits_out,
                       int update, void* ws, size_t ws_bytes, void* stream);
 
+/* Forward pass only, BatchNorm in inference mode (the way the paper measures single-GPU
+ * throughput of the models: section 3a, Table 1, videos per second at batch 16).
+ * Every BatchNorm uses the running statistics in bn_state (layout as above) instead of batch statistics:
+ * z = gamma*(y - mean)/sqrt(var + bn_eps) + beta.  On the bf16 path this affine map, the shortcut and the
+ * ReLU are applied in the epilogue of the convolution that produces y.
+ * Uses of desc: N, T, size, num_classes, fold_div, bn_eps, dtype (the optimiser fields are ignored).
+ * clips as for tsm_resnet50_step; params fp32 [param_count] (read only); bn_state fp32 [bn_state_count]
+ * (read only, required); logits_out fp32 [N,num_classes]: mean over the T per-frame predictions.
+ * All pointers are device pointers; the call is asynchronous on `stream`; ws is caller-owned scratch of at
+ * least tsm_resnet50_infer_workspace_bytes(desc) bytes (0 is returned for an invalid descriptor). */
+size_t tsm_resnet50_infer_workspace_bytes(const tsm_r50_desc* d);
+int tsm_resnet50_infer(const tsm_r50_desc* d, const void* clips, const float* params,
+                       const float* bn_state, float* logits_out,
+                       void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -609,6 +609,29 @@ def resnet50_infer(P, bn_state, clips, fold_div=8, eps=1e-5, q=_ident, wq=_ident
     return (pooled @ P["fc.w"].T + P["fc.b"]).mean(axis=1)
 
 
+def resnet50_batch_stats(P, clips, fold_div=8, eps=1e-5, q=_ident, wq=_ident):
+    """Training-mode forward pass that records, per BatchNorm, the batch mean and (biased) variance it
+    normalised with, as a flat vector in the bn_state layout: statistics of the kind the running averages
+    converge to, used to give the inference path realistic inputs."""
+    S = {}
+    y0 = q(conv_fwd(clips, wq(P["conv1.w"]), 2, 3, 0))
+    a0, bn0 = bn_fwd(y0, P["bn1.g"], P["bn1.b"], eps)
+    S["bn1"] = (bn0[2], bn0[3])
+    x, _ = maxpool_fwd(q(relu(a0)))
+    for name, blocks, mid, stride in STAGES:
+        for b in range(blocks):
+            pre = "%s.%d." % (name, b)
+            p = _block_params(P, pre, b == 0)
+            for k in ("w1", "w2", "w3", "wd"):
+                if k in p:
+                    p[k] = wq(p[k])
+            x, c = bottleneck_fwd(x, p, stride if b == 0 else 1, fold_div, eps, q)
+            for k, slot in (("bn1", "bn1"), ("bn2", "bn2"), ("bn3", "bn3"), ("bnd", "dsbn")):
+                if k in c:
+                    S[pre + slot] = (c[k][2], c[k][3])
+    return np.concatenate([np.concatenate([np.ravel(S[n][0]), np.ravel(S[n][1])]) for n, _ in bn_state_slots()])
+
+
 def sgd_update(P, V, G, lr, momentum=0.9, weight_decay=1e-4, num_classes=400):
     """g <- g + wd*w on convolution and fc weights only (no decay on BatchNorm
     and bias, section 4.1); v <- momentum*v + g; w <- w - lr*v."""

@@ -24,7 +24,7 @@ EXPORTS = ["tsm_last_error", "tsm_profile_begin", "tsm_profile_end", "tsm_shift_
            "tsm_conv_dgrad", "tsm_conv_wgrad", "tsm_block_saved_bytes", "tsm_block_workspace_bytes",
            "tsm_block_fwd", "tsm_block_bwd", "tsm_resnet50_param_count", "tsm_resnet50_num_tensors",
            "tsm_resnet50_param_info", "tsm_resnet50_bn_state_count", "tsm_resnet50_workspace_bytes",
-           "tsm_resnet50_step"]
+           "tsm_resnet50_step", "tsm_resnet50_infer_workspace_bytes", "tsm_resnet50_infer"]
 
 
 class TsmError(RuntimeError):
@@ -84,7 +84,7 @@ def lib():
         sig("tsm_profile_begin", ci, [vp])
         sig("tsm_profile_end", ci, [ctypes.c_char_p, sz])
         for n in ("tsm_conv_workspace_bytes", "tsm_block_saved_bytes", "tsm_block_workspace_bytes",
-                  "tsm_resnet50_workspace_bytes"):
+                  "tsm_resnet50_workspace_bytes", "tsm_resnet50_infer_workspace_bytes"):
             sig(n, sz, [vp])
         sig("tsm_resnet50_param_count", ctypes.c_int64, [ci])
         sig("tsm_resnet50_num_tensors", ci, [])
@@ -99,6 +99,7 @@ def lib():
         sig("tsm_resnet50_param_info", ci, [ci, ci, ctypes.c_char_p, ci, ctypes.POINTER(ctypes.c_int64),
                                             ctypes.POINTER(ci), ctypes.POINTER(ci * 4), ctypes.POINTER(ci)])
         sig("tsm_resnet50_step", ci, [vp, vp, vp, vp, vp, vp, vp, vp, vp, ci, vp, sz, vp])
+        sig("tsm_resnet50_infer", ci, [vp, vp, vp, vp, vp, vp, sz, vp])
         _LIB = L
     return _LIB
 
@@ -245,3 +246,13 @@ def tsm_resnet50_step(desc, clips, labels, params, momentum, bn_state, grads_out
     _check(lib().tsm_resnet50_step(ctypes.addressof(desc), _ptr(clips), _ptr(labels), _ptr(params), _ptr(momentum),
                                    _ptr(bn_state), _ptr(grads_out), _ptr(loss_out), _ptr(logits_out), int(update),
                                    p, n, _stream(stream)))
+
+
+def tsm_resnet50_infer_workspace_bytes(desc):
+    return int(lib().tsm_resnet50_infer_workspace_bytes(ctypes.addressof(desc)))
+
+
+def tsm_resnet50_infer(desc, clips, params, bn_state, logits_out, ws, stream=None):
+    p, n = _ws(ws)
+    _check(lib().tsm_resnet50_infer(ctypes.addressof(desc), _ptr(clips), _ptr(params), _ptr(bn_state),
+                                    _ptr(logits_out), p, n, _stream(stream)))

@@ -52,7 +52,7 @@ int run_conv_fwd(const ConvP& p, int dtype, const void* x, const void* w, const 
             RUN(pack_weights_fwd(dtype, w, pk, p.Cout, p.Cin, p.taps(), p.Cin, s));
             wp = pk;
         }
-        RUN(conv_mfma_fwd(p, (const bf16_t*)x, wp, (bf16_t*)y, stats_partial, s));
+        RUN(conv_mfma_fwd(p, (const bf16_t*)x, wp, (bf16_t*)y, stats_partial, nullptr, s));
     } else {
         RUN(conv_direct_fwd(p, dtype, x, w, y, s));
         if (stats_partial) RUN(channel_stats(dtype, y, p.rows_out(), p.Cout, stats_partial, s));

@@ -44,6 +44,13 @@ struct IgemmArgs {
     const bf16_t* ybn;
     const float* bn_mean;
     const float* bn_rstd;
+    // fwd, igemm_ring_kernel only (nullable): the stored result is act(ep_scale[c]*y + ep_shift[c] + ep_res), y
+    // rounded to bf16 first; ep_res (nullable) has the shape of dst; act = ReLU when ep_relu, identity otherwise.
+    // This is BatchNorm with known statistics (inference) folded into the epilogue.
+    const float* ep_scale;
+    const float* ep_shift;
+    const bf16_t* ep_res;
+    int ep_relu;
     int F, T;
     int Hs, Ws, Cs;        // source frame
     int pitch;             // elements between consecutive source pixels (Cs, or less: see ConvP::pitch)
@@ -751,17 +758,19 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
 #pragma unroll
         for (int j = 0; j < NJ; ++j) s1[j] = s2[j] = 0.f;
         // fused BatchNorm backward: this thread stores the same eight columns of every row it handles
-        constexpr int FV = DGRAD ? 8 : 1;
+        // (forward with an affine epilogue keeps scale / shift of the same eight columns in mu / rs)
+        constexpr int FV = 8;
+        const bool affine = !DGRAD && a.ep_scale != nullptr;
         float f1[FV], f2[FV], mu[FV], rs[FV];
 #pragma unroll
         for (int q = 0; q < FV; ++q) f1[q] = f2[q] = mu[q] = rs[q] = 0.f;
-        if (fuse_bn) {
+        if (fuse_bn || affine) {
             const int c0 = cur_n0 + (tid % (BN / 8)) * 8;
             if (c0 < a.Cd) {
 #pragma unroll
                 for (int q = 0; q < FV; ++q) {
-                    mu[q] = a.bn_mean[c0 + q];
-                    rs[q] = a.bn_rstd[c0 + q];
+                    mu[q] = DGRAD ? a.bn_mean[c0 + q] : a.ep_scale[c0 + q];
+                    rs[q] = DGRAD ? a.bn_rstd[c0 + q] : a.ep_shift[c0 + q];
                 }
             }
         }
@@ -839,8 +848,22 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                     const int row = pss * RPS + r0;
                     const int mrow = s_row[rb * BM + h * HM + row].dst;
                     if (mrow < 0 || col >= a.Cd) continue;
-                    const u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
+                    u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
                     u32x4* q = (u32x4*)(a.dst + (long)mrow * a.Cd + col);
+                    if (affine) {
+                        u32x4 r = u32x4{0u, 0u, 0u, 0u};
+                        if (a.ep_res) r = *(const u32x4*)(a.ep_res + (long)mrow * a.Cd + col);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            float lo = fmaf(__uint_as_float(v[e] << 16), mu[2 * e], rs[2 * e]) + __uint_as_float(r[e] << 16);
+                            float hi = fmaf(__uint_as_float(v[e] & 0xffff0000u), mu[2 * e + 1], rs[2 * e + 1]) + __uint_as_float(r[e] & 0xffff0000u);
+                            if (a.ep_relu) {
+                                lo = lo > 0.f ? lo : 0.f;
+                                hi = hi > 0.f ? hi : 0.f;
+                            }
+                            v[e] = pack_bf16x2(lo, hi);
+                        }
+                    }
                     if (STREAM) __builtin_nontemporal_store(v, q);
                     else *q = v;
                 }
@@ -1098,10 +1121,20 @@ int conv_mfma_fwd_blocks(const ConvP& p) {
     return igemm_grid((int)((p.rows_out() + 127) / 128), p.Cout, bn, 2);
 }
 
-int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, float* stats, hipStream_t s) {
+bool conv_mfma_fwd_can_fuse(const ConvP& p) {
+    return ring_eligible(p.Cin, p.rows_in() * (long)p.pix_pitch() + p.Cin + (long)(p.pad * p.W + p.pad) * p.pix_pitch(), (long)p.Cout * p.K());
+}
+
+int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, float* stats, const FwdEpilogue* ep,
+                  hipStream_t s) {
     IgemmArgs a;
     a.src = x; a.wp = wp; a.dst = y; a.addend = nullptr; a.stats = stats;
     a.act = nullptr; a.ybn = nullptr; a.bn_mean = nullptr; a.bn_rstd = nullptr;
+    a.ep_scale = nullptr; a.ep_shift = nullptr; a.ep_res = nullptr; a.ep_relu = 0;
+    if (ep) {
+        if (!conv_mfma_fwd_can_fuse(p)) return fail(TSM_ERR_UNSUPPORTED, "conv forward: this layer's kernel has no affine epilogue");
+        a.ep_scale = ep->scale; a.ep_shift = ep->shift; a.ep_res = ep->res; a.ep_relu = ep->relu;
+    }
     a.F = p.F; a.T = p.T;
     a.Hs = p.H; a.Ws = p.W; a.Cs = p.Cin; a.pitch = p.pix_pitch();
     a.Hd = p.Ho; a.Wd = p.Wo; a.Cd = p.Cout;
@@ -1136,6 +1169,7 @@ int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* 
     IgemmArgs a;
     a.src = dy; a.wp = wd; a.dst = dx; a.addend = addend; a.stats = nullptr;
     a.act = nullptr; a.ybn = nullptr; a.bn_mean = nullptr; a.bn_rstd = nullptr;
+    a.ep_scale = nullptr; a.ep_shift = nullptr; a.ep_res = nullptr; a.ep_relu = 0;
     dgrad_args(p, a);
     if (fuse) {
         if (conv_mfma_dgrad_blocks(p) == 0) return fail(TSM_ERR_UNSUPPORTED, "dgrad: this layer's kernel cannot fuse the BatchNorm reductions");

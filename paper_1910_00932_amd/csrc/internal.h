@@ -89,7 +89,17 @@ bool mfma_conv_supported(const ConvP& p);
 int conv_mfma_fwd_blocks(const ConvP& p);
 // y = conv(S(x)); wp = bf16 [Cout][taps][Cin]; stats_partial (nullable), fp32 [conv_mfma_fwd_blocks(p)][2*Cout],
 // receives per block the per-channel sum / sum of squares of the stored (rounded) output.
-int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, float* stats_partial, hipStream_t s);
+// Optional epilogue (nullable): the stored result is act(scale[c]*y + shift[c] + res) -- BatchNorm with known
+// statistics, the shortcut and the ReLU folded into the convolution; only where conv_mfma_fwd_can_fuse(p).
+struct FwdEpilogue {
+    const float* scale;
+    const float* shift;
+    const bf16_t* res;   // nullable, shape of y
+    int relu;
+};
+bool conv_mfma_fwd_can_fuse(const ConvP& p);
+int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, float* stats_partial,
+                  const FwdEpilogue* ep, hipStream_t s);
 // Optional fusion into the data-gradient epilogue: dx is the gradient w.r.t. act = ReLU(BatchNorm(y)) (all
 // [rows_in][Cin] bf16); it is stored already masked with act > 0, and `partial`, fp32
 // [conv_mfma_dgrad_blocks(p)][2*Cin], receives per block the per-channel sums of dz and of dz*(y-mean)*rstd.

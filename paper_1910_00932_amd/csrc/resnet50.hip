@@ -414,6 +414,33 @@ __global__ void __launch_bounds__(256) pack_all_kernel(PackTable t, const float*
     out[(size_t)t.out_off[lo] + e] = f32_to_bf16(v);
 }
 
+// ---- inference-mode BatchNorm parameters of the whole network in one launch ---------------------
+// scale = gamma / sqrt(var + eps), shift = beta - mean * scale, written at the BatchNorm's position in the
+// concatenated channel space (BatchNorms in parameter-table order).
+struct BnTable {
+    int n;
+    unsigned start[56];       // first channel of BatchNorm l in the concatenated channel space (start[n] = total)
+    unsigned g_off[55];       // element offsets of gamma / beta in the parameter vector
+    unsigned b_off[55];
+    unsigned s_off[55];       // offset of the BatchNorm's mean in the running-statistics vector (variance follows)
+};
+
+__global__ void __launch_bounds__(256) bn_eval_params_kernel(BnTable t, const float* __restrict__ params,
+                                                             const float* __restrict__ bn_state, float eps,
+                                                             float* __restrict__ scale, float* __restrict__ shift) {
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= t.start[t.n]) return;
+    int lo = 0, hi = t.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (t.start[mid] <= i) lo = mid; else hi = mid - 1;
+    }
+    const unsigned c = i - t.start[lo], C = t.start[lo + 1] - t.start[lo];
+    const float sc = params[t.g_off[lo] + c] / sqrtf(bn_state[t.s_off[lo] + C + c] + eps);
+    scale[i] = sc;
+    shift[i] = fmaf(-bn_state[t.s_off[lo] + c], sc, params[t.b_off[lo] + c]);
+}
+
 // ---- SGD with momentum; weight decay only inside "decay" segments -----------------------------
 struct SgdSegments {
     int n;
@@ -664,7 +691,7 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
             RUN(transpose_frames(clips, x0, F, 3, S * S, 4, s));
         }
         if (bf) {
-            RUN(conv_mfma_fwd(stem, (const bf16_t*)x0, wp0, (bf16_t*)y0, part0, s));
+            RUN(conv_mfma_fwd(stem, (const bf16_t*)x0, wp0, (bf16_t*)y0, part0, nullptr, s));
         } else {
             RUN(conv_direct_fwd(stem, dtype, x0, P("conv1.w"), y0, s));
             RUN(channel_stats(dtype, y0, stem.rows_out(), 64, part0, s));
@@ -771,6 +798,252 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
 
 using namespace tsm;
 
+// ---- forward only (inference): BatchNorm with the running statistics, folded into the convolution
+// epilogues on the bf16 path; nothing is saved for a backward pass ------------------------------------
+static int r50_infer(const tsm_r50_desc* d, const void* clips, const float* params, const float* bn_state,
+                     float* logits_out, void* wsp, size_t ws_bytes, bool dry, hipStream_t s, size_t* need) {
+    const char* who = "tsm_resnet50_infer";
+    if (!d) return fail(TSM_ERR_NULLPTR, "%s: null descriptor", who);
+    if (d->N <= 0 || d->T <= 0 || d->size < 32 || d->num_classes <= 0)
+        return fail(TSM_ERR_SHAPE, "%s: N, T, num_classes must be positive and size >= 32", who);
+    if (d->size % 32) return fail(TSM_ERR_SHAPE, "%s: size must be a multiple of 32", who);
+    if ((long)d->N * d->T > 65535) return fail(TSM_ERR_SHAPE, "%s: too many frames", who);
+    if (d->dtype != TSM_F32 && d->dtype != TSM_BF16) return fail(TSM_ERR_DTYPE, "%s: unknown dtype %d", who, d->dtype);
+    int fold_chk = 0;
+    if (fold_of(64, d->fold_div, &fold_chk) != TSM_OK) return fail(TSM_ERR_FOLD, "%s: invalid fold_div %d", who, d->fold_div);
+    if (!(d->bn_eps >= 0.f)) return fail(TSM_ERR_SHAPE, "%s: bn_eps must be >= 0", who);
+    if (!dry) {
+        if (!clips || !params || !bn_state || !logits_out) return fail(TSM_ERR_NULLPTR, "%s: null pointer", who);
+        if (!aligned16(clips) || !aligned16(params) || !aligned16(wsp))
+            return fail(TSM_ERR_ALIGN, "%s: pointers must be 16-byte aligned", who);
+        size_t req = 0;
+        TSM_TRY(r50_infer(d, clips, params, bn_state, logits_out, nullptr, 0, true, s, &req));
+        if (req > ws_bytes) return fail(TSM_ERR_WORKSPACE, "%s: workspace %zu bytes, need %zu", who, ws_bytes, req);
+        if (!wsp) return fail(TSM_ERR_NULLPTR, "%s: null workspace", who);
+    }
+    static thread_local std::vector<TensorInfo> table;
+    static thread_local int table_classes = -1;
+    if (table_classes != d->num_classes) {
+        table = build_table(d->num_classes);
+        table_classes = d->num_classes;
+    }
+    const int F = d->N * d->T, T = d->T, S = d->size, K = d->num_classes;
+    const int dtype = d->dtype;
+    const bool bf = dtype == TSM_BF16;
+    const size_t es = dtype_size(dtype);
+    const int VEC = bf ? 8 : 4;
+    Arena A(dry ? nullptr : wsp, (size_t)-1);
+    auto P = [&](const std::string& name) { return params + table[find_tensor(table, name)].offset; };
+
+    // ---- BatchNorm parameters: one launch over all channels
+    BnTable bt;
+    bt.n = 0;
+    bt.start[0] = 0;
+    unsigned s_off = 0;
+    for (size_t i = 0; i < table.size(); ++i) {
+        const std::string& nm = table[i].name;
+        if (nm.size() < 2 || nm.compare(nm.size() - 2, 2, ".g") != 0) continue;
+        if (bt.n >= 55) return fail(TSM_ERR_UNSUPPORTED, "%s: too many BatchNorms", who);
+        const unsigned C = (unsigned)table[i].count();
+        bt.g_off[bt.n] = (unsigned)table[i].offset;
+        bt.b_off[bt.n] = (unsigned)table[i + 1].offset;   // beta follows gamma in the table
+        bt.s_off[bt.n] = s_off;
+        bt.start[bt.n + 1] = bt.start[bt.n] + C;
+        s_off += 2 * C;
+        ++bt.n;
+    }
+    const unsigned nch = bt.start[bt.n];
+    float* scale_all = A.take_n<float>(nch);
+    float* shift_all = A.take_n<float>(nch);
+    int bn_next = 0;   // BatchNorms are consumed in table order
+    auto bn_slot = [&](const float** sc, const float** sh) {
+        *sc = scale_all + bt.start[bn_next];
+        *sh = shift_all + bt.start[bn_next];
+        ++bn_next;
+    };
+
+    // ---- forward weights (bf16: packed working copies, one launch)
+    PackTable pk;
+    pk.n = 0;
+    pk.start[0] = 0;
+    bf16_t* const pack_base = (bf16_t*)(dry ? nullptr : wsp);
+    auto pack_conv = [&](const std::string& name, int Cout, int Cin, int k, const bf16_t** wp) -> int {
+        *wp = nullptr;
+        if (!bf) return TSM_OK;
+        if (pk.n >= 55) return fail(TSM_ERR_UNSUPPORTED, "%s: too many convolutions", who);
+        const size_t nf = (size_t)Cout * Cin * k * k;
+        bf16_t* a = A.take_n<bf16_t>(nf);
+        const int l = pk.n++;
+        pk.in_off[l] = (unsigned)table[find_tensor(table, name)].offset;
+        pk.out_off[l] = (unsigned)(a - pack_base);
+        pk.cout[l] = (unsigned short)Cout; pk.cin[l] = (unsigned short)Cin; pk.cinp[l] = (unsigned short)Cin;
+        pk.k[l] = (unsigned short)k;
+        pk.start[l + 1] = pk.start[l] + (unsigned)nf;
+        *wp = a;
+        return TSM_OK;
+    };
+
+    // ---- stem
+    const int H1 = S / 2, Hp = S / 4, Hs = H1 + 3;
+    bf16_t* wp0 = bf ? A.take_n<bf16_t>(64 * 256) : nullptr;
+    void* x0 = bf ? A.take((size_t)F * Hs * Hs * 16 * es) : A.take((size_t)F * S * S * 3 * es);
+    void* y0 = A.take((size_t)F * H1 * H1 * 64 * es);
+    uint8_t* arg0 = A.take_n<uint8_t>((size_t)F * Hp * Hp * 64);
+    void* p0 = A.take((size_t)F * Hp * Hp * 64 * es);
+    ConvP stem{};
+    stem.F = F; stem.T = T; stem.Ho = H1; stem.Wo = H1; stem.Cout = 64; stem.KT = 1; stem.fold = 0;
+    if (bf) {
+        stem.H = Hs; stem.W = Hs; stem.Cin = 64; stem.pitch = 16; stem.KH = 4; stem.KW = 1; stem.stride = 1; stem.pad = 0;
+    } else {
+        stem.H = S; stem.W = S; stem.Cin = 3; stem.KH = 7; stem.KW = 7; stem.stride = 2; stem.pad = 3;
+    }
+    const float *sc0, *sh0;
+    bn_slot(&sc0, &sh0);
+
+    // ---- blocks: geometry, weights, BatchNorm slots; activations ping-pong between two buffers
+    struct IBlk {
+        BlockPlan plan;
+        const bf16_t* wp[4];
+        const float *sc[4], *sh[4];
+    };
+    std::vector<IBlk> blks;
+    size_t wide_max = (size_t)F * Hp * Hp * 64 * es, mid_max = 0;
+    {
+        int cin = 64, h = Hp;
+        for (const StageSpec& st : kStages) {
+            for (int b = 0; b < st.blocks; ++b) {
+                const std::string pre = std::string(st.name) + "." + std::to_string(b) + ".";
+                tsm_block_desc bd{};
+                bd.kind = TSM_BLOCK_BOTTLENECK; bd.N = d->N; bd.T = T; bd.Cin = cin; bd.H = h; bd.W = h;
+                bd.Cmid = st.mid; bd.Cout = 4 * st.mid; bd.stride = b == 0 ? st.stride : 1; bd.has_projection = b == 0;
+                bd.fold_div = d->fold_div; bd.dtype = dtype; bd.layout = TSM_NTHWC; bd.bn_eps = d->bn_eps;
+                IBlk blk;
+                TSM_TRY(make_block_plan(&bd, &blk.plan, who));
+                const char* cn[3] = {"c1.w", "c2.w", "c3.w"};
+                for (int i = 0; i < 3; ++i) {
+                    StageDef& sd = blk.plan.st[i];
+                    TSM_TRY(pack_conv(pre + cn[i], sd.p.Cout, sd.p.Cin, sd.p.KH, &blk.wp[i]));
+                    sd.w = P(pre + cn[i]);
+                    bn_slot(&blk.sc[i], &blk.sh[i]);
+                    const size_t by = (size_t)sd.p.rows_out() * sd.p.Cout * es;
+                    if (i < 2 && by > mid_max) mid_max = by;
+                    if (i == 2 && by > wide_max) wide_max = by;
+                }
+                blk.wp[3] = nullptr; blk.sc[3] = blk.sh[3] = nullptr;
+                if (blk.plan.proj) {
+                    StageDef& sd = blk.plan.ds;
+                    TSM_TRY(pack_conv(pre + "ds.w", sd.p.Cout, sd.p.Cin, 1, &blk.wp[3]));
+                    sd.w = P(pre + "ds.w");
+                    bn_slot(&blk.sc[3], &blk.sh[3]);
+                }
+                blks.push_back(blk);
+                cin = 4 * st.mid;
+                h = blk.plan.st[2].p.Ho;
+            }
+        }
+    }
+    void* act[2] = {A.take(wide_max), A.take(wide_max)};
+    void* mid[2] = {A.take(mid_max), A.take(mid_max)};
+    void* ytmp = A.take(wide_max);    // raw convolution output where the epilogue cannot be fused
+    void* scbuf = A.take(wide_max);   // projection shortcut
+    const ConvP& lastp = blks.back().plan.st[2].p;
+    const int Cf = lastp.Cout, rows_clip = T * lastp.Ho * lastp.Wo;
+    float* pm = A.take_n<float>((size_t)d->N * Cf);
+    char* scratch_base = dry ? nullptr : (char*)wsp + A.used;
+    const size_t scratch_cap = dry ? (size_t)-1 : (ws_bytes > A.used ? ws_bytes - A.used : 0);
+    size_t scratch_need = 0;
+
+    // out = act(scale*conv(x) + shift + res): fused where the kernel can, else convolution + elementwise pass
+    auto conv_bn_act = [&](const StageDef& sd, const bf16_t* wp, const void* x, const float* sc, const float* sh,
+                           const void* res, void* out) -> int {
+        Arena ws(scratch_base, scratch_cap);
+        if (bf && mfma_conv_supported(sd.p) && conv_mfma_fwd_can_fuse(sd.p)) {
+            const FwdEpilogue ep = {sc, sh, (const bf16_t*)res, 1};
+            RUN(conv_mfma_fwd(sd.p, (const bf16_t*)x, wp, (bf16_t*)out, nullptr, &ep, s));
+            return TSM_OK;
+        }
+        TSM_TRY(run_conv_fwd(sd.p, dtype, x, sd.w, wp, ytmp, nullptr, ws, dry, s));
+        if (ws.used > scratch_need) scratch_need = ws.used;
+        if (res)
+            RUN(block_tail_fwd(dtype, ytmp, sd.p.rows_out(), sd.p.Cout, sc, sh, res, nullptr, nullptr, out, s));
+        else
+            RUN(bn_relu_apply(dtype, ytmp, sd.p.rows_out(), sd.p.Cout, sc, sh, out, s));
+        return TSM_OK;
+    };
+
+    // ================= forward =================
+    if (!dry) {
+        bn_eval_params_kernel<<<dim3(cdiv(nch, 256)), dim3(256), 0, s>>>(bt, params, bn_state, d->bn_eps, scale_all, shift_all);
+        LAUNCH_CHECK("bn_eval_params");
+        if (bf) {
+            pack_all_kernel<<<dim3(cdiv(pk.start[pk.n], 256)), dim3(256), 0, s>>>(pk, params, pack_base, 0);
+            LAUNCH_CHECK("pack_weights_fwd");
+            const long total = (long)F * Hs * Hs;
+            clips_to_s2d_kernel<<<dim3(cdiv(total, 256)), dim3(256), 0, s>>>((const bf16_t*)clips, (uint4*)x0, S, Hs, total);
+            LAUNCH_CHECK("clips_to_s2d");
+            stem_pack_kernel<<<dim3(64), dim3(256), 0, s>>>(P("conv1.w"), wp0);
+            LAUNCH_CHECK("stem_pack");
+        }
+    }
+    if (bf) {
+        RUN(conv_mfma_fwd(stem, (const bf16_t*)x0, wp0, (bf16_t*)y0, nullptr, nullptr, s));
+    } else {
+        RUN(transpose_frames(clips, x0, F, 3, S * S, 4, s));
+        RUN(conv_direct_fwd(stem, dtype, x0, P("conv1.w"), y0, s));
+    }
+    {
+        const int cv = 64 / VEC;
+        const long ptotal = (long)F * Hp * Hp * cv;
+        if (!dry) {
+            if (bf)
+                stem_pool_fwd_kernel<bf16_t><<<dim3(cdiv(ptotal, 256)), dim3(256), 0, s>>>((const bf16_t*)y0, sc0, sh0, (bf16_t*)p0, arg0, H1, H1, Hp, Hp, cv, ptotal);
+            else
+                stem_pool_fwd_kernel<float><<<dim3(cdiv(ptotal, 256)), dim3(256), 0, s>>>((const float*)y0, sc0, sh0, (float*)p0, arg0, H1, H1, Hp, Hp, cv, ptotal);
+            LAUNCH_CHECK("stem_pool_fwd");
+        }
+    }
+    const void* cur = p0;
+    int flip = 0;
+    for (IBlk& b : blks) {
+        BlockPlan& pl = b.plan;
+        TSM_TRY(conv_bn_act(pl.st[0], b.wp[0], cur, b.sc[0], b.sh[0], nullptr, mid[0]));
+        TSM_TRY(conv_bn_act(pl.st[1], b.wp[1], mid[0], b.sc[1], b.sh[1], nullptr, mid[1]));
+        void* out = act[flip];
+        if (pl.proj) {
+            const StageDef& sd = pl.ds;
+            if (bf && mfma_conv_supported(sd.p) && conv_mfma_fwd_can_fuse(sd.p)) {
+                // shortcut = BatchNorm(conv(x)) by the affine epilogue, then added in the last convolution's epilogue
+                const FwdEpilogue ep = {b.sc[3], b.sh[3], nullptr, 0};
+                RUN(conv_mfma_fwd(sd.p, (const bf16_t*)cur, b.wp[3], (bf16_t*)scbuf, nullptr, &ep, s));
+                TSM_TRY(conv_bn_act(pl.st[2], b.wp[2], mid[1], b.sc[2], b.sh[2], scbuf, out));
+            } else {
+                // unfused: both raw convolution outputs, then one pass relu(bn3(y3) + bnd(yd))
+                Arena ws(scratch_base, scratch_cap);
+                TSM_TRY(run_conv_fwd(sd.p, dtype, cur, sd.w, b.wp[3], scbuf, nullptr, ws, dry, s));
+                TSM_TRY(run_conv_fwd(pl.st[2].p, dtype, mid[1], pl.st[2].w, b.wp[2], ytmp, nullptr, ws, dry, s));
+                if (ws.used > scratch_need) scratch_need = ws.used;
+                RUN(block_tail_fwd(dtype, ytmp, pl.st[2].p.rows_out(), pl.st[2].p.Cout, b.sc[2], b.sh[2], scbuf, b.sc[3],
+                                   b.sh[3], out, s));
+            }
+        } else {
+            TSM_TRY(conv_bn_act(pl.st[2], b.wp[2], mid[1], b.sc[2], b.sh[2], cur, out));
+        }
+        cur = out;
+        flip ^= 1;
+    }
+    if (!dry) {
+        if (bf)
+            pool_mean_kernel<bf16_t><<<dim3(cdiv(Cf, 256), d->N), dim3(256), 0, s>>>((const bf16_t*)cur, pm, rows_clip, Cf);
+        else
+            pool_mean_kernel<float><<<dim3(cdiv(Cf, 256), d->N), dim3(256), 0, s>>>((const float*)cur, pm, rows_clip, Cf);
+        LAUNCH_CHECK("pool_mean");
+        fc_fwd_kernel<<<dim3(K), dim3(256), 0, s>>>(pm, P("fc.w"), P("fc.b"), logits_out, d->N, Cf, K);
+        LAUNCH_CHECK("fc_fwd");
+    }
+    if (need) *need = align_up(A.used) + align_up(scratch_need) + 256;
+    return TSM_OK;
+}
+
 extern "C" {
 
 int64_t tsm_resnet50_param_count(int num_classes) {
@@ -818,6 +1091,17 @@ int tsm_resnet50_step(const tsm_r50_desc* d, const void* clips, const int32_t* l
                       size_t ws_bytes, void* stream) {
     return r50_step(d, clips, labels, params, momentum, bn_state, grads_out, loss_out, logits_out, update, ws, ws_bytes,
                     false, (hipStream_t)stream, nullptr);
+}
+
+size_t tsm_resnet50_infer_workspace_bytes(const tsm_r50_desc* d) {
+    size_t need = 0;
+    if (r50_infer(d, nullptr, nullptr, nullptr, nullptr, nullptr, 0, true, nullptr, &need) != TSM_OK) return 0;
+    return need;
+}
+
+int tsm_resnet50_infer(const tsm_r50_desc* d, const void* clips, const float* params, const float* bn_state,
+                       float* logits_out, void* ws, size_t ws_bytes, void* stream) {
+    return r50_infer(d, clips, params, bn_state, logits_out, ws, ws_bytes, false, (hipStream_t)stream, nullptr);
 }
 
 }  // extern "C"

@@ -72,3 +72,31 @@ def test_bn_state_layout_and_network_inference_shape():
     # a clip is classified independently of the other clips in the batch (no batch statistics are involved)
     two = np.concatenate([clips, I.clips(1, 2, 32, 5, "f32").astype(np.float64)])
     assert np.allclose(O.resnet50_infer(P, state, two)[0], logits[0], rtol=0, atol=1e-9)
+
+
+def test_inference_with_recorded_batch_statistics_equals_training_forward():
+    """Whole network: the statistics recorded by a training-mode forward, fed back as running statistics,
+    make the inference path reproduce the training-mode logits (computed by the separate forward+backward
+    routine through bn_fwd).  A BatchNorm wired to the wrong slot, a missing shortcut BN or a swapped
+    mean/variance breaks this."""
+    table = O.resnet50_param_table(10)
+    flat = I.init_params([(n, s) for n, s, _ in table], 3).astype(np.float64)
+    rng = np.random.default_rng(4)
+    off = 0
+    for name, shape, _ in table:      # distinct BatchNorm scales/offsets
+        n = int(np.prod(shape))
+        if len(shape) == 1 and name != "fc.b":
+            flat[off:off + n] += 0.1 * rng.standard_normal(n)
+        off += n
+    P = O.unflatten_params(flat, 10)
+    clips = I.clips(2, 2, 32, 0, "f32").astype(np.float64)
+    state = O.resnet50_batch_stats(P, clips)
+    assert state.shape == (O.bn_state_count(),)
+    S = O.unflatten_bn_state(state)
+    assert all(np.all(v > 0) for _, v in S.values())          # second half of every slot is a variance
+    _, logits_train, _ = O.resnet50_fwd_bwd(P, clips, np.array([1, 2]))
+    assert np.allclose(O.resnet50_infer(P, state, clips), logits_train, rtol=0, atol=1e-9)
+    # and the statistics matter: perturbing one variance changes the logits
+    state2 = state.copy()
+    state2[64:128] *= 4.0
+    assert not np.allclose(O.resnet50_infer(P, state2, clips), logits_train, atol=1e-6)
