@@ -226,9 +226,17 @@ def infer_workload(args, torch, B, I):
     logits = torch.empty((N, K), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
 
-    def step():
-        B.tsm_resnet50_infer(d, clips, params, bn_state, logits, ws, stream)
+    def eager():
+        B.tsm_resnet50_infer(d, clips, params, bn_state, logits, ws, torch.cuda.current_stream())
 
+    step = eager
+    if args.graph:      # the call is stream-ordered and allocates nothing: record it once, replay it per step
+        eager()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            eager()
+        step = graph.replay
     for _ in range(args.warmup):
         step()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -242,7 +250,7 @@ def infer_workload(args, torch, B, I):
     if not bool(torch.isfinite(logits).all()):
         sys.exit("bench.py: logits are not finite")
     B.tsm_profile_begin(stream)
-    step()
+    eager()
     prof = B.tsm_profile_end()
     F = N * T
     work, byt = {}, {}
@@ -277,7 +285,7 @@ def infer_workload(args, torch, B, I):
                       "clips_per_step": N, "frames": T, "size": S, "num_classes": K},
            "step_tflops": flops / (ms * 1e-3) / 1e12,
            "pct_bf16_mfma_peak": 100.0 * flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-           "roofline": roof,
+           "roofline": roof, "hip_graph": bool(args.graph),
            "kernel_classes": {k: {"launches": v[0], "ms": round(v[1], 4),
                                   "tflops": round(work[k] / (v[1] * 1e-3) / 1e12, 1) if k in work else None}
                               for k, v in sorted(prof.items(), key=lambda kv: -kv[1][1])},
@@ -304,6 +312,8 @@ def main():
                     help="clips per step: 64 = configs[3] (throughput run, the default), 8 = configs[2]; "
                          "--workload infer defaults to the paper's batch of 16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="record one call into a HIP graph and time replays of it (step and infer workloads)")
     ap.add_argument("--workload", default="step", choices=["step", "res2", "cmp", "infer"],
                     help="step: the full train step (the headline, default); res2: configs[1], the three res2 bottlenecks "
                          "fwd+bwd at 8 clips; cmp: configs[4], TSM block against the 3x1x1 temporal-conv block")
@@ -345,9 +355,17 @@ def main():
     loss = torch.zeros(1, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
 
-    def step():
-        B.tsm_resnet50_step(d, clips, labels, params, mom, bn_state, None, loss, None, 1, ws, stream)
+    def eager():
+        B.tsm_resnet50_step(d, clips, labels, params, mom, bn_state, None, loss, None, 1, ws, torch.cuda.current_stream())
 
+    step = eager
+    if args.graph:      # the call is stream-ordered and allocates nothing: record it once, replay it per step
+        eager()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            eager()
+        step = graph.replay
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -367,7 +385,7 @@ def main():
 
     # per-class time of one more step, HIP events on the launch stream after every launch
     B.tsm_profile_begin(stream)
-    step()
+    eager()
     prof = B.tsm_profile_end()
     work = class_work(N * T, S)
     dom = max(prof, key=lambda k: prof[k][1])
@@ -409,7 +427,7 @@ def main():
                    "clips_per_step": N, "frames": T, "size": S, "num_classes": K},
         "step_tflops": flops_step / (ms_per_step * 1e-3) / 1e12,
         "pct_bf16_mfma_peak": 100.0 * flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        "loss_after": final_loss, "wall_s": wall,
+        "loss_after": final_loss, "wall_s": wall, "hip_graph": bool(args.graph),
         "roofline": roof, "kernel_classes": classes, "profiled_step_ms": prof_total,
     }
 

@@ -650,6 +650,37 @@ def resnet50_step(P, V, clips, labels, lr, momentum=0.9, weight_decay=1e-4,
     return loss, logits, G, P2, V2
 
 
+def resnet50_accum_step(P, V, micro_batches, lr, momentum=0.9, weight_decay=1e-4,
+                        fold_div=8, eps=1e-5, q=_ident, wq=_ident):
+    """One update from k micro-batches (gradient accumulation, the way the paper simulates node counts it
+    could not run, section 5): every micro-batch (clips, labels) goes through forward + backward on its own
+    (its BatchNorms see only its own frames), the k gradients are averaged, and one SGD update is applied.
+    Returns the list of micro-batch losses, the averaged gradients, and the updated P, V."""
+    k = len(micro_batches)
+    losses, acc = [], None
+    for clips, labels in micro_batches:
+        loss, _, G = resnet50_fwd_bwd(P, clips, labels, fold_div, eps, q, wq)
+        losses.append(loss)
+        acc = dict(G) if acc is None else {n: acc[n] + G[n] for n in acc}
+    G = {n: v / k for n, v in acc.items()}
+    P2, V2 = sgd_update(P, V, G, lr, momentum, weight_decay, P["fc.w"].shape[0])
+    return losses, G, P2, V2
+
+
+def lr_schedule(epoch, total_batch, warm_batch=8, warmup_epochs=5.0, total_epochs=100.0, base_lr=0.00125, base_batch=8):
+    """Learning rate at (fractional) `epoch` of the paper's recipe (section 4.1): base_lr per base_batch samples
+    scaled linearly with the total batch (eta = 0.00125 k for k GPUs of 8 clips); gradual warm-up over the first
+    warmup_epochs, rising linearly from the rate of `warm_batch` samples (one GPU's batch) to the full rate;
+    then cosine decay that reaches zero at total_epochs."""
+    peak = base_lr * total_batch / base_batch
+    start = base_lr * min(warm_batch, total_batch) / base_batch
+    if epoch < warmup_epochs:
+        return start + (peak - start) * epoch / warmup_epochs
+    if epoch >= total_epochs:
+        return 0.0
+    return 0.5 * peak * (1.0 + np.cos(np.pi * (epoch - warmup_epochs) / (total_epochs - warmup_epochs)))
+
+
 # ----------------------------------------------------------------------------
 # bf16 storage emulation (round-to-nearest-even on the upper 16 bits of fp32)
 # ----------------------------------------------------------------------------

@@ -99,3 +99,57 @@ def test_infer_rejects_bad_arguments():
     bad = B.R50Desc(N=1, T=2, size=40, num_classes=400, fold_div=8, lr=0.0, momentum=0.9, weight_decay=1e-4,
                     bn_eps=1e-5, bn_momentum=0.1, dtype=B.TSM_BF16)
     assert B.tsm_resnet50_infer_workspace_bytes(bad) == 0
+
+
+def test_infer_full_size_batch16_sampled_clips():
+    """The benchmark's launch configuration (16 clips x 8 frames x 224x224, bf16): inference is independent per
+    clip, so the logits of two of the sixteen clips are checked against the oracle run on those two clips alone."""
+    N, T, S = 16, 8, 224
+    table, flat, clips2, P, state = setup(2, T, S, "bf16", g3=0.25)
+    clips = np.concatenate([clips2[0:1]] + [I.clips(1, T, S, 20 + i, "bf16") for i in range(N - 2)] + [clips2[1:2]])
+    got = run_infer(N, T, S, "bf16", flat, clips, state)
+    assert np.all(np.isfinite(got))
+    c64, s64 = clips2.astype(np.float64), state.astype(np.float64)
+    refq = O.resnet50_infer(P, s64, c64, q=O.round_bf16, wq=O.round_bf16)
+    ref = O.resnet50_infer(P, s64, c64)
+    sens = rel_l2(refq, ref)
+    pick = got[[0, N - 1]]
+    errs = (rel_l2(pick, refq), rel_l2(pick, ref), sens)
+    print("bf16 inference at batch 16, 224x224: err %.4f vs bf16 oracle, %.4f vs fp64 oracle (sens %.4f)" % errs)
+    bound = max(2e-2, 1.5 * sens)
+    assert errs[0] < bound and errs[1] < bound, errs
+
+
+def test_infer_replays_from_a_hip_graph():
+    """The call is stream-ordered and allocates nothing, so it can be recorded into a HIP graph; every replay,
+    with eager work and synchronisation in between, reproduces the eager logits bit for bit (the forward path
+    has no atomics)."""
+    N, T, S = 2, 4, 64
+    table, flat, clips, P, state = setup(N, T, S, "bf16", g3=0.25)
+    d = B.R50Desc(N=N, T=T, size=S, num_classes=400, fold_div=8, lr=0.0, momentum=0.9, weight_decay=1e-4,
+                  bn_eps=1e-5, bn_momentum=0.1, dtype=B.TSM_BF16)
+    ws = workspace(B.tsm_resnet50_infer_workspace_bytes(d))
+    x = torch.from_numpy(clips).to(torch.bfloat16).cuda()
+    p, st = torch.from_numpy(flat).cuda(), torch.from_numpy(state).cuda()
+    logits = torch.empty((N, 400), dtype=torch.float32, device="cuda")
+    B.tsm_resnet50_infer(d, x, p, st, logits, ws)
+    torch.cuda.synchronize()
+    eager = logits.cpu().numpy().copy()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        B.tsm_resnet50_infer(d, x, p, st, logits, ws, torch.cuda.current_stream())
+    for i in range(3):
+        logits.fill_(float(i))          # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(logits.cpu().numpy(), eager), i
+    x2 = torch.from_numpy(I.clips(N, T, S, 7, "bf16")).to(torch.bfloat16).cuda()
+    x.copy_(x2)                          # new input in the same buffer: the replay follows it
+    g.replay()
+    torch.cuda.synchronize()
+    replayed = logits.cpu().numpy().copy()
+    B.tsm_resnet50_infer(d, x, p, st, logits, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(logits.cpu().numpy(), replayed)
+    assert not np.array_equal(replayed, eager)
