@@ -224,6 +224,25 @@ int tsm_resnet50_step(const tsm_r50_desc* d, const void* clips, const int32_t* l
                       float* grads_out, float* loss_out, float* logits_out,
                       int update, void* ws, size_t ws_bytes, void* stream);
 
+/* Gradient accumulation (the paper simulates node counts it could not run this way, section 5): one SGD
+ * update from micro_count calls, each a forward + backward pass over its own micro-batch (its BatchNorms
+ * normalise over its own N*T frames, running statistics are updated per call).  Call micro_index 0 overwrites
+ * grads_accum (fp32 [param_count], caller-owned, must stay untouched between the calls) with its gradients,
+ * later calls add theirs; the last call (micro_index == micro_count - 1) then applies the SGD update with
+ * grads_accum / micro_count, i.e. the mean gradient over all micro-batches, and desc.lr.
+ * Other arguments, workspace size and error behaviour as tsm_resnet50_step. */
+int tsm_resnet50_accum_step(const tsm_r50_desc* d, const void* clips, const int32_t* labels,
+                            float* params, float* momentum, float* bn_state,
+                            float* grads_accum, float* loss_out, float* logits_out,
+                            int micro_index, int micro_count, void* ws, size_t ws_bytes, void* stream);
+
+/* Host-side helper (no GPU work): learning rate of the paper's recipe (section 4.1) at a fractional epoch.
+ * 0.00125 per 8 samples scaled linearly with total_batch (eta = 0.00125 k for k GPUs of 8 clips); gradual
+ * warm-up over the first warmup_epochs (paper: 5), rising linearly from the rate of warm_batch samples (one
+ * GPU's batch, 8) to the full rate; then cosine decay reaching 0 at total_epochs (paper: 100).
+ * Returns -1 (and sets tsm_last_error) for invalid arguments. */
+double tsm_lr_schedule(double epoch, int total_batch, int warm_batch, double warmup_epochs, double total_epochs);
+
 /* Forward pass only, BatchNorm in inference mode (the way the paper measures single-GPU
  * throughput of the models: section 3a, Table 1, videos per second at batch 16).
  * Every BatchNorm uses the running statistics in bn_state (layout as above) instead of batch statistics:

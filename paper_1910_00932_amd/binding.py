@@ -24,7 +24,8 @@ EXPORTS = ["tsm_last_error", "tsm_profile_begin", "tsm_profile_end", "tsm_shift_
            "tsm_conv_dgrad", "tsm_conv_wgrad", "tsm_block_saved_bytes", "tsm_block_workspace_bytes",
            "tsm_block_fwd", "tsm_block_bwd", "tsm_resnet50_param_count", "tsm_resnet50_num_tensors",
            "tsm_resnet50_param_info", "tsm_resnet50_bn_state_count", "tsm_resnet50_workspace_bytes",
-           "tsm_resnet50_step", "tsm_resnet50_infer_workspace_bytes", "tsm_resnet50_infer"]
+           "tsm_resnet50_step", "tsm_resnet50_infer_workspace_bytes", "tsm_resnet50_infer",
+           "tsm_resnet50_accum_step", "tsm_lr_schedule"]
 
 
 class TsmError(RuntimeError):
@@ -100,6 +101,8 @@ def lib():
                                             ctypes.POINTER(ci), ctypes.POINTER(ci * 4), ctypes.POINTER(ci)])
         sig("tsm_resnet50_step", ci, [vp, vp, vp, vp, vp, vp, vp, vp, vp, ci, vp, sz, vp])
         sig("tsm_resnet50_infer", ci, [vp, vp, vp, vp, vp, vp, sz, vp])
+        sig("tsm_resnet50_accum_step", ci, [vp, vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, vp, sz, vp])
+        sig("tsm_lr_schedule", ctypes.c_double, [ctypes.c_double, ci, ci, ctypes.c_double, ctypes.c_double])
         _LIB = L
     return _LIB
 
@@ -256,3 +259,19 @@ def tsm_resnet50_infer(desc, clips, params, bn_state, logits_out, ws, stream=Non
     p, n = _ws(ws)
     _check(lib().tsm_resnet50_infer(ctypes.addressof(desc), _ptr(clips), _ptr(params), _ptr(bn_state),
                                     _ptr(logits_out), p, n, _stream(stream)))
+
+
+def tsm_resnet50_accum_step(desc, clips, labels, params, momentum, bn_state, grads_accum, loss_out, logits_out,
+                            micro_index, micro_count, ws, stream=None):
+    p, n = _ws(ws)
+    _check(lib().tsm_resnet50_accum_step(ctypes.addressof(desc), _ptr(clips), _ptr(labels), _ptr(params), _ptr(momentum),
+                                         _ptr(bn_state), _ptr(grads_accum), _ptr(loss_out), _ptr(logits_out),
+                                         int(micro_index), int(micro_count), p, n, _stream(stream)))
+
+
+def tsm_lr_schedule(epoch, total_batch, warm_batch=8, warmup_epochs=5.0, total_epochs=100.0):
+    v = float(lib().tsm_lr_schedule(float(epoch), int(total_batch), int(warm_batch), float(warmup_epochs),
+                                    float(total_epochs)))
+    if v < 0:
+        _check(-2)
+    return v

@@ -8,6 +8,7 @@
 // stream of kernel launches on the caller's stream, with no host synchronisation.
 #include <string.h>
 #include <algorithm>
+#include <cmath>
 #include <string>
 #include <vector>
 #include "block.h"
@@ -450,7 +451,7 @@ struct SgdSegments {
 
 __global__ void __launch_bounds__(256) sgd_kernel(float* __restrict__ w, float* __restrict__ v,
                                                   const float* __restrict__ g, long total, SgdSegments seg, float lr,
-                                                  float momentum, float wd) {
+                                                  float momentum, float wd, float gscale) {
     long i = (long)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
     int lo = 0, hi = seg.n - 1;
@@ -459,11 +460,25 @@ __global__ void __launch_bounds__(256) sgd_kernel(float* __restrict__ w, float* 
         if ((long)seg.start[mid] <= i) lo = mid; else hi = mid - 1;
     }
     const float wi = w[i];
-    const float gi = g[i] + (seg.decays[lo] ? wd * wi : 0.f);
+    const float gi = g[i] * gscale + (seg.decays[lo] ? wd * wi : 0.f);
     const float vi = fmaf(momentum, v[i], gi);
     v[i] = vi;
     w[i] = wi - lr * vi;
 }
+
+// Gradient accumulation over micro-batches: acc = g (first micro-batch) or acc += g.
+__global__ void __launch_bounds__(256) grad_accum_kernel(float* __restrict__ acc, const float* __restrict__ g, long n,
+                                                         int first) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    acc[i] = first ? g[i] : acc[i] + g[i];
+}
+
+// micro-batch `index` of `count` whose gradients are summed in `buf` (fp32 [param_count])
+struct GradAccum {
+    float* buf;
+    int index, count;
+};
 
 // ---- the step ---------------------------------------------------------------------------------
 #define RUN(expr)                          \
@@ -474,8 +489,8 @@ __global__ void __launch_bounds__(256) sgd_kernel(float* __restrict__ w, float* 
 
 static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* labels, float* params, float* momentum,
                     float* bn_state, float* grads_out, float* loss_out, float* logits_out, int update, void* wsp,
-                    size_t ws_bytes, bool dry, hipStream_t s, size_t* need) {
-    const char* who = "tsm_resnet50_step";
+                    size_t ws_bytes, bool dry, hipStream_t s, size_t* need, const GradAccum* acc = nullptr) {
+    const char* who = acc ? "tsm_resnet50_accum_step" : "tsm_resnet50_step";
     if (!d) return fail(TSM_ERR_NULLPTR, "%s: null descriptor", who);
     if (d->N <= 0 || d->T <= 0 || d->size < 32 || d->num_classes <= 0)
         return fail(TSM_ERR_SHAPE, "%s: N, T, num_classes must be positive and size >= 32", who);
@@ -776,6 +791,10 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
             RUN(conv_direct_wgrad(stem, dtype, x0, da0, G("conv1.w"), s));
     }
     // ================= update =================
+    if (acc && !dry) {
+        grad_accum_kernel<<<dim3(cdiv(nparams, 256)), dim3(256), 0, s>>>(acc->buf, grads, nparams, acc->index == 0);
+        LAUNCH_CHECK("grad_accum");
+    }
     if (update && !dry) {
         SgdSegments seg;
         seg.n = 0;
@@ -787,7 +806,9 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
                 ++seg.n;
             }
         }
-        sgd_kernel<<<dim3(cdiv(nparams, 256)), dim3(256), 0, s>>>(params, momentum, grads, nparams, seg, d->lr, d->momentum, d->weight_decay);
+        const float* gsrc = acc ? acc->buf : grads;
+        sgd_kernel<<<dim3(cdiv(nparams, 256)), dim3(256), 0, s>>>(params, momentum, gsrc, nparams, seg, d->lr, d->momentum,
+                                                                  d->weight_decay, acc ? 1.f / (float)acc->count : 1.f);
         LAUNCH_CHECK("sgd");
     }
     if (need) *need = A.used + scratch_need;
@@ -1091,6 +1112,32 @@ int tsm_resnet50_step(const tsm_r50_desc* d, const void* clips, const int32_t* l
                       size_t ws_bytes, void* stream) {
     return r50_step(d, clips, labels, params, momentum, bn_state, grads_out, loss_out, logits_out, update, ws, ws_bytes,
                     false, (hipStream_t)stream, nullptr);
+}
+
+int tsm_resnet50_accum_step(const tsm_r50_desc* d, const void* clips, const int32_t* labels, float* params,
+                            float* momentum, float* bn_state, float* grads_accum, float* loss_out, float* logits_out,
+                            int micro_index, int micro_count, void* ws, size_t ws_bytes, void* stream) {
+    if (micro_count <= 0 || micro_index < 0 || micro_index >= micro_count)
+        return fail(TSM_ERR_SHAPE, "tsm_resnet50_accum_step: micro_index %d outside [0, %d)", micro_index, micro_count);
+    if (!grads_accum) return fail(TSM_ERR_NULLPTR, "tsm_resnet50_accum_step: null accumulation buffer");
+    const GradAccum acc = {grads_accum, micro_index, micro_count};
+    return r50_step(d, clips, labels, params, momentum, bn_state, nullptr, loss_out, logits_out,
+                    micro_index == micro_count - 1, ws, ws_bytes, false, (hipStream_t)stream, nullptr, &acc);
+}
+
+// Host-side helper, no GPU work: learning rate of the training recipe at a (fractional) epoch.
+double tsm_lr_schedule(double epoch, int total_batch, int warm_batch, double warmup_epochs, double total_epochs) {
+    if (total_batch <= 0 || warm_batch <= 0 || !(warmup_epochs >= 0.0) || !(total_epochs > warmup_epochs) || !(epoch >= 0.0)) {
+        fail(TSM_ERR_SHAPE, "tsm_lr_schedule: invalid arguments");
+        return -1.0;
+    }
+    const double per_sample = 0.00125 / 8.0;                 // 0.00125 for every 8 samples, scaled linearly
+    const double peak = per_sample * total_batch;
+    const double start = per_sample * (warm_batch < total_batch ? warm_batch : total_batch);
+    if (epoch < warmup_epochs) return start + (peak - start) * (epoch / warmup_epochs);
+    if (epoch >= total_epochs) return 0.0;
+    const double phase = (epoch - warmup_epochs) / (total_epochs - warmup_epochs);
+    return 0.5 * peak * (1.0 + cos(3.14159265358979323846 * phase));
 }
 
 size_t tsm_resnet50_infer_workspace_bytes(const tsm_r50_desc* d) {

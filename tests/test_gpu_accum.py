@@ -1,0 +1,116 @@
+"""Gradient accumulation over micro-batches (section 5) through tsm_resnet50_accum_step against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tsm_oracle as O
+from paper_1910_00932_amd import binding as B
+from paper_1910_00932_amd import inputs as I
+from conftest import rel_l2
+from gpu_util import workspace
+
+pytestmark = pytest.mark.gpu
+
+
+def _params(seed=1, K=400):
+    table = B.tsm_resnet50_param_table(K)
+    flat = I.init_params([(n, s) for n, _, s, _ in table], seed)
+    rng = np.random.default_rng(5)
+    for name, off, shape, _ in table:
+        if len(shape) == 1 and name != "fc.b":
+            flat[off:off + shape[0]] += (0.1 * rng.standard_normal(shape[0])).astype(np.float32)
+    return table, flat
+
+
+def _run_accum(micro, T, S, dtype, flat, lr):
+    n = micro[0][0].shape[0]
+    d = B.R50Desc(N=n, T=T, size=S, num_classes=400, fold_div=8, lr=lr, momentum=0.9, weight_decay=1e-4, bn_eps=1e-5,
+                  bn_momentum=0.1, dtype=B.TSM_BF16 if dtype == "bf16" else B.TSM_F32)
+    ws = workspace(B.tsm_resnet50_workspace_bytes(d))
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    params = torch.from_numpy(flat).cuda()
+    mom = torch.zeros_like(params)
+    acc = torch.full_like(params, 123.0)          # stale contents: the first micro-batch must overwrite them
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    losses, snapshots = [], []
+    for i, (clips, labels) in enumerate(micro):
+        B.tsm_resnet50_accum_step(d, torch.from_numpy(clips).to(tdt).cuda(), torch.from_numpy(labels).cuda(), params, mom,
+                                  None, acc, loss, None, i, len(micro), ws)
+        torch.cuda.synchronize()
+        losses.append(float(loss.item()))
+        snapshots.append(params.cpu().numpy().copy())
+    return losses, acc.cpu().numpy(), snapshots, mom.cpu().numpy()
+
+
+def test_accum_fp32_against_oracle():
+    """Two micro-batches of one clip each, fp32: losses, mean gradient and the single update against the fp64 oracle.
+    Gradient tolerances as for the plain step (ReLU-mask flips move whole gradient tensors by 1e-3..1e-2)."""
+    T, S, lr = 4, 64, 0.01
+    table, flat = _params()
+    micro = [(I.clips(1, T, S, 0, "f32"), I.labels(1, 400, 2)), (I.clips(1, T, S, 1, "f32"), I.labels(1, 400, 3))]
+    losses, acc, snaps, mom = _run_accum(micro, T, S, "f32", flat, lr)
+    assert np.array_equal(snaps[0], flat)                 # no update before the last micro-batch
+    P = O.unflatten_params(flat.astype(np.float64))
+    V = {k: np.zeros_like(v) for k, v in P.items()}
+    ol, G, P2, V2 = O.resnet50_accum_step(P, V, [(c.astype(np.float64), l) for c, l in micro], lr)
+    assert np.allclose(losses, ol, rtol=1e-4)
+    num = den = 0.0
+    for name, off, shape, decays in table:
+        n = int(np.prod(shape))
+        g = acc[off:off + n] / 2.0
+        e = rel_l2(g, G[name])
+        assert e < 1e-1, (name, e)
+        num += np.sum((g.ravel() - G[name].ravel()) ** 2)
+        den += np.sum(G[name] ** 2)
+        # the update itself is exact arithmetic on the accumulated gradient: mean, decay on weights only
+        gg = g.astype(np.float64) + (1e-4 * flat[off:off + n] if decays else 0.0)
+        assert np.allclose(mom[off:off + n], gg, rtol=1e-5, atol=1e-9), name
+        assert np.allclose(snaps[1][off:off + n], flat[off:off + n] - lr * gg, rtol=1e-6, atol=1e-8), name
+    assert np.sqrt(num / den) < 5e-2
+
+
+def test_accum_bf16_sums_the_micro_batch_gradients():
+    """bf16: the accumulation buffer holds the sum of the gradients that plain backward-only steps return for
+    the same micro-batches (same kernels; differences only from the order of the atomic sums), and k identical
+    micro-batches give the update of one plain step."""
+    T, S, lr = 4, 64, 0.01
+    table, flat = _params()
+    micro = [(I.clips(2, T, S, 0, "bf16"), I.labels(2, 400, 2)), (I.clips(2, T, S, 1, "bf16"), I.labels(2, 400, 3)),
+             (I.clips(2, T, S, 2, "bf16"), I.labels(2, 400, 4))]
+    losses, acc, snaps, mom = _run_accum(micro, T, S, "bf16", flat, lr)
+    d = B.R50Desc(N=2, T=T, size=S, num_classes=400, fold_div=8, lr=lr, momentum=0.9, weight_decay=1e-4, bn_eps=1e-5,
+                  bn_momentum=0.1, dtype=B.TSM_BF16)
+    ws = workspace(B.tsm_resnet50_workspace_bytes(d))
+    total = np.zeros(len(flat), dtype=np.float64)
+    for clips, labels in micro:
+        params = torch.from_numpy(flat).cuda()
+        grads = torch.empty_like(params)
+        loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+        B.tsm_resnet50_step(d, torch.from_numpy(clips).to(torch.bfloat16).cuda(), torch.from_numpy(labels).cuda(), params,
+                            torch.zeros_like(params), None, grads, loss, None, 0, ws)
+        torch.cuda.synchronize()
+        total += grads.cpu().numpy()
+    assert rel_l2(acc, total) < 1e-5, rel_l2(acc, total)
+    same = [micro[0]] * 2
+    _, acc2, snaps2, _ = _run_accum(same, T, S, "bf16", flat, lr)
+    params = torch.from_numpy(flat).cuda()
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    B.tsm_resnet50_step(d, torch.from_numpy(micro[0][0]).to(torch.bfloat16).cuda(), torch.from_numpy(micro[0][1]).cuda(),
+                        params, torch.zeros_like(params), None, None, loss, None, 1, ws)
+    torch.cuda.synchronize()
+    assert rel_l2(snaps2[1] - flat, params.cpu().numpy() - flat) < 1e-4
+
+
+def test_accum_rejects_bad_arguments():
+    table, flat = _params()
+    d = B.R50Desc(N=1, T=2, size=32, num_classes=400, fold_div=8, lr=0.01, momentum=0.9, weight_decay=1e-4, bn_eps=1e-5,
+                  bn_momentum=0.1, dtype=B.TSM_BF16)
+    ws = workspace(B.tsm_resnet50_workspace_bytes(d))
+    params = torch.from_numpy(flat).cuda()
+    x = torch.from_numpy(I.clips(1, 2, 32, 0, "bf16")).to(torch.bfloat16).cuda()
+    y = torch.from_numpy(I.labels(1)).cuda()
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    for idx, cnt, acc in ((2, 2, torch.empty_like(params)), (-1, 2, torch.empty_like(params)), (0, 0, torch.empty_like(params)),
+                          (0, 2, None)):
+        with pytest.raises(B.TsmError):
+            B.tsm_resnet50_accum_step(d, x, y, params, torch.zeros_like(params), None, acc, loss, None, idx, cnt, ws)
