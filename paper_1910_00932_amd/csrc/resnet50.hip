@@ -275,69 +275,96 @@ __global__ void __launch_bounds__(256) stem_pool_bwd_kernel(const T* __restrict_
 // ---- head: global average pool + temporal consensus + linear + softmax cross-entropy ---------
 // The consensus (mean over T of the per-frame linear outputs) is an affine map, so the
 // mean over frames and pixels is taken first: pm[n][c] = mean_{t,h,w} feat[n,t,h,w,c].
+// Block = 32 channel vectors x 8 row lanes: 16-byte loads, the eight row lanes meet in LDS in a fixed order.
 template <typename T>
 __global__ void __launch_bounds__(256) pool_mean_kernel(const T* __restrict__ feat, float* __restrict__ pm,
                                                         int rows_per_clip, int C) {
+    constexpr int V = Elem<T>::VEC;
+    __shared__ float red[8][32 * V];
     const int n = blockIdx.y;
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= C) return;
-    const T* p = feat + (long)n * rows_per_clip * C + c;
-    float s = 0.f;
-    for (int r = 0; r < rows_per_clip; ++r) s += Elem<T>::ld(p[(long)r * C]);
-    pm[(long)n * C + c] = s / (float)rows_per_clip;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int c0 = (blockIdx.x * 32 + tx) * V;
+    float acc[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) acc[j] = 0.f;
+    if (c0 < C) {
+        const T* p = feat + (long)n * rows_per_clip * C + c0;
+        for (int r = ty; r < rows_per_clip; r += 8) {
+            const Vec16<T> v = *(const Vec16<T>*)(p + (long)r * C);
+#pragma unroll
+            for (int j = 0; j < V; ++j) acc[j] += Elem<T>::ld(v.v[j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < V; ++j) red[ty][tx * V + j] = acc[j];
+    __syncthreads();
+    const int col = threadIdx.x;
+    if (col < 32 * V && blockIdx.x * 32 * V + col < C) {
+        float t = 0.f;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) t += red[r][col];
+        pm[(long)n * C + blockIdx.x * 32 * V + col] = t / (float)rows_per_clip;
+    }
 }
 
-// logits[n][k] = b[k] + sum_c W[k][c] * pm[n][c]; one block per class k.
+// logits[n][k] = b[k] + sum_c W[k][c] * pm[n][c]; one block per class k whose weight row stays in registers
+// (up to 64 * FC_WREG input channels, more fall back to re-reading), one wavefront per clip at a time.
+static constexpr int FC_WREG = 32;
 __global__ void __launch_bounds__(256) fc_fwd_kernel(const float* __restrict__ pm, const float* __restrict__ W,
                                                      const float* __restrict__ b, float* __restrict__ logits, int N,
                                                      int C, int K) {
-    __shared__ float red[4];
     const int k = blockIdx.x;
-    for (int n = 0; n < N; ++n) {
-        float s = 0.f;
-        for (int c = threadIdx.x; c < C; c += 256) s = fmaf(W[(long)k * C + c], pm[(long)n * C + c], s);
+    const int lane = threadIdx.x & 63;
+    const float* w = W + (long)k * C;
+    float wr[FC_WREG];
+#pragma unroll
+    for (int j = 0; j < FC_WREG; ++j) wr[j] = lane + 64 * j < C ? w[lane + 64 * j] : 0.f;
+    const float bias = b[k];
+    for (int n = threadIdx.x >> 6; n < N; n += 4) {
+        const float* x = pm + (long)n * C;
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int j = 0; j < FC_WREG; j += 2) {
+            s0 = fmaf(wr[j], lane + 64 * j < C ? x[lane + 64 * j] : 0.f, s0);
+            s1 = fmaf(wr[j + 1], lane + 64 * (j + 1) < C ? x[lane + 64 * (j + 1)] : 0.f, s1);
+        }
+        for (int c = lane + 64 * FC_WREG; c < C; c += 64) s0 = fmaf(w[c], x[c], s0);
+        float s = s0 + s1;
         for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o, 64);
-        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
-        __syncthreads();
-        if (threadIdx.x == 0) logits[(long)n * K + k] = red[0] + red[1] + red[2] + red[3] + b[k];
-        __syncthreads();
+        if (lane == 0) logits[(long)n * K + k] = s + bias;
     }
 }
 
-// One block; loss = -mean_n log softmax(logits[n])[label[n]]; dlogits = (softmax - onehot)/N.
-__global__ void __launch_bounds__(256) softmax_ce_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
-                                                         float* __restrict__ dlogits, float* __restrict__ loss, int N,
-                                                         int K) {
-    __shared__ float red[4];
-    __shared__ float bcast;
+// One block of 16 wavefronts, one wavefront per clip at a time; loss = -mean_n log softmax(logits[n])[label[n]];
+// dlogits = (softmax - onehot)/N.  The per-wavefront loss sums meet in LDS in a fixed order.
+__global__ void __launch_bounds__(1024) softmax_ce_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
+                                                          float* __restrict__ dlogits, float* __restrict__ loss, int N,
+                                                          int K) {
+    __shared__ float red[16];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     float total = 0.f;
-    for (int n = 0; n < N; ++n) {
+    for (int n = wv; n < N; n += 16) {
         const float* z = logits + (long)n * K;
         float mx = -3.0e38f;
-        for (int k = threadIdx.x; k < K; k += 256) mx = fmaxf(mx, z[k]);
-        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_down(mx, o, 64));
-        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
-        __syncthreads();
-        if (threadIdx.x == 0) bcast = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-        __syncthreads();
-        mx = bcast;
+        for (int k = lane; k < K; k += 64) mx = fmaxf(mx, z[k]);
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
         float s = 0.f;
-        for (int k = threadIdx.x; k < K; k += 256) s += expf(z[k] - mx);
-        for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o, 64);
-        __syncthreads();
-        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
-        __syncthreads();
-        if (threadIdx.x == 0) bcast = red[0] + red[1] + red[2] + red[3];
-        __syncthreads();
-        const float lse = mx + logf(bcast);
+        for (int k = lane; k < K; k += 64) s += expf(z[k] - mx);
+        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+        const float lse = mx + logf(s);
         int lab = labels[n];
         if (lab < 0 || lab >= K) lab = 0;   // out-of-range labels are treated as class 0
-        for (int k = threadIdx.x; k < K; k += 256)
+        for (int k = lane; k < K; k += 64)
             dlogits[(long)n * K + k] = (expf(z[k] - lse) - (k == lab ? 1.f : 0.f)) / (float)N;
         total += lse - z[lab];
-        __syncthreads();
     }
-    if (threadIdx.x == 0) *loss = total / (float)N;
+    if (lane == 0) red[wv] = total;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.f;
+        for (int i = 0; i < 16; ++i) t += red[i];
+        *loss = t / (float)N;
+    }
 }
 
 // dW[k][c] = sum_n dlogits[n][k]*pm[n][c]; db[k] = sum_n dlogits[n][k]
@@ -358,26 +385,54 @@ __global__ void __launch_bounds__(256) fc_bwd_w_kernel(const float* __restrict__
     }
 }
 
-// dpm[n][c] = sum_k dlogits[n][k]*W[k][c]
-__global__ void __launch_bounds__(256) fc_bwd_x_kernel(const float* __restrict__ dlogits, const float* __restrict__ W,
-                                                       float* __restrict__ dpm, int C, int K) {
-    const int n = blockIdx.y;
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= C) return;
-    float s = 0.f;
-    for (int k = 0; k < K; ++k) s = fmaf(dlogits[(long)n * K + k], W[(long)k * C + c], s);
-    dpm[(long)n * C + c] = s;
+// dpm[n][c] = sum_k dlogits[n][k]*W[k][c]; block = 64 channels x 16 slices of the classes, eight clips per
+// weight read; the slices meet in LDS in a fixed order.
+__global__ void __launch_bounds__(1024) fc_bwd_x_kernel(const float* __restrict__ dlogits, const float* __restrict__ W,
+                                                        float* __restrict__ dpm, int N, int C, int K) {
+    __shared__ float red[16][8][64];
+    const int n0 = blockIdx.y * 8;
+    const int tx = threadIdx.x & 63, sl = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + tx;
+    const float* dl[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) dl[j] = dlogits + (long)(n0 + j < N ? n0 + j : N - 1) * K;
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+    if (c < C) {
+        for (int k = sl; k < K; k += 16) {
+            const float w = W[(long)k * C + c];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = fmaf(dl[j][k], w, acc[j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) red[sl][j][tx] = acc[j];
+    __syncthreads();
+    if (threadIdx.x < 512) {
+        const int j = threadIdx.x >> 6;
+        float t = 0.f;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) t += red[q][j][tx];
+        if (c < C && n0 + j < N) dpm[(long)(n0 + j) * C + c] = t;
+    }
 }
 
-// dfeat[n][r][c] = dpm[n][c] / rows_per_clip
+// dfeat[n][r][c] = dpm[n][c] / rows_per_clip; one 16-byte vector per thread (C is a multiple of the vector width)
 template <typename T>
 __global__ void __launch_bounds__(256) pool_mean_bwd_kernel(const float* __restrict__ dpm, T* __restrict__ dfeat,
-                                                            int rows_per_clip, int C, long total) {
-    long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= total) return;
-    const int c = (int)(i % C);
-    const long n = i / ((long)rows_per_clip * C);
-    dfeat[i] = Elem<T>::st(dpm[n * C + c] / (float)rows_per_clip);
+                                                            int rows_per_clip, int C, long total_vec) {
+    constexpr int V = Elem<T>::VEC;
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total_vec) return;
+    const int cv = C / V;
+    const int c0 = (int)(i % cv) * V;
+    const long n = i / ((long)rows_per_clip * cv);
+    const float inv = 1.f / (float)rows_per_clip;
+    Vec16<T> o;
+#pragma unroll
+    for (int j = 0; j < V; ++j) o.v[j] = Elem<T>::st(dpm[n * C + c0 + j] * inv);
+    *(Vec16<T>*)(dfeat + i * V) = o;
 }
 
 // ---- bf16 working copies of all convolution weights, one launch per packing ---------------------
@@ -389,6 +444,8 @@ struct PackTable {
     unsigned in_off[55];      // element offset into the fp32 parameter vector
     unsigned out_off[55];     // bf16 element offset from the output base
     unsigned short cout[55], cin[55], cinp[55], k[55];
+    unsigned tstart[56];      // first 64 x 64 (Cout x Cin) tile of entry l, for pack_tiles_kernel; tiled == 0 if any
+    int tiled;                // entry has a channel count that is not a multiple of 64 or padded input channels
 };
 
 __global__ void __launch_bounds__(256) pack_all_kernel(PackTable t, const float* __restrict__ params,
@@ -413,6 +470,48 @@ __global__ void __launch_bounds__(256) pack_all_kernel(PackTable t, const float*
         v = w[((size_t)co * Cin + ci) * taps + kh * K + kw];
     }
     out[(size_t)t.out_off[lo] + e] = f32_to_bf16(v);
+}
+
+// Same packings, both from one read of the fp32 weights, for tables whose channel counts are all multiples of 64:
+// a block converts one 64 x 64 (Cout x Cin) tile of one convolution tap by tap; the forward order is written
+// as read (input channels innermost), the data-gradient order (output channels innermost, taps flipped) goes
+// through an LDS transpose.  `td` may equal `tf` when with_dgrad == 0.
+__global__ void __launch_bounds__(256) pack_tiles_kernel(PackTable tf, PackTable td, const float* __restrict__ params,
+                                                         bf16_t* __restrict__ out, int with_dgrad) {
+    __shared__ bf16_t tile[64][66];
+    const unsigned b = blockIdx.x;
+    int lo = 0, hi = tf.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (tf.tstart[mid] <= b) lo = mid; else hi = mid - 1;
+    }
+    const unsigned e = b - tf.tstart[lo];
+    const int Cout = tf.cout[lo], Cin = tf.cin[lo], taps = tf.k[lo] * tf.k[lo];
+    const int tiles_ci = Cin / 64;
+    const int co0 = (int)(e / tiles_ci) * 64, ci0 = (int)(e % tiles_ci) * 64;
+    const float* w = params + tf.in_off[lo];
+    bf16_t* of = out + tf.out_off[lo];
+    bf16_t* od = out + td.out_off[lo];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int tap = 0; tap < taps; ++tap) {
+#pragma unroll 4
+        for (int r = 0; r < 16; ++r) {
+            const int co = r * 4 + ty;
+            const bf16_t v = f32_to_bf16(w[((size_t)(co0 + co) * Cin + ci0 + tx) * taps + tap]);
+            of[((size_t)(co0 + co) * taps + tap) * Cin + ci0 + tx] = v;
+            if (with_dgrad) tile[co][tx] = v;
+        }
+        if (with_dgrad) {
+            __syncthreads();
+            const int ftap = taps - 1 - tap;
+#pragma unroll 4
+            for (int r = 0; r < 16; ++r) {
+                const int ci = r * 4 + ty;
+                od[((size_t)(ci0 + ci) * taps + ftap) * Cout + co0 + tx] = tile[tx][ci];
+            }
+            __syncthreads();
+        }
+    }
 }
 
 // ---- inference-mode BatchNorm parameters of the whole network in one launch ---------------------
@@ -449,21 +548,42 @@ struct SgdSegments {
     unsigned char decays[120];
 };
 
-__global__ void __launch_bounds__(256) sgd_kernel(float* __restrict__ w, float* __restrict__ v,
-                                                  const float* __restrict__ g, long total, SgdSegments seg, float lr,
-                                                  float momentum, float wd, float gscale) {
-    long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= total) return;
+__device__ __forceinline__ int sgd_segment(const SgdSegments& seg, long i) {
     int lo = 0, hi = seg.n - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
         if ((long)seg.start[mid] <= i) lo = mid; else hi = mid - 1;
     }
-    const float wi = w[i];
-    const float gi = g[i] * gscale + (seg.decays[lo] ? wd * wi : 0.f);
-    const float vi = fmaf(momentum, v[i], gi);
-    v[i] = vi;
-    w[i] = wi - lr * vi;
+    return lo;
+}
+
+// Four parameters per thread (16-byte accesses) where they lie in one segment, one at a time across a boundary.
+__global__ void __launch_bounds__(256) sgd_kernel(float* __restrict__ w, float* __restrict__ v,
+                                                  const float* __restrict__ g, long total, SgdSegments seg, float lr,
+                                                  float momentum, float wd, float gscale) {
+    const long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= total) return;
+    const int lo = sgd_segment(seg, i);
+    if (i + 3 < total && (lo == seg.n - 1 || (long)seg.start[lo + 1] > i + 3)) {
+        const float dec = seg.decays[lo] ? wd : 0.f;
+        float4 wi = *(const float4*)(w + i), vi = *(const float4*)(v + i);
+        const float4 gi = *(const float4*)(g + i);
+        vi.x = fmaf(momentum, vi.x, gi.x * gscale + dec * wi.x);
+        vi.y = fmaf(momentum, vi.y, gi.y * gscale + dec * wi.y);
+        vi.z = fmaf(momentum, vi.z, gi.z * gscale + dec * wi.z);
+        vi.w = fmaf(momentum, vi.w, gi.w * gscale + dec * wi.w);
+        wi.x -= lr * vi.x; wi.y -= lr * vi.y; wi.z -= lr * vi.z; wi.w -= lr * vi.w;
+        *(float4*)(v + i) = vi;
+        *(float4*)(w + i) = wi;
+        return;
+    }
+    for (long e = i; e < i + 4 && e < total; ++e) {
+        const float we = w[e];
+        const float ge = g[e] * gscale + (seg.decays[sgd_segment(seg, e)] ? wd * we : 0.f);
+        const float ve = fmaf(momentum, v[e], ge);
+        v[e] = ve;
+        w[e] = we - lr * ve;
+    }
 }
 
 // Gradient accumulation over micro-batches: acc = g (first micro-batch) or acc += g.
@@ -543,6 +663,8 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
     PackTable pk_fwd, pk_dg;
     pk_fwd.n = pk_dg.n = 0;
     pk_fwd.start[0] = pk_dg.start[0] = 0;
+    pk_fwd.tstart[0] = pk_dg.tstart[0] = 0;
+    pk_fwd.tiled = pk_dg.tiled = 1;
     bf16_t* const pack_base = (bf16_t*)(dry ? nullptr : wsp);   // packed buffers are addressed relative to the workspace
     auto pack_entry = [&](PackTable& t, const std::string& name, int Cout, int Cin, int k, int CinP, size_t count,
                           const bf16_t* dst) {
@@ -552,6 +674,8 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
         t.cout[l] = (unsigned short)Cout; t.cin[l] = (unsigned short)Cin; t.cinp[l] = (unsigned short)CinP;
         t.k[l] = (unsigned short)k;
         t.start[l + 1] = t.start[l] + (unsigned)count;
+        t.tstart[l + 1] = t.tstart[l] + (unsigned)((Cout / 64) * (Cin / 64));
+        if (Cout % 64 || Cin % 64 || CinP != Cin) t.tiled = 0;
     };
     auto pack_conv = [&](const std::string& name, int Cout, int Cin, int k, int CinP, const bf16_t** wp,
                          const bf16_t** wd) -> int {
@@ -685,11 +809,16 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
 
     // every weight gradient is accumulated with atomics: one fill for the whole gradient vector
     RUN(fill_zero(grads, (size_t)nparams * sizeof(float), s));
-    if (bf && !dry) {   // bf16 working copies of all convolution weights: two launches
-        pack_all_kernel<<<dim3(cdiv(pk_fwd.start[pk_fwd.n], 256)), dim3(256), 0, s>>>(pk_fwd, params, pack_base, 0);
-        LAUNCH_CHECK("pack_weights_fwd");
-        pack_all_kernel<<<dim3(cdiv(pk_dg.start[pk_dg.n], 256)), dim3(256), 0, s>>>(pk_dg, params, pack_base, 1);
-        LAUNCH_CHECK("pack_weights_dgrad");
+    if (bf && !dry) {   // bf16 working copies of all convolution weights in both packings
+        if (pk_fwd.tiled && pk_dg.tiled && pk_fwd.n == pk_dg.n) {
+            pack_tiles_kernel<<<dim3(pk_fwd.tstart[pk_fwd.n]), dim3(256), 0, s>>>(pk_fwd, pk_dg, params, pack_base, 1);
+            LAUNCH_CHECK("pack_weights");
+        } else {
+            pack_all_kernel<<<dim3(cdiv(pk_fwd.start[pk_fwd.n], 256)), dim3(256), 0, s>>>(pk_fwd, params, pack_base, 0);
+            LAUNCH_CHECK("pack_weights_fwd");
+            pack_all_kernel<<<dim3(cdiv(pk_dg.start[pk_dg.n], 256)), dim3(256), 0, s>>>(pk_dg, params, pack_base, 1);
+            LAUNCH_CHECK("pack_weights_dgrad");
+        }
     }
 
     // ================= forward =================
@@ -732,22 +861,22 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
         if (bf)
             pool_mean_kernel<bf16_t><<<dim3(cdiv(Cf, 256), d->N), dim3(256), 0, s>>>((const bf16_t*)blks.back().out, pm, rows_clip, Cf);
         else
-            pool_mean_kernel<float><<<dim3(cdiv(Cf, 256), d->N), dim3(256), 0, s>>>((const float*)blks.back().out, pm, rows_clip, Cf);
+            pool_mean_kernel<float><<<dim3(cdiv(Cf, 128), d->N), dim3(256), 0, s>>>((const float*)blks.back().out, pm, rows_clip, Cf);
         LAUNCH_CHECK("pool_mean");
         fc_fwd_kernel<<<dim3(K), dim3(256), 0, s>>>(pm, P("fc.w"), P("fc.b"), logits, d->N, Cf, K);
         LAUNCH_CHECK("fc_fwd");
-        softmax_ce_kernel<<<dim3(1), dim3(256), 0, s>>>(logits, labels, dlogits, loss_out, d->N, K);
+        softmax_ce_kernel<<<dim3(1), dim3(1024), 0, s>>>(logits, labels, dlogits, loss_out, d->N, K);
         LAUNCH_CHECK("softmax_ce");
         // ================= backward =================
         fc_bwd_w_kernel<<<dim3(cdiv(Cf, 256), K), dim3(256), 0, s>>>(dlogits, pm, G("fc.w"), G("fc.b"), d->N, Cf, K);
         LAUNCH_CHECK("fc_bwd_w");
-        fc_bwd_x_kernel<<<dim3(cdiv(Cf, 256), d->N), dim3(256), 0, s>>>(dlogits, P("fc.w"), dpm, Cf, K);
+        fc_bwd_x_kernel<<<dim3(cdiv(Cf, 64), cdiv(d->N, 8)), dim3(1024), 0, s>>>(dlogits, P("fc.w"), dpm, d->N, Cf, K);
         LAUNCH_CHECK("fc_bwd_x");
         const long ftotal = (long)d->N * rows_clip * Cf;
         if (bf)
-            pool_mean_bwd_kernel<bf16_t><<<dim3(cdiv(ftotal, 256)), dim3(256), 0, s>>>(dpm, (bf16_t*)dbuf[0], rows_clip, Cf, ftotal);
+            pool_mean_bwd_kernel<bf16_t><<<dim3(cdiv(ftotal / 8, 256)), dim3(256), 0, s>>>(dpm, (bf16_t*)dbuf[0], rows_clip, Cf, ftotal / 8);
         else
-            pool_mean_bwd_kernel<float><<<dim3(cdiv(ftotal, 256)), dim3(256), 0, s>>>(dpm, (float*)dbuf[0], rows_clip, Cf, ftotal);
+            pool_mean_bwd_kernel<float><<<dim3(cdiv(ftotal / 4, 256)), dim3(256), 0, s>>>(dpm, (float*)dbuf[0], rows_clip, Cf, ftotal / 4);
         LAUNCH_CHECK("pool_mean_bwd");
     }
     int cur = 0;
@@ -807,7 +936,7 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
             }
         }
         const float* gsrc = acc ? acc->buf : grads;
-        sgd_kernel<<<dim3(cdiv(nparams, 256)), dim3(256), 0, s>>>(params, momentum, gsrc, nparams, seg, d->lr, d->momentum,
+        sgd_kernel<<<dim3(cdiv(nparams, 1024)), dim3(256), 0, s>>>(params, momentum, gsrc, nparams, seg, d->lr, d->momentum,
                                                                   d->weight_decay, acc ? 1.f / (float)acc->count : 1.f);
         LAUNCH_CHECK("sgd");
     }
@@ -887,6 +1016,8 @@ static int r50_infer(const tsm_r50_desc* d, const void* clips, const float* para
     PackTable pk;
     pk.n = 0;
     pk.start[0] = 0;
+    pk.tstart[0] = 0;
+    pk.tiled = 1;
     bf16_t* const pack_base = (bf16_t*)(dry ? nullptr : wsp);
     auto pack_conv = [&](const std::string& name, int Cout, int Cin, int k, const bf16_t** wp) -> int {
         *wp = nullptr;
@@ -900,6 +1031,8 @@ static int r50_infer(const tsm_r50_desc* d, const void* clips, const float* para
         pk.cout[l] = (unsigned short)Cout; pk.cin[l] = (unsigned short)Cin; pk.cinp[l] = (unsigned short)Cin;
         pk.k[l] = (unsigned short)k;
         pk.start[l + 1] = pk.start[l] + (unsigned)nf;
+        pk.tstart[l + 1] = pk.tstart[l] + (unsigned)((Cout / 64) * (Cin / 64));
+        if (Cout % 64 || Cin % 64) pk.tiled = 0;
         *wp = a;
         return TSM_OK;
     };
@@ -997,7 +1130,10 @@ static int r50_infer(const tsm_r50_desc* d, const void* clips, const float* para
         bn_eval_params_kernel<<<dim3(cdiv(nch, 256)), dim3(256), 0, s>>>(bt, params, bn_state, d->bn_eps, scale_all, shift_all);
         LAUNCH_CHECK("bn_eval_params");
         if (bf) {
-            pack_all_kernel<<<dim3(cdiv(pk.start[pk.n], 256)), dim3(256), 0, s>>>(pk, params, pack_base, 0);
+            if (pk.tiled)
+                pack_tiles_kernel<<<dim3(pk.tstart[pk.n]), dim3(256), 0, s>>>(pk, pk, params, pack_base, 0);
+            else
+                pack_all_kernel<<<dim3(cdiv(pk.start[pk.n], 256)), dim3(256), 0, s>>>(pk, params, pack_base, 0);
             LAUNCH_CHECK("pack_weights_fwd");
             const long total = (long)F * Hs * Hs;
             clips_to_s2d_kernel<<<dim3(cdiv(total, 256)), dim3(256), 0, s>>>((const bf16_t*)clips, (uint4*)x0, S, Hs, total);
@@ -1056,7 +1192,7 @@ static int r50_infer(const tsm_r50_desc* d, const void* clips, const float* para
         if (bf)
             pool_mean_kernel<bf16_t><<<dim3(cdiv(Cf, 256), d->N), dim3(256), 0, s>>>((const bf16_t*)cur, pm, rows_clip, Cf);
         else
-            pool_mean_kernel<float><<<dim3(cdiv(Cf, 256), d->N), dim3(256), 0, s>>>((const float*)cur, pm, rows_clip, Cf);
+            pool_mean_kernel<float><<<dim3(cdiv(Cf, 128), d->N), dim3(256), 0, s>>>((const float*)cur, pm, rows_clip, Cf);
         LAUNCH_CHECK("pool_mean");
         fc_fwd_kernel<<<dim3(K), dim3(256), 0, s>>>(pm, P("fc.w"), P("fc.b"), logits_out, d->N, Cf, K);
         LAUNCH_CHECK("fc_fwd");
@@ -1120,6 +1256,7 @@ int tsm_resnet50_accum_step(const tsm_r50_desc* d, const void* clips, const int3
     if (micro_count <= 0 || micro_index < 0 || micro_index >= micro_count)
         return fail(TSM_ERR_SHAPE, "tsm_resnet50_accum_step: micro_index %d outside [0, %d)", micro_index, micro_count);
     if (!grads_accum) return fail(TSM_ERR_NULLPTR, "tsm_resnet50_accum_step: null accumulation buffer");
+    if (!aligned16(grads_accum)) return fail(TSM_ERR_ALIGN, "tsm_resnet50_accum_step: accumulation buffer must be 16-byte aligned");
     const GradAccum acc = {grads_accum, micro_index, micro_count};
     return r50_step(d, clips, labels, params, momentum, bn_state, nullptr, loss_out, logits_out,
                     micro_index == micro_count - 1, ws, ws_bytes, false, (hipStream_t)stream, nullptr, &acc);
