@@ -78,10 +78,15 @@ int run_conv_dgrad(const ConvP& p, int dtype, const void* dy, const void* w, con
     return TSM_OK;
 }
 
-int run_conv_wgrad(const ConvP& p, int dtype, const void* x, const void* dy, float* dw, int accumulate, Arena& ws,
-                   bool dry, hipStream_t s) {
+int run_conv_wgrad(const ConvP& p, int dtype, const void* x, const void* dy, float* dw, float* dwp_zeroed, int accumulate,
+                   Arena& ws, bool dry, hipStream_t s) {
     // all kernels add with atomics; "accumulate" skips the zero fill of dw
     const size_t n = (size_t)p.Cout * p.K();
+    if (use_mfma(p, dtype) && p.taps() > 1 && dwp_zeroed) {
+        // the caller owns a zeroed packed buffer and permutes it into dw later (one fill / one permutation per step)
+        RUN(conv_mfma_wgrad(p, (const bf16_t*)x, (const bf16_t*)dy, dwp_zeroed, p.Cin, true, s));
+        return TSM_OK;
+    }
     if (use_mfma(p, dtype) && p.taps() > 1) {
         // several taps: accumulate in the packed order (contiguous atomics), then permute into dw
         float* dwp = ws.take_n<float>(n);
@@ -158,7 +163,7 @@ static int conv_entry(int which, const tsm_conv_desc* d, const void* a0, const v
             x = xt;
             dy = dyt;
         }
-        TSM_TRY(run_conv_wgrad(p, d->dtype, x, dy, (float*)out, accumulate, ws, dry, s));
+        TSM_TRY(run_conv_wgrad(p, d->dtype, x, dy, (float*)out, nullptr, accumulate, ws, dry, s));
     }
     if (need) *need = ws.used;
     return TSM_OK;
@@ -252,7 +257,7 @@ int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dou
     for (int i = L; i >= 1; --i) {
         StageDef& st = b.st[i];
         const ConvP& pp = b.st[i - 1].p;  // producer of this stage's input
-        TSM_TRY(run_conv_wgrad(st.p, b.dtype, b.z[i - 1], g, st.dw, acc_flag, ws, dry, s));
+        TSM_TRY(run_conv_wgrad(st.p, b.dtype, b.z[i - 1], g, st.dw, st.dwp, acc_flag, ws, dry, s));
         void* dzin = ws.take((size_t)pp.rows_out() * pp.Cout * es);
         // the ReLU mask and the BatchNorm reductions of the producing stage ride in the data gradient's
         // epilogue when its kernel can do that; otherwise they are a pass of their own
@@ -273,7 +278,7 @@ int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dou
         RUN(bn_bwd_apply(b.dtype, dzin, b.y[i - 1], pp.rows_out(), pp.Cout, coef, dzin, s));
         g = dzin;
     }
-    TSM_TRY(run_conv_wgrad(b.st[0].p, b.dtype, x, g, b.st[0].dw, acc_flag, ws, dry, s));
+    TSM_TRY(run_conv_wgrad(b.st[0].p, b.dtype, x, g, b.st[0].dw, b.st[0].dwp, acc_flag, ws, dry, s));
     const void* addend = dzL;
     if (b.proj) {
         StageDef& st = b.ds;
@@ -281,7 +286,7 @@ int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dou
         float* coefd = ws.take_n<float>(3 * (size_t)pl.Cout);
         RUN(bn_bwd_coeffs(partd, nbL, pl.rows_out(), pl.Cout, b.bnd.mean, b.bnd.rstd, st.g, coefd, st.dg, st.db, s));
         RUN(bn_bwd_apply(b.dtype, dzL, b.yd, pl.rows_out(), pl.Cout, coefd, dyd, s));
-        TSM_TRY(run_conv_wgrad(st.p, b.dtype, x, dyd, st.dw, acc_flag, ws, dry, s));
+        TSM_TRY(run_conv_wgrad(st.p, b.dtype, x, dyd, st.dw, st.dwp, acc_flag, ws, dry, s));
         void* dsc = ws.take((size_t)st.p.rows_in() * st.p.Cin * es);
         TSM_TRY(run_conv_dgrad(st.p, b.dtype, dyd, st.w, st.wd, dsc, nullptr, nullptr, ws, dry, s));
         addend = dsc;

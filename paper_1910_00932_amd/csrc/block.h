@@ -13,6 +13,8 @@ struct StageDef {
     const float *g, *b;   // BatchNorm scale / offset
     float *dw, *dg, *db;  // gradients (fp32)
     float *run_mean, *run_var;  // optional running statistics
+    float* dwp = nullptr;  // optional zeroed buffer [Cout][taps][Cin] that receives the weight gradient of a several-tap
+                           // convolution in the packed order; the caller permutes it into dw afterwards
 };
 
 struct BlockPlan {
@@ -44,7 +46,7 @@ int run_conv_fwd(const ConvP& p, int dtype, const void* x, const void* w, const 
 int conv_dgrad_fuse_blocks(const ConvP& p, int dtype);
 int run_conv_dgrad(const ConvP& p, int dtype, const void* dy, const void* w, const bf16_t* wd, void* dx,
                    const void* addend, const DgradFuse* fuse, Arena& ws, bool dry, hipStream_t s);
-int run_conv_wgrad(const ConvP& p, int dtype, const void* x, const void* dy, float* dw, int accumulate, Arena& ws,
+int run_conv_wgrad(const ConvP& p, int dtype, const void* x, const void* dy, float* dw, float* dwp, int accumulate, Arena& ws,
                    bool dry, hipStream_t s);
 
 int make_block_plan(const tsm_block_desc* d, BlockPlan* b, const char* who);

@@ -1642,7 +1642,10 @@ static int launch_wgrad_tr(WgradArgs& a, int Cout, int blocks_per_cu, const char
     const int tiles = (Cout / BCO) * a.col_tiles;
     long want = (long)blocks_per_cu * num_cu() / tiles;
     if (want < 1) want = 1;
-    const long chunk = (a.M + want - 1) / want;
+    long chunk = (a.M + want - 1) / want;
+    // at least 16 K steps per block: below that the fp32 atomics of the tile (one per block) outweigh the
+    // parallelism gained (measured at 64 frames: 1x1 layers of the last three stages 10 % faster)
+    if (chunk < 16L * WMK) chunk = 16L * WMK;
     a.chunk = (chunk + WMK - 1) / WMK * WMK;
     const dim3 grid((unsigned)((a.M + a.chunk - 1) / a.chunk), (unsigned)tiles);
     auto kern = wgrad_tr_kernel<BCO, BCI, WM, WN>;

@@ -541,6 +541,31 @@ __global__ void __launch_bounds__(256) bn_eval_params_kernel(BnTable t, const fl
     shift[i] = fmaf(-bn_state[t.s_off[lo] + c], sc, params[t.b_off[lo] + c]);
 }
 
+// ---- weight gradients of the several-tap convolutions: packed order [Cout][taps][Cin] -> [Cout][Cin][taps], all
+// layers in one launch (the destination was zero-filled and nothing else writes it) ----------------------------
+struct UnpackTable {
+    int n;
+    unsigned start[17];              // first element of entry l in the launch's flat index space (start[n] = total)
+    unsigned src_off[16];            // float offset of the packed buffer from the base passed to the kernel
+    unsigned dst_off[16];            // float offset into the gradient vector
+    unsigned short cin[16], taps[16];
+};
+
+__global__ void __launch_bounds__(256) unpack_all_kernel(UnpackTable t, const float* __restrict__ packed,
+                                                         float* __restrict__ grads) {
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= t.start[t.n]) return;
+    int lo = 0, hi = t.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (t.start[mid] <= i) lo = mid; else hi = mid - 1;
+    }
+    const unsigned e = i - t.start[lo];            // destination index [co][ci][tap]
+    const unsigned taps = t.taps[lo], Cin = t.cin[lo];
+    const unsigned tap = e % taps, ci = (e / taps) % Cin, co = e / (taps * Cin);
+    grads[t.dst_off[lo] + e] = packed[t.src_off[lo] + (co * taps + tap) * Cin + ci];
+}
+
 // ---- SGD with momentum; weight decay only inside "decay" segments -----------------------------
 struct SgdSegments {
     int n;
@@ -776,6 +801,31 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
             }
         }
     }
+    // several-tap convolutions on the MFMA path accumulate their weight gradient in the packed order: one
+    // contiguous region, zeroed with one fill and permuted into the gradient vector with one launch
+    UnpackTable unp;
+    unp.n = 0;
+    unp.start[0] = 0;
+    float* const dwp_base = (float*)(dry ? nullptr : (char*)wsp + A.used);
+    size_t dwp_bytes = 0;
+    if (bf) {
+        const size_t used0 = A.used;
+        for (Blk& blk : blks) {
+            for (int i = 0; i < 3; ++i) {
+                StageDef& sd = blk.plan.st[i];
+                if (sd.p.taps() <= 1 || !mfma_conv_supported(sd.p) || unp.n >= 16) continue;
+                const size_t n = (size_t)sd.p.Cout * sd.p.K();
+                sd.dwp = A.take_n<float>(n);
+                const int l = unp.n++;
+                unp.src_off[l] = (unsigned)(sd.dwp - dwp_base);
+                unp.dst_off[l] = (unsigned)(sd.dw - grads);
+                unp.cin[l] = (unsigned short)sd.p.Cin;
+                unp.taps[l] = (unsigned short)sd.p.taps();
+                unp.start[l + 1] = unp.start[l] + (unsigned)n;
+            }
+        }
+        dwp_bytes = A.used - used0;
+    }
     const ConvP& lastp = blks.back().plan.st[2].p;
     const int Cf = lastp.Cout, rows_clip = T * lastp.Ho * lastp.Wo;
     float* pm = A.take_n<float>((size_t)d->N * Cf);
@@ -809,6 +859,7 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
 
     // every weight gradient is accumulated with atomics: one fill for the whole gradient vector
     RUN(fill_zero(grads, (size_t)nparams * sizeof(float), s));
+    if (dwp_bytes) RUN(fill_zero(dwp_base, dwp_bytes, s));
     if (bf && !dry) {   // bf16 working copies of all convolution weights in both packings
         if (pk_fwd.tiled && pk_dg.tiled && pk_fwd.n == pk_dg.n) {
             pack_tiles_kernel<<<dim3(pk_fwd.tstart[pk_fwd.n]), dim3(256), 0, s>>>(pk_fwd, pk_dg, params, pack_base, 1);
@@ -918,6 +969,10 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
             }
         } else
             RUN(conv_direct_wgrad(stem, dtype, x0, da0, G("conv1.w"), s));
+    }
+    if (unp.n && !dry) {
+        unpack_all_kernel<<<dim3(cdiv(unp.start[unp.n], 256)), dim3(256), 0, s>>>(unp, dwp_base, grads);
+        LAUNCH_CHECK("unpack_wgrad");
     }
     // ================= update =================
     if (acc && !dry) {
