@@ -227,8 +227,65 @@ int block_fwd_impl(BlockPlan& b, const void* x, void* out, Arena& ws, bool dry, 
     return TSM_OK;
 }
 
+// ---- weight gradients beside the data-gradient chain -----------------------------------------------------
+// A weight gradient only feeds the optimiser, so inside one block's backward pass it runs on a second stream
+// (default priority) while the main stream goes on with the data gradients: fork = the side stream waits for an
+// event recorded on the main stream after the kernel that produced the weight gradient's operand; join = the main
+// stream waits, at the end of the block, for an event recorded behind the last weight gradient.  Nothing the
+// weight gradients read is rewritten inside the block, and the join comes before the block's scratch is reused.
+// Per host thread and device; TSM_WGRAD_OVERLAP=0, per-launch profiling or a failed stream creation keep
+// everything on the caller's stream.  The first call on a device creates the stream and events (do not make that
+// call under stream capture; later calls capture as a fork/join pattern).
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    int state = 0;   // 0 untried, 1 ready, -1 unavailable
+};
+
+static SideStream* side_stream() {
+    static int enabled = -1;
+    if (enabled < 0) {
+        const char* e = getenv("TSM_WGRAD_OVERLAP");
+        enabled = (e && e[0] == '0') ? 0 : 1;
+    }
+    if (!enabled || profiling_active()) return nullptr;
+    static thread_local SideStream side[16];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
+    SideStream& ss = side[dev];
+    if (ss.state == 0) {
+        ss.state = -1;
+        if (hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess &&
+            hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) == hipSuccess)
+            ss.state = 1;
+        else
+            (void)hipGetLastError();
+    }
+    return ss.state == 1 ? &ss : nullptr;
+}
+
+// Runs one weight gradient on the side stream behind everything enqueued on `s` so far (or on `s` itself).
+static int wgrad_beside(SideStream* ss, bool* forked, const ConvP& p, int dtype, const void* x, const void* dy, float* dw,
+                        float* dwp, int accumulate, Arena& ws, bool dry, hipStream_t s) {
+    if (!ss || dry) return run_conv_wgrad(p, dtype, x, dy, dw, dwp, accumulate, ws, dry, s);
+    if (hipEventRecord(ss->fork, s) != hipSuccess || hipStreamWaitEvent(ss->stream, ss->fork, 0) != hipSuccess)
+        return fail(TSM_ERR_LAUNCH, "block backward: cannot fork the weight-gradient stream");
+    *forked = true;
+    return run_conv_wgrad(p, dtype, x, dy, dw, dwp, accumulate, ws, dry, ss->stream);
+}
+
+static int wgrad_join(SideStream* ss, bool forked, hipStream_t s) {
+    if (!ss || !forked) return TSM_OK;
+    if (hipEventRecord(ss->join, ss->stream) != hipSuccess || hipStreamWaitEvent(s, ss->join, 0) != hipSuccess)
+        return fail(TSM_ERR_LAUNCH, "block backward: cannot join the weight-gradient stream");
+    return TSM_OK;
+}
+
 int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dout, void* dx, Arena& ws, bool dry,
                    hipStream_t s) {
+    SideStream* const ss = dry ? nullptr : side_stream();
+    bool forked = false;
     const int es = (int)dtype_size(b.dtype);
     const int L = b.nst - 1;
     const ConvP& pl = b.st[L].p;
@@ -257,7 +314,7 @@ int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dou
     for (int i = L; i >= 1; --i) {
         StageDef& st = b.st[i];
         const ConvP& pp = b.st[i - 1].p;  // producer of this stage's input
-        TSM_TRY(run_conv_wgrad(st.p, b.dtype, b.z[i - 1], g, st.dw, st.dwp, acc_flag, ws, dry, s));
+        TSM_TRY(wgrad_beside(ss, &forked, st.p, b.dtype, b.z[i - 1], g, st.dw, st.dwp, acc_flag, ws, dry, s));
         void* dzin = ws.take((size_t)pp.rows_out() * pp.Cout * es);
         // the ReLU mask and the BatchNorm reductions of the producing stage ride in the data gradient's
         // epilogue when its kernel can do that; otherwise they are a pass of their own
@@ -278,7 +335,7 @@ int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dou
         RUN(bn_bwd_apply(b.dtype, dzin, b.y[i - 1], pp.rows_out(), pp.Cout, coef, dzin, s));
         g = dzin;
     }
-    TSM_TRY(run_conv_wgrad(b.st[0].p, b.dtype, x, g, b.st[0].dw, b.st[0].dwp, acc_flag, ws, dry, s));
+    TSM_TRY(wgrad_beside(ss, &forked, b.st[0].p, b.dtype, x, g, b.st[0].dw, b.st[0].dwp, acc_flag, ws, dry, s));
     const void* addend = dzL;
     if (b.proj) {
         StageDef& st = b.ds;
@@ -286,13 +343,13 @@ int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dou
         float* coefd = ws.take_n<float>(3 * (size_t)pl.Cout);
         RUN(bn_bwd_coeffs(partd, nbL, pl.rows_out(), pl.Cout, b.bnd.mean, b.bnd.rstd, st.g, coefd, st.dg, st.db, s));
         RUN(bn_bwd_apply(b.dtype, dzL, b.yd, pl.rows_out(), pl.Cout, coefd, dyd, s));
-        TSM_TRY(run_conv_wgrad(st.p, b.dtype, x, dyd, st.dw, st.dwp, acc_flag, ws, dry, s));
+        TSM_TRY(wgrad_beside(ss, &forked, st.p, b.dtype, x, dyd, st.dw, st.dwp, acc_flag, ws, dry, s));
         void* dsc = ws.take((size_t)st.p.rows_in() * st.p.Cin * es);
         TSM_TRY(run_conv_dgrad(st.p, b.dtype, dyd, st.w, st.wd, dsc, nullptr, nullptr, ws, dry, s));
         addend = dsc;
     }
     if (dx || dry) TSM_TRY(run_conv_dgrad(b.st[0].p, b.dtype, g, b.st[0].w, b.st[0].wd, dx, addend, b.dx_fuse, ws, dry, s));
-    return TSM_OK;
+    return wgrad_join(ss, forked, s);
 }
 
 static void set_stage(StageDef& st, int F, int T, int H, int W, int Cin, int Cout, int KT, int k, int stride, int pad,

@@ -13,6 +13,7 @@ void set_error(const char* fmt, ...);
 int fail(int code, const char* fmt, ...);
 // Checks the launch error state of the calling thread after a kernel launch.
 int check_launch(const char* what);
+bool profiling_active();   // per-launch timing is on (every launch must then stay on the profiled stream)
 
 #define TSM_TRY(expr)                 \
     do {                              \

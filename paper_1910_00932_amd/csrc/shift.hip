@@ -54,6 +54,8 @@ static hipEvent_t prof_next_event() {
     return g_prof.pool[g_prof.used++];
 }
 
+bool profiling_active() { return g_prof.on; }
+
 int check_launch(const char* what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(TSM_ERR_LAUNCH, "%s: %s", what, hipGetErrorString(e));

@@ -113,3 +113,39 @@ def test_step_bf16_against_oracle_reduced_size():
           (errs["logits"], sens["logits"], errs["g:fc.w"], sens["g:fc.w"]))
     assert not bad, bad
     _check_sgd(r, 0.00125)
+
+
+def test_step_replays_from_a_hip_graph():
+    """The step is stream-ordered and allocates nothing: recorded into a HIP graph (its weight gradients run on
+    the library's second stream, which the capture follows as a fork/join), every replay, with eager work and
+    synchronisation in between, reproduces the eager loss and gradients up to the order of the atomic sums."""
+    N, T, S = 2, 4, 64
+    table = B.tsm_resnet50_param_table(400)
+    flat = I.init_params([(n, s) for n, _, s, _ in table], 1)
+    d = B.R50Desc(N=N, T=T, size=S, num_classes=400, fold_div=8, lr=0.01, momentum=0.9, weight_decay=1e-4, bn_eps=1e-5,
+                  bn_momentum=0.1, dtype=B.TSM_BF16)
+    ws = workspace(B.tsm_resnet50_workspace_bytes(d))
+    clips = torch.from_numpy(I.clips(N, T, S, 0, "bf16")).to(torch.bfloat16).cuda()
+    labels = torch.from_numpy(I.labels(N)).cuda()
+    params = torch.from_numpy(flat).cuda()
+    mom = torch.zeros_like(params)
+    grads = torch.empty_like(params)
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+
+    def call():
+        B.tsm_resnet50_step(d, clips, labels, params, mom, None, grads, loss, None, 0, ws, torch.cuda.current_stream())
+
+    call()                                # first call on the device: creates the library's second stream
+    torch.cuda.synchronize()
+    g0, l0 = grads.cpu().numpy().copy(), float(loss.item())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for i in range(3):
+        grads.fill_(float(i))             # eager work between the replays
+        loss.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert abs(float(loss.item()) - l0) <= 1e-6 * abs(l0), i
+        assert rel_l2(grads.cpu().numpy(), g0) < 1e-5, (i, rel_l2(grads.cpu().numpy(), g0))
