@@ -312,6 +312,9 @@ def main():
                     help="clips per step: 64 = configs[3] (throughput run, the default), 8 = configs[2]; "
                          "--workload infer defaults to the paper's batch of 16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="keep the weight gradients on the launch stream (the library otherwise runs them on a second "
+                         "stream beside the data gradients); for per-kernel profiles with exclusive durations")
     ap.add_argument("--graph", action="store_true",
                     help="record one call into a HIP graph and time replays of it (step and infer workloads)")
     ap.add_argument("--workload", default="step", choices=["step", "res2", "cmp", "infer"],
@@ -322,6 +325,8 @@ def main():
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); --gpus %d is not supported"
                  % args.gpus)
 
+    if args.no_overlap:
+        os.environ["TSM_WGRAD_OVERLAP"] = "0"      # read by the library when it first runs a block backward
     import torch
     from paper_1910_00932_amd import binding as B
     from paper_1910_00932_amd import inputs as I
@@ -427,7 +432,7 @@ def main():
                    "clips_per_step": N, "frames": T, "size": S, "num_classes": K},
         "step_tflops": flops_step / (ms_per_step * 1e-3) / 1e12,
         "pct_bf16_mfma_peak": 100.0 * flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        "loss_after": final_loss, "wall_s": wall, "hip_graph": bool(args.graph),
+        "loss_after": final_loss, "wall_s": wall, "hip_graph": bool(args.graph), "wgrad_overlap": not args.no_overlap,
         "roofline": roof, "kernel_classes": classes, "profiled_step_ms": prof_total,
     }
 
