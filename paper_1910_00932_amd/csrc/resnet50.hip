@@ -216,24 +216,33 @@ __global__ void __launch_bounds__(256) stem_pool_bwd_kernel(const T* __restrict_
         float g[V];
 #pragma unroll
         for (int j = 0; j < V; ++j) g[j] = 0.f;
-        const int oh_lo = ih / 2, oh_hi = (ih + 1) / 2;   // windows [2*oh-1, 2*oh+1] containing ih
-        const int ow_lo = iw / 2, ow_hi = (iw + 1) / 2;
-        for (int oh = oh_lo; oh <= oh_hi; ++oh) {
-            if (oh >= Ho) continue;
-            const int kh = ih - (2 * oh - 1);
-            for (int ow = ow_lo; ow <= ow_hi; ++ow) {
-                if (ow >= Wo) continue;
-                const int code = kh * 3 + (iw - (2 * ow - 1));
-                const long o = ((f * Ho + oh) * Wo + ow) * (long)cv + v;
-                const Vec16<T> d = *(const Vec16<T>*)(dp + o * V);
-                uint8_t ab[V];   // the V winner codes in one load
-                if (V == 8) *(uint2*)ab = *(const uint2*)(arg + o * V);
-                else *(uint32_t*)ab = *(const uint32_t*)(arg + o * V);
+        // windows [2*oh-1, 2*oh+1] containing ih: one (even ih) or two (odd ih), likewise along w.  All four
+        // candidates are loaded without branches (clamped to a valid window, duplicates and windows beyond the
+        // border get a code that no winner has), so that their latencies overlap.
+        const int oh0 = ih / 2, oh1 = (ih + 1) / 2, ow0 = iw / 2, ow1 = (iw + 1) / 2;
+        const bool vh0 = oh0 < Ho, vh1 = oh1 != oh0 && oh1 < Ho, vw0 = ow0 < Wo, vw1 = ow1 != ow0 && ow1 < Wo;
+        const int ch0 = oh0 < Ho ? oh0 : Ho - 1, ch1 = oh1 < Ho ? oh1 : Ho - 1;
+        const int cw0 = ow0 < Wo ? ow0 : Wo - 1, cw1 = ow1 < Wo ? ow1 : Wo - 1;
+        const int kh0 = ih - (2 * oh0 - 1), kh1 = ih - (2 * oh1 - 1), kw0 = iw - (2 * ow0 - 1), kw1 = iw - (2 * ow1 - 1);
+        const long fo = f * Ho;
+        const long o00 = ((fo + ch0) * Wo + cw0) * (long)cv + v, o01 = ((fo + ch0) * Wo + cw1) * (long)cv + v;
+        const long o10 = ((fo + ch1) * Wo + cw0) * (long)cv + v, o11 = ((fo + ch1) * Wo + cw1) * (long)cv + v;
+        const int code[4] = {vh0 && vw0 ? kh0 * 3 + kw0 : 255, vh0 && vw1 ? kh0 * 3 + kw1 : 255,
+                             vh1 && vw0 ? kh1 * 3 + kw0 : 255, vh1 && vw1 ? kh1 * 3 + kw1 : 255};
+        const long off[4] = {o00, o01, o10, o11};
+        Vec16<T> dq[4];
+        uint8_t aq[4][V];
 #pragma unroll
-                for (int j = 0; j < V; ++j)
-                    if ((int)ab[j] == code) g[j] += Elem<T>::ld(d.v[j]);
-            }
+        for (int q = 0; q < 4; ++q) {
+            dq[q] = *(const Vec16<T>*)(dp + off[q] * V);
+            if (V == 8) *(uint2*)aq[q] = *(const uint2*)(arg + off[q] * V);
+            else *(uint32_t*)aq[q] = *(const uint32_t*)(arg + off[q] * V);
         }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int j = 0; j < V; ++j)
+                if ((int)aq[q][j] == code[q]) g[j] += Elem<T>::ld(dq[q].v[j]);
         const long i = r * cv + v;
         const Vec16<T> pk = *(const Vec16<T>*)(y + i * V);
         Vec16<T> o;
