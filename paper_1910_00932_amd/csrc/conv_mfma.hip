@@ -537,19 +537,22 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
             int cls = 0;
             while (cls + 1 < a.ncls && mt >= a.mt0[cls + 1]) ++cls;
             const int hc = a.hc[cls], wc = a.wc[cls];
-            const long Mc = (long)a.F * hc * wc;
-            const long m = (long)(mt - a.mt0[cls]) * BM + tid;
+            // (row counts are below 2^31: 32-bit divisions)
+            const unsigned Mc = (unsigned)a.F * (unsigned)(hc * wc);
+            const unsigned m = (unsigned)(mt - a.mt0[cls]) * BM + tid;
             RowInfo info;
             info.off = 0;
             info.mask = 0;
             info.dst = -1;
             if (m < Mc) {
-                const int f = (int)(m / (hc * wc));
-                const int q = (int)(m - (long)f * (hc * wc));
-                const int qh = q / wc, qw = q - qh * wc;
+                const int f = (int)(m / (unsigned)(hc * wc));
+                const int q = (int)(m - (unsigned)f * (unsigned)(hc * wc));
+                const int qh = (int)((unsigned)q / (unsigned)wc), qw = q - qh * wc;
                 const int dh = qh * a.cstep + a.ph[cls], dw = qw * a.cstep + a.pw[cls];
-                const int oh = DGRAD ? (dh - a.padh + a.a0h[cls]) / a.cstep : dh * a.stride - a.padh;
-                const int ow = DGRAD ? (dw - a.padw + a.a0w[cls]) / a.cstep : dw * a.stride - a.padw;
+                // (the class step is 1 or 2 and divides the numerators exactly, negative ones included)
+                const int sh = a.cstep == 2 ? 1 : 0;
+                const int oh = DGRAD ? (dh - a.padh + a.a0h[cls]) >> sh : dh * a.stride - a.padh;
+                const int ow = DGRAD ? (dw - a.padw + a.a0w[cls]) >> sh : dw * a.stride - a.padw;
                 const int t = f % a.T;
                 uint32_t mask = 0;
                 for (int th = 0; th < a.nth[cls]; ++th)
@@ -679,6 +682,14 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
         for (int i = 0; i < NP; ++i) load_piece(p1, i);
     }
     int cur_nk = tile >= 0 ? pc.nk : 0, cur_n0 = tile >= 0 ? pc.n0 : 0;
+    // Per-channel sums (forward statistics, or the BatchNorm-backward sums of a fused data gradient) of the eight
+    // columns this thread stores.  They run on across the tiles of the block as long as the column tile stays the
+    // same (with a grid that is a multiple of 8 * ntiles it never changes) and are reduced and flushed when it
+    // changes and after the last tile.
+    constexpr int FV = 8;
+    float f1[FV], f2[FV];
+#pragma unroll
+    for (int q = 0; q < FV; ++q) f1[q] = f2[q] = 0.f;
 
     while (tile >= 0) {
         const int ntile = next_tile(tile + gridDim.x);
@@ -739,7 +750,9 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
                     for (int j = 0; j < NJ; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb][i], bfr[cb][j], acc[i][j], 0, 0, 0);
+                        // operands swapped: the result block is [channel][pixel], so a lane holds four consecutive
+                        // channels of one pixel per register quad, which the epilogue stores to LDS as one 8-byte piece
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cb][j], af[cb][i], acc[i][j], 0, 0, 0);
 #pragma unroll
                 for (int q = ks * PPK; q < (ks + 1) * PPK && q < NP; ++q) {
                     store_piece(cstage ^ 1, q);
@@ -754,16 +767,12 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
 
         // ---- epilogue, one pass per row block through the staging tile; the registers and the other LDS
         // stage already hold the first two K steps of the next tile.
-        float s1[NJ], s2[NJ];
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) s1[j] = s2[j] = 0.f;
         // fused BatchNorm backward: this thread stores the same eight columns of every row it handles
         // (forward with an affine epilogue keeps scale / shift of the same eight columns in mu / rs)
-        constexpr int FV = 8;
         const bool affine = !DGRAD && a.ep_scale != nullptr;
-        float f1[FV], f2[FV], mu[FV], rs[FV];
+        float mu[FV], rs[FV];
 #pragma unroll
-        for (int q = 0; q < FV; ++q) f1[q] = f2[q] = mu[q] = rs[q] = 0.f;
+        for (int q = 0; q < FV; ++q) mu[q] = rs[q] = 0.f;
         if (fuse_bn || affine) {
             const int c0 = cur_n0 + (tid % (BN / 8)) * 8;
             if (c0 < a.Cd) {
@@ -812,36 +821,17 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
             if (h > 0) __syncthreads();   // previous pass stored (the previous tile's last pass: barrier at its end)
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
-                const int col = wn * TN + j * 32 + (lane & 31);
-                const bool odd = lane & 1;
+                // lane: pixel lane % 32 of the row block, channels 8*q + 4*(lane / 32) + {0..3} of the column block
+                bf16_t* dstp = Cst + (wm * 32 + (lane & 31)) * LDC + wn * TN + j * 32 + 4 * (lane >> 5);
 #pragma unroll
-                for (int r = 0; r < 16; r += 2) {
-                    const float v0 = acc[h][j][r], v1 = acc[h][j][r + 1];
-                    if (do_stats) {   // statistics of the values as stored (rows beyond M are exact zeros)
-                        const uint32_t own = pack_bf16x2(v0, v1);
-                        const float q0 = __uint_as_float(own << 16), q1 = __uint_as_float(own & 0xffff0000u);
-                        s1[j] += q0 + q1;
-                        s2[j] = fmaf(q0, q0, fmaf(q1, q1, s2[j]));
-                    }
-                    const float got = __uint_as_float(pair_swap(__float_as_uint(odd ? v0 : v1)));
-                    const uint32_t word = pack_bf16x2(odd ? got : v0, odd ? v1 : got);
-                    const int row = wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3) + (odd ? 1 : 0);
-                    *(uint32_t*)(Cst + row * LDC + (col & ~1)) = word;
-                }
-                if (do_stats && h == MI - 1) {   // own slot: (wavefront row, lane half) x column
-                    const int slot = wm * 2 + (lane >> 5);
-                    s_part[slot * BN + col] = s1[j];
-                    s_part[(WM * 2 + slot) * BN + col] = s2[j];
+                for (int q = 0; q < 4; ++q) {
+                    uint2 w;
+                    w.x = pack_bf16x2(acc[h][j][4 * q], acc[h][j][4 * q + 1]);
+                    w.y = pack_bf16x2(acc[h][j][4 * q + 2], acc[h][j][4 * q + 3]);
+                    *(uint2*)(dstp + 8 * q) = w;
                 }
             }
             __syncthreads();
-            if (do_stats && h == MI - 1 && tid < 2 * BN) {   // fixed summation order over the slots
-                const int stat = tid / BN, col = tid % BN;
-                float v = 0.f;
-#pragma unroll
-                for (int sl = 0; sl < WM * 2; ++sl) v += s_part[(stat * WM * 2 + sl) * BN + col];
-                if (cur_n0 + col < a.Cd) atomicAdd(prow + stat * a.Cd + cur_n0 + col, v);
-            }
             if (!DGRAD) {
 #pragma unroll
                 for (int pss = 0; pss < HM / RPS; ++pss) {
@@ -850,6 +840,16 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                     if (mrow < 0 || col >= a.Cd) continue;
                     u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
                     u32x4* q = (u32x4*)(a.dst + (long)mrow * a.Cd + col);
+                    if (do_stats) {   // statistics of the values as stored
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float lo = __uint_as_float(v[e] << 16), hi = __uint_as_float(v[e] & 0xffff0000u);
+                            f1[2 * e] += lo;
+                            f1[2 * e + 1] += hi;
+                            f2[2 * e] = fmaf(lo, lo, f2[2 * e]);
+                            f2[2 * e + 1] = fmaf(hi, hi, f2[2 * e + 1]);
+                        }
+                    }
                     if (affine) {
                         u32x4 r = u32x4{0u, 0u, 0u, 0u};
                         if (a.ep_res) r = *(const u32x4*)(a.ep_res + (long)mrow * a.Cd + col);
@@ -913,7 +913,7 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                 if (h + 1 < MI) request(h + 1);
             }
         }
-        if (fuse_bn) {
+        if ((fuse_bn || do_stats) && (ntile < 0 || next_n0 != cur_n0)) {
             // lanes CV apart hold the same columns: fold them, then one slot per wavefront, fixed order over the slots
             constexpr int CV = BN / 8;
 #pragma unroll
@@ -939,6 +939,8 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                 for (int sl = 0; sl < WM * WN; ++sl) v += s_part[(stat * WM * 2 + sl) * BN + col];
                 if (cur_n0 + col < a.Cd) atomicAdd(prow + stat * a.Cd + cur_n0 + col, v);
             }
+#pragma unroll
+            for (int q = 0; q < FV; ++q) f1[q] = f2[q] = 0.f;
         }
         __syncthreads();   // the row buffer of this tile is decoded into again at the top of the next tile
         tile = ntile;
