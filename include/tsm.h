@@ -14,7 +14,14 @@
  *    says "host".  The library allocates no device memory; scratch space comes in
  *    through the (ws, ws_bytes) pair, sized by the matching *_workspace_bytes().
  *  - Calls are asynchronous on the caller's hipStream_t (passed as void*; NULL is
- *    the default stream) and never synchronise the device.
+ *    the default stream) and never synchronise the device.  The backward entry
+ *    points (tsm_block_bwd, tsm_resnet50_step, tsm_resnet50_accum_step) run the
+ *    weight gradients on a second stream that the library creates per host thread
+ *    and device on first use; it forks from and joins the caller's stream with
+ *    events inside the call, so the call as a whole stays ordered on the caller's
+ *    stream and can be recorded into a HIP graph (make the first call on a device
+ *    outside stream capture).  TSM_WGRAD_OVERLAP=0 in the environment keeps
+ *    everything on the caller's stream.
  *  - Return value: TSM_OK or a negative tsm_status.  On error nothing has been
  *    launched (argument errors) or the stream's state is undefined
  *    (TSM_ERR_LAUNCH).  tsm_last_error() returns a host string describing the
