@@ -67,29 +67,39 @@ int check_launch(const char* what) {
 }
 
 // ---- channels-innermost shift ------------------------------------------------
-// One thread moves one V-sized piece of one pixel's channel vector.  `dir` is +1
-// for S (group 1 reads t+1, group 2 reads t-1) and -1 for S^T.
-// foldv/cv: fold and C measured in V units.
+// One thread moves one V-sized piece of one pixel's channel vector.  `dir` is +1 for S (group 1 reads t+1,
+// group 2 reads t-1) and -1 for S^T.  foldv/cv: fold and C measured in V units.
+// blockIdx.y walks the frames (frame index and clip position are uniform in a block), blockIdx.x and the thread
+// cover the frame's vectors: 32-bit index arithmetic, no division by the frame size per thread.  Measured on a
+// [64,8,256,56,56] bf16 tensor: one vector per thread beats two or four (5.3 TB/s), blocks of 128 threads beat
+// 256 and 1024 (6.33 / 6.28 / 6.0 TB/s), regular loads with nontemporal stores beat nontemporal loads (5.9 TB/s).
+static constexpr int SHIFT_U = 1;     // vectors per thread
+static constexpr int SHIFT_NT = 128;  // threads per block
 template <typename V>
-__global__ void __launch_bounds__(256) shift_nthwc_kernel(const V* __restrict__ x, V* __restrict__ y,
-                                                          size_t total, int T, size_t frame_v,
-                                                          int cv, int foldv, int dir) {
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= total) return;
-    const int c = (int)(i % cv);
-    const size_t f = i / frame_v;
-    const int t = (int)(f % T);
-    int dt = 0;
-    if (c < foldv) dt = dir;
-    else if (c < 2 * foldv) dt = -dir;
-    const int ts = t + dt;
-    V v;
-    if (ts >= 0 && ts < T) {
-        v = __builtin_nontemporal_load(x + (ptrdiff_t)i + (ptrdiff_t)dt * (ptrdiff_t)frame_v);
-    } else {
-        v = V{};
+__global__ void __launch_bounds__(SHIFT_NT) shift_nthwc_kernel(const V* __restrict__ x, V* __restrict__ y,
+                                                               unsigned frames, int T, unsigned frame_v,
+                                                               unsigned cv, unsigned foldv, int dir) {
+    for (unsigned f = blockIdx.y; f < frames; f += gridDim.y) {
+        const int t = (int)(f % (unsigned)T);
+        const V* xf = x + (size_t)f * frame_v;
+        V* yf = y + (size_t)f * frame_v;
+        const bool up_ok = t + dir >= 0 && t + dir < T;        // group 1 reads frame t + dir
+        const bool dn_ok = t - dir >= 0 && t - dir < T;        // group 2 reads frame t - dir
+        const ptrdiff_t up = (ptrdiff_t)dir * (ptrdiff_t)frame_v;
+#pragma unroll
+        for (int u = 0; u < SHIFT_U; ++u) {
+            const unsigned j = (blockIdx.x * SHIFT_U + u) * (unsigned)SHIFT_NT + threadIdx.x;
+            if (j >= frame_v) break;
+            const unsigned c = j % cv;
+            // one load site for all three channel groups (lanes of a wavefront fall into all of them)
+            const bool g1 = c < foldv, g2 = !g1 && c < 2 * foldv;
+            const ptrdiff_t off = g1 ? up : (g2 ? -up : 0);
+            const bool valid = g1 ? up_ok : (g2 ? dn_ok : true);
+            V v = V{};
+            if (valid) v = xf[j + off];
+            __builtin_nontemporal_store(v, yf + j);
+        }
     }
-    __builtin_nontemporal_store(v, y + i);
 }
 
 // ---- channel-planes shift (the paper's memory order) ---------------------------
@@ -125,11 +135,14 @@ static int launch_nthwc(const void* x, void* y, size_t bytes, int T, size_t fram
                         int fold_bytes, int dir, hipStream_t s) {
     size_t total = bytes / sizeof(V);
     if (total == 0) return TSM_OK;
-    size_t blocks = (total + 255) / 256;
-    if (blocks > 0x7fffffffull) return fail(TSM_ERR_SHAPE, "shift: tensor too large");
-    shift_nthwc_kernel<V><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(
-        (const V*)x, (V*)y, total, T, frame_bytes / sizeof(V), c_bytes / (int)sizeof(V),
-        fold_bytes / (int)sizeof(V), dir);
+    const size_t frame_v = frame_bytes / sizeof(V);
+    const size_t frames = total / frame_v;
+    if (frame_v > 0x7fffffffull || frames > 0x7fffffffull) return fail(TSM_ERR_SHAPE, "shift: tensor too large");
+    const unsigned gx = (unsigned)((frame_v + SHIFT_NT * SHIFT_U - 1) / (SHIFT_NT * SHIFT_U));
+    const unsigned gy = (unsigned)(frames < 65535 ? frames : 65535);
+    shift_nthwc_kernel<V><<<dim3(gx, gy), dim3(SHIFT_NT), 0, s>>>(
+        (const V*)x, (V*)y, (unsigned)frames, T, (unsigned)frame_v, (unsigned)(c_bytes / (int)sizeof(V)),
+        (unsigned)(fold_bytes / (int)sizeof(V)), dir);
     return check_launch("shift_nthwc");
 }
 
