@@ -108,3 +108,17 @@ def test_shift_equals_one_hot_temporal_conv():
         w[c, c, 2 if c < fold else (0 if c < 2 * fold else 1)] = 1.0
     assert np.allclose(O.tconv_fwd(x, w), O.shift(x, 8), atol=0, rtol=0)
     assert np.allclose(O.tconv_dgrad(x, w, 3, 3), O.shift_adjoint(x, 8), atol=0, rtol=0)
+
+
+def test_sum_identity_counts_exactly_what_falls_off_the_clip_ends():
+    """The shift only moves values and drops those pushed past a clip end: the sum over the output equals the sum
+    over the input minus group 1's first frames and group 2's last frames (exact in integers); the adjoint drops
+    the mirror-image frames."""
+    rng = np.random.default_rng(7)
+    N, T, C, H, W, fd = 3, 5, 24, 4, 3, 4
+    fold = C // fd
+    x = rng.integers(-50, 50, size=(N, T, C, H, W)).astype(np.float64)
+    lost = x[:, 0, :fold].sum() + x[:, T - 1, fold:2 * fold].sum()
+    assert O.shift(x, fd).sum() == x.sum() - lost
+    lost_adj = x[:, T - 1, :fold].sum() + x[:, 0, fold:2 * fold].sum()
+    assert O.shift_adjoint(x, fd).sum() == x.sum() - lost_adj
