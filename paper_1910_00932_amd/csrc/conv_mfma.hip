@@ -481,6 +481,7 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
     constexpr int ROWB = BK * 2;                    // bytes per LDS row
     constexpr int STAGE = (BM + BN) * ROWB;         // bytes per ring stage
     constexpr int LDC = BN + 8;                     // staging pitch (elements)
+    constexpr int NSLOT = WM * WN;                  // one statistics slot per wavefront
     static_assert(BK == 64 && KV == 8, "rows of eight 16-byte vectors");
     static_assert(BM % RPP == 0 && BN % RPP == 0 && HM == WM * 32, "tile / thread mismatch");
     static_assert((HM * LDC * 2) % 16 == 0, "alignment of the regions behind the staging tile");
@@ -489,7 +490,7 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16_t* Cst = (bf16_t*)(smem + NS * STAGE);      // [HM][LDC] staging tile of the epilogue
     float* s_part = (float*)(Cst + HM * LDC);        // [2 stats][WM*2 slots][BN] statistics slots
-    RowInfo* s_row = (RowInfo*)(s_part + 2 * WM * 2 * BN);   // [2][BM]: rows of the current and of the next tile
+    RowInfo* s_row = (RowInfo*)(s_part + 2 * NSLOT * BN);   // [2][BM]: rows of the current and of the next tile
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -498,7 +499,6 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
     const int kvec = (tid % KV) ^ ((lrow >> 1) & 7);             // K vector this thread fetches (see layout above)
     const bool do_stats = (!DGRAD) && a.stats != nullptr;
     const bool fuse_bn = DGRAD && a.act != nullptr;   // ReLU mask + BatchNorm-backward sums in the epilogue
-    static_assert(WM * WN <= WM * 2, "one statistics slot per wavefront");
 
     const int hw_d = a.Hd * a.Wd;
     const int hw_s = a.Hs * a.Ws;
@@ -682,6 +682,15 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
         for (int i = 0; i < NP; ++i) load_piece(p1, i);
     }
     int cur_nk = tile >= 0 ? pc.nk : 0, cur_n0 = tile >= 0 ? pc.n0 : 0;
+    // Fragment registers live across K steps and tiles: the first fragments of a step are read from its stage
+    // while the last MFMA group of the step before is still in the pipeline (see the main loop).
+    constexpr int KS = BK / 16;
+    bf16x8 af[2][MI], bfr[2][NJ];
+    __syncthreads();                 // stage 0 holds the first step
+#pragma unroll
+    for (int i = 0; i < MI; ++i) af[0][i] = *(const bf16x8*)(smem + a_rd[0] + i * HM * ROWB);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) bfr[0][j] = *(const bf16x8*)(smem + b_rd[0] + j * 32 * ROWB);
     // Per-channel sums (forward statistics, or the BatchNorm-backward sums of a fused data gradient) of the eight
     // columns this thread stores.  They run on across the tiles of the block as long as the column tile stays the
     // same (with a grid that is a multiple of 8 * ntiles it never changes) and are reduced and flushed when it
@@ -728,15 +737,13 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
         __syncthreads();       // the next tile's rows are decoded
         Plan pl = plan_next();
         for (int kc = 0; kc < cur_nk; ++kc) {
-            __syncthreads();   // stage `cstage` is complete, and everybody is done with the other stage
+            // One barrier per step, in front of the last MFMA group: by then every wavefront has written its pieces
+            // of the next step into the other stage and has read its last fragments of this stage, so behind the
+            // barrier the next step's first fragments are read (their latency overlaps the last MFMA group) and
+            // the next step may overwrite this stage.
             const unsigned char* st = smem + cstage * STAGE;
-            constexpr int KS = BK / 16;
+            const unsigned char* stn = smem + (cstage ^ 1) * STAGE;
             constexpr int PPK = (NP + KS - 2) / (KS - 1);     // pieces handled after each of the first KS-1 groups
-            bf16x8 af[2][MI], bfr[2][NJ];
-#pragma unroll
-            for (int i = 0; i < MI; ++i) af[0][i] = *(const bf16x8*)(st + a_rd[0] + i * HM * ROWB);
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) bfr[0][j] = *(const bf16x8*)(st + b_rd[0] + j * 32 * ROWB);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 const int cb = ks & 1, nb = cb ^ 1;
@@ -745,6 +752,12 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                     for (int i = 0; i < MI; ++i) af[nb][i] = *(const bf16x8*)(st + a_rd[ks + 1] + i * HM * ROWB);
 #pragma unroll
                     for (int j = 0; j < NJ; ++j) bfr[nb][j] = *(const bf16x8*)(st + b_rd[ks + 1] + j * 32 * ROWB);
+                } else {
+                    __syncthreads();
+#pragma unroll
+                    for (int i = 0; i < MI; ++i) af[nb][i] = *(const bf16x8*)(stn + a_rd[0] + i * HM * ROWB);
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) bfr[nb][j] = *(const bf16x8*)(stn + b_rd[0] + j * 32 * ROWB);
                 }
 #pragma unroll
                 for (int i = 0; i < MI; ++i)
@@ -928,7 +941,7 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
 #pragma unroll
                 for (int q = 0; q < FV; ++q) {
                     s_part[wave * BN + lane * 8 + q] = f1[q];
-                    s_part[(WM * 2 + wave) * BN + lane * 8 + q] = f2[q];
+                    s_part[(NSLOT + wave) * BN + lane * 8 + q] = f2[q];
                 }
             }
             __syncthreads();
@@ -936,7 +949,7 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                 const int stat = tid / BN, col = tid % BN;
                 float v = 0.f;
 #pragma unroll
-                for (int sl = 0; sl < WM * WN; ++sl) v += s_part[(stat * WM * 2 + sl) * BN + col];
+                for (int sl = 0; sl < NSLOT; ++sl) v += s_part[(stat * NSLOT + sl) * BN + col];
                 if (cur_n0 + col < a.Cd) atomicAdd(prow + stat * a.Cd + cur_n0 + col, v);
             }
 #pragma unroll
@@ -1047,7 +1060,7 @@ static int launch_igemm_ring_s(IgemmArgs& a, const char* name, hipStream_t s) {
     a.ntiles = (a.Cd + BN - 1) / BN;
     // two operand stages, staging tile of one epilogue pass, statistics slots, two row buffers
     const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t) + (size_t)(WM * 32) * (BN + 8) * sizeof(bf16_t) +
-                        (size_t)2 * WM * 2 * BN * sizeof(float) + (size_t)2 * BM * sizeof(RowInfo);
+                        (size_t)2 * WM * WN * BN * sizeof(float) + (size_t)2 * BM * sizeof(RowInfo);
     auto kern = igemm_ring_kernel<BM, BN, WM, WN, DGRAD, STREAM>;
     static bool configured = false;
     if (!configured) {
