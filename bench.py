@@ -112,6 +112,8 @@ def class_bytes(F, size):
             chained = name.endswith(".c1") and (blk >= 2 or (blk == 0 and not name.startswith("res2")))
             if name.endswith((".c2", ".c3")) or chained:
                 extra += 2.0 * x_b
+            elif name.endswith(".c1") and blk == 1:
+                extra += x_b           # the block below has a projection shortcut: only its ReLU mask rides along
             add(igemm_class("dgrad", cin, cout, rin), x_b + y_b + extra)
         add("wgrad_tr_64x256" if stem else wgrad_class(cout, cin, taps), x_b + y_b)
     return byt

@@ -302,6 +302,12 @@ int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dou
     if (chained) {
         dzL = const_cast<void*>(dout);
         partL = const_cast<float*>(b.dout_part);
+    } else if (b.dout_masked) {
+        // dout is dz already (the producing data gradient applied the mask): only the sums are taken
+        dzL = const_cast<void*>(dout);
+        RUN(relu_bn_bwd_reduce(b.dtype, dout, nullptr, b.y[L], pl.rows_out(), pl.Cout, b.bn[L].mean, b.bn[L].rstd, nullptr, partL,
+                               b.proj ? b.yd : nullptr, b.proj ? b.bnd.mean : nullptr, b.proj ? b.bnd.rstd : nullptr,
+                               b.proj ? partd : nullptr, s));
     } else {
         RUN(relu_bn_bwd_reduce(b.dtype, dout, out, b.y[L], pl.rows_out(), pl.Cout, b.bn[L].mean, b.bn[L].rstd, dzL, partL,
                                b.proj ? b.yd : nullptr, b.proj ? b.bnd.mean : nullptr, b.proj ? b.bnd.rstd : nullptr,

@@ -30,6 +30,8 @@ struct BlockPlan {
     // producer was a fused data gradient).  dx_fuse: applied to the data gradient that produces dx.
     const float* dout_part;
     int dout_nb;
+    bool dout_masked;      // the gradient handed to block_bwd_impl is already masked with out > 0, without sums (the
+                           // producer was a data gradient in mask-only mode): the sums are reduced from it
     const DgradFuse* dx_fuse;
     // saved-for-backward buffers (caller-owned memory)
     void* y[3];           // convolution outputs

@@ -498,7 +498,8 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
     const int lrow = tid / KV;                                   // row within a load pass
     const int kvec = (tid % KV) ^ ((lrow >> 1) & 7);             // K vector this thread fetches (see layout above)
     const bool do_stats = (!DGRAD) && a.stats != nullptr;
-    const bool fuse_bn = DGRAD && a.act != nullptr;   // ReLU mask + BatchNorm-backward sums in the epilogue
+    const bool fuse_mask = DGRAD && a.act != nullptr;        // ReLU mask in the epilogue ...
+    const bool fuse_bn = fuse_mask && a.ybn != nullptr;      // ... and the BatchNorm-backward sums of the masked values
 
     const int hw_d = a.Hd * a.Wd;
     const int hw_s = a.Hs * a.Ws;
@@ -824,7 +825,7 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                 const long e = mr[pss] * a.Cd + col;
                 const bool ok = mr[pss] >= 0;
                 ad[pss] = *(const u32x4*)((ok && a.addend) ? a.addend + e : zero_page_d);
-                ac[pss] = *(const u32x4*)((ok && fuse_bn) ? a.act + e : zero_page_d);
+                ac[pss] = *(const u32x4*)((ok && fuse_mask) ? a.act + e : zero_page_d);
                 yy[pss] = *(const u32x4*)((ok && fuse_bn) ? a.ybn + e : zero_page_d);
             }
         };
@@ -891,7 +892,7 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                             o[q] = pack_bf16x2(lo, hi);
                         }
                     }
-                    if (fuse_bn) {   // on the values as stored (bf16)
+                    if (fuse_mask) {   // on the values as stored (bf16); without ybn the sums are not used
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
                             const float alo = __uint_as_float(ac[q] << 16), ahi = __uint_as_float(ac[q] & 0xffff0000u);
@@ -917,10 +918,8 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                     const long e = mz[pss] * a.Cd + col;
                     u32x4 zad = u32x4{0u, 0u, 0u, 0u}, zac = zad, zyy = zad;
                     if (a.addend) zad = *(const u32x4*)(a.addend + e);
-                    if (fuse_bn) {
-                        zac = *(const u32x4*)(a.act + e);
-                        zyy = *(const u32x4*)(a.ybn + e);
-                    }
+                    if (fuse_mask) zac = *(const u32x4*)(a.act + e);
+                    if (fuse_bn) zyy = *(const u32x4*)(a.ybn + e);
                     finish(mz[pss], u32x4{0u, 0u, 0u, 0u}, zad, zac, zyy);
                 }
                 if (h + 1 < MI) request(h + 1);
@@ -1188,7 +1187,8 @@ int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* 
     dgrad_args(p, a);
     if (fuse) {
         if (conv_mfma_dgrad_blocks(p) == 0) return fail(TSM_ERR_UNSUPPORTED, "dgrad: this layer's kernel cannot fuse the BatchNorm reductions");
-        a.act = fuse->act; a.ybn = fuse->y; a.bn_mean = fuse->mean; a.bn_rstd = fuse->rstd; a.stats = fuse->partial;
+        // (y == nullptr: only the ReLU mask of `act` is applied, no sums)
+        a.act = fuse->act; a.ybn = fuse->y; a.bn_mean = fuse->mean; a.bn_rstd = fuse->rstd; a.stats = fuse->y ? fuse->partial : nullptr;
     }
     return dispatch_igemm<true>(a, s);
 }

@@ -353,7 +353,7 @@ __global__ void __launch_bounds__(256) relu_bn_bwd_reduce_kernel(
                 s2[j] = fmaf(dz, (Elem<T>::ld(yy.v[j]) - mu[j]) * rs[j], s2[j]);
                 if (y2) s3[j] = fmaf(dz, (Elem<T>::ld(yy2.v[j]) - mu2[j]) * rs2[j], s3[j]);
             }
-            *(Pack<T, V>*)(dz_out + off) = o;
+            if (dz_out) *(Pack<T, V>*)(dz_out + off) = o;
         }
     }
     block_partial_2<V>(s1, s2, cvi, cv, C, partial + (size_t)blockIdx.x * 2 * C);

@@ -60,7 +60,7 @@ int bn_relu_apply(int dtype, const void* y, long rows, int C, const float* scale
 // out = relu(scale*y + shift + sc), sc = shortcut (scale_d == null) or scale_d*shortcut + shift_d
 int block_tail_fwd(int dtype, const void* y, long rows, int C, const float* scale, const float* shift,
                    const void* shortcut, const float* scale_d, const float* shift_d, void* out, hipStream_t s);
-// dz = dout * [act > 0] (act == null: no mask) written to dz_out (may alias dout); partial rows receive
+// dz = dout * [act > 0] (act == null: no mask) written to dz_out (may alias dout; null: not written); partial rows receive
 // sum dz and sum dz*yhat with yhat = (y - mean)*rstd.  If y2 != null a second BatchNorm (projection
 // shortcut) is reduced into partial2.
 int relu_bn_bwd_reduce(int dtype, const void* dout, const void* act, const void* y, long rows, int C,

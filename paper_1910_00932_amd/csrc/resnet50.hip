@@ -951,6 +951,12 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
             b.plan.dx_fuse = &fz;
             pp.dout_part = dry ? (const float*)1 : chain_part[i - 1];   // (dry run: only the flag matters)
             pp.dout_nb = chain_nb[i - 1];
+        } else if (i > 0 && blks[i - 1].plan.proj && conv_dgrad_fuse_blocks(b.plan.st[0].p, dtype)) {
+            // block i-1 has a projection shortcut (two BatchNorms share its output gradient): the data gradient
+            // applies its output ReLU mask only, the two pairs of sums are reduced from the masked gradient
+            fz = DgradFuse{(const bf16_t*)blks[i - 1].out, nullptr, nullptr, nullptr, nullptr};
+            b.plan.dx_fuse = &fz;
+            blks[i - 1].plan.dout_masked = true;
         }
         TSM_TRY(block_bwd_impl(b.plan, b.in, b.out, dbuf[cur], dbuf[cur ^ 1], sc, dry, s));
         note(sc);
