@@ -78,3 +78,32 @@ def test_block_argument_errors():
     assert L.tsm_block_fwd(ctypes.addressof(d), a, ctypes.addressof(ps), a, a, a, 1 << 24, None) == -2
     d.kind = 7
     assert L.tsm_block_fwd(ctypes.addressof(d), a, ctypes.addressof(ps), a, a, a, 1 << 24, None) == -9
+
+
+def _r50_desc(**kw):
+    v = dict(N=1, T=2, size=32, num_classes=10, fold_div=8, lr=0.01, momentum=0.9, weight_decay=1e-4, bn_eps=1e-5,
+             bn_momentum=0.1, dtype=B.TSM_BF16)
+    v.update(kw)
+    return B.R50Desc(**v)
+
+
+def test_network_entry_points_argument_errors():
+    """Argument checks of the whole-network entry points come before any GPU work."""
+    L = B.lib()
+    a = 4096   # fake, aligned, never dereferenced
+    d = _r50_desc()
+    need_step, need_inf = B.tsm_resnet50_workspace_bytes(d), B.tsm_resnet50_infer_workspace_bytes(d)
+    assert need_step > need_inf > 0
+    da = ctypes.addressof(d)
+    assert L.tsm_resnet50_infer(None, a, a, a, a, a, need_inf, None) == -1
+    assert L.tsm_resnet50_infer(da, a, a, None, a, a, need_inf, None) == -1            # running statistics required
+    assert L.tsm_resnet50_infer(da, a, a, a, a, a, need_inf - 1, None) == -6
+    assert "workspace" in B.tsm_last_error()
+    assert L.tsm_resnet50_infer(da, a + 4, a, a, a, a, need_inf, None) == -7
+    for bad in (_r50_desc(size=40), _r50_desc(N=0), _r50_desc(fold_div=1), _r50_desc(dtype=5)):
+        assert B.tsm_resnet50_infer_workspace_bytes(bad) == 0 and B.tsm_resnet50_workspace_bytes(bad) == 0
+    assert L.tsm_resnet50_step(da, a, a, a, a, None, None, a, None, 1, a, need_step - 1, None) == -6
+    assert L.tsm_resnet50_step(da, a, None, a, a, None, None, a, None, 1, a, need_step, None) == -1
+    assert L.tsm_resnet50_accum_step(da, a, a, a, a, None, a, a, None, 2, 2, a, need_step, None) == -2  # index out of range
+    assert L.tsm_resnet50_accum_step(da, a, a, a, a, None, None, a, None, 0, 2, a, need_step, None) == -1
+    assert L.tsm_resnet50_accum_step(da, a, a, a, a, None, a + 4, a, None, 0, 2, a, need_step, None) == -7
