@@ -554,25 +554,29 @@ __global__ void __launch_bounds__(256) bn_eval_params_kernel(BnTable t, const fl
 // layers in one launch (the destination was zero-filled and nothing else writes it) ----------------------------
 struct UnpackTable {
     int n;
-    unsigned start[17];              // first element of entry l in the launch's flat index space (start[n] = total)
+    unsigned start[17];              // first (Cout, Cin) pair of entry l in the launch's flat index space (start[n] = total)
     unsigned src_off[16];            // float offset of the packed buffer from the base passed to the kernel
     unsigned dst_off[16];            // float offset into the gradient vector
     unsigned short cin[16], taps[16];
 };
 
+// One thread per (output channel, input channel) pair: its taps are read Cin floats apart (consecutive threads read
+// consecutive addresses) and written as one contiguous run.
 __global__ void __launch_bounds__(256) unpack_all_kernel(UnpackTable t, const float* __restrict__ packed,
                                                          float* __restrict__ grads) {
-    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;       // pair index in the launch's flat space
     if (i >= t.start[t.n]) return;
     int lo = 0, hi = t.n - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
         if (t.start[mid] <= i) lo = mid; else hi = mid - 1;
     }
-    const unsigned e = i - t.start[lo];            // destination index [co][ci][tap]
+    const unsigned e = i - t.start[lo];                       // co * Cin + ci
     const unsigned taps = t.taps[lo], Cin = t.cin[lo];
-    const unsigned tap = e % taps, ci = (e / taps) % Cin, co = e / (taps * Cin);
-    grads[t.dst_off[lo] + e] = packed[t.src_off[lo] + (co * taps + tap) * Cin + ci];
+    const unsigned ci = e % Cin, co = e / Cin;
+    const float* src = packed + t.src_off[lo] + (size_t)co * taps * Cin + ci;
+    float* dst = grads + t.dst_off[lo] + (size_t)e * taps;
+    for (unsigned tap = 0; tap < taps; ++tap) dst[tap] = src[(size_t)tap * Cin];
 }
 
 // ---- SGD with momentum; weight decay only inside "decay" segments -----------------------------
@@ -830,7 +834,7 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
                 unp.dst_off[l] = (unsigned)(sd.dw - grads);
                 unp.cin[l] = (unsigned short)sd.p.Cin;
                 unp.taps[l] = (unsigned short)sd.p.taps();
-                unp.start[l + 1] = unp.start[l] + (unsigned)n;
+                unp.start[l + 1] = unp.start[l] + (unsigned)(n / sd.p.taps());
             }
         }
         dwp_bytes = A.used - used0;
