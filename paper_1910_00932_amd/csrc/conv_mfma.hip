@@ -1084,14 +1084,16 @@ static int launch_igemm_ring(IgemmArgs& a, const char* name, hipStream_t s) {
 // most 64 channels) takes every layer whose source channels are a multiple of 64 and whose tensors stay below
 // the 2 GiB that its 32-bit buffer offsets address; the rest goes to the register-prefetch kernels, two blocks
 // per CU: 128x64 tiles for narrow outputs (<= 64 channels), 128x128 otherwise.
-static bool ring_eligible(int Cs, long src_elems, long w_elems) {
-    static int enabled = -1;   // TSM_IGEMM_RING=0 keeps the register-prefetch kernels everywhere (for comparisons)
+// `needed`: the layer has a pixel pitch other than its channel count (the stem in space-to-depth form), which only
+// this kernel handles, so the comparison switch does not apply to it.
+static bool ring_eligible(int Cs, long src_elems, long w_elems, bool needed) {
+    static int enabled = -1;   // TSM_IGEMM_RING=0 keeps the register-prefetch kernels wherever they can run (for comparisons)
     if (enabled < 0) {
         const char* e = getenv("TSM_IGEMM_RING");
         enabled = (e && e[0] == '0') ? 0 : 1;
     }
     const long limit = 0x7ff00000L;   // bytes, leaves room for the padding bias in front of the tensor
-    return enabled && Cs % BK == 0 && src_elems * 2 < limit && w_elems * 2 < limit;
+    return (enabled || needed) && Cs % BK == 0 && src_elems * 2 < limit && w_elems * 2 < limit;
 }
 
 // Rows per tile of the ring kernel: 256, or 128 when 256-row tiles would leave a good part of the CUs without
@@ -1112,7 +1114,7 @@ template <bool DGRAD>
 static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     const long rows = (long)a.F * a.Hd * a.Wd;
     if (rows == 0) return TSM_OK;
-    if (ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K)) {
+    if (ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K, a.pitch != a.Cs)) {
         if (ring_rows(rows, a.Cd) == 128) {
             if (a.Cd <= 64) return launch_igemm_ring<128, 64, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_r128x64" : "igemm_fwd_r128x64", s);
             return launch_igemm_ring<128, 128, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_r128x128" : "igemm_fwd_r128x128", s);
@@ -1127,7 +1129,7 @@ static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
 
 int conv_mfma_fwd_blocks(const ConvP& p) {
     const int bn = p.Cout <= 64 ? 64 : 128;
-    if (ring_eligible(p.Cin, p.rows_in() * (long)p.pix_pitch() + p.Cin + (long)(p.pad * p.W + p.pad) * p.pix_pitch(), (long)p.Cout * p.K()))
+    if (ring_eligible(p.Cin, p.rows_in() * (long)p.pix_pitch() + p.Cin + (long)(p.pad * p.W + p.pad) * p.pix_pitch(), (long)p.Cout * p.K(), p.pix_pitch() != p.Cin))
     {
         const int bm = ring_rows(p.rows_out(), p.Cout);
         return igemm_grid((int)((p.rows_out() + bm - 1) / bm), p.Cout, bn, 1);
@@ -1136,7 +1138,8 @@ int conv_mfma_fwd_blocks(const ConvP& p) {
 }
 
 bool conv_mfma_fwd_can_fuse(const ConvP& p) {
-    return ring_eligible(p.Cin, p.rows_in() * (long)p.pix_pitch() + p.Cin + (long)(p.pad * p.W + p.pad) * p.pix_pitch(), (long)p.Cout * p.K());
+    return ring_eligible(p.Cin, p.rows_in() * (long)p.pix_pitch() + p.Cin + (long)(p.pad * p.W + p.pad) * p.pix_pitch(), (long)p.Cout * p.K(),
+                         p.pix_pitch() != p.Cin);
 }
 
 int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, float* stats, const FwdEpilogue* ep,
@@ -1172,7 +1175,7 @@ static void dgrad_args(const ConvP& p, IgemmArgs& a) {
 int conv_mfma_dgrad_blocks(const ConvP& p) {
     IgemmArgs a;
     dgrad_args(p, a);
-    if (!ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K)) return 0;
+    if (!ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K, a.pitch != a.Cs)) return 0;
     if ((long)a.F * a.Hd * a.Wd == 0) return 0;
     const int mtiles = setup_classes(a, true, ring_rows((long)a.F * a.Hd * a.Wd, a.Cd));
     return igemm_grid(mtiles, a.Cd, a.Cd <= 64 ? 64 : 128, 1);
@@ -1700,7 +1703,8 @@ int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw
         const long limit = 0x7ff00000L;
         const bool fits = a.M * p.Cout * 2 < limit &&
                           (p.rows_in() * (long)a.pitch + p.Cin + (long)(p.pad * p.W + p.pad) * a.pitch) * 2 < limit;
-        if (enabled && fits && cin_real == p.Cin && p.Cin % 64 == 0 && p.Cout % 64 == 0) {
+        // (a pixel pitch other than the channel count -- the stem in space-to-depth form -- only runs here)
+        if ((enabled || a.pitch != p.Cin) && fits && cin_real == p.Cin && p.Cin % 64 == 0 && p.Cout % 64 == 0) {
             // blocks per CU follow from the LDS footprint of two stages
             if (p.Cout % 256 == 0 && p.Cin % 128 == 0) return launch_wgrad_tr<256, 128, 4, 2>(a, p.Cout, 1, "wgrad_tr_256x128", s);
             if (p.Cout % 256 == 0) return launch_wgrad_tr<256, 64, 4, 1>(a, p.Cout, 1, "wgrad_tr_256x64", s);
