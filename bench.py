@@ -467,6 +467,16 @@ def main():
                     "bytes": "one read + one write of the tensor", "plain_copy_gbs": cp_gbs}
     del xs, ys
 
+    # what the matrix cores sustain with nothing in the way (register-only bf16 MFMAs), next to the published peak
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    B.tsm_mfma_probe(1000, sink, stream)
+    s0.record(stream)
+    probe_flops = B.tsm_mfma_probe(20000, sink, stream)
+    s1.record(stream)
+    torch.cuda.synchronize()
+    out["mfma_probe"] = {"achieved": probe_flops / (s0.elapsed_time(s1) * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
+                         "unit": "TFLOP/s", "kernel": "register-only v_mfma_f32_32x32x16_bf16, 8 wavefronts per CU"}
+
     if not args.no_cpu_baseline:
         from oracle import tsm_oracle as O
         P = O.unflatten_params(flat.astype(np.float64))

@@ -88,6 +88,16 @@ const char* tsm_last_error(void);
 int tsm_profile_begin(void* stream);
 int tsm_profile_end(char* report, size_t report_cap);
 
+/* Measurement aid, not part of the method: launches a kernel of register-only
+ * bf16 MFMAs (32x32x16, no memory traffic) on `stream` and writes the number
+ * of floating-point operations of that launch into the host variable
+ * *flops_out, so that a caller who times the launch reads the rate the matrix
+ * cores sustain on this chip next to the published peak.  `iters` (1 .. 2^24)
+ * MFMAs per accumulator chain; `sink` is a device float the kernel never
+ * writes in practice (it keeps the arithmetic alive).  TSM_ERR_SHAPE /
+ * TSM_ERR_NULLPTR on bad arguments, nothing is launched then. */
+int tsm_mfma_probe(int iters, float* sink, double* flops_out, void* stream);
+
 /* ------------------------------------------------------------------------
  * Temporal shift, stand-alone (section 2, Fig. 1: zero FLOPs, zero parameters).
  * y = S(x) / gx = S^T(gy); a pure copy, bit-exact for any 2- or 4-byte type.

@@ -20,7 +20,7 @@ STATUS = {0: "TSM_OK", -1: "TSM_ERR_NULLPTR", -2: "TSM_ERR_SHAPE", -3: "TSM_ERR_
           -5: "TSM_ERR_LAYOUT", -6: "TSM_ERR_WORKSPACE", -7: "TSM_ERR_ALIGN", -8: "TSM_ERR_LAUNCH",
           -9: "TSM_ERR_UNSUPPORTED"}
 
-EXPORTS = ["tsm_last_error", "tsm_profile_begin", "tsm_profile_end", "tsm_shift_fwd", "tsm_shift_bwd", "tsm_conv_workspace_bytes", "tsm_conv_fwd",
+EXPORTS = ["tsm_last_error", "tsm_profile_begin", "tsm_profile_end", "tsm_mfma_probe", "tsm_shift_fwd", "tsm_shift_bwd", "tsm_conv_workspace_bytes", "tsm_conv_fwd",
            "tsm_conv_dgrad", "tsm_conv_wgrad", "tsm_block_saved_bytes", "tsm_block_workspace_bytes",
            "tsm_block_fwd", "tsm_block_bwd", "tsm_resnet50_param_count", "tsm_resnet50_num_tensors",
            "tsm_resnet50_param_info", "tsm_resnet50_bn_state_count", "tsm_resnet50_workspace_bytes",
@@ -84,6 +84,7 @@ def lib():
         sig("tsm_last_error", ctypes.c_char_p, [])
         sig("tsm_profile_begin", ci, [vp])
         sig("tsm_profile_end", ci, [ctypes.c_char_p, sz])
+        sig("tsm_mfma_probe", ci, [ci, vp, ctypes.POINTER(ctypes.c_double), vp])
         for n in ("tsm_conv_workspace_bytes", "tsm_block_saved_bytes", "tsm_block_workspace_bytes",
                   "tsm_resnet50_workspace_bytes", "tsm_resnet50_infer_workspace_bytes"):
             sig(n, sz, [vp])
@@ -140,6 +141,13 @@ def tsm_last_error():
 
 def tsm_profile_begin(stream=None):
     _check(lib().tsm_profile_begin(_stream(stream)))
+
+
+def tsm_mfma_probe(iters, sink, stream=None):
+    """Launches the register-only MFMA kernel; returns the floating-point operations of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(lib().tsm_mfma_probe(int(iters), _ptr(sink), ctypes.byref(flops), _stream(stream)))
+    return flops.value
 
 
 def tsm_profile_end():

@@ -42,6 +42,14 @@ def test_shift_argument_errors():
     assert "overlap" in B.tsm_last_error()
 
 
+def test_probe_argument_errors():
+    L = B.lib()
+    flops = ctypes.c_double(0.0)
+    assert L.tsm_mfma_probe(0, 4096, ctypes.byref(flops), None) == -2
+    assert L.tsm_mfma_probe(10, None, ctypes.byref(flops), None) == -1
+    assert L.tsm_mfma_probe(10, 4096, None, None) == -1
+
+
 def test_conv_argument_errors():
     L = B.lib()
     a = 4096

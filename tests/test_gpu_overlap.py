@@ -1,6 +1,14 @@
 """The backward entry points run their weight gradients on a second stream; TSM_WGRAD_OVERLAP=0 keeps one stream.
 Both settings must give the same step (the switch is read once per process, so each setting runs in a process
-of its own; results differ only by the order of the atomic sums of the weight gradients)."""
+of its own; results differ only by the order of the atomic sums of the weight gradients).
+
+What is compared, and why not a training run: the atomic sums leave the gradients of two runs a few 1e-8 apart,
+whatever the streams, and this small configuration (2 clips, 2x2 maps in the last stage) amplifies such a
+difference in the parameters to 1e-2 in the next step's gradients and to O(1) in the step after -- two runs of the
+SAME setting drift apart like that, in fp32 as in bf16 (seen in one process out of five).  So the steps that run
+back to back here, with no synchronisation in between -- the sequence that would expose a missing wait between
+the tail of one step and the head of the next -- use learning rate 0: every step sees the same parameters, the
+momentum buffer still accumulates all gradients, and one last step applies the update."""
 import os
 import subprocess
 import sys
@@ -19,31 +27,33 @@ import numpy as np, torch
 from paper_1910_00932_amd import binding as B
 from paper_1910_00932_amd import inputs as I
 N, T, S = 2, 4, 64
+bf = sys.argv[2] == "bf16"
 table = B.tsm_resnet50_param_table(400)
 flat = I.init_params([(n, s) for n, _, s, _ in table], 1)
-d = B.R50Desc(N=N, T=T, size=S, num_classes=400, fold_div=8, lr=0.01, momentum=0.9, weight_decay=1e-4, bn_eps=1e-5,
-              bn_momentum=0.1, dtype=B.TSM_BF16)
-ws = torch.empty(B.tsm_resnet50_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+desc = lambda lr: B.R50Desc(N=N, T=T, size=S, num_classes=400, fold_div=8, lr=lr, momentum=0.9, weight_decay=1e-4,
+                            bn_eps=1e-5, bn_momentum=0.1, dtype=B.TSM_BF16 if bf else B.TSM_F32)
+ws = torch.empty(B.tsm_resnet50_workspace_bytes(desc(0.0)), dtype=torch.uint8, device="cuda")
 params = torch.from_numpy(flat).cuda(); mom = torch.zeros_like(params); grads = torch.empty_like(params)
 loss = torch.zeros(1, dtype=torch.float32, device="cuda")
-clips = torch.from_numpy(I.clips(N, T, S, 0, "bf16")).to(torch.bfloat16).cuda()
+clips = torch.from_numpy(I.clips(N, T, S, 0, sys.argv[2])).to(torch.bfloat16 if bf else torch.float32).cuda()
 labels = torch.from_numpy(I.labels(N)).cuda()
-for _ in range(3):     # three updates: any race between the streams would show in the parameters
-    B.tsm_resnet50_step(d, clips, labels, params, mom, None, grads, loss, None, 1, ws)
+for lr in (0.0, 0.0, 0.0, 0.01):     # back to back, no synchronisation in between
+    B.tsm_resnet50_step(desc(lr), clips, labels, params, mom, None, grads, loss, None, 1, ws)
 torch.cuda.synchronize()
-np.save(sys.argv[1], np.concatenate([params.cpu().numpy(), grads.cpu().numpy(), [float(loss.item())]]))
+np.save(sys.argv[1], np.concatenate([params.cpu().numpy(), mom.cpu().numpy(), grads.cpu().numpy(), [float(loss.item())]]))
 """ % (ROOT, os.path.join(ROOT, "tests"))
 
 
-def _run(tmp_path, overlap):
-    out = str(tmp_path / ("step_%s.npy" % overlap))
+def _run(tmp_path, overlap, dtype):
+    out = str(tmp_path / ("step_%s_%s.npy" % (dtype, overlap)))
     env = dict(os.environ, TSM_WGRAD_OVERLAP=overlap)
-    subprocess.run([sys.executable, "-c", SCRIPT, out], check=True, env=env, timeout=300)
+    subprocess.run([sys.executable, "-c", SCRIPT, out, dtype], check=True, env=env, timeout=300)
     return np.load(out)
 
 
-def test_one_stream_and_two_streams_agree(tmp_path):
-    a, b = _run(tmp_path, "1"), _run(tmp_path, "0")
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_one_stream_and_two_streams_agree(tmp_path, dtype):
+    a, b = _run(tmp_path, "1", dtype), _run(tmp_path, "0", dtype)
     assert np.all(np.isfinite(a)) and np.all(np.isfinite(b))
     rel = np.linalg.norm(a - b) / np.linalg.norm(b)
     assert rel < 1e-5, rel
