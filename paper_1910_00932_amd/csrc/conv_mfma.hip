@@ -15,6 +15,8 @@
 // v_mfma_f32_32x32x16_bf16, operands staged through LDS, fp32 accumulation.  Kernels:
 //   igemm_ring_kernel  fwd/dgrad, source channels % 64 == 0: 256 x {128,64} tile, eight wavefronts,
 //                      buffer-load gathers, loads and LDS stores spread over the MFMA groups
+//   conv3x3_c64_kernel fwd/dgrad, 3x3 stride 1, 64 -> 64 channels, many tiles: weights and the tile's input patch
+//                      resident in LDS, no barrier inside a tile's main loop
 //   igemm_kernel       fwd/dgrad, any channel count % 8 == 0: 128 x {128,64} tile, four wavefronts,
 //                      register prefetch (the fallback)
 //   wgrad_tr_kernel    wgrad, channels % 64 == 0: operands read with the transposing LDS load
@@ -964,6 +966,300 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
+// 3x3, stride 1, pad 1, 64 -> 64 channels, no shift: the middle convolution of the first stage (and its data
+// gradient, which is the same convolution with the flipped, transposed weights).  These layers have the most
+// pixels per FLOP of all 3x3 layers (56x56 maps) and K = 576 is only nine steps, so in the general kernel above
+// they pay nine gathers of the input and a barrier per 16 MFMAs.  Here everything a tile needs sits in LDS:
+//
+//  * the weights of all nine taps (72 KB), loaded once per block and kept for all of its tiles;
+//  * the tile's input patch: the 256 pixels of the tile are consecutive rows of the [pixel][64] tensor, and
+//    the neighbours (h + th - 1, w + tw - 1) of pixel p are rows p + (th - 1) * W + (tw - 1), so the patch is
+//    the row range [p0 - W - 1, p0 + 256 + W + 1), read from memory once.  A tap is then a row offset into the
+//    patch, the same for every lane; the lanes whose neighbour lies outside the frame read a row of zeros
+//    instead (one select on the address per tap, no select on the data);
+//  * patch rows are 144 bytes apart (128 + 16): the rows of 16 consecutive pixels then fall 36 banks apart and
+//    a fragment read is conflict-free at every tap offset, which a swizzle tied to the row number is not.
+//
+// The main loop of a tile has no barrier and no global load of its own: while it runs, the next tile's patch
+// is fetched into registers (six 16-byte pieces per thread) and written to LDS after the last MFMA.
+static constexpr int C64_BM = 256;                            // pixels per tile
+static constexpr int C64_WMAX = 57;                           // widest map: the patch has BM + 2 * (W + 1) rows
+static constexpr int C64_PROW = 144;                          // bytes per patch row
+static constexpr int C64_PR = C64_BM + 2 * (C64_WMAX + 1);    // patch rows at the widest map
+static constexpr int C64_NPP = (C64_PR * 8 + 511) / 512;      // 16-byte patch pieces per thread
+static constexpr int C64_W_BYTES = 9 * 64 * 128;
+static constexpr int C64_PATCH_BYTES = C64_PR * C64_PROW;
+static constexpr int C64_ZERO_BYTES = 160;                    // a fragment's reach from the zero row: 16 + 3 * 32 + 16
+static constexpr int C64_LDC = 64 + 8;                        // staging pitch (elements)
+static constexpr int C64_CST_BYTES = 128 * C64_LDC * 2;
+static constexpr int C64_PART_BYTES = 2 * 8 * 64 * 4;
+static constexpr int C64_SMEM = C64_W_BYTES + C64_PATCH_BYTES + C64_ZERO_BYTES + C64_CST_BYTES + C64_PART_BYTES;
+static_assert(C64_SMEM <= 160 * 1024, "LDS budget");
+static_assert(C64_PATCH_BYTES % 16 == 0 && C64_ZERO_BYTES % 16 == 0 && C64_CST_BYTES % 16 == 0, "alignment");
+
+template <bool DGRAD, bool STREAM>
+__global__ void __launch_bounds__(512) conv3x3_c64_kernel(IgemmArgs a) {
+    constexpr int NT = 512, BM = C64_BM, BN = 64, MI = 2, HM = 128, LDC = C64_LDC, PROW = C64_PROW, NPP = C64_NPP;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* s_w = smem;                                    // [9][64][8 positions of 16 bytes], swizzled
+    unsigned char* s_patch = smem + C64_W_BYTES;                  // [patch rows][144 bytes]
+    constexpr int ZERO_OFF = C64_PATCH_BYTES;                     // the zero row, as an offset from s_patch
+    bf16_t* Cst = (bf16_t*)(s_patch + C64_PATCH_BYTES + C64_ZERO_BYTES);   // [128][LDC] staging tile of the epilogue
+    float* s_part = (float*)((unsigned char*)Cst + C64_CST_BYTES);         // [2 stats][8 wavefronts][64]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;        // wavefront: rows wm*32 (+128 for the second row block), channels wn*32
+    const int r = lane & 31, hi = lane >> 5;
+    const int W = a.Ws, H = a.Hs, hw = H * W;
+    const unsigned M = (unsigned)a.F * (unsigned)hw;              // pixels (source and destination maps coincide)
+    const int mtiles = (int)((M + BM - 1) / BM);
+    const bool do_stats = !DGRAD && a.stats != nullptr;
+    const bool fuse_mask = DGRAD && a.act != nullptr;
+    const bool fuse_bn = fuse_mask && a.ybn != nullptr;
+    const bool affine = !DGRAD && a.ep_scale != nullptr;
+
+    float* prow = (do_stats || fuse_bn) ? a.stats + (size_t)blockIdx.x * 2 * BN : nullptr;
+    if (prow && tid < 2 * BN) prow[tid] = 0.f;
+
+    // ---- weights and the zero row
+    {
+        const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.wp, (uint32_t)(BN * 9 * 64 * 2));
+#pragma unroll
+        for (int s = 0; s < 9; ++s) {
+            const int q = tid + s * NT;                           // piece: tap s, channel row n, position pos
+            const int n = (q >> 3) & 63, pos = q & 7, kv = pos ^ ((n >> 1) & 7);
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, n * (9 * 128) + s * 128 + kv * 16, 0, 0);
+            *(u32x4*)(s_w + q * 16) = v;
+        }
+        if (tid < C64_ZERO_BYTES / 16) *(u32x4*)(s_patch + ZERO_OFF + tid * 16) = u32x4{0u, 0u, 0u, 0u};
+    }
+
+    // ---- the patch producer.  Row j of the patch is row p0 + j of the buffer, which starts W + 1 rows before
+    // the tensor (rows in front of the tensor and behind its end are never fetched: they read as zeros).
+    const int lead = W + 1;
+    const int npieces = (BM + 2 * lead) * 8;
+    const __amdgpu_buffer_rsrc_t rsrc_a =
+        make_rsrc(a.src - (long)lead * 64, (uint32_t)(((long)M + lead) * 128));
+    u32x4 preg[NPP];
+    auto load_patch = [&](int tile) {
+        const unsigned p0 = (unsigned)tile * BM;
+#pragma unroll
+        for (int s = 0; s < NPP; ++s) {
+            const int q = tid + s * NT;
+            const unsigned row = p0 + (unsigned)(q >> 3);
+            const bool ok = q < npieces && row >= (unsigned)lead;
+            preg[s] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, ok ? (int)(row * 128u + (unsigned)(q & 7) * 16u) : (int)OOB_OFFSET, 0, 0);
+        }
+    };
+    auto store_patch = [&]() {
+#pragma unroll
+        for (int s = 0; s < NPP; ++s) {
+            const int q = tid + s * NT;
+            if (q < npieces) *(u32x4*)(s_patch + (q >> 3) * PROW + (q & 7) * 16) = preg[s];
+        }
+    };
+
+    // ---- fragment addresses: weights row (lane % 32) of the wavefront's channel block, K vector 2*ks + lane/32 at
+    // its swizzled position; patch row (lane % 32) of the wavefront's row block (tap offset added per tap)
+    int b_rd[4], a_base[MI];
+    {
+        const int n = wn * 32 + r;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) b_rd[ks] = n * 128 + (((2 * ks + hi) ^ ((n >> 1) & 7)) * 16);
+#pragma unroll
+        for (int i = 0; i < MI; ++i) a_base[i] = (i * HM + wm * 32 + r) * PROW + hi * 16;
+    }
+    const int zero_addr = ZERO_OFF + hi * 16;
+
+    constexpr int FV = 8, CV = BN / 8, RPS = NT / CV, NPS = HM / RPS;
+    float f1[FV], f2[FV];
+#pragma unroll
+    for (int q = 0; q < FV; ++q) f1[q] = f2[q] = 0.f;
+    const int vcol = tid % CV, r0 = tid / CV;
+    // the eight channels this thread stores: BatchNorm mean / rstd of a fused data gradient, or scale / shift of an
+    // affine forward epilogue
+    float mu[FV], rs[FV];
+#pragma unroll
+    for (int q = 0; q < FV; ++q) mu[q] = rs[q] = 0.f;
+    if (fuse_bn || affine) {
+#pragma unroll
+        for (int q = 0; q < FV; ++q) {
+            mu[q] = DGRAD ? a.bn_mean[vcol * 8 + q] : a.ep_scale[vcol * 8 + q];
+            rs[q] = DGRAD ? a.bn_rstd[vcol * 8 + q] : a.ep_shift[vcol * 8 + q];
+        }
+    }
+
+    // Blocks are dealt round-robin over the eight XCDs, each with an L2 of its own: an XCD takes a contiguous eighth
+    // of the tiles, so that the patch rows a tile shares with its neighbours are found in that L2.
+    const bool by_xcd = (gridDim.x % 8) == 0;
+    const int per_xcd = by_xcd ? (mtiles + 7) / 8 : mtiles;
+    const int xcd = by_xcd ? (int)(blockIdx.x % 8) : 0;
+    const int seq_step = by_xcd ? (int)(gridDim.x / 8) : (int)gridDim.x;
+    auto tile_at = [&](int seq) {
+        const int t = xcd * per_xcd + seq;
+        return (seq < per_xcd && t < mtiles) ? t : -1;
+    };
+    int seq = by_xcd ? (int)(blockIdx.x / 8) : (int)blockIdx.x;
+    int tile = tile_at(seq);
+    if (tile >= 0) load_patch(tile);
+    __syncthreads();                      // weights, zero row, statistics row
+    if (tile >= 0) store_patch();
+
+    while (tile >= 0) {
+        seq += seq_step;
+        const int ntile = tile_at(seq);
+        __syncthreads();                  // this tile's patch is in LDS
+
+        // which of the nine neighbours of this lane's pixels lie inside the frame (bit th*3 + tw)
+        unsigned vmask[MI];
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const unsigned P = (unsigned)tile * BM + (unsigned)(i * HM + wm * 32 + r);
+            unsigned m = 0;
+            if (P < M) {
+                const int q = (int)(P % (unsigned)hw);
+                const int h = q / W, w = q - h * W;
+                const unsigned rows_ok = (h > 0 ? 1u : 0u) | 2u | (h + 1 < H ? 4u : 0u);
+                const unsigned cols_ok = (w > 0 ? 1u : 0u) | 2u | (w + 1 < W ? 4u : 0u);
+#pragma unroll
+                for (int th = 0; th < 3; ++th)
+                    if (rows_ok >> th & 1u) m |= cols_ok << (3 * th);
+            }
+            vmask[i] = m;
+        }
+
+        f32x16 acc[MI];
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+
+        if (ntile >= 0) load_patch(ntile);   // lands in registers while this tile is multiplied
+
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) {
+            const int toff = ((tap / 3) * W + (tap % 3)) * PROW;
+            int a_addr[MI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) a_addr[i] = (vmask[i] >> tap & 1u) ? a_base[i] + toff : zero_addr;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const bf16x8 bfr = *(const bf16x8*)(s_w + tap * (64 * 128) + b_rd[ks]);
+                bf16x8 af[MI];
+#pragma unroll
+                for (int i = 0; i < MI; ++i) af[i] = *(const bf16x8*)(s_patch + a_addr[i] + ks * 32);
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+                    // operands swapped as in igemm_ring_kernel: the result block is [channel][pixel]
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr, af[i], acc[i], 0, 0, 0);
+            }
+        }
+
+        __syncthreads();                  // every wavefront has read its last fragment of the patch
+        if (ntile >= 0) store_patch();
+
+        // ---- epilogue, one pass per row block through the staging tile
+#pragma unroll
+        for (int h = 0; h < MI; ++h) {
+            if (h > 0) __syncthreads();
+            {
+                // lane: pixel lane % 32 of the wavefront's rows, channels 8*q + 4*(lane / 32) + {0..3} of its channel block
+                bf16_t* dstp = Cst + (wm * 32 + r) * LDC + wn * 32 + 4 * hi;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint2 w2;
+                    w2.x = pack_bf16x2(acc[h][4 * q], acc[h][4 * q + 1]);
+                    w2.y = pack_bf16x2(acc[h][4 * q + 2], acc[h][4 * q + 3]);
+                    *(uint2*)(dstp + 8 * q) = w2;
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int pss = 0; pss < NPS; ++pss) {
+                const int row = pss * RPS + r0;
+                const unsigned P = (unsigned)tile * BM + (unsigned)(h * HM + row);
+                if (P >= M) continue;
+                u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
+                const long e = (long)P * BN + vcol * 8;
+                if (!DGRAD) {
+                    if (do_stats) {   // statistics of the values as stored
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const float lo = __uint_as_float(v[q] << 16), hi2 = __uint_as_float(v[q] & 0xffff0000u);
+                            f1[2 * q] += lo;
+                            f1[2 * q + 1] += hi2;
+                            f2[2 * q] = fmaf(lo, lo, f2[2 * q]);
+                            f2[2 * q + 1] = fmaf(hi2, hi2, f2[2 * q + 1]);
+                        }
+                    }
+                    if (affine) {
+                        u32x4 rr = u32x4{0u, 0u, 0u, 0u};
+                        if (a.ep_res) rr = *(const u32x4*)(a.ep_res + e);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            float lo = fmaf(__uint_as_float(v[q] << 16), mu[2 * q], rs[2 * q]) + __uint_as_float(rr[q] << 16);
+                            float hi2 = fmaf(__uint_as_float(v[q] & 0xffff0000u), mu[2 * q + 1], rs[2 * q + 1]) + __uint_as_float(rr[q] & 0xffff0000u);
+                            if (a.ep_relu) {
+                                lo = lo > 0.f ? lo : 0.f;
+                                hi2 = hi2 > 0.f ? hi2 : 0.f;
+                            }
+                            v[q] = pack_bf16x2(lo, hi2);
+                        }
+                    }
+                } else if (fuse_mask) {   // ReLU mask of the layer below and its BatchNorm-backward sums, on the values as stored
+                    const u32x4 ac = *(const u32x4*)(a.act + e);
+                    u32x4 yy = u32x4{0u, 0u, 0u, 0u};
+                    if (fuse_bn) yy = *(const u32x4*)(a.ybn + e);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float alo = __uint_as_float(ac[q] << 16), ahi = __uint_as_float(ac[q] & 0xffff0000u);
+                        const float dlo = alo > 0.f ? __uint_as_float(v[q] << 16) : 0.f;
+                        const float dhi = ahi > 0.f ? __uint_as_float(v[q] & 0xffff0000u) : 0.f;
+                        v[q] = (alo > 0.f ? v[q] & 0xffffu : 0u) | (ahi > 0.f ? v[q] & 0xffff0000u : 0u);
+                        f1[2 * q] += dlo;
+                        f1[2 * q + 1] += dhi;
+                        f2[2 * q] = fmaf(dlo, (__uint_as_float(yy[q] << 16) - mu[2 * q]) * rs[2 * q], f2[2 * q]);
+                        f2[2 * q + 1] = fmaf(dhi, (__uint_as_float(yy[q] & 0xffff0000u) - mu[2 * q + 1]) * rs[2 * q + 1], f2[2 * q + 1]);
+                    }
+                }
+                u32x4* dq = (u32x4*)(a.dst + e);
+                if (STREAM) __builtin_nontemporal_store(v, dq);
+                else *dq = v;
+            }
+        }
+        tile = ntile;
+    }
+
+    if (do_stats || fuse_bn) {
+        // lanes CV apart hold the same columns: fold them, then one slot per wavefront, fixed order over the slots
+#pragma unroll
+        for (int q = 0; q < FV; ++q) {
+#pragma unroll
+            for (int off = CV; off < 64; off <<= 1) {
+                f1[q] += __shfl_xor(f1[q], off);
+                f2[q] += __shfl_xor(f2[q], off);
+            }
+        }
+        __syncthreads();
+        if (lane < CV) {
+#pragma unroll
+            for (int q = 0; q < FV; ++q) {
+                s_part[wave * BN + lane * 8 + q] = f1[q];
+                s_part[(8 + wave) * BN + lane * 8 + q] = f2[q];
+            }
+        }
+        __syncthreads();
+        if (tid < 2 * BN) {
+            const int stat = tid / BN, col = tid % BN;
+            float v = 0.f;
+#pragma unroll
+            for (int sl = 0; sl < 8; ++sl) v += s_part[(stat * 8 + sl) * BN + col];
+            prow[stat * BN + col] += v;   // (this block's row: zeroed above by the same thread)
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
 static int g_num_cu = 0;
 static int num_cu() {
     if (g_num_cu == 0) {
@@ -1110,10 +1406,50 @@ static int ring_rows(long rows, int Cd) {
     return tiles256 * 4 < (long)num_cu() * 3 ? 128 : 256;
 }
 
+// The 64 -> 64 channel 3x3 kernel takes the layers it is written for when the general kernel would run them with
+// 256-row tiles (the two then launch the same number of blocks, which is what callers size the statistics rows by)
+// and there are at least five rounds of tiles: every block first loads all weights and a tile is long, so with
+// three rounds (8 clips) the general kernel is 1 % of the step faster, with six (16 clips) the two are level, with
+// 24 (64 clips) this one saves 1.1 % of the step.  TSM_CONV3X3_C64=0 leaves these layers to the general kernel,
+// TSM_CONV3X3_C64_MIN_TILES=<n> moves the threshold (both read at every call: tests and comparisons set them).
+static bool c64_eligible(const IgemmArgs& a) {
+    const char* e = getenv("TSM_CONV3X3_C64");
+    const bool enabled = !(e && e[0] == '0');
+    const char* t = getenv("TSM_CONV3X3_C64_MIN_TILES");
+    const long min_tiles = t ? atol(t) : 5L * num_cu();
+    const long rows = (long)a.F * a.Hd * a.Wd;
+    return enabled && (rows + C64_BM - 1) / C64_BM >= min_tiles && a.Cs == 64 && a.Cd == 64 && a.pitch == 64 && a.KT == 1 && a.KH == 3 && a.KW == 3 && a.stride == 1 &&
+           a.padh == 1 && a.padw == 1 && a.fold == 0 && a.addend == nullptr && a.Hs == a.Hd && a.Ws == a.Wd &&
+           a.Ws <= C64_WMAX && (rows + a.Ws + 1) * 128 < 0x7ff00000L &&
+           ring_eligible(64, rows * 64 + 64 + (long)(a.Ws + 1) * 64, 64L * a.K, false) && ring_rows(rows, 64) == 256;
+}
+
+template <bool DGRAD, bool STREAM>
+static int launch_c64_s(IgemmArgs& a, hipStream_t s) {
+    auto kern = conv3x3_c64_kernel<DGRAD, STREAM>;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return fail(TSM_ERR_LAUNCH, "conv3x3_c64: cannot raise dynamic LDS limit");
+        configured = true;
+    }
+    const long rows = (long)a.F * a.Hd * a.Wd;
+    const int grid = igemm_grid((int)((rows + C64_BM - 1) / C64_BM), 64, 64, 1);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), C64_SMEM, s, a);
+    return check_launch(DGRAD ? "igemm_dgrad_c64" : "igemm_fwd_c64");
+}
+
+template <bool DGRAD>
+static int launch_c64(IgemmArgs& a, hipStream_t s) {
+    if ((long)a.F * a.Hd * a.Wd * a.Cd * 2 > (64L << 20)) return launch_c64_s<DGRAD, true>(a, s);
+    return launch_c64_s<DGRAD, false>(a, s);
+}
+
 template <bool DGRAD>
 static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     const long rows = (long)a.F * a.Hd * a.Wd;
     if (rows == 0) return TSM_OK;
+    if (c64_eligible(a)) return launch_c64<DGRAD>(a, s);
     if (ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K, a.pitch != a.Cs)) {
         if (ring_rows(rows, a.Cd) == 128) {
             if (a.Cd <= 64) return launch_igemm_ring<128, 64, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_r128x64" : "igemm_fwd_r128x64", s);

@@ -108,3 +108,48 @@ def test_fold_zero_equals_unshifted_and_shift_matters():
 def test_conv_full_size_layers(case):
     """Full-size layers in the launch configuration of the benchmark, every element against the oracle."""
     _run(case, "bf16", "nthwc")
+
+
+@pytest.mark.parametrize("case", [
+    (2, 8, 64, 55, 57, 64, 3, 1, 1, 0),      # widest map the kernel takes, H != W, ragged last tile
+    (16, 8, 64, 20, 20, 64, 3, 1, 1, 0),     # tiles that straddle frames (400 pixels per frame)
+])
+def test_conv3x3_c64_kernel_every_element(case, monkeypatch):
+    """The 64 -> 64 channel 3x3 kernel (forward with the statistics epilogue, data gradient) on sizes the oracle
+    covers element by element; the library would leave so few tiles to the general kernel, the threshold is moved."""
+    monkeypatch.setenv("TSM_CONV3X3_C64_MIN_TILES", "1")
+    B.tsm_profile_begin()
+    _run(case, "bf16", "nthwc")
+    classes = B.tsm_profile_end()
+    assert "igemm_fwd_c64" in classes and "igemm_dgrad_c64" in classes, sorted(classes)
+
+
+def test_conv3x3_c64_kernel_where_the_library_picks_it():
+    """112 frames of 56x56 (1372 tiles: the default dispatch takes the 64-channel kernel) against the oracle on the
+    first, a middle and the last frame; without shift the frames are independent."""
+    N, T, C, H = 14, 8, 64, 56
+    x = I.normal((N, T, C, H, H), 0, "bf16")
+    w = I.kaiming_conv((C, C, 3, 3), 1, "bf16")
+    dy = I.normal((N, T, C, H, H), 3, "bf16")
+    d = B.ConvDesc(N=N, T=T, Cin=C, H=H, W=H, Cout=C, kh=3, kw=3, stride=1, pad=1, fold_div=0, dtype=B.TSM_BF16,
+                   layout=B.TSM_NTHWC)
+    ws = workspace(B.tsm_conv_workspace_bytes(d))
+    y, dx = empty_act((N, T, C, H, H), "bf16", "nthwc"), empty_act((N, T, C, H, H), "bf16", "nthwc")
+    s1 = torch.empty(C, dtype=torch.float32, device="cuda")
+    s2 = torch.empty(C, dtype=torch.float32, device="cuda")
+    xd, wd, dyd = to_dev(x, "bf16", "nthwc"), dev_vec(w, "bf16"), to_dev(dy, "bf16", "nthwc")
+    B.tsm_profile_begin()
+    B.tsm_conv_fwd(d, xd, wd, y, s1, s2, ws)
+    B.tsm_conv_dgrad(d, dyd, wd, dx, ws)
+    classes = B.tsm_profile_end()
+    assert "igemm_fwd_c64" in classes and "igemm_dgrad_c64" in classes, sorted(classes)
+    yg, dxg = from_dev(y, "nthwc"), from_dev(dx, "nthwc")
+    w64 = w.astype(np.float64)
+    for f in (0, 57, N * T - 1):
+        n, t = divmod(f, T)
+        yo = O.conv_fwd(x[n:n + 1, t:t + 1].astype(np.float64), w64, 1, 1, 0)
+        assert rel_l2(yg[n:n + 1, t:t + 1], yo) < 2e-2, ("fwd", f)
+        dxo = O.conv_dgrad(dy[n:n + 1, t:t + 1].astype(np.float64), w64, H, H, 1, 1, 0)
+        assert rel_l2(dxg[n:n + 1, t:t + 1], dxo) < 2e-2, ("dgrad", f)
+    assert np.allclose(s1.cpu().numpy(), yg.sum(axis=(0, 1, 3, 4)), rtol=1e-3, atol=1e-2 * np.sqrt(N * T * H * H))
+    assert np.allclose(s2.cpu().numpy(), (yg ** 2).sum(axis=(0, 1, 3, 4)), rtol=1e-3)
