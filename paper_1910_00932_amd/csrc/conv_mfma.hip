@@ -534,6 +534,7 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
         int kt, th, tw, chb, ltap;   // next K step to fetch: class-local tap, first channel of the step, flat tap
     };
 
+    const bool pointwise = a.KT == 1 && a.KH == 1 && a.KW == 1 && a.stride == 1 && a.padh == 0 && a.padw == 0 && a.ncls == 1;
     auto decode_rows = [&](int tile, int rb) {
         if (tid < BM) {
             const int mt = tile_mt(tile);
@@ -547,7 +548,18 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
             info.off = 0;
             info.mask = 0;
             info.dst = -1;
-            if (m < Mc) {
+            if (m < Mc && pointwise) {
+                // 1x1, stride 1: source row = destination row = m; only the shift needs the frame's place in its clip
+                uint32_t mask = 1u | (1u << 8) | (1u << 30) | (1u << 31);
+                if (a.fold > 0) {
+                    const int t = (int)(m / (unsigned)hw_d) % a.T;
+                    if (t + 1 >= a.T) mask &= ~(1u << 30);
+                    if (t < 1) mask &= ~(1u << 31);
+                }
+                info.off = (long)m * a.pitch;
+                info.mask = mask;
+                info.dst = (int)m;
+            } else if (m < Mc) {
                 const int f = (int)(m / (unsigned)(hc * wc));
                 const int q = (int)(m - (unsigned)f * (unsigned)(hc * wc));
                 const int qh = (int)((unsigned)q / (unsigned)wc), qw = q - qh * wc;
