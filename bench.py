@@ -46,6 +46,8 @@ def igemm_class(kind, cd, cs, rows, taps=1, stride=1):
     """Kernel and tile the library picks for a forward ("fwd") or data-gradient ("dgrad") convolution that produces
     `rows` pixels of `cd` channels from `cs` source channels (tensors below 2 GiB, which holds for every workload
     here; 256 CUs)."""
+    if stride == "stem":      # the space-to-depth stem: its own kernel from five rounds of tiles on
+        return "igemm_fwd_stem" if -(-rows // 256) >= 5 * 256 else "igemm_fwd_256x64"
     if cs % 64 == 0:
         tiles256 = -(-rows // 256) * (1 if cd <= 64 else -(-cd // 128))
         r = "r128" if tiles256 * 4 < 256 * 3 else "256"
@@ -85,7 +87,7 @@ def class_work(F, size):
     for name, rin, cin, rout, cout, taps, has_dgrad in conv_layers(F, size):
         macs = float(rout) * cout * cin * taps
         stem = name == "conv1"   # runs in space-to-depth form: 64 "channels" x 4 taps, see the library
-        add(igemm_class("fwd", cout, 64 if stem else cin, rout, taps, 1 if rin == rout else 2), macs)
+        add(igemm_class("fwd", cout, 64 if stem else cin, rout, taps, "stem" if stem else (1 if rin == rout else 2)), macs)
         if has_dgrad:
             add(igemm_class("dgrad", cin, cout, rin, taps, 1 if rin == rout else 2), macs)
         add("wgrad_tr_64x256" if stem else wgrad_class(cout, cin, taps), macs)
@@ -105,7 +107,7 @@ def class_bytes(F, size):
         x_b, y_b = 2.0 * rin * cin, 2.0 * rout * cout
         if stem:   # the space-to-depth image: (size/2 + 3)^2 pixels of 16 values per frame
             x_b = 2.0 * F * (size // 2 + 3) ** 2 * 16
-        add(igemm_class("fwd", cout, 64 if stem else cin, rout, taps, 1 if rin == rout else 2), x_b + y_b)
+        add(igemm_class("fwd", cout, 64 if stem else cin, rout, taps, "stem" if stem else (1 if rin == rout else 2)), x_b + y_b)
         if has_dgrad:
             extra = x_b if name.endswith(".c1") else 0.0       # the shortcut gradient added in the epilogue
             # ReLU mask and BatchNorm sums of the layer below ride in the epilogue (two more tensors of the
@@ -260,7 +262,7 @@ def infer_workload(args, torch, B, I):
     work, byt = {}, {}
     for name, rin, cin, rout, cout, taps, _ in conv_layers(F, S):
         stem = name == "conv1"
-        cls = igemm_class("fwd", cout, 64 if stem else cin, rout, taps, 1 if rin == rout else 2)
+        cls = igemm_class("fwd", cout, 64 if stem else cin, rout, taps, "stem" if stem else (1 if rin == rout else 2))
         x_b = 2.0 * F * (S // 2 + 3) ** 2 * 16 if stem else 2.0 * rin * cin
         res_b = 2.0 * rout * cout if name.endswith(".c3") else 0.0     # the shortcut read by the epilogue
         work[cls] = work.get(cls, 0.0) + 2.0 * rout * cout * cin * taps

@@ -17,6 +17,7 @@
 //                      buffer-load gathers, loads and LDS stores spread over the MFMA groups
 //   conv3x3_c64_kernel fwd/dgrad, 3x3 stride 1, 64 -> 64 channels, many tiles: weights and the tile's input patch
 //                      resident in LDS, no barrier inside a tile's main loop
+//   stem_s2d_kernel    fwd of the stem in space-to-depth form, many tiles: the same scheme for its 4-row window
 //   igemm_kernel       fwd/dgrad, any channel count % 8 == 0: 128 x {128,64} tile, four wavefronts,
 //                      register prefetch (the fallback)
 //   wgrad_tr_kernel    wgrad, channels % 64 == 0: operands read with the transposing LDS load
@@ -1272,6 +1273,246 @@ __global__ void __launch_bounds__(512) conv3x3_c64_kernel(IgemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
+// The stem in its space-to-depth form (4 tap rows x 64 "channels" = 4 consecutive 16-value pixels, 64 output
+// channels, forward only): K = 256 is four steps, so in the general kernel a tile is all prologue and epilogue.
+// Same scheme as conv3x3_c64_kernel: the weights (32 KB) stay in LDS for all tiles of a block, the tile's input --
+// the pixel range from the first output pixel's window to the end of the last one's, read once -- sits in LDS as a
+// patch of 16-value pixels, a tap row is a pixel offset into it (the image carries its own zero border: no
+// masks), and the next tile's patch travels through registers meanwhile.  A patch pixel takes 48 bytes (32 + 16):
+// the fragment reads of 16 consecutive pixels then fall 12 banks apart, without conflicts.
+static constexpr int STEM_BM = 256;
+static constexpr int STEM_PPIX = 48;                          // bytes per patch pixel
+static constexpr int STEM_PMAX = 1280;                        // patch pixels (the host checks the geometry against it)
+static constexpr int STEM_NPP = (STEM_PMAX * 2 + 511) / 512;  // 16-byte patch pieces per thread
+static constexpr int STEM_W_BYTES = 4 * 64 * 128;
+static constexpr int STEM_PATCH_BYTES = STEM_PMAX * STEM_PPIX;
+static constexpr int STEM_SMEM = STEM_W_BYTES + STEM_PATCH_BYTES + C64_CST_BYTES + C64_PART_BYTES;
+static_assert(STEM_SMEM <= 160 * 1024, "LDS budget");
+
+template <bool STREAM>
+__global__ void __launch_bounds__(512) stem_s2d_kernel(IgemmArgs a) {
+    constexpr int NT = 512, BM = STEM_BM, BN = 64, MI = 2, HM = 128, LDC = C64_LDC, PPIX = STEM_PPIX, NPP = STEM_NPP;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* s_w = smem;                                    // [4][64][8 positions of 16 bytes], swizzled
+    unsigned char* s_patch = smem + STEM_W_BYTES;                 // [patch pixels][48 bytes]
+    bf16_t* Cst = (bf16_t*)(s_patch + STEM_PATCH_BYTES);
+    float* s_part = (float*)((unsigned char*)Cst + C64_CST_BYTES);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r = lane & 31, hi = lane >> 5;
+    const int Ws = a.Ws, Wd = a.Wd, hw_d = a.Hd * a.Wd, hw_s = a.Hs * a.Ws;
+    const unsigned M = (unsigned)a.F * (unsigned)hw_d;            // output pixels
+    const unsigned Min = (unsigned)a.F * (unsigned)hw_s;          // input pixels
+    const int mtiles = (int)((M + BM - 1) / BM);
+    const bool do_stats = a.stats != nullptr;
+    const bool affine = a.ep_scale != nullptr;
+
+    float* prow = do_stats ? a.stats + (size_t)blockIdx.x * 2 * BN : nullptr;
+    if (prow && tid < 2 * BN) prow[tid] = 0.f;
+
+    {
+        const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.wp, (uint32_t)(BN * 256 * 2));
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int q = tid + s * NT;                           // piece: tap row s, channel row n, position pos
+            const int n = (q >> 3) & 63, pos = q & 7, kv = pos ^ ((n >> 1) & 7);
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, n * 512 + s * 128 + kv * 16, 0, 0);
+            *(u32x4*)(s_w + q * 16) = v;
+        }
+    }
+
+    // input pixel (frame f, row h, column w of the input image) under output pixel P = (f, h, w)
+    auto pin_of = [&](unsigned P) {
+        const unsigned f = P / (unsigned)hw_d, q = P - f * (unsigned)hw_d;
+        const unsigned h = q / (unsigned)Wd, w = q - h * (unsigned)Wd;
+        return f * (unsigned)hw_s + h * (unsigned)Ws + w;
+    };
+    // the patch of a tile: input pixels [pin_of(first), pin_of(last) + 3 rows + 4), two 16-byte pieces per pixel
+    const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(a.src, (uint32_t)((long)Min * 32));
+    u32x4 preg[NPP];
+    auto load_patch = [&](int tile) {
+        const unsigned P0 = (unsigned)tile * BM;
+        const unsigned Pl = P0 + BM - 1 < M ? P0 + BM - 1 : M - 1;
+        const unsigned pin0 = pin_of(P0);
+        const int npx = (int)(pin_of(Pl) - pin0) + 3 * Ws + 4;
+#pragma unroll
+        for (int s = 0; s < NPP; ++s) {
+            const int q = tid + s * NT;
+            const bool ok = (q >> 1) < npx;   // (pixels behind the end of the tensor read as zeros)
+            preg[s] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, ok ? (int)((pin0 + (unsigned)(q >> 1)) * 32u + (unsigned)(q & 1) * 16u) : (int)OOB_OFFSET, 0, 0);
+        }
+    };
+    auto store_patch = [&]() {
+#pragma unroll
+        for (int s = 0; s < NPP; ++s) {
+            const int q = tid + s * NT;
+            *(u32x4*)(s_patch + (q >> 1) * PPIX + (q & 1) * 16) = preg[s];
+        }
+    };
+
+    int b_rd[4];
+    {
+        const int n = wn * 32 + r;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) b_rd[ks] = n * 128 + (((2 * ks + hi) ^ ((n >> 1) & 7)) * 16);
+    }
+
+    constexpr int FV = 8, CV = BN / 8, RPS = NT / CV, NPS = HM / RPS;
+    float f1[FV], f2[FV];
+#pragma unroll
+    for (int q = 0; q < FV; ++q) f1[q] = f2[q] = 0.f;
+    const int vcol = tid % CV, r0 = tid / CV;
+    float mu[FV], rs[FV];
+#pragma unroll
+    for (int q = 0; q < FV; ++q) mu[q] = rs[q] = 0.f;
+    if (affine) {
+#pragma unroll
+        for (int q = 0; q < FV; ++q) {
+            mu[q] = a.ep_scale[vcol * 8 + q];
+            rs[q] = a.ep_shift[vcol * 8 + q];
+        }
+    }
+
+    // an XCD takes a contiguous eighth of the tiles (see conv3x3_c64_kernel)
+    const bool by_xcd = (gridDim.x % 8) == 0;
+    const int per_xcd = by_xcd ? (mtiles + 7) / 8 : mtiles;
+    const int xcd = by_xcd ? (int)(blockIdx.x % 8) : 0;
+    const int seq_step = by_xcd ? (int)(gridDim.x / 8) : (int)gridDim.x;
+    auto tile_at = [&](int seq) {
+        const int t = xcd * per_xcd + seq;
+        return (seq < per_xcd && t < mtiles) ? t : -1;
+    };
+    int seq = by_xcd ? (int)(blockIdx.x / 8) : (int)blockIdx.x;
+    int tile = tile_at(seq);
+    if (tile >= 0) load_patch(tile);
+    __syncthreads();                      // weights, statistics row
+    if (tile >= 0) store_patch();
+
+    while (tile >= 0) {
+        seq += seq_step;
+        const int ntile = tile_at(seq);
+        __syncthreads();                  // this tile's patch is in LDS
+
+        // this lane's pixels: offset of their window's first pixel in the patch (rows beyond M compute on pixel 0)
+        int a_base[MI];
+        {
+            const unsigned P0 = (unsigned)tile * BM;
+            const unsigned pin0 = pin_of(P0);
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+                const unsigned P = P0 + (unsigned)(i * HM + wm * 32 + r);
+                a_base[i] = (P < M ? (int)(pin_of(P) - pin0) : 0) * PPIX + hi * 16;
+            }
+        }
+
+        f32x16 acc[MI];
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+
+        if (ntile >= 0) load_patch(ntile);   // lands in registers while this tile is multiplied
+
+#pragma unroll
+        for (int tap = 0; tap < 4; ++tap) {
+            const int toff = tap * Ws * PPIX;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {      // 16 of the tap row's 64 values: one pixel; lanes >= 32 take its second half
+                const bf16x8 bfr = *(const bf16x8*)(s_w + tap * (64 * 128) + b_rd[ks]);
+                bf16x8 af[MI];
+#pragma unroll
+                for (int i = 0; i < MI; ++i) af[i] = *(const bf16x8*)(s_patch + a_base[i] + toff + ks * PPIX);
+#pragma unroll
+                for (int i = 0; i < MI; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr, af[i], acc[i], 0, 0, 0);
+            }
+        }
+
+        __syncthreads();                  // every wavefront has read its last fragment of the patch
+        if (ntile >= 0) store_patch();
+
+#pragma unroll
+        for (int h = 0; h < MI; ++h) {
+            if (h > 0) __syncthreads();
+            {
+                bf16_t* dstp = Cst + (wm * 32 + r) * LDC + wn * 32 + 4 * hi;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint2 w2;
+                    w2.x = pack_bf16x2(acc[h][4 * q], acc[h][4 * q + 1]);
+                    w2.y = pack_bf16x2(acc[h][4 * q + 2], acc[h][4 * q + 3]);
+                    *(uint2*)(dstp + 8 * q) = w2;
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int pss = 0; pss < NPS; ++pss) {
+                const int row = pss * RPS + r0;
+                const unsigned P = (unsigned)tile * BM + (unsigned)(h * HM + row);
+                if (P >= M) continue;
+                u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
+                const long e = (long)P * BN + vcol * 8;
+                if (do_stats) {   // statistics of the values as stored
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float lo = __uint_as_float(v[q] << 16), hi2 = __uint_as_float(v[q] & 0xffff0000u);
+                        f1[2 * q] += lo;
+                        f1[2 * q + 1] += hi2;
+                        f2[2 * q] = fmaf(lo, lo, f2[2 * q]);
+                        f2[2 * q + 1] = fmaf(hi2, hi2, f2[2 * q + 1]);
+                    }
+                }
+                if (affine) {
+                    u32x4 rr = u32x4{0u, 0u, 0u, 0u};
+                    if (a.ep_res) rr = *(const u32x4*)(a.ep_res + e);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float lo = fmaf(__uint_as_float(v[q] << 16), mu[2 * q], rs[2 * q]) + __uint_as_float(rr[q] << 16);
+                        float hi2 = fmaf(__uint_as_float(v[q] & 0xffff0000u), mu[2 * q + 1], rs[2 * q + 1]) + __uint_as_float(rr[q] & 0xffff0000u);
+                        if (a.ep_relu) {
+                            lo = lo > 0.f ? lo : 0.f;
+                            hi2 = hi2 > 0.f ? hi2 : 0.f;
+                        }
+                        v[q] = pack_bf16x2(lo, hi2);
+                    }
+                }
+                u32x4* dq = (u32x4*)(a.dst + e);
+                if (STREAM) __builtin_nontemporal_store(v, dq);
+                else *dq = v;
+            }
+        }
+        tile = ntile;
+    }
+
+    if (do_stats) {
+#pragma unroll
+        for (int q = 0; q < FV; ++q) {
+#pragma unroll
+            for (int off = CV; off < 64; off <<= 1) {
+                f1[q] += __shfl_xor(f1[q], off);
+                f2[q] += __shfl_xor(f2[q], off);
+            }
+        }
+        __syncthreads();
+        if (lane < CV) {
+#pragma unroll
+            for (int q = 0; q < FV; ++q) {
+                s_part[wave * BN + lane * 8 + q] = f1[q];
+                s_part[(8 + wave) * BN + lane * 8 + q] = f2[q];
+            }
+        }
+        __syncthreads();
+        if (tid < 2 * BN) {
+            const int stat = tid / BN, col = tid % BN;
+            float v = 0.f;
+#pragma unroll
+            for (int sl = 0; sl < 8; ++sl) v += s_part[(stat * 8 + sl) * BN + col];
+            prow[stat * BN + col] += v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
 static int g_num_cu = 0;
 static int num_cu() {
     if (g_num_cu == 0) {
@@ -1457,11 +1698,50 @@ static int launch_c64(IgemmArgs& a, hipStream_t s) {
     return launch_c64_s<DGRAD, false>(a, s);
 }
 
+// The stem kernel: the space-to-depth stem (forward), under the same conditions as the 64-channel 3x3 kernel and
+// the same switches; the worst-case patch of a tile (output rows crossed, a frame boundary crossed) must fit.
+static bool stem_eligible(const IgemmArgs& a) {
+    const char* e = getenv("TSM_CONV3X3_C64");
+    const char* e2 = getenv("TSM_STEM_KERNEL");
+    const bool enabled = !(e && e[0] == '0') && !(e2 && e2[0] == '0');
+    const char* t = getenv("TSM_CONV3X3_C64_MIN_TILES");
+    const long min_tiles = t ? atol(t) : 5L * num_cu();
+    const long rows = (long)a.F * a.Hd * a.Wd;
+    if (!(enabled && a.Cs == 64 && a.Cd == 64 && a.pitch == 16 && a.KT == 1 && a.KH == 4 && a.KW == 1 && a.stride == 1 &&
+          a.padh == 0 && a.padw == 0 && a.fold == 0 && a.addend == nullptr && a.Hd == a.Hs - 3 && a.Wd == a.Ws - 3 && a.Wd >= 1 &&
+          a.Hd >= 1))
+        return false;
+    // A tile's patch runs from the first output pixel's window to the end of the last one's: the input rows under the
+    // output rows it crosses, three more per frame boundary it crosses, the three tap rows below, and less than a row.
+    const long hw_d = (long)a.Hd * a.Wd;
+    const long rows_crossed = (STEM_BM - 1) / a.Wd + 1, frames_crossed = (STEM_BM - 1) / hw_d + 1;
+    const long worst = (rows_crossed + 3 * frames_crossed) * a.Ws + (a.Wd - 1) + 3L * a.Ws + 4;
+    return worst <= STEM_PMAX && (rows + STEM_BM - 1) / STEM_BM >= min_tiles && (long)a.F * a.Hs * a.Ws * 32 < 0x7ff00000L &&
+           ring_eligible(64, (long)a.F * a.Hs * a.Ws * 16 + 64, 64L * a.K, true) && ring_rows(rows, 64) == 256;
+}
+
+template <bool STREAM>
+static int launch_stem_s(IgemmArgs& a, hipStream_t s) {
+    auto kern = stem_s2d_kernel<STREAM>;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return fail(TSM_ERR_LAUNCH, "stem_s2d: cannot raise dynamic LDS limit");
+        configured = true;
+    }
+    const long rows = (long)a.F * a.Hd * a.Wd;
+    const int grid = igemm_grid((int)((rows + STEM_BM - 1) / STEM_BM), 64, 64, 1);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), STEM_SMEM, s, a);
+    return check_launch("igemm_fwd_stem");
+}
+
 template <bool DGRAD>
 static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     const long rows = (long)a.F * a.Hd * a.Wd;
     if (rows == 0) return TSM_OK;
     if (c64_eligible(a)) return launch_c64<DGRAD>(a, s);
+    if (!DGRAD && stem_eligible(a))
+        return rows * a.Cd * 2 > (64L << 20) ? launch_stem_s<true>(a, s) : launch_stem_s<false>(a, s);
     if (ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K, a.pitch != a.Cs)) {
         if (ring_rows(rows, a.Cd) == 128) {
             if (a.Cd <= 64) return launch_igemm_ring<128, 64, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_r128x64" : "igemm_fwd_r128x64", s);

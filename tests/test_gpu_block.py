@@ -140,6 +140,17 @@ def test_config1_full_size_bottleneck():
     run_block("bottleneck", 8, 8, 256, 56, 56, 64, 256, 1, False, 8, "bf16", "nthwc")
 
 
+def test_config1_full_size_bottleneck_with_the_64_channel_kernel(monkeypatch):
+    """The same block with its 3x3 convolution on the 64-channel kernel (8 clips are fewer tiles than the library's
+    threshold for it, so the threshold is moved): forward with the statistics epilogue, data gradient with the ReLU
+    mask and the BatchNorm sums of the layer below in its epilogue, against the oracle like the run above."""
+    monkeypatch.setenv("TSM_CONV3X3_C64_MIN_TILES", "1")
+    B.tsm_profile_begin()
+    run_block("bottleneck", 8, 8, 256, 56, 56, 64, 256, 1, False, 8, "bf16", "nthwc")
+    classes = B.tsm_profile_end()
+    assert "igemm_fwd_c64" in classes and "igemm_dgrad_c64" in classes, sorted(classes)
+
+
 def test_config4_full_size_tsm_block():
     """The TSM block of configs[4] at its full size: x[8,8,1024,14,14] bf16, 1024 -> 256 -> 256 -> 1024."""
     run_block("bottleneck", 8, 8, 1024, 14, 14, 256, 1024, 1, False, 8, "bf16", "nthwc")
