@@ -22,6 +22,12 @@
  *    stream and can be recorded into a HIP graph (make the first call on a device
  *    outside stream capture).  TSM_WGRAD_OVERLAP=0 in the environment keeps
  *    everything on the caller's stream.
+ *  - Which kernel runs a convolution is the library's choice and does not change
+ *    what is computed.  For comparisons the environment can take choices away:
+ *    TSM_IGEMM_RING=0 / TSM_WGRAD_TR=0 (read once per process) fall back to the
+ *    kernels for channel counts that are not multiples of 64 wherever those can
+ *    run; TSM_CONV3X3_C64=0 and TSM_STEM_KERNEL=0 (read at every call) leave the
+ *    layers that have a kernel of their own to the general one.
  *  - Return value: TSM_OK or a negative tsm_status.  On error nothing has been
  *    launched (argument errors) or the stream's state is undefined
  *    (TSM_ERR_LAUNCH).  tsm_last_error() returns a host string describing the
