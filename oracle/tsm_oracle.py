@@ -27,6 +27,9 @@ What each function follows:
   ResBlock" (section 3, model (3)), 8 frames, no temporal pooling (Table 2),
   400 classes (section 4.1), SGD with weight decay 1e-4 that skips BatchNorm
   and bias parameters (section 4.1).
+* ``Gates`` -- not arithmetic of the method: a way to take the 0/1 decisions of
+  ReLU and max-pooling in the precision of the implementation under test while
+  all arithmetic stays plain fp64.
 
 Parity status: every function below is pinned by ``tests/test_oracle_*.py``
 (closed forms, adjoint identities, library special cases, finite differences,
@@ -270,6 +273,49 @@ def relu_bwd(dout, out):
     return dout * (out > 0)
 
 
+class Gates:
+    """The 0/1 decisions of a pass (which units a ReLU lets through, which window position a max-pool picks),
+    recorded in one pass and imposed on another.
+
+    A ReLU network's gradients are discontinuous in the forward values: an implementation that stores
+    activations in bf16 takes a few of these decisions differently from fp64 arithmetic, and every such unit
+    moves gradient entries by O(1).  Where floating point decides an integer, both sides of a comparison have to
+    take the decision in the same precision -- the kernel's.  So the block and network functions below accept a
+    `gates` object: with `record` set, the pass (typically the storage-emulating one, `q = round_bf16`) stores
+    its decisions under the names of the tensors; with `record` cleared, a pass (typically the plain fp64 one)
+    uses the stored decisions in place of its own comparisons: z = a * gate instead of max(a, 0), gradient
+    dout * gate, pooled value / routing at the recorded window position.  With gates=None nothing changes.
+    A pass that replays the decisions it would have taken itself reproduces the ungated pass bit for bit."""
+
+    def __init__(self):
+        self.store = {}
+        self.record = True
+
+    def flips(self, other):
+        """(decisions that differ, decisions) against another recorded set of the same network."""
+        diff = total = 0
+        for k, m in self.store.items():
+            diff += int((m != other.store[k]).sum())
+            total += m.size
+        return diff, total
+
+
+def _relu_g(a, gates, key):
+    """ReLU of `a`; records or replays the unit decisions under `key`."""
+    if gates is None:
+        return relu(a)
+    if gates.record:
+        gates.store[key] = a > 0
+        return relu(a)
+    return a * gates.store[key]
+
+
+def _relu_bwd_g(dout, out, gates, key):
+    if gates is None or gates.record:
+        return relu_bwd(dout, out)
+    return dout * gates.store[key]
+
+
 def _ident(a):
     return a
 
@@ -282,27 +328,27 @@ def _ident(a):
 # mode used to separate rounding drift from bugs).
 # ----------------------------------------------------------------------------
 
-def basic_block_fwd(x, p, fold_div=8, eps=1e-5, q=_ident):
+def basic_block_fwd(x, p, fold_div=8, eps=1e-5, q=_ident, gates=None, pre=""):
     """ReLU(BN(conv3x3(ReLU(BN(conv3x3(S(x)))))) + x); p: w1,g1,b1,w2,g2,b2."""
     c = {"x": x}
     c["y1"] = q(conv_fwd(x, p["w1"], 1, 1, fold_div))
     a1, c["bn1"] = bn_fwd(c["y1"], p["g1"], p["b1"], eps)
-    c["z1"] = q(relu(a1))
+    c["z1"] = q(_relu_g(a1, gates, pre + "z1"))
     c["y2"] = q(conv_fwd(c["z1"], p["w2"], 1, 1, 0))
     a2, c["bn2"] = bn_fwd(c["y2"], p["g2"], p["b2"], eps)
-    c["out"] = q(relu(a2 + x))
+    c["out"] = q(_relu_g(a2 + x, gates, pre + "out"))
     return c["out"], c
 
 
-def basic_block_bwd(dout, c, p, fold_div=8, q=_ident):
+def basic_block_bwd(dout, c, p, fold_div=8, q=_ident, gates=None, pre=""):
     g = {}
     H, W = c["x"].shape[3:]
-    da2 = q(relu_bwd(dout, c["out"]))
+    da2 = q(_relu_bwd_g(dout, c["out"], gates, pre + "out"))
     dy2, g["g2"], g["b2"] = bn_bwd(da2, c["bn2"], p["g2"])
     dy2 = q(dy2)
     g["w2"] = conv_wgrad(c["z1"], dy2, 3, 3, 1, 1, 0)
     dz1 = q(conv_dgrad(dy2, p["w2"], H, W, 1, 1, 0))
-    da1 = q(relu_bwd(dz1, c["z1"]))
+    da1 = q(_relu_bwd_g(dz1, c["z1"], gates, pre + "z1"))
     dy1, g["g1"], g["b1"] = bn_bwd(da1, c["bn1"], p["g1"])
     dy1 = q(dy1)
     g["w1"] = conv_wgrad(c["x"], dy1, 3, 3, 1, 1, fold_div)
@@ -310,7 +356,7 @@ def basic_block_bwd(dout, c, p, fold_div=8, q=_ident):
     return dx, g
 
 
-def bottleneck_fwd(x, p, stride=1, fold_div=8, eps=1e-5, q=_ident, temporal=False):
+def bottleneck_fwd(x, p, stride=1, fold_div=8, eps=1e-5, q=_ident, temporal=False, gates=None, pre=""):
     """1x1 -> 3x3(stride) -> 1x1, BN after each, ReLU after the first two, then
     ReLU(residual + shortcut).  p: w1,g1,b1,w2,g2,b2,w3,g3,b3 and, for a
     projection shortcut, wd,gd,bd (1x1 conv with the block's stride + BN).
@@ -322,10 +368,10 @@ def bottleneck_fwd(x, p, stride=1, fold_div=8, eps=1e-5, q=_ident, temporal=Fals
     else:
         c["y1"] = q(conv_fwd(x, p["w1"], 1, 0, fold_div))
     a1, c["bn1"] = bn_fwd(c["y1"], p["g1"], p["b1"], eps)
-    c["z1"] = q(relu(a1))
+    c["z1"] = q(_relu_g(a1, gates, pre + "z1"))
     c["y2"] = q(conv_fwd(c["z1"], p["w2"], stride, 1, 0))
     a2, c["bn2"] = bn_fwd(c["y2"], p["g2"], p["b2"], eps)
-    c["z2"] = q(relu(a2))
+    c["z2"] = q(_relu_g(a2, gates, pre + "z2"))
     c["y3"] = q(conv_fwd(c["z2"], p["w3"], 1, 0, 0))
     a3, c["bn3"] = bn_fwd(c["y3"], p["g3"], p["b3"], eps)
     if "wd" in p:
@@ -333,26 +379,26 @@ def bottleneck_fwd(x, p, stride=1, fold_div=8, eps=1e-5, q=_ident, temporal=Fals
         sc, c["bnd"] = bn_fwd(c["yd"], p["gd"], p["bd"], eps)
     else:
         sc = x
-    c["out"] = q(relu(a3 + sc))
+    c["out"] = q(_relu_g(a3 + sc, gates, pre + "out"))
     return c["out"], c
 
 
-def bottleneck_bwd(dout, c, p, stride=1, fold_div=8, q=_ident, temporal=False):
+def bottleneck_bwd(dout, c, p, stride=1, fold_div=8, q=_ident, temporal=False, gates=None, pre=""):
     g = {}
     H, W = c["x"].shape[3:]
     Hm, Wm = c["z1"].shape[3:]
     Ho, Wo = c["z2"].shape[3:]
-    da3 = q(relu_bwd(dout, c["out"]))
+    da3 = q(_relu_bwd_g(dout, c["out"], gates, pre + "out"))
     dy3, g["g3"], g["b3"] = bn_bwd(da3, c["bn3"], p["g3"])
     dy3 = q(dy3)
     g["w3"] = conv_wgrad(c["z2"], dy3, 1, 1, 1, 0, 0)
     dz2 = q(conv_dgrad(dy3, p["w3"], Ho, Wo, 1, 0, 0))
-    da2 = q(relu_bwd(dz2, c["z2"]))
+    da2 = q(_relu_bwd_g(dz2, c["z2"], gates, pre + "z2"))
     dy2, g["g2"], g["b2"] = bn_bwd(da2, c["bn2"], p["g2"])
     dy2 = q(dy2)
     g["w2"] = conv_wgrad(c["z1"], dy2, 3, 3, stride, 1, 0)
     dz1 = q(conv_dgrad(dy2, p["w2"], Hm, Wm, stride, 1, 0))
-    da1 = q(relu_bwd(dz1, c["z1"]))
+    da1 = q(_relu_bwd_g(dz1, c["z1"], gates, pre + "z1"))
     dy1, g["g1"], g["b1"] = bn_bwd(da1, c["bn1"], p["g1"])
     dy1 = q(dy1)
     if temporal:
@@ -375,11 +421,16 @@ def bottleneck_bwd(dout, c, p, stride=1, fold_div=8, q=_ident, temporal=False):
 # The rest of ResNet-50: stem, pooling, head, loss, update
 # ----------------------------------------------------------------------------
 
-def maxpool_fwd(x):
+def maxpool_fwd(x, arg=None):
     """3x3 window, stride 2, padding 1 (padding never wins).  Returns the pooled
     tensor and, per output, the flat input index (ih*W+iw) of the first maximum
-    in row-major window order."""
+    in row-major window order.  With `arg` given (positions decided by another pass, see Gates) the
+    values at those positions are returned instead of the maxima."""
     N, T, C, H, W = x.shape
+    if arg is not None:
+        flat = x.reshape(N * T * C, H * W)
+        picked = np.take_along_axis(flat, arg.reshape(N * T * C, -1), axis=1)
+        return picked.reshape(arg.shape), arg
     Ho, Wo = (H + 2 - 3) // 2 + 1, (W + 2 - 3) // 2 + 1
     best = np.full((N, T, C, Ho, Wo), -np.inf)
     arg = np.full((N, T, C, Ho, Wo), -1, dtype=np.int64)
@@ -505,19 +556,25 @@ _BLOCK_KEYS = {"w1": "c1.w", "g1": "bn1.g", "b1": "bn1.b", "w2": "c2.w", "g2": "
                "w3": "c3.w", "g3": "bn3.g", "b3": "bn3.b", "wd": "ds.w", "gd": "dsbn.g", "bd": "dsbn.b"}
 
 
-def resnet50_fwd_bwd(P, clips, labels, fold_div=8, eps=1e-5, q=_ident, wq=_ident):
+def resnet50_fwd_bwd(P, clips, labels, fold_div=8, eps=1e-5, q=_ident, wq=_ident, gates=None):
     """One forward + backward pass of TSM-ResNet-50.
     P: dict name -> float64 array; clips [N,T,3,S,S]; labels [N] ints.
     `wq` is applied to the convolution weights before use (the HIP path keeps a
-    bf16 working copy of them); `q` as in the block functions.
+    bf16 working copy of them); `q` as in the block functions; `gates` records or
+    imposes the ReLU / max-pool decisions (see Gates).
     Returns loss, logits [N,K], grads dict (same names as P)."""
     num_classes = P["fc.w"].shape[0]
     G = {}
     w0 = wq(P["conv1.w"])
     y0 = q(conv_fwd(clips, w0, 2, 3, 0))
     a0, bn0 = bn_fwd(y0, P["bn1.g"], P["bn1.b"], eps)
-    z0 = q(relu(a0))
-    x, pool_arg = maxpool_fwd(z0)
+    z0 = q(_relu_g(a0, gates, "stem.z"))
+    if gates is not None and not gates.record:
+        x, pool_arg = maxpool_fwd(z0, gates.store["stem.pool"])
+    else:
+        x, pool_arg = maxpool_fwd(z0)
+        if gates is not None:
+            gates.store["stem.pool"] = pool_arg
     caches = []
     for name, blocks, mid, stride in STAGES:
         for b in range(blocks):
@@ -527,17 +584,17 @@ def resnet50_fwd_bwd(P, clips, labels, fold_div=8, eps=1e-5, q=_ident, wq=_ident
                 if k in p:
                     p[k] = wq(p[k])
             s = stride if b == 0 else 1
-            x, c = bottleneck_fwd(x, p, s, fold_div, eps, q)
+            x, c = bottleneck_fwd(x, p, s, fold_div, eps, q, gates=gates, pre=pre)
             caches.append((pre, p, s, c))
     loss, logits, hc = head_fwd(x, P["fc.w"], P["fc.b"], labels)
     dx, G["fc.w"], G["fc.b"], _ = head_bwd(hc, x.shape, P["fc.w"], labels)
     dx = q(dx)
     for pre, p, s, c in reversed(caches):
-        dx, g = bottleneck_bwd(dx, c, p, s, fold_div, q)
+        dx, g = bottleneck_bwd(dx, c, p, s, fold_div, q, gates=gates, pre=pre)
         for k, v in g.items():
             G[pre + _BLOCK_KEYS[k]] = v
     dz0 = maxpool_bwd(dx, pool_arg, z0.shape[3], z0.shape[4])
-    da0 = q(relu_bwd(dz0, z0))
+    da0 = q(_relu_bwd_g(dz0, z0, gates, "stem.z"))
     dy0, G["bn1.g"], G["bn1.b"] = bn_bwd(da0, bn0, P["bn1.g"])
     dy0 = q(dy0)
     G["conv1.w"] = conv_wgrad(clips, dy0, 7, 7, 2, 3, 0)
@@ -644,8 +701,8 @@ def sgd_update(P, V, G, lr, momentum=0.9, weight_decay=1e-4, num_classes=400):
 
 
 def resnet50_step(P, V, clips, labels, lr, momentum=0.9, weight_decay=1e-4,
-                  fold_div=8, eps=1e-5, q=_ident, wq=_ident):
-    loss, logits, G = resnet50_fwd_bwd(P, clips, labels, fold_div, eps, q, wq)
+                  fold_div=8, eps=1e-5, q=_ident, wq=_ident, gates=None):
+    loss, logits, G = resnet50_fwd_bwd(P, clips, labels, fold_div, eps, q, wq, gates)
     P2, V2 = sgd_update(P, V, G, lr, momentum, weight_decay, P["fc.w"].shape[0])
     return loss, logits, G, P2, V2
 
@@ -653,7 +710,7 @@ def resnet50_step(P, V, clips, labels, lr, momentum=0.9, weight_decay=1e-4,
 def resnet50_accum_step(P, V, micro_batches, lr, momentum=0.9, weight_decay=1e-4,
                         fold_div=8, eps=1e-5, q=_ident, wq=_ident):
     """One update from k micro-batches (gradient accumulation, the way the paper simulates node counts it
-    could not run, section 5): every micro-batch (clips, labels) goes through forward + backward on its own
+    could not run, section 4.2): every micro-batch (clips, labels) goes through forward + backward on its own
     (its BatchNorms see only its own frames), the k gradients are averaged, and one SGD update is applied.
     Returns the list of micro-batch losses, the averaged gradients, and the updated P, V."""
     k = len(micro_batches)

@@ -146,3 +146,73 @@ def test_tsm_block_equals_temporal_block_with_one_hot_weights():
     assert np.allclose(dxa, dxb, atol=1e-11)
     assert np.allclose(ga["w1"][:, :fold, 0, 0], gb["w1"][:, :fold, 2], atol=1e-11)
     assert np.allclose(ga["w1"][:, 2 * fold:, 0, 0], gb["w1"][:, 2 * fold:, 1], atol=1e-11)
+
+
+# ---- Gates: decisions recorded in one pass, imposed on another -----------------------------------------------
+def test_gates_replaying_own_decisions_changes_nothing():
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((2, 3, 8, 4, 4))
+    p = _bparams(rng, 8, 4, True, 12)
+    dout = rng.standard_normal((2, 3, 12, 2, 2))
+    out0, c0 = O.bottleneck_fwd(x, p, 2, 4)
+    dx0, g0 = O.bottleneck_bwd(dout, c0, p, 2, 4)
+    gates = O.Gates()
+    out1, c1 = O.bottleneck_fwd(x, p, 2, 4, gates=gates, pre="b.")      # recording pass: arithmetic untouched
+    dx1, g1 = O.bottleneck_bwd(dout, c1, p, 2, 4, gates=gates, pre="b.")
+    assert np.array_equal(out0, out1) and np.array_equal(dx0, dx1)
+    assert sorted(gates.store) == ["b.out", "b.z1", "b.z2"]
+    assert np.array_equal(gates.store["b.out"], out0 > 0)
+    gates.record = False
+    out2, c2 = O.bottleneck_fwd(x, p, 2, 4, gates=gates, pre="b.")
+    dx2, g2 = O.bottleneck_bwd(dout, c2, p, 2, 4, gates=gates, pre="b.")
+    assert np.array_equal(out0, out2) and np.array_equal(dx0, dx2)
+    assert all(np.array_equal(g0[k], g2[k]) for k in g0)
+    assert gates.flips(gates) == (0, sum(m.size for m in gates.store.values()))
+
+
+@pytest.mark.parametrize("kind", ["bottleneck", "basic"])
+def test_gated_pass_is_the_derivative_of_the_gate_frozen_block(kind):
+    """Decisions recorded from the bf16-storage pass and imposed on the plain pass: the block is then a smooth
+    function of its inputs (no ReLU kinks left), its value differs from the ungated plain pass only at the few
+    units the two passes decide differently, and its backward pass is exactly its derivative."""
+    rng = np.random.default_rng(8)
+    if kind == "bottleneck":
+        x = rng.standard_normal((2, 3, 8, 5, 5))
+        p = _bparams(rng, 8, 4, False)
+        fwd = lambda a, b, **kw: O.bottleneck_fwd(a, b, 1, 4, **kw)
+        bwd = lambda d, c, b, **kw: O.bottleneck_bwd(d, c, b, 1, 4, **kw)
+    else:
+        x = rng.standard_normal((1, 3, 8, 4, 4))
+        p = {"w1": rng.standard_normal((8, 8, 3, 3)) * 0.2, "w2": rng.standard_normal((8, 8, 3, 3)) * 0.2,
+             "g1": rng.standard_normal(8) * 0.3 + 1, "b1": rng.standard_normal(8) * 0.3,
+             "g2": rng.standard_normal(8) * 0.3 + 1, "b2": rng.standard_normal(8) * 0.3}
+        fwd = lambda a, b, **kw: O.basic_block_fwd(a, b, 4, **kw)
+        bwd = lambda d, c, b, **kw: O.basic_block_bwd(d, c, b, 4, **kw)
+    dout = rng.standard_normal(x.shape)
+    gates = O.Gates()
+    outq, _ = fwd(x, p, q=O.round_bf16, gates=gates, pre="")
+    gates.record = False
+    plain, _ = fwd(x, p)
+    own = O.Gates()
+    fwd(x, p, gates=own, pre="")
+    nflip, ntot = gates.flips(own)
+    assert nflip < 0.05 * ntot
+    gated, _ = fwd(x, p, gates=gates, pre="")
+    # the gated value and the plain value agree wherever no decision on the way differs; overall they are close
+    assert np.linalg.norm(gated - plain) <= 0.2 * np.linalg.norm(plain)
+    assert np.linalg.norm(gated - outq) < 2e-2 * np.linalg.norm(outq)
+    _fd_check(lambda a, b: fwd(a, b, gates=gates, pre=""), lambda d, c, b: bwd(d, c, b, gates=gates, pre=""),
+              x, p, dout, rng)
+
+
+def test_maxpool_with_given_positions():
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((1, 2, 3, 6, 6))
+    best, arg = O.maxpool_fwd(x)
+    again, arg2 = O.maxpool_fwd(x, arg)
+    assert np.array_equal(best, again) and arg2 is arg
+    y = x + 0.01 * rng.standard_normal(x.shape)
+    picked, _ = O.maxpool_fwd(y, arg)
+    flat = y.reshape(6, 36)
+    assert np.array_equal(picked.reshape(6, -1), np.take_along_axis(flat, arg.reshape(6, -1), axis=1))
+    assert np.all(picked <= O.maxpool_fwd(y)[0])

@@ -127,6 +127,39 @@ def test_whole_step_shapes_loss_and_directional_derivatives():
         assert min(errs) < 1e-4, (name, errs, ana)
 
 
+def test_gated_network_pass():
+    """Gates on the whole network: replaying a pass's own decisions reproduces it exactly; with the decisions of
+    the bf16-storage pass imposed, the plain pass is smooth, so a central difference with a comfortable step
+    matches its gradient closely (the ungated network needs a tiny step because of the ReLU / max-pool kinks)."""
+    P = _tiny_net()
+    clips = I.clips(2, 4, 32, seed=0, dtype="f32").astype(np.float64)
+    labels = I.labels(2)
+    loss0, logits0, G0 = O.resnet50_fwd_bwd(P, clips, labels)
+    own = O.Gates()
+    loss1, logits1, G1 = O.resnet50_fwd_bwd(P, clips, labels, gates=own)
+    assert loss1 == loss0 and all(np.array_equal(G0[k], G1[k]) for k in G0)
+    own.record = False
+    loss2, logits2, G2 = O.resnet50_fwd_bwd(P, clips, labels, gates=own)
+    assert loss2 == loss0 and np.array_equal(logits2, logits0) and all(np.array_equal(G0[k], G2[k]) for k in G0)
+    assert "stem.pool" in own.store and "stem.z" in own.store and "res5.2.out" in own.store and len(own.store) == 2 + 16 * 3
+
+    gq = O.Gates()
+    O.resnet50_fwd_bwd(P, clips, labels, q=O.round_bf16, wq=O.round_bf16, gates=gq)
+    nflip, ntot = gq.flips(own)
+    assert 0 < nflip < 0.1 * ntot
+    gq.record = False
+    loss, logits, G = O.resnet50_fwd_bwd(P, clips, labels, gates=gq)
+    rng = np.random.default_rng(4)
+    for name in ("conv1.w", "res2.1.bn2.g", "res3.0.ds.w", "res4.3.c2.w", "res5.2.c3.w", "fc.b"):
+        D = rng.standard_normal(P[name].shape)
+        D /= np.linalg.norm(D)
+        ana = (G[name] * D).sum()
+        h = 1e-5
+        lp = O.resnet50_fwd_bwd(dict(P, **{name: P[name] + h * D}), clips, labels, gates=gq)[0]
+        lm = O.resnet50_fwd_bwd(dict(P, **{name: P[name] - h * D}), clips, labels, gates=gq)[0]
+        assert abs((lp - lm) / (2 * h) - ana) < 1e-5 * max(abs(ana), 1e-3), (name, (lp - lm) / (2 * h), ana)
+
+
 def test_loss_at_init_is_log_400_and_one_step_lowers_it():
     table = O.resnet50_param_table()
     P = O.unflatten_params(I.init_params(table, 1).astype(np.float64))

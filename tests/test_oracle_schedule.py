@@ -1,5 +1,5 @@
 """Pins of the oracle's learning-rate schedule and gradient accumulation (training recipe, section 4.1;
-gradient accumulation, section 5) against the values the paper fixes and against closed forms."""
+gradient accumulation, section 4.2) against the values the paper fixes and against closed forms."""
 import numpy as np
 
 from oracle import tsm_oracle as O
@@ -9,7 +9,7 @@ from paper_1910_00932_amd import inputs as I
 def test_lr_values_the_paper_states():
     # 0.00125 for every 8 samples, total rate 0.00125*k for k GPUs of 8 clips (section 4.1)
     assert O.lr_schedule(5.0, 8) == 0.00125                       # one GPU: k = 1
-    assert abs(O.lr_schedule(5.0, 8 * 1536) - 0.00125 * 1536) < 1e-15     # 1536 GPUs, batch 12288 (section 5)
+    assert abs(O.lr_schedule(5.0, 8 * 1536) - 0.00125 * 1536) < 1e-15     # 1536 GPUs, batch 12288 (section 4.2, Table 3)
     assert abs(O.lr_schedule(5.0, 64) - 0.01) < 1e-15             # 64 clips
 
 
