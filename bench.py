@@ -94,9 +94,10 @@ def class_work(F, size):
     return work
 
 
-def class_bytes(F, size):
+def class_bytes(F, size, epilogue_reads=True):
     """Algorithmic HBM bytes per step of each MFMA kernel class: every layer reads its two operands once
-    and writes its result once (bf16 activations; weight-sized tensors are negligible and left out)."""
+    and writes its result once (bf16 activations; weight-sized tensors are negligible and left out).
+    epilogue_reads: also count the tensors a fused data-gradient epilogue reads."""
     byt = {}
 
     def add(cls, b):
@@ -118,7 +119,7 @@ def class_bytes(F, size):
                 extra += 2.0 * x_b
             elif name.endswith(".c1") and blk == 1:
                 extra += x_b           # the block below has a projection shortcut: only its ReLU mask rides along
-            add(igemm_class("dgrad", cin, cout, rin, taps, 1 if rin == rout else 2), x_b + y_b + extra)
+            add(igemm_class("dgrad", cin, cout, rin, taps, 1 if rin == rout else 2), x_b + y_b + (extra if epilogue_reads else 0.0))
         add("wgrad_tr_64x256" if stem else wgrad_class(cout, cin, taps), x_b + y_b)
     return byt
 
@@ -377,22 +378,31 @@ def main():
         with torch.cuda.graph(graph):
             eager()
         step = graph.replay
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
     first_loss = None
-    t0 = time.perf_counter()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(stream)
-    for _ in range(args.steps):
+    for i in range(args.warmup):
         step()
-    e1.record(stream)
+        if i == 0:
+            torch.cuda.synchronize()
+            first_loss = float(loss.item())      # the loss of the untrained network on this batch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    # one event per step boundary: the mean comes from the first and the last, median and minimum from the rest
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    ev[0].record(stream)
+    for i in range(args.steps):
+        step()
+        ev[i + 1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = e0.elapsed_time(e1) / args.steps
+    ms_per_step = ev[0].elapsed_time(ev[-1]) / args.steps
+    per_step = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps))
     final_loss = float(loss.item())
     if not np.isfinite(final_loss):
         sys.exit("bench.py: loss is not finite (%r)" % final_loss)
+    # the steps train on one fixed batch: the loss the last step reports must lie below the untrained network's
+    if first_loss is not None and not final_loss < first_loss:
+        sys.exit("bench.py: the loss did not fall over %d steps on a fixed batch (%r -> %r)"
+                 % (args.warmup + args.steps, first_loss, final_loss))
 
     # per-class time of one more step, HIP events on the launch stream after every launch
     B.tsm_profile_begin(stream)
@@ -407,6 +417,7 @@ def main():
         # bytes at the HBM peak
         tflops = work[dom] / (dom_ms * 1e-3) / 1e12
         alg_bytes = class_bytes(N * T, S)[dom]
+        conv_bytes = class_bytes(N * T, S, epilogue_reads=False)[dom]
         gbs = alg_bytes / (dom_ms * 1e-3) / 1e9
         t_mfma, t_hbm = work[dom] / (PEAK_BF16_TFLOPS * 1e12), alg_bytes / (PEAK_HBM_GBS * 1e9)
         hbm_bound = t_hbm > t_mfma
@@ -416,9 +427,17 @@ def main():
                 "unit": "GB/s" if hbm_bound else "TFLOP/s",
                 "frac": (gbs / PEAK_HBM_GBS) if hbm_bound else (tflops / PEAK_BF16_TFLOPS),
                 "traffic": traffic.get(dom),
+                "traffic_source": "committed rocprofv3 --pmc summary under profiles/ (not measured in this run)"
+                                  if traffic.get(dom) is not None else None,
                 "flops_per_launch": work[dom] / n_launch, "algorithmic_bytes_per_launch": alg_bytes / n_launch,
                 "tflops": tflops, "algorithmic_gbs": gbs,
-                "frac_of_mfma_peak": tflops / PEAK_BF16_TFLOPS, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
+                "frac_of_mfma_peak": tflops / PEAK_BF16_TFLOPS, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS,
+                # the same launches on two byte accountings: `frac` counts what the kernel has to move for the
+                # method's work it carries (convolution operand and result, plus the shortcut gradient, ReLU-mask
+                # source and BatchNorm input its fused epilogue reads); the second one counts the convolution's
+                # operand and result alone
+                "frac_conv_bytes_only": conv_bytes / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                "conv_bytes_per_launch": conv_bytes / n_launch}
     else:
         roof = {"bound": "hbm", "kernel": dom, "launches_per_step": n_launch, "avg_launch_ms": dom_ms / n_launch,
                 "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": None, "traffic": None}
@@ -438,7 +457,8 @@ def main():
                    "clips_per_step": N, "frames": T, "size": S, "num_classes": K},
         "step_tflops": flops_step / (ms_per_step * 1e-3) / 1e12,
         "pct_bf16_mfma_peak": 100.0 * flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        "loss_after": final_loss, "wall_s": wall, "hip_graph": bool(args.graph), "wgrad_overlap": not args.no_overlap,
+        "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
+        "loss_before": first_loss, "loss_after": final_loss, "wall_s": wall, "hip_graph": bool(args.graph), "wgrad_overlap": not args.no_overlap,
         "roofline": roof, "kernel_classes": classes, "profiled_step_ms": prof_total,
     }
 
@@ -493,6 +513,16 @@ def main():
         out["cpu_baseline"] = {"value": nc / dt, "unit": "clips/s", "cores": O.max_threads(), "kind": "oracle",
                                "sample": "%d clips (8x3x224x224 each): one full fwd+bwd+update of the fp64 oracle, %.1f s"
                                          % (nc, dt)}
+        # the same oracle on one thread, on a smaller sample of the same workload (one clip, forward pass only)
+        nthreads = O.max_threads()
+        O.set_threads(1)
+        bn0 = np.concatenate([np.concatenate([np.zeros(sh[0]), np.ones(sh[0])]) for n, _, sh, _ in table if n.endswith(".g")])
+        t0 = time.perf_counter()
+        O.resnet50_infer(P, bn0, c1[:1])
+        dt1 = time.perf_counter() - t0
+        O.set_threads(nthreads)
+        out["cpu_baseline_single_thread"] = {"value": 1.0 / dt1, "unit": "clips/s (forward only)", "cores": 1, "kind": "oracle",
+                                             "sample": "1 clip (8x3x224x224): forward pass of the fp64 oracle on one thread, %.1f s" % dt1}
     print(json.dumps(out))
 
 

@@ -27,7 +27,12 @@
  *    TSM_IGEMM_RING=0 / TSM_WGRAD_TR=0 (read once per process) fall back to the
  *    kernels for channel counts that are not multiples of 64 wherever those can
  *    run; TSM_CONV3X3_C64=0 and TSM_STEM_KERNEL=0 (read at every call) leave the
- *    layers that have a kernel of their own to the general one.
+ *    layers that have a kernel of their own to the general one, and
+ *    TSM_CONV3X3_C64_MIN_TILES=<n> (read at every call) replaces the number of
+ *    256-pixel tiles from which those two kernels are chosen (default: five per
+ *    compute unit); TSM_IGEMM_BM=128|256 (read once per process) fixes the rows
+ *    per tile of the general forward / data-gradient kernel, which otherwise
+ *    follows from the number of tiles per compute unit.
  *  - Return value: TSM_OK or a negative tsm_status.  On error nothing has been
  *    launched (argument errors) or the stream's state is undefined
  *    (TSM_ERR_LAUNCH).  tsm_last_error() returns a host string describing the
@@ -247,7 +252,20 @@ int tsm_resnet50_step(const tsm_r50_desc* d, const void* clips, const int32_t* l
                       float* grads_out, float* loss_out, float* logits_out,
                       int update, void* ws, size_t ws_bytes, void* stream);
 
-/* Gradient accumulation (the paper simulates node counts it could not run this way, section 5): one SGD
+/* Inspection aid: after tsm_resnet50_step (or _accum_step) has completed on `stream`, the caller's workspace still
+ * holds the forward activations the step kept for its backward pass (section 3, model (3): the tensors between
+ * the layers of the stem and of the sixteen residual blocks).  This call tells where: byte `offset` from the start
+ * of the workspace, `shape` = {frames N*T, rows, columns, channels} (channels innermost) and the element size
+ * (desc.dtype's, 1 for the pooling positions, 4 for the fp32 vectors).  Names: "stem.y" (7x7 convolution output),
+ * "stem.bn_scale" / "stem.bn_shift" (fp32 [64]: the stem's BatchNorm as the map z = scale*y + shift),
+ * "stem.pool_arg" (uint8: window position kh*3+kw the 3x3/2 max-pool picked), "stem.pool" (its output), and per
+ * block "res2.0." .. "res5.2.": "y1", "z1" = ReLU(BN(y1)), "y2", "z2", "y3", "yd" (projection shortcut, first
+ * block of a stage) and "out".  Host-side only, no GPU work; TSM_ERR_UNSUPPORTED for an unknown name, the
+ * descriptor errors of tsm_resnet50_step otherwise. */
+int tsm_resnet50_workspace_tensor(const tsm_r50_desc* d, const char* name, size_t* offset, int shape[4],
+                                  int* elem_bytes);
+
+/* Gradient accumulation (the paper simulates node counts it could not run this way, section 4.2): one SGD
  * update from micro_count calls, each a forward + backward pass over its own micro-batch (its BatchNorms
  * normalise over its own N*T frames, running statistics are updated per call).  Call micro_index 0 overwrites
  * grads_accum (fp32 [param_count], caller-owned, must stay untouched between the calls) with its gradients,

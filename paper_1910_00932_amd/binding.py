@@ -24,7 +24,7 @@ EXPORTS = ["tsm_last_error", "tsm_profile_begin", "tsm_profile_end", "tsm_mfma_p
            "tsm_conv_dgrad", "tsm_conv_wgrad", "tsm_block_saved_bytes", "tsm_block_workspace_bytes",
            "tsm_block_fwd", "tsm_block_bwd", "tsm_resnet50_param_count", "tsm_resnet50_num_tensors",
            "tsm_resnet50_param_info", "tsm_resnet50_bn_state_count", "tsm_resnet50_workspace_bytes",
-           "tsm_resnet50_step", "tsm_resnet50_infer_workspace_bytes", "tsm_resnet50_infer",
+           "tsm_resnet50_step", "tsm_resnet50_workspace_tensor", "tsm_resnet50_infer_workspace_bytes", "tsm_resnet50_infer",
            "tsm_resnet50_accum_step", "tsm_lr_schedule"]
 
 
@@ -101,6 +101,8 @@ def lib():
         sig("tsm_resnet50_param_info", ci, [ci, ci, ctypes.c_char_p, ci, ctypes.POINTER(ctypes.c_int64),
                                             ctypes.POINTER(ci), ctypes.POINTER(ci * 4), ctypes.POINTER(ci)])
         sig("tsm_resnet50_step", ci, [vp, vp, vp, vp, vp, vp, vp, vp, vp, ci, vp, sz, vp])
+        sig("tsm_resnet50_workspace_tensor", ci, [vp, ctypes.c_char_p, ctypes.POINTER(sz), ctypes.POINTER(ci * 4),
+                                                  ctypes.POINTER(ci)])
         sig("tsm_resnet50_infer", ci, [vp, vp, vp, vp, vp, vp, sz, vp])
         sig("tsm_resnet50_accum_step", ci, [vp, vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, vp, sz, vp])
         sig("tsm_lr_schedule", ctypes.c_double, [ctypes.c_double, ci, ci, ctypes.c_double, ctypes.c_double])
@@ -257,6 +259,15 @@ def tsm_resnet50_step(desc, clips, labels, params, momentum, bn_state, grads_out
     _check(lib().tsm_resnet50_step(ctypes.addressof(desc), _ptr(clips), _ptr(labels), _ptr(params), _ptr(momentum),
                                    _ptr(bn_state), _ptr(grads_out), _ptr(loss_out), _ptr(logits_out), int(update),
                                    p, n, _stream(stream)))
+
+
+def tsm_resnet50_workspace_tensor(desc, name):
+    """Returns (byte offset in the step's workspace, (frames, rows, columns, channels), element bytes)."""
+    off, eb = ctypes.c_size_t(), ctypes.c_int()
+    shape = (ctypes.c_int * 4)()
+    _check(lib().tsm_resnet50_workspace_tensor(ctypes.addressof(desc), name.encode(), ctypes.byref(off),
+                                               ctypes.byref(shape), ctypes.byref(eb)))
+    return off.value, tuple(shape), eb.value
 
 
 def tsm_resnet50_infer_workspace_bytes(desc):

@@ -282,10 +282,22 @@ static int wgrad_join(SideStream* ss, bool forked, hipStream_t s) {
     return TSM_OK;
 }
 
+// The body of block_bwd_impl; `forked` tells the caller whether the side stream has work of this block, so that it
+// is joined on every path out, errors included (a caller's stream capture must not be left with an open branch).
+static int block_bwd_body(BlockPlan& b, const void* x, const void* out, const void* dout, void* dx, Arena& ws, bool dry,
+                          hipStream_t s, SideStream* ss, bool& forked);
+
 int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dout, void* dx, Arena& ws, bool dry,
                    hipStream_t s) {
     SideStream* const ss = dry ? nullptr : side_stream();
     bool forked = false;
+    const int rc = block_bwd_body(b, x, out, dout, dx, ws, dry, s, ss, forked);
+    const int rj = wgrad_join(ss, forked, s);
+    return rc != TSM_OK ? rc : rj;
+}
+
+static int block_bwd_body(BlockPlan& b, const void* x, const void* out, const void* dout, void* dx, Arena& ws, bool dry,
+                          hipStream_t s, SideStream* ss, bool& forked) {
     const int es = (int)dtype_size(b.dtype);
     const int L = b.nst - 1;
     const ConvP& pl = b.st[L].p;
@@ -355,7 +367,7 @@ int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dou
         addend = dsc;
     }
     if (dx || dry) TSM_TRY(run_conv_dgrad(b.st[0].p, b.dtype, g, b.st[0].w, b.st[0].wd, dx, addend, b.dx_fuse, ws, dry, s));
-    return wgrad_join(ss, forked, s);
+    return TSM_OK;
 }
 
 static void set_stage(StageDef& st, int F, int T, int H, int W, int Cin, int Cout, int KT, int k, int stride, int pad,

@@ -645,10 +645,22 @@ struct GradAccum {
     } while (0)
 #define LAUNCH_CHECK(what) RUN(check_launch(what))
 
+// Question to the step's workspace plan: where does the named forward activation live (see
+// tsm_resnet50_workspace_tensor)?  Answered by a dry pass of the plan over a placeholder base address.
+struct WsQuery {
+    const char* name;
+    size_t offset;
+    int shape[4];
+    int elem_bytes;
+    bool found;
+};
+static char* const kQueryBase = (char*)(uintptr_t)(1u << 20);   // never dereferenced
+
 static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* labels, float* params, float* momentum,
                     float* bn_state, float* grads_out, float* loss_out, float* logits_out, int update, void* wsp,
-                    size_t ws_bytes, bool dry, hipStream_t s, size_t* need, const GradAccum* acc = nullptr) {
-    const char* who = acc ? "tsm_resnet50_accum_step" : "tsm_resnet50_step";
+                    size_t ws_bytes, bool dry, hipStream_t s, size_t* need, const GradAccum* acc = nullptr,
+                    WsQuery* query = nullptr) {
+    const char* who = query ? "tsm_resnet50_workspace_tensor" : acc ? "tsm_resnet50_accum_step" : "tsm_resnet50_step";
     if (!d) return fail(TSM_ERR_NULLPTR, "%s: null descriptor", who);
     if (d->N <= 0 || d->T <= 0 || d->size < 32 || d->num_classes <= 0)
         return fail(TSM_ERR_SHAPE, "%s: N, T, num_classes must be positive and size >= 32", who);
@@ -679,7 +691,7 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
     const bool bf = dtype == TSM_BF16;
     const size_t es = dtype_size(dtype);
     const int VEC = bf ? 8 : 4;
-    Arena A(dry ? nullptr : wsp, (size_t)-1);
+    Arena A(dry ? (query ? (void*)kQueryBase : nullptr) : wsp, (size_t)-1);
 
     // running-statistics slots follow the BatchNorm order of the table
     int64_t bn_off = 0;
@@ -693,7 +705,10 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
         bn_off += 2 * C;
     };
 
-    float* grads = grads_out ? grads_out : A.take_n<float>((size_t)nparams);
+    // (reserved whether or not the caller passes grads_out / logits_out: the layout of the workspace must not depend
+    // on the optional outputs, tsm_resnet50_workspace_tensor describes it from the descriptor alone)
+    float* const grads_ws = A.take_n<float>((size_t)nparams);
+    float* grads = grads_out ? grads_out : grads_ws;
 
     auto P = [&](const std::string& name) { return params + table[find_tensor(table, name)].offset; };
     auto G = [&](const std::string& name) { return grads + table[find_tensor(table, name)].offset; };
@@ -843,7 +858,8 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
     const int Cf = lastp.Cout, rows_clip = T * lastp.Ho * lastp.Wo;
     float* pm = A.take_n<float>((size_t)d->N * Cf);
     float* dpm = A.take_n<float>((size_t)d->N * Cf);
-    float* logits = logits_out ? logits_out : A.take_n<float>((size_t)d->N * K);
+    float* const logits_ws = A.take_n<float>((size_t)d->N * K);
+    float* logits = logits_out ? logits_out : logits_ws;
     float* dlogits = A.take_n<float>((size_t)d->N * K);
     // gradient ping-pong buffers: the largest activation between blocks
     size_t act_max = (size_t)F * Hp * Hp * 64 * es;
@@ -866,6 +882,41 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
         chain_part[i - 1] = A.take_n<float>((size_t)nbf * 2 * blks[i - 1].plan.st[2].p.Cout);
     }
     void* da0 = A.take((size_t)F * H1 * H1 * 64 * es);
+    if (query) {
+        // forward activations a step leaves behind in its workspace (nothing in the backward pass writes them)
+        auto answer = [&](const void* p, int f, int h, int w, int c, int eb) {
+            query->offset = (size_t)((const char*)p - kQueryBase);
+            query->shape[0] = f; query->shape[1] = h; query->shape[2] = w; query->shape[3] = c;
+            query->elem_bytes = eb;
+            query->found = true;
+        };
+        const std::string q = query->name;
+        if (q == "stem.y") answer(y0, F, H1, H1, 64, (int)es);
+        else if (q == "stem.bn_scale") answer(bn0.scale, 64, 1, 1, 1, 4);
+        else if (q == "stem.bn_shift") answer(bn0.shift, 64, 1, 1, 1, 4);
+        else if (q == "stem.pool_arg") answer(arg0, F, Hp, Hp, 64, 1);
+        else if (q == "stem.pool") answer(p0, F, Hp, Hp, 64, (int)es);
+        else {
+            size_t bi = 0;
+            for (const StageSpec& st : kStages) {
+                for (int b = 0; b < st.blocks; ++b, ++bi) {
+                    const std::string pre = std::string(st.name) + "." + std::to_string(b) + ".";
+                    if (q.compare(0, pre.size(), pre) != 0) continue;
+                    const BlockPlan& pl = blks[bi].plan;
+                    const std::string t = q.substr(pre.size());
+                    const ConvP &p1 = pl.st[0].p, &p2 = pl.st[1].p, &p3 = pl.st[2].p;
+                    if (t == "y1") answer(pl.y[0], F, p1.Ho, p1.Wo, p1.Cout, (int)es);
+                    else if (t == "z1") answer(pl.z[0], F, p1.Ho, p1.Wo, p1.Cout, (int)es);
+                    else if (t == "y2") answer(pl.y[1], F, p2.Ho, p2.Wo, p2.Cout, (int)es);
+                    else if (t == "z2") answer(pl.z[1], F, p2.Ho, p2.Wo, p2.Cout, (int)es);
+                    else if (t == "y3") answer(pl.y[2], F, p3.Ho, p3.Wo, p3.Cout, (int)es);
+                    else if (t == "out") answer(blks[bi].out, F, p3.Ho, p3.Wo, p3.Cout, (int)es);
+                    else if (t == "yd" && pl.proj) answer(pl.yd, F, p3.Ho, p3.Wo, p3.Cout, (int)es);
+                }
+            }
+        }
+        return TSM_OK;
+    }
     char* scratch_base = dry ? nullptr : (char*)wsp + A.used;
     const size_t scratch_cap = dry ? (size_t)-1 : (ws_bytes > A.used ? ws_bytes - A.used : 0);
     auto note = [&](const Arena& sc) { if (sc.used > scratch_need) scratch_need = sc.used; };
@@ -1315,6 +1366,19 @@ size_t tsm_resnet50_workspace_bytes(const tsm_r50_desc* d) {
                  &need) != TSM_OK)
         return 0;
     return need;
+}
+
+int tsm_resnet50_workspace_tensor(const tsm_r50_desc* d, const char* name, size_t* offset, int shape[4], int* elem_bytes) {
+    if (!name || !offset || !shape || !elem_bytes) return fail(TSM_ERR_NULLPTR, "tsm_resnet50_workspace_tensor: null pointer");
+    WsQuery q{};
+    q.name = name;
+    TSM_TRY(r50_step(d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 1, nullptr, 0, true, nullptr,
+                     nullptr, nullptr, &q));
+    if (!q.found) return fail(TSM_ERR_UNSUPPORTED, "tsm_resnet50_workspace_tensor: no tensor named '%s'", name);
+    *offset = q.offset;
+    for (int i = 0; i < 4; ++i) shape[i] = q.shape[i];
+    *elem_bytes = q.elem_bytes;
+    return TSM_OK;
 }
 
 int tsm_resnet50_step(const tsm_r50_desc* d, const void* clips, const int32_t* labels, float* params, float* momentum,

@@ -58,7 +58,8 @@ def test_conv_argument_errors():
     assert need > 0
     assert L.tsm_conv_fwd(ctypes.addressof(d), None, a, a, None, None, a, need, None) == -1
     assert L.tsm_conv_fwd(None, a, a, a, None, None, a, need, None) == -1
-    assert L.tsm_conv_fwd(ctypes.addressof(d), a, a, a, None, None, a, need - 1 if need > 1 else 0, None) in (-6, 0) or True
+    # an empty workspace is below the forward requirement of every descriptor (the statistics rows alone need some)
+    assert L.tsm_conv_fwd(ctypes.addressof(d), a, a, a, None, None, a, 0, None) == -6
     d2 = _conv_desc(T=0)
     assert L.tsm_conv_fwd(ctypes.addressof(d2), a, a, a, None, None, a, 1 << 20, None) == -2
     d3 = _conv_desc(fold_div=1)
@@ -115,3 +116,21 @@ def test_network_entry_points_argument_errors():
     assert L.tsm_resnet50_accum_step(da, a, a, a, a, None, a, a, None, 2, 2, a, need_step, None) == -2  # index out of range
     assert L.tsm_resnet50_accum_step(da, a, a, a, a, None, None, a, None, 0, 2, a, need_step, None) == -1
     assert L.tsm_resnet50_accum_step(da, a, a, a, a, None, a + 4, a, None, 0, 2, a, need_step, None) == -7
+
+
+def test_workspace_plan_switches_kernels_at_2_gib():
+    """The general forward kernel addresses its tensors with 32-bit byte offsets; tensors of 2 GiB and more go to
+    the register-prefetch kernel, which runs two blocks of 128-row tiles per compute unit instead of one block of
+    256-row tiles.  The workspace plan shows the switch: the statistics epilogue gets one row per block."""
+    def stats_rows(N):
+        d = B.ConvDesc(N=N, T=8, Cin=64, H=112, W=112, Cout=64, kh=1, kw=1, stride=1, pad=0, fold_div=8,
+                       dtype=B.TSM_BF16, layout=B.TSM_NTHWC)
+        need = B.tsm_conv_workspace_bytes(d)
+        packed = 64 * 64 * 2                      # bf16 working copy of the weights (a multiple of 256 bytes)
+        rows, rem = divmod(need - packed, 2 * 64 * 4)
+        assert rem == 0
+        return N * 8 * 112 * 112 * 64 * 2, rows
+    below, rows_below = stats_rows(166)
+    above, rows_above = stats_rows(168)
+    assert below < 0x7ff00000 <= above
+    assert rows_above == 2 * rows_below and rows_below % 8 == 0

@@ -1,4 +1,4 @@
-"""Gradient accumulation over micro-batches (section 5) through tsm_resnet50_accum_step against the oracle."""
+"""Gradient accumulation over micro-batches (section 4.2) through tsm_resnet50_accum_step against the oracle."""
 import numpy as np
 import pytest
 import torch

@@ -10,7 +10,7 @@ from oracle import tsm_oracle as O
 from paper_1910_00932_amd import binding as B
 from paper_1910_00932_amd import inputs as I
 from conftest import rel_l2
-from gpu_util import CDT, CLAY, TOL, dev_vec, empty_act, from_dev, to_dev, workspace
+from gpu_util import CDT, CLAY, TOL, compare_act, compare_local, dev_vec, empty_act, from_dev, to_dev, workspace
 
 pytestmark = pytest.mark.gpu
 
@@ -58,39 +58,64 @@ def run_block(kind, N, T, Cin, H, W, Cmid, Cout, stride, proj, fd, dtype, layout
     p64 = {k: v.astype(np.float64) for k, v in p.items()}
     x64, dout64 = x.astype(np.float64), dout.astype(np.float64)
 
-    def oracle(q):
+    def oracle(q, gates=None):
         if kind == "basic":
-            oo, c = O.basic_block_fwd(x64, p64, fd, eps, q)
-            odx, og = O.basic_block_bwd(dout64, c, p64, fd, q)
+            oo, c = O.basic_block_fwd(x64, p64, fd, eps, q, gates=gates)
+            odx, og = O.basic_block_bwd(dout64, c, p64, fd, q, gates=gates)
         else:
-            oo, c = O.bottleneck_fwd(x64, p64, stride, fd, eps, q, temporal=(kind == "t3"))
-            odx, og = O.bottleneck_bwd(dout64, c, p64, stride, fd, q, temporal=(kind == "t3"))
-        return oo, odx, og
+            oo, c = O.bottleneck_fwd(x64, p64, stride, fd, eps, q, temporal=(kind == "t3"), gates=gates)
+            odx, og = O.bottleneck_bwd(dout64, c, p64, stride, fd, q, temporal=(kind == "t3"), gates=gates)
+        ref = {"out": oo, "dx": odx}
+        ref.update({"d" + k: v for k, v in og.items()})
+        return ref
 
     tol = TOL[dtype]
     got = {"out": from_dev(out, layout), "dx": from_dev(dx, layout)}
     got.update({k: v.cpu().numpy() for k, v in dg.items()})
-    # fp32: the plain fp64 oracle.  bf16: the oracle with every tensor the HIP path stores rounded to
-    # bf16 at the same points, so that the ReLU masks (a 0/1 decision) are taken in the kernel's
-    # precision; the tensors that do not hinge on those decisions are also held to the plain oracle.
-    oo, odx, og = oracle(O.round_bf16 if dtype == "bf16" else (lambda a: a))
-    ref = {"out": oo, "dx": odx}
-    ref.update({"d" + k: v for k, v in og.items()})
-    errs = {k: rel_l2(got[k].reshape(ref[k].shape), ref[k]) for k in ref}
-    bad = {k: e for k, e in errs.items() if not e < tol}
-    if dtype == "bf16":
-        # Against the plain fp64 oracle the forward output keeps the same bound.  The gradients do not:
-        # bf16 rounding of the forward activations flips a fraction f of the ReLU masks of
-        # near-zero pre-activations, and each flip moves a gradient entry by O(1), i.e. a relative L2
-        # change of about sqrt(f) (6% measured here) in any bf16 implementation; they get a gross-error guard.
-        po, pdx, pg = oracle(lambda a: a)
-        errs["out_vs_fp64"] = rel_l2(got["out"], po)
-        if not errs["out_vs_fp64"] < tol:
-            bad["out_vs_fp64"] = errs["out_vs_fp64"]
-        errs["dx_vs_fp64"] = rel_l2(got["dx"], pdx)
-        if not errs["dx_vs_fp64"] < 0.25:
-            bad["dx_vs_fp64"] = errs["dx_vs_fp64"]
-    assert not bad, (bad, errs)
+    what = "%s %s %s" % (kind, (N, T, Cin, H, W, Cmid, Cout, stride, proj, fd), dtype)
+
+    def check(ref, tag, bound, local=True):
+        """Every tensor against one oracle pass: whole tensor; every frame / 256-row tile of the activations; every
+        output channel of the weight gradients."""
+        errs = {}
+        for k in ref:
+            g = got[k].reshape(ref[k].shape)
+            if k in ("out", "dx") and local:
+                # frames and tiles at the bound; elements only as a gross-error guard (a block's output passes
+                # through several roundings and a normalisation, so single elements move by more than one rounding)
+                errs[k] = compare_act(g, ref[k], bound, "%s %s vs %s" % (what, k, tag), dtype, elem=False)["l2"]
+            elif ref[k].ndim >= 3 and local:
+                # per output channel; a few channels may carry a ReLU decision that falls the other way (see compare_local)
+                errs[k] = compare_local(g, ref[k], bound, "%s %s vs %s" % (what, k, tag), local_factor=4.0,
+                                        part_outliers=0.02, part_cap=25.0)["l2"]
+            else:
+                errs[k] = rel_l2(g, ref[k])
+                assert errs[k] < bound, (what, k, tag, errs[k])
+        return errs
+
+    if dtype != "bf16":
+        # fp32: the plain fp64 oracle, every tensor at 1e-4
+        return check(oracle(lambda a: a), "fp64", tol)
+    # bf16, three passes of the oracle:
+    #  (a) every tensor the HIP path stores rounded to bf16 at the same points: everything at 2e-2;
+    #  (b) plain fp64 arithmetic with the ReLU decisions of pass (a) imposed -- the decisions are taken in the
+    #      kernel's precision, nothing else is emulated: out, dx, dW, dgamma, dbeta all at 2e-2;
+    #  (c) plain fp64 throughout: the forward output at 2e-2.  Its gradients differ from any bf16 implementation by
+    #      the units whose ReLU decision bf16 storage flips (counted below), each of which moves gradient entries by
+    #      O(1); they get a gross-error guard only.
+    gates = O.Gates()
+    errs = check(oracle(O.round_bf16, gates), "bf16-storage oracle", tol)
+    gates.record = False
+    eg = check(oracle(lambda a: a, gates), "fp64 oracle with bf16 decisions", tol)
+    errs.update({k + "_gated_fp64": v for k, v in eg.items()})
+    own = O.Gates()
+    plain = oracle(lambda a: a, own)
+    nflip, ntot = gates.flips(own)
+    errs["out_vs_fp64"] = compare_act(got["out"], plain["out"], tol, what + " out vs fp64", dtype, elem=False)["l2"]
+    errs["dx_vs_fp64"] = rel_l2(got["dx"], plain["dx"])
+    assert errs["dx_vs_fp64"] < 0.25, (what, errs["dx_vs_fp64"])
+    print("%s: ReLU decisions flipped by bf16 storage %d of %d; dx against plain fp64 %.3f, with those decisions imposed %.4f"
+          % (what, nflip, ntot, errs["dx_vs_fp64"], eg["dx"]))
     return errs
 
 
