@@ -151,6 +151,17 @@ int tsm_conv_fwd(const tsm_conv_desc* d, const void* x, const void* w, void* y,
                  void* ws, size_t ws_bytes, void* stream);
 int tsm_conv_dgrad(const tsm_conv_desc* d, const void* dy, const void* w, void* dx,
                    void* ws, size_t ws_bytes, void* stream);
+/* tsm_conv_fwd for callers that cannot allocate device memory or supply a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and error codes as
+ * tsm_conv_fwd without (ws, ws_bytes): the scratch (packed weights, statistics rows, transposed copies for
+ * TSM_NTCHW) is a buffer of TSM_NOALLOC_SCRATCH_BYTES that is part of the library's device image, one copy per
+ * GPU, held until the process ends.  A convolution whose scratch need (tsm_conv_workspace_bytes is an upper
+ * bound) exceeds that returns TSM_ERR_WORKSPACE and launches nothing.  The call allocates and frees nothing.
+ * All calls on one GPU share the buffer: calls that may overlap in time on one GPU (different streams, or
+ * threads) race and must be ordered by the caller; calls on one stream are ordered by the stream. */
+#define TSM_NOALLOC_SCRATCH_BYTES (16u << 20)
+int tsm_conv_fwd_noalloc(const tsm_conv_desc* d, const void* x, const void* w, void* y,
+                         float* ch_sum, float* ch_sumsq, void* stream);
 /* accumulate != 0 adds into dw instead of overwriting it (micro-batch
  * gradient accumulation, section 4.2's simulation of larger node counts). */
 int tsm_conv_wgrad(const tsm_conv_desc* d, const void* x, const void* dy, float* dw,

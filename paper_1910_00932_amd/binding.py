@@ -21,6 +21,7 @@ STATUS = {0: "TSM_OK", -1: "TSM_ERR_NULLPTR", -2: "TSM_ERR_SHAPE", -3: "TSM_ERR_
           -9: "TSM_ERR_UNSUPPORTED"}
 
 EXPORTS = ["tsm_last_error", "tsm_profile_begin", "tsm_profile_end", "tsm_mfma_probe", "tsm_shift_fwd", "tsm_shift_bwd", "tsm_conv_workspace_bytes", "tsm_conv_fwd",
+           "tsm_conv_fwd_noalloc",
            "tsm_conv_dgrad", "tsm_conv_wgrad", "tsm_block_saved_bytes", "tsm_block_workspace_bytes",
            "tsm_block_fwd", "tsm_block_bwd", "tsm_resnet50_param_count", "tsm_resnet50_num_tensors",
            "tsm_resnet50_param_info", "tsm_resnet50_bn_state_count", "tsm_resnet50_workspace_bytes",
@@ -94,6 +95,7 @@ def lib():
         sig("tsm_shift_fwd", ci, [vp, vp] + [ci] * 8 + [vp])
         sig("tsm_shift_bwd", ci, [vp, vp] + [ci] * 8 + [vp])
         sig("tsm_conv_fwd", ci, [vp, vp, vp, vp, vp, vp, vp, sz, vp])
+        sig("tsm_conv_fwd_noalloc", ci, [vp, vp, vp, vp, vp, vp, vp])
         sig("tsm_conv_dgrad", ci, [vp, vp, vp, vp, vp, sz, vp])
         sig("tsm_conv_wgrad", ci, [vp, vp, vp, vp, ci, vp, sz, vp])
         sig("tsm_block_fwd", ci, [vp, vp, vp, vp, vp, vp, sz, vp])
@@ -179,6 +181,14 @@ def tsm_conv_fwd(desc, x, w, y, ch_sum, ch_sumsq, ws, stream=None):
     p, n = _ws(ws)
     _check(lib().tsm_conv_fwd(ctypes.addressof(desc), _ptr(x), _ptr(w), _ptr(y), _ptr(ch_sum), _ptr(ch_sumsq), p, n,
                               _stream(stream)))
+
+
+NOALLOC_SCRATCH_BYTES = 16 << 20   # TSM_NOALLOC_SCRATCH_BYTES of include/tsm.h
+
+
+def tsm_conv_fwd_noalloc(desc, x, w, y, ch_sum, ch_sumsq, stream=None):
+    _check(lib().tsm_conv_fwd_noalloc(ctypes.addressof(desc), _ptr(x), _ptr(w), _ptr(y), _ptr(ch_sum), _ptr(ch_sumsq),
+                                      _stream(stream)))
 
 
 def tsm_conv_dgrad(desc, dy, w, dx, ws, stream=None):

@@ -1,5 +1,6 @@
 // C-ABI entry points for the shift-fused convolutions and the residual blocks,
 // and the internal block driver the TSM-ResNet-50 step reuses.
+#include <mutex>
 #include "internal.h"
 #include "block.h"
 
@@ -545,6 +546,54 @@ int tsm_conv_dgrad(const tsm_conv_desc* d, const void* dy, const void* w, void* 
 int tsm_conv_wgrad(const tsm_conv_desc* d, const void* x, const void* dy, float* dw, int accumulate, void* ws,
                    size_t ws_bytes, void* stream) {
     return conv_entry(CONV_WGRAD, d, x, dy, dw, nullptr, nullptr, accumulate, ws, ws_bytes, false, (hipStream_t)stream, nullptr);
+}
+
+// ---- tsm_conv_fwd for callers that cannot allocate --------------------------------------------------------------
+// The scratch of the forward convolution (the bf16 working copy of the weights, the per-block rows of the
+// statistics epilogue, the transposed copies for the paper's memory order) lives in a device array that is part of
+// the library's image: every GPU the library runs on holds its own copy, at its own address, until the process
+// ends.  In host code the array's name only stands for the symbol; the device address comes from
+// hipGetSymbolAddress, asked once per device with that device current, and only that address is handed to kernels.
+static __device__ __align__(256) unsigned char g_noalloc_scratch[TSM_NOALLOC_SCRATCH_BYTES];
+
+static int noalloc_scratch(void** out) {
+    static void* ptr[16];               // per device; written once under the lock
+    static std::mutex lock;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16)
+        return fail(TSM_ERR_LAUNCH, "tsm_conv_fwd_noalloc: cannot tell the current device");
+    std::lock_guard<std::mutex> hold(lock);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_noalloc_scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return fail(TSM_ERR_LAUNCH, "tsm_conv_fwd_noalloc: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+        }
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return TSM_OK;
+}
+
+int tsm_conv_fwd_noalloc(const tsm_conv_desc* d, const void* x, const void* w, void* y, float* ch_sum, float* ch_sumsq,
+                         void* stream) {
+    size_t need = 0;
+    TSM_TRY(conv_entry(CONV_FWD, d, nullptr, nullptr, nullptr, nullptr, nullptr, 0, nullptr, 0, true, nullptr, &need));
+    if (need > (size_t)TSM_NOALLOC_SCRATCH_BYTES)
+        return fail(TSM_ERR_WORKSPACE, "tsm_conv_fwd_noalloc: this convolution needs %zu bytes of scratch, the built-in buffer holds %zu",
+                    need, (size_t)TSM_NOALLOC_SCRATCH_BYTES);
+    // argument errors are reported before the device is touched
+    if (!x || !w || !y) return fail(TSM_ERR_NULLPTR, "tsm_conv_fwd_noalloc: null tensor pointer");
+    if ((ch_sum == nullptr) != (ch_sumsq == nullptr))
+        return fail(TSM_ERR_NULLPTR, "tsm_conv_fwd_noalloc: ch_sum and ch_sumsq must both be set or both be NULL");
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return fail(TSM_ERR_ALIGN, "tsm_conv_fwd_noalloc: pointers must be 16-byte aligned");
+    void* scratch = nullptr;
+    TSM_TRY(noalloc_scratch(&scratch));
+    // Nothing in the buffer has to start at zero: the packed weights and the transposed copies are written in full
+    // before they are read, and every block of the convolution clears its own statistics row first.
+    return conv_entry(CONV_FWD, d, x, w, y, ch_sum, ch_sumsq, 0, scratch, (size_t)TSM_NOALLOC_SCRATCH_BYTES, false,
+                      (hipStream_t)stream, nullptr);
 }
 
 size_t tsm_block_saved_bytes(const tsm_block_desc* d) {
