@@ -32,7 +32,11 @@
  *    256-pixel tiles from which those two kernels are chosen (default: five per
  *    compute unit); TSM_IGEMM_BM=128|256 (read once per process) fixes the rows
  *    per tile of the general forward / data-gradient kernel, which otherwise
- *    follows from the number of tiles per compute unit.
+ *    follows from the number of tiles per compute unit; TSM_FUSED_TAIL=0 (read
+ *    at every call) keeps the inference paths on one kernel per convolution and
+ *    TSM_FUSED_TAIL_MIN_TILES=<n> replaces the number of 256-pixel tiles from
+ *    which the two-convolution kernel is chosen (default: three per four
+ *    compute units).
  *  - Return value: TSM_OK or a negative tsm_status.  On error nothing has been
  *    launched (argument errors) or the stream's state is undefined
  *    (TSM_ERR_LAUNCH).  tsm_last_error() returns a host string describing the
@@ -217,6 +221,22 @@ int tsm_block_bwd(const tsm_block_desc* d, const void* x, const void* out, const
                   const void* saved, const tsm_block_params* p,
                   void* dx, const tsm_block_grads* g,
                   void* ws, size_t ws_bytes, void* stream);
+
+/* Forward pass of one block with BatchNorm in inference mode (the mode of the paper's single-GPU throughput
+ * measurement, section 3a / Table 1): every BatchNorm is the fixed map z = gamma*(y - mean)/sqrt(var + bn_eps) + beta
+ * with the running statistics given here.  On the bf16 path (channels innermost) the maps, the shortcut and the
+ * ReLUs ride in the convolution epilogues, and the 3x3 and the last 1x1 convolution of a bottleneck with 64 or 128
+ * middle channels run as ONE kernel that keeps the tensor between them on the chip (the "hardware-friendly
+ * operator" side of section 3's guideline (1): fewer bytes moved per FLOP); TSM_FUSED_TAIL=0 in the environment
+ * (read at every call) keeps one kernel per convolution.  Nothing is saved for a backward pass.
+ * x [N,T,Cin,H,W] -> out [N,T,Cout,Ho,Wo]; statistics fp32 [channels] per BatchNorm (m3/v3: bottlenecks only,
+ * md/vd: projection only); workspace of at least tsm_block_infer_workspace_bytes(desc); errors as tsm_block_fwd. */
+typedef struct {              /* device pointers, fp32: running mean and variance of each BatchNorm */
+    const float *m1, *v1, *m2, *v2, *m3, *v3, *md, *vd;
+} tsm_block_stats;
+size_t tsm_block_infer_workspace_bytes(const tsm_block_desc* d);
+int tsm_block_infer(const tsm_block_desc* d, const void* x, const tsm_block_params* p, const tsm_block_stats* st,
+                    void* out, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
  * One training iteration of TSM-ResNet-50 on one GPU (section 3 model (3),

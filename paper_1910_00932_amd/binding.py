@@ -23,7 +23,7 @@ STATUS = {0: "TSM_OK", -1: "TSM_ERR_NULLPTR", -2: "TSM_ERR_SHAPE", -3: "TSM_ERR_
 EXPORTS = ["tsm_last_error", "tsm_profile_begin", "tsm_profile_end", "tsm_mfma_probe", "tsm_shift_fwd", "tsm_shift_bwd", "tsm_conv_workspace_bytes", "tsm_conv_fwd",
            "tsm_conv_fwd_noalloc",
            "tsm_conv_dgrad", "tsm_conv_wgrad", "tsm_block_saved_bytes", "tsm_block_workspace_bytes",
-           "tsm_block_fwd", "tsm_block_bwd", "tsm_resnet50_param_count", "tsm_resnet50_num_tensors",
+           "tsm_block_fwd", "tsm_block_bwd", "tsm_block_infer_workspace_bytes", "tsm_block_infer", "tsm_resnet50_param_count", "tsm_resnet50_num_tensors",
            "tsm_resnet50_param_info", "tsm_resnet50_bn_state_count", "tsm_resnet50_workspace_bytes",
            "tsm_resnet50_step", "tsm_resnet50_workspace_tensor", "tsm_resnet50_infer_workspace_bytes", "tsm_resnet50_infer",
            "tsm_resnet50_accum_step", "tsm_lr_schedule"]
@@ -56,6 +56,10 @@ class BlockGrads(ctypes.Structure):
                 ("dw1", "dw2", "dw3", "dwd", "dg1", "db1", "dg2", "db2", "dg3", "db3", "dgd", "dbd")]
 
 
+class BlockStats(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("m1", "v1", "m2", "v2", "m3", "v3", "md", "vd")]
+
+
 class R50Desc(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int), ("T", ctypes.c_int), ("size", ctypes.c_int), ("num_classes", ctypes.c_int),
                 ("fold_div", ctypes.c_int), ("lr", ctypes.c_float), ("momentum", ctypes.c_float),
@@ -86,7 +90,7 @@ def lib():
         sig("tsm_profile_begin", ci, [vp])
         sig("tsm_profile_end", ci, [ctypes.c_char_p, sz])
         sig("tsm_mfma_probe", ci, [ci, vp, ctypes.POINTER(ctypes.c_double), vp])
-        for n in ("tsm_conv_workspace_bytes", "tsm_block_saved_bytes", "tsm_block_workspace_bytes",
+        for n in ("tsm_conv_workspace_bytes", "tsm_block_saved_bytes", "tsm_block_workspace_bytes", "tsm_block_infer_workspace_bytes",
                   "tsm_resnet50_workspace_bytes", "tsm_resnet50_infer_workspace_bytes"):
             sig(n, sz, [vp])
         sig("tsm_resnet50_param_count", ctypes.c_int64, [ci])
@@ -99,6 +103,7 @@ def lib():
         sig("tsm_conv_dgrad", ci, [vp, vp, vp, vp, vp, sz, vp])
         sig("tsm_conv_wgrad", ci, [vp, vp, vp, vp, ci, vp, sz, vp])
         sig("tsm_block_fwd", ci, [vp, vp, vp, vp, vp, vp, sz, vp])
+        sig("tsm_block_infer", ci, [vp, vp, vp, vp, vp, vp, sz, vp])
         sig("tsm_block_bwd", ci, [vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp])
         sig("tsm_resnet50_param_info", ci, [ci, ci, ctypes.c_char_p, ci, ctypes.POINTER(ctypes.c_int64),
                                             ctypes.POINTER(ci), ctypes.POINTER(ci * 4), ctypes.POINTER(ci)])
@@ -223,6 +228,19 @@ def tsm_block_fwd(desc, x, params, out, saved, ws, stream=None):
     p, n = _ws(ws)
     _check(lib().tsm_block_fwd(ctypes.addressof(desc), _ptr(x), ctypes.addressof(ps), _ptr(out), _ptr(saved), p, n,
                                _stream(stream)))
+
+
+def tsm_block_infer_workspace_bytes(desc):
+    return int(lib().tsm_block_infer_workspace_bytes(ctypes.addressof(desc)))
+
+
+def tsm_block_infer(desc, x, params, stats, out, ws, stream=None):
+    """params: dict of tsm_block_params fields; stats: dict of tsm_block_stats fields (m1, v1, ...)."""
+    ps = _fill_struct(BlockParams, params)
+    ss = _fill_struct(BlockStats, stats)
+    p, n = _ws(ws)
+    _check(lib().tsm_block_infer(ctypes.addressof(desc), _ptr(x), ctypes.addressof(ps), ctypes.addressof(ss), _ptr(out), p, n,
+                                 _stream(stream)))
 
 
 def tsm_block_bwd(desc, x, out, dout, saved, params, dx, grads, ws, stream=None):

@@ -1,5 +1,6 @@
 // C-ABI entry points for the shift-fused convolutions and the residual blocks,
 // and the internal block driver the TSM-ResNet-50 step reuses.
+#include <algorithm>
 #include <mutex>
 #include "internal.h"
 #include "block.h"
@@ -225,6 +226,131 @@ int block_fwd_impl(BlockPlan& b, const void* x, void* out, Arena& ws, bool dry, 
     const ConvP& pl = b.st[L].p;
     RUN(block_tail_fwd(b.dtype, b.y[L], pl.rows_out(), pl.Cout, b.bn[L].scale, b.bn[L].shift, b.proj ? b.yd : x,
                        b.proj ? b.bnd.scale : nullptr, b.proj ? b.bnd.shift : nullptr, out, s));
+    return TSM_OK;
+}
+
+// ---- forward only, BatchNorm with known statistics (inference) -------------------------------------------------
+// out = act(scale*conv(x) + shift + res): in the convolution's epilogue where its kernel can, else the raw
+// convolution into ytmp and an elementwise pass.
+static int conv_affine_fwd(const StageDef& sd, int dtype, const bf16_t* wp, const void* x, const float* sc, const float* sh,
+                           const void* res, int relu, void* out, void* ytmp, Arena& ws, bool dry, hipStream_t s) {
+    if (use_mfma(sd.p, dtype) && wp && conv_mfma_fwd_can_fuse(sd.p)) {
+        const FwdEpilogue ep = {sc, sh, (const bf16_t*)res, relu};
+        RUN(conv_mfma_fwd(sd.p, (const bf16_t*)x, wp, (bf16_t*)out, nullptr, &ep, s));
+        return TSM_OK;
+    }
+    if (!relu) return fail(TSM_ERR_UNSUPPORTED, "inference: no unfused path for an affine map without ReLU");
+    TSM_TRY(run_conv_fwd(sd.p, dtype, x, sd.w, wp, ytmp, nullptr, ws, dry, s));
+    if (res)
+        RUN(block_tail_fwd(dtype, ytmp, sd.p.rows_out(), sd.p.Cout, sc, sh, res, nullptr, nullptr, out, s));
+    else
+        RUN(bn_relu_apply(dtype, ytmp, sd.p.rows_out(), sd.p.Cout, sc, sh, out, s));
+    return TSM_OK;
+}
+
+int block_infer_impl(BlockPlan& b, const InferParams& ip, const void* x, void* out, void* mid0, void* mid1, void* ytmp,
+                     void* scbuf, Arena& ws, bool dry, hipStream_t s) {
+    const int L = b.nst - 1;
+    const bool bf = b.dtype == TSM_BF16;
+    // the projection shortcut first: BatchNorm(conv(x)) by the affine epilogue where the kernel has one
+    const bool proj_fused = b.proj && use_mfma(b.ds.p, b.dtype) && ip.wp[3] && conv_mfma_fwd_can_fuse(b.ds.p);
+    // the last two convolutions of a bottleneck as one kernel (the tensor between them stays on the chip)
+    const bool tail = bf && b.nst == 3 && ip.wp[1] && ip.wp[2] && (!b.proj || proj_fused) && use_mfma(b.st[1].p, b.dtype) &&
+                      use_mfma(b.st[2].p, b.dtype) && conv_mfma_fused_tail_supported(b.st[1].p, b.st[2].p);
+    const void* cur = x;
+    void* mids[2] = {mid0, mid1};
+    const int plain_stages = tail ? 1 : L;
+    for (int i = 0; i < plain_stages; ++i) {
+        TSM_TRY(conv_affine_fwd(b.st[i], b.dtype, ip.wp[i], cur, ip.sc[i], ip.sh[i], nullptr, 1, mids[i & 1], ytmp, ws, dry, s));
+        cur = mids[i & 1];
+    }
+    const void* res = x;
+    if (b.proj) {
+        if (proj_fused) {
+            const FwdEpilogue ep = {ip.sc[3], ip.sh[3], nullptr, 0};
+            RUN(conv_mfma_fwd(b.ds.p, (const bf16_t*)x, ip.wp[3], (bf16_t*)scbuf, nullptr, &ep, s));
+            res = scbuf;
+        } else {
+            // unfused: both raw convolution outputs, then one pass relu(bn(y) + bn_d(yd))
+            TSM_TRY(run_conv_fwd(b.ds.p, b.dtype, x, b.ds.w, ip.wp[3], scbuf, nullptr, ws, dry, s));
+            TSM_TRY(run_conv_fwd(b.st[L].p, b.dtype, cur, b.st[L].w, ip.wp[L], ytmp, nullptr, ws, dry, s));
+            RUN(block_tail_fwd(b.dtype, ytmp, b.st[L].p.rows_out(), b.st[L].p.Cout, ip.sc[L], ip.sh[L], scbuf, ip.sc[3],
+                               ip.sh[3], out, s));
+            return TSM_OK;
+        }
+    }
+    if (tail) {
+        RUN(conv_mfma_fused_tail(b.st[1].p, b.st[2].p, (const bf16_t*)cur, ip.wp[1], ip.wp[2], ip.sc[1], ip.sh[1], ip.sc[2],
+                                 ip.sh[2], (const bf16_t*)res, (bf16_t*)out, s));
+        return TSM_OK;
+    }
+    return conv_affine_fwd(b.st[L], b.dtype, ip.wp[L], cur, ip.sc[L], ip.sh[L], res, 1, out, ytmp, ws, dry, s);
+}
+
+static void bind_params(BlockPlan& b, const tsm_block_params* p, const tsm_block_grads* g);
+static int check_block_ptrs(const BlockPlan& b, bool bwd, const char* who);
+
+static int block_infer_entry(const tsm_block_desc* d, const void* x, const tsm_block_params* prm, const tsm_block_stats* st,
+                             void* out, void* wsp, size_t ws_bytes, bool dry, hipStream_t s, size_t* need) {
+    const char* who = "tsm_block_infer";
+    BlockPlan b;
+    TSM_TRY(make_block_plan(d, &b, who));
+    const bool tr = d->layout == TSM_NTCHW;
+    if (!dry) {
+        if (!prm || !st) return fail(TSM_ERR_NULLPTR, "%s: null params or statistics", who);
+        bind_params(b, prm, nullptr);
+        TSM_TRY(check_block_ptrs(b, false, who));
+        const float* mv[8] = {st->m1, st->v1, st->m2, st->v2, st->m3, st->v3, st->md, st->vd};
+        for (int i = 0; i < b.nst; ++i)
+            if (!mv[2 * i] || !mv[2 * i + 1]) return fail(TSM_ERR_NULLPTR, "%s: null running statistics (stage %d)", who, i + 1);
+        if (b.proj && (!st->md || !st->vd)) return fail(TSM_ERR_NULLPTR, "%s: null running statistics (projection)", who);
+        if (!x || !out) return fail(TSM_ERR_NULLPTR, "%s: null tensor pointer", who);
+        if (!aligned16(x) || !aligned16(out) || !aligned16(wsp)) return fail(TSM_ERR_ALIGN, "%s: pointers must be 16-byte aligned", who);
+        size_t req = 0;
+        TSM_TRY(block_infer_entry(d, x, prm, st, out, nullptr, 0, true, s, &req));
+        if (req > ws_bytes) return fail(TSM_ERR_WORKSPACE, "%s: workspace %zu bytes, need %zu", who, ws_bytes, req);
+        if (req > 0 && !wsp) return fail(TSM_ERR_NULLPTR, "%s: null workspace", who);
+    }
+    Arena ws(dry ? nullptr : wsp, dry ? (size_t)-1 : ws_bytes);
+    const int es = (int)dtype_size(d->dtype);
+    const ConvP& p0 = b.st[0].p;
+    const ConvP& pl = b.st[b.nst - 1].p;
+    const size_t out_bytes = (size_t)pl.rows_out() * pl.Cout * es;
+    size_t mid_bytes = 0;
+    for (int i = 0; i + 1 < b.nst; ++i) mid_bytes = std::max(mid_bytes, (size_t)b.st[i].p.rows_out() * b.st[i].p.Cout * es);
+    void* mid0 = ws.take(mid_bytes);
+    void* mid1 = ws.take(mid_bytes);
+    void* ytmp = ws.take(out_bytes);
+    void* scbuf = ws.take(out_bytes);
+    InferParams ip{};
+    const StageDef* sds[4] = {&b.st[0], &b.st[1], b.nst == 3 ? &b.st[2] : nullptr, b.proj ? &b.ds : nullptr};
+    const float* mean[4] = {dry ? nullptr : st->m1, dry ? nullptr : st->m2, dry ? nullptr : st->m3, dry ? nullptr : st->md};
+    const float* var[4] = {dry ? nullptr : st->v1, dry ? nullptr : st->v2, dry ? nullptr : st->v3, dry ? nullptr : st->vd};
+    for (int i = 0; i < 4; ++i) {
+        if (!sds[i]) continue;
+        const ConvP& p = sds[i]->p;
+        float* sc = ws.take_n<float>(p.Cout);
+        float* sh = ws.take_n<float>(p.Cout);
+        RUN(bn_eval_vec(sds[i]->g, sds[i]->b, mean[i], var[i], d->bn_eps, p.Cout, sc, sh, s));
+        ip.sc[i] = sc;
+        ip.sh[i] = sh;
+        if (use_mfma(p, d->dtype)) {
+            bf16_t* pk = ws.take_n<bf16_t>((size_t)p.Cout * p.K());
+            RUN(pack_weights_fwd(d->dtype, sds[i]->w, pk, p.Cout, p.Cin, p.taps(), p.Cin, s));
+            ip.wp[i] = pk;
+        }
+    }
+    const void* xi = x;
+    void* oi = out;
+    if (tr) {
+        void* xt = ws.take((size_t)p0.rows_in() * p0.Cin * es);
+        oi = ws.take(out_bytes);
+        RUN(transpose_frames(x, xt, p0.F, p0.Cin, p0.H * p0.W, es, s));
+        xi = xt;
+    }
+    TSM_TRY(block_infer_impl(b, ip, xi, oi, mid0, mid1, ytmp, scbuf, ws, dry, s));
+    if (tr) RUN(transpose_frames(oi, out, pl.F, pl.Ho * pl.Wo, pl.Cout, es, s));
+    if (need) *need = ws.used;
     return TSM_OK;
 }
 
@@ -594,6 +720,17 @@ int tsm_conv_fwd_noalloc(const tsm_conv_desc* d, const void* x, const void* w, v
     // before they are read, and every block of the convolution clears its own statistics row first.
     return conv_entry(CONV_FWD, d, x, w, y, ch_sum, ch_sumsq, 0, scratch, (size_t)TSM_NOALLOC_SCRATCH_BYTES, false,
                       (hipStream_t)stream, nullptr);
+}
+
+size_t tsm_block_infer_workspace_bytes(const tsm_block_desc* d) {
+    size_t need = 0;
+    if (block_infer_entry(d, nullptr, nullptr, nullptr, nullptr, nullptr, 0, true, nullptr, &need) != TSM_OK) return 0;
+    return need;
+}
+
+int tsm_block_infer(const tsm_block_desc* d, const void* x, const tsm_block_params* p, const tsm_block_stats* st, void* out,
+                    void* ws, size_t ws_bytes, void* stream) {
+    return block_infer_entry(d, x, p, st, out, ws, ws_bytes, false, (hipStream_t)stream, nullptr);
 }
 
 size_t tsm_block_saved_bytes(const tsm_block_desc* d) {

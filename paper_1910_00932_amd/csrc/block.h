@@ -51,6 +51,20 @@ int run_conv_dgrad(const ConvP& p, int dtype, const void* dy, const void* w, con
 int run_conv_wgrad(const ConvP& p, int dtype, const void* x, const void* dy, float* dw, float* dwp, int accumulate, Arena& ws,
                    bool dry, hipStream_t s);
 
+// Forward pass of one block with every BatchNorm as a known per-channel affine map (inference): per stage i
+// (0..nst-1, 3 = projection) packed forward weights wp[i] (bf16 path, nullable: packed into the workspace then) and
+// scale / shift vectors sc[i] / sh[i].  Buffers, all caller-owned: mid0 / mid1 hold the outputs of all but the last
+// stage, ytmp a raw convolution output where the kernel cannot apply the map itself, scbuf the projection shortcut
+// (ytmp and scbuf: size of the block's output).  On the bf16 path the maps, the shortcut and the ReLUs ride in the
+// convolution epilogues, and the last two convolutions of a bottleneck run as one kernel where there is one.
+struct InferParams {
+    const bf16_t* wp[4];
+    const float* sc[4];
+    const float* sh[4];
+};
+int block_infer_impl(BlockPlan& b, const InferParams& ip, const void* x, void* out, void* mid0, void* mid1, void* ytmp,
+                     void* scbuf, Arena& ws, bool dry, hipStream_t s);
+
 int make_block_plan(const tsm_block_desc* d, BlockPlan* b, const char* who);
 void block_saved_layout(BlockPlan& b, Arena& sv, bool keep_x_copy);
 int block_fwd_impl(BlockPlan& b, const void* x, void* out, Arena& ws, bool dry, hipStream_t s);

@@ -1513,6 +1513,318 @@ __global__ void __launch_bounds__(512) stem_s2d_kernel(IgemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
+// Two layers in one kernel, forward only, BatchNorm as a known per-channel affine map (inference): the 3x3
+// convolution of a bottleneck (MID -> MID channels, any stride) and the 1x1 convolution behind it (MID -> 4*MID),
+// for MID = 64 or 128.  The MID-channel tensor between them never leaves the chip:
+//
+//   phase 1  a 256-pixel tile of the 3x3 convolution, all MID output channels, as in igemm_ring_kernel: buffer-load
+//            gathers, two LDS stages of A rows [256][64] and B rows [MID][64] in the same swizzled layout, the
+//            next K step in flight in registers;
+//   between  the accumulators go through the affine map and the ReLU (the convolution result rounded to bf16
+//            first, the activation rounded once: what the two-kernel path stores) into the A parts of the stages,
+//            64 channels per stage, in the fragment layout: they are now the A operand of
+//   phase 2  the 1x1 convolution, 128 of its output channels at a time; only its weights move through the stages.
+//            Every column tile ends with the affine map, the shortcut and the ReLU of the block's output and
+//            16-byte stores, staged through LDS as in the other kernels.
+//
+// One block of eight wavefronts per CU; an XCD takes a contiguous eighth of the tiles (neighbouring tiles share the
+// rows above and below a tile's pixels).
+struct TailArgs {
+    const bf16_t* src;        // [F][Hs][Ws][MID]: the activation in front of the 3x3 convolution
+    const bf16_t* w2;         // packed [MID][9][MID]
+    const bf16_t* w3;         // packed [4*MID][MID]
+    const float *sc2, *sh2;   // [MID]: affine map behind the 3x3 convolution (ReLU follows)
+    const float *sc3, *sh3;   // [4*MID]: affine map behind the 1x1 convolution
+    const bf16_t* res;        // [F*Hd*Wd][4*MID]: added before the last ReLU
+    bf16_t* dst;              // [F*Hd*Wd][4*MID]
+    int F, Hs, Ws, Hd, Wd, stride;
+};
+
+template <int MID, bool STREAM>
+__global__ void __launch_bounds__(512) fused_tail_kernel(TailArgs a) {
+    constexpr int NT = 512, BM = 256, WN = 2, MI = 2, HM = 128;
+    constexpr int BN1 = MID, TN1 = BN1 / WN, NJ1 = TN1 / 32;        // phase 1: all MID columns
+    constexpr int BN2 = 128, TN2 = BN2 / WN, NJ2 = TN2 / 32;        // phase 2: 128 columns at a time
+    constexpr int N2 = 4 * MID, NT2 = N2 / BN2, NK2 = MID / BK, CB = MID / BK;
+    constexpr int ROWB = BK * 2;                                    // bytes per LDS row
+    constexpr int STAGE = (BM + BN2) * ROWB;                        // A rows, then up to 128 B rows
+    constexpr int LDC = BN2 + 8;
+    constexpr int PA = BM / (NT / 8), PB1 = BN1 / (NT / 8), PB2 = BN2 / (NT / 8);
+    constexpr int KS = BK / 16;
+    static_assert(MID == 64 || MID == 128, "two stages hold the intermediate tile");
+    static_assert(PA == 4 && PB2 == 2 && PB1 >= 1, "piece counts");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t* Cst = (bf16_t*)(smem + 2 * STAGE);                      // [HM][LDC]
+    RowInfo* s_row = (RowInfo*)(Cst + HM * LDC);                    // [BM]
+    float* s_aff = (float*)(s_row + BM);                            // sc2, sh2 [MID]; sc3, sh3 [N2]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int lrow = tid / 8;
+    const int kvec = (tid % 8) ^ ((lrow >> 1) & 7);
+    const int r = lane & 31, hi = lane >> 5;
+
+    for (int c = tid; c < MID; c += NT) {
+        s_aff[c] = a.sc2[c];
+        s_aff[MID + c] = a.sh2[c];
+    }
+    for (int c = tid; c < N2; c += NT) {
+        s_aff[2 * MID + c] = a.sc3[c];
+        s_aff[2 * MID + N2 + c] = a.sh3[c];
+    }
+
+    const int hw_d = a.Hd * a.Wd, hw_s = a.Hs * a.Ws;
+    const unsigned M = (unsigned)a.F * (unsigned)hw_d;
+    const int mtiles = (int)((M + BM - 1) / BM);
+    const int bias_el = (a.Ws + 1) * MID;                           // the most negative tap origin (pad 1)
+    const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(a.src - bias_el, (uint32_t)(((long)a.F * hw_s * MID + bias_el) * 2));
+    const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.w2, (uint32_t)(MID * 9 * MID * 2));
+    const __amdgpu_buffer_rsrc_t rsrc_c = make_rsrc(a.w3, (uint32_t)(N2 * MID * 2));
+
+    // fragment addresses inside a stage (see igemm_ring_kernel)
+    int a_rd[KS], b_rd[KS];
+    {
+        const int sw = (r >> 1) & 7;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int pos = ((2 * ks + hi) ^ sw) * 16;
+            a_rd[ks] = (wm * 32 + r) * ROWB + pos;
+            b_rd[ks] = (BM + r) * ROWB + pos;                       // + (wn * TN + j * 32) rows
+        }
+    }
+
+    // an XCD takes a contiguous eighth of the tiles
+    const bool by_xcd = (gridDim.x % 8) == 0;
+    const int per_xcd = by_xcd ? (mtiles + 7) / 8 : mtiles;
+    const int xcd = by_xcd ? (int)(blockIdx.x % 8) : 0;
+    const int seq_step = by_xcd ? (int)(gridDim.x / 8) : (int)gridDim.x;
+    auto tile_at = [&](int seq) {
+        const int t = xcd * per_xcd + seq;
+        return (seq < per_xcd && t < mtiles) ? t : -1;
+    };
+
+    u32x4 greg[PA + PB2];
+    uint32_t aoff[PA], amask[PA];
+
+    // phase 1, K step k = (tap, 64-channel block): gathers of the A rows and the weights of the tap
+    auto load1 = [&](int k) {
+        const int tap = k / CB, chb = (k - tap * CB) * BK;
+        const int th = tap / 3, tw = tap - th * 3;
+        const uint32_t need = (1u << th) | (1u << (8 + tw));
+        const int soff_a = ((th * a.Ws + tw) * MID + chb) * 2;
+        const int soff_b = (tap * MID + chb) * 2;
+#pragma unroll
+        for (int i = 0; i < PA; ++i)
+            greg[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, (int)((amask[i] & need) == need ? aoff[i] : OOB_OFFSET), soff_a, 0);
+#pragma unroll
+        for (int j = 0; j < PB1; ++j)
+            greg[PA + j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, (int)((uint32_t)(j * (NT / 8) + lrow) * (9 * MID * 2) + kvec * 16), soff_b, 0);
+    };
+    auto store1 = [&](int stage) {
+#pragma unroll
+        for (int i = 0; i < PA; ++i) *(u32x4*)(smem + stage * STAGE + i * (NT / 8) * ROWB + tid * 16) = greg[i];
+#pragma unroll
+        for (int j = 0; j < PB1; ++j) *(u32x4*)(smem + stage * STAGE + (BM + j * (NT / 8)) * ROWB + tid * 16) = greg[PA + j];
+    };
+    // phase 2, step s = (column tile, 64-channel block): weights of the 1x1 convolution only
+    auto load2 = [&](int s2) {
+        const int nt = s2 / NK2, kk = s2 - nt * NK2;
+#pragma unroll
+        for (int j = 0; j < PB2; ++j)
+            greg[PA + j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_c, (int)((uint32_t)(nt * BN2 + j * (NT / 8) + lrow) * (MID * 2) + kvec * 16), kk * BK * 2, 0);
+    };
+    auto store2 = [&](int stage) {
+#pragma unroll
+        for (int j = 0; j < PB2; ++j) *(u32x4*)(smem + stage * STAGE + (BM + j * (NT / 8)) * ROWB + tid * 16) = greg[PA + j];
+    };
+
+    __syncthreads();   // the affine vectors
+
+    for (int seq = by_xcd ? (int)(blockIdx.x / 8) : (int)blockIdx.x, tile = tile_at(seq); tile >= 0; seq += seq_step, tile = tile_at(seq)) {
+        // ---- rows of the tile: gather origin, tap validity, destination row
+        if (tid < BM) {
+            const unsigned m = (unsigned)tile * BM + tid;
+            RowInfo info;
+            info.off = 0;
+            info.mask = 0;
+            info.dst = -1;
+            if (m < M) {
+                const int f = (int)(m / (unsigned)hw_d);
+                const int q = (int)(m - (unsigned)f * (unsigned)hw_d);
+                const int dh = q / a.Wd, dw = q - dh * a.Wd;
+                const int oh = dh * a.stride - 1, ow = dw * a.stride - 1;
+                uint32_t mask = 0;
+#pragma unroll
+                for (int t = 0; t < 3; ++t) {
+                    if (oh + t >= 0 && oh + t < a.Hs) mask |= 1u << t;
+                    if (ow + t >= 0 && ow + t < a.Ws) mask |= 1u << (8 + t);
+                }
+                info.off = ((long)f * hw_s + (long)oh * a.Ws + ow) * MID;
+                info.mask = mask;
+                info.dst = (int)m;
+            }
+            s_row[tid] = info;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < PA; ++i) {
+            const RowInfo ri = s_row[i * (NT / 8) + lrow];
+            aoff[i] = (uint32_t)((ri.off + bias_el) * 2) + kvec * 16;
+            amask[i] = ri.mask;
+        }
+
+        // ---- phase 1
+        f32x16 acc1[MI][NJ1];
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ1; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc1[i][j][e] = 0.f;
+        constexpr int NK1 = 9 * CB;
+        load1(0);
+        store1(0);
+        __syncthreads();
+        for (int k = 0; k < NK1; ++k) {
+            const unsigned char* st = smem + (k & 1) * STAGE;
+            if (k + 1 < NK1) load1(k + 1);
+            else load2(0);                  // the first weights of phase 2 travel behind the last step
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                bf16x8 af[MI], bfr[NJ1];
+#pragma unroll
+                for (int i = 0; i < MI; ++i) af[i] = *(const bf16x8*)(st + a_rd[ks] + i * HM * ROWB);
+#pragma unroll
+                for (int j = 0; j < NJ1; ++j) bfr[j] = *(const bf16x8*)(st + b_rd[ks] + (wn * TN1 + j * 32) * ROWB);
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NJ1; ++j)
+                        // operands swapped as in igemm_ring_kernel: the result block is [channel][pixel]
+                        acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc1[i][j], 0, 0, 0);
+            }
+            if (k + 1 < NK1) store1((k + 1) & 1);
+            __syncthreads();
+        }
+
+        // ---- the intermediate tile: affine map + ReLU, into the A parts of the stages (64 channels per stage; with
+        // 64 channels in all, stage 0).  Lane: pixel r of its row block, channels 8*q + 4*hi + {0..3} of its column block.
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int row = i * HM + wm * 32 + r;
+            const int sw = (row >> 1) & 7;
+#pragma unroll
+            for (int j = 0; j < NJ1; ++j) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int c0 = wn * TN1 + j * 32 + 8 * q + 4 * hi;      // first of four channels
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float y = bf16_to_f32(f32_to_bf16(acc1[i][j][4 * q + e]));
+                        const float z = fmaf(y, s_aff[c0 + e], s_aff[MID + c0 + e]);
+                        v[e] = z > 0.f ? z : 0.f;
+                    }
+                    uint2 w;
+                    w.x = pack_bf16x2(v[0], v[1]);
+                    w.y = pack_bf16x2(v[2], v[3]);
+                    const int stage = c0 / BK, cv = (c0 % BK) / 8;
+                    *(uint2*)(smem + stage * STAGE + row * ROWB + ((cv ^ sw) * 16) + (c0 & 4) * 2) = w;
+                }
+            }
+        }
+        store2(0);
+        __syncthreads();
+
+        // ---- phase 2
+        constexpr int CV = BN2 / 8, RPS = NT / CV, NPS = HM / RPS;
+        const int vcol = tid % CV, r0 = tid / CV;
+        int s2 = 0;
+        for (int nt = 0; nt < NT2; ++nt) {
+            f32x16 acc2[MI][NJ2];
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ2; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc2[i][j][e] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < NK2; ++kk, ++s2) {
+                const bool more = s2 + 1 < NT2 * NK2;
+                if (more) load2(s2 + 1);
+                const unsigned char* sa = smem + (NK2 == 1 ? 0 : kk) * STAGE;    // the intermediate tile's 64-channel block
+                const unsigned char* sb = smem + (s2 & 1) * STAGE;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    bf16x8 af[MI], bfr[NJ2];
+#pragma unroll
+                    for (int i = 0; i < MI; ++i) af[i] = *(const bf16x8*)(sa + a_rd[ks] + i * HM * ROWB);
+#pragma unroll
+                    for (int j = 0; j < NJ2; ++j) bfr[j] = *(const bf16x8*)(sb + b_rd[ks] + (wn * TN2 + j * 32) * ROWB);
+#pragma unroll
+                    for (int i = 0; i < MI; ++i)
+#pragma unroll
+                        for (int j = 0; j < NJ2; ++j)
+                            acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc2[i][j], 0, 0, 0);
+                }
+                if (more) store2((s2 + 1) & 1);
+                __syncthreads();
+            }
+            // epilogue of the column tile: scale / shift of this thread's eight columns, shortcut, ReLU
+            const int col = nt * BN2 + vcol * 8;
+            float sc[8], sh[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                sc[q] = s_aff[2 * MID + col + q];
+                sh[q] = s_aff[2 * MID + N2 + col + q];
+            }
+#pragma unroll
+            for (int h = 0; h < MI; ++h) {
+                if (h > 0) __syncthreads();
+                // the shortcut of this pass is requested before the staging
+                u32x4 rr[NPS];
+                int mrow[NPS];
+#pragma unroll
+                for (int pss = 0; pss < NPS; ++pss) {
+                    mrow[pss] = s_row[h * HM + pss * RPS + r0].dst;
+                    rr[pss] = *(const u32x4*)(mrow[pss] >= 0 ? a.res + (long)mrow[pss] * N2 + col : (const bf16_t*)g_zero_page);
+                }
+#pragma unroll
+                for (int j = 0; j < NJ2; ++j) {
+                    bf16_t* dstp = Cst + (wm * 32 + r) * LDC + wn * TN2 + j * 32 + 4 * hi;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        uint2 w;
+                        w.x = pack_bf16x2(acc2[h][j][4 * q], acc2[h][j][4 * q + 1]);
+                        w.y = pack_bf16x2(acc2[h][j][4 * q + 2], acc2[h][j][4 * q + 3]);
+                        *(uint2*)(dstp + 8 * q) = w;
+                    }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int pss = 0; pss < NPS; ++pss) {
+                    if (mrow[pss] < 0) continue;
+                    u32x4 v = *(const u32x4*)(Cst + (pss * RPS + r0) * LDC + vcol * 8);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float lo = fmaf(__uint_as_float(v[e] << 16), sc[2 * e], sh[2 * e]) + __uint_as_float(rr[pss][e] << 16);
+                        float hi2 = fmaf(__uint_as_float(v[e] & 0xffff0000u), sc[2 * e + 1], sh[2 * e + 1]) + __uint_as_float(rr[pss][e] & 0xffff0000u);
+                        lo = lo > 0.f ? lo : 0.f;
+                        hi2 = hi2 > 0.f ? hi2 : 0.f;
+                        v[e] = pack_bf16x2(lo, hi2);
+                    }
+                    u32x4* dq = (u32x4*)(a.dst + (long)mrow[pss] * N2 + col);
+                    if (STREAM) __builtin_nontemporal_store(v, dq);
+                    else *dq = v;
+                }
+            }
+        }
+        __syncthreads();   // the row table and the stages are rewritten by the next tile
+    }
+}
+
+// ---------------------------------------------------------------------------------
 static int g_num_cu = 0;
 static int num_cu() {
     if (g_num_cu == 0) {
@@ -2367,6 +2679,57 @@ int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw
     else
         wgrad_kernel<64, 64><<<grid, dim3(256), 0, s>>>(a);
     return check_launch(big ? "wgrad_128x128" : (wide ? "wgrad_64x192" : "wgrad_64x64"));
+}
+
+// ---- 3x3 + 1x1 in one kernel (inference) ------------------------------------------------------------------------
+bool conv_mfma_fused_tail_supported(const ConvP& p2, const ConvP& p3) {
+    const char* e = getenv("TSM_FUSED_TAIL");   // TSM_FUSED_TAIL=0 keeps one kernel per convolution (read at every call)
+    if (e && e[0] == '0') return false;
+    const int mid = p2.Cin;
+    if (!(mid == 64 || mid == 128)) return false;
+    if (p2.Cout != mid || p3.Cin != mid || p3.Cout != 4 * mid) return false;
+    if (p2.KT != 1 || p2.KH != 3 || p2.KW != 3 || p2.pad != 1 || p2.fold != 0 || p2.pitch != 0 || p2.stride < 1 || p2.stride > 2) return false;
+    if (p3.KT != 1 || p3.KH != 1 || p3.KW != 1 || p3.pad != 0 || p3.stride != 1 || p3.fold != 0 || p3.pitch != 0) return false;
+    if (p3.H != p2.Ho || p3.W != p2.Wo || p3.F != p2.F) return false;
+    const long limit = 0x7ff00000L;
+    if ((p2.rows_in() + p2.W + 1) * (long)mid * 2 >= limit || p3.rows_out() * 4L * mid * 2 >= limit) return false;
+    // fewer than three quarters of a round of tiles: the two-kernel path spreads such layers over more blocks
+    // (TSM_FUSED_TAIL_MIN_TILES=<n>, read at every call, moves the threshold: tests and comparisons set it)
+    const char* t = getenv("TSM_FUSED_TAIL_MIN_TILES");
+    const long min_tiles = t ? atol(t) : ((long)num_cu() * 3 + 3) / 4;
+    if ((p2.rows_out() + 255) / 256 < min_tiles) return false;
+    return true;
+}
+
+template <int MID, bool STREAM>
+static int launch_fused_tail(const TailArgs& a, long rows, hipStream_t s) {
+    auto kern = fused_tail_kernel<MID, STREAM>;
+    constexpr size_t smem = (size_t)2 * (256 + 128) * BK * sizeof(bf16_t) + (size_t)128 * (128 + 8) * sizeof(bf16_t) +
+                            (size_t)256 * sizeof(RowInfo) + (size_t)10 * MID * sizeof(float);
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return fail(TSM_ERR_LAUNCH, "fused_tail: cannot raise dynamic LDS limit");
+        configured = true;
+    }
+    const int grid = igemm_grid((int)((rows + 255) / 256), 64, 64, 1);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), smem, s, a);
+    return check_launch(MID == 64 ? "fused_tail_64" : "fused_tail_128");
+}
+
+int conv_mfma_fused_tail(const ConvP& p2, const ConvP& p3, const bf16_t* x, const bf16_t* w2p, const bf16_t* w3p,
+                         const float* sc2, const float* sh2, const float* sc3, const float* sh3, const bf16_t* res,
+                         bf16_t* out, hipStream_t s) {
+    if (!conv_mfma_fused_tail_supported(p2, p3)) return fail(TSM_ERR_UNSUPPORTED, "fused tail: no kernel for this pair of layers");
+    if (!res) return fail(TSM_ERR_NULLPTR, "fused tail: the shortcut is required");
+    TailArgs a;
+    a.src = x; a.w2 = w2p; a.w3 = w3p; a.sc2 = sc2; a.sh2 = sh2; a.sc3 = sc3; a.sh3 = sh3; a.res = res; a.dst = out;
+    a.F = p2.F; a.Hs = p2.H; a.Ws = p2.W; a.Hd = p2.Ho; a.Wd = p2.Wo; a.stride = p2.stride;
+    const long rows = p2.rows_out();
+    if (rows == 0) return TSM_OK;
+    const bool stream = rows * 4L * p2.Cin * 2 > (64L << 20);
+    if (p2.Cin == 64) return stream ? launch_fused_tail<64, true>(a, rows, s) : launch_fused_tail<64, false>(a, rows, s);
+    return stream ? launch_fused_tail<128, true>(a, rows, s) : launch_fused_tail<128, false>(a, rows, s);
 }
 
 }  // namespace tsm

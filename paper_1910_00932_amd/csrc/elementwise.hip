@@ -209,6 +209,24 @@ int bn_finalize(const float* partial, int nblocks, long rows, int C, const float
     return check_launch("bn_finalize");
 }
 
+// Inference-mode BatchNorm as an affine map: scale = gamma / sqrt(var + eps), shift = beta - mean * scale.
+__global__ void __launch_bounds__(256) bn_eval_vec_kernel(const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                          const float* __restrict__ mean, const float* __restrict__ var,
+                                                          float eps, int C, float* __restrict__ scale,
+                                                          float* __restrict__ shift) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C) return;
+    const float sc = gamma[c] / sqrtf(var[c] + eps);
+    scale[c] = sc;
+    shift[c] = fmaf(-mean[c], sc, beta[c]);
+}
+
+int bn_eval_vec(const float* gamma, const float* beta, const float* mean, const float* var, float eps, int C,
+                float* scale, float* shift, hipStream_t s) {
+    bn_eval_vec_kernel<<<dim3(cdiv(C, 256)), dim3(256), 0, s>>>(gamma, beta, mean, var, eps, C, scale, shift);
+    return check_launch("bn_eval_vec");
+}
+
 __global__ void stats_to_float_kernel(const float* __restrict__ partial, int nblocks, int C, float* sum, float* sumsq) {
     const int c = blockIdx.x * SP_C + threadIdx.x;
     double s1, s2;

@@ -54,6 +54,9 @@ struct BnVec {           // per-channel fp32 vectors of one BatchNorm, each [C]
 int bn_finalize(const float* partial, int nblocks, long rows, int C, const float* gamma, const float* beta,
                 float eps, BnVec out, float* run_mean, float* run_var, float momentum, hipStream_t s);
 int stats_to_float(const float* partial, int nblocks, int C, float* sum, float* sumsq, hipStream_t s);
+// scale = gamma / sqrt(var + eps), shift = beta - mean * scale (BatchNorm with known statistics)
+int bn_eval_vec(const float* gamma, const float* beta, const float* mean, const float* var, float eps, int C,
+                float* scale, float* shift, hipStream_t s);
 // z = relu(scale*y + shift)
 int bn_relu_apply(int dtype, const void* y, long rows, int C, const float* scale, const float* shift, void* z,
                   hipStream_t s);
@@ -100,6 +103,14 @@ struct FwdEpilogue {
 bool conv_mfma_fwd_can_fuse(const ConvP& p);
 int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, float* stats_partial,
                   const FwdEpilogue* ep, hipStream_t s);
+// The 3x3 convolution of a bottleneck and the 1x1 convolution behind it in one kernel, forward only, with both
+// BatchNorms as known per-channel affine maps (inference): out = relu(sc3*conv1x1(relu(sc2*conv3x3(x) + sh2)) + sh3
+// + res).  p2 / p3 describe the two convolutions; w2p / w3p are their packed forward weights.  The intermediate
+// tensor stays on the chip.  Supported: 64 -> 64 -> 256 and 128 -> 128 -> 512 channels, stride 1 or 2 on the 3x3.
+bool conv_mfma_fused_tail_supported(const ConvP& p2, const ConvP& p3);
+int conv_mfma_fused_tail(const ConvP& p2, const ConvP& p3, const bf16_t* x, const bf16_t* w2p, const bf16_t* w3p,
+                         const float* sc2, const float* sh2, const float* sc3, const float* sh3, const bf16_t* res,
+                         bf16_t* out, hipStream_t s);
 // Optional fusion into the data-gradient epilogue: dx is the gradient w.r.t. act = ReLU(BatchNorm(y)) (all
 // [rows_in][Cin] bf16); it is stored already masked with act > 0, and `partial`, fp32
 // [conv_mfma_dgrad_blocks(p)][2*Cin], receives per block the per-channel sums of dz and of dz*(y-mean)*rstd.

@@ -1232,24 +1232,6 @@ static int r50_infer(const tsm_r50_desc* d, const void* clips, const float* para
     const size_t scratch_cap = dry ? (size_t)-1 : (ws_bytes > A.used ? ws_bytes - A.used : 0);
     size_t scratch_need = 0;
 
-    // out = act(scale*conv(x) + shift + res): fused where the kernel can, else convolution + elementwise pass
-    auto conv_bn_act = [&](const StageDef& sd, const bf16_t* wp, const void* x, const float* sc, const float* sh,
-                           const void* res, void* out) -> int {
-        Arena ws(scratch_base, scratch_cap);
-        if (bf && mfma_conv_supported(sd.p) && conv_mfma_fwd_can_fuse(sd.p)) {
-            const FwdEpilogue ep = {sc, sh, (const bf16_t*)res, 1};
-            RUN(conv_mfma_fwd(sd.p, (const bf16_t*)x, wp, (bf16_t*)out, nullptr, &ep, s));
-            return TSM_OK;
-        }
-        TSM_TRY(run_conv_fwd(sd.p, dtype, x, sd.w, wp, ytmp, nullptr, ws, dry, s));
-        if (ws.used > scratch_need) scratch_need = ws.used;
-        if (res)
-            RUN(block_tail_fwd(dtype, ytmp, sd.p.rows_out(), sd.p.Cout, sc, sh, res, nullptr, nullptr, out, s));
-        else
-            RUN(bn_relu_apply(dtype, ytmp, sd.p.rows_out(), sd.p.Cout, sc, sh, out, s));
-        return TSM_OK;
-    };
-
     // ================= forward =================
     if (!dry) {
         bn_eval_params_kernel<<<dim3(cdiv(nch, 256)), dim3(256), 0, s>>>(bt, params, bn_state, d->bn_eps, scale_all, shift_all);
@@ -1287,29 +1269,16 @@ static int r50_infer(const tsm_r50_desc* d, const void* clips, const float* para
     const void* cur = p0;
     int flip = 0;
     for (IBlk& b : blks) {
-        BlockPlan& pl = b.plan;
-        TSM_TRY(conv_bn_act(pl.st[0], b.wp[0], cur, b.sc[0], b.sh[0], nullptr, mid[0]));
-        TSM_TRY(conv_bn_act(pl.st[1], b.wp[1], mid[0], b.sc[1], b.sh[1], nullptr, mid[1]));
-        void* out = act[flip];
-        if (pl.proj) {
-            const StageDef& sd = pl.ds;
-            if (bf && mfma_conv_supported(sd.p) && conv_mfma_fwd_can_fuse(sd.p)) {
-                // shortcut = BatchNorm(conv(x)) by the affine epilogue, then added in the last convolution's epilogue
-                const FwdEpilogue ep = {b.sc[3], b.sh[3], nullptr, 0};
-                RUN(conv_mfma_fwd(sd.p, (const bf16_t*)cur, b.wp[3], (bf16_t*)scbuf, nullptr, &ep, s));
-                TSM_TRY(conv_bn_act(pl.st[2], b.wp[2], mid[1], b.sc[2], b.sh[2], scbuf, out));
-            } else {
-                // unfused: both raw convolution outputs, then one pass relu(bn3(y3) + bnd(yd))
-                Arena ws(scratch_base, scratch_cap);
-                TSM_TRY(run_conv_fwd(sd.p, dtype, cur, sd.w, b.wp[3], scbuf, nullptr, ws, dry, s));
-                TSM_TRY(run_conv_fwd(pl.st[2].p, dtype, mid[1], pl.st[2].w, b.wp[2], ytmp, nullptr, ws, dry, s));
-                if (ws.used > scratch_need) scratch_need = ws.used;
-                RUN(block_tail_fwd(dtype, ytmp, pl.st[2].p.rows_out(), pl.st[2].p.Cout, b.sc[2], b.sh[2], scbuf, b.sc[3],
-                                   b.sh[3], out, s));
-            }
-        } else {
-            TSM_TRY(conv_bn_act(pl.st[2], b.wp[2], mid[1], b.sc[2], b.sh[2], cur, out));
+        Arena ws(scratch_base, scratch_cap);
+        InferParams ip{};
+        for (int i = 0; i < 4; ++i) {
+            ip.wp[i] = b.wp[i];
+            ip.sc[i] = b.sc[i];
+            ip.sh[i] = b.sh[i];
         }
+        void* out = act[flip];
+        TSM_TRY(block_infer_impl(b.plan, ip, cur, out, mid[0], mid[1], ytmp, scbuf, ws, dry, s));
+        if (ws.used > scratch_need) scratch_need = ws.used;
         cur = out;
         flip ^= 1;
     }

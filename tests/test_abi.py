@@ -134,3 +134,29 @@ def test_workspace_plan_switches_kernels_at_2_gib():
     above, rows_above = stats_rows(168)
     assert below < 0x7ff00000 <= above
     assert rows_above == 2 * rows_below and rows_below % 8 == 0
+
+
+def test_block_infer_argument_errors():
+    L = B.lib()
+    a = 4096
+    d = B.BlockDesc(kind=B.TSM_BLOCK_BOTTLENECK, N=1, T=2, Cin=16, H=4, W=4, Cmid=8, Cout=16, stride=1,
+                    has_projection=0, fold_div=8, dtype=B.TSM_F32, layout=B.TSM_NTHWC, bn_eps=1e-5)
+    need = B.tsm_block_infer_workspace_bytes(d)
+    assert need > 0
+    ps, ss = B.BlockParams(), B.BlockStats()
+    for n, _ in B.BlockParams._fields_:
+        setattr(ps, n, a)
+    for n, _ in B.BlockStats._fields_:
+        setattr(ss, n, a)
+    args = lambda **kw: [kw.get("d", ctypes.addressof(d)), kw.get("x", a), kw.get("p", ctypes.addressof(ps)),
+                         kw.get("s", ctypes.addressof(ss)), kw.get("out", a), a, kw.get("n", need), None]
+    assert L.tsm_block_infer(*args(x=None)) == -1
+    assert L.tsm_block_infer(*args(p=None)) == -1
+    assert L.tsm_block_infer(*args(s=None)) == -1
+    assert L.tsm_block_infer(*args(n=need - 1)) == -6
+    assert L.tsm_block_infer(*args(out=a + 8)) == -7
+    ss.m2 = None
+    assert L.tsm_block_infer(*args()) == -1 and "statistics" in B.tsm_last_error()
+    bad = B.BlockDesc(kind=B.TSM_BLOCK_BOTTLENECK, N=1, T=2, Cin=16, H=4, W=4, Cmid=8, Cout=32, stride=1,
+                      has_projection=0, fold_div=8, dtype=B.TSM_F32, layout=B.TSM_NTHWC, bn_eps=1e-5)
+    assert B.tsm_block_infer_workspace_bytes(bad) == 0
