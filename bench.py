@@ -53,7 +53,9 @@ def igemm_class(kind, cd, cs, rows, taps=1, stride=1):
         r = "r128" if tiles256 * 4 < 256 * 3 else "256"
         if cs == 64 and cd == 64 and taps == 9 and stride == 1 and -(-rows // 256) >= 5 * 256:
             return "igemm_%s_c64" % kind      # the 64 -> 64 channel 3x3 kernel (five rounds of tiles or more)
-        return "igemm_%s_%sx%s" % (kind, r, "64" if cd <= 64 else "128")
+        # 64 columns per tile for narrow outputs, and where even 128x128 tiles leave a quarter of the CUs idle
+        narrow = cd <= 64 or (r == "r128" and -(-rows // 128) * -(-cd // 128) * 4 < 256 * 3)
+        return "igemm_%s_%sx%s" % (kind, r, "64" if narrow else "128")
     return "igemm_%s_%s" % (kind, "128x64" if cd <= 64 else "128x128")
 
 

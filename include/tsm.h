@@ -32,7 +32,9 @@
  *    256-pixel tiles from which those two kernels are chosen (default: five per
  *    compute unit); TSM_IGEMM_BM=128|256 (read once per process) fixes the rows
  *    per tile of the general forward / data-gradient kernel, which otherwise
- *    follows from the number of tiles per compute unit; TSM_FUSED_TAIL=0 (read
+ *    follows from the number of tiles per compute unit; TSM_IGEMM_NARROW=0 (read once
+ *    per process) keeps 128-column tiles where the library would take 64
+ *    columns to fill the machine; TSM_FUSED_TAIL=0 (read
  *    at every call) keeps the inference paths on one kernel per convolution and
  *    TSM_FUSED_TAIL_MIN_TILES=<n> replaces the number of 256-pixel tiles from
  *    which the two-convolution kernel is chosen (default: three per four

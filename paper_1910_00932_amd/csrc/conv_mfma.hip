@@ -1971,6 +1971,21 @@ static int ring_rows(long rows, int Cd) {
     return tiles256 * 4 < (long)num_cu() * 3 ? 128 : 256;
 }
 
+// Columns per tile of the ring kernel: 128, or 64 for outputs of at most 64 channels and where even 128-row tiles
+// with 128 columns would leave a good part of the CUs without a tile (the last stage at the paper's batch of 8
+// clips: 25 row tiles x 4 column tiles for 256 CUs).  TSM_IGEMM_NARROW=0 keeps 128 columns (for comparisons).
+static int ring_cols(long rows, int Cd) {
+    if (Cd <= 64) return 64;
+    static int enabled = -1;
+    if (enabled < 0) {
+        const char* e = getenv("TSM_IGEMM_NARROW");
+        enabled = (e && e[0] == '0') ? 0 : 1;
+    }
+    if (!enabled || ring_rows(rows, Cd) != 128) return 128;
+    const long tiles = ((rows + 127) / 128) * ((Cd + 127) / 128);
+    return tiles * 4 < (long)num_cu() * 3 ? 64 : 128;
+}
+
 // The 64 -> 64 channel 3x3 kernel takes the layers it is written for when the general kernel would run them with
 // 256-row tiles (the two then launch the same number of blocks, which is what callers size the statistics rows by)
 // and there are at least five rounds of tiles: every block first loads all weights and a tile is long, so with
@@ -2056,7 +2071,7 @@ static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
         return rows * a.Cd * 2 > (64L << 20) ? launch_stem_s<true>(a, s) : launch_stem_s<false>(a, s);
     if (ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K, a.pitch != a.Cs)) {
         if (ring_rows(rows, a.Cd) == 128) {
-            if (a.Cd <= 64) return launch_igemm_ring<128, 64, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_r128x64" : "igemm_fwd_r128x64", s);
+            if (ring_cols(rows, a.Cd) == 64) return launch_igemm_ring<128, 64, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_r128x64" : "igemm_fwd_r128x64", s);
             return launch_igemm_ring<128, 128, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_r128x128" : "igemm_fwd_r128x128", s);
         }
         if (a.Cd <= 64) return launch_igemm_ring<256, 64, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_256x64" : "igemm_fwd_256x64", s);
@@ -2072,7 +2087,7 @@ int conv_mfma_fwd_blocks(const ConvP& p) {
     if (ring_eligible(p.Cin, p.rows_in() * (long)p.pix_pitch() + p.Cin + (long)(p.pad * p.W + p.pad) * p.pix_pitch(), (long)p.Cout * p.K(), p.pix_pitch() != p.Cin))
     {
         const int bm = ring_rows(p.rows_out(), p.Cout);
-        return igemm_grid((int)((p.rows_out() + bm - 1) / bm), p.Cout, bn, 1);
+        return igemm_grid((int)((p.rows_out() + bm - 1) / bm), p.Cout, ring_cols(p.rows_out(), p.Cout), 1);
     }
     return igemm_grid((int)((p.rows_out() + 127) / 128), p.Cout, bn, 2);
 }
@@ -2118,7 +2133,7 @@ int conv_mfma_dgrad_blocks(const ConvP& p) {
     if (!ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K, a.pitch != a.Cs)) return 0;
     if ((long)a.F * a.Hd * a.Wd == 0) return 0;
     const int mtiles = setup_classes(a, true, ring_rows((long)a.F * a.Hd * a.Wd, a.Cd));
-    return igemm_grid(mtiles, a.Cd, a.Cd <= 64 ? 64 : 128, 1);
+    return igemm_grid(mtiles, a.Cd, ring_cols((long)a.F * a.Hd * a.Wd, a.Cd), 1);
 }
 
 int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* dx, const bf16_t* addend,

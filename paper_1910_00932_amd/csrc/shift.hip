@@ -73,6 +73,10 @@ int check_launch(const char* what) {
 // cover the frame's vectors: 32-bit index arithmetic, no division by the frame size per thread.  Measured on a
 // [64,8,256,56,56] bf16 tensor: one vector per thread beats two or four (5.3 TB/s), blocks of 128 threads beat
 // 256 and 1024 (6.33 / 6.28 / 6.0 TB/s), regular loads with nontemporal stores beat nontemporal loads (5.9 TB/s).
+// A second sweep with all loads of a thread issued before its stores: 2 / 4 vectors per thread 6.1-6.2 / 5.7-6.0 TB/s,
+// grid-stride blocks of 256 threads with 4 or 8 vectors 5.5 / 5.2, blocks of 64 / 192 / 256 threads 6.33 / 6.08 / 6.24,
+// regular stores 6.3, frames on the fast grid axis 5.1 -- against 6.27-6.39 for this form (the memory system here
+// prefers many small independent wavefronts; the figure itself drifts by 1-2 % within a process).
 static constexpr int SHIFT_U = 1;     // vectors per thread
 static constexpr int SHIFT_NT = 128;  // threads per block
 template <typename V>
