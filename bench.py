@@ -78,6 +78,14 @@ def wgrad_class(cout, cin, taps):
     return "wgrad_64x192" if (cout <= 64 and kk >= 192 and kk % 192 == 0) else "wgrad_64x64"
 
 
+def dgrad_class(name, rin, cin, rout, cout, taps):
+    """Class of a layer's data gradient.  A strided 1x1 projection sends gradient only to the input pixels with even
+    row and column: the library computes it as a stride-1 data gradient on the output grid (compact form)."""
+    if name.endswith(".ds") and rin != rout:
+        return igemm_class("dgrad", cin, cout, rout, 1, 1)
+    return igemm_class("dgrad", cin, cout, rin, taps, 1 if rin == rout else 2)
+
+
 def class_work(F, size):
     """Algorithmic FLOPs per step of each MFMA kernel class (2 x multiply-accumulates of the layers it
     runs) -- counted from the layer table, never from padded tiles."""
@@ -91,7 +99,7 @@ def class_work(F, size):
         stem = name == "conv1"   # runs in space-to-depth form: 64 "channels" x 4 taps, see the library
         add(igemm_class("fwd", cout, 64 if stem else cin, rout, taps, "stem" if stem else (1 if rin == rout else 2)), macs)
         if has_dgrad:
-            add(igemm_class("dgrad", cin, cout, rin, taps, 1 if rin == rout else 2), macs)
+            add(dgrad_class(name, rin, cin, rout, cout, taps), macs)
         add("wgrad_tr_64x256" if stem else wgrad_class(cout, cin, taps), macs)
     return work
 
@@ -113,6 +121,10 @@ def class_bytes(F, size, epilogue_reads=True):
         add(igemm_class("fwd", cout, 64 if stem else cin, rout, taps, "stem" if stem else (1 if rin == rout else 2)), x_b + y_b)
         if has_dgrad:
             extra = x_b if name.endswith(".c1") else 0.0       # the shortcut gradient added in the epilogue
+            blk0 = int(name.split(".")[1]) == 0
+            if name.endswith(".c1") and blk0 and not name.startswith("res2"):
+                extra = x_b / 4.0                              # ... in compact form behind a strided projection
+            dx_b = x_b / 4.0 if (name.endswith(".ds") and rin != rout) else x_b   # the compact form is what is written
             # ReLU mask and BatchNorm sums of the layer below ride in the epilogue (two more tensors of the
             # result's size are read): always for c2 / c3, for c1 when the block below has an identity shortcut
             blk = int(name.split(".")[1])
@@ -121,7 +133,7 @@ def class_bytes(F, size, epilogue_reads=True):
                 extra += 2.0 * x_b
             elif name.endswith(".c1") and blk == 1:
                 extra += x_b           # the block below has a projection shortcut: only its ReLU mask rides along
-            add(igemm_class("dgrad", cin, cout, rin, taps, 1 if rin == rout else 2), x_b + y_b + (extra if epilogue_reads else 0.0))
+            add(dgrad_class(name, rin, cin, rout, cout, taps), dx_b + y_b + (extra if epilogue_reads else 0.0))
         add("wgrad_tr_64x256" if stem else wgrad_class(cout, cin, taps), x_b + y_b)
     return byt
 

@@ -65,15 +65,16 @@ int run_conv_fwd(const ConvP& p, int dtype, const void* x, const void* w, const 
 int conv_dgrad_fuse_blocks(const ConvP& p, int dtype) { return use_mfma(p, dtype) ? conv_mfma_dgrad_blocks(p) : 0; }
 
 int run_conv_dgrad(const ConvP& p, int dtype, const void* dy, const void* w, const bf16_t* wd, void* dx,
-                   const void* addend, const DgradFuse* fuse, Arena& ws, bool dry, hipStream_t s) {
+                   const void* addend, const DgradFuse* fuse, Arena& ws, bool dry, hipStream_t s, int addend_stride) {
     if (fuse && !use_mfma(p, dtype)) return fail(TSM_ERR_UNSUPPORTED, "dgrad: no fused path for this layer");
+    if (addend_stride != 1 && !use_mfma(p, dtype)) return fail(TSM_ERR_UNSUPPORTED, "dgrad: no compact addend for this layer");
     if (use_mfma(p, dtype)) {
         if (!wd) {
             bf16_t* pk = ws.take_n<bf16_t>((size_t)p.Cout * p.K());
             RUN(pack_weights_dgrad(dtype, w, pk, p.Cout, p.Cin, p.KT, p.KH, p.KW, s));
             wd = pk;
         }
-        RUN(conv_mfma_dgrad(p, (const bf16_t*)dy, wd, (bf16_t*)dx, (const bf16_t*)addend, fuse, s));
+        RUN(conv_mfma_dgrad(p, (const bf16_t*)dy, wd, (bf16_t*)dx, (const bf16_t*)addend, fuse, s, addend_stride));
     } else {
         RUN(conv_direct_dgrad(p, dtype, dy, w, dx, addend, s));
     }
@@ -482,6 +483,7 @@ static int block_bwd_body(BlockPlan& b, const void* x, const void* out, const vo
     }
     TSM_TRY(wgrad_beside(ss, &forked, b.st[0].p, b.dtype, x, g, b.st[0].dw, b.st[0].dwp, acc_flag, ws, dry, s));
     const void* addend = dzL;
+    int addend_stride = 1;
     if (b.proj) {
         StageDef& st = b.ds;
         void* dyd = ws.take(out_bytes);
@@ -490,10 +492,22 @@ static int block_bwd_body(BlockPlan& b, const void* x, const void* out, const vo
         RUN(bn_bwd_apply(b.dtype, dzL, b.yd, pl.rows_out(), pl.Cout, coefd, dyd, s));
         TSM_TRY(wgrad_beside(ss, &forked, st.p, b.dtype, x, dyd, st.dw, st.dwp, acc_flag, ws, dry, s));
         void* dsc = ws.take((size_t)st.p.rows_in() * st.p.Cin * es);
-        TSM_TRY(run_conv_dgrad(st.p, b.dtype, dyd, st.w, st.wd, dsc, nullptr, nullptr, ws, dry, s));
+        // A 1x1 projection with stride 2 sends gradient only to the input pixels with even row and column: its data
+        // gradient is the 1x1 stride-1 data gradient on the output grid, kept in that compact form and added at the
+        // even pixels by the kernel that produces dx (three quarters of the tensor are neither written nor read)
+        if (st.p.stride == 2 && st.p.taps() == 1 && st.p.pad == 0 && use_mfma(st.p, b.dtype) && use_mfma(b.st[0].p, b.dtype) &&
+            conv_mfma_dgrad_compact_addend_ok(b.st[0].p) && (dx || dry)) {
+            ConvP pc = st.p;
+            pc.H = st.p.Ho; pc.W = st.p.Wo; pc.stride = 1;
+            TSM_TRY(run_conv_dgrad(pc, b.dtype, dyd, st.w, st.wd, dsc, nullptr, nullptr, ws, dry, s));
+            addend_stride = 2;
+        } else {
+            TSM_TRY(run_conv_dgrad(st.p, b.dtype, dyd, st.w, st.wd, dsc, nullptr, nullptr, ws, dry, s));
+        }
         addend = dsc;
     }
-    if (dx || dry) TSM_TRY(run_conv_dgrad(b.st[0].p, b.dtype, g, b.st[0].w, b.st[0].wd, dx, addend, b.dx_fuse, ws, dry, s));
+    if (dx || dry)
+        TSM_TRY(run_conv_dgrad(b.st[0].p, b.dtype, g, b.st[0].w, b.st[0].wd, dx, addend, b.dx_fuse, ws, dry, s, addend_stride));
     return TSM_OK;
 }
 

@@ -47,7 +47,7 @@ int run_conv_fwd(const ConvP& p, int dtype, const void* x, const void* w, const 
 // Rows of the partial buffer a fused data gradient fills (see DgradFuse); 0 when it cannot fuse.
 int conv_dgrad_fuse_blocks(const ConvP& p, int dtype);
 int run_conv_dgrad(const ConvP& p, int dtype, const void* dy, const void* w, const bf16_t* wd, void* dx,
-                   const void* addend, const DgradFuse* fuse, Arena& ws, bool dry, hipStream_t s);
+                   const void* addend, const DgradFuse* fuse, Arena& ws, bool dry, hipStream_t s, int addend_stride = 1);
 int run_conv_wgrad(const ConvP& p, int dtype, const void* x, const void* dy, float* dw, float* dwp, int accumulate, Arena& ws,
                    bool dry, hipStream_t s);
 

@@ -39,6 +39,10 @@ struct IgemmArgs {
     const bf16_t* wp;      // packed weights [N][K]
     bf16_t* dst;           // y (fwd) or dx (dgrad)
     const bf16_t* addend;  // dgrad only: added to dx (nullable)
+    // igemm_ring_kernel only: with add_stride == 2 the addend holds only the destination pixels whose row and
+    // column are even, densely, as [F][add_ho][add_wo][Cd] (the data gradient of a 1x1 stride-2 projection:
+    // everything else is structurally zero and is neither stored nor read)
+    int add_stride, add_ho, add_wo;
     float* stats;          // per-block partial sums, [gridDim.x][2*Cd] (nullable): fwd: sum and sum of squares of
                            // y; dgrad with `act`: the two BatchNorm-backward sums of the masked gradient
     // dgrad, igemm_ring_kernel only (nullable): dst is the gradient w.r.t. act = ReLU(BatchNorm(ybn)).  The
@@ -471,8 +475,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
     return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
 }
 
-template <int BM, int BN, int WM, int WN, bool DGRAD, bool STREAM>
+// CADD: the addend of a data gradient comes in the compact form described at IgemmArgs::add_stride (a variant of its
+// own: the dense form stays free of the extra address arithmetic).
+template <int BM, int BN, int WM, int WN, bool DGRAD, bool STREAM, bool CADD = false>
 __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
+    static_assert(DGRAD || !CADD, "only data gradients add a tensor");
     constexpr int NT = WM * WN * 64;                // threads
     constexpr int NS = 2;                           // LDS stages
     constexpr int MI = BM / (WM * 32), NJ = BN / (WN * 32);   // 32x32 MFMA tiles per wavefront
@@ -494,6 +501,7 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
     bf16_t* Cst = (bf16_t*)(smem + NS * STAGE);      // [HM][LDC] staging tile of the epilogue
     float* s_part = (float*)(Cst + HM * LDC);        // [2 stats][WM*2 slots][BN] statistics slots
     RowInfo* s_row = (RowInfo*)(s_part + 2 * NSLOT * BN);   // [2][BM]: rows of the current and of the next tile
+    int* s_arow = (int*)(s_row + 2 * BM);                   // [2][BM]: row of a compact addend (-1: none), dgrad only
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -582,6 +590,17 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                 info.dst = (f * a.Hd + dh) * a.Wd + dw;
             }
             s_row[rb * BM + tid] = info;
+            if (CADD) {
+                // the destination pixel's place in the compact addend (frame offsets of the adjoint shift are added
+                // where the row is used: they do not change the pixel)
+                int arow = -1;
+                if (info.dst >= 0) {
+                    const unsigned f = (unsigned)info.dst / (unsigned)hw_d, q = (unsigned)info.dst - f * (unsigned)hw_d;
+                    const unsigned h = q / (unsigned)a.Wd, w = q - h * (unsigned)a.Wd;
+                    if (((h | w) & 1u) == 0) arow = (int)((f * (unsigned)a.add_ho + (h >> 1)) * (unsigned)a.add_wo + (w >> 1));
+                }
+                s_arow[rb * BM + tid] = arow;
+            }
         }
     };
     auto make_ctx = [&](int tile, int rb) {
@@ -839,7 +858,13 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                 // under a condition would be awaited where the branches join
                 const long e = mr[pss] * a.Cd + col;
                 const bool ok = mr[pss] >= 0;
-                ad[pss] = *(const u32x4*)((ok && a.addend) ? a.addend + e : zero_page_d);
+                if (CADD) {
+                    const int arow = s_arow[rb * BM + h * HM + pss * RPS + r0];
+                    const long ea = ((long)arow + (long)dt * (a.add_ho * a.add_wo)) * a.Cd + col;
+                    ad[pss] = *(const u32x4*)((ok && arow >= 0) ? a.addend + ea : zero_page_d);
+                } else {
+                    ad[pss] = *(const u32x4*)((ok && a.addend) ? a.addend + e : zero_page_d);
+                }
                 ac[pss] = *(const u32x4*)((ok && fuse_mask) ? a.act + e : zero_page_d);
                 yy[pss] = *(const u32x4*)((ok && fuse_bn) ? a.ybn + e : zero_page_d);
             }
@@ -932,7 +957,12 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                     if (mz[pss] < 0) continue;
                     const long e = mz[pss] * a.Cd + col;
                     u32x4 zad = u32x4{0u, 0u, 0u, 0u}, zac = zad, zyy = zad;
-                    if (a.addend) zad = *(const u32x4*)(a.addend + e);
+                    if (CADD) {
+                        const int arow = s_arow[rb * BM + h * HM + pss * RPS + r0];
+                        if (arow >= 0) zad = *(const u32x4*)(a.addend + (long)arow * a.Cd + col);
+                    } else if (a.addend) {
+                        zad = *(const u32x4*)(a.addend + e);
+                    }
                     if (fuse_mask) zac = *(const u32x4*)(a.act + e);
                     if (fuse_bn) zyy = *(const u32x4*)(a.ybn + e);
                     finish(mz[pss], u32x4{0u, 0u, 0u, 0u}, zad, zac, zyy);
@@ -1914,14 +1944,14 @@ static int launch_igemm(IgemmArgs& a, const char* name, hipStream_t s) {
     return check_launch(name);   // class names carry the tile shape so that they map one-to-one onto kernel symbols
 }
 
-template <int BM, int BN, int WM, int WN, bool DGRAD, bool STREAM>
+template <int BM, int BN, int WM, int WN, bool DGRAD, bool STREAM, bool CADD = false>
 static int launch_igemm_ring_s(IgemmArgs& a, const char* name, hipStream_t s) {
     const int mtiles = setup_classes(a, DGRAD, BM);
     a.ntiles = (a.Cd + BN - 1) / BN;
     // two operand stages, staging tile of one epilogue pass, statistics slots, two row buffers
     const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t) + (size_t)(WM * 32) * (BN + 8) * sizeof(bf16_t) +
-                        (size_t)2 * WM * WN * BN * sizeof(float) + (size_t)2 * BM * sizeof(RowInfo);
-    auto kern = igemm_ring_kernel<BM, BN, WM, WN, DGRAD, STREAM>;
+                        (size_t)2 * WM * WN * BN * sizeof(float) + (size_t)2 * BM * sizeof(RowInfo) + (size_t)2 * BM * sizeof(int);
+    auto kern = igemm_ring_kernel<BM, BN, WM, WN, DGRAD, STREAM, CADD>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -1937,7 +1967,15 @@ static int launch_igemm_ring_s(IgemmArgs& a, const char* name, hipStream_t s) {
 // and what is cached survives); smaller ones take the normal path.
 template <int BM, int BN, int WM, int WN, bool DGRAD>
 static int launch_igemm_ring(IgemmArgs& a, const char* name, hipStream_t s) {
-    if ((long)a.F * a.Hd * a.Wd * a.Cd * 2 > (64L << 20)) return launch_igemm_ring_s<BM, BN, WM, WN, DGRAD, true>(a, name, s);
+    const bool stream = (long)a.F * a.Hd * a.Wd * a.Cd * 2 > (64L << 20);
+    if (a.add_stride == 2) {
+        // (outputs of at most 64 channels never carry a projection's gradient)
+        if constexpr (DGRAD && !(BM == 256 && BN == 64))
+            return stream ? launch_igemm_ring_s<BM, BN, WM, WN, DGRAD, true, true>(a, name, s)
+                          : launch_igemm_ring_s<BM, BN, WM, WN, DGRAD, false, true>(a, name, s);
+        return fail(TSM_ERR_UNSUPPORTED, "igemm: no compact addend on this tile");
+    }
+    if (stream) return launch_igemm_ring_s<BM, BN, WM, WN, DGRAD, true>(a, name, s);
     return launch_igemm_ring_s<BM, BN, WM, WN, DGRAD, false>(a, name, s);
 }
 
@@ -1984,6 +2022,15 @@ static int ring_cols(long rows, int Cd) {
     if (!enabled || ring_rows(rows, Cd) != 128) return 128;
     const long tiles = ((rows + 127) / 128) * ((Cd + 127) / 128);
     return tiles * 4 < (long)num_cu() * 3 ? 64 : 128;
+}
+
+// Tile of the ring kernel for a layer (one block per CU whatever the tile: the 128 x 64 tile with two blocks per CU,
+// tried on the 1x1 data gradients with one to eight K steps so that one block's epilogue overlaps the other's main
+// loop, was 3 - 20 % slower on them than 256 x 128 tiles).
+static void ring_tile(const IgemmArgs& a, int* bm, int* bn) {
+    const long rows = (long)a.F * a.Hd * a.Wd;
+    *bm = ring_rows(rows, a.Cd);
+    *bn = ring_cols(rows, a.Cd);
 }
 
 // The 64 -> 64 channel 3x3 kernel takes the layers it is written for when the general kernel would run them with
@@ -2070,8 +2117,10 @@ static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     if (!DGRAD && stem_eligible(a))
         return rows * a.Cd * 2 > (64L << 20) ? launch_stem_s<true>(a, s) : launch_stem_s<false>(a, s);
     if (ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K, a.pitch != a.Cs)) {
-        if (ring_rows(rows, a.Cd) == 128) {
-            if (ring_cols(rows, a.Cd) == 64) return launch_igemm_ring<128, 64, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_r128x64" : "igemm_fwd_r128x64", s);
+        int bm, bn;
+        ring_tile(a, &bm, &bn);
+        if (bm == 128) {
+            if (bn == 64) return launch_igemm_ring<128, 64, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_r128x64" : "igemm_fwd_r128x64", s);
             return launch_igemm_ring<128, 128, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_r128x128" : "igemm_fwd_r128x128", s);
         }
         if (a.Cd <= 64) return launch_igemm_ring<256, 64, 4, 2, DGRAD>(a, DGRAD ? "igemm_dgrad_256x64" : "igemm_fwd_256x64", s);
@@ -2086,8 +2135,8 @@ int conv_mfma_fwd_blocks(const ConvP& p) {
     const int bn = p.Cout <= 64 ? 64 : 128;
     if (ring_eligible(p.Cin, p.rows_in() * (long)p.pix_pitch() + p.Cin + (long)(p.pad * p.W + p.pad) * p.pix_pitch(), (long)p.Cout * p.K(), p.pix_pitch() != p.Cin))
     {
-        const int bm = ring_rows(p.rows_out(), p.Cout);
-        return igemm_grid((int)((p.rows_out() + bm - 1) / bm), p.Cout, ring_cols(p.rows_out(), p.Cout), 1);
+        const int bm = ring_rows(p.rows_out(), p.Cout), bnn = ring_cols(p.rows_out(), p.Cout);
+        return igemm_grid((int)((p.rows_out() + bm - 1) / bm), p.Cout, bnn, 1);
     }
     return igemm_grid((int)((p.rows_out() + 127) / 128), p.Cout, bn, 2);
 }
@@ -2100,7 +2149,7 @@ bool conv_mfma_fwd_can_fuse(const ConvP& p) {
 int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, float* stats, const FwdEpilogue* ep,
                   hipStream_t s) {
     IgemmArgs a;
-    a.src = x; a.wp = wp; a.dst = y; a.addend = nullptr; a.stats = stats;
+    a.src = x; a.wp = wp; a.dst = y; a.addend = nullptr; a.add_stride = 1; a.add_ho = a.add_wo = 0; a.stats = stats;
     a.act = nullptr; a.ybn = nullptr; a.bn_mean = nullptr; a.bn_rstd = nullptr;
     a.ep_scale = nullptr; a.ep_shift = nullptr; a.ep_res = nullptr; a.ep_relu = 0;
     if (ep) {
@@ -2132,14 +2181,24 @@ int conv_mfma_dgrad_blocks(const ConvP& p) {
     dgrad_args(p, a);
     if (!ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K, a.pitch != a.Cs)) return 0;
     if ((long)a.F * a.Hd * a.Wd == 0) return 0;
-    const int mtiles = setup_classes(a, true, ring_rows((long)a.F * a.Hd * a.Wd, a.Cd));
-    return igemm_grid(mtiles, a.Cd, ring_cols((long)a.F * a.Hd * a.Wd, a.Cd), 1);
+    int bm, bn;
+    ring_tile(a, &bm, &bn);
+    const int mtiles = setup_classes(a, true, bm);
+    return igemm_grid(mtiles, a.Cd, bn, 1);
 }
 
+bool conv_mfma_dgrad_compact_addend_ok(const ConvP& p) { return conv_mfma_dgrad_blocks(p) > 0; }
+
 int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* dx, const bf16_t* addend,
-                    const DgradFuse* fuse, hipStream_t s) {
+                    const DgradFuse* fuse, hipStream_t s, int addend_stride) {
     IgemmArgs a;
     a.src = dy; a.wp = wd; a.dst = dx; a.addend = addend; a.stats = nullptr;
+    a.add_stride = 1; a.add_ho = a.add_wo = 0;
+    if (addend && addend_stride != 1) {
+        if (addend_stride != 2 || !conv_mfma_dgrad_compact_addend_ok(p))
+            return fail(TSM_ERR_UNSUPPORTED, "dgrad: this layer's kernel takes a dense addend only");
+        a.add_stride = 2; a.add_ho = (p.H + 1) / 2; a.add_wo = (p.W + 1) / 2;
+    }
     a.act = nullptr; a.ybn = nullptr; a.bn_mean = nullptr; a.bn_rstd = nullptr;
     a.ep_scale = nullptr; a.ep_shift = nullptr; a.ep_res = nullptr; a.ep_relu = 0;
     dgrad_args(p, a);

@@ -124,9 +124,13 @@ struct DgradFuse {
 // Blocks the data-gradient kernel launches for p when it can fuse (rows of DgradFuse::partial); 0 when this
 // layer's kernel cannot.
 int conv_mfma_dgrad_blocks(const ConvP& p);
-// dx = S^T(conv^T(dy)) + addend; wd = bf16 [Cin][flipped taps][Cout]; fuse nullable
+// dx = S^T(conv^T(dy)) + addend; wd = bf16 [Cin][flipped taps][Cout]; fuse nullable.
+// addend_stride 1: addend has the shape of dx.  2 (only where conv_mfma_dgrad_compact_addend_ok(p)): addend is
+// [F][ceil(H/2)][ceil(W/2)][Cin] and holds the values for the pixels of dx whose row and column are even; all other
+// pixels get nothing added (the data gradient of a 1x1 stride-2 convolution, whose other entries are zero).
+bool conv_mfma_dgrad_compact_addend_ok(const ConvP& p);
 int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* dx, const bf16_t* addend,
-                    const DgradFuse* fuse, hipStream_t s);
+                    const DgradFuse* fuse, hipStream_t s, int addend_stride = 1);
 // dw fp32, accumulated with atomics: zero it first (or keep what is there to accumulate).
 // packed: [Cout][taps][p.Cin] (contiguous atomics, the fast order when taps > 1);
 // otherwise the ABI order [Cout][cin_real][taps].  Channels >= cin_real are padding and are not written.
