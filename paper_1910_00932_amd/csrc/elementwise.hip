@@ -22,17 +22,30 @@ __device__ __forceinline__ void store_pack(T* p, const Pack<T, V>& v, bool strea
 static inline bool stream_result(long rows, int C, int dtype) { return rows * C * (long)dtype_size(dtype) > (64L << 20); }
 
 // ---------------------------------------------------------------------------------
-__global__ void fill_zero_kernel(uint32_t* p, size_t n) {
+// 16-byte stores over the aligned body, 4-byte stores over the (at most three) words in front of it and behind it.
+__global__ void __launch_bounds__(256) fill_zero_kernel(uint32_t* p, int nhead, uint4* body, size_t n16, uint32_t* tail, int ntail) {
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * 256;
-    for (; i < n; i += stride) p[i] = 0u;
+    for (; i < n16; i += stride) body[i] = make_uint4(0u, 0u, 0u, 0u);
+    if (blockIdx.x == 0) {
+        if ((int)threadIdx.x < nhead) p[threadIdx.x] = 0u;
+        if ((int)threadIdx.x < ntail) tail[threadIdx.x] = 0u;
+    }
 }
 
+// p: 4-byte aligned, bytes: a multiple of 4 (rounded up otherwise: every caller's buffer ends on a word)
 int fill_zero(void* p, size_t bytes, hipStream_t s) {
     if (bytes == 0) return TSM_OK;
-    size_t n = (bytes + 3) / 4;  // buffers come from 256-byte aligned arena slots
-    unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
-    fill_zero_kernel<<<dim3(blocks), dim3(256), 0, s>>>((uint32_t*)p, n);
+    size_t words = (bytes + 3) / 4;
+    uint32_t* w = (uint32_t*)p;
+    size_t nhead = ((16 - ((uintptr_t)p & 15)) & 15) / 4;
+    if (nhead > words) nhead = words;
+    words -= nhead;
+    const size_t n16 = words / 4;
+    const int ntail = (int)(words - n16 * 4);
+    const size_t want = (n16 + 255) / 256;
+    const unsigned blocks = (unsigned)(want < 1 ? 1 : (want < 16384 ? want : 16384));
+    fill_zero_kernel<<<dim3(blocks), dim3(256), 0, s>>>(w, (int)nhead, (uint4*)(w + nhead), n16, w + nhead + n16 * 4, ntail);
     return check_launch("fill_zero");
 }
 
