@@ -129,10 +129,14 @@ def class_bytes(F, size, epilogue_reads=True):
             # result's size are read): always for c2 / c3, for c1 when the block below has an identity shortcut
             blk = int(name.split(".")[1])
             chained = name.endswith(".c1") and (blk >= 2 or (blk == 0 and not name.startswith("res2")))
-            if name.endswith((".c2", ".c3")) or chained:
+            # (a block's output mask is read as decision bits, a sixteenth of the tensor; inside a block the
+            # activation itself is the mask)
+            if name.endswith((".c2", ".c3")):
                 extra += 2.0 * x_b
+            elif chained:
+                extra += x_b + x_b / 16.0
             elif name.endswith(".c1") and blk == 1:
-                extra += x_b           # the block below has a projection shortcut: only its ReLU mask rides along
+                extra += x_b / 16.0    # the block below has a projection shortcut: only its ReLU mask rides along
             add(dgrad_class(name, rin, cin, rout, cout, taps), dx_b + y_b + (extra if epilogue_reads else 0.0))
         add("wgrad_tr_64x256" if stem else wgrad_class(cout, cin, taps), x_b + y_b)
     return byt

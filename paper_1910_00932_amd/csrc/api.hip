@@ -226,7 +226,7 @@ int block_fwd_impl(BlockPlan& b, const void* x, void* out, Arena& ws, bool dry, 
     const int L = b.nst - 1;
     const ConvP& pl = b.st[L].p;
     RUN(block_tail_fwd(b.dtype, b.y[L], pl.rows_out(), pl.Cout, b.bn[L].scale, b.bn[L].shift, b.proj ? b.yd : x,
-                       b.proj ? b.bnd.scale : nullptr, b.proj ? b.bnd.shift : nullptr, out, s));
+                       b.proj ? b.bnd.scale : nullptr, b.proj ? b.bnd.shift : nullptr, out, s, b.out_bits));
     return TSM_OK;
 }
 

@@ -39,6 +39,7 @@ struct BlockPlan {
     void* yd;             // projection output
     BnVec bn[3], bnd;
     void *x_copy, *out_copy;  // channels-innermost copies when the caller's order is NTCHW
+    uint8_t* out_bits = nullptr;  // optional: receives the ReLU decisions of the block's output (see block_tail_fwd)
 };
 
 int conv_stats_blocks(const ConvP& p, int dtype);

@@ -51,6 +51,7 @@ struct IgemmArgs {
     const bf16_t* ybn;
     const float* bn_mean;
     const float* bn_rstd;
+    const uint8_t* act_bits;   // igemm_ring_kernel, MBITS variants: the decisions act > 0 as bits, [rows][Cd/8]
     // fwd, igemm_ring_kernel only (nullable): the stored result is act(ep_scale[c]*y + ep_shift[c] + ep_res), y
     // rounded to bf16 first; ep_res (nullable) has the shape of dst; act = ReLU when ep_relu, identity otherwise.
     // This is BatchNorm with known statistics (inference) folded into the epilogue.
@@ -477,9 +478,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 
 // CADD: the addend of a data gradient comes in the compact form described at IgemmArgs::add_stride (a variant of its
 // own: the dense form stays free of the extra address arithmetic).
-template <int BM, int BN, int WM, int WN, bool DGRAD, bool STREAM, bool CADD = false>
+// MBITS: the ReLU decisions of a fused data-gradient epilogue come as one byte per eight channels (IgemmArgs::act_bits)
+// instead of the activation itself: a sixteenth of the bytes.
+template <int BM, int BN, int WM, int WN, bool DGRAD, bool STREAM, bool CADD = false, bool MBITS = false>
 __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
-    static_assert(DGRAD || !CADD, "only data gradients add a tensor");
+    static_assert(DGRAD || !(CADD || MBITS), "only data gradients add a tensor or apply a mask");
     constexpr int NT = WM * WN * 64;                // threads
     constexpr int NS = 2;                           // LDS stages
     constexpr int MI = BM / (WM * 32), NJ = BN / (WN * 32);   // 32x32 MFMA tiles per wavefront
@@ -509,7 +512,7 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
     const int lrow = tid / KV;                                   // row within a load pass
     const int kvec = (tid % KV) ^ ((lrow >> 1) & 7);             // K vector this thread fetches (see layout above)
     const bool do_stats = (!DGRAD) && a.stats != nullptr;
-    const bool fuse_mask = DGRAD && a.act != nullptr;        // ReLU mask in the epilogue ...
+    const bool fuse_mask = DGRAD && (MBITS ? a.act_bits != nullptr : a.act != nullptr);   // ReLU mask in the epilogue ...
     const bool fuse_bn = fuse_mask && a.ybn != nullptr;      // ... and the BatchNorm-backward sums of the masked values
 
     const int hw_d = a.Hd * a.Wd;
@@ -865,7 +868,12 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                 } else {
                     ad[pss] = *(const u32x4*)((ok && a.addend) ? a.addend + e : zero_page_d);
                 }
-                ac[pss] = *(const u32x4*)((ok && fuse_mask) ? a.act + e : zero_page_d);
+                if (MBITS) {
+                    // (bit j of the byte: channel col + j; rows that are not stored read a zero byte)
+                    ac[pss][0] = *((ok && fuse_mask) ? a.act_bits + (mr[pss] * a.Cd + col) / 8 : (const uint8_t*)zero_page_d);
+                } else {
+                    ac[pss] = *(const u32x4*)((ok && fuse_mask) ? a.act + e : zero_page_d);
+                }
                 yy[pss] = *(const u32x4*)((ok && fuse_bn) ? a.ybn + e : zero_page_d);
             }
         };
@@ -935,10 +943,11 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                     if (fuse_mask) {   // on the values as stored (bf16); without ybn the sums are not used
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
-                            const float alo = __uint_as_float(ac[q] << 16), ahi = __uint_as_float(ac[q] & 0xffff0000u);
-                            const float dlo = alo > 0.f ? __uint_as_float(o[q] << 16) : 0.f;
-                            const float dhi = ahi > 0.f ? __uint_as_float(o[q] & 0xffff0000u) : 0.f;
-                            o[q] = (alo > 0.f ? o[q] & 0xffffu : 0u) | (ahi > 0.f ? o[q] & 0xffff0000u : 0u);
+                            const bool plo = MBITS ? ((ac[0] >> (2 * q)) & 1u) != 0 : __uint_as_float(ac[q] << 16) > 0.f;
+                            const bool phi = MBITS ? ((ac[0] >> (2 * q + 1)) & 1u) != 0 : __uint_as_float(ac[q] & 0xffff0000u) > 0.f;
+                            const float dlo = plo ? __uint_as_float(o[q] << 16) : 0.f;
+                            const float dhi = phi ? __uint_as_float(o[q] & 0xffff0000u) : 0.f;
+                            o[q] = (plo ? o[q] & 0xffffu : 0u) | (phi ? o[q] & 0xffff0000u : 0u);
                             f1[2 * q] += dlo;
                             f1[2 * q + 1] += dhi;
                             f2[2 * q] = fmaf(dlo, (__uint_as_float(yy[q] << 16) - mu[2 * q]) * rs[2 * q], f2[2 * q]);
@@ -963,7 +972,10 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
                     } else if (a.addend) {
                         zad = *(const u32x4*)(a.addend + e);
                     }
-                    if (fuse_mask) zac = *(const u32x4*)(a.act + e);
+                    if (fuse_mask) {
+                        if (MBITS) zac[0] = a.act_bits[e / 8];
+                        else zac = *(const u32x4*)(a.act + e);
+                    }
                     if (fuse_bn) zyy = *(const u32x4*)(a.ybn + e);
                     finish(mz[pss], u32x4{0u, 0u, 0u, 0u}, zad, zac, zyy);
                 }
@@ -1944,14 +1956,14 @@ static int launch_igemm(IgemmArgs& a, const char* name, hipStream_t s) {
     return check_launch(name);   // class names carry the tile shape so that they map one-to-one onto kernel symbols
 }
 
-template <int BM, int BN, int WM, int WN, bool DGRAD, bool STREAM, bool CADD = false>
+template <int BM, int BN, int WM, int WN, bool DGRAD, bool STREAM, bool CADD = false, bool MBITS = false>
 static int launch_igemm_ring_s(IgemmArgs& a, const char* name, hipStream_t s) {
     const int mtiles = setup_classes(a, DGRAD, BM);
     a.ntiles = (a.Cd + BN - 1) / BN;
     // two operand stages, staging tile of one epilogue pass, statistics slots, two row buffers
     const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t) + (size_t)(WM * 32) * (BN + 8) * sizeof(bf16_t) +
                         (size_t)2 * WM * WN * BN * sizeof(float) + (size_t)2 * BM * sizeof(RowInfo) + (size_t)2 * BM * sizeof(int);
-    auto kern = igemm_ring_kernel<BM, BN, WM, WN, DGRAD, STREAM, CADD>;
+    auto kern = igemm_ring_kernel<BM, BN, WM, WN, DGRAD, STREAM, CADD, MBITS>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -1968,12 +1980,23 @@ static int launch_igemm_ring_s(IgemmArgs& a, const char* name, hipStream_t s) {
 template <int BM, int BN, int WM, int WN, bool DGRAD>
 static int launch_igemm_ring(IgemmArgs& a, const char* name, hipStream_t s) {
     const bool stream = (long)a.F * a.Hd * a.Wd * a.Cd * 2 > (64L << 20);
-    if (a.add_stride == 2) {
-        // (outputs of at most 64 channels never carry a projection's gradient)
-        if constexpr (DGRAD && !(BM == 256 && BN == 64))
-            return stream ? launch_igemm_ring_s<BM, BN, WM, WN, DGRAD, true, true>(a, name, s)
-                          : launch_igemm_ring_s<BM, BN, WM, WN, DGRAD, false, true>(a, name, s);
-        return fail(TSM_ERR_UNSUPPORTED, "igemm: no compact addend on this tile");
+    if constexpr (DGRAD && !(BM == 256 && BN == 64)) {
+        // variants of the data gradient: compact addend, mask from decision bits (outputs of at most 64 channels carry
+        // neither a projection's gradient nor a block output's mask)
+        const bool cadd = a.add_stride == 2, mbits = a.act_bits != nullptr;
+        if (!mbits) a.act_bits = nullptr;
+        if (cadd && mbits)
+            return stream ? launch_igemm_ring_s<BM, BN, WM, WN, true, true, true, true>(a, name, s)
+                          : launch_igemm_ring_s<BM, BN, WM, WN, true, false, true, true>(a, name, s);
+        if (cadd)
+            return stream ? launch_igemm_ring_s<BM, BN, WM, WN, true, true, true, false>(a, name, s)
+                          : launch_igemm_ring_s<BM, BN, WM, WN, true, false, true, false>(a, name, s);
+        if (mbits)
+            return stream ? launch_igemm_ring_s<BM, BN, WM, WN, true, true, false, true>(a, name, s)
+                          : launch_igemm_ring_s<BM, BN, WM, WN, true, false, false, true>(a, name, s);
+    } else {
+        if (a.add_stride == 2) return fail(TSM_ERR_UNSUPPORTED, "igemm: no compact addend on this tile");
+        a.act_bits = nullptr;   // this tile takes the mask from the activation
     }
     if (stream) return launch_igemm_ring_s<BM, BN, WM, WN, DGRAD, true>(a, name, s);
     return launch_igemm_ring_s<BM, BN, WM, WN, DGRAD, false>(a, name, s);
@@ -2150,7 +2173,7 @@ int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, 
                   hipStream_t s) {
     IgemmArgs a;
     a.src = x; a.wp = wp; a.dst = y; a.addend = nullptr; a.add_stride = 1; a.add_ho = a.add_wo = 0; a.stats = stats;
-    a.act = nullptr; a.ybn = nullptr; a.bn_mean = nullptr; a.bn_rstd = nullptr;
+    a.act = nullptr; a.ybn = nullptr; a.bn_mean = nullptr; a.bn_rstd = nullptr; a.act_bits = nullptr;
     a.ep_scale = nullptr; a.ep_shift = nullptr; a.ep_res = nullptr; a.ep_relu = 0;
     if (ep) {
         if (!conv_mfma_fwd_can_fuse(p)) return fail(TSM_ERR_UNSUPPORTED, "conv forward: this layer's kernel has no affine epilogue");
@@ -2199,10 +2222,18 @@ int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* 
             return fail(TSM_ERR_UNSUPPORTED, "dgrad: this layer's kernel takes a dense addend only");
         a.add_stride = 2; a.add_ho = (p.H + 1) / 2; a.add_wo = (p.W + 1) / 2;
     }
-    a.act = nullptr; a.ybn = nullptr; a.bn_mean = nullptr; a.bn_rstd = nullptr;
+    a.act = nullptr; a.ybn = nullptr; a.bn_mean = nullptr; a.bn_rstd = nullptr; a.act_bits = nullptr;
     a.ep_scale = nullptr; a.ep_shift = nullptr; a.ep_res = nullptr; a.ep_relu = 0;
     dgrad_args(p, a);
     if (fuse) {
+        // (the general kernel reads the decision bits where it has them; the 64-channel kernel and tiles without the
+        // variant read `act`)
+        static int bits_on = -1;   // TSM_MASK_BITS=0 keeps the activation as the mask source (for comparisons)
+        if (bits_on < 0) {
+            const char* e = getenv("TSM_MASK_BITS");
+            bits_on = (e && e[0] == '0') ? 0 : 1;
+        }
+        if (bits_on && p.Cin % 8 == 0) a.act_bits = fuse->act_bits;
         if (conv_mfma_dgrad_blocks(p) == 0) return fail(TSM_ERR_UNSUPPORTED, "dgrad: this layer's kernel cannot fuse the BatchNorm reductions");
         // (y == nullptr: only the ReLU mask of `act` is applied, no sums)
         a.act = fuse->act; a.ybn = fuse->y; a.bn_mean = fuse->mean; a.bn_rstd = fuse->rstd; a.stats = fuse->y ? fuse->partial : nullptr;

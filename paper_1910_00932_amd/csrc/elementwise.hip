@@ -302,7 +302,8 @@ template <typename T, int V, bool PROJ>
 __global__ void __launch_bounds__(256) tail_kernel(const T* __restrict__ y, long rows, int C, int cv,
                                                    const float* __restrict__ scale, const float* __restrict__ shift,
                                                    const T* __restrict__ sc, const float* __restrict__ scale_d,
-                                                   const float* __restrict__ shift_d, T* __restrict__ out, bool stream) {
+                                                   const float* __restrict__ shift_d, T* __restrict__ out, bool stream,
+                                                   uint8_t* __restrict__ bits) {
     const int cvi = blockIdx.y * blockDim.x + threadIdx.x;
     if (cvi >= cv) return;
     float s0[V], h0[V], s1[V], h1[V];
@@ -324,30 +325,40 @@ __global__ void __launch_bounds__(256) tail_kernel(const T* __restrict__ y, long
             o.v[j] = Elem<T>::st(v > 0.f ? v : 0.f);
         }
         store_pack<T, V>(out + off, o, stream);
+        if (V == 8 && bits) {   // which of the eight stored values are positive: the ReLU decisions, one byte per vector
+            unsigned m = 0;
+#pragma unroll
+            for (int j = 0; j < V; ++j) m |= (Elem<T>::ld(o.v[j]) > 0.f ? 1u : 0u) << j;
+            bits[r * cv + cvi] = (uint8_t)m;
+        }
     }
 }
 
 template <typename T, int V>
 static int tail_tv(const T* y, long rows, int C, const float* scale, const float* shift, const T* sc,
-                   const float* scale_d, const float* shift_d, T* out, hipStream_t s) {
+                   const float* scale_d, const float* shift_d, T* out, uint8_t* bits, hipStream_t s) {
     RowShape r = row_shape(rows, C, V, EW_ROWS_PER_THREAD, EW_MAX_GX, EW_THREADS);
     const bool st = stream_result(rows, C, sizeof(T) == 2 ? TSM_BF16 : TSM_F32);
     if (scale_d)
-        tail_kernel<T, V, true><<<r.grid, r.block, 0, s>>>(y, rows, C, r.cv, scale, shift, sc, scale_d, shift_d, out, st);
+        tail_kernel<T, V, true><<<r.grid, r.block, 0, s>>>(y, rows, C, r.cv, scale, shift, sc, scale_d, shift_d, out, st, bits);
     else
-        tail_kernel<T, V, false><<<r.grid, r.block, 0, s>>>(y, rows, C, r.cv, scale, shift, sc, scale_d, shift_d, out, st);
+        tail_kernel<T, V, false><<<r.grid, r.block, 0, s>>>(y, rows, C, r.cv, scale, shift, sc, scale_d, shift_d, out, st, bits);
     return check_launch("block_tail_fwd");
 }
 
+bool block_tail_writes_bits(int dtype, int C) { return dtype == TSM_BF16 && C % 8 == 0; }
+
 int block_tail_fwd(int dtype, const void* y, long rows, int C, const float* scale, const float* shift,
-                   const void* shortcut, const float* scale_d, const float* shift_d, void* out, hipStream_t s) {
+                   const void* shortcut, const float* scale_d, const float* shift_d, void* out, hipStream_t s,
+                   uint8_t* out_bits) {
     if (rows == 0) return TSM_OK;
     const int v = vec_of(dtype, C);
+    if (out_bits && !block_tail_writes_bits(dtype, C)) return fail(TSM_ERR_UNSUPPORTED, "block tail: decision bits need bf16 and channels % 8 == 0");
     if (dtype == TSM_F32)
-        return v == 4 ? tail_tv<float, 4>((const float*)y, rows, C, scale, shift, (const float*)shortcut, scale_d, shift_d, (float*)out, s)
-                      : tail_tv<float, 1>((const float*)y, rows, C, scale, shift, (const float*)shortcut, scale_d, shift_d, (float*)out, s);
-    return v == 8 ? tail_tv<bf16_t, 8>((const bf16_t*)y, rows, C, scale, shift, (const bf16_t*)shortcut, scale_d, shift_d, (bf16_t*)out, s)
-                  : tail_tv<bf16_t, 1>((const bf16_t*)y, rows, C, scale, shift, (const bf16_t*)shortcut, scale_d, shift_d, (bf16_t*)out, s);
+        return v == 4 ? tail_tv<float, 4>((const float*)y, rows, C, scale, shift, (const float*)shortcut, scale_d, shift_d, (float*)out, nullptr, s)
+                      : tail_tv<float, 1>((const float*)y, rows, C, scale, shift, (const float*)shortcut, scale_d, shift_d, (float*)out, nullptr, s);
+    return v == 8 ? tail_tv<bf16_t, 8>((const bf16_t*)y, rows, C, scale, shift, (const bf16_t*)shortcut, scale_d, shift_d, (bf16_t*)out, out_bits, s)
+                  : tail_tv<bf16_t, 1>((const bf16_t*)y, rows, C, scale, shift, (const bf16_t*)shortcut, scale_d, shift_d, (bf16_t*)out, nullptr, s);
 }
 
 // ---- backward, pass A: ReLU mask + the two BatchNorm reductions -------------------------------------

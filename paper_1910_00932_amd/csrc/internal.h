@@ -61,8 +61,12 @@ int bn_eval_vec(const float* gamma, const float* beta, const float* mean, const 
 int bn_relu_apply(int dtype, const void* y, long rows, int C, const float* scale, const float* shift, void* z,
                   hipStream_t s);
 // out = relu(scale*y + shift + sc), sc = shortcut (scale_d == null) or scale_d*shortcut + shift_d
+// out_bits (nullable; only where block_tail_writes_bits): one byte per eight channels, [rows][C/8], bit j set where
+// channel 8*v + j of the stored output is positive -- the ReLU decisions, a sixteenth of the tensor, for the backward pass.
+bool block_tail_writes_bits(int dtype, int C);
 int block_tail_fwd(int dtype, const void* y, long rows, int C, const float* scale, const float* shift,
-                   const void* shortcut, const float* scale_d, const float* shift_d, void* out, hipStream_t s);
+                   const void* shortcut, const float* scale_d, const float* shift_d, void* out, hipStream_t s,
+                   uint8_t* out_bits = nullptr);
 // dz = dout * [act > 0] (act == null: no mask) written to dz_out (may alias dout; null: not written); partial rows receive
 // sum dz and sum dz*yhat with yhat = (y - mean)*rstd.  If y2 != null a second BatchNorm (projection
 // shortcut) is reduced into partial2.
@@ -120,6 +124,9 @@ struct DgradFuse {
     const float* mean;
     const float* rstd;
     float* partial;
+    // optional: the decisions act > 0 as bits ([rows][Cin/8], see block_tail_fwd); kernels that can read them
+    // instead of `act`, which must still be given
+    const uint8_t* act_bits = nullptr;
 };
 // Blocks the data-gradient kernel launches for p when it can fuse (rows of DgradFuse::partial); 0 when this
 // layer's kernel cannot.

@@ -821,6 +821,9 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
                 block_saved_layout(pl, A, false);
                 const ConvP& last = pl.st[2].p;
                 blk.out = A.take((size_t)last.rows_out() * last.Cout * es);
+                // the output's ReLU decisions as bits: what the next block's first data gradient reads as its mask
+                pl.out_bits = block_tail_writes_bits(dtype, last.Cout)
+                                  ? A.take_n<uint8_t>((size_t)last.rows_out() * last.Cout / 8) : nullptr;
                 blk.in = cur;
                 cur = blk.out;
                 blks.push_back(blk);
@@ -1002,14 +1005,14 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
         b.plan.dx_fuse = nullptr;
         if (i > 0 && chain_nb[i - 1]) {
             BlockPlan& pp = blks[i - 1].plan;
-            fz = DgradFuse{(const bf16_t*)blks[i - 1].out, (const bf16_t*)pp.y[2], pp.bn[2].mean, pp.bn[2].rstd, chain_part[i - 1]};
+            fz = DgradFuse{(const bf16_t*)blks[i - 1].out, (const bf16_t*)pp.y[2], pp.bn[2].mean, pp.bn[2].rstd, chain_part[i - 1], pp.out_bits};
             b.plan.dx_fuse = &fz;
             pp.dout_part = dry ? (const float*)1 : chain_part[i - 1];   // (dry run: only the flag matters)
             pp.dout_nb = chain_nb[i - 1];
         } else if (i > 0 && blks[i - 1].plan.proj && conv_dgrad_fuse_blocks(b.plan.st[0].p, dtype)) {
             // block i-1 has a projection shortcut (two BatchNorms share its output gradient): the data gradient
             // applies its output ReLU mask only, the two pairs of sums are reduced from the masked gradient
-            fz = DgradFuse{(const bf16_t*)blks[i - 1].out, nullptr, nullptr, nullptr, nullptr};
+            fz = DgradFuse{(const bf16_t*)blks[i - 1].out, nullptr, nullptr, nullptr, nullptr, blks[i - 1].plan.out_bits};
             b.plan.dx_fuse = &fz;
             blks[i - 1].plan.dout_masked = true;
         }
