@@ -38,7 +38,9 @@
  *    at every call) keeps the inference paths on one kernel per convolution and
  *    TSM_FUSED_TAIL_MIN_TILES=<n> replaces the number of 256-pixel tiles from
  *    which the two-convolution kernel is chosen (default: three per four
- *    compute units).
+ *    compute units); TSM_MASK_BITS=0 (read once per process) makes the train
+ *    step's data gradients take the ReLU mask of a block output from the
+ *    activation itself instead of from the decision bits its forward pass keeps.
  *  - Return value: TSM_OK or a negative tsm_status.  On error nothing has been
  *    launched (argument errors) or the stream's state is undefined
  *    (TSM_ERR_LAUNCH).  tsm_last_error() returns a host string describing the
