@@ -451,7 +451,7 @@ struct PackTable {
     int n;
     unsigned start[56];       // first output element of entry l in the launch's flat index space (start[n] = total)
     unsigned in_off[55];      // element offset into the fp32 parameter vector
-    unsigned out_off[55];     // bf16 element offset from the output base
+    unsigned long long out_off[55];   // bf16 element offset from the output base (the workspace: 64 bits, it exceeds 8 GiB at a few dozen clips)
     unsigned short cout[55], cin[55], cinp[55], k[55];
     unsigned tstart[56];      // first 64 x 64 (Cout x Cin) tile of entry l, for pack_tiles_kernel; tiled == 0 if any
     int tiled;                // entry has a channel count that is not a multiple of 64 or padded input channels
@@ -723,7 +723,7 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
                           const bf16_t* dst) {
         const int l = t.n++;
         t.in_off[l] = (unsigned)table[find_tensor(table, name)].offset;
-        t.out_off[l] = (unsigned)(dst - pack_base);
+        t.out_off[l] = (unsigned long long)(dst - pack_base);
         t.cout[l] = (unsigned short)Cout; t.cin[l] = (unsigned short)Cin; t.cinp[l] = (unsigned short)CinP;
         t.k[l] = (unsigned short)k;
         t.start[l + 1] = t.start[l] + (unsigned)count;
@@ -1155,7 +1155,7 @@ static int r50_infer(const tsm_r50_desc* d, const void* clips, const float* para
         bf16_t* a = A.take_n<bf16_t>(nf);
         const int l = pk.n++;
         pk.in_off[l] = (unsigned)table[find_tensor(table, name)].offset;
-        pk.out_off[l] = (unsigned)(a - pack_base);
+        pk.out_off[l] = (unsigned long long)(a - pack_base);
         pk.cout[l] = (unsigned short)Cout; pk.cin[l] = (unsigned short)Cin; pk.cinp[l] = (unsigned short)Cin;
         pk.k[l] = (unsigned short)k;
         pk.start[l + 1] = pk.start[l] + (unsigned)nf;

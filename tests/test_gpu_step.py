@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 G3 = 0.25          # scale of the last BatchNorm of every block in the full-frame and gated tests (see their docstrings)
 
 
-def run_step(N, T, S, dtype="bf16", lr=0.00125, update=1, seed=1, g3=1.0):
+def run_step(N, T, S, dtype="bf16", lr=0.00125, update=1, seed=1, g3=1.0, clips=None, labels=None):
     table = B.tsm_resnet50_param_table(400)
     flat = I.init_params([(n, s) for n, _, s, _ in table], seed)
     rng = np.random.default_rng(5)
@@ -25,8 +25,8 @@ def run_step(N, T, S, dtype="bf16", lr=0.00125, update=1, seed=1, g3=1.0):
             flat[off:off + n] += (0.1 * rng.standard_normal(n)).astype(np.float32)
             if name.endswith("bn3.g"):     # scale of the residual branches (see the full-frame test)
                 flat[off:off + n] *= g3
-    clips = I.clips(N, T, S, 0, dtype)
-    labels = I.labels(N)
+    if clips is None:
+        clips, labels = I.clips(N, T, S, 0, dtype), I.labels(N)
     d = B.R50Desc(N=N, T=T, size=S, num_classes=400, fold_div=8, lr=lr, momentum=0.9, weight_decay=1e-4, bn_eps=1e-5,
                   bn_momentum=0.1, dtype=B.TSM_BF16 if dtype == "bf16" else B.TSM_F32)
     ws = workspace(B.tsm_resnet50_workspace_bytes(d))
@@ -44,29 +44,33 @@ def run_step(N, T, S, dtype="bf16", lr=0.00125, update=1, seed=1, g3=1.0):
                 bn_state=bn_state.cpu().numpy())
 
 
-def _ws_tensor(r, name):
-    """A forward activation the step left in its workspace, as float64 numpy [frames, rows, columns, channels]."""
+def _ws_tensor(r, name, frames=None):
+    """A forward activation the step left in its workspace, as float64 numpy [frames, rows, columns, channels]
+    (`frames`: only that many leading frames)."""
     off, shape, eb = B.tsm_resnet50_workspace_tensor(r["desc"], name)
+    if frames is not None and shape[1] * shape[2] * shape[3] > 1:
+        shape = (frames,) + tuple(shape[1:])
     raw = r["ws"][off:off + int(np.prod(shape)) * eb]
     t = raw if eb == 1 else raw.view(torch.bfloat16 if eb == 2 else torch.float32)
     return t.reshape(shape).to(torch.float64 if eb > 1 else torch.int64).cpu().numpy()
 
 
 def gpu_gates(r, N, T):
-    """The ReLU and max-pool decisions the HIP step took, read from the activations it left in its workspace, as an
-    oracle Gates object in replay mode: a ReLU let a unit through where the stored activation is positive; the
-    max-pool's window position comes as kh*3+kw and becomes the oracle's flat index into the input map."""
+    """The ReLU and max-pool decisions the HIP step took on its first N clips, read from the activations it left in
+    its workspace, as an oracle Gates object in replay mode: a ReLU let a unit through where the stored activation is
+    positive; the max-pool's window position comes as kh*3+kw and becomes the oracle's flat index into the input map."""
     g = O.Gates()
     g.record = False
     to5 = lambda a: np.ascontiguousarray(a.reshape((N, T) + a.shape[1:]).transpose(0, 1, 4, 2, 3))
+    F = N * T
     for stage, blocks, _, _ in O.STAGES:
         for b in range(blocks):
             pre = "%s.%d." % (stage, b)
             for t in ("z1", "z2", "out"):
-                g.store[pre + t] = to5(_ws_tensor(r, pre + t)) > 0
-    y0, sc, sh = _ws_tensor(r, "stem.y"), _ws_tensor(r, "stem.bn_scale").ravel(), _ws_tensor(r, "stem.bn_shift").ravel()
+                g.store[pre + t] = to5(_ws_tensor(r, pre + t, F)) > 0
+    y0, sc, sh = _ws_tensor(r, "stem.y", F), _ws_tensor(r, "stem.bn_scale").ravel(), _ws_tensor(r, "stem.bn_shift").ravel()
     g.store["stem.z"] = to5(y0 * sc + sh) > 0
-    code = _ws_tensor(r, "stem.pool_arg")                      # [F, Hp, Wp, 64]
+    code = _ws_tensor(r, "stem.pool_arg", F)                   # [F, Hp, Wp, 64]
     Hp, Wp, W1 = code.shape[1], code.shape[2], y0.shape[2]
     ih = 2 * np.arange(Hp).reshape(1, Hp, 1, 1) + code // 3 - 1
     iw = 2 * np.arange(Wp).reshape(1, 1, Wp, 1) + code % 3 - 1
@@ -197,6 +201,26 @@ def _own_passes(N, P, V, x, labels, lr):
     return _FULL[N]
 
 
+def _hold_to_passes(r, passes):
+    """Loss and logits of the HIP step within 2e-2 of every oracle pass; every gradient tensor within 2e-2 or 1.5 x
+    the distance between the passes of its pair, whichever is larger (see the full-frame test)."""
+    bad = {}
+    for tag, ref, dist in passes:
+        errs = _errors(r, ref[0], ref[1], ref[2])
+        errs["all gradients"] = rel_l2(r["grads"], O.flatten_params(ref[2]))
+        print("  %-36s loss %.1e logits %.1e (passes apart %.1e); gradients: all %.1e (%.1e) " % (tag, errs["loss"], errs["logits"], dist["logits"], errs["all gradients"], dist["all gradients"]) +
+              " ".join("%s %.1e (%.1e)" % (k, errs["g:" + k], dist["g:" + k]) for k in PICKS))
+        gk = [k for k in errs if k.startswith("g:")]
+        worst = max(gk, key=lambda k: errs[k] / max(2e-2, 1.5 * dist[k]))
+        print("  %-36s closest to its bound: %s %.1e (%.1e); gradient tensors above 2e-2: %d of %d" %
+              ("", worst, errs[worst], dist[worst], sum(1 for k in gk if errs[k] >= 2e-2), len(gk)))
+        assert errs["loss"] < 2e-2 and errs["logits"] < 2e-2, (tag, errs["loss"], errs["logits"])
+        for k in gk + ["all gradients"]:
+            if not errs[k] < max(2e-2, 1.5 * dist[k]):
+                bad[(tag, k)] = (errs[k], dist[k])
+    assert not bad, bad
+
+
 @pytest.mark.parametrize("N,dispatch", [(2, "default"), (2, "special"), (8, "special")])
 def test_step_bf16_full_frame_against_oracle(N, dispatch, monkeypatch):
     """The configuration the benchmark times -- bf16 storage, 8 frames of 3x224x224 per clip -- at 2 clips and at
@@ -249,26 +273,70 @@ def test_step_bf16_full_frame_against_oracle(N, dispatch, monkeypatch):
         passes += [("(a) bf16 storage, own decisions", emul, free), ("(c) fp64, own decisions", plain, free)]
     else:
         print("\nN=%d dispatch=%s" % (N, dispatch))
-    bad = {}
-    for tag, ref, dist in passes:
-        errs = _errors(r, ref[0], ref[1], ref[2])
-        errs["all gradients"] = rel_l2(r["grads"], O.flatten_params(ref[2]))
-        print("  %-36s loss %.1e logits %.1e (passes apart %.1e); gradients: all %.1e (%.1e) " % (tag, errs["loss"], errs["logits"], dist["logits"], errs["all gradients"], dist["all gradients"]) +
-              " ".join("%s %.1e (%.1e)" % (k, errs["g:" + k], dist["g:" + k]) for k in PICKS))
-        gk = [k for k in errs if k.startswith("g:")]
-        worst = max(gk, key=lambda k: errs[k] / max(2e-2, 1.5 * dist[k]))
-        print("  %-36s closest to its bound: %s %.1e (%.1e); gradient tensors above 2e-2: %d of %d" %
-              ("", worst, errs[worst], dist[worst], sum(1 for k in gk if errs[k] >= 2e-2), len(gk)))
-        assert errs["loss"] < 2e-2 and errs["logits"] < 2e-2, (tag, errs["loss"], errs["logits"])
-        for k in gk + ["all gradients"]:
-            if not errs[k] < max(2e-2, 1.5 * dist[k]):
-                bad[(tag, k)] = (errs[k], dist[k])
-    assert not bad, bad
+    _hold_to_passes(r, passes)
     # updated weights: the SGD arithmetic is exact given the gradients, and the update itself matches the oracle's
     _check_sgd(r, lr)
     upd = r["params"].astype(np.float64) - r["flat"].astype(np.float64)
     upd_o = O.flatten_params(emul_k[3]) - r["flat"].astype(np.float64)
     assert rel_l2(upd, upd_o) < max(2e-2, 1.5 * imposed["all gradients"]), rel_l2(upd, upd_o)
+    assert rel_l2(r["params"], O.flatten_params(emul_k[3])) < 1e-5
+
+
+def test_step_bf16_64_clips_as_the_benchmark_times_it():
+    """configs[3], the workload the benchmark times (64 clips x 8 frames x 3x224x224, bf16, default dispatch, weight
+    gradients on the second stream), held to the oracle.  The batch is the benchmark's: 8 distinct clips repeated
+    8 times.  Then
+
+      * every per-frame result is a function of the frame and of the BatchNorm statistics only, so the eight copies
+        of a clip must come out BIT-IDENTICAL in every saved activation, in the pooling positions and in the
+        logits, wherever their frames lie in the tiles of this size (a wrong tile edge, ragged last tile or
+        clip-end frame breaks this);
+      * the statistics of the repeated batch are those of its 8 distinct clips and every gradient is a mean over
+        clips, so the oracle's step on the 8 clips IS the 64-clip step: loss, logits, all 161 gradients and the
+        update are held to it exactly as in the full-frame test above (the two oracle passes with the decisions
+        of this HIP step imposed, read from the first copy's activations).
+
+    The one-stream run (per-launch profiling) and the two-stream run must agree, and the kernels the benchmark's
+    profile shows must be the ones that ran."""
+    T, S, lr = 8, 224, 0.00125
+    c8, l8 = I.clips(8, T, S, 0, "bf16"), I.labels(8)
+    c64, l64 = np.tile(c8, (8, 1, 1, 1, 1)), np.tile(l8, 8)
+    B.tsm_profile_begin()      # (per-launch profiling keeps the step on one stream)
+    r1 = run_step(64, T, S, "bf16", lr=lr, g3=G3, clips=c64, labels=l64)
+    classes = set(B.tsm_profile_end())
+    assert {"igemm_fwd_c64", "igemm_dgrad_c64", "igemm_fwd_stem", "igemm_dgrad_256x128", "wgrad_tr_256x128"} <= classes, sorted(classes)
+    one_stream = {k: r1[k] for k in ("loss", "logits", "grads")}
+    del r1
+    torch.cuda.empty_cache()
+    r = run_step(64, T, S, "bf16", lr=lr, g3=G3, clips=c64, labels=l64)      # as timed: weight gradients on the second stream
+    assert np.array_equal(r["logits"], one_stream["logits"]) and r["loss"] == one_stream["loss"]
+    assert rel_l2(r["grads"], one_stream["grads"]) < 1e-5      # (atomic sums: equal up to their order)
+    # the copies among themselves
+    lg = r["logits"].reshape(8, 8, 400)
+    assert np.array_equal(lg, np.broadcast_to(lg[0], lg.shape)), "logits differ between copies of a clip"
+    names = ["stem.y", "stem.pool_arg", "stem.pool"]
+    for res, nb, _, _ in O.STAGES:
+        for b in range(nb):
+            names += ["%s.%d.%s" % (res, b, t) for t in ("y1", "z1", "y2", "z2", "y3", "out")]
+            if b == 0:
+                names.append("%s.0.yd" % res)
+    for name in names:
+        off, shape, eb = B.tsm_resnet50_workspace_tensor(r["desc"], name)
+        n = int(np.prod(shape)) * eb
+        t = r["ws"][off:off + n].view(8, n // 8)
+        assert bool((t == t[0:1]).all().item()), "%s differs between copies of a clip" % name
+    # against the oracle's step on the 8 distinct clips
+    P = O.unflatten_params(r["flat"].astype(np.float64))
+    V = {k: np.zeros_like(v) for k, v in P.items()}
+    x = c8.astype(np.float64)
+    gates = gpu_gates(r, 8, T)
+    emul_k = O.resnet50_step(P, V, x, l8, lr, q=O.round_bf16, wq=O.round_bf16, gates=gates)
+    plain_k = O.resnet50_step(P, V, x, l8, lr, wq=O.round_bf16, gates=gates)
+    imposed = _dist(emul_k, plain_k)
+    print("\n64 clips (8 distinct clips x 8) against the oracle's step on the 8 clips")
+    _hold_to_passes(dict(r, logits=lg[0]), [("(a') bf16 storage, kernel decisions", emul_k, imposed),
+                                            ("(c') fp64, kernel decisions", plain_k, imposed)])
+    _check_sgd(r, lr)
     assert rel_l2(r["params"], O.flatten_params(emul_k[3])) < 1e-5
 
 
