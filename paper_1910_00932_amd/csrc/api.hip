@@ -367,6 +367,8 @@ static int block_infer_entry(const tsm_block_desc* d, const void* x, const tsm_b
 struct SideStream {
     hipStream_t stream = nullptr;
     hipEvent_t fork = nullptr, join = nullptr;
+    hipEvent_t lag[2] = {nullptr, nullptr};   // joins that the launch stream takes one block late (see block_bwd_impl)
+    bool pending[2] = {false, false};
     int state = 0;   // 0 untried, 1 ready, -1 unavailable
 };
 
@@ -385,7 +387,9 @@ static SideStream* side_stream() {
         ss.state = -1;
         if (hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess &&
             hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) == hipSuccess &&
-            hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) == hipSuccess)
+            hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&ss.lag[0], hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&ss.lag[1], hipEventDisableTiming) == hipSuccess)
             ss.state = 1;
         else
             (void)hipGetLastError();
@@ -415,11 +419,46 @@ static int wgrad_join(SideStream* ss, bool forked, hipStream_t s) {
 static int block_bwd_body(BlockPlan& b, const void* x, const void* out, const void* dout, void* dx, Arena& ws, bool dry,
                           hipStream_t s, SideStream* ss, bool& forked);
 
+// Takes the joins that block_bwd_impl left open in its late-join mode.
+int block_bwd_flush(hipStream_t s) {
+    SideStream* const ss = side_stream();
+    int rc = TSM_OK;
+    if (!ss) return rc;
+    for (int k = 0; k < 2; ++k) {
+        if (!ss->pending[k]) continue;
+        ss->pending[k] = false;
+        if (hipStreamWaitEvent(s, ss->lag[k], 0) != hipSuccess) rc = fail(TSM_ERR_LAUNCH, "block backward: cannot join the weight-gradient stream");
+    }
+    return rc;
+}
+
+// lag_slot < 0: the launch stream joins the weight-gradient stream at the end of the block.  lag_slot 0 / 1 (a chain of
+// blocks whose scratch alternates between two regions, slot = region): the join of this block is left open and the one
+// the previous call left open -- the other slot's -- is taken instead, so the weight gradients of a block may run on
+// beside the next block's kernels and are complete before the block after that reuses their scratch region.  The
+// caller ends the chain with block_bwd_flush, on every path.
 int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dout, void* dx, Arena& ws, bool dry,
-                   hipStream_t s) {
+                   hipStream_t s, int lag_slot) {
     SideStream* const ss = dry ? nullptr : side_stream();
     bool forked = false;
     const int rc = block_bwd_body(b, x, out, dout, dx, ws, dry, s, ss, forked);
+    if (lag_slot >= 0 && ss && rc == TSM_OK) {
+        const int k = lag_slot & 1;
+        if (ss->pending[k]) return fail(TSM_ERR_LAUNCH, "block backward: the scratch region of this slot is still in use");
+        if (forked) {
+            if (hipEventRecord(ss->lag[k], ss->stream) != hipSuccess) {
+                (void)wgrad_join(ss, true, s);
+                return fail(TSM_ERR_LAUNCH, "block backward: cannot record the weight-gradient stream's join");
+            }
+            ss->pending[k] = true;
+        }
+        if (ss->pending[k ^ 1]) {
+            ss->pending[k ^ 1] = false;
+            if (hipStreamWaitEvent(s, ss->lag[k ^ 1], 0) != hipSuccess)
+                return fail(TSM_ERR_LAUNCH, "block backward: cannot join the weight-gradient stream");
+        }
+        return TSM_OK;
+    }
     const int rj = wgrad_join(ss, forked, s);
     return rc != TSM_OK ? rc : rj;
 }

@@ -71,6 +71,7 @@ void block_saved_layout(BlockPlan& b, Arena& sv, bool keep_x_copy);
 int block_fwd_impl(BlockPlan& b, const void* x, void* out, Arena& ws, bool dry, hipStream_t s);
 // dx may be null (no input gradient wanted).
 int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dout, void* dx, Arena& ws, bool dry,
-                   hipStream_t s);
+                   hipStream_t s, int lag_slot = -1);
+int block_bwd_flush(hipStream_t s);
 
 }  // namespace tsm

@@ -997,10 +997,19 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
             pool_mean_bwd_kernel<float><<<dim3(cdiv(ftotal / 4, 256)), dim3(256), 0, s>>>(dpm, (float*)dbuf[0], rows_clip, Cf, ftotal / 4);
         LAUNCH_CHECK("pool_mean_bwd");
     }
+    // The blocks' scratch alternates between two halves of the scratch region, so that the weight gradients of a
+    // block, which run on the library's second stream, need not be complete before the next block starts (see
+    // block_bwd_impl); whatever path leaves this function first takes the joins still open.
+    struct Flush {
+        hipStream_t s; bool on;
+        ~Flush() { if (on) (void)block_bwd_flush(s); }
+    } flush{s, !dry};
+    const size_t half_cap = dry ? (size_t)-1 : (scratch_cap / 2) & ~(size_t)255;
+    size_t bwd_need = 0;
     int cur = 0;
     for (int i = (int)blks.size() - 1; i >= 0; --i) {
         Blk& b = blks[i];
-        Arena sc(scratch_base, scratch_cap);
+        Arena sc(dry ? nullptr : scratch_base + (size_t)(i & 1) * half_cap, half_cap);
         DgradFuse fz;
         b.plan.dx_fuse = nullptr;
         if (i > 0 && chain_nb[i - 1]) {
@@ -1016,10 +1025,12 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
             b.plan.dx_fuse = &fz;
             blks[i - 1].plan.dout_masked = true;
         }
-        TSM_TRY(block_bwd_impl(b.plan, b.in, b.out, dbuf[cur], dbuf[cur ^ 1], sc, dry, s));
-        note(sc);
+        TSM_TRY(block_bwd_impl(b.plan, b.in, b.out, dbuf[cur], dbuf[cur ^ 1], sc, dry, s, i & 1));
+        if (sc.used > bwd_need) bwd_need = sc.used;
         cur ^= 1;
     }
+    if (!dry) TSM_TRY(block_bwd_flush(s));
+    if (2 * ((bwd_need + 255) & ~(size_t)255) > scratch_need) scratch_need = 2 * ((bwd_need + 255) & ~(size_t)255);
     {   // stem backward: max-pool routing + ReLU mask, BatchNorm backward, weight gradient (no input gradient)
         const long rows0 = stem.rows_out();
         if (!dry) {
