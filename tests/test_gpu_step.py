@@ -284,8 +284,8 @@ def test_step_bf16_full_frame_against_oracle(N, dispatch, monkeypatch):
 
 def test_step_bf16_64_clips_as_the_benchmark_times_it():
     """configs[3], the workload the benchmark times (64 clips x 8 frames x 3x224x224, bf16, default dispatch, weight
-    gradients on the second stream), held to the oracle.  The batch is the benchmark's: 8 distinct clips repeated
-    8 times.  Then
+    gradients on the second stream), held to the oracle.  The batch is 8 distinct clips repeated 8 times (what
+    makes an oracle comparison possible at this size; the benchmark times 64 distinct clips).  Then
 
       * every per-frame result is a function of the frame and of the BatchNorm statistics only, so the eight copies
         of a clip must come out BIT-IDENTICAL in every saved activation, in the pooling positions and in the
