@@ -176,6 +176,53 @@ def test_config1_full_size_bottleneck_with_the_64_channel_kernel(monkeypatch):
     assert "igemm_fwd_c64" in classes and "igemm_dgrad_c64" in classes, sorted(classes)
 
 
+def test_config1_bottleneck_at_64_clips_ties_to_the_8_clip_block():
+    """The configs[1] bottleneck at the benchmark's 64 clips (x[64,8,256,56,56] bf16, 822 MB per wide tensor: the
+    tile counts, streaming stores and the 64-channel kernel of that size), through properties that tie it to the
+    8-clip block the tests above hold to the oracle.  The batch is 8 clips repeated 8 times, with the output
+    gradient repeated likewise:
+
+      * a frame's forward values and input gradient depend on the frame and on the batch statistics / the
+        BatchNorm-backward means only, so the eight copies must be bit-identical in out and in dx;
+      * those statistics and means are the 8-clip batch's, so out and dx of a copy are the 8-clip block's and the
+        parameter gradients (sums over frames) are 8 times the 8-clip block's -- up to the order of the sums in the
+        statistics, which moves a mean by about 1e-7 and with it the bf16 rounding of a few values per million."""
+    kind, T, Cin, H, W, Cmid, Cout = B.TSM_BLOCK_BOTTLENECK, 8, 256, 56, 56, 64, 256
+    p = make_params("bottleneck", Cin, Cmid, Cout, False, "bf16")
+    dp = {k: dev_vec(v, "bf16" if k.startswith("w") else "f32") for k, v in p.items()}
+    x8 = to_dev(I.normal((8, T, Cin, H, W), 0, "bf16"), "bf16", "nthwc")
+    dout8 = to_dev(I.normal((8, T, Cout, H, W), 3, "bf16"), "bf16", "nthwc")
+
+    def run(N, xd, doutd):
+        d = B.BlockDesc(kind=kind, N=N, T=T, Cin=Cin, H=H, W=W, Cmid=Cmid, Cout=Cout, stride=1, has_projection=0,
+                        fold_div=8, dtype=B.TSM_BF16, layout=B.TSM_NTHWC, bn_eps=1e-5)
+        saved = workspace(B.tsm_block_saved_bytes(d))
+        ws = workspace(B.tsm_block_workspace_bytes(d))
+        dg = {"d" + k: torch.empty(v.shape, dtype=torch.float32, device="cuda") for k, v in p.items()}
+        out = empty_act((N, T, Cout, H, W), "bf16", "nthwc")
+        dx = empty_act((N, T, Cin, H, W), "bf16", "nthwc")
+        B.tsm_profile_begin()
+        B.tsm_block_fwd(d, xd, dp, out, saved, ws)
+        B.tsm_block_bwd(d, xd, out, doutd, saved, dp, dx, dg, ws)
+        classes = set(B.tsm_profile_end())
+        torch.cuda.synchronize()
+        return out, dx, {k: v.double().cpu().numpy() for k, v in dg.items()}, classes
+
+    out8, dx8, g8, _ = run(8, x8, dout8)
+    out, dx, g, classes = run(64, x8.repeat(8, 1, 1, 1, 1), dout8.repeat(8, 1, 1, 1, 1))
+    assert {"igemm_fwd_c64", "igemm_dgrad_c64"} <= classes, sorted(classes)      # the library's own choice at this size
+    for name, t in (("out", out), ("dx", dx)):
+        v = t.view(torch.int16).view(8, -1)
+        assert bool((v == v[0:1]).all().item()), "%s differs between copies of a clip" % name
+    e_out = rel_l2(out[:8].double().cpu().numpy(), out8.double().cpu().numpy())
+    e_dx = rel_l2(dx[:8].double().cpu().numpy(), dx8.double().cpu().numpy())
+    e_g = {k: rel_l2(g[k], 8.0 * g8[k]) for k in g}
+    print("\n64 clips against 8 clips: out %.1e dx %.1e " % (e_out, e_dx) + " ".join("%s %.1e" % kv for kv in sorted(e_g.items())))
+    # measured: out 3e-5, dx 8e-4, parameter gradients 2e-4 .. 8e-4
+    assert e_out < 1e-3 and e_dx < 5e-3, (e_out, e_dx)
+    assert max(e_g.values()) < 5e-3, e_g
+
+
 def test_config4_full_size_tsm_block():
     """The TSM block of configs[4] at its full size: x[8,8,1024,14,14] bf16, 1024 -> 256 -> 256 -> 1024."""
     run_block("bottleneck", 8, 8, 1024, 14, 14, 256, 1024, 1, False, 8, "bf16", "nthwc")
