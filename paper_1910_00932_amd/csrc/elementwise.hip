@@ -152,45 +152,61 @@ int channel_stats(int dtype, const void* y, long rows, int C, float* partial, hi
                   : channel_stats_tv<bf16_t, 1>((const bf16_t*)y, rows, C, partial, s);
 }
 
-// Adds up the rows of a partial buffer for channel c = blockIdx.x*16 + threadIdx.x: the 16 ty lanes of a
-// (16 x 16) block split the rows (short dependent chains: this kernel is pure latency), keep two
-// independent accumulators each, then meet in LDS in a fixed order.  Totals are valid on every thread.
-static constexpr int SP_C = 16, SP_R = 16;
+// Adds up the rows of a partial buffer for channel c = blockIdx.x*16 + threadIdx.x.  This kernel is pure latency (it
+// sits between two dependent launches of every BatchNorm, forward and backward), so the rows are split over 64 ty
+// lanes of a (16 x 64) block and a lane issues the loads of its first four rows together: up to 256 rows cost one
+// memory round trip.  The lanes meet in a fixed order: the four ty lanes of a wavefront by two shuffles, the sixteen
+// wavefronts through LDS.  The totals are valid on the threads with threadIdx.y == 0.
+static constexpr int SP_C = 16, SP_R = 64;
 __device__ __forceinline__ void sum_partials(const float* __restrict__ partial, int nblocks, int C, int c,
                                              double* out1, double* out2) {
-    __shared__ double red[2][SP_R][SP_C];
+    __shared__ double red[2][SP_R / 4][SP_C];
     double s1 = 0.0, s2 = 0.0;
     if (c < C) {
-        float a0 = 0.f, a1 = 0.f, b0 = 0.f, b1 = 0.f;
-        int b = threadIdx.y;
-        for (; b + SP_R < nblocks; b += 2 * SP_R) {
-            a0 += partial[(size_t)b * 2 * C + c];
-            b0 += partial[(size_t)b * 2 * C + C + c];
-            a1 += partial[(size_t)(b + SP_R) * 2 * C + c];
-            b1 += partial[(size_t)(b + SP_R) * 2 * C + C + c];
+        float a[4] = {0.f, 0.f, 0.f, 0.f}, b[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int b0 = threadIdx.y; b0 < nblocks; b0 += 4 * SP_R) {
+            float va[4], vb[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {   // rows beyond the end re-read the last row and count as zero: no branch around the loads
+                const int r = b0 + k * SP_R;
+                const size_t at = (size_t)(r < nblocks ? r : nblocks - 1) * 2 * C + c;
+                va[k] = partial[at];
+                vb[k] = partial[at + C];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool in = b0 + k * SP_R < nblocks;
+                a[k] += in ? va[k] : 0.f;
+                b[k] += in ? vb[k] : 0.f;
+            }
         }
-        if (b < nblocks) {
-            a0 += partial[(size_t)b * 2 * C + c];
-            b0 += partial[(size_t)b * 2 * C + C + c];
-        }
-        s1 = (double)a0 + (double)a1;
-        s2 = (double)b0 + (double)b1;
+        s1 = ((double)a[0] + (double)a[1]) + ((double)a[2] + (double)a[3]);
+        s2 = ((double)b[0] + (double)b[1]) + ((double)b[2] + (double)b[3]);
     }
-    red[0][threadIdx.y][threadIdx.x] = s1;
-    red[1][threadIdx.y][threadIdx.x] = s2;
+    // thread (tx, ty) is lane (ty % 4) * 16 + tx of wavefront ty / 4
+    s1 += __shfl_xor(s1, 16);
+    s2 += __shfl_xor(s2, 16);
+    s1 += __shfl_xor(s1, 32);
+    s2 += __shfl_xor(s2, 32);
+    if ((threadIdx.y & 3) == 0) {
+        red[0][threadIdx.y >> 2][threadIdx.x] = s1;
+        red[1][threadIdx.y >> 2][threadIdx.x] = s2;
+    }
     __syncthreads();
     double t1 = 0.0, t2 = 0.0;
+    if (threadIdx.y == 0) {
 #pragma unroll
-    for (int r = 0; r < SP_R; ++r) {
-        t1 += red[0][r][threadIdx.x];
-        t2 += red[1][r][threadIdx.x];
+        for (int r = 0; r < SP_R / 4; ++r) {
+            t1 += red[0][r][threadIdx.x];
+            t2 += red[1][r][threadIdx.x];
+        }
     }
     *out1 = t1;
     *out2 = t2;
 }
 
 // ---- partial statistics -> per-channel vectors ------------------------------------------------------
-__global__ void bn_finalize_kernel(const float* __restrict__ partial, int nblocks, double inv_m, double unbias, int C,
+__global__ void __launch_bounds__(SP_C * SP_R) bn_finalize_kernel(const float* __restrict__ partial, int nblocks, double inv_m, double unbias, int C,
                                    const float* __restrict__ gamma, const float* __restrict__ beta, float eps,
                                    BnVec o, float* run_mean, float* run_var, float momentum) {
     const int c = blockIdx.x * SP_C + threadIdx.x;
@@ -240,7 +256,7 @@ int bn_eval_vec(const float* gamma, const float* beta, const float* mean, const 
     return check_launch("bn_eval_vec");
 }
 
-__global__ void stats_to_float_kernel(const float* __restrict__ partial, int nblocks, int C, float* sum, float* sumsq) {
+__global__ void __launch_bounds__(SP_C * SP_R) stats_to_float_kernel(const float* __restrict__ partial, int nblocks, int C, float* sum, float* sumsq) {
     const int c = blockIdx.x * SP_C + threadIdx.x;
     double s1, s2;
     sum_partials(partial, nblocks, C, c, &s1, &s2);
@@ -433,7 +449,7 @@ int relu_bn_bwd_reduce(int dtype, const void* dout, const void* act, const void*
 // dy = gamma*rstd*(dz - S1/m - yhat*S2/m), yhat = (y-mean)*rstd, rewritten as dy = a*dz + b*y + c with
 //   a = gamma*rstd,  b = -gamma*rstd^2*S2/m,  c = gamma*rstd*(mean*rstd*S2/m - S1/m);
 // dbeta = S1, dgamma = S2.
-__global__ void bn_bwd_coeffs_kernel(const float* __restrict__ partial, int nblocks, double inv_m, int C,
+__global__ void __launch_bounds__(SP_C * SP_R) bn_bwd_coeffs_kernel(const float* __restrict__ partial, int nblocks, double inv_m, int C,
                                      const float* __restrict__ mean, const float* __restrict__ rstd,
                                      const float* __restrict__ gamma, float* __restrict__ coef,
                                      float* __restrict__ dgamma, float* __restrict__ dbeta) {
