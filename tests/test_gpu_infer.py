@@ -120,6 +120,23 @@ def test_infer_full_size_batch16_sampled_clips():
     assert errs[0] < bound and errs[1] < bound, errs
 
 
+def test_infer_batch_64_agrees_with_batch_16_clip_by_clip():
+    """Inference is independent per clip (fixed statistics), so a batch of 64 made of a batch of 16 four times over
+    must give four bit-identical copies of the logits, wherever the clips fall in the tiles of the larger launch,
+    and those must agree with the batch-16 call (which the test above holds to the oracle) up to the different
+    tile choices the library makes at the two sizes (bf16 storage at the same points; different summation order
+    inside a layer only where a different kernel takes it)."""
+    T, S = 8, 224
+    table, flat, clips2, P, state = setup(2, T, S, "bf16", g3=0.25)
+    clips16 = np.concatenate([clips2] + [I.clips(1, T, S, 20 + i, "bf16") for i in range(14)])
+    l16 = run_infer(16, T, S, "bf16", flat, clips16, state)
+    l64 = run_infer(64, T, S, "bf16", flat, np.tile(clips16, (4, 1, 1, 1, 1)), state).reshape(4, 16, -1)
+    assert np.array_equal(l64, np.broadcast_to(l64[0], l64.shape)), "logits differ between copies of a clip"
+    err = rel_l2(l64[0], l16)
+    print("bf16 inference, batch 64 against batch 16: %.1e" % err)
+    assert err < 5e-3, err
+
+
 def test_infer_replays_from_a_hip_graph():
     """The call is stream-ordered and allocates nothing, so it can be recorded into a HIP graph; every replay,
     with eager work and synchronisation in between, reproduces the eager logits bit for bit (the forward path
