@@ -494,7 +494,16 @@ static int block_bwd_body(BlockPlan& b, const void* x, const void* out, const vo
     }
     RUN(bn_bwd_coeffs(partL, nbL, pl.rows_out(), pl.Cout, b.bn[L].mean, b.bn[L].rstd, b.st[L].g, coefL, b.st[L].dg,
                       b.st[L].db, s));
-    RUN(bn_bwd_apply(b.dtype, dzL, b.y[L], pl.rows_out(), pl.Cout, coefL, dyL, s));
+    // a projection shortcut's BatchNorm takes the same upstream gradient: both are applied from one read of it
+    void* dyd = nullptr;
+    if (b.proj) {
+        dyd = ws.take(out_bytes);
+        float* coefd = ws.take_n<float>(3 * (size_t)pl.Cout);
+        RUN(bn_bwd_coeffs(partd, nbL, pl.rows_out(), pl.Cout, b.bnd.mean, b.bnd.rstd, b.ds.g, coefd, b.ds.dg, b.ds.db, s));
+        RUN(bn_bwd_apply2(b.dtype, dzL, b.y[L], coefL, dyL, b.yd, coefd, dyd, pl.rows_out(), pl.Cout, s));
+    } else {
+        RUN(bn_bwd_apply(b.dtype, dzL, b.y[L], pl.rows_out(), pl.Cout, coefL, dyL, s));
+    }
     void* g = dyL;
     for (int i = L; i >= 1; --i) {
         StageDef& st = b.st[i];
@@ -525,10 +534,6 @@ static int block_bwd_body(BlockPlan& b, const void* x, const void* out, const vo
     int addend_stride = 1;
     if (b.proj) {
         StageDef& st = b.ds;
-        void* dyd = ws.take(out_bytes);
-        float* coefd = ws.take_n<float>(3 * (size_t)pl.Cout);
-        RUN(bn_bwd_coeffs(partd, nbL, pl.rows_out(), pl.Cout, b.bnd.mean, b.bnd.rstd, st.g, coefd, st.dg, st.db, s));
-        RUN(bn_bwd_apply(b.dtype, dzL, b.yd, pl.rows_out(), pl.Cout, coefd, dyd, s));
         TSM_TRY(wgrad_beside(ss, &forked, st.p, b.dtype, x, dyd, st.dw, st.dwp, acc_flag, ws, dry, s));
         void* dsc = ws.take((size_t)st.p.rows_in() * st.p.Cin * es);
         // A 1x1 projection with stride 2 sends gradient only to the input pixels with even row and column: its data

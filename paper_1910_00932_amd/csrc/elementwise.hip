@@ -506,6 +506,58 @@ static int bn_bwd_apply_tv(const T* dz, const T* y, long rows, int C, const floa
     return check_launch("bn_bwd_apply");
 }
 
+// Two BatchNorms that share one upstream gradient (the last stage of a block and its projection shortcut):
+// dy1 = a1*dz + b1*y1 + c1 and dy2 = a2*dz + b2*y2 + c2 from one read of dz.
+template <typename T, int V>
+__global__ void __launch_bounds__(256) bn_bwd_apply2_kernel(const T* __restrict__ dz, const T* __restrict__ y1,
+                                                            const T* __restrict__ y2, long rows, int C, int cv,
+                                                            const float* __restrict__ coef1, const float* __restrict__ coef2,
+                                                            T* __restrict__ dy1, T* __restrict__ dy2) {
+    const int cvi = blockIdx.y * blockDim.x + threadIdx.x;
+    if (cvi >= cv) return;
+    float ka[V], kb[V], kc[V], la[V], lb[V], lc[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        ka[j] = coef1[cvi * V + j];
+        kb[j] = coef1[C + cvi * V + j];
+        kc[j] = coef1[2 * C + cvi * V + j];
+        la[j] = coef2[cvi * V + j];
+        lb[j] = coef2[C + cvi * V + j];
+        lc[j] = coef2[2 * C + cvi * V + j];
+    }
+    for (long r = (long)blockIdx.x * blockDim.y + threadIdx.y; r < rows; r += (long)gridDim.x * blockDim.y) {
+        const long off = r * C + (long)cvi * V;
+        Pack<T, V> a = *(const Pack<T, V>*)(dz + off), b = *(const Pack<T, V>*)(y1 + off), c = *(const Pack<T, V>*)(y2 + off), o, p;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const float g = Elem<T>::ld(a.v[j]);
+            o.v[j] = Elem<T>::st(fmaf(ka[j], g, fmaf(kb[j], Elem<T>::ld(b.v[j]), kc[j])));
+            p.v[j] = Elem<T>::st(fmaf(la[j], g, fmaf(lb[j], Elem<T>::ld(c.v[j]), lc[j])));
+        }
+        *(Pack<T, V>*)(dy1 + off) = o;
+        *(Pack<T, V>*)(dy2 + off) = p;
+    }
+}
+
+template <typename T, int V>
+static int bn_bwd_apply2_tv(const T* dz, const T* y1, const T* y2, long rows, int C, const float* coef1, const float* coef2,
+                            T* dy1, T* dy2, hipStream_t s) {
+    RowShape r = row_shape(rows, C, V, EW_ROWS_PER_THREAD, EW_MAX_GX, EW_THREADS);
+    bn_bwd_apply2_kernel<T, V><<<r.grid, r.block, 0, s>>>(dz, y1, y2, rows, C, r.cv, coef1, coef2, dy1, dy2);
+    return check_launch("bn_bwd_apply");
+}
+
+int bn_bwd_apply2(int dtype, const void* dz, const void* y1, const float* coef1, void* dy1, const void* y2,
+                  const float* coef2, void* dy2, long rows, int C, hipStream_t s) {
+    if (rows == 0) return TSM_OK;
+    const int v = vec_of(dtype, C);
+    if (dtype == TSM_F32)
+        return v == 4 ? bn_bwd_apply2_tv<float, 4>((const float*)dz, (const float*)y1, (const float*)y2, rows, C, coef1, coef2, (float*)dy1, (float*)dy2, s)
+                      : bn_bwd_apply2_tv<float, 1>((const float*)dz, (const float*)y1, (const float*)y2, rows, C, coef1, coef2, (float*)dy1, (float*)dy2, s);
+    return v == 8 ? bn_bwd_apply2_tv<bf16_t, 8>((const bf16_t*)dz, (const bf16_t*)y1, (const bf16_t*)y2, rows, C, coef1, coef2, (bf16_t*)dy1, (bf16_t*)dy2, s)
+                  : bn_bwd_apply2_tv<bf16_t, 1>((const bf16_t*)dz, (const bf16_t*)y1, (const bf16_t*)y2, rows, C, coef1, coef2, (bf16_t*)dy1, (bf16_t*)dy2, s);
+}
+
 // coef: fp32 [3*C] from bn_bwd_coeffs
 int bn_bwd_apply(int dtype, const void* dz, const void* y, long rows, int C, const float* coef, void* dy,
                  hipStream_t s) {

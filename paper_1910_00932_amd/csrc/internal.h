@@ -78,6 +78,10 @@ int bn_bwd_coeffs(const float* partial, int nblocks, long rows, int C, const flo
                   const float* gamma, float* coef, float* dgamma, float* dbeta, hipStream_t s);
 int bn_bwd_apply(int dtype, const void* dz, const void* y, long rows, int C, const float* coef, void* dy,
                  hipStream_t s);
+// The same for two BatchNorms that share the upstream gradient dz, from one read of it: dy1 from (y1, coef1), dy2 from
+// (y2, coef2).  No buffer may alias another.
+int bn_bwd_apply2(int dtype, const void* dz, const void* y1, const float* coef1, void* dy1, const void* y2,
+                  const float* coef2, void* dy2, long rows, int C, hipStream_t s);
 // out = a + b
 int add_tensors(int dtype, const void* a, const void* b, void* out, size_t n, hipStream_t s);
 // dtype conversion / repacking of weights
