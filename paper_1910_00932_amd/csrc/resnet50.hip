@@ -281,6 +281,104 @@ __global__ void __launch_bounds__(256) stem_pool_bwd_kernel(const T* __restrict_
     }
 }
 
+// The same for even H and W, one 2 x 2 patch of conv-output pixels per thread and pass: the patch (2a.., 2b..) lies in
+// the pooling windows (a, b), (a, b+1), (a+1, b), (a+1, b+1) only, so four window loads serve four pixels (the
+// one-pixel form loads four windows per pixel).  Window (oh, ow) covers rows 2*oh-1 .. 2*oh+1: the code kh*3 + kw of
+// a pixel inside a window follows from its position in the patch.
+template <typename T>
+__global__ void __launch_bounds__(256) stem_pool_bwd_patch_kernel(const T* __restrict__ dp, const uint8_t* __restrict__ arg,
+                                                                  const T* __restrict__ y, const float* __restrict__ scale,
+                                                                  const float* __restrict__ shift, const float* __restrict__ mean,
+                                                                  const float* __restrict__ rstd, T* __restrict__ da,
+                                                                  float* __restrict__ partial, int H, int W, int Ho, int Wo,
+                                                                  long patches) {
+    constexpr int V = Elem<T>::VEC, C = 64, cv = C / V;
+    const int v = threadIdx.x;
+    float sc[V], sh[V], mu[V], rs[V], s1[V], s2[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        sc[j] = scale[v * V + j];
+        sh[j] = shift[v * V + j];
+        mu[j] = mean[v * V + j];
+        rs[j] = rstd[v * V + j];
+        s1[j] = s2[j] = 0.f;
+    }
+    const int H2 = H / 2, W2 = W / 2;
+    for (long r = (long)blockIdx.x * blockDim.y + threadIdx.y; r < patches; r += (long)gridDim.x * blockDim.y) {
+        const int b = (int)(r % W2), a = (int)((r / W2) % H2);
+        const long f = r / ((long)W2 * H2);
+        // windows w = 2*dh + dw at (a + dh, b + dw); those beyond the border are clamped for the load and get a code
+        // that no winner has
+        const bool vh[2] = {a < Ho, a + 1 < Ho}, vw[2] = {b < Wo, b + 1 < Wo};
+        Vec16<T> dq[4];
+        uint8_t aq[4][V];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const int oh = a + (w >> 1), ow = b + (w & 1);
+            const long o = (((f * Ho) + (oh < Ho ? oh : Ho - 1)) * Wo + (ow < Wo ? ow : Wo - 1)) * (long)cv + v;
+            dq[w] = *(const Vec16<T>*)(dp + o * V);
+            if (V == 8) *(uint2*)aq[w] = *(const uint2*)(arg + o * V);
+            else *(uint32_t*)aq[w] = *(const uint32_t*)(arg + o * V);
+        }
+        Vec16<T> pk[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            pk[p] = *(const Vec16<T>*)(y + (((f * H + 2 * a + (p >> 1)) * W + 2 * b + (p & 1)) * (long)cv + v) * V);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int ph = p >> 1, pw = p & 1;      // pixel (2a + ph, 2b + pw)
+            float g[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) g[j] = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const int dh = w >> 1, dw = w & 1;
+                // rows of window a + dh: 2a + 2dh - 1 .. 2a + 2dh + 1; the pixel's row 2a + ph lies inside iff
+                // kh = ph + 1 - 2dh is in 0..2 (ph = 0 is outside the lower window), likewise along w
+                const int kh = ph + 1 - 2 * dh, kw = pw + 1 - 2 * dw;
+                if (kh < 0 || kw < 0) continue;      // (compile-time: p, w are unrolled)
+                const int code = vh[dh] && vw[dw] ? kh * 3 + kw : 255;
+#pragma unroll
+                for (int j = 0; j < V; ++j)
+                    if ((int)aq[w][j] == code) g[j] += Elem<T>::ld(dq[w].v[j]);
+            }
+            Vec16<T> o;
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const float yv = Elem<T>::ld(pk[p].v[j]);
+                const float z = fmaf(yv, sc[j], sh[j]);
+                const bool live = Elem<T>::ld(Elem<T>::st(z > 0.f ? z : 0.f)) > 0.f;
+                o.v[j] = Elem<T>::st(live ? g[j] : 0.f);
+                const float dz = Elem<T>::ld(o.v[j]);
+                s1[j] += dz;
+                s2[j] = fmaf(dz, (yv - mu[j]) * rs[j], s2[j]);
+            }
+            *(Vec16<T>*)(da + (((f * H + 2 * a + ph) * W + 2 * b + pw) * (long)cv + v) * V) = o;
+        }
+    }
+    __shared__ float red[2][256 * V];
+    const int t = threadIdx.y * cv + v;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        red[0][t * V + j] = s1[j];
+        red[1][t * V + j] = s2[j];
+    }
+    __syncthreads();
+    if (threadIdx.y == 0) {
+        float* prow = partial + (size_t)blockIdx.x * 2 * C;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            float sa = 0.f, sb = 0.f;
+            for (int q = 0; q < (int)blockDim.y; ++q) {
+                sa += red[0][(q * cv + v) * V + j];
+                sb += red[1][(q * cv + v) * V + j];
+            }
+            prow[v * V + j] = sa;
+            prow[C + v * V + j] = sb;
+        }
+    }
+}
+
 // ---- head: global average pool + temporal consensus + linear + softmax cross-entropy ---------
 // The consensus (mean over T of the per-frame linear outputs) is an affine map, so the
 // mean over frames and pixels is taken first: pm[n][c] = mean_{t,h,w} feat[n,t,h,w,c].
@@ -1035,7 +1133,9 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
         const long rows0 = stem.rows_out();
         if (!dry) {
             const dim3 blk(64 / VEC, 256 / (64 / VEC));
-            if (bf)
+            if (bf && H1 % 2 == 0)
+                stem_pool_bwd_patch_kernel<bf16_t><<<dim3(nb0b), blk, 0, s>>>((const bf16_t*)dbuf[cur], arg0, (const bf16_t*)y0, bn0.scale, bn0.shift, bn0.mean, bn0.rstd, (bf16_t*)da0, part0, H1, H1, Hp, Hp, rows0 / 4);
+            else if (bf)
                 stem_pool_bwd_kernel<bf16_t><<<dim3(nb0b), blk, 0, s>>>((const bf16_t*)dbuf[cur], arg0, (const bf16_t*)y0, bn0.scale, bn0.shift, bn0.mean, bn0.rstd, (bf16_t*)da0, part0, H1, H1, Hp, Hp, rows0);
             else
                 stem_pool_bwd_kernel<float><<<dim3(nb0b), blk, 0, s>>>((const float*)dbuf[cur], arg0, (const float*)y0, bn0.scale, bn0.shift, bn0.mean, bn0.rstd, (float*)da0, part0, H1, H1, Hp, Hp, rows0);
