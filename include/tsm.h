@@ -40,7 +40,11 @@
  *    which the two-convolution kernel is chosen (default: three per four
  *    compute units); TSM_MASK_BITS=0 (read once per process) makes the train
  *    step's data gradients take the ReLU mask of a block output from the
- *    activation itself instead of from the decision bits its forward pass keeps.
+ *    activation itself instead of from the decision bits its forward pass keeps;
+ *    TSM_SHORTCUT_BRANCH=0 (read once per process) keeps the kernels of a
+ *    projection shortcut on the launch stream (they otherwise run on the library's
+ *    second stream beside the residual branch, like the weight gradients, and
+ *    TSM_WGRAD_OVERLAP=0 keeps everything on the launch stream).
  *  - Return value: TSM_OK or a negative tsm_status.  On error nothing has been
  *    launched (argument errors) or the stream's state is undefined
  *    (TSM_ERR_LAUNCH).  tsm_last_error() returns a host string describing the

@@ -201,7 +201,80 @@ void block_saved_layout(BlockPlan& b, Arena& sv, bool keep_x_copy) {
     }
 }
 
-int block_fwd_impl(BlockPlan& b, const void* x, void* out, Arena& ws, bool dry, hipStream_t s) {
+// ---- weight gradients beside the data-gradient chain -----------------------------------------------------
+// A weight gradient only feeds the optimiser, so inside one block's backward pass it runs on a second stream
+// (default priority) while the main stream goes on with the data gradients: fork = the side stream waits for an
+// event recorded on the main stream after the kernel that produced the weight gradient's operand; join = the main
+// stream waits, at the end of the block, for an event recorded behind the last weight gradient.  Nothing the
+// weight gradients read is rewritten inside the block, and the join comes before the block's scratch is reused.
+// Per host thread and device; TSM_WGRAD_OVERLAP=0, per-launch profiling or a failed stream creation keep
+// everything on the caller's stream.  The first call on a device creates the stream and events (do not make that
+// call under stream capture; later calls capture as a fork/join pattern).
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    hipEvent_t lag[2] = {nullptr, nullptr};   // joins that the launch stream takes one block late (see block_bwd_impl)
+    hipEvent_t branch = nullptr;              // end of a projection shortcut's work on the side stream
+    bool pending[2] = {false, false};
+    int state = 0;   // 0 untried, 1 ready, -1 unavailable
+};
+
+static SideStream* side_stream() {
+    static int enabled = -1;
+    if (enabled < 0) {
+        const char* e = getenv("TSM_WGRAD_OVERLAP");
+        enabled = (e && e[0] == '0') ? 0 : 1;
+    }
+    if (!enabled || profiling_active()) return nullptr;
+    static thread_local SideStream side[16];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
+    SideStream& ss = side[dev];
+    if (ss.state == 0) {
+        ss.state = -1;
+        if (hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess &&
+            hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&ss.lag[0], hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&ss.lag[1], hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&ss.branch, hipEventDisableTiming) == hipSuccess)
+            ss.state = 1;
+        else
+            (void)hipGetLastError();
+    }
+    return ss.state == 1 ? &ss : nullptr;
+}
+
+// Runs one weight gradient on the side stream behind everything enqueued on `s` so far (or on `s` itself).
+static int wgrad_beside(SideStream* ss, bool* forked, const ConvP& p, int dtype, const void* x, const void* dy, float* dw,
+                        float* dwp, int accumulate, Arena& ws, bool dry, hipStream_t s) {
+    if (!ss || dry) return run_conv_wgrad(p, dtype, x, dy, dw, dwp, accumulate, ws, dry, s);
+    if (hipEventRecord(ss->fork, s) != hipSuccess || hipStreamWaitEvent(ss->stream, ss->fork, 0) != hipSuccess)
+        return fail(TSM_ERR_LAUNCH, "block backward: cannot fork the weight-gradient stream");
+    *forked = true;
+    return run_conv_wgrad(p, dtype, x, dy, dw, dwp, accumulate, ws, dry, ss->stream);
+}
+
+// TSM_SHORTCUT_BRANCH=0 (read once per process) keeps a projection shortcut's kernels on the launch stream.
+static bool shortcut_branch_enabled() {
+    static int enabled = -1;
+    if (enabled < 0) {
+        const char* e = getenv("TSM_SHORTCUT_BRANCH");
+        enabled = (e && e[0] == '0') ? 0 : 1;
+    }
+    return enabled != 0;
+}
+
+static int wgrad_join(SideStream* ss, bool forked, hipStream_t s) {
+    if (!ss || !forked) return TSM_OK;
+    if (hipEventRecord(ss->join, ss->stream) != hipSuccess || hipStreamWaitEvent(s, ss->join, 0) != hipSuccess)
+        return fail(TSM_ERR_LAUNCH, "block backward: cannot join the weight-gradient stream");
+    return TSM_OK;
+}
+
+// The projection shortcut (convolution + BatchNorm statistics) depends on the block input only: it runs on the side
+// stream beside the first convolution, which reads the same tensor, and is joined in front of the block's tail.
+static int block_fwd_stages(BlockPlan& b, const void* x, Arena& ws, bool dry, hipStream_t s) {
     const void* cur = x;
     for (int i = 0; i < b.nst; ++i) {
         StageDef& st = b.st[i];
@@ -215,14 +288,37 @@ int block_fwd_impl(BlockPlan& b, const void* x, void* out, Arena& ws, bool dry, 
             cur = b.z[i];
         }
     }
+    return TSM_OK;
+}
+
+static int block_fwd_shortcut(BlockPlan& b, const void* x, Arena& ws, bool dry, hipStream_t s) {
+    StageDef& st = b.ds;
+    const int nb = conv_stats_blocks(st.p, b.dtype);
+    float* part = ws.take_n<float>((size_t)nb * 2 * st.p.Cout);
+    TSM_TRY(run_conv_fwd(st.p, b.dtype, x, st.w, st.wp, b.yd, part, ws, dry, s));
+    RUN(bn_finalize(part, nb, st.p.rows_out(), st.p.Cout, st.g, st.b, b.eps, b.bnd, st.run_mean, st.run_var,
+                    b.bn_momentum, s));
+    return TSM_OK;
+}
+
+int block_fwd_impl(BlockPlan& b, const void* x, void* out, Arena& ws, bool dry, hipStream_t s) {
+    SideStream* const ss = (dry || !b.proj || !shortcut_branch_enabled()) ? nullptr : side_stream();
+    bool forked = false;
+    int rc = TSM_OK;
     if (b.proj) {
-        StageDef& st = b.ds;
-        const int nb = conv_stats_blocks(st.p, b.dtype);
-        float* part = ws.take_n<float>((size_t)nb * 2 * st.p.Cout);
-        TSM_TRY(run_conv_fwd(st.p, b.dtype, x, st.w, st.wp, b.yd, part, ws, dry, s));
-        RUN(bn_finalize(part, nb, st.p.rows_out(), st.p.Cout, st.g, st.b, b.eps, b.bnd, st.run_mean, st.run_var,
-                        b.bn_momentum, s));
+        hipStream_t sd = s;
+        if (ss) {
+            if (hipEventRecord(ss->fork, s) != hipSuccess || hipStreamWaitEvent(ss->stream, ss->fork, 0) != hipSuccess)
+                return fail(TSM_ERR_LAUNCH, "block forward: cannot fork the side stream");
+            forked = true;
+            sd = ss->stream;
+        }
+        rc = block_fwd_shortcut(b, x, ws, dry, sd);
     }
+    if (rc == TSM_OK) rc = block_fwd_stages(b, x, ws, dry, s);
+    const int rj = wgrad_join(ss, forked, s);      // on every path: a caller's stream capture must not keep an open branch
+    if (rc != TSM_OK) return rc;
+    if (rj != TSM_OK) return rj;
     const int L = b.nst - 1;
     const ConvP& pl = b.st[L].p;
     RUN(block_tail_fwd(b.dtype, b.y[L], pl.rows_out(), pl.Cout, b.bn[L].scale, b.bn[L].shift, b.proj ? b.yd : x,
@@ -355,65 +451,6 @@ static int block_infer_entry(const tsm_block_desc* d, const void* x, const tsm_b
     return TSM_OK;
 }
 
-// ---- weight gradients beside the data-gradient chain -----------------------------------------------------
-// A weight gradient only feeds the optimiser, so inside one block's backward pass it runs on a second stream
-// (default priority) while the main stream goes on with the data gradients: fork = the side stream waits for an
-// event recorded on the main stream after the kernel that produced the weight gradient's operand; join = the main
-// stream waits, at the end of the block, for an event recorded behind the last weight gradient.  Nothing the
-// weight gradients read is rewritten inside the block, and the join comes before the block's scratch is reused.
-// Per host thread and device; TSM_WGRAD_OVERLAP=0, per-launch profiling or a failed stream creation keep
-// everything on the caller's stream.  The first call on a device creates the stream and events (do not make that
-// call under stream capture; later calls capture as a fork/join pattern).
-struct SideStream {
-    hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
-    hipEvent_t lag[2] = {nullptr, nullptr};   // joins that the launch stream takes one block late (see block_bwd_impl)
-    bool pending[2] = {false, false};
-    int state = 0;   // 0 untried, 1 ready, -1 unavailable
-};
-
-static SideStream* side_stream() {
-    static int enabled = -1;
-    if (enabled < 0) {
-        const char* e = getenv("TSM_WGRAD_OVERLAP");
-        enabled = (e && e[0] == '0') ? 0 : 1;
-    }
-    if (!enabled || profiling_active()) return nullptr;
-    static thread_local SideStream side[16];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
-    SideStream& ss = side[dev];
-    if (ss.state == 0) {
-        ss.state = -1;
-        if (hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess &&
-            hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) == hipSuccess &&
-            hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) == hipSuccess &&
-            hipEventCreateWithFlags(&ss.lag[0], hipEventDisableTiming) == hipSuccess &&
-            hipEventCreateWithFlags(&ss.lag[1], hipEventDisableTiming) == hipSuccess)
-            ss.state = 1;
-        else
-            (void)hipGetLastError();
-    }
-    return ss.state == 1 ? &ss : nullptr;
-}
-
-// Runs one weight gradient on the side stream behind everything enqueued on `s` so far (or on `s` itself).
-static int wgrad_beside(SideStream* ss, bool* forked, const ConvP& p, int dtype, const void* x, const void* dy, float* dw,
-                        float* dwp, int accumulate, Arena& ws, bool dry, hipStream_t s) {
-    if (!ss || dry) return run_conv_wgrad(p, dtype, x, dy, dw, dwp, accumulate, ws, dry, s);
-    if (hipEventRecord(ss->fork, s) != hipSuccess || hipStreamWaitEvent(ss->stream, ss->fork, 0) != hipSuccess)
-        return fail(TSM_ERR_LAUNCH, "block backward: cannot fork the weight-gradient stream");
-    *forked = true;
-    return run_conv_wgrad(p, dtype, x, dy, dw, dwp, accumulate, ws, dry, ss->stream);
-}
-
-static int wgrad_join(SideStream* ss, bool forked, hipStream_t s) {
-    if (!ss || !forked) return TSM_OK;
-    if (hipEventRecord(ss->join, ss->stream) != hipSuccess || hipStreamWaitEvent(s, ss->join, 0) != hipSuccess)
-        return fail(TSM_ERR_LAUNCH, "block backward: cannot join the weight-gradient stream");
-    return TSM_OK;
-}
-
 // The body of block_bwd_impl; `forked` tells the caller whether the side stream has work of this block, so that it
 // is joined on every path out, errors included (a caller's stream capture must not be left with an open branch).
 static int block_bwd_body(BlockPlan& b, const void* x, const void* out, const void* dout, void* dx, Arena& ws, bool dry,
@@ -504,11 +541,49 @@ static int block_bwd_body(BlockPlan& b, const void* x, const void* out, const vo
     } else {
         RUN(bn_bwd_apply(b.dtype, dzL, b.y[L], pl.rows_out(), pl.Cout, coefL, dyL, s));
     }
+    // The projection shortcut's data gradient depends on dyd only and is needed by the block's last data gradient only:
+    // it runs on the side stream, behind the last stage's weight gradient, beside the chain of the residual branch.
+    const void* addend = dzL;
+    int addend_stride = 1;
+    bool branch_open = false;
+    SideStream* const ss_all = ss;
+    auto shortcut_dgrad = [&]() -> int {
+        StageDef& st = b.ds;
+        void* dsc = ws.take((size_t)st.p.rows_in() * st.p.Cin * es);
+        hipStream_t sd = s;
+        SideStream* const ss = shortcut_branch_enabled() ? ss_all : nullptr;
+        if (ss) {
+            if (hipEventRecord(ss->fork, s) != hipSuccess || hipStreamWaitEvent(ss->stream, ss->fork, 0) != hipSuccess)
+                return fail(TSM_ERR_LAUNCH, "block backward: cannot fork the side stream");
+            forked = true;
+            sd = ss->stream;
+        }
+        // A 1x1 projection with stride 2 sends gradient only to the input pixels with even row and column: its data
+        // gradient is the 1x1 stride-1 data gradient on the output grid, kept in that compact form and added at the
+        // even pixels by the kernel that produces dx (three quarters of the tensor are neither written nor read)
+        if (st.p.stride == 2 && st.p.taps() == 1 && st.p.pad == 0 && use_mfma(st.p, b.dtype) && use_mfma(b.st[0].p, b.dtype) &&
+            conv_mfma_dgrad_compact_addend_ok(b.st[0].p) && (dx || dry)) {
+            ConvP pc = st.p;
+            pc.H = st.p.Ho; pc.W = st.p.Wo; pc.stride = 1;
+            TSM_TRY(run_conv_dgrad(pc, b.dtype, dyd, st.w, st.wd, dsc, nullptr, nullptr, ws, dry, sd));
+            addend_stride = 2;
+        } else {
+            TSM_TRY(run_conv_dgrad(st.p, b.dtype, dyd, st.w, st.wd, dsc, nullptr, nullptr, ws, dry, sd));
+        }
+        if (ss) {
+            if (hipEventRecord(ss->branch, ss->stream) != hipSuccess)
+                return fail(TSM_ERR_LAUNCH, "block backward: cannot record the side stream's event");
+            branch_open = true;
+        }
+        addend = dsc;
+        return TSM_OK;
+    };
     void* g = dyL;
     for (int i = L; i >= 1; --i) {
         StageDef& st = b.st[i];
         const ConvP& pp = b.st[i - 1].p;  // producer of this stage's input
         TSM_TRY(wgrad_beside(ss, &forked, st.p, b.dtype, b.z[i - 1], g, st.dw, st.dwp, acc_flag, ws, dry, s));
+        if (i == L && b.proj) TSM_TRY(shortcut_dgrad());
         void* dzin = ws.take((size_t)pp.rows_out() * pp.Cout * es);
         // the ReLU mask and the BatchNorm reductions of the producing stage ride in the data gradient's
         // epilogue when its kernel can do that; otherwise they are a pass of their own
@@ -530,25 +605,11 @@ static int block_bwd_body(BlockPlan& b, const void* x, const void* out, const vo
         g = dzin;
     }
     TSM_TRY(wgrad_beside(ss, &forked, b.st[0].p, b.dtype, x, g, b.st[0].dw, b.st[0].dwp, acc_flag, ws, dry, s));
-    const void* addend = dzL;
-    int addend_stride = 1;
     if (b.proj) {
         StageDef& st = b.ds;
         TSM_TRY(wgrad_beside(ss, &forked, st.p, b.dtype, x, dyd, st.dw, st.dwp, acc_flag, ws, dry, s));
-        void* dsc = ws.take((size_t)st.p.rows_in() * st.p.Cin * es);
-        // A 1x1 projection with stride 2 sends gradient only to the input pixels with even row and column: its data
-        // gradient is the 1x1 stride-1 data gradient on the output grid, kept in that compact form and added at the
-        // even pixels by the kernel that produces dx (three quarters of the tensor are neither written nor read)
-        if (st.p.stride == 2 && st.p.taps() == 1 && st.p.pad == 0 && use_mfma(st.p, b.dtype) && use_mfma(b.st[0].p, b.dtype) &&
-            conv_mfma_dgrad_compact_addend_ok(b.st[0].p) && (dx || dry)) {
-            ConvP pc = st.p;
-            pc.H = st.p.Ho; pc.W = st.p.Wo; pc.stride = 1;
-            TSM_TRY(run_conv_dgrad(pc, b.dtype, dyd, st.w, st.wd, dsc, nullptr, nullptr, ws, dry, s));
-            addend_stride = 2;
-        } else {
-            TSM_TRY(run_conv_dgrad(st.p, b.dtype, dyd, st.w, st.wd, dsc, nullptr, nullptr, ws, dry, s));
-        }
-        addend = dsc;
+        if (branch_open && hipStreamWaitEvent(s, ss->branch, 0) != hipSuccess)
+            return fail(TSM_ERR_LAUNCH, "block backward: cannot wait for the side stream");
     }
     if (dx || dry)
         TSM_TRY(run_conv_dgrad(b.st[0].p, b.dtype, g, b.st[0].w, b.st[0].wd, dx, addend, b.dx_fuse, ws, dry, s, addend_stride));
