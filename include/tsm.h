@@ -14,9 +14,10 @@
  *    says "host".  The library allocates no device memory; scratch space comes in
  *    through the (ws, ws_bytes) pair, sized by the matching *_workspace_bytes().
  *  - Calls are asynchronous on the caller's hipStream_t (passed as void*; NULL is
- *    the default stream) and never synchronise the device.  The backward entry
- *    points (tsm_block_bwd, tsm_resnet50_step, tsm_resnet50_accum_step) run the
- *    weight gradients on a second stream that the library creates per host thread
+ *    the default stream) and never synchronise the device.  The training entry
+ *    points (tsm_block_fwd, tsm_block_bwd, tsm_resnet50_step,
+ *    tsm_resnet50_accum_step) run the weight gradients and the kernels of a
+ *    projection shortcut on a second stream that the library creates per host thread
  *    and device on first use; it forks from and joins the caller's stream with
  *    events inside the call, so the call as a whole stays ordered on the caller's
  *    stream and can be recorded into a HIP graph (make the first call on a device
