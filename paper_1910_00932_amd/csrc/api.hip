@@ -255,6 +255,26 @@ static int wgrad_beside(SideStream* ss, bool* forked, const ConvP& p, int dtype,
     return run_conv_wgrad(p, dtype, x, dy, dw, dwp, accumulate, ws, dry, ss->stream);
 }
 
+// A branch of independent work for a caller inside the library: the side stream, forked behind everything enqueued on
+// `s` so far (or `s` itself where there is no side stream); side_branch_end joins it (a no-op for `s` itself).
+hipStream_t side_branch_begin(hipStream_t s) {
+    SideStream* const ss = side_stream();
+    if (!ss) return s;
+    if (hipEventRecord(ss->fork, s) != hipSuccess || hipStreamWaitEvent(ss->stream, ss->fork, 0) != hipSuccess) {
+        (void)hipGetLastError();
+        return s;
+    }
+    return ss->stream;
+}
+
+int side_branch_end(hipStream_t s, hipStream_t branch) {
+    if (branch == s) return TSM_OK;
+    SideStream* const ss = side_stream();
+    if (!ss || hipEventRecord(ss->join, ss->stream) != hipSuccess || hipStreamWaitEvent(s, ss->join, 0) != hipSuccess)
+        return fail(TSM_ERR_LAUNCH, "cannot join the side stream");
+    return TSM_OK;
+}
+
 // TSM_SHORTCUT_BRANCH=0 (read once per process) keeps a projection shortcut's kernels on the launch stream.
 static bool shortcut_branch_enabled() {
     static int enabled = -1;

@@ -73,5 +73,9 @@ int block_fwd_impl(BlockPlan& b, const void* x, void* out, Arena& ws, bool dry, 
 int block_bwd_impl(BlockPlan& b, const void* x, const void* out, const void* dout, void* dx, Arena& ws, bool dry,
                    hipStream_t s, int lag_slot = -1);
 int block_bwd_flush(hipStream_t s);
+// A branch of independent work on the library's second stream, forked behind what `s` holds so far; returns `s` itself
+// where there is no second stream (one-stream mode, profiling).  side_branch_end joins it, on every path.
+hipStream_t side_branch_begin(hipStream_t s);
+int side_branch_end(hipStream_t s, hipStream_t branch);
 
 }  // namespace tsm

@@ -1022,17 +1022,26 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
     const size_t scratch_cap = dry ? (size_t)-1 : (ws_bytes > A.used ? ws_bytes - A.used : 0);
     auto note = [&](const Arena& sc) { if (sc.used > scratch_need) scratch_need = sc.used; };
 
+    // The fills and the weight packing are needed from the first residual block on: they run on the second stream
+    // beside the stem and are joined in front of the blocks (on every path out of this function).
+    struct Branch {
+        hipStream_t s, b;
+        bool open;
+        int end() { const int rc = open ? side_branch_end(s, b) : TSM_OK; open = false; return rc; }
+        ~Branch() { (void)end(); }
+    } prep{s, dry ? s : side_branch_begin(s), !dry};
+    const hipStream_t sp = prep.b;
     // every weight gradient is accumulated with atomics: one fill for the whole gradient vector
-    RUN(fill_zero(grads, (size_t)nparams * sizeof(float), s));
-    if (dwp_bytes) RUN(fill_zero(dwp_base, dwp_bytes, s));
+    RUN(fill_zero(grads, (size_t)nparams * sizeof(float), sp));
+    if (dwp_bytes) RUN(fill_zero(dwp_base, dwp_bytes, sp));
     if (bf && !dry) {   // bf16 working copies of all convolution weights in both packings
         if (pk_fwd.tiled && pk_dg.tiled && pk_fwd.n == pk_dg.n) {
-            pack_tiles_kernel<<<dim3(pk_fwd.tstart[pk_fwd.n]), dim3(256), 0, s>>>(pk_fwd, pk_dg, params, pack_base, 1);
+            pack_tiles_kernel<<<dim3(pk_fwd.tstart[pk_fwd.n]), dim3(256), 0, sp>>>(pk_fwd, pk_dg, params, pack_base, 1);
             LAUNCH_CHECK("pack_weights");
         } else {
-            pack_all_kernel<<<dim3(cdiv(pk_fwd.start[pk_fwd.n], 256)), dim3(256), 0, s>>>(pk_fwd, params, pack_base, 0);
+            pack_all_kernel<<<dim3(cdiv(pk_fwd.start[pk_fwd.n], 256)), dim3(256), 0, sp>>>(pk_fwd, params, pack_base, 0);
             LAUNCH_CHECK("pack_weights_fwd");
-            pack_all_kernel<<<dim3(cdiv(pk_dg.start[pk_dg.n], 256)), dim3(256), 0, s>>>(pk_dg, params, pack_base, 1);
+            pack_all_kernel<<<dim3(cdiv(pk_dg.start[pk_dg.n], 256)), dim3(256), 0, sp>>>(pk_dg, params, pack_base, 1);
             LAUNCH_CHECK("pack_weights_dgrad");
         }
     }
@@ -1068,6 +1077,7 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
             LAUNCH_CHECK("stem_pool_fwd");
         }
     }
+    TSM_TRY(prep.end());
     for (Blk& b : blks) {
         Arena sc(scratch_base, scratch_cap);
         TSM_TRY(block_fwd_impl(b.plan, b.in, b.out, sc, dry, s));
