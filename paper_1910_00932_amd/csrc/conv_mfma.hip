@@ -2265,6 +2265,11 @@ struct WgradArgs {
     long chunk;            // pixels per block (multiple of 64)
     int K;                 // taps * Cin
     int col_tiles;
+    // wgrad_tr_kernel, AFF variants: dy is not stored; the loader forms it from dz (passed as `dy`) and the
+    // BatchNorm input ay as dy = a*dz + b*ay + c per output channel, coefficients aff = [3][Cout] (BatchNorm
+    // backward, see bn_bwd_apply), rounded to bf16 as the stored tensor would be
+    const bf16_t* ay;
+    const float* aff;
 };
 
 static constexpr int WMK = 64;        // pixels per main-loop step
@@ -2489,7 +2494,7 @@ __device__ __forceinline__ bf16x8 lds_read_tr_pair(const unsigned char* p0, cons
     return __builtin_bit_cast(bf16x8, v);
 }
 
-template <int BCO, int BCI, int WM, int WN>
+template <int BCO, int BCI, int WM, int WN, bool AFF = false>
 __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BCO / WM, TN = BCI / WN;       // wavefront tile
@@ -2526,11 +2531,20 @@ __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
     const int hw = a.Ho * a.Wo;
     const int bias_el = (a.pad * a.W + a.pad) * a.pitch;
     const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(a.dy, (uint32_t)(a.M * a.Cout * 2));
+    const __amdgpu_buffer_rsrc_t rsrc_y = make_rsrc(AFF ? a.ay : a.dy, (uint32_t)(a.M * a.Cout * 2));
     const __amdgpu_buffer_rsrc_t rsrc_b =
         make_rsrc(a.x - bias_el, (uint32_t)(((long)a.F * a.H * a.W * a.pitch + (a.Cin - a.pitch) + bias_el) * 2));
 
     // ---- this thread's pieces: dy rows arow + i*RA, x rows brow + j*RB of every step
     const int avec = tid % AVR, arow = tid / AVR;
+    float ka[8], kb[8], kc[8];                        // AFF: coefficients of this thread's eight output channels
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int c = co0 + avec * 8 + q;
+        ka[q] = AFF ? a.aff[c] : 1.f;
+        kb[q] = AFF ? a.aff[a.Cout + c] : 0.f;
+        kc[q] = AFF ? a.aff[2 * a.Cout + c] : 0.f;
+    }
     uint32_t a_off[PA];
 #pragma unroll
     for (int i = 0; i < PA; ++i) a_off[i] = (uint32_t)(((arow + i * RA) * a.Cout + co0 + avec * 8) * 2);
@@ -2614,13 +2628,31 @@ __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
         return p;
     };
     u32x4 greg[NP];
+    u32x4 gy[AFF ? PA : 1];       // AFF: the BatchNorm input beside each dz piece
+    uint32_t gvalid = 0;          // AFF: bit i = piece i lies inside the pixel range (rows beyond it must stay zero)
     auto load_piece = [&](const Plan& p, int i) {
         greg[i] = i < PA ? __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, (int)p.v[i], p.soff_a, 0)
                          : __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, (int)p.v[i], 0, 0);
+        if (AFF && i < PA) {
+            gy[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_y, (int)p.v[i], p.soff_a, 0);
+            gvalid = p.v[i] != OOB_OFFSET ? gvalid | (1u << i) : gvalid & ~(1u << i);
+        }
     };
     auto store_piece = [&](int stage, int i) {
         const int pos = i < PA ? a_wr + i * RA * ROWA : b_wr[i < PA ? 0 : i - PA];
-        *(u32x4*)(smem + stage * STAGE + pos) = greg[i];
+        u32x4 v = greg[i];
+        if (AFF && i < PA) {
+            const u32x4 y = gy[i];
+            const bool in = (gvalid >> i) & 1u;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lo = fmaf(ka[2 * e], __uint_as_float(v[e] << 16), fmaf(kb[2 * e], __uint_as_float(y[e] << 16), kc[2 * e]));
+                const float hi = fmaf(ka[2 * e + 1], __uint_as_float(v[e] & 0xffff0000u),
+                                      fmaf(kb[2 * e + 1], __uint_as_float(y[e] & 0xffff0000u), kc[2 * e + 1]));
+                v[e] = in ? pack_bf16x2(lo, hi) : 0u;
+            }
+        }
+        *(u32x4*)(smem + stage * STAGE + pos) = v;
     };
 
     f32x16 acc[MI][NJ];
@@ -2698,7 +2730,7 @@ __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
         }
 }
 
-template <int BCO, int BCI, int WM, int WN>
+template <int BCO, int BCI, int WM, int WN, bool AFF = false>
 static int launch_wgrad_tr(WgradArgs& a, int Cout, int blocks_per_cu, const char* name, hipStream_t s) {
     constexpr int NT = WM * WN * 64;
     a.col_tiles = a.K / BCI;
@@ -2711,7 +2743,7 @@ static int launch_wgrad_tr(WgradArgs& a, int Cout, int blocks_per_cu, const char
     if (chunk < 16L * WMK) chunk = 16L * WMK;
     a.chunk = (chunk + WMK - 1) / WMK * WMK;
     const dim3 grid((unsigned)((a.M + a.chunk - 1) / a.chunk), (unsigned)tiles);
-    auto kern = wgrad_tr_kernel<BCO, BCI, WM, WN>;
+    auto kern = wgrad_tr_kernel<BCO, BCI, WM, WN, AFF>;
     const size_t smem = (size_t)2 * WMK * (BCO * 2 + (BCI == 192 ? 512 : BCI * 2)) + (size_t)2 * NT * sizeof(PixInfo);
     static bool configured = false;
     if (!configured) {
@@ -2723,10 +2755,21 @@ static int launch_wgrad_tr(WgradArgs& a, int Cout, int blocks_per_cu, const char
     return check_launch(name);
 }
 
+bool conv_mfma_wgrad_affine_ok(const ConvP& p) {
+    const long limit = 0x7ff00000L;
+    const int pitch = p.pix_pitch();
+    return p.rows_out() * p.Cout * 2 < limit && (p.rows_in() * (long)pitch + p.Cin + (long)(p.pad * p.W + p.pad) * pitch) * 2 < limit &&
+           p.Cin % 64 == 0 && p.Cout == 64 && p.K() % 256 == 0 && pitch != p.Cin;
+}
+
 int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, bool packed,
-                    hipStream_t s) {
+                    hipStream_t s, const bf16_t* affine_y, const float* affine_coef) {
     WgradArgs a;
     a.x = x; a.dy = dy; a.dw = dw; a.cin_real = cin_real;
+    a.ay = affine_y; a.aff = affine_coef;
+    if ((affine_y != nullptr) != (affine_coef != nullptr)) return fail(TSM_ERR_NULLPTR, "wgrad: the affine form needs both its operands");
+    if (affine_y && !(conv_mfma_wgrad_affine_ok(p) && cin_real == p.Cin))
+        return fail(TSM_ERR_UNSUPPORTED, "wgrad: this layer's kernel cannot form dy while loading");
     if (packed) {   // [Cout][taps][p.Cin]: consecutive lanes (channels) hit consecutive addresses
         a.so = (long)p.taps() * p.Cin; a.si = 1; a.st = p.Cin;
     } else {        // ABI order [Cout][cin_real][taps]
@@ -2755,12 +2798,14 @@ int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw
             if (p.Cout % 256 == 0) return launch_wgrad_tr<256, 64, 4, 1>(a, p.Cout, 1, "wgrad_tr_256x64", s);
             if (p.Cout % 128 == 0 && p.Cin % 128 == 0) return launch_wgrad_tr<128, 128, 2, 2>(a, p.Cout, 2, "wgrad_tr_128x128", s);
             // (a column tile may span several taps: 64 input channels x 4 taps fill the 256 columns too)
+            if (affine_y) return launch_wgrad_tr<64, 256, 1, 4, true>(a, p.Cout, 1, "wgrad_tr_64x256", s);
             if (a.K % 256 == 0 && (p.Cin % 256 == 0 || a.pitch != p.Cin)) return launch_wgrad_tr<64, 256, 1, 4>(a, p.Cout, 1, "wgrad_tr_64x256", s);
             if (p.taps() == 1) return launch_wgrad_tr<64, 64, 2, 2>(a, p.Cout, 4, "wgrad_tr_64x64", s);
             // 64 input channels and several taps: a column tile of three taps shares the dy tile among them
             if (a.K % 192 == 0) return launch_wgrad_tr<64, 192, 2, 2>(a, p.Cout, 1, "wgrad_tr_64x192", s);
         }
     }
+    if (affine_y) return fail(TSM_ERR_UNSUPPORTED, "wgrad: the affine form needs the transposing-read kernels");
     if (a.pitch != p.Cin) return fail(TSM_ERR_UNSUPPORTED, "wgrad: a pixel pitch other than the channel count needs the transposing-read kernels");
     // tiles: 128x128 for wide outputs; for <= 64 output channels a 64x192 tile when K is long enough (the
     // transposed dy tile is then shared by three times as many columns); 64x64 otherwise

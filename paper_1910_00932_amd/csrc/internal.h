@@ -145,7 +145,12 @@ int conv_mfma_dgrad(const ConvP& p, const bf16_t* dy, const bf16_t* wd, bf16_t* 
 // dw fp32, accumulated with atomics: zero it first (or keep what is there to accumulate).
 // packed: [Cout][taps][p.Cin] (contiguous atomics, the fast order when taps > 1);
 // otherwise the ABI order [Cout][cin_real][taps].  Channels >= cin_real are padding and are not written.
+// affine_y / affine_coef (both or neither; only where conv_mfma_wgrad_affine_ok(p)): `dy` then holds dz, the gradient
+// in front of a BatchNorm backward, and the kernel forms dy = a*dz + b*affine_y + c per output channel while loading
+// (coefficients [3][Cout] from bn_bwd_coeffs, result rounded to bf16 as bn_bwd_apply would store it): for a layer
+// whose dy nothing else reads, that pass and its tensor disappear.
+bool conv_mfma_wgrad_affine_ok(const ConvP& p);
 int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, bool packed,
-                    hipStream_t s);
+                    hipStream_t s, const bf16_t* affine_y = nullptr, const float* affine_coef = nullptr);
 
 }  // namespace tsm

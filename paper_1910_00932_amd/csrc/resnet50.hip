@@ -1152,11 +1152,14 @@ static int r50_step(const tsm_r50_desc* d, const void* clips, const int32_t* lab
             LAUNCH_CHECK("stem_pool_bwd");
         }
         RUN(bn_bwd_coeffs(part0, nb0b, rows0, 64, bn0.mean, bn0.rstd, P("bn1.g"), coef0, G("bn1.g"), G("bn1.b"), s));
-        RUN(bn_bwd_apply(dtype, da0, y0, stem.rows_out(), 64, coef0, da0, s));
+        // nothing but the weight gradient reads the stem's dy: on the bf16 path its loader forms it from dz and y0
+        const bool affine = bf && conv_mfma_wgrad_affine_ok(stem);
+        if (!affine) RUN(bn_bwd_apply(dtype, da0, y0, stem.rows_out(), 64, coef0, da0, s));
         // the gradient buffer was zeroed at the start of the step; both kernels add into it
         if (bf) {
             RUN(fill_zero(dwp0, (size_t)64 * 256 * sizeof(float), s));
-            RUN(conv_mfma_wgrad(stem, (const bf16_t*)x0, (const bf16_t*)da0, dwp0, 64, true, s));
+            RUN(conv_mfma_wgrad(stem, (const bf16_t*)x0, (const bf16_t*)da0, dwp0, 64, true, s,
+                                affine ? (const bf16_t*)y0 : nullptr, affine ? coef0 : nullptr));
             if (!dry) {
                 stem_unpack_kernel<<<dim3(64), dim3(256), 0, s>>>(dwp0, G("conv1.w"));
                 LAUNCH_CHECK("stem_unpack");
