@@ -138,7 +138,8 @@ def class_bytes(F, size, epilogue_reads=True):
             elif name.endswith(".c1") and blk == 1:
                 extra += x_b / 16.0    # the block below has a projection shortcut: only its ReLU mask rides along
             add(dgrad_class(name, rin, cin, rout, cout, taps), dx_b + y_b + (extra if epilogue_reads else 0.0))
-        add("wgrad_tr_64x256" if stem else wgrad_class(cout, cin, taps), x_b + y_b)
+        # (the stem's weight gradient forms its dy while loading: it reads dz and the BatchNorm input instead)
+        add("wgrad_tr_64x256" if stem else wgrad_class(cout, cin, taps), x_b + (2.0 if stem else 1.0) * y_b)
     return byt
 
 
