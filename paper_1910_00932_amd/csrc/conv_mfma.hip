@@ -1927,6 +1927,157 @@ static int setup_classes(IgemmArgs& a, bool dgrad, int BM) {
     return a.mt0[a.ncls];
 }
 
+// ---------------------------------------------------------------------------------
+// 1x1, stride 1, 64 -> 256 channels, forward with the statistics epilogue (the last convolution and the projection of
+// the first stage's blocks): four bytes written per byte read, one K step.  In the general kernel a tile of such a layer
+// is all prologue, barriers and epilogue; here nothing is shared between wavefronts but the weights:
+//
+//  * the weights (32 KB) sit in LDS for the life of the block, swizzled as in igemm_ring_kernel;
+//  * a wavefront takes 32 pixels at a time: its A operand comes straight from memory in fragment order (lane = pixel
+//    lane % 32, K vector 2*ks + lane / 32: the 32 rows of 128 bytes are one contiguous 4 KB piece), the next pass's
+//    fragments are requested before this pass is multiplied;
+//  * 128 output channels at a time go through a staging tile that belongs to the wavefront alone (no block barrier
+//    anywhere in the loop) and leave as 16-byte stores, 256 contiguous bytes per pixel row; the statistics are taken
+//    from the staged values, eight fixed channels per lane, reduced once at the end of the block.
+static constexpr int PW_LDC = 128 + 8;                        // staging pitch (elements)
+static constexpr int PW_W_BYTES = 256 * 128;
+static constexpr int PW_CST_BYTES = 32 * PW_LDC * 2;          // per wavefront
+static constexpr int PW_PART_BYTES = 2 * 8 * 256 * 4;
+static constexpr int PW_SMEM = PW_W_BYTES + 8 * PW_CST_BYTES + PW_PART_BYTES;
+static_assert(PW_SMEM <= 160 * 1024 && PW_CST_BYTES % 16 == 0, "LDS budget / alignment");
+
+template <bool STREAM>
+__global__ void __launch_bounds__(512) pw64x256_kernel(IgemmArgs a) {
+    constexpr int LDC = PW_LDC;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* s_w = smem;                                                       // [256][8 positions of 16 bytes]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    bf16_t* Cst = (bf16_t*)(smem + PW_W_BYTES + wave * PW_CST_BYTES);                // [32][LDC], this wavefront's
+    float* s_part = (float*)(smem + PW_W_BYTES + 8 * PW_CST_BYTES);                  // [2 stats][8 wavefronts][256]
+    const int r = lane & 31, hi = lane >> 5;
+    const long M = (long)a.F * a.Hd * a.Wd;
+    const bool do_stats = a.stats != nullptr;
+
+    {
+        const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.wp, (uint32_t)(256 * 64 * 2));
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int q = tid + q4 * 512;                          // piece: weight row n, position pos
+            const int n = q >> 3, pos = q & 7, kv = pos ^ ((n >> 1) & 7);
+            *(u32x4*)(s_w + q * 16) = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, n * 128 + kv * 16, 0, 0);
+        }
+    }
+    __syncthreads();
+
+    int b_rd[4];                                                   // fragment of weight rows 32*j + r, step ks
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) b_rd[ks] = r * 128 + (((2 * ks + hi) ^ ((r >> 1) & 7)) << 4);
+    const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(a.src, (uint32_t)(M * 128));
+    const long nslabs = (M + 31) / 32;
+    const long nwaves = (long)gridDim.x * 8;
+    auto load_a = [&](long sl, bf16x8* fr) {
+        const long row = sl * 32 + r;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, row < M ? (int)(row * 128 + (2 * ks + hi) * 16) : (int)OOB_OFFSET, 0, 0);
+            fr[ks] = __builtin_bit_cast(bf16x8, v);
+        }
+    };
+    float f1[2][8], f2[2][8];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) f1[h][q] = f2[h][q] = 0.f;
+    const int vcol = lane & 15, row0 = lane >> 4;                  // store loop: piece lane + 64*t is row row0 + 4*t, vector vcol
+
+    long slab = (long)blockIdx.x * 8 + wave;
+    bf16x8 cur[4], nxt[4];
+    if (slab < nslabs) load_a(slab, cur);
+    for (; slab < nslabs; slab += nwaves) {
+        if (slab + nwaves < nslabs) load_a(slab + nwaves, nxt);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            f32x16 acc[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bf16x8 bfrag = *(const bf16x8*)(s_w + (h * 4 + j) * 32 * 128 + b_rd[ks]);
+                    // operands swapped as in igemm_ring_kernel: the result block is [channel][pixel]
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, cur[ks], acc[j], 0, 0, 0);
+                }
+            // lane: pixel r, channels 32*j + 8*q + 4*hi + {0..3}
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                bf16_t* dstp = Cst + r * LDC + j * 32 + 4 * hi;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint2 w;
+                    w.x = pack_bf16x2(acc[j][4 * q], acc[j][4 * q + 1]);
+                    w.y = pack_bf16x2(acc[j][4 * q + 2], acc[j][4 * q + 3]);
+                    *(uint2*)(dstp + 8 * q) = w;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();                       // (LDS serves a wavefront's accesses in order)
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int row = row0 + 4 * t;
+                const long grow = slab * 32 + row;
+                const u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
+                if (grow < M) {
+                    if (do_stats) {   // statistics of the values as stored
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float lo = __uint_as_float(v[e] << 16), hv = __uint_as_float(v[e] & 0xffff0000u);
+                            f1[h][2 * e] += lo;
+                            f1[h][2 * e + 1] += hv;
+                            f2[h][2 * e] = fmaf(lo, lo, f2[h][2 * e]);
+                            f2[h][2 * e + 1] = fmaf(hv, hv, f2[h][2 * e + 1]);
+                        }
+                    }
+                    u32x4* q = (u32x4*)(a.dst + grow * 256 + h * 128 + vcol * 8);
+                    if (STREAM) __builtin_nontemporal_store(v, q);
+                    else *q = v;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) cur[ks] = nxt[ks];
+    }
+    if (do_stats) {
+        // lanes 16 apart hold the same columns: fold them, then one slot per wavefront, fixed order over the slots
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                f1[h][q] += __shfl_xor(f1[h][q], 16);
+                f2[h][q] += __shfl_xor(f2[h][q], 16);
+                f1[h][q] += __shfl_xor(f1[h][q], 32);
+                f2[h][q] += __shfl_xor(f2[h][q], 32);
+            }
+        if (lane < 16) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    s_part[wave * 256 + h * 128 + lane * 8 + q] = f1[h][q];
+                    s_part[(8 + wave) * 256 + h * 128 + lane * 8 + q] = f2[h][q];
+                }
+        }
+        __syncthreads();
+        const int stat = tid >> 8, col = tid & 255;
+        float v = 0.f;
+#pragma unroll
+        for (int sl = 0; sl < 8; ++sl) v += s_part[(stat * 8 + sl) * 256 + col];
+        a.stats[(size_t)blockIdx.x * 2 * 256 + stat * 256 + col] = v;
+    }
+}
+
 // Persistent grid: `per_cu` blocks per CU (a multiple of 8 blocks so that a block stays on one XCD), capped
 // by the number of tile ids, which enumerate (group of 8 M tiles) x N tiles x (xcd).
 static int igemm_grid(int mtiles, int Cd, int BN, int per_cu) {
@@ -2132,11 +2283,44 @@ static int launch_stem_s(IgemmArgs& a, hipStream_t s) {
     return check_launch("igemm_fwd_stem");
 }
 
+// The 64 -> 256 channel 1x1 forward kernel takes its layers when the general kernel would run them with 256-row tiles
+// (the two then launch the same number of blocks, which callers size the statistics rows by) and every wavefront of the
+// grid has at least two passes.  TSM_PW_KERNEL=0 leaves these layers to the general kernel, TSM_PW_MIN_ROWS=<n> moves
+// the threshold (both read at every call: tests and comparisons set them).
+static bool pw64x256_eligible(const IgemmArgs& a) {
+    const char* e = getenv("TSM_PW_KERNEL");
+    if (e && e[0] == '0') return false;
+    const char* t = getenv("TSM_PW_MIN_ROWS");
+    const long min_rows = t ? atol(t) : 2L * 32 * 8 * num_cu();
+    const long rows = (long)a.F * a.Hd * a.Wd;
+    return a.Cs == 64 && a.pitch == 64 && a.Cd == 256 && a.KT == 1 && a.KH == 1 && a.KW == 1 && a.stride == 1 && a.padh == 0 &&
+           a.padw == 0 && a.fold == 0 && a.addend == nullptr && a.ep_scale == nullptr && a.Hs == a.Hd && a.Ws == a.Wd &&
+           rows * 128 < 0x7ff00000L && ring_eligible(64, rows * 64 + 64, 256L * 64, false) && ring_rows(rows, 256) == 256 &&
+           rows >= min_rows;
+}
+
+template <bool STREAM>
+static int launch_pw64x256(IgemmArgs& a, hipStream_t s) {
+    auto kern = pw64x256_kernel<STREAM>;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return fail(TSM_ERR_LAUNCH, "pw64x256: cannot raise dynamic LDS limit");
+        configured = true;
+    }
+    const long rows = (long)a.F * a.Hd * a.Wd;
+    const int grid = igemm_grid((int)((rows + 255) / 256), 256, 128, 1);      // as the general kernel with 256 x 128 tiles
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), PW_SMEM, s, a);
+    return check_launch("igemm_fwd_pw64");
+}
+
 template <bool DGRAD>
 static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     const long rows = (long)a.F * a.Hd * a.Wd;
     if (rows == 0) return TSM_OK;
     if (c64_eligible(a)) return launch_c64<DGRAD>(a, s);
+    if (!DGRAD && pw64x256_eligible(a))
+        return rows * a.Cd * 2 > (64L << 20) ? launch_pw64x256<true>(a, s) : launch_pw64x256<false>(a, s);
     if (!DGRAD && stem_eligible(a))
         return rows * a.Cd * 2 > (64L << 20) ? launch_stem_s<true>(a, s) : launch_stem_s<false>(a, s);
     if (ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K, a.pitch != a.Cs)) {

@@ -133,6 +133,21 @@ def test_conv3x3_c64_kernel_every_element(case, monkeypatch):
     assert "igemm_fwd_c64" in classes and "igemm_dgrad_c64" in classes, sorted(classes)
 
 
+@pytest.mark.parametrize("case", [
+    (2, 4, 64, 57, 57, 256, 1, 1, 0, 0),     # 25992 pixels: a ragged last pass of 8 pixels
+    (3, 8, 64, 33, 35, 256, 1, 1, 0, 0),     # 27720 pixels, H != W; some wavefronts get one pass more than others
+])
+def test_pointwise_64_to_256_kernel_every_element(case, monkeypatch):
+    """The 64 -> 256 channel 1x1 forward kernel (statistics epilogue; one wavefront per 32 pixels, nothing shared but
+    the weights) on sizes the oracle covers element by element; the library would leave so few pixels to the general
+    kernel, the threshold is moved.  (Data and weight gradient of the case run on the general kernels as usual.)"""
+    monkeypatch.setenv("TSM_PW_MIN_ROWS", "1")
+    B.tsm_profile_begin()
+    _run(case, "bf16", "nthwc")
+    classes = B.tsm_profile_end()
+    assert "igemm_fwd_pw64" in classes, sorted(classes)
+
+
 def test_conv3x3_c64_kernel_where_the_library_picks_it():
     """112 frames of 56x56 (1372 tiles: the default dispatch takes the 64-channel kernel) against the oracle on the
     first, a middle and the last frame; without shift the frames are independent."""
