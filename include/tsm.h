@@ -39,8 +39,10 @@
  *    at every call) keeps the inference paths on one kernel per convolution and
  *    TSM_FUSED_TAIL_MIN_TILES=<n> replaces the number of 256-pixel tiles from
  *    which the two-convolution kernel is chosen (default: three per four
- *    compute units); TSM_PW_KERNEL=0 (read at every call) leaves the 64 -> 256
- *    channel 1x1 forward layers to the general kernel and TSM_PW_MIN_ROWS=<n>
+ *    compute units); TSM_PW_KERNEL=0 (read at every call) leaves the short-K 1x1
+ *    layers that have kernels of their own (64 -> 256 channels forward; the data
+ *    gradient of a block's first convolution in the first two stages) to the
+ *    general kernel and TSM_PW_MIN_ROWS=<n>
  *    replaces the number of pixels from which their own kernel is chosen (default:
  *    two passes of 32 pixels per wavefront of the grid); TSM_MASK_BITS=0 (read once per process) makes the train
  *    step's data gradients take the ReLU mask of a block output from the

@@ -2078,6 +2078,227 @@ __global__ void __launch_bounds__(512) pw64x256_kernel(IgemmArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------
+// The same scheme for the data gradient of a block's first convolution where it is short in K and wide in its result
+// (1x1, stride 1, KC = 64 or 128 channels of dy -> 256 or 512 channels of dx): these tiles carry, besides the
+// convolution, three tensors of the result's size through the epilogue -- the shortcut gradient, the BatchNorm input of
+// the block below and the result itself -- so the layer is a stream with a small product attached.  A block holds the
+// weights of 256 result channels (a result of 512 channels is split over pairs of neighbouring blocks, which read the
+// same rows of dy); a wavefront takes 32 pixels at a time, 128 result channels at a time through its own staging tile.
+// The epilogue is the one of igemm_ring_kernel's data gradient, value for value: adjoint shift as a frame offset on the
+// destination row (a lane's eight channels lie in one shift group), zero value for the frame a group leaves empty,
+// shortcut gradient added, mask from the decision bits, BatchNorm-backward sums of the stored values; the operands of
+// a few destination pieces are requested together, the first group ahead of the staging of the accumulators.
+// Partial rows (a.stats, [gridDim.x][2][Cd]): row s of the first gridDim.x / nsplit rows receives the sums of stream s,
+// the others are written as zeros (callers size and sum the rows by the general kernel's grid).
+template <int KC>
+struct PwD {
+    static constexpr int ROWB = KC * 2;                        // bytes per weight row
+    static constexpr int W_BYTES = 256 * ROWB;
+    static constexpr int SMEM = W_BYTES + 8 * PW_CST_BYTES + PW_PART_BYTES;
+};
+static_assert(PwD<128>::SMEM <= 160 * 1024, "LDS budget");
+
+template <int KC, bool STREAM>
+__global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
+    constexpr int LDC = PW_LDC, KS = KC / 16, ROWB = PwD<KC>::ROWB, KV = KC / 8;
+    constexpr int GP = KC == 64 ? 4 : 2;                           // destination pieces requested together (registers)
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* s_w = smem;                                                       // [256][KV positions of 16 bytes]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    bf16_t* Cst = (bf16_t*)(smem + PwD<KC>::W_BYTES + wave * PW_CST_BYTES);          // [32][LDC], this wavefront's
+    float* s_part = (float*)(smem + PwD<KC>::W_BYTES + 8 * PW_CST_BYTES);            // [2 sums][8 wavefronts][256]
+    const int r = lane & 31, hi = lane >> 5;
+    const int hw = a.Hd * a.Wd;
+    const long M = (long)a.F * hw;
+    const int nsplit = a.Cd / 256;
+    const int nb0 = ((int)blockIdx.x % nsplit) * 256;              // first result channel of this block
+    const long stream0 = (long)((int)blockIdx.x / nsplit) * 8 + wave;
+    const long nstreams = (long)((int)gridDim.x / nsplit) * 8;
+    const bool fuse_mask = a.act_bits != nullptr;
+    const bool fuse_bn = fuse_mask && a.ybn != nullptr;
+    // position p of weight row n holds K vector p ^ swz(n): the 16 (or 2 x 8) rows that one quarter-wave reads together
+    // then lie in 16 different 16-byte bank groups
+    auto swz = [](int n) { return KC == 128 ? (n & 15) : ((n >> 1) & 7); };
+
+    {
+        const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.wp + (long)nb0 * KC, (uint32_t)(256 * ROWB));
+#pragma unroll
+        for (int q4 = 0; q4 < 256 * KV / 512; ++q4) {
+            const int q = tid + q4 * 512;                          // piece: weight row n, position pos
+            const int n = q / KV, pos = q % KV, kv = pos ^ swz(n);
+            *(u32x4*)(s_w + q * 16) = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, n * ROWB + kv * 16, 0, 0);
+        }
+    }
+    __syncthreads();
+
+    int b_rd[KS];                                                  // fragment of weight rows 32*j + r, step ks
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) b_rd[ks] = r * ROWB + (((2 * ks + hi) ^ swz(r)) << 4);
+    const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(a.src, (uint32_t)(M * ROWB));
+    const long nslabs = (M + 31) / 32;
+    bf16x8 cur[KS];
+    auto load_a = [&](long sl) {
+        const long row = sl * 32 + r;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, row < M ? (int)(row * ROWB + (2 * ks + hi) * 16) : (int)OOB_OFFSET, 0, 0);
+            cur[ks] = __builtin_bit_cast(bf16x8, v);
+        }
+    };
+    // store loop: piece lane + 64*t of a 32 x 128 half is row row0 + 4*t, vector vcol: a lane's channels never change
+    const int vcol = lane & 15, row0 = lane >> 4;
+    float f1[2][8], f2[2][8], mu[2][8], rs[2][8];
+    int dt[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int c0 = nb0 + h * 128 + vcol * 8;
+        dt[h] = group_dt(c0, a.fold);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            f1[h][q] = f2[h][q] = 0.f;
+            mu[h][q] = fuse_bn ? a.bn_mean[c0 + q] : 0.f;
+            rs[h][q] = fuse_bn ? a.bn_rstd[c0 + q] : 0.f;
+        }
+    }
+    const bf16_t* zero_page = (const bf16_t*)g_zero_page;
+
+    long slab = stream0;
+    if (slab < nslabs) load_a(slab);
+    for (; slab < nslabs; slab += nstreams) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int col = nb0 + h * 128 + vcol * 8;
+            f32x16 acc[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bf16x8 bfrag = *(const bf16x8*)(s_w + (h * 4 + j) * 32 * ROWB + b_rd[ks]);
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, cur[ks], acc[j], 0, 0, 0);
+                }
+            // the next pass's fragments: this pass has no further use for the registers
+            if (h == 1 && slab + nstreams < nslabs) load_a(slab + nstreams);
+            // value (+ addend) -> optional mask and BatchNorm sums -> store, as igemm_ring_kernel's data gradient
+            auto finish = [&](int mr, u32x4 o, const u32x4& ad, uint32_t bits, const u32x4& yy) {
+                if (a.addend) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float lo = __uint_as_float(o[q] << 16) + __uint_as_float(ad[q] << 16);
+                        const float hv = __uint_as_float(o[q] & 0xffff0000u) + __uint_as_float(ad[q] & 0xffff0000u);
+                        o[q] = pack_bf16x2(lo, hv);
+                    }
+                }
+                if (fuse_mask) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const bool plo = ((bits >> (2 * q)) & 1u) != 0, phi = ((bits >> (2 * q + 1)) & 1u) != 0;
+                        const float dlo = plo ? __uint_as_float(o[q] << 16) : 0.f;
+                        const float dhi = phi ? __uint_as_float(o[q] & 0xffff0000u) : 0.f;
+                        o[q] = (plo ? o[q] & 0xffffu : 0u) | (phi ? o[q] & 0xffff0000u : 0u);
+                        f1[h][2 * q] += dlo;
+                        f1[h][2 * q + 1] += dhi;
+                        f2[h][2 * q] = fmaf(dlo, (__uint_as_float(yy[q] << 16) - mu[h][2 * q]) * rs[h][2 * q], f2[h][2 * q]);
+                        f2[h][2 * q + 1] = fmaf(dhi, (__uint_as_float(yy[q] & 0xffff0000u) - mu[h][2 * q + 1]) * rs[h][2 * q + 1], f2[h][2 * q + 1]);
+                    }
+                }
+                u32x4* qd = (u32x4*)(a.dst + (long)mr * a.Cd + col);
+                if (STREAM) __builtin_nontemporal_store(o, qd);
+                else *qd = o;
+            };
+            // lane: pixel r, channels 32*j + 8*q + 4*hi + {0..3}
+#pragma unroll
+            for (int g = 0; g < 8 / GP; ++g) {                     // groups of GP pieces
+                int mr[GP], mz[GP];
+                u32x4 ad[GP], yy[GP];
+                uint32_t bt[GP];
+#pragma unroll
+                for (int t = 0; t < GP; ++t) {
+                    const long grow = slab * 32 + row0 + 4 * (GP * g + t);
+                    const bool live = grow < M;
+                    const int tt = live ? (int)((grow / hw) % a.T) : 0;
+                    const bool in_clip = tt + dt[h] >= 0 && tt + dt[h] < a.T;
+                    mr[t] = live && in_clip ? (int)grow + dt[h] * hw : -1;
+                    mz[t] = live && ((dt[h] == 1 && tt == 0) || (dt[h] == -1 && tt == a.T - 1)) ? (int)grow : -1;
+                    // loads without a branch around them (rows that are not stored read the zero page)
+                    const long e = (long)mr[t] * a.Cd + col;
+                    const bool ok = mr[t] >= 0;
+                    ad[t] = *(const u32x4*)((ok && a.addend) ? a.addend + e : zero_page);
+                    bt[t] = *((ok && fuse_mask) ? a.act_bits + e / 8 : (const uint8_t*)zero_page);
+                    yy[t] = *(const u32x4*)((ok && fuse_bn) ? a.ybn + e : zero_page);
+                }
+                if (g == 0) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        bf16_t* dstp = Cst + r * LDC + j * 32 + 4 * hi;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            uint2 w;
+                            w.x = pack_bf16x2(acc[j][4 * q], acc[j][4 * q + 1]);
+                            w.y = pack_bf16x2(acc[j][4 * q + 2], acc[j][4 * q + 3]);
+                            *(uint2*)(dstp + 8 * q) = w;
+                        }
+                    }
+                    __builtin_amdgcn_wave_barrier();               // (LDS serves a wavefront's accesses in order)
+                }
+#pragma unroll
+                for (int t = 0; t < GP; ++t) {
+                    const int row = row0 + 4 * (GP * g + t);
+                    const u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
+                    if (mr[t] >= 0) finish(mr[t], v, ad[t], bt[t], yy[t]);
+                }
+#pragma unroll
+                for (int t = 0; t < GP; ++t) {                     // the frame that receives nothing from inside the clip
+                    if (mz[t] < 0) continue;
+                    const long e = (long)mz[t] * a.Cd + col;
+                    u32x4 zad = u32x4{0u, 0u, 0u, 0u}, zyy = zad;
+                    uint32_t zbt = 0;
+                    if (a.addend) zad = *(const u32x4*)(a.addend + e);
+                    if (fuse_mask) zbt = a.act_bits[e / 8];
+                    if (fuse_bn) zyy = *(const u32x4*)(a.ybn + e);
+                    finish(mz[t], u32x4{0u, 0u, 0u, 0u}, zad, zbt, zyy);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    if (a.stats) {
+        // lanes 16 apart hold the same columns: fold them, then one slot per wavefront, fixed order over the slots
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                f1[h][q] += __shfl_xor(f1[h][q], 16);
+                f2[h][q] += __shfl_xor(f2[h][q], 16);
+                f1[h][q] += __shfl_xor(f1[h][q], 32);
+                f2[h][q] += __shfl_xor(f2[h][q], 32);
+            }
+        if (lane < 16) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    s_part[wave * 256 + h * 128 + lane * 8 + q] = f1[h][q];
+                    s_part[(8 + wave) * 256 + h * 128 + lane * 8 + q] = f2[h][q];
+                }
+        }
+        __syncthreads();
+        const int stat = tid >> 8, c = tid & 255;
+        float v = 0.f;
+#pragma unroll
+        for (int sl = 0; sl < 8; ++sl) v += s_part[(stat * 8 + sl) * 256 + c];
+        const int rows_used = (int)gridDim.x / nsplit, row_s = (int)blockIdx.x / nsplit;
+        a.stats[((size_t)row_s * 2 + stat) * a.Cd + nb0 + c] = v;
+        // rows beyond the streams: zeros (block b clears the part of row rows_used + b / nsplit * ... it owns)
+        for (int rz = rows_used + row_s; rz < (int)gridDim.x; rz += rows_used)
+            a.stats[((size_t)rz * 2 + stat) * a.Cd + nb0 + c] = 0.f;
+    }
+}
+
 // Persistent grid: `per_cu` blocks per CU (a multiple of 8 blocks so that a block stays on one XCD), capped
 // by the number of tile ids, which enumerate (group of 8 M tiles) x N tiles x (xcd).
 static int igemm_grid(int mtiles, int Cd, int BN, int per_cu) {
@@ -2314,11 +2535,49 @@ static int launch_pw64x256(IgemmArgs& a, hipStream_t s) {
     return check_launch("igemm_fwd_pw64");
 }
 
+// The short-K, wide-result 1x1 data-gradient kernel takes its layers under the same conditions as the forward kernel
+// above; where the epilogue needs a ReLU mask, only with the decision bits (see DgradFuse::act_bits).
+static bool pw_dgrad_eligible(const IgemmArgs& a) {
+    const char* e = getenv("TSM_PW_KERNEL");
+    if (e && e[0] == '0') return false;
+    const char* t = getenv("TSM_PW_MIN_ROWS");
+    const long min_rows = t ? atol(t) : 2L * 32 * 8 * num_cu();
+    const long rows = (long)a.F * a.Hd * a.Wd;
+    if (!((a.Cs == 64 || a.Cs == 128) && a.pitch == a.Cs && (a.Cd == 256 || a.Cd == 512) && a.KT == 1 && a.KH == 1 && a.KW == 1 &&
+          a.stride == 1 && a.padh == 0 && a.padw == 0 && a.Hs == a.Hd && a.Ws == a.Wd && a.add_stride == 1 && a.fold % 8 == 0))
+        return false;
+    if (a.act != nullptr && a.act_bits == nullptr) return false;      // a mask that only the activation can give
+    if (a.ybn != nullptr && a.stats == nullptr) return false;
+    return rows * a.Cs * 2 < 0x7ff00000L && ring_eligible(a.Cs, rows * a.Cs + a.Cs, (long)a.Cd * a.Cs, false) &&
+           ring_rows(rows, a.Cd) == 256 && rows >= min_rows;
+}
+
+template <int KC, bool STREAM>
+static int launch_pw_dgrad(IgemmArgs& a, hipStream_t s) {
+    auto kern = pw_dgrad_kernel<KC, STREAM>;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return fail(TSM_ERR_LAUNCH, "pw_dgrad: cannot raise dynamic LDS limit");
+        configured = true;
+    }
+    const long rows = (long)a.F * a.Hd * a.Wd;
+    const int grid = igemm_grid((int)((rows + 255) / 256), a.Cd, 128, 1);      // as the general kernel with 256 x 128 tiles
+    if (grid % (a.Cd / 256) != 0) return fail(TSM_ERR_LAUNCH, "pw_dgrad: grid does not split over the column halves");
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), PwD<KC>::SMEM, s, a);
+    return check_launch("igemm_dgrad_pw");
+}
+
 template <bool DGRAD>
 static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     const long rows = (long)a.F * a.Hd * a.Wd;
     if (rows == 0) return TSM_OK;
     if (c64_eligible(a)) return launch_c64<DGRAD>(a, s);
+    if (DGRAD && pw_dgrad_eligible(a)) {
+        const bool st = rows * a.Cd * 2 > (64L << 20);
+        if (a.Cs == 64) return st ? launch_pw_dgrad<64, true>(a, s) : launch_pw_dgrad<64, false>(a, s);
+        return st ? launch_pw_dgrad<128, true>(a, s) : launch_pw_dgrad<128, false>(a, s);
+    }
     if (!DGRAD && pw64x256_eligible(a))
         return rows * a.Cd * 2 > (64L << 20) ? launch_pw64x256<true>(a, s) : launch_pw64x256<false>(a, s);
     if (!DGRAD && stem_eligible(a))

@@ -148,6 +148,24 @@ def test_pointwise_64_to_256_kernel_every_element(case, monkeypatch):
     assert "igemm_fwd_pw64" in classes, sorted(classes)
 
 
+@pytest.mark.parametrize("case", [
+    (2, 4, 256, 57, 57, 64, 1, 1, 0, 8),     # 64 -> 256 channels of dx, shifted; 25992 pixels: a ragged last pass
+    (3, 8, 256, 33, 35, 64, 1, 1, 0, 8),     # H != W, clips of 8 frames: both clip ends inside the tensor
+    (2, 8, 512, 28, 28, 128, 1, 1, 0, 8),    # 128 -> 512 channels: the result is split over pairs of blocks
+    (2, 8, 256, 40, 40, 128, 1, 1, 0, 8),    # 128 -> 256 channels
+    (2, 8, 256, 57, 57, 64, 1, 1, 0, 0),     # no shift
+])
+def test_pointwise_data_gradient_kernel_every_element(case, monkeypatch):
+    """The short-K, wide-result 1x1 data-gradient kernel (adjoint shift on the store, zero rows at the clip ends) on
+    sizes the oracle covers element by element; the threshold is moved as above.  Its fused epilogue (shortcut
+    gradient, mask bits, BatchNorm sums) runs inside the block and step tests."""
+    monkeypatch.setenv("TSM_PW_MIN_ROWS", "1")
+    B.tsm_profile_begin()
+    _run(case, "bf16", "nthwc")
+    classes = B.tsm_profile_end()
+    assert "igemm_dgrad_pw" in classes, sorted(classes)
+
+
 def test_conv3x3_c64_kernel_where_the_library_picks_it():
     """112 frames of 56x56 (1372 tiles: the default dispatch takes the 64-channel kernel) against the oracle on the
     first, a middle and the last frame; without shift the frames are independent."""

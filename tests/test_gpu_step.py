@@ -228,9 +228,10 @@ def test_step_bf16_full_frame_against_oracle(N, dispatch, monkeypatch):
     (the five named in the table printed below among them) and the updated weights.
 
     `dispatch`: "default" is what the library picks at this batch (the general kernels); "special" moves the
-    tile-count threshold so that the 64-channel 3x3 kernel and the space-to-depth stem kernel -- which the
-    benchmark's 64 clips get -- run inside this comparison, together with the data-gradient epilogues fused across
-    blocks (those run in either mode).
+    size thresholds so that the 64-channel 3x3 kernel, the space-to-depth stem kernel and the two 1x1 kernels with
+    one wavefront per 32 pixels (64 -> 256 forward; the short-K data gradient with its whole fused epilogue) -- which
+    the benchmark's 64 clips get -- run inside this comparison, together with the data-gradient epilogues fused
+    across blocks (those run in either mode).
 
     Oracle passes.  (a) bf16 storage emulated at the points the library stores tensors and (c) plain fp64, each
     taking its own ReLU / max-pool decisions; (a') and (c'): the same two with the decisions of the HIP step imposed
@@ -249,11 +250,12 @@ def test_step_bf16_full_frame_against_oracle(N, dispatch, monkeypatch):
     gradients of the two decision-imposed passes differ by tens of per cent."""
     if dispatch == "special":
         monkeypatch.setenv("TSM_CONV3X3_C64_MIN_TILES", "1")
+        monkeypatch.setenv("TSM_PW_MIN_ROWS", "1")
     T, S, lr = 8, 224, 0.00125
     B.tsm_profile_begin()
     r = run_step(N, T, S, "bf16", lr=lr, g3=G3)
     classes = B.tsm_profile_end()
-    special = {"igemm_fwd_c64", "igemm_dgrad_c64", "igemm_fwd_stem"}
+    special = {"igemm_fwd_c64", "igemm_dgrad_c64", "igemm_fwd_stem", "igemm_fwd_pw64", "igemm_dgrad_pw"}
     assert (special <= set(classes)) == (dispatch == "special"), sorted(classes)
     P = O.unflatten_params(r["flat"].astype(np.float64))
     V = {k: np.zeros_like(v) for k, v in P.items()}
@@ -304,7 +306,8 @@ def test_step_bf16_64_clips_as_the_benchmark_times_it():
     B.tsm_profile_begin()      # (per-launch profiling keeps the step on one stream)
     r1 = run_step(64, T, S, "bf16", lr=lr, g3=G3, clips=c64, labels=l64)
     classes = set(B.tsm_profile_end())
-    assert {"igemm_fwd_c64", "igemm_dgrad_c64", "igemm_fwd_stem", "igemm_dgrad_256x128", "wgrad_tr_256x128"} <= classes, sorted(classes)
+    assert {"igemm_fwd_c64", "igemm_dgrad_c64", "igemm_fwd_stem", "igemm_fwd_pw64", "igemm_dgrad_pw", "igemm_dgrad_256x128",
+            "wgrad_tr_256x128"} <= classes, sorted(classes)
     one_stream = {k: r1[k] for k in ("loss", "logits", "grads")}
     del r1
     torch.cuda.empty_cache()
