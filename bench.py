@@ -53,8 +53,8 @@ def igemm_class(kind, cd, cs, rows, taps=1, stride=1):
         r = "r128" if tiles256 * 4 < 256 * 3 else "256"
         if cs == 64 and cd == 64 and taps == 9 and stride == 1 and -(-rows // 256) >= 5 * 256:
             return "igemm_%s_c64" % kind      # the 64 -> 64 channel 3x3 kernel (five rounds of tiles or more)
-        if kind == "fwd" and cs == 64 and cd == 256 and taps == 1 and stride == 1 and r == "256" and rows >= 2 * 32 * 8 * 256:
-            return "igemm_fwd_pw64"           # the 64 -> 256 channel 1x1 forward kernel
+        if kind == "fwd" and cs in (64, 128) and cd in (256, 512) and taps == 1 and stride == 1 and r == "256" and rows >= 2 * 32 * 8 * 256:
+            return "igemm_fwd_pw"             # the short-K 1x1 forward kernel
         # 64 columns per tile for narrow outputs, and where even 128x128 tiles leave a quarter of the CUs idle
         narrow = cd <= 64 or (r == "r128" and -(-rows // 128) * -(-cd // 128) * 4 < 256 * 3)
         return "igemm_%s_%sx%s" % (kind, r, "64" if narrow else "128")

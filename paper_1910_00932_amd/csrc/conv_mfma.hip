@@ -1928,58 +1928,73 @@ static int setup_classes(IgemmArgs& a, bool dgrad, int BM) {
 }
 
 // ---------------------------------------------------------------------------------
-// 1x1, stride 1, 64 -> 256 channels, forward with the statistics epilogue (the last convolution and the projection of
-// the first stage's blocks): four bytes written per byte read, one K step.  In the general kernel a tile of such a layer
-// is all prologue, barriers and epilogue; here nothing is shared between wavefronts but the weights:
+// 1x1, stride 1, KC = 64 or 128 -> 256 or 512 channels, forward with the statistics epilogue (the last convolution of
+// the first two stages' blocks, the first stage's projection): four bytes written per byte read, one or two K steps.
+// In the general kernel a tile of such a layer is all prologue, barriers and epilogue; here nothing is shared between
+// wavefronts but the weights:
 //
-//  * the weights (32 KB) sit in LDS for the life of the block, swizzled as in igemm_ring_kernel;
+//  * the weights of 256 result channels (32 or 64 KB) sit in LDS for the life of the block, swizzled; a result of 512
+//    channels is split over pairs of neighbouring blocks, which read the same rows of the input;
 //  * a wavefront takes 32 pixels at a time: its A operand comes straight from memory in fragment order (lane = pixel
-//    lane % 32, K vector 2*ks + lane / 32: the 32 rows of 128 bytes are one contiguous 4 KB piece), the next pass's
+//    lane % 32, K vector 2*ks + lane / 32: the 32 rows of 128 or 256 bytes are one contiguous piece), the next pass's
 //    fragments are requested before this pass is multiplied;
 //  * 128 output channels at a time go through a staging tile that belongs to the wavefront alone (no block barrier
 //    anywhere in the loop) and leave as 16-byte stores, 256 contiguous bytes per pixel row; the statistics are taken
 //    from the staged values, eight fixed channels per lane, reduced once at the end of the block.
+// Partial rows (a.stats, [gridDim.x][2][Cd]): row s of the first gridDim.x / nsplit rows receives the sums of stream s,
+// the others are written as zeros (callers size and sum the rows by the general kernel's grid).
 static constexpr int PW_LDC = 128 + 8;                        // staging pitch (elements)
-static constexpr int PW_W_BYTES = 256 * 128;
 static constexpr int PW_CST_BYTES = 32 * PW_LDC * 2;          // per wavefront
 static constexpr int PW_PART_BYTES = 2 * 8 * 256 * 4;
-static constexpr int PW_SMEM = PW_W_BYTES + 8 * PW_CST_BYTES + PW_PART_BYTES;
-static_assert(PW_SMEM <= 160 * 1024 && PW_CST_BYTES % 16 == 0, "LDS budget / alignment");
+static_assert(PW_CST_BYTES % 16 == 0, "alignment");
+template <int KC>
+struct PwD {
+    static constexpr int ROWB = KC * 2;                        // bytes per weight row
+    static constexpr int W_BYTES = 256 * ROWB;
+    static constexpr int SMEM = W_BYTES + 8 * PW_CST_BYTES + PW_PART_BYTES;
+};
+static_assert(PwD<128>::SMEM <= 160 * 1024, "LDS budget");
 
-template <bool STREAM>
-__global__ void __launch_bounds__(512) pw64x256_kernel(IgemmArgs a) {
-    constexpr int LDC = PW_LDC;
+template <int KC, bool STREAM>
+__global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
+    constexpr int LDC = PW_LDC, KS = KC / 16, ROWB = PwD<KC>::ROWB, KV = KC / 8;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char* s_w = smem;                                                       // [256][8 positions of 16 bytes]
+    unsigned char* s_w = smem;                                                       // [256][KV positions of 16 bytes]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    bf16_t* Cst = (bf16_t*)(smem + PW_W_BYTES + wave * PW_CST_BYTES);                // [32][LDC], this wavefront's
-    float* s_part = (float*)(smem + PW_W_BYTES + 8 * PW_CST_BYTES);                  // [2 stats][8 wavefronts][256]
+    bf16_t* Cst = (bf16_t*)(smem + PwD<KC>::W_BYTES + wave * PW_CST_BYTES);          // [32][LDC], this wavefront's
+    float* s_part = (float*)(smem + PwD<KC>::W_BYTES + 8 * PW_CST_BYTES);            // [2 stats][8 wavefronts][256]
     const int r = lane & 31, hi = lane >> 5;
     const long M = (long)a.F * a.Hd * a.Wd;
     const bool do_stats = a.stats != nullptr;
+    const int nsplit = a.Cd / 256;
+    const int nb0 = ((int)blockIdx.x % nsplit) * 256;              // first result channel of this block
+    const long stream0 = (long)((int)blockIdx.x / nsplit) * 8 + wave;
+    const long nstreams = (long)((int)gridDim.x / nsplit) * 8;
+    // position p of weight row n holds K vector p ^ swz(n): the 16 (or 2 x 8) rows that one quarter-wave reads together
+    // then lie in 16 different 16-byte bank groups
+    auto swz = [](int n) { return KC == 128 ? (n & 15) : ((n >> 1) & 7); };
 
     {
-        const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.wp, (uint32_t)(256 * 64 * 2));
+        const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.wp + (long)nb0 * KC, (uint32_t)(256 * ROWB));
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
+        for (int q4 = 0; q4 < 256 * KV / 512; ++q4) {
             const int q = tid + q4 * 512;                          // piece: weight row n, position pos
-            const int n = q >> 3, pos = q & 7, kv = pos ^ ((n >> 1) & 7);
-            *(u32x4*)(s_w + q * 16) = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, n * 128 + kv * 16, 0, 0);
+            const int n = q / KV, pos = q % KV, kv = pos ^ swz(n);
+            *(u32x4*)(s_w + q * 16) = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, n * ROWB + kv * 16, 0, 0);
         }
     }
     __syncthreads();
 
-    int b_rd[4];                                                   // fragment of weight rows 32*j + r, step ks
+    int b_rd[KS];                                                  // fragment of weight rows 32*j + r, step ks
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) b_rd[ks] = r * 128 + (((2 * ks + hi) ^ ((r >> 1) & 7)) << 4);
-    const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(a.src, (uint32_t)(M * 128));
+    for (int ks = 0; ks < KS; ++ks) b_rd[ks] = r * ROWB + (((2 * ks + hi) ^ swz(r)) << 4);
+    const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(a.src, (uint32_t)(M * ROWB));
     const long nslabs = (M + 31) / 32;
-    const long nwaves = (long)gridDim.x * 8;
     auto load_a = [&](long sl, bf16x8* fr) {
         const long row = sl * 32 + r;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, row < M ? (int)(row * 128 + (2 * ks + hi) * 16) : (int)OOB_OFFSET, 0, 0);
+        for (int ks = 0; ks < KS; ++ks) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, row < M ? (int)(row * ROWB + (2 * ks + hi) * 16) : (int)OOB_OFFSET, 0, 0);
             fr[ks] = __builtin_bit_cast(bf16x8, v);
         }
     };
@@ -1990,11 +2005,11 @@ __global__ void __launch_bounds__(512) pw64x256_kernel(IgemmArgs a) {
         for (int q = 0; q < 8; ++q) f1[h][q] = f2[h][q] = 0.f;
     const int vcol = lane & 15, row0 = lane >> 4;                  // store loop: piece lane + 64*t is row row0 + 4*t, vector vcol
 
-    long slab = (long)blockIdx.x * 8 + wave;
-    bf16x8 cur[4], nxt[4];
+    long slab = stream0;
+    bf16x8 cur[KS], nxt[KS];
     if (slab < nslabs) load_a(slab, cur);
-    for (; slab < nslabs; slab += nwaves) {
-        if (slab + nwaves < nslabs) load_a(slab + nwaves, nxt);
+    for (; slab < nslabs; slab += nstreams) {
+        if (slab + nstreams < nslabs) load_a(slab + nstreams, nxt);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             f32x16 acc[4];
@@ -2003,10 +2018,10 @@ __global__ void __launch_bounds__(512) pw64x256_kernel(IgemmArgs a) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
+            for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const bf16x8 bfrag = *(const bf16x8*)(s_w + (h * 4 + j) * 32 * 128 + b_rd[ks]);
+                    const bf16x8 bfrag = *(const bf16x8*)(s_w + (h * 4 + j) * 32 * ROWB + b_rd[ks]);
                     // operands swapped as in igemm_ring_kernel: the result block is [channel][pixel]
                     acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, cur[ks], acc[j], 0, 0, 0);
                 }
@@ -2039,7 +2054,7 @@ __global__ void __launch_bounds__(512) pw64x256_kernel(IgemmArgs a) {
                             f2[h][2 * e + 1] = fmaf(hv, hv, f2[h][2 * e + 1]);
                         }
                     }
-                    u32x4* q = (u32x4*)(a.dst + grow * 256 + h * 128 + vcol * 8);
+                    u32x4* q = (u32x4*)(a.dst + grow * a.Cd + nb0 + h * 128 + vcol * 8);
                     if (STREAM) __builtin_nontemporal_store(v, q);
                     else *q = v;
                 }
@@ -2047,7 +2062,7 @@ __global__ void __launch_bounds__(512) pw64x256_kernel(IgemmArgs a) {
             __builtin_amdgcn_wave_barrier();
         }
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) cur[ks] = nxt[ks];
+        for (int ks = 0; ks < KS; ++ks) cur[ks] = nxt[ks];
     }
     if (do_stats) {
         // lanes 16 apart hold the same columns: fold them, then one slot per wavefront, fixed order over the slots
@@ -2070,11 +2085,14 @@ __global__ void __launch_bounds__(512) pw64x256_kernel(IgemmArgs a) {
                 }
         }
         __syncthreads();
-        const int stat = tid >> 8, col = tid & 255;
+        const int stat = tid >> 8, c = tid & 255;
         float v = 0.f;
 #pragma unroll
-        for (int sl = 0; sl < 8; ++sl) v += s_part[(stat * 8 + sl) * 256 + col];
-        a.stats[(size_t)blockIdx.x * 2 * 256 + stat * 256 + col] = v;
+        for (int sl = 0; sl < 8; ++sl) v += s_part[(stat * 8 + sl) * 256 + c];
+        const int rows_used = (int)gridDim.x / nsplit, row_s = (int)blockIdx.x / nsplit;
+        a.stats[((size_t)row_s * 2 + stat) * a.Cd + nb0 + c] = v;
+        for (int rz = rows_used + row_s; rz < (int)gridDim.x; rz += rows_used)      // rows beyond the streams: zeros
+            a.stats[((size_t)rz * 2 + stat) * a.Cd + nb0 + c] = 0.f;
     }
 }
 
@@ -2091,14 +2109,6 @@ __global__ void __launch_bounds__(512) pw64x256_kernel(IgemmArgs a) {
 // a few destination pieces are requested together, the first group ahead of the staging of the accumulators.
 // Partial rows (a.stats, [gridDim.x][2][Cd]): row s of the first gridDim.x / nsplit rows receives the sums of stream s,
 // the others are written as zeros (callers size and sum the rows by the general kernel's grid).
-template <int KC>
-struct PwD {
-    static constexpr int ROWB = KC * 2;                        // bytes per weight row
-    static constexpr int W_BYTES = 256 * ROWB;
-    static constexpr int SMEM = W_BYTES + 8 * PW_CST_BYTES + PW_PART_BYTES;
-};
-static_assert(PwD<128>::SMEM <= 160 * 1024, "LDS budget");
-
 template <int KC, bool STREAM>
 __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
     constexpr int LDC = PW_LDC, KS = KC / 16, ROWB = PwD<KC>::ROWB, KV = KC / 8;
@@ -2504,35 +2514,36 @@ static int launch_stem_s(IgemmArgs& a, hipStream_t s) {
     return check_launch("igemm_fwd_stem");
 }
 
-// The 64 -> 256 channel 1x1 forward kernel takes its layers when the general kernel would run them with 256-row tiles
-// (the two then launch the same number of blocks, which callers size the statistics rows by) and every wavefront of the
-// grid has at least two passes.  TSM_PW_KERNEL=0 leaves these layers to the general kernel, TSM_PW_MIN_ROWS=<n> moves
-// the threshold (both read at every call: tests and comparisons set them).
-static bool pw64x256_eligible(const IgemmArgs& a) {
+// The short-K 1x1 forward kernel takes its layers when the general kernel would run them with 256-row tiles (the two
+// then launch the same number of blocks, which callers size the statistics rows by) and every wavefront of the grid has
+// at least two passes.  TSM_PW_KERNEL=0 leaves these layers to the general kernel, TSM_PW_MIN_ROWS=<n> moves the
+// threshold (both read at every call: tests and comparisons set them).
+static bool pw_fwd_eligible(const IgemmArgs& a) {
     const char* e = getenv("TSM_PW_KERNEL");
     if (e && e[0] == '0') return false;
     const char* t = getenv("TSM_PW_MIN_ROWS");
     const long min_rows = t ? atol(t) : 2L * 32 * 8 * num_cu();
     const long rows = (long)a.F * a.Hd * a.Wd;
-    return a.Cs == 64 && a.pitch == 64 && a.Cd == 256 && a.KT == 1 && a.KH == 1 && a.KW == 1 && a.stride == 1 && a.padh == 0 &&
-           a.padw == 0 && a.fold == 0 && a.addend == nullptr && a.ep_scale == nullptr && a.Hs == a.Hd && a.Ws == a.Wd &&
-           rows * 128 < 0x7ff00000L && ring_eligible(64, rows * 64 + 64, 256L * 64, false) && ring_rows(rows, 256) == 256 &&
-           rows >= min_rows;
+    return (a.Cs == 64 || a.Cs == 128) && a.pitch == a.Cs && (a.Cd == 256 || a.Cd == 512) && a.KT == 1 && a.KH == 1 && a.KW == 1 &&
+           a.stride == 1 && a.padh == 0 && a.padw == 0 && a.fold == 0 && a.addend == nullptr && a.ep_scale == nullptr &&
+           a.Hs == a.Hd && a.Ws == a.Wd && rows * a.Cs * 2 < 0x7ff00000L &&
+           ring_eligible(a.Cs, rows * a.Cs + a.Cs, (long)a.Cd * a.Cs, false) && ring_rows(rows, a.Cd) == 256 && rows >= min_rows;
 }
 
-template <bool STREAM>
-static int launch_pw64x256(IgemmArgs& a, hipStream_t s) {
-    auto kern = pw64x256_kernel<STREAM>;
+template <int KC, bool STREAM>
+static int launch_pw_fwd(IgemmArgs& a, hipStream_t s) {
+    auto kern = pw_fwd_kernel<KC, STREAM>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return fail(TSM_ERR_LAUNCH, "pw64x256: cannot raise dynamic LDS limit");
+            return fail(TSM_ERR_LAUNCH, "pw_fwd: cannot raise dynamic LDS limit");
         configured = true;
     }
     const long rows = (long)a.F * a.Hd * a.Wd;
-    const int grid = igemm_grid((int)((rows + 255) / 256), 256, 128, 1);      // as the general kernel with 256 x 128 tiles
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), PW_SMEM, s, a);
-    return check_launch("igemm_fwd_pw64");
+    const int grid = igemm_grid((int)((rows + 255) / 256), a.Cd, 128, 1);      // as the general kernel with 256 x 128 tiles
+    if (grid % (a.Cd / 256) != 0) return fail(TSM_ERR_LAUNCH, "pw_fwd: grid does not split over the column halves");
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), PwD<KC>::SMEM, s, a);
+    return check_launch("igemm_fwd_pw");
 }
 
 // The short-K, wide-result 1x1 data-gradient kernel takes its layers under the same conditions as the forward kernel
@@ -2578,8 +2589,11 @@ static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
         if (a.Cs == 64) return st ? launch_pw_dgrad<64, true>(a, s) : launch_pw_dgrad<64, false>(a, s);
         return st ? launch_pw_dgrad<128, true>(a, s) : launch_pw_dgrad<128, false>(a, s);
     }
-    if (!DGRAD && pw64x256_eligible(a))
-        return rows * a.Cd * 2 > (64L << 20) ? launch_pw64x256<true>(a, s) : launch_pw64x256<false>(a, s);
+    if (!DGRAD && pw_fwd_eligible(a)) {
+        const bool st = rows * a.Cd * 2 > (64L << 20);
+        if (a.Cs == 64) return st ? launch_pw_fwd<64, true>(a, s) : launch_pw_fwd<64, false>(a, s);
+        return st ? launch_pw_fwd<128, true>(a, s) : launch_pw_fwd<128, false>(a, s);
+    }
     if (!DGRAD && stem_eligible(a))
         return rows * a.Cd * 2 > (64L << 20) ? launch_stem_s<true>(a, s) : launch_stem_s<false>(a, s);
     if (ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K, a.pitch != a.Cs)) {
@@ -2708,6 +2722,7 @@ struct WgradArgs {
     long chunk;            // pixels per block (multiple of 64)
     int K;                 // taps * Cin
     int col_tiles;
+    int tiles, nchunks, group;   // wgrad_tr_kernel: tiles of D, chunks of pixels, block index mapping (see the kernel)
     // wgrad_tr_kernel, AFF variants: dy is not stored; the loader forms it from dz (passed as `dy`) and the
     // BatchNorm input ay as dy = a*dz + b*ay + c per output channel, coefficients aff = [3][Cout] (BatchNorm
     // backward, see bn_bwd_apply), rounded to bf16 as the stored tensor would be
@@ -2964,9 +2979,16 @@ __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int co0 = (blockIdx.y / a.col_tiles) * BCO;
-    const int j0 = (blockIdx.y % a.col_tiles) * BCI;
-    const long mbeg = (long)blockIdx.x * a.chunk;
+    // One-dimensional grid.  Workgroups go to the eight XCDs round-robin by index, and every tile of D reads the
+    // same pixels of a chunk (all of dy for its row tile, all of x for its column tile): with a.group == 8 the
+    // tiles of one chunk are the indices 8 apart inside a run of 8 * tiles, so they share an XCD, start together
+    // and find each other's rows in that XCD's L2.  a.group == 0 (few chunks): chunk fastest, tile slowest.
+    const int bid = (int)blockIdx.x;
+    const int tile_id = a.group ? (bid >> 3) % a.tiles : bid / a.nchunks;
+    const int chunk_id = a.group ? (bid / (8 * a.tiles)) * 8 + (bid & 7) : bid % a.nchunks;
+    const int co0 = (tile_id / a.col_tiles) * BCO;
+    const int j0 = (tile_id % a.col_tiles) * BCI;
+    const long mbeg = (long)chunk_id * a.chunk;
     long mend = mbeg + a.chunk;
     if (mend > a.M) mend = a.M;
     if (mbeg >= mend) return;
@@ -3180,12 +3202,20 @@ static int launch_wgrad_tr(WgradArgs& a, int Cout, int blocks_per_cu, const char
     const int tiles = (Cout / BCO) * a.col_tiles;
     long want = (long)blocks_per_cu * num_cu() / tiles;
     if (want < 1) want = 1;
+    const char* xe = getenv("TSM_WGRAD_XCD");   // TSM_WGRAD_XCD=0 (read at every call): chunk-fastest block order everywhere
+    // (whole groups of eight chunks, all blocks resident at once; not where rounding down to a multiple of
+    //  eight would idle more than 3 % of the CUs)
+    const bool grouped = !(xe && xe[0] == '0') && tiles > 1 && want >= 16 && (want & 7) * 100 <= want * 3;
+    if (grouped) want = want / 8 * 8;
     long chunk = (a.M + want - 1) / want;
     // at least 16 K steps per block: below that the fp32 atomics of the tile (one per block) outweigh the
     // parallelism gained (measured at 64 frames: 1x1 layers of the last three stages 10 % faster)
     if (chunk < 16L * WMK) chunk = 16L * WMK;
     a.chunk = (chunk + WMK - 1) / WMK * WMK;
-    const dim3 grid((unsigned)((a.M + a.chunk - 1) / a.chunk), (unsigned)tiles);
+    a.tiles = tiles;
+    a.nchunks = (int)((a.M + a.chunk - 1) / a.chunk);
+    a.group = grouped ? 8 : 0;
+    const dim3 grid((unsigned)((grouped ? (a.nchunks + 7) / 8 * 8 : a.nchunks) * tiles));
     auto kern = wgrad_tr_kernel<BCO, BCI, WM, WN, AFF>;
     const size_t smem = (size_t)2 * WMK * (BCO * 2 + (BCI == 192 ? 512 : BCI * 2)) + (size_t)2 * NT * sizeof(PixInfo);
     static bool configured = false;

@@ -136,16 +136,19 @@ def test_conv3x3_c64_kernel_every_element(case, monkeypatch):
 @pytest.mark.parametrize("case", [
     (2, 4, 64, 57, 57, 256, 1, 1, 0, 0),     # 25992 pixels: a ragged last pass of 8 pixels
     (3, 8, 64, 33, 35, 256, 1, 1, 0, 0),     # 27720 pixels, H != W; some wavefronts get one pass more than others
+    (2, 8, 128, 28, 28, 512, 1, 1, 0, 0),    # 128 -> 512 channels: the result is split over pairs of blocks
+    (2, 8, 128, 41, 41, 256, 1, 1, 0, 0),    # 128 -> 256 channels, ragged last pass
+    (2, 8, 64, 30, 30, 512, 1, 1, 0, 0),     # 64 -> 512 channels
 ])
-def test_pointwise_64_to_256_kernel_every_element(case, monkeypatch):
-    """The 64 -> 256 channel 1x1 forward kernel (statistics epilogue; one wavefront per 32 pixels, nothing shared but
+def test_pointwise_forward_kernel_every_element(case, monkeypatch):
+    """The short-K, wide-result 1x1 forward kernel (statistics epilogue; one wavefront per 32 pixels, nothing shared but
     the weights) on sizes the oracle covers element by element; the library would leave so few pixels to the general
-    kernel, the threshold is moved.  (Data and weight gradient of the case run on the general kernels as usual.)"""
+    kernel, the threshold is moved.  (The weight gradient of the case runs on the general kernels as usual.)"""
     monkeypatch.setenv("TSM_PW_MIN_ROWS", "1")
     B.tsm_profile_begin()
     _run(case, "bf16", "nthwc")
     classes = B.tsm_profile_end()
-    assert "igemm_fwd_pw64" in classes, sorted(classes)
+    assert "igemm_fwd_pw" in classes, sorted(classes)
 
 
 @pytest.mark.parametrize("case", [
