@@ -85,11 +85,10 @@ def dgrad_class(name, rin, cin, rout, cout, taps):
     row and column: the library computes it as a stride-1 data gradient on the output grid (compact form)."""
     if name.endswith(".ds") and rin != rout:
         return igemm_class("dgrad", cin, cout, rout, 1, 1)
-    # the first convolution of a block, short in K and wide in its result: the kernel of its own (not behind a strided
-    # projection, whose gradient arrives in compact form)
-    blk0 = int(name.split(".")[1]) == 0 if name != "conv1" else False
+    # the first convolution of a block, short in K and wide in its result: the kernel of its own (behind a strided
+    # projection, whose gradient arrives in compact form, the variant for 128 source channels: res3's first block)
     if (name.endswith(".c1") and taps == 1 and rin == rout and cout in (64, 128) and cin in (256, 512) and
-            rin >= 2 * 32 * 8 * 256 and not (blk0 and not name.startswith("res2"))):
+            rin >= 2 * 32 * 8 * 256):
         tiles256 = -(-rin // 256) * -(-cin // 128)
         if tiles256 * 4 >= 256 * 3:
             return "igemm_dgrad_pw"

@@ -2109,7 +2109,8 @@ __global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
 // a few destination pieces are requested together, the first group ahead of the staging of the accumulators.
 // Partial rows (a.stats, [gridDim.x][2][Cd]): row s of the first gridDim.x / nsplit rows receives the sums of stream s,
 // the others are written as zeros (callers size and sum the rows by the general kernel's grid).
-template <int KC, bool STREAM>
+// CADD: the shortcut gradient comes in the compact form described at IgemmArgs::add_stride.
+template <int KC, bool STREAM, bool CADD = false>
 __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
     constexpr int LDC = PW_LDC, KS = KC / 16, ROWB = PwD<KC>::ROWB, KV = KC / 8;
     constexpr int GP = KC == 64 ? 4 : 2;                           // destination pieces requested together (registers)
@@ -2224,20 +2225,31 @@ __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
 #pragma unroll
             for (int g = 0; g < 8 / GP; ++g) {                     // groups of GP pieces
                 int mr[GP], mz[GP];
+                int arow[CADD ? GP : 1];                           // the pixel's row in the compact addend, or -1
                 u32x4 ad[GP], yy[GP];
                 uint32_t bt[GP];
 #pragma unroll
                 for (int t = 0; t < GP; ++t) {
                     const long grow = slab * 32 + row0 + 4 * (GP * g + t);
                     const bool live = grow < M;
-                    const int tt = live ? (int)((grow / hw) % a.T) : 0;
+                    const unsigned fr = CADD && live ? (unsigned)grow / (unsigned)hw : 0u;
+                    const int tt = CADD ? (int)(fr % (unsigned)a.T) : (live ? (int)((grow / hw) % a.T) : 0);
                     const bool in_clip = tt + dt[h] >= 0 && tt + dt[h] < a.T;
                     mr[t] = live && in_clip ? (int)grow + dt[h] * hw : -1;
                     mz[t] = live && ((dt[h] == 1 && tt == 0) || (dt[h] == -1 && tt == a.T - 1)) ? (int)grow : -1;
                     // loads without a branch around them (rows that are not stored read the zero page)
                     const long e = (long)mr[t] * a.Cd + col;
                     const bool ok = mr[t] >= 0;
-                    ad[t] = *(const u32x4*)((ok && a.addend) ? a.addend + e : zero_page);
+                    if (CADD) {
+                        // (the frame offset of the adjoint shift does not change the pixel)
+                        const unsigned q = (unsigned)grow - fr * (unsigned)hw;
+                        const unsigned ph = q / (unsigned)a.Wd, pw = q - ph * (unsigned)a.Wd;
+                        arow[t] = live && ((ph | pw) & 1u) == 0 ? (int)((fr * (unsigned)a.add_ho + (ph >> 1)) * (unsigned)a.add_wo + (pw >> 1)) : -1;
+                        const long ea = ((long)arow[t] + (long)dt[h] * (a.add_ho * a.add_wo)) * a.Cd + col;
+                        ad[t] = *(const u32x4*)((ok && arow[t] >= 0) ? a.addend + ea : zero_page);
+                    } else {
+                        ad[t] = *(const u32x4*)((ok && a.addend) ? a.addend + e : zero_page);
+                    }
                     bt[t] = *((ok && fuse_mask) ? a.act_bits + e / 8 : (const uint8_t*)zero_page);
                     yy[t] = *(const u32x4*)((ok && fuse_bn) ? a.ybn + e : zero_page);
                 }
@@ -2267,7 +2279,11 @@ __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
                     const long e = (long)mz[t] * a.Cd + col;
                     u32x4 zad = u32x4{0u, 0u, 0u, 0u}, zyy = zad;
                     uint32_t zbt = 0;
-                    if (a.addend) zad = *(const u32x4*)(a.addend + e);
+                    if (CADD) {
+                        if (arow[t] >= 0) zad = *(const u32x4*)(a.addend + (long)arow[t] * a.Cd + col);
+                    } else if (a.addend) {
+                        zad = *(const u32x4*)(a.addend + e);
+                    }
                     if (fuse_mask) zbt = a.act_bits[e / 8];
                     if (fuse_bn) zyy = *(const u32x4*)(a.ybn + e);
                     finish(mz[t], u32x4{0u, 0u, 0u, 0u}, zad, zbt, zyy);
@@ -2555,17 +2571,19 @@ static bool pw_dgrad_eligible(const IgemmArgs& a) {
     const long min_rows = t ? atol(t) : 2L * 32 * 8 * num_cu();
     const long rows = (long)a.F * a.Hd * a.Wd;
     if (!((a.Cs == 64 || a.Cs == 128) && a.pitch == a.Cs && (a.Cd == 256 || a.Cd == 512) && a.KT == 1 && a.KH == 1 && a.KW == 1 &&
-          a.stride == 1 && a.padh == 0 && a.padw == 0 && a.Hs == a.Hd && a.Ws == a.Wd && a.add_stride == 1 && a.fold % 8 == 0))
+          a.stride == 1 && a.padh == 0 && a.padw == 0 && a.Hs == a.Hd && a.Ws == a.Wd && a.fold % 8 == 0))
         return false;
+    if (a.add_stride == 2 && !(a.addend != nullptr && a.Cs == 128)) return false;   // the compact addend: one variant built
+    if ((long)a.F * a.Hd * a.Wd > 0x7fffffffL) return false;
     if (a.act != nullptr && a.act_bits == nullptr) return false;      // a mask that only the activation can give
     if (a.ybn != nullptr && a.stats == nullptr) return false;
     return rows * a.Cs * 2 < 0x7ff00000L && ring_eligible(a.Cs, rows * a.Cs + a.Cs, (long)a.Cd * a.Cs, false) &&
            ring_rows(rows, a.Cd) == 256 && rows >= min_rows;
 }
 
-template <int KC, bool STREAM>
+template <int KC, bool STREAM, bool CADD = false>
 static int launch_pw_dgrad(IgemmArgs& a, hipStream_t s) {
-    auto kern = pw_dgrad_kernel<KC, STREAM>;
+    auto kern = pw_dgrad_kernel<KC, STREAM, CADD>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -2587,6 +2605,7 @@ static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     if (DGRAD && pw_dgrad_eligible(a)) {
         const bool st = rows * a.Cd * 2 > (64L << 20);
         if (a.Cs == 64) return st ? launch_pw_dgrad<64, true>(a, s) : launch_pw_dgrad<64, false>(a, s);
+        if (a.add_stride == 2) return st ? launch_pw_dgrad<128, true, true>(a, s) : launch_pw_dgrad<128, false, true>(a, s);
         return st ? launch_pw_dgrad<128, true>(a, s) : launch_pw_dgrad<128, false>(a, s);
     }
     if (!DGRAD && pw_fwd_eligible(a)) {

@@ -144,6 +144,17 @@ def test_bottleneck_projection_stride2():
     run_block("bottleneck", 2, 2, 16, 7, 7, 8, 32, 2, True, 4, "f32", "ntchw")
 
 
+def test_bottleneck_projection_stride2_with_the_pointwise_kernels(monkeypatch):
+    """The first block of the second stage (256 -> 128 -> 128 -> 512, stride 2, projection) on odd 43x43 maps with the
+    short-K 1x1 kernels taking its layers (the threshold is moved): the data gradient of the first convolution adds the
+    projection's gradient from its compact form (22x22 pixels per frame) and shifts frames on the store."""
+    monkeypatch.setenv("TSM_PW_MIN_ROWS", "1")
+    B.tsm_profile_begin()
+    run_block("bottleneck", 2, 8, 256, 43, 43, 128, 512, 2, True, 8, "bf16", "nthwc")
+    classes = B.tsm_profile_end()
+    assert "igemm_dgrad_pw" in classes, sorted(classes)
+
+
 def test_bottleneck_first_of_stage_projection_stride1():
     run_block("bottleneck", 1, 4, 64, 14, 14, 64, 256, 1, True, 8, "bf16", "nthwc")
 
