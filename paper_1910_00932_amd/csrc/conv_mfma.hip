@@ -2977,8 +2977,8 @@ __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
     constexpr int TM = BCO / WM, TN = BCI / WN;       // wavefront tile
     constexpr int MI = TM / 32, NJ = TN / 32;
     constexpr int PXS = WMK;                          // pixels per step
-    // bytes per pixel row of the two operands in LDS (a power of two: 192 columns sit in 512-byte rows)
-    constexpr int ROWA = BCO * 2, ROWB = BCI == 192 ? 512 : BCI * 2;
+    // bytes per pixel row of the two operands in LDS
+    constexpr int ROWA = BCO * 2, ROWB = BCI * 2;
     constexpr int STAGE = PXS * (ROWA + ROWB);
     constexpr int AVR = BCO / 8, BVR = BCI / 8;       // 16-byte pieces per row
     constexpr int RA = NT / AVR;                      // dy rows per load pass
@@ -3033,7 +3033,9 @@ __global__ void __launch_bounds__(WM * WN * 64) wgrad_tr_kernel(WgradArgs a) {
 #pragma unroll
     for (int i = 0; i < PA; ++i) a_off[i] = (uint32_t)(((arow + i * RA) * a.Cout + co0 + avec * 8) * 2);
     auto swz_a = [](int r) { return ROWA >= 256 ? 2 * (r & 3) : 2 * ((r >> 1) & 1); };
-    auto swz_b = [](int r) { return ROWB >= 256 ? 2 * (r & 3) : 2 * ((r >> 1) & 1); };
+    // (rows of 384 bytes, like rows of 128, start half a bank cycle apart: row parity already separates two of the four
+    //  pixels, and an XOR that only touches bit 1 of the block index stays inside the row's twelve blocks)
+    auto swz_b = [](int r) { return ROWB % 256 == 0 ? 2 * (r & 3) : 2 * ((r >> 1) & 1); };
     constexpr int PBV = BREG ? 1 : PB;               // distinct (need, const) pairs per thread
     uint32_t b_need[PBV], b_const[PBV];
     int b_row[PB], b_wr[PB];                          // row within the step, LDS position
@@ -3236,7 +3238,7 @@ static int launch_wgrad_tr(WgradArgs& a, int Cout, int blocks_per_cu, const char
     a.group = grouped ? 8 : 0;
     const dim3 grid((unsigned)((grouped ? (a.nchunks + 7) / 8 * 8 : a.nchunks) * tiles));
     auto kern = wgrad_tr_kernel<BCO, BCI, WM, WN, AFF>;
-    const size_t smem = (size_t)2 * WMK * (BCO * 2 + (BCI == 192 ? 512 : BCI * 2)) + (size_t)2 * NT * sizeof(PixInfo);
+    const size_t smem = (size_t)2 * WMK * (BCO * 2 + BCI * 2) + (size_t)2 * NT * sizeof(PixInfo);
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -3294,7 +3296,8 @@ int conv_mfma_wgrad(const ConvP& p, const bf16_t* x, const bf16_t* dy, float* dw
             if (a.K % 256 == 0 && (p.Cin % 256 == 0 || a.pitch != p.Cin)) return launch_wgrad_tr<64, 256, 1, 4>(a, p.Cout, 1, "wgrad_tr_64x256", s);
             if (p.taps() == 1) return launch_wgrad_tr<64, 64, 2, 2>(a, p.Cout, 4, "wgrad_tr_64x64", s);
             // 64 input channels and several taps: a column tile of three taps shares the dy tile among them
-            if (a.K % 192 == 0) return launch_wgrad_tr<64, 192, 2, 2>(a, p.Cout, 1, "wgrad_tr_64x192", s);
+            // (two blocks per CU: the layer is bound by the latency of its gathers, not by a unit)
+            if (a.K % 192 == 0) return launch_wgrad_tr<64, 192, 2, 2>(a, p.Cout, 2, "wgrad_tr_64x192", s);
         }
     }
     if (affine_y) return fail(TSM_ERR_UNSUPPORTED, "wgrad: the affine form needs the transposing-read kernels");
