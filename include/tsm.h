@@ -40,11 +40,13 @@
  *    TSM_FUSED_TAIL_MIN_TILES=<n> replaces the number of 256-pixel tiles from
  *    which the two-convolution kernel is chosen (default: three per four
  *    compute units); TSM_PW_KERNEL=0 (read at every call) leaves the short-K 1x1
- *    layers that have kernels of their own (64 -> 256 channels forward; the data
- *    gradient of a block's first convolution in the first two stages) to the
- *    general kernel and TSM_PW_MIN_ROWS=<n>
- *    replaces the number of pixels from which their own kernel is chosen (default:
- *    two passes of 32 pixels per wavefront of the grid); TSM_MASK_BITS=0 (read once per process) makes the train
+ *    layers that have kernels of their own (64 or 128 -> 256 or 512 channels:
+ *    forward, and the data gradient of a block's first convolution) to the
+ *    general kernel and TSM_PW_MIN_ROWS=<n> replaces the number of pixels from
+ *    which their own kernel is chosen (default: two passes of 32 pixels per
+ *    wavefront of the grid); TSM_WGRAD_XCD=0 (read at every call) launches the
+ *    weight gradient's tiles in chunk-fastest order instead of grouping the
+ *    tiles of one pixel chunk on one XCD; TSM_MASK_BITS=0 (read once per process) makes the train
  *    step's data gradients take the ReLU mask of a block output from the
  *    activation itself instead of from the decision bits its forward pass keeps;
  *    TSM_SHORTCUT_BRANCH=0 (read once per process) keeps the kernels of a
