@@ -127,13 +127,15 @@ def class_bytes(F, size, epilogue_reads=True):
         x_b, y_b = 2.0 * rin * cin, 2.0 * rout * cout
         if stem:   # the space-to-depth image: (size/2 + 3)^2 pixels of 16 values per frame
             x_b = 2.0 * F * (size // 2 + 3) ** 2 * 16
-        add(igemm_class("fwd", cout, 64 if stem else cin, rout, taps, "stem" if stem else (1 if rin == rout else 2)), x_b + y_b)
+        # (a strided 1x1 projection reads, and its gradients read or write, only the input pixels with even row and column)
+        xs_b = x_b / 4.0 if (name.endswith(".ds") and rin != rout) else x_b
+        add(igemm_class("fwd", cout, 64 if stem else cin, rout, taps, "stem" if stem else (1 if rin == rout else 2)), xs_b + y_b)
         if has_dgrad:
             extra = x_b if name.endswith(".c1") else 0.0       # the shortcut gradient added in the epilogue
             blk0 = int(name.split(".")[1]) == 0
             if name.endswith(".c1") and blk0 and not name.startswith("res2"):
                 extra = x_b / 4.0                              # ... in compact form behind a strided projection
-            dx_b = x_b / 4.0 if (name.endswith(".ds") and rin != rout) else x_b   # the compact form is what is written
+            dx_b = xs_b                                        # (the compact form is what is written)
             # ReLU mask and BatchNorm sums of the layer below ride in the epilogue (two more tensors of the
             # result's size are read): always for c2 / c3, for c1 when the block below has an identity shortcut
             blk = int(name.split(".")[1])
@@ -148,7 +150,7 @@ def class_bytes(F, size, epilogue_reads=True):
                 extra += x_b / 16.0    # the block below has a projection shortcut: only its ReLU mask rides along
             add(dgrad_class(name, rin, cin, rout, cout, taps), dx_b + y_b + (extra if epilogue_reads else 0.0))
         # (the stem's weight gradient forms its dy while loading: it reads dz and the BatchNorm input instead)
-        add("wgrad_tr_64x256" if stem else wgrad_class(cout, cin, taps), x_b + (2.0 if stem else 1.0) * y_b)
+        add("wgrad_tr_64x256" if stem else wgrad_class(cout, cin, taps), xs_b + (2.0 if stem else 1.0) * y_b)
     return byt
 
 
