@@ -2113,7 +2113,7 @@ __global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
 template <int KC, bool STREAM, bool CADD = false>
 __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
     constexpr int LDC = PW_LDC, KS = KC / 16, ROWB = PwD<KC>::ROWB, KV = KC / 8;
-    constexpr int GP = KC == 64 ? 4 : 2;                           // destination pieces requested together (registers)
+    constexpr int GP = KC == 64 ? 8 : 4;                           // destination pieces requested together (registers)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* s_w = smem;                                                       // [256][KV positions of 16 bytes]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -2159,18 +2159,16 @@ __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
     };
     // store loop: piece lane + 64*t of a 32 x 128 half is row row0 + 4*t, vector vcol: a lane's channels never change
     const int vcol = lane & 15, row0 = lane >> 4;
-    float f1[2][8], f2[2][8], mu[2][8], rs[2][8];
+    // BatchNorm-backward sums: f1 = sum(dz), f2 = sum(dz * y) with the raw BatchNorm input; the block turns the second
+    // into sum(dz * (y - mean) * rstd) = (f2 - mean * f1) * rstd once, when it writes its partial row (the mean and rstd
+    // of a lane's sixteen channels would cost the loop 32 registers, which it spends on operands in flight instead)
+    float f1[2][8], f2[2][8];
     int dt[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        const int c0 = nb0 + h * 128 + vcol * 8;
-        dt[h] = group_dt(c0, a.fold);
+        dt[h] = group_dt(nb0 + h * 128 + vcol * 8, a.fold);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            f1[h][q] = f2[h][q] = 0.f;
-            mu[h][q] = fuse_bn ? a.bn_mean[c0 + q] : 0.f;
-            rs[h][q] = fuse_bn ? a.bn_rstd[c0 + q] : 0.f;
-        }
+        for (int q = 0; q < 8; ++q) f1[h][q] = f2[h][q] = 0.f;
     }
     const bf16_t* zero_page = (const bf16_t*)g_zero_page;
 
@@ -2213,8 +2211,8 @@ __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
                         o[q] = (plo ? o[q] & 0xffffu : 0u) | (phi ? o[q] & 0xffff0000u : 0u);
                         f1[h][2 * q] += dlo;
                         f1[h][2 * q + 1] += dhi;
-                        f2[h][2 * q] = fmaf(dlo, (__uint_as_float(yy[q] << 16) - mu[h][2 * q]) * rs[h][2 * q], f2[h][2 * q]);
-                        f2[h][2 * q + 1] = fmaf(dhi, (__uint_as_float(yy[q] & 0xffff0000u) - mu[h][2 * q + 1]) * rs[h][2 * q + 1], f2[h][2 * q + 1]);
+                        f2[h][2 * q] = fmaf(dlo, __uint_as_float(yy[q] << 16), f2[h][2 * q]);
+                        f2[h][2 * q + 1] = fmaf(dhi, __uint_as_float(yy[q] & 0xffff0000u), f2[h][2 * q + 1]);
                     }
                 }
                 u32x4* qd = (u32x4*)(a.dst + (long)mr * a.Cd + col);
@@ -2222,6 +2220,23 @@ __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
                 else *qd = o;
             };
             // lane: pixel r, channels 32*j + 8*q + 4*hi + {0..3}
+            auto stage = [&]() {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    bf16_t* dstp = Cst + r * LDC + j * 32 + 4 * hi;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        uint2 w;
+                        w.x = pack_bf16x2(acc[j][4 * q], acc[j][4 * q + 1]);
+                        w.y = pack_bf16x2(acc[j][4 * q + 2], acc[j][4 * q + 3]);
+                        *(uint2*)(dstp + 8 * q) = w;
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();                   // (LDS serves a wavefront's accesses in order)
+            };
+            // the first group's operands are requested ahead of the staging of the accumulators; where all eight pieces
+            // are requested at once the accumulators go first, to make room for them
+            if (GP == 8) stage();
 #pragma unroll
             for (int g = 0; g < 8 / GP; ++g) {                     // groups of GP pieces
                 int mr[GP], mz[GP];
@@ -2253,20 +2268,7 @@ __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
                     bt[t] = *((ok && fuse_mask) ? a.act_bits + e / 8 : (const uint8_t*)zero_page);
                     yy[t] = *(const u32x4*)((ok && fuse_bn) ? a.ybn + e : zero_page);
                 }
-                if (g == 0) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        bf16_t* dstp = Cst + r * LDC + j * 32 + 4 * hi;
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            uint2 w;
-                            w.x = pack_bf16x2(acc[j][4 * q], acc[j][4 * q + 1]);
-                            w.y = pack_bf16x2(acc[j][4 * q + 2], acc[j][4 * q + 3]);
-                            *(uint2*)(dstp + 8 * q) = w;
-                        }
-                    }
-                    __builtin_amdgcn_wave_barrier();               // (LDS serves a wavefront's accesses in order)
-                }
+                if (GP < 8 && g == 0) stage();
 #pragma unroll
                 for (int t = 0; t < GP; ++t) {
                     const int row = row0 + 4 * (GP * g + t);
@@ -2314,11 +2316,15 @@ __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
         }
         __syncthreads();
         const int stat = tid >> 8, c = tid & 255;
-        float v = 0.f;
+        float v1 = 0.f, v2 = 0.f;
 #pragma unroll
-        for (int sl = 0; sl < 8; ++sl) v += s_part[(stat * 8 + sl) * 256 + c];
+        for (int sl = 0; sl < 8; ++sl) {
+            v1 += s_part[sl * 256 + c];
+            v2 += s_part[(8 + sl) * 256 + c];
+        }
+        if (fuse_bn) v2 = (v2 - a.bn_mean[nb0 + c] * v1) * a.bn_rstd[nb0 + c];
         const int rows_used = (int)gridDim.x / nsplit, row_s = (int)blockIdx.x / nsplit;
-        a.stats[((size_t)row_s * 2 + stat) * a.Cd + nb0 + c] = v;
+        a.stats[((size_t)row_s * 2 + stat) * a.Cd + nb0 + c] = stat ? v2 : v1;
         // rows beyond the streams: zeros (block b clears the part of row rows_used + b / nsplit * ... it owns)
         for (int rz = rows_used + row_s; rz < (int)gridDim.x; rz += rows_used)
             a.stats[((size_t)rz * 2 + stat) * a.Cd + nb0 + c] = 0.f;
