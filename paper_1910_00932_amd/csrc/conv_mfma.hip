@@ -2103,10 +2103,11 @@ __global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
 // the block below and the result itself -- so the layer is a stream with a small product attached.  A block holds the
 // weights of 256 result channels (a result of 512 channels is split over pairs of neighbouring blocks, which read the
 // same rows of dy); a wavefront takes 32 pixels at a time, 128 result channels at a time through its own staging tile.
-// The epilogue is the one of igemm_ring_kernel's data gradient, value for value: adjoint shift as a frame offset on the
-// destination row (a lane's eight channels lie in one shift group), zero value for the frame a group leaves empty,
-// shortcut gradient added, mask from the decision bits, BatchNorm-backward sums of the stored values; the operands of
-// a few destination pieces are requested together, the first group ahead of the staging of the accumulators.
+// The stored values are those of igemm_ring_kernel's data gradient, value for value: adjoint shift as a frame offset on
+// the destination row (a lane's eight channels lie in one shift group), zero value for the frame a group leaves empty,
+// shortcut gradient added, mask from the decision bits.  The BatchNorm-backward sums of the stored values are taken in
+// a different order (raw sums in the loop, mean and rstd applied once per block: see f1, f2 below).  The operands of
+// four or eight destination pieces are requested together: the kernel is bound by the bytes a CU has in flight.
 // Partial rows (a.stats, [gridDim.x][2][Cd]): row s of the first gridDim.x / nsplit rows receives the sums of stream s,
 // the others are written as zeros (callers size and sum the rows by the general kernel's grid).
 // CADD: the shortcut gradient comes in the compact form described at IgemmArgs::add_stride.
