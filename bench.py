@@ -42,6 +42,15 @@ def conv_layers(F, size):
     return layers
 
 
+def pw_layer(cs, cd, rows):
+    """Shapes the short-K, wide-result 1x1 kernels take: K of 64, 128 or 256 channels, a result at least twice as wide
+    (a block holds 256 of its channels, 128 at K = 256), two passes of 32 pixels per wavefront of the grid."""
+    if cs not in (64, 128, 256) or not 256 <= cd <= 1024 or cd < 2 * cs:
+        return False
+    nb = 256 if cs <= 128 else 128
+    return cd % nb == 0 and rows >= 2 * 32 * 8 * 256 // (cd // nb)
+
+
 def igemm_class(kind, cd, cs, rows, taps=1, stride=1):
     """Kernel and tile the library picks for a forward ("fwd") or data-gradient ("dgrad") convolution that produces
     `rows` pixels of `cd` channels from `cs` source channels (tensors below 2 GiB, which holds for every workload
@@ -53,7 +62,7 @@ def igemm_class(kind, cd, cs, rows, taps=1, stride=1):
         r = "r128" if tiles256 * 4 < 256 * 3 else "256"
         if cs == 64 and cd == 64 and taps == 9 and stride == 1 and -(-rows // 256) >= 5 * 256:
             return "igemm_%s_c64" % kind      # the 64 -> 64 channel 3x3 kernel (five rounds of tiles or more)
-        if kind == "fwd" and cs in (64, 128) and cd in (256, 512) and taps == 1 and stride == 1 and r == "256" and rows >= 2 * 32 * 8 * 256:
+        if kind == "fwd" and taps == 1 and stride == 1 and r == "256" and pw_layer(cs, cd, rows):
             return "igemm_fwd_pw"             # the short-K 1x1 forward kernel
         # 64 columns per tile for narrow outputs, and where even 128x128 tiles leave a quarter of the CUs idle
         narrow = cd <= 64 or (r == "r128" and -(-rows // 128) * -(-cd // 128) * 4 < 256 * 3)
@@ -86,9 +95,8 @@ def dgrad_class(name, rin, cin, rout, cout, taps):
     if name.endswith(".ds") and rin != rout:
         return igemm_class("dgrad", cin, cout, rout, 1, 1)
     # the first convolution of a block, short in K and wide in its result: the kernel of its own (behind a strided
-    # projection, whose gradient arrives in compact form, the variant for 128 source channels: res3's first block)
-    if (name.endswith(".c1") and taps == 1 and rin == rout and cout in (64, 128) and cin in (256, 512) and
-            rin >= 2 * 32 * 8 * 256):
+    # projection, whose gradient arrives in compact form, the variants for 128 and 256 source channels)
+    if name.endswith(".c1") and taps == 1 and rin == rout and pw_layer(cout, cin, rin):
         tiles256 = -(-rin // 256) * -(-cin // 128)
         if tiles256 * 4 >= 256 * 3:
             return "igemm_dgrad_pw"

@@ -1950,34 +1950,54 @@ static_assert(PW_CST_BYTES % 16 == 0, "alignment");
 template <int KC>
 struct PwD {
     static constexpr int ROWB = KC * 2;                        // bytes per weight row
-    static constexpr int W_BYTES = 256 * ROWB;
+    static constexpr int NB = KC <= 128 ? 256 : 128;           // result channels per block (64 KB of weights at most)
+    static constexpr int NH = NB / 128;                        // passes of 128 result channels
+    static constexpr int W_BYTES = NB * ROWB;
     static constexpr int SMEM = W_BYTES + 8 * PW_CST_BYTES + PW_PART_BYTES;
 };
-static_assert(PwD<128>::SMEM <= 160 * 1024, "LDS budget");
+static_assert(PwD<128>::SMEM <= 160 * 1024 && PwD<256>::SMEM <= 160 * 1024, "LDS budget");
+
+// Block index -> (stream of pixels, part of the result channels).  The nsplit blocks that share a stream read the same
+// rows of the operand: they get indices 8 apart inside a run of 8 * nsplit, so that they share an XCD (workgroups go to
+// the XCDs round-robin by index) and its L2.  Grids that are not a multiple of 8 * nsplit: neighbouring indices.
+__device__ __forceinline__ void pw_block_role(int nsplit, int* stream, int* part) {
+    const int bid = (int)blockIdx.x;
+    if (nsplit > 1 && (int)gridDim.x % (8 * nsplit) == 0) {
+        const int local = bid >> 3;
+        *part = local % nsplit;
+        *stream = (local / nsplit) * 8 + (bid & 7);
+    } else {
+        *part = bid % nsplit;
+        *stream = bid / nsplit;
+    }
+}
 
 template <int KC, bool STREAM>
 __global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
-    constexpr int LDC = PW_LDC, KS = KC / 16, ROWB = PwD<KC>::ROWB, KV = KC / 8;
+    constexpr int LDC = PW_LDC, KS = KC / 16, ROWB = PwD<KC>::ROWB, KV = KC / 8, NB = PwD<KC>::NB, NH = PwD<KC>::NH;
+    constexpr bool DB = KC <= 128;                                 // the next pass's fragments in registers of their own
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char* s_w = smem;                                                       // [256][KV positions of 16 bytes]
+    unsigned char* s_w = smem;                                                       // [NB][KV positions of 16 bytes]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     bf16_t* Cst = (bf16_t*)(smem + PwD<KC>::W_BYTES + wave * PW_CST_BYTES);          // [32][LDC], this wavefront's
-    float* s_part = (float*)(smem + PwD<KC>::W_BYTES + 8 * PW_CST_BYTES);            // [2 stats][8 wavefronts][256]
+    float* s_part = (float*)(smem + PwD<KC>::W_BYTES + 8 * PW_CST_BYTES);            // [2 stats][8 wavefronts][NB]
     const int r = lane & 31, hi = lane >> 5;
     const long M = (long)a.F * a.Hd * a.Wd;
     const bool do_stats = a.stats != nullptr;
-    const int nsplit = a.Cd / 256;
-    const int nb0 = ((int)blockIdx.x % nsplit) * 256;              // first result channel of this block
-    const long stream0 = (long)((int)blockIdx.x / nsplit) * 8 + wave;
+    const int nsplit = a.Cd / NB;
+    int row_s, part;
+    pw_block_role(nsplit, &row_s, &part);
+    const int nb0 = part * NB;                                     // first result channel of this block
+    const long stream0 = (long)row_s * 8 + wave;
     const long nstreams = (long)((int)gridDim.x / nsplit) * 8;
     // position p of weight row n holds K vector p ^ swz(n): the 16 (or 2 x 8) rows that one quarter-wave reads together
     // then lie in 16 different 16-byte bank groups
-    auto swz = [](int n) { return KC == 128 ? (n & 15) : ((n >> 1) & 7); };
+    auto swz = [](int n) { return KC >= 128 ? (n & 15) : ((n >> 1) & 7); };
 
     {
-        const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.wp + (long)nb0 * KC, (uint32_t)(256 * ROWB));
+        const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.wp + (long)nb0 * KC, (uint32_t)(NB * ROWB));
 #pragma unroll
-        for (int q4 = 0; q4 < 256 * KV / 512; ++q4) {
+        for (int q4 = 0; q4 < NB * KV / 512; ++q4) {
             const int q = tid + q4 * 512;                          // piece: weight row n, position pos
             const int n = q / KV, pos = q % KV, kv = pos ^ swz(n);
             *(u32x4*)(s_w + q * 16) = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, n * ROWB + kv * 16, 0, 0);
@@ -1998,20 +2018,20 @@ __global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
             fr[ks] = __builtin_bit_cast(bf16x8, v);
         }
     };
-    float f1[2][8], f2[2][8];
+    float f1[NH][8], f2[NH][8];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int h = 0; h < NH; ++h)
 #pragma unroll
         for (int q = 0; q < 8; ++q) f1[h][q] = f2[h][q] = 0.f;
     const int vcol = lane & 15, row0 = lane >> 4;                  // store loop: piece lane + 64*t is row row0 + 4*t, vector vcol
 
     long slab = stream0;
-    bf16x8 cur[KS], nxt[KS];
+    bf16x8 cur[KS], nxt[DB ? KS : 1];
     if (slab < nslabs) load_a(slab, cur);
     for (; slab < nslabs; slab += nstreams) {
-        if (slab + nstreams < nslabs) load_a(slab + nstreams, nxt);
+        if (DB && slab + nstreams < nslabs) load_a(slab + nstreams, nxt);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < NH; ++h) {
             f32x16 acc[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -2025,6 +2045,8 @@ __global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
                     // operands swapped as in igemm_ring_kernel: the result block is [channel][pixel]
                     acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, cur[ks], acc[j], 0, 0, 0);
                 }
+            // (long K: the next pass's fragments take the place of this pass's, which the last product has read)
+            if (!DB && h == NH - 1 && slab + nstreams < nslabs) load_a(slab + nstreams, cur);
             // lane: pixel r, channels 32*j + 8*q + 4*hi + {0..3}
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -2061,13 +2083,15 @@ __global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
             }
             __builtin_amdgcn_wave_barrier();
         }
+        if (DB) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) cur[ks] = nxt[ks];
+            for (int ks = 0; ks < KS; ++ks) cur[ks] = nxt[DB ? ks : 0];
+        }
     }
     if (do_stats) {
         // lanes 16 apart hold the same columns: fold them, then one slot per wavefront, fixed order over the slots
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < NH; ++h)
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 f1[h][q] += __shfl_xor(f1[h][q], 16);
@@ -2077,22 +2101,24 @@ __global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
             }
         if (lane < 16) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int h = 0; h < NH; ++h)
 #pragma unroll
                 for (int q = 0; q < 8; ++q) {
-                    s_part[wave * 256 + h * 128 + lane * 8 + q] = f1[h][q];
-                    s_part[(8 + wave) * 256 + h * 128 + lane * 8 + q] = f2[h][q];
+                    s_part[wave * NB + h * 128 + lane * 8 + q] = f1[h][q];
+                    s_part[(8 + wave) * NB + h * 128 + lane * 8 + q] = f2[h][q];
                 }
         }
         __syncthreads();
-        const int stat = tid >> 8, c = tid & 255;
-        float v = 0.f;
+        if (tid < 2 * NB) {
+            const int stat = tid / NB, c = tid % NB;
+            float v = 0.f;
 #pragma unroll
-        for (int sl = 0; sl < 8; ++sl) v += s_part[(stat * 8 + sl) * 256 + c];
-        const int rows_used = (int)gridDim.x / nsplit, row_s = (int)blockIdx.x / nsplit;
-        a.stats[((size_t)row_s * 2 + stat) * a.Cd + nb0 + c] = v;
-        for (int rz = rows_used + row_s; rz < (int)gridDim.x; rz += rows_used)      // rows beyond the streams: zeros
-            a.stats[((size_t)rz * 2 + stat) * a.Cd + nb0 + c] = 0.f;
+            for (int sl = 0; sl < 8; ++sl) v += s_part[(stat * 8 + sl) * NB + c];
+            const int rows_used = (int)gridDim.x / nsplit;
+            a.stats[((size_t)row_s * 2 + stat) * a.Cd + nb0 + c] = v;
+            for (int rz = rows_used + row_s; rz < (int)gridDim.x; rz += rows_used)      // rows beyond the streams: zeros
+                a.stats[((size_t)rz * 2 + stat) * a.Cd + nb0 + c] = 0.f;
+        }
     }
 }
 
@@ -2113,30 +2139,32 @@ __global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
 // CADD: the shortcut gradient comes in the compact form described at IgemmArgs::add_stride.
 template <int KC, bool STREAM, bool CADD = false>
 __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
-    constexpr int LDC = PW_LDC, KS = KC / 16, ROWB = PwD<KC>::ROWB, KV = KC / 8;
+    constexpr int LDC = PW_LDC, KS = KC / 16, ROWB = PwD<KC>::ROWB, KV = KC / 8, NB = PwD<KC>::NB, NH = PwD<KC>::NH;
     constexpr int GP = KC == 64 ? 8 : 4;                           // destination pieces requested together (registers)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char* s_w = smem;                                                       // [256][KV positions of 16 bytes]
+    unsigned char* s_w = smem;                                                       // [NB][KV positions of 16 bytes]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     bf16_t* Cst = (bf16_t*)(smem + PwD<KC>::W_BYTES + wave * PW_CST_BYTES);          // [32][LDC], this wavefront's
-    float* s_part = (float*)(smem + PwD<KC>::W_BYTES + 8 * PW_CST_BYTES);            // [2 sums][8 wavefronts][256]
+    float* s_part = (float*)(smem + PwD<KC>::W_BYTES + 8 * PW_CST_BYTES);            // [2 sums][8 wavefronts][NB]
     const int r = lane & 31, hi = lane >> 5;
     const int hw = a.Hd * a.Wd;
     const long M = (long)a.F * hw;
-    const int nsplit = a.Cd / 256;
-    const int nb0 = ((int)blockIdx.x % nsplit) * 256;              // first result channel of this block
-    const long stream0 = (long)((int)blockIdx.x / nsplit) * 8 + wave;
+    const int nsplit = a.Cd / NB;
+    int row_s, part;
+    pw_block_role(nsplit, &row_s, &part);
+    const int nb0 = part * NB;                                     // first result channel of this block
+    const long stream0 = (long)row_s * 8 + wave;
     const long nstreams = (long)((int)gridDim.x / nsplit) * 8;
     const bool fuse_mask = a.act_bits != nullptr;
     const bool fuse_bn = fuse_mask && a.ybn != nullptr;
     // position p of weight row n holds K vector p ^ swz(n): the 16 (or 2 x 8) rows that one quarter-wave reads together
     // then lie in 16 different 16-byte bank groups
-    auto swz = [](int n) { return KC == 128 ? (n & 15) : ((n >> 1) & 7); };
+    auto swz = [](int n) { return KC >= 128 ? (n & 15) : ((n >> 1) & 7); };
 
     {
-        const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.wp + (long)nb0 * KC, (uint32_t)(256 * ROWB));
+        const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.wp + (long)nb0 * KC, (uint32_t)(NB * ROWB));
 #pragma unroll
-        for (int q4 = 0; q4 < 256 * KV / 512; ++q4) {
+        for (int q4 = 0; q4 < NB * KV / 512; ++q4) {
             const int q = tid + q4 * 512;                          // piece: weight row n, position pos
             const int n = q / KV, pos = q % KV, kv = pos ^ swz(n);
             *(u32x4*)(s_w + q * 16) = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, n * ROWB + kv * 16, 0, 0);
@@ -2163,10 +2191,10 @@ __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
     // BatchNorm-backward sums: f1 = sum(dz), f2 = sum(dz * y) with the raw BatchNorm input; the block turns the second
     // into sum(dz * (y - mean) * rstd) = (f2 - mean * f1) * rstd once, when it writes its partial row (the mean and rstd
     // of a lane's sixteen channels would cost the loop 32 registers, which it spends on operands in flight instead)
-    float f1[2][8], f2[2][8];
-    int dt[2];
+    float f1[NH][8], f2[NH][8];
+    int dt[NH];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < NH; ++h) {
         dt[h] = group_dt(nb0 + h * 128 + vcol * 8, a.fold);
 #pragma unroll
         for (int q = 0; q < 8; ++q) f1[h][q] = f2[h][q] = 0.f;
@@ -2177,7 +2205,7 @@ __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
     if (slab < nslabs) load_a(slab);
     for (; slab < nslabs; slab += nstreams) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < NH; ++h) {
             const int col = nb0 + h * 128 + vcol * 8;
             f32x16 acc[4];
 #pragma unroll
@@ -2192,7 +2220,7 @@ __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
                     acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, cur[ks], acc[j], 0, 0, 0);
                 }
             // the next pass's fragments: this pass has no further use for the registers
-            if (h == 1 && slab + nstreams < nslabs) load_a(slab + nstreams);
+            if (h == NH - 1 && slab + nstreams < nslabs) load_a(slab + nstreams);
             // value (+ addend) -> optional mask and BatchNorm sums -> store, as igemm_ring_kernel's data gradient
             auto finish = [&](int mr, u32x4 o, const u32x4& ad, uint32_t bits, const u32x4& yy) {
                 if (a.addend) {
@@ -2298,7 +2326,7 @@ __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
     if (a.stats) {
         // lanes 16 apart hold the same columns: fold them, then one slot per wavefront, fixed order over the slots
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < NH; ++h)
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 f1[h][q] += __shfl_xor(f1[h][q], 16);
@@ -2308,27 +2336,29 @@ __global__ void __launch_bounds__(512) pw_dgrad_kernel(IgemmArgs a) {
             }
         if (lane < 16) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int h = 0; h < NH; ++h)
 #pragma unroll
                 for (int q = 0; q < 8; ++q) {
-                    s_part[wave * 256 + h * 128 + lane * 8 + q] = f1[h][q];
-                    s_part[(8 + wave) * 256 + h * 128 + lane * 8 + q] = f2[h][q];
+                    s_part[wave * NB + h * 128 + lane * 8 + q] = f1[h][q];
+                    s_part[(8 + wave) * NB + h * 128 + lane * 8 + q] = f2[h][q];
                 }
         }
         __syncthreads();
-        const int stat = tid >> 8, c = tid & 255;
-        float v1 = 0.f, v2 = 0.f;
+        if (tid < 2 * NB) {
+            const int stat = tid / NB, c = tid % NB;
+            float v1 = 0.f, v2 = 0.f;
 #pragma unroll
-        for (int sl = 0; sl < 8; ++sl) {
-            v1 += s_part[sl * 256 + c];
-            v2 += s_part[(8 + sl) * 256 + c];
+            for (int sl = 0; sl < 8; ++sl) {
+                v1 += s_part[sl * NB + c];
+                v2 += s_part[(8 + sl) * NB + c];
+            }
+            if (fuse_bn) v2 = (v2 - a.bn_mean[nb0 + c] * v1) * a.bn_rstd[nb0 + c];
+            const int rows_used = (int)gridDim.x / nsplit;
+            a.stats[((size_t)row_s * 2 + stat) * a.Cd + nb0 + c] = stat ? v2 : v1;
+            // rows beyond the streams: zeros (each block clears its own channels in the rows congruent to its stream)
+            for (int rz = rows_used + row_s; rz < (int)gridDim.x; rz += rows_used)
+                a.stats[((size_t)rz * 2 + stat) * a.Cd + nb0 + c] = 0.f;
         }
-        if (fuse_bn) v2 = (v2 - a.bn_mean[nb0 + c] * v1) * a.bn_rstd[nb0 + c];
-        const int rows_used = (int)gridDim.x / nsplit, row_s = (int)blockIdx.x / nsplit;
-        a.stats[((size_t)row_s * 2 + stat) * a.Cd + nb0 + c] = stat ? v2 : v1;
-        // rows beyond the streams: zeros (block b clears the part of row rows_used + b / nsplit * ... it owns)
-        for (int rz = rows_used + row_s; rz < (int)gridDim.x; rz += rows_used)
-            a.stats[((size_t)rz * 2 + stat) * a.Cd + nb0 + c] = 0.f;
     }
 }
 
@@ -2541,16 +2571,26 @@ static int launch_stem_s(IgemmArgs& a, hipStream_t s) {
 // then launch the same number of blocks, which callers size the statistics rows by) and every wavefront of the grid has
 // at least two passes.  TSM_PW_KERNEL=0 leaves these layers to the general kernel, TSM_PW_MIN_ROWS=<n> moves the
 // threshold (both read at every call: tests and comparisons set them).
-static bool pw_fwd_eligible(const IgemmArgs& a) {
+// (K = 64, 128: a block holds 256 result channels; K = 256: 128.  The threshold counts the passes of the streams that
+// the grid forms: two per wavefront.)
+static int pw_block_channels(int Cs) { return Cs <= 128 ? 256 : 128; }
+static bool pw_shape_ok(const IgemmArgs& a) {
     const char* e = getenv("TSM_PW_KERNEL");
     if (e && e[0] == '0') return false;
-    const char* t = getenv("TSM_PW_MIN_ROWS");
-    const long min_rows = t ? atol(t) : 2L * 32 * 8 * num_cu();
+    if (!((a.Cs == 64 || a.Cs == 128 || a.Cs == 256) && a.pitch == a.Cs && a.KT == 1 && a.KH == 1 && a.KW == 1 && a.stride == 1 &&
+          a.padh == 0 && a.padw == 0 && a.Hs == a.Hd && a.Ws == a.Wd))
+        return false;
+    const int nb = pw_block_channels(a.Cs);
+    if (a.Cd < 256 || a.Cd > 1024 || a.Cd % nb != 0 || a.Cd < 2 * a.Cs) return false;     // wide results only
     const long rows = (long)a.F * a.Hd * a.Wd;
-    return (a.Cs == 64 || a.Cs == 128) && a.pitch == a.Cs && (a.Cd == 256 || a.Cd == 512) && a.KT == 1 && a.KH == 1 && a.KW == 1 &&
-           a.stride == 1 && a.padh == 0 && a.padw == 0 && a.fold == 0 && a.addend == nullptr && a.ep_scale == nullptr &&
-           a.Hs == a.Hd && a.Ws == a.Wd && rows * a.Cs * 2 < 0x7ff00000L &&
-           ring_eligible(a.Cs, rows * a.Cs + a.Cs, (long)a.Cd * a.Cs, false) && ring_rows(rows, a.Cd) == 256 && rows >= min_rows;
+    const char* t = getenv("TSM_PW_MIN_ROWS");
+    const long min_rows = t ? atol(t) : 2L * 32 * 8 * num_cu() / (a.Cd / nb);
+    return rows <= 0x7fffffffL && rows * a.Cs * 2 < 0x7ff00000L && ring_eligible(a.Cs, rows * a.Cs + a.Cs, (long)a.Cd * a.Cs, false) &&
+           ring_rows(rows, a.Cd) == 256 && rows >= min_rows;
+}
+
+static bool pw_fwd_eligible(const IgemmArgs& a) {
+    return pw_shape_ok(a) && a.fold == 0 && a.addend == nullptr && a.ep_scale == nullptr;
 }
 
 template <int KC, bool STREAM>
@@ -2564,7 +2604,7 @@ static int launch_pw_fwd(IgemmArgs& a, hipStream_t s) {
     }
     const long rows = (long)a.F * a.Hd * a.Wd;
     const int grid = igemm_grid((int)((rows + 255) / 256), a.Cd, 128, 1);      // as the general kernel with 256 x 128 tiles
-    if (grid % (a.Cd / 256) != 0) return fail(TSM_ERR_LAUNCH, "pw_fwd: grid does not split over the column halves");
+    if (grid % (a.Cd / PwD<KC>::NB) != 0) return fail(TSM_ERR_LAUNCH, "pw_fwd: grid does not split over the parts of the result");
     hipLaunchKernelGGL(kern, dim3(grid), dim3(512), PwD<KC>::SMEM, s, a);
     return check_launch("igemm_fwd_pw");
 }
@@ -2572,20 +2612,11 @@ static int launch_pw_fwd(IgemmArgs& a, hipStream_t s) {
 // The short-K, wide-result 1x1 data-gradient kernel takes its layers under the same conditions as the forward kernel
 // above; where the epilogue needs a ReLU mask, only with the decision bits (see DgradFuse::act_bits).
 static bool pw_dgrad_eligible(const IgemmArgs& a) {
-    const char* e = getenv("TSM_PW_KERNEL");
-    if (e && e[0] == '0') return false;
-    const char* t = getenv("TSM_PW_MIN_ROWS");
-    const long min_rows = t ? atol(t) : 2L * 32 * 8 * num_cu();
-    const long rows = (long)a.F * a.Hd * a.Wd;
-    if (!((a.Cs == 64 || a.Cs == 128) && a.pitch == a.Cs && (a.Cd == 256 || a.Cd == 512) && a.KT == 1 && a.KH == 1 && a.KW == 1 &&
-          a.stride == 1 && a.padh == 0 && a.padw == 0 && a.Hs == a.Hd && a.Ws == a.Wd && a.fold % 8 == 0))
-        return false;
-    if (a.add_stride == 2 && !(a.addend != nullptr && a.Cs == 128)) return false;   // the compact addend: one variant built
-    if ((long)a.F * a.Hd * a.Wd > 0x7fffffffL) return false;
+    if (!pw_shape_ok(a) || a.fold % 8 != 0) return false;
+    if (a.add_stride == 2 && !(a.addend != nullptr && a.Cs >= 128)) return false;   // the compact addend: variants for K = 128, 256
     if (a.act != nullptr && a.act_bits == nullptr) return false;      // a mask that only the activation can give
     if (a.ybn != nullptr && a.stats == nullptr) return false;
-    return rows * a.Cs * 2 < 0x7ff00000L && ring_eligible(a.Cs, rows * a.Cs + a.Cs, (long)a.Cd * a.Cs, false) &&
-           ring_rows(rows, a.Cd) == 256 && rows >= min_rows;
+    return true;
 }
 
 template <int KC, bool STREAM, bool CADD = false>
@@ -2599,7 +2630,7 @@ static int launch_pw_dgrad(IgemmArgs& a, hipStream_t s) {
     }
     const long rows = (long)a.F * a.Hd * a.Wd;
     const int grid = igemm_grid((int)((rows + 255) / 256), a.Cd, 128, 1);      // as the general kernel with 256 x 128 tiles
-    if (grid % (a.Cd / 256) != 0) return fail(TSM_ERR_LAUNCH, "pw_dgrad: grid does not split over the column halves");
+    if (grid % (a.Cd / PwD<KC>::NB) != 0) return fail(TSM_ERR_LAUNCH, "pw_dgrad: grid does not split over the parts of the result");
     hipLaunchKernelGGL(kern, dim3(grid), dim3(512), PwD<KC>::SMEM, s, a);
     return check_launch("igemm_dgrad_pw");
 }
@@ -2612,13 +2643,18 @@ static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     if (DGRAD && pw_dgrad_eligible(a)) {
         const bool st = rows * a.Cd * 2 > (64L << 20);
         if (a.Cs == 64) return st ? launch_pw_dgrad<64, true>(a, s) : launch_pw_dgrad<64, false>(a, s);
-        if (a.add_stride == 2) return st ? launch_pw_dgrad<128, true, true>(a, s) : launch_pw_dgrad<128, false, true>(a, s);
-        return st ? launch_pw_dgrad<128, true>(a, s) : launch_pw_dgrad<128, false>(a, s);
+        if (a.Cs == 128) {
+            if (a.add_stride == 2) return st ? launch_pw_dgrad<128, true, true>(a, s) : launch_pw_dgrad<128, false, true>(a, s);
+            return st ? launch_pw_dgrad<128, true>(a, s) : launch_pw_dgrad<128, false>(a, s);
+        }
+        if (a.add_stride == 2) return st ? launch_pw_dgrad<256, true, true>(a, s) : launch_pw_dgrad<256, false, true>(a, s);
+        return st ? launch_pw_dgrad<256, true>(a, s) : launch_pw_dgrad<256, false>(a, s);
     }
     if (!DGRAD && pw_fwd_eligible(a)) {
         const bool st = rows * a.Cd * 2 > (64L << 20);
         if (a.Cs == 64) return st ? launch_pw_fwd<64, true>(a, s) : launch_pw_fwd<64, false>(a, s);
-        return st ? launch_pw_fwd<128, true>(a, s) : launch_pw_fwd<128, false>(a, s);
+        if (a.Cs == 128) return st ? launch_pw_fwd<128, true>(a, s) : launch_pw_fwd<128, false>(a, s);
+        return st ? launch_pw_fwd<256, true>(a, s) : launch_pw_fwd<256, false>(a, s);
     }
     if (!DGRAD && stem_eligible(a))
         return rows * a.Cd * 2 > (64L << 20) ? launch_stem_s<true>(a, s) : launch_stem_s<false>(a, s);

@@ -155,6 +155,17 @@ def test_bottleneck_projection_stride2_with_the_pointwise_kernels(monkeypatch):
     assert "igemm_dgrad_pw" in classes, sorted(classes)
 
 
+def test_bottleneck_projection_stride2_with_the_pointwise_kernel_at_256_channels(monkeypatch):
+    """The first block of the third stage (512 -> 256 -> 256 -> 1024, stride 2, projection) on odd 29x29 maps: the data
+    gradient of the first convolution (256 -> 512 channels, split over four blocks per stream) with the projection's
+    gradient in compact form."""
+    monkeypatch.setenv("TSM_PW_MIN_ROWS", "1")
+    B.tsm_profile_begin()
+    run_block("bottleneck", 2, 8, 512, 29, 29, 256, 1024, 2, True, 8, "bf16", "nthwc")
+    classes = B.tsm_profile_end()
+    assert "igemm_dgrad_pw" in classes, sorted(classes)
+
+
 def test_bottleneck_first_of_stage_projection_stride1():
     run_block("bottleneck", 1, 4, 64, 14, 14, 64, 256, 1, True, 8, "bf16", "nthwc")
 

@@ -139,6 +139,8 @@ def test_conv3x3_c64_kernel_every_element(case, monkeypatch):
     (2, 8, 128, 28, 28, 512, 1, 1, 0, 0),    # 128 -> 512 channels: the result is split over pairs of blocks
     (2, 8, 128, 41, 41, 256, 1, 1, 0, 0),    # 128 -> 256 channels, ragged last pass
     (2, 8, 64, 30, 30, 512, 1, 1, 0, 0),     # 64 -> 512 channels
+    (2, 8, 256, 27, 29, 1024, 1, 1, 0, 0),   # 256 -> 1024 channels: blocks of 128 result channels, eight per stream
+    (2, 8, 256, 31, 31, 512, 1, 1, 0, 0),    # 256 -> 512 channels
 ])
 def test_pointwise_forward_kernel_every_element(case, monkeypatch):
     """The short-K, wide-result 1x1 forward kernel (statistics epilogue; one wavefront per 32 pixels, nothing shared but
@@ -157,6 +159,8 @@ def test_pointwise_forward_kernel_every_element(case, monkeypatch):
     (2, 8, 512, 28, 28, 128, 1, 1, 0, 8),    # 128 -> 512 channels: the result is split over pairs of blocks
     (2, 8, 256, 40, 40, 128, 1, 1, 0, 8),    # 128 -> 256 channels
     (2, 8, 256, 57, 57, 64, 1, 1, 0, 0),     # no shift
+    (2, 8, 1024, 27, 29, 256, 1, 1, 0, 8),   # 256 -> 1024 channels of dx: blocks of 128 result channels
+    (2, 8, 512, 31, 31, 256, 1, 1, 0, 8),    # 256 -> 512 channels of dx
 ])
 def test_pointwise_data_gradient_kernel_every_element(case, monkeypatch):
     """The short-K, wide-result 1x1 data-gradient kernel (adjoint shift on the store, zero rows at the clip ends) on
