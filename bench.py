@@ -162,6 +162,32 @@ def class_bytes(F, size, epilogue_reads=True):
     return byt
 
 
+def elementwise_bytes(F, size):
+    """Algorithmic bytes per step of the stand-alone elementwise classes of the train step (bf16 tensors; y_b = one
+    convolution output): what each pass has to read and write once."""
+    byt = {"bn_bwd_apply": 0.0, "block_tail_fwd": 0.0, "bn_relu_apply": 0.0, "relu_bn_bwd_reduce": 0.0}
+    layers = conv_layers(F, size)
+    last_block = layers[-1][0].rsplit(".", 1)[0]
+    for name, rin, cin, rout, cout, taps, has_dgrad in layers:
+        if name == "conv1":
+            continue          # the stem's BatchNorm backward is formed in its weight gradient's loader
+        y_b = 2.0 * rout * cout
+        blk, lay = name.rsplit(".", 1)
+        proj = any(n == blk + ".ds" for n, *_ in layers)
+        # BatchNorm backward map dy = a*dz + b*y + c: two tensors in, one out; a projection's map shares the read of
+        # the upstream gradient with the block's last layer
+        byt["bn_bwd_apply"] += 2.0 * y_b if lay == "ds" else 3.0 * y_b
+        if lay in ("c1", "c2"):
+            byt["bn_relu_apply"] += 2.0 * y_b                     # z = ReLU(BatchNorm(y))
+        if lay == "c3":
+            byt["block_tail_fwd"] += 3.0 * y_b + y_b / 16.0       # BatchNorm output + shortcut -> ReLU, decision bits
+            if proj:
+                byt["relu_bn_bwd_reduce"] += 3.0 * y_b            # masked gradient and the two BatchNorm inputs
+            elif blk == last_block:
+                byt["relu_bn_bwd_reduce"] += 4.0 * y_b            # gradient, block output, BatchNorm input in; dz out
+    return byt
+
+
 def measured_traffic(clips):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, scaled by
     the copy-kernel calibration stated there); None when no summary for this workload is committed."""
@@ -456,10 +482,25 @@ def main():
     eager()
     prof = B.tsm_profile_end()
     work = class_work(N * T, S)
-    dom = max(prof, key=lambda k: prof[k][1])
-    n_launch, dom_ms = prof[dom]
+    ew_bytes = elementwise_bytes(N * T, S)
     traffic = measured_traffic(N)
-    if dom in work:
+
+    def class_roofline(dom):
+        n_launch, dom_ms = prof[dom]
+        if dom in work:
+            return conv_roofline(dom, n_launch, dom_ms)
+        if dom in ew_bytes:    # an elementwise pass: bytes at the HBM peak
+            gbs = ew_bytes[dom] / (dom_ms * 1e-3) / 1e9
+            return {"bound": "hbm", "kernel": dom, "launches_per_step": n_launch, "avg_launch_ms": dom_ms / n_launch,
+                    "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                    "traffic": traffic.get(dom),
+                    "traffic_source": "committed rocprofv3 --pmc summary under profiles/ (not measured in this run)"
+                                      if traffic.get(dom) is not None else None,
+                    "algorithmic_bytes_per_launch": ew_bytes[dom] / n_launch}
+        return {"bound": "hbm", "kernel": dom, "launches_per_step": n_launch, "avg_launch_ms": dom_ms / n_launch,
+                "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": None, "traffic": None}
+
+    def conv_roofline(dom, n_launch, dom_ms):
         # the bound is the larger of the class's two floors: algorithmic FLOPs at the MFMA peak, algorithmic
         # bytes at the HBM peak
         tflops = work[dom] / (dom_ms * 1e-3) / 1e12
@@ -468,7 +509,7 @@ def main():
         gbs = alg_bytes / (dom_ms * 1e-3) / 1e9
         t_mfma, t_hbm = work[dom] / (PEAK_BF16_TFLOPS * 1e12), alg_bytes / (PEAK_HBM_GBS * 1e9)
         hbm_bound = t_hbm > t_mfma
-        roof = {"bound": "hbm" if hbm_bound else "mfma", "kernel": dom, "launches_per_step": n_launch,
+        return {"bound": "hbm" if hbm_bound else "mfma", "kernel": dom, "launches_per_step": n_launch,
                 "avg_launch_ms": dom_ms / n_launch,
                 "achieved": gbs if hbm_bound else tflops, "peak": PEAK_HBM_GBS if hbm_bound else PEAK_BF16_TFLOPS,
                 "unit": "GB/s" if hbm_bound else "TFLOP/s",
@@ -485,9 +526,11 @@ def main():
                 # operand and result alone
                 "frac_conv_bytes_only": conv_bytes / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                 "conv_bytes_per_launch": conv_bytes / n_launch}
-    else:
-        roof = {"bound": "hbm", "kernel": dom, "launches_per_step": n_launch, "avg_launch_ms": dom_ms / n_launch,
-                "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": None, "traffic": None}
+
+    # the dominant class of the step, and (where that is an elementwise pass) the largest convolution class beside it
+    roof = class_roofline(max(prof, key=lambda k: prof[k][1]))
+    conv_dom = max((k for k in prof if k in work), key=lambda k: prof[k][1])
+    roof_conv = class_roofline(conv_dom)
     prof_total = sum(v[1] for v in prof.values())
     classes = {k: {"launches": v[0], "ms": round(v[1], 4),
                    "tflops": round(work[k] / (v[1] * 1e-3) / 1e12, 1) if k in work else None}
@@ -506,7 +549,7 @@ def main():
         "pct_bf16_mfma_peak": 100.0 * flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "loss_before": first_loss, "loss_after": final_loss, "wall_s": wall, "hip_graph": bool(args.graph), "wgrad_overlap": not args.no_overlap,
-        "roofline": roof, "kernel_classes": classes, "profiled_step_ms": prof_total,
+        "roofline": roof, "roofline_largest_conv_class": roof_conv, "kernel_classes": classes, "profiled_step_ms": prof_total,
     }
 
     # the stand-alone shift (a pure gather copy) at the configs[1] activation shape x 64 clips: HBM GB/s

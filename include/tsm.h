@@ -40,8 +40,9 @@
  *    TSM_FUSED_TAIL_MIN_TILES=<n> replaces the number of 256-pixel tiles from
  *    which the two-convolution kernel is chosen (default: three per four
  *    compute units); TSM_PW_KERNEL=0 (read at every call) leaves the short-K 1x1
- *    layers that have kernels of their own (64 or 128 -> 256 or 512 channels:
- *    forward, and the data gradient of a block's first convolution) to the
+ *    layers that have kernels of their own (64, 128 or 256 channels into a result
+ *    at least twice as wide, up to 1024 channels: forward, and the data gradient
+ *    of a block's first convolution) to the
  *    general kernel and TSM_PW_MIN_ROWS=<n> replaces the number of pixels from
  *    which their own kernel is chosen (default: two passes of 32 pixels per
  *    wavefront of the grid); TSM_WGRAD_XCD=0 (read at every call) launches the
