@@ -44,11 +44,11 @@ def conv_layers(F, size):
 
 def pw_layer(cs, cd, rows):
     """Shapes the short-K, wide-result 1x1 kernels take: K of 64, 128 or 256 channels, a result at least twice as wide
-    (a block holds 256 of its channels, 128 at K = 256), two passes of 32 pixels per wavefront of the grid."""
+    (a block holds 256 of its channels, 128 at K = 256), a pass of 32 pixels for every wavefront of the grid."""
     if cs not in (64, 128, 256) or not 256 <= cd <= 1024 or cd < 2 * cs:
         return False
     nb = 256 if cs <= 128 else 128
-    return cd % nb == 0 and rows >= 2 * 32 * 8 * 256 // (cd // nb)
+    return cd % nb == 0 and rows >= 32 * 8 * 256 // (cd // nb)
 
 
 def igemm_class(kind, cd, cs, rows, taps=1, stride=1):

@@ -44,7 +44,7 @@
  *    at least twice as wide, up to 1024 channels: forward, and the data gradient
  *    of a block's first convolution) to the
  *    general kernel and TSM_PW_MIN_ROWS=<n> replaces the number of pixels from
- *    which their own kernel is chosen (default: two passes of 32 pixels per
+ *    which their own kernel is chosen (default: one pass of 32 pixels per
  *    wavefront of the grid); TSM_WGRAD_XCD=0 (read at every call) launches the
  *    weight gradient's tiles in chunk-fastest order instead of grouping the
  *    tiles of one pixel chunk on one XCD; TSM_MASK_BITS=0 (read once per process) makes the train

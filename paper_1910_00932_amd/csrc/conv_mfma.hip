@@ -2569,10 +2569,11 @@ static int launch_stem_s(IgemmArgs& a, hipStream_t s) {
 
 // The short-K 1x1 forward kernel takes its layers when the general kernel would run them with 256-row tiles (the two
 // then launch the same number of blocks, which callers size the statistics rows by) and every wavefront of the grid has
-// at least two passes.  TSM_PW_KERNEL=0 leaves these layers to the general kernel, TSM_PW_MIN_ROWS=<n> moves the
-// threshold (both read at every call: tests and comparisons set them).
+// a pass of its own (measured at 8 clips: 6.92 -> 6.83 ms against a threshold of two passes).  TSM_PW_KERNEL=0 leaves
+// these layers to the general kernel, TSM_PW_MIN_ROWS=<n> moves the threshold (both read at every call: tests and
+// comparisons set them).
 // (K = 64, 128: a block holds 256 result channels; K = 256: 128.  The threshold counts the passes of the streams that
-// the grid forms: two per wavefront.)
+// the grid forms.)
 static int pw_block_channels(int Cs) { return Cs <= 128 ? 256 : 128; }
 static bool pw_shape_ok(const IgemmArgs& a) {
     const char* e = getenv("TSM_PW_KERNEL");
@@ -2584,7 +2585,7 @@ static bool pw_shape_ok(const IgemmArgs& a) {
     if (a.Cd < 256 || a.Cd > 1024 || a.Cd % nb != 0 || a.Cd < 2 * a.Cs) return false;     // wide results only
     const long rows = (long)a.F * a.Hd * a.Wd;
     const char* t = getenv("TSM_PW_MIN_ROWS");
-    const long min_rows = t ? atol(t) : 2L * 32 * 8 * num_cu() / (a.Cd / nb);
+    const long min_rows = t ? atol(t) : 32L * 8 * num_cu() / (a.Cd / nb);
     return rows <= 0x7fffffffL && rows * a.Cs * 2 < 0x7ff00000L && ring_eligible(a.Cs, rows * a.Cs + a.Cs, (long)a.Cd * a.Cs, false) &&
            ring_rows(rows, a.Cd) == 256 && rows >= min_rows;
 }
