@@ -51,10 +51,11 @@ def pw_layer(cs, cd, rows):
     return cd % nb == 0 and rows >= 32 * 8 * 256 // (cd // nb)
 
 
-def igemm_class(kind, cd, cs, rows, taps=1, stride=1):
+def igemm_class(kind, cd, cs, rows, taps=1, stride=1, affine=False):
     """Kernel and tile the library picks for a forward ("fwd") or data-gradient ("dgrad") convolution that produces
     `rows` pixels of `cd` channels from `cs` source channels (tensors below 2 GiB, which holds for every workload
-    here; 256 CUs)."""
+    here; 256 CUs).  affine: a forward layer with the affine epilogue of the inference path, which the kernels that
+    only carry the statistics epilogue do not take."""
     if stride == "stem":      # the space-to-depth stem: its own kernel from five rounds of tiles on
         return "igemm_fwd_stem" if -(-rows // 256) >= 5 * 256 else "igemm_fwd_256x64"
     if cs % 64 == 0:
@@ -62,8 +63,10 @@ def igemm_class(kind, cd, cs, rows, taps=1, stride=1):
         r = "r128" if tiles256 * 4 < 256 * 3 else "256"
         if cs == 64 and cd == 64 and taps == 9 and stride == 1 and -(-rows // 256) >= 5 * 256:
             return "igemm_%s_c64" % kind      # the 64 -> 64 channel 3x3 kernel (five rounds of tiles or more)
-        if kind == "fwd" and taps == 1 and stride == 1 and r == "256" and pw_layer(cs, cd, rows):
+        if kind == "fwd" and not affine and taps == 1 and stride == 1 and r == "256" and pw_layer(cs, cd, rows):
             return "igemm_fwd_pw"             # the short-K 1x1 forward kernel
+        if kind == "fwd" and not affine and cd % 256 == 0 and r == "256" and -(-rows // 256) * (cd // 256) * 4 >= 256 * 3:
+            return "igemm_fwd_256x256"        # wide results: 256-column tiles from three quarters of a round on
         # 64 columns per tile for narrow outputs, and where even 128x128 tiles leave a quarter of the CUs idle
         narrow = cd <= 64 or (r == "r128" and -(-rows // 128) * -(-cd // 128) * 4 < 256 * 3)
         return "igemm_%s_%sx%s" % (kind, r, "64" if narrow else "128")
@@ -327,7 +330,7 @@ def infer_workload(args, torch, B, I):
     fused_on = os.environ.get("TSM_FUSED_TAIL", "1")[:1] != "0"
     for name, rin, cin, rout, cout, taps, _ in conv_layers(F, S):
         stem = name == "conv1"
-        cls = igemm_class("fwd", cout, 64 if stem else cin, rout, taps, "stem" if stem else (1 if rin == rout else 2))
+        cls = igemm_class("fwd", cout, 64 if stem else cin, rout, taps, "stem" if stem else (1 if rin == rout else 2), affine=True)
         x_b = 2.0 * F * (S // 2 + 3) ** 2 * 16 if stem else 2.0 * rin * cin
         res_b = 2.0 * rout * cout if name.endswith(".c3") else 0.0     # the shortcut read by the epilogue
         y_b = 2.0 * rout * cout

@@ -500,9 +500,15 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
     static_assert((HM * LDC * 2) % 16 == 0, "alignment of the regions behind the staging tile");
     static_assert(sizeof(RowInfo) == 16, "one 16-byte LDS read per row");
 
+    // 256-column tiles (forward, statistics epilogue only): the two stages take 128 KB, so the staging tile of the
+    // epilogue lies in the stage that the tile's last K step was multiplied from.  Behind the barrier of that step no
+    // wavefront reads it any more, and the next tile's steps are not written into it before the barrier at the top of
+    // the next tile, which every wavefront reaches after its last read of the staging tile.
+    constexpr bool ALIAS = BN == 256;
+    static_assert(!ALIAS || (!DGRAD && HM * LDC * 2 <= STAGE), "the staging tile must fit a stage");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    bf16_t* Cst = (bf16_t*)(smem + NS * STAGE);      // [HM][LDC] staging tile of the epilogue
-    float* s_part = (float*)(Cst + HM * LDC);        // [2 stats][WM*2 slots][BN] statistics slots
+    bf16_t* Cst = (bf16_t*)(smem + NS * STAGE);      // [HM][LDC] staging tile of the epilogue (ALIAS: set per tile)
+    float* s_part = ALIAS ? (float*)(smem + NS * STAGE) : (float*)(Cst + HM * LDC);   // [2 stats][WM*2 slots][BN] statistics slots
     RowInfo* s_row = (RowInfo*)(s_part + 2 * NSLOT * BN);   // [2][BM]: rows of the current and of the next tile
     int* s_arow = (int*)(s_row + 2 * BM);                   // [2][BM]: row of a compact addend (-1: none), dgrad only
 
@@ -820,7 +826,8 @@ __global__ void __launch_bounds__(WM * WN * 64) igemm_ring_kernel(IgemmArgs a) {
         // stage already hold the first two K steps of the next tile.
         // fused BatchNorm backward: this thread stores the same eight columns of every row it handles
         // (forward with an affine epilogue keeps scale / shift of the same eight columns in mu / rs)
-        const bool affine = !DGRAD && a.ep_scale != nullptr;
+        if (ALIAS) Cst = (bf16_t*)(smem + (cstage ^ 1) * STAGE);
+        const bool affine = !DGRAD && !ALIAS && a.ep_scale != nullptr;
         float mu[FV], rs[FV];
 #pragma unroll
         for (int q = 0; q < FV; ++q) mu[q] = rs[q] = 0.f;
@@ -2396,8 +2403,10 @@ static int launch_igemm_ring_s(IgemmArgs& a, const char* name, hipStream_t s) {
     const int mtiles = setup_classes(a, DGRAD, BM);
     a.ntiles = (a.Cd + BN - 1) / BN;
     // two operand stages, staging tile of one epilogue pass, statistics slots, two row buffers
-    const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t) + (size_t)(WM * 32) * (BN + 8) * sizeof(bf16_t) +
+    const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t) + (BN == 256 ? 0 : (size_t)(WM * 32) * (BN + 8) * sizeof(bf16_t)) +
                         (size_t)2 * WM * WN * BN * sizeof(float) + (size_t)2 * BM * sizeof(RowInfo) + (size_t)2 * BM * sizeof(int);
+    static_assert((size_t)2 * (BM + BN) * BK * sizeof(bf16_t) + (BN == 256 ? 0 : (size_t)(WM * 32) * (BN + 8) * sizeof(bf16_t)) +
+                  (size_t)2 * WM * WN * BN * sizeof(float) + (size_t)2 * BM * sizeof(RowInfo) + (size_t)2 * BM * sizeof(int) <= 160 * 1024, "LDS budget");
     auto kern = igemm_ring_kernel<BM, BN, WM, WN, DGRAD, STREAM, CADD, MBITS>;
     static bool configured = false;
     if (!configured) {
@@ -2636,6 +2645,25 @@ static int launch_pw_dgrad(IgemmArgs& a, hipStream_t s) {
     return check_launch("igemm_dgrad_pw");
 }
 
+// Forward layers whose result is a multiple of 256 channels wide take 256 x 256 tiles (wavefront tiles of 128 x 64:
+// three quarters of the LDS fragment bytes and two thirds of the operand stream per MFMA of the 256 x 128 tile) when
+// the general kernel would run them with 256-row tiles, no kernel of their own takes them, they have no affine
+// epilogue (the variant keeps the statistics epilogue only) and the wide tiles still give three quarters of the CUs
+// a tile.  TSM_IGEMM_WIDE=0 (read at every call) keeps 128 columns, TSM_IGEMM_WIDE_MIN_TILES=<n> replaces the number
+// of wide tiles from which they are chosen (tests and comparisons set them).
+static bool wide_fwd_eligible(const IgemmArgs& a) {
+    const char* e = getenv("TSM_IGEMM_WIDE");
+    if (e && e[0] == '0') return false;
+    const char* t = getenv("TSM_IGEMM_WIDE_MIN_TILES");
+    const long min_tiles = t ? atol(t) : ((long)num_cu() * 3 + 3) / 4;
+    const long rows = (long)a.F * a.Hd * a.Wd;
+    if (a.Cd % 256 != 0 || a.ep_scale != nullptr || a.addend != nullptr || a.pitch != a.Cs) return false;
+    if (pw_fwd_eligible(a)) return false;
+    if (!ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K, false)) return false;
+    if (ring_rows(rows, a.Cd) != 256) return false;
+    return ((rows + 255) / 256) * (a.Cd / 256) >= min_tiles;
+}
+
 template <bool DGRAD>
 static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     const long rows = (long)a.F * a.Hd * a.Wd;
@@ -2660,6 +2688,9 @@ static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     if (!DGRAD && stem_eligible(a))
         return rows * a.Cd * 2 > (64L << 20) ? launch_stem_s<true>(a, s) : launch_stem_s<false>(a, s);
     if (ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K, a.pitch != a.Cs)) {
+        if constexpr (!DGRAD) {
+            if (wide_fwd_eligible(a)) return launch_igemm_ring<256, 256, 2, 4, false>(a, "igemm_fwd_256x256", s);
+        }
         int bm, bn;
         ring_tile(a, &bm, &bn);
         if (bm == 128) {
@@ -2674,8 +2705,25 @@ static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     return launch_igemm<128, 128, 2, 2, DGRAD, 1, 2>(a, DGRAD ? "igemm_dgrad_128x128" : "igemm_fwd_128x128", s);
 }
 
+static void fwd_args(const ConvP& p, IgemmArgs& a) {
+    a.F = p.F; a.T = p.T;
+    a.Hs = p.H; a.Ws = p.W; a.Cs = p.Cin; a.pitch = p.pix_pitch();
+    a.Hd = p.Ho; a.Wd = p.Wo; a.Cd = p.Cout;
+    a.KT = p.KT; a.KH = p.KH; a.KW = p.KW;
+    a.stride = p.stride; a.padh = p.pad; a.padw = p.pad;
+    a.fold = p.fold;
+    a.K = (int)p.K();
+}
+
+// Blocks the forward convolution with the statistics epilogue launches (= partial rows it writes).
 int conv_mfma_fwd_blocks(const ConvP& p) {
     const int bn = p.Cout <= 64 ? 64 : 128;
+    {
+        IgemmArgs a;
+        a.addend = nullptr; a.ep_scale = nullptr;
+        fwd_args(p, a);
+        if (wide_fwd_eligible(a)) return igemm_grid((int)((p.rows_out() + 255) / 256), p.Cout, 256, 1);
+    }
     if (ring_eligible(p.Cin, p.rows_in() * (long)p.pix_pitch() + p.Cin + (long)(p.pad * p.W + p.pad) * p.pix_pitch(), (long)p.Cout * p.K(), p.pix_pitch() != p.Cin))
     {
         const int bm = ring_rows(p.rows_out(), p.Cout), bnn = ring_cols(p.rows_out(), p.Cout);
@@ -2699,13 +2747,7 @@ int conv_mfma_fwd(const ConvP& p, const bf16_t* x, const bf16_t* wp, bf16_t* y, 
         if (!conv_mfma_fwd_can_fuse(p)) return fail(TSM_ERR_UNSUPPORTED, "conv forward: this layer's kernel has no affine epilogue");
         a.ep_scale = ep->scale; a.ep_shift = ep->shift; a.ep_res = ep->res; a.ep_relu = ep->relu;
     }
-    a.F = p.F; a.T = p.T;
-    a.Hs = p.H; a.Ws = p.W; a.Cs = p.Cin; a.pitch = p.pix_pitch();
-    a.Hd = p.Ho; a.Wd = p.Wo; a.Cd = p.Cout;
-    a.KT = p.KT; a.KH = p.KH; a.KW = p.KW;
-    a.stride = p.stride; a.padh = p.pad; a.padw = p.pad;
-    a.fold = p.fold;
-    a.K = (int)p.K();
+    fwd_args(p, a);
     return dispatch_igemm<false>(a, s);
 }
 

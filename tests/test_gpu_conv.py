@@ -134,6 +134,23 @@ def test_conv3x3_c64_kernel_every_element(case, monkeypatch):
 
 
 @pytest.mark.parametrize("case", [
+    (2, 8, 64, 40, 40, 256, 3, 1, 1, 0),     # 3x3, 64 -> 256 channels: one column tile, nine K steps
+    (2, 8, 512, 40, 40, 256, 1, 1, 0, 8),    # shifted 1x1, 512 -> 256 channels: eight K steps
+    (4, 8, 128, 57, 57, 256, 3, 2, 1, 0),    # strided 3x3, 26912 pixels: a ragged last tile, an odd number of K steps
+    (2, 8, 512, 31, 31, 512, 1, 1, 0, 8),    # two column tiles
+])
+def test_forward_with_256_column_tiles_every_element(case, monkeypatch):
+    """Forward layers whose result is a multiple of 256 channels wide on 256 x 256 tiles (the staging tile of the
+    epilogue lies in the operand stage that the last K step has left; statistics epilogue), on sizes the oracle covers
+    element by element; the library would give so few tiles to 128-column tiles, the threshold is moved."""
+    monkeypatch.setenv("TSM_IGEMM_WIDE_MIN_TILES", "1")
+    B.tsm_profile_begin()
+    _run(case, "bf16", "nthwc")
+    classes = B.tsm_profile_end()
+    assert "igemm_fwd_256x256" in classes, sorted(classes)
+
+
+@pytest.mark.parametrize("case", [
     (2, 4, 64, 57, 57, 256, 1, 1, 0, 0),     # 25992 pixels: a ragged last pass of 8 pixels
     (3, 8, 64, 33, 35, 256, 1, 1, 0, 0),     # 27720 pixels, H != W; some wavefronts get one pass more than others
     (2, 8, 128, 28, 28, 512, 1, 1, 0, 0),    # 128 -> 512 channels: the result is split over pairs of blocks
