@@ -65,8 +65,8 @@ def igemm_class(kind, cd, cs, rows, taps=1, stride=1, affine=False):
             return "igemm_%s_c64" % kind      # the 64 -> 64 channel 3x3 kernel (five rounds of tiles or more)
         if kind == "fwd" and not affine and taps == 1 and stride == 1 and r == "256" and pw_layer(cs, cd, rows):
             return "igemm_fwd_pw"             # the short-K 1x1 forward kernel
-        if kind == "fwd" and not affine and cd % 256 == 0 and r == "256" and -(-rows // 256) * (cd // 256) * 4 >= 256 * 3:
-            return "igemm_fwd_256x256"        # wide results: 256-column tiles from three quarters of a round on
+        if kind == "fwd" and not affine and cd % 256 == 0 and r == "256" and -(-rows // 256) * (cd // 256) * 2 >= 256:
+            return "igemm_fwd_256x256"        # wide results: 256-column tiles from half a round on
         # 64 columns per tile for narrow outputs, and where even 128x128 tiles leave a quarter of the CUs idle
         narrow = cd <= 64 or (r == "r128" and -(-rows // 128) * -(-cd // 128) * 4 < 256 * 3)
         return "igemm_%s_%sx%s" % (kind, r, "64" if narrow else "128")

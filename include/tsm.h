@@ -36,7 +36,7 @@
  *    follows from the number of tiles per compute unit; TSM_IGEMM_WIDE=0 (read at
  *    every call) keeps 128-column tiles for the forward layers that would run on
  *    256-column tiles (results that are a multiple of 256 channels wide,
- *    statistics epilogue, from three quarters of a round of such tiles on:
+ *    statistics epilogue, from half a round of such tiles on:
  *    TSM_IGEMM_WIDE_MIN_TILES=<n> replaces that number); TSM_IGEMM_NARROW=0 (read once
  *    per process) keeps 128-column tiles where the library would take 64
  *    columns to fill the machine; TSM_FUSED_TAIL=0 (read

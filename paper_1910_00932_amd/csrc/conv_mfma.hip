@@ -2648,14 +2648,14 @@ static int launch_pw_dgrad(IgemmArgs& a, hipStream_t s) {
 // Forward layers whose result is a multiple of 256 channels wide take 256 x 256 tiles (wavefront tiles of 128 x 64:
 // three quarters of the LDS fragment bytes and two thirds of the operand stream per MFMA of the 256 x 128 tile) when
 // the general kernel would run them with 256-row tiles, no kernel of their own takes them, they have no affine
-// epilogue (the variant keeps the statistics epilogue only) and the wide tiles still give three quarters of the CUs
-// a tile.  TSM_IGEMM_WIDE=0 (read at every call) keeps 128 columns, TSM_IGEMM_WIDE_MIN_TILES=<n> replaces the number
+// epilogue (the variant keeps the statistics epilogue only) and the wide tiles still give half of the CUs a tile
+// (measured: better from 148 tiles on, worse at 98).  TSM_IGEMM_WIDE=0 (read at every call) keeps 128 columns, TSM_IGEMM_WIDE_MIN_TILES=<n> replaces the number
 // of wide tiles from which they are chosen (tests and comparisons set them).
 static bool wide_fwd_eligible(const IgemmArgs& a) {
     const char* e = getenv("TSM_IGEMM_WIDE");
     if (e && e[0] == '0') return false;
     const char* t = getenv("TSM_IGEMM_WIDE_MIN_TILES");
-    const long min_tiles = t ? atol(t) : ((long)num_cu() * 3 + 3) / 4;
+    const long min_tiles = t ? atol(t) : ((long)num_cu() + 1) / 2;
     const long rows = (long)a.F * a.Hd * a.Wd;
     if (a.Cd % 256 != 0 || a.ep_scale != nullptr || a.addend != nullptr || a.pitch != a.Cs) return false;
     if (pw_fwd_eligible(a)) return false;
