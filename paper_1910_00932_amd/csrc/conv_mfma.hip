@@ -2539,6 +2539,157 @@ static int launch_c64(IgemmArgs& a, hipStream_t s) {
     return launch_c64_s<DGRAD, false>(a, s);
 }
 
+// ---------------------------------------------------------------------------------
+// The stem in space-to-depth form, forward with the statistics epilogue, one wavefront per 32 output pixels (the scheme
+// of pw_fwd_kernel): the layer writes 128 bytes per output pixel and reads a fifth of that, so it is a stream of stores
+// with a product attached (K = 256: 32 MFMAs per pass), and in the block-wide schedule of stem_s2d_kernel the eight
+// wavefronts wait on each other between the patch, the product and the two epilogue passes.  Here the weights (32 KB)
+// sit in LDS for the life of the block; a wavefront reads the sixteen 16-byte fragments of its pixels straight from
+// memory (tap row th, pixel ks of the row's four, half lane / 32: neighbouring output pixels share three of their four
+// input pixels per row, which the caches serve), multiplies, passes the 32 x 64 result through a staging tile of its
+// own and stores 128 contiguous bytes per pixel; the next pass's fragments are requested before this pass is
+// multiplied.  No block barrier in the loop.  Partial rows (a.stats): one per block, [2][64].
+static constexpr int SPW_LDC = 64 + 8;
+static constexpr int SPW_CST_BYTES = 32 * SPW_LDC * 2;        // per wavefront
+static constexpr int SPW_SMEM = STEM_W_BYTES + 8 * SPW_CST_BYTES + 2 * 8 * 64 * 4;
+
+template <bool STREAM>
+__global__ void __launch_bounds__(512) stem_pw_kernel(IgemmArgs a) {
+    constexpr int LDC = SPW_LDC;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* s_w = smem;                                                       // [4][64][8 positions of 16 bytes], swizzled
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    bf16_t* Cst = (bf16_t*)(smem + STEM_W_BYTES + wave * SPW_CST_BYTES);             // [32][LDC], this wavefront's
+    float* s_part = (float*)(smem + STEM_W_BYTES + 8 * SPW_CST_BYTES);               // [2 stats][8 wavefronts][64]
+    const int r = lane & 31, hi = lane >> 5;
+    const int Ws = a.Ws, Wd = a.Wd, hw_d = a.Hd * a.Wd, hw_s = a.Hs * a.Ws;
+    const unsigned M = (unsigned)a.F * (unsigned)hw_d;            // output pixels
+    const unsigned Min = (unsigned)a.F * (unsigned)hw_s;          // input pixels
+    const bool do_stats = a.stats != nullptr;
+
+    {
+        const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(a.wp, (uint32_t)(64 * 256 * 2));
+#pragma unroll
+        for (int sidx = 0; sidx < 4; ++sidx) {
+            const int q = tid + sidx * 512;                       // piece: tap row sidx, channel row n, position pos
+            const int n = (q >> 3) & 63, pos = q & 7, kv = pos ^ ((n >> 1) & 7);
+            *(u32x4*)(s_w + q * 16) = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, n * 512 + sidx * 128 + kv * 16, 0, 0);
+        }
+    }
+    __syncthreads();
+
+    int b_rd[4];                                                   // fragment of weight rows 32*j + r, step ks of a tap row
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) b_rd[ks] = r * 128 + (((2 * ks + hi) ^ ((r >> 1) & 7)) * 16);
+    const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(a.src, (uint32_t)((long)Min * 32));
+    const unsigned nslabs = (M + 31) / 32;
+    const unsigned nwaves = gridDim.x * 8;
+    bf16x8 cur[16], nxt[16];
+    auto load_a = [&](unsigned sl, bf16x8* fr) {
+        const unsigned P = sl * 32 + (unsigned)r;
+        unsigned base = OOB_OFFSET;
+        if (P < M) {
+            const unsigned f = P / (unsigned)hw_d, q = P - f * (unsigned)hw_d;
+            const unsigned h = q / (unsigned)Wd, w = q - h * (unsigned)Wd;
+            base = (f * (unsigned)hw_s + h * (unsigned)Ws + w) * 32u + (unsigned)hi * 16u;
+        }
+#pragma unroll
+        for (int th = 0; th < 4; ++th)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, P < M ? (int)(base + (unsigned)(th * Ws + ks) * 32u) : (int)OOB_OFFSET, 0, 0);
+                fr[th * 4 + ks] = __builtin_bit_cast(bf16x8, v);
+            }
+    };
+    float f1[8], f2[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) f1[q] = f2[q] = 0.f;
+    const int vcol = lane & 7, row0 = lane >> 3;                   // store loop: piece lane + 64*t is row row0 + 8*t, vector vcol
+
+    unsigned slab = blockIdx.x * 8 + (unsigned)wave;
+    if (slab < nslabs) load_a(slab, cur);
+    for (; slab < nslabs; slab += nwaves) {
+        if (slab + nwaves < nslabs) load_a(slab + nwaves, nxt);    // in flight while this pass is multiplied and stored
+        f32x16 acc[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+#pragma unroll
+        for (int th = 0; th < 4; ++th)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const bf16x8 bfrag = *(const bf16x8*)(s_w + th * (64 * 128) + j * 32 * 128 + b_rd[ks]);
+                    // operands swapped as in igemm_ring_kernel: the result block is [channel][pixel]
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, cur[th * 4 + ks], acc[j], 0, 0, 0);
+                }
+        // lane: pixel r, channels 32*j + 8*q + 4*hi + {0..3}
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            bf16_t* dstp = Cst + r * LDC + j * 32 + 4 * hi;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint2 w;
+                w.x = pack_bf16x2(acc[j][4 * q], acc[j][4 * q + 1]);
+                w.y = pack_bf16x2(acc[j][4 * q + 2], acc[j][4 * q + 3]);
+                *(uint2*)(dstp + 8 * q) = w;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();                           // (LDS serves a wavefront's accesses in order)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int row = row0 + 8 * t;
+            const unsigned P = slab * 32 + (unsigned)row;
+            const u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
+            if (P < M) {
+                if (do_stats) {   // statistics of the values as stored
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float lo = __uint_as_float(v[e] << 16), hv = __uint_as_float(v[e] & 0xffff0000u);
+                        f1[2 * e] += lo;
+                        f1[2 * e + 1] += hv;
+                        f2[2 * e] = fmaf(lo, lo, f2[2 * e]);
+                        f2[2 * e + 1] = fmaf(hv, hv, f2[2 * e + 1]);
+                    }
+                }
+                u32x4* q = (u32x4*)(a.dst + (long)P * 64 + vcol * 8);
+                if (STREAM) __builtin_nontemporal_store(v, q);
+                else *q = v;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int q = 0; q < 16; ++q) cur[q] = nxt[q];
+    }
+    if (do_stats) {
+        // lanes 8 apart hold the same columns: fold them, then one slot per wavefront, fixed order over the slots
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+#pragma unroll
+            for (int off = 8; off < 64; off <<= 1) {
+                f1[q] += __shfl_xor(f1[q], off);
+                f2[q] += __shfl_xor(f2[q], off);
+            }
+        if (lane < 8) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                s_part[wave * 64 + lane * 8 + q] = f1[q];
+                s_part[(8 + wave) * 64 + lane * 8 + q] = f2[q];
+            }
+        }
+        __syncthreads();
+        if (tid < 128) {
+            const int stat = tid >> 6, c = tid & 63;
+            float v = 0.f;
+#pragma unroll
+            for (int sl = 0; sl < 8; ++sl) v += s_part[(stat * 8 + sl) * 64 + c];
+            a.stats[((size_t)blockIdx.x * 2 + stat) * 64 + c] = v;
+        }
+    }
+}
+
 // The stem kernel: the space-to-depth stem (forward), under the same conditions as the 64-channel 3x3 kernel and
 // the same switches; the worst-case patch of a tile (output rows crossed, a frame boundary crossed) must fit.
 static bool stem_eligible(const IgemmArgs& a) {
@@ -2559,6 +2710,23 @@ static bool stem_eligible(const IgemmArgs& a) {
     const long worst = (rows_crossed + 3 * frames_crossed) * a.Ws + (a.Wd - 1) + 3L * a.Ws + 4;
     return worst <= STEM_PMAX && (rows + STEM_BM - 1) / STEM_BM >= min_tiles && (long)a.F * a.Hs * a.Ws * 32 < 0x7ff00000L &&
            ring_eligible(64, (long)a.F * a.Hs * a.Ws * 16 + 64, 64L * a.K, true) && ring_rows(rows, 64) == 256;
+}
+
+// (the wavefront-per-32-pixels variant takes the training forward pass: statistics epilogue only; TSM_STEM_PW=0,
+//  read at every call, keeps the block-wide kernel)
+template <bool STREAM>
+static int launch_stem_pw(IgemmArgs& a, hipStream_t s) {
+    auto kern = stem_pw_kernel<STREAM>;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return fail(TSM_ERR_LAUNCH, "stem_pw: cannot raise dynamic LDS limit");
+        configured = true;
+    }
+    const long rows = (long)a.F * a.Hd * a.Wd;
+    const int grid = igemm_grid((int)((rows + STEM_BM - 1) / STEM_BM), 64, 64, 1);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), SPW_SMEM, s, a);
+    return check_launch("igemm_fwd_stem");
 }
 
 template <bool STREAM>
@@ -2685,8 +2853,12 @@ static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
         if (a.Cs == 128) return st ? launch_pw_fwd<128, true>(a, s) : launch_pw_fwd<128, false>(a, s);
         return st ? launch_pw_fwd<256, true>(a, s) : launch_pw_fwd<256, false>(a, s);
     }
-    if (!DGRAD && stem_eligible(a))
+    if (!DGRAD && stem_eligible(a)) {
+        const char* pe = getenv("TSM_STEM_PW");
+        if (a.ep_scale == nullptr && rows < 0x7fffffffL / 2 && !(pe && pe[0] == '0'))
+            return rows * a.Cd * 2 > (64L << 20) ? launch_stem_pw<true>(a, s) : launch_stem_pw<false>(a, s);
         return rows * a.Cd * 2 > (64L << 20) ? launch_stem_s<true>(a, s) : launch_stem_s<false>(a, s);
+    }
     if (ring_eligible(a.Cs, (long)a.F * a.Hs * a.Ws * a.pitch + a.Cs + (long)(a.padh * a.Ws + a.padw) * a.pitch, (long)a.Cd * a.K, a.pitch != a.Cs)) {
         if constexpr (!DGRAD) {
             if (wide_fwd_eligible(a)) return launch_igemm_ring<256, 256, 2, 4, false>(a, "igemm_fwd_256x256", s);
