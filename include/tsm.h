@@ -29,8 +29,8 @@
  *    kernels for channel counts that are not multiples of 64 wherever those can
  *    run; TSM_CONV3X3_C64=0 and TSM_STEM_KERNEL=0 (read at every call) leave the
  *    layers that have a kernel of their own to the general one (TSM_STEM_PW=0,
- *    read at every call, keeps the train step's stem on the block-wide one of
- *    its two kernels), and
+ *    read at every call, keeps the stem on the block-wide one of its two
+ *    kernels), and
  *    TSM_CONV3X3_C64_MIN_TILES=<n> (read at every call) replaces the number of
  *    256-pixel tiles from which those two kernels are chosen (default: five per
  *    compute unit); TSM_IGEMM_BM=128|256 (read once per process) fixes the rows

@@ -2712,8 +2712,8 @@ static bool stem_eligible(const IgemmArgs& a) {
            ring_eligible(64, (long)a.F * a.Hs * a.Ws * 16 + 64, 64L * a.K, true) && ring_rows(rows, 64) == 256;
 }
 
-// (the wavefront-per-32-pixels variant takes the training forward pass: statistics epilogue only; TSM_STEM_PW=0,
-//  read at every call, keeps the block-wide kernel)
+// (the wavefront-per-32-pixels variant takes the stem wherever no affine epilogue is asked for -- it carries the
+//  statistics epilogue only; TSM_STEM_PW=0, read at every call, keeps the block-wide kernel)
 template <bool STREAM>
 static int launch_stem_pw(IgemmArgs& a, hipStream_t s) {
     auto kern = stem_pw_kernel<STREAM>;
