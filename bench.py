@@ -54,8 +54,8 @@ def pw_layer(cs, cd, rows):
 def igemm_class(kind, cd, cs, rows, taps=1, stride=1, affine=False):
     """Kernel and tile the library picks for a forward ("fwd") or data-gradient ("dgrad") convolution that produces
     `rows` pixels of `cd` channels from `cs` source channels (tensors below 2 GiB, which holds for every workload
-    here; 256 CUs).  affine: a forward layer with the affine epilogue of the inference path, which the kernels that
-    only carry the statistics epilogue do not take."""
+    here; 256 CUs).  affine: a forward layer with the affine epilogue of the inference path, which the 256-column tiles
+    and the short-K kernel at K = 128 do not carry."""
     if stride == "stem":      # the space-to-depth stem: its own kernel from five rounds of tiles on
         return "igemm_fwd_stem" if -(-rows // 256) >= 5 * 256 else "igemm_fwd_256x64"
     if cs % 64 == 0:
@@ -63,8 +63,8 @@ def igemm_class(kind, cd, cs, rows, taps=1, stride=1, affine=False):
         r = "r128" if tiles256 * 4 < 256 * 3 else "256"
         if cs == 64 and cd == 64 and taps == 9 and stride == 1 and -(-rows // 256) >= 5 * 256:
             return "igemm_%s_c64" % kind      # the 64 -> 64 channel 3x3 kernel (five rounds of tiles or more)
-        if kind == "fwd" and not affine and taps == 1 and stride == 1 and r == "256" and pw_layer(cs, cd, rows):
-            return "igemm_fwd_pw"             # the short-K 1x1 forward kernel
+        if kind == "fwd" and not (affine and cs == 128) and taps == 1 and stride == 1 and r == "256" and pw_layer(cs, cd, rows):
+            return "igemm_fwd_pw"             # the short-K 1x1 forward kernel (affine epilogue: K = 64 and 256 only)
         if kind == "fwd" and not affine and cd % 256 == 0 and r == "256" and -(-rows // 256) * (cd // 256) * 2 >= 256:
             return "igemm_fwd_256x256"        # wide results: 256-column tiles from half a round on
         # 64 columns per tile for narrow outputs, and where even 128x128 tiles leave a quarter of the CUs idle

@@ -1979,7 +1979,10 @@ __device__ __forceinline__ void pw_block_role(int nsplit, int* stream, int* part
     }
 }
 
-template <int KC, bool STREAM>
+// AFF: the affine epilogue of IgemmArgs::ep_scale (inference: BatchNorm with known statistics, optional residual and
+// ReLU), applied to the staged values as igemm_ring_kernel applies it; the residual pieces of a pass are requested ahead
+// of the staging of the accumulators.
+template <int KC, bool STREAM, bool AFF = false>
 __global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
     constexpr int LDC = PW_LDC, KS = KC / 16, ROWB = PwD<KC>::ROWB, KV = KC / 8, NB = PwD<KC>::NB, NH = PwD<KC>::NH;
     constexpr bool DB = KC <= 128;                                 // the next pass's fragments in registers of their own
@@ -2031,6 +2034,17 @@ __global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) f1[h][q] = f2[h][q] = 0.f;
     const int vcol = lane & 15, row0 = lane >> 4;                  // store loop: piece lane + 64*t is row row0 + 4*t, vector vcol
+    float sc[AFF ? NH : 1][8], sh[AFF ? NH : 1][8];                // AFF: scale and shift of this lane's channels
+    if (AFF) {
+#pragma unroll
+        for (int h = 0; h < NH; ++h)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                sc[AFF ? h : 0][q] = a.ep_scale[nb0 + h * 128 + vcol * 8 + q];
+                sh[AFF ? h : 0][q] = a.ep_shift[nb0 + h * 128 + vcol * 8 + q];
+            }
+    }
+    const bf16_t* zero_page_f = (const bf16_t*)g_zero_page;
 
     long slab = stream0;
     bf16x8 cur[KS], nxt[DB ? KS : 1];
@@ -2054,6 +2068,17 @@ __global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
                 }
             // (long K: the next pass's fragments take the place of this pass's, which the last product has read)
             if (!DB && h == NH - 1 && slab + nstreams < nslabs) load_a(slab + nstreams, cur);
+            constexpr int RG = KC == 256 ? 8 : 4;                  // AFF: residual pieces requested together (registers)
+            u32x4 rr[AFF ? RG : 1];
+            auto request = [&](int g) {
+#pragma unroll
+                for (int t = 0; t < RG; ++t) {
+                    const long grow = slab * 32 + row0 + 4 * (g * RG + t);
+                    // (a load without a branch around it: rows that are not stored read the zero page)
+                    rr[AFF ? t : 0] = *(const u32x4*)((a.ep_res && grow < M) ? a.ep_res + grow * a.Cd + nb0 + h * 128 + vcol * 8 : zero_page_f);
+                }
+            };
+            if (AFF) request(0);
             // lane: pixel r, channels 32*j + 8*q + 4*hi + {0..3}
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -2071,7 +2096,7 @@ __global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
             for (int t = 0; t < 8; ++t) {
                 const int row = row0 + 4 * t;
                 const long grow = slab * 32 + row;
-                const u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
+                u32x4 v = *(const u32x4*)(Cst + row * LDC + vcol * 8);
                 if (grow < M) {
                     if (do_stats) {   // statistics of the values as stored
 #pragma unroll
@@ -2083,10 +2108,24 @@ __global__ void __launch_bounds__(512) pw_fwd_kernel(IgemmArgs a) {
                             f2[h][2 * e + 1] = fmaf(hv, hv, f2[h][2 * e + 1]);
                         }
                     }
+                    if (AFF) {
+                        const u32x4 rv = rr[AFF ? t % RG : 0];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            float lo = fmaf(__uint_as_float(v[e] << 16), sc[AFF ? h : 0][2 * e], sh[AFF ? h : 0][2 * e]) + __uint_as_float(rv[e] << 16);
+                            float hv = fmaf(__uint_as_float(v[e] & 0xffff0000u), sc[AFF ? h : 0][2 * e + 1], sh[AFF ? h : 0][2 * e + 1]) + __uint_as_float(rv[e] & 0xffff0000u);
+                            if (a.ep_relu) {
+                                lo = lo > 0.f ? lo : 0.f;
+                                hv = hv > 0.f ? hv : 0.f;
+                            }
+                            v[e] = pack_bf16x2(lo, hv);
+                        }
+                    }
                     u32x4* q = (u32x4*)(a.dst + grow * a.Cd + nb0 + h * 128 + vcol * 8);
                     if (STREAM) __builtin_nontemporal_store(v, q);
                     else *q = v;
                 }
+                if (AFF && RG < 8 && t == RG - 1) request(1);
             }
             __builtin_amdgcn_wave_barrier();
         }
@@ -2768,12 +2807,13 @@ static bool pw_shape_ok(const IgemmArgs& a) {
 }
 
 static bool pw_fwd_eligible(const IgemmArgs& a) {
-    return pw_shape_ok(a) && a.fold == 0 && a.addend == nullptr && a.ep_scale == nullptr;
+    // (the affine epilogue: variants for K = 64 and K = 256, the inference call's layers outside its fused kernels)
+    return pw_shape_ok(a) && a.fold == 0 && a.addend == nullptr && (a.ep_scale == nullptr || a.Cs != 128);
 }
 
-template <int KC, bool STREAM>
+template <int KC, bool STREAM, bool AFF = false>
 static int launch_pw_fwd(IgemmArgs& a, hipStream_t s) {
-    auto kern = pw_fwd_kernel<KC, STREAM>;
+    auto kern = pw_fwd_kernel<KC, STREAM, AFF>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -2849,6 +2889,10 @@ static int dispatch_igemm(IgemmArgs& a, hipStream_t s) {
     }
     if (!DGRAD && pw_fwd_eligible(a)) {
         const bool st = rows * a.Cd * 2 > (64L << 20);
+        if (a.ep_scale != nullptr) {   // the affine epilogue of the inference path
+            if (a.Cs == 64) return st ? launch_pw_fwd<64, true, true>(a, s) : launch_pw_fwd<64, false, true>(a, s);
+            return st ? launch_pw_fwd<256, true, true>(a, s) : launch_pw_fwd<256, false, true>(a, s);
+        }
         if (a.Cs == 64) return st ? launch_pw_fwd<64, true>(a, s) : launch_pw_fwd<64, false>(a, s);
         if (a.Cs == 128) return st ? launch_pw_fwd<128, true>(a, s) : launch_pw_fwd<128, false>(a, s);
         return st ? launch_pw_fwd<256, true>(a, s) : launch_pw_fwd<256, false>(a, s);
